@@ -1,0 +1,313 @@
+"""Seeded synthetic inputs shaped like the paper's workloads (Table 2 and the experiment settings).
+
+This module only *draws inputs*: graphs, partition maps, features, labels, weights and target
+batches.  It contains none of the method's arithmetic (no sampling, splitting, dedup or GNN
+maths) and is the one piece of code that the CPU oracle's tests and the HIP path's tests both
+use, so that the two sides see the very same arrays.
+
+Everything is written with torch tensor ops so that the large graphs can be generated on the GPU
+in seconds; the arrays are then handed (or copied to the host) unchanged to whichever side needs
+them.  A torch.Generator seeded from one master seed plus a fixed per-purpose offset drives every
+draw.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import torch
+
+MASTER_SEED = 0x5EED
+
+_OFF_GRAPH = 1
+_OFF_PERM = 2
+_OFF_FEAT = 3
+_OFF_LABEL = 4
+_OFF_WEIGHT = 5
+_OFF_PMAP = 6
+_OFF_TARGET = 7
+
+
+def _gen(device, seed: int) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & 0x7FFFFFFFFFFFFFFF)
+    return g
+
+
+def rmat_edges(scale: int, n_draws: int, a: float, b: float, c: float, *, seed: int,
+               device="cpu", chunk: int = 1 << 25):
+    """Draw `n_draws` directed (src, dst) pairs from the recursive-matrix model on 2**scale ids.
+
+    Each of the `scale` bit levels picks one of four quadrants with probabilities (a, b, c, 1-a-b-c):
+    a = (0,0), b = (0,1), c = (1,0), d = (1,1) for the (src bit, dst bit) pair.
+    """
+    g = _gen(device, seed)
+    srcs, dsts = [], []
+    done = 0
+    while done < n_draws:
+        m = min(chunk, n_draws - done)
+        src = torch.zeros(m, dtype=torch.int64, device=device)
+        dst = torch.zeros(m, dtype=torch.int64, device=device)
+        for _ in range(scale):
+            u = torch.rand(m, generator=g, device=device)
+            sbit = (u >= a + b).to(torch.int64)
+            dbit = (((u >= a) & (u < a + b)) | (u >= a + b + c)).to(torch.int64)
+            src = (src << 1) | sbit
+            dst = (dst << 1) | dbit
+        srcs.append(src)
+        dsts.append(dst)
+        done += m
+    return torch.cat(srcs), torch.cat(dsts)
+
+
+def build_csr(src: torch.Tensor, dst: torch.Tensor, n_vertices: int, *, symmetrise: bool,
+              index64: bool):
+    """Sorted, duplicate-free, self-loop-free CSR.  Row v lists the vertices v aggregates from."""
+    keep = (src != dst) & (src < n_vertices) & (dst < n_vertices)
+    src, dst = src[keep], dst[keep]
+    if symmetrise:
+        src, dst = torch.cat([src, dst]), torch.cat([dst, src])
+    keys = torch.unique(src * n_vertices + dst)  # sorted ascending => rows sorted, no dups
+    del src, dst
+    rows = torch.div(keys, n_vertices, rounding_mode="floor")
+    cols = (keys - rows * n_vertices).to(torch.int32)
+    del keys
+    deg = torch.bincount(rows, minlength=n_vertices)
+    del rows
+    indptr = torch.zeros(n_vertices + 1, dtype=torch.int64, device=cols.device)
+    indptr[1:] = torch.cumsum(deg, 0)
+    if not index64:
+        assert int(indptr[-1]) < 2 ** 31
+        indptr = indptr.to(torch.int32)
+    return indptr.contiguous(), cols.contiguous()
+
+
+def rmat_graph(n_vertices: int, n_directed_target: int, abc: Sequence[float], *, seed: int,
+               symmetrise: bool = True, permute_ids: bool = True, index64: bool = False,
+               device="cpu", exact_draws: Optional[int] = None):
+    """R-MAT graph with about `n_directed_target` directed edges after clean-up.
+
+    ids >= n_vertices are rejected (scale is the next power of two); a seeded random relabelling
+    spreads the hubs over the id range unless permute_ids is False.  If `exact_draws` is given that
+    many pairs are drawn once (the Tiny workload fixes the number of draws, not of edges);
+    otherwise batches are drawn until the cleaned edge count reaches the target.
+    """
+    scale = max(1, math.ceil(math.log2(n_vertices)))
+    a, b, c = abc
+    if exact_draws is not None:
+        s, d = rmat_edges(scale, exact_draws, a, b, c, seed=seed + _OFF_GRAPH, device=device)
+    else:
+        per_dir = n_directed_target // (2 if symmetrise else 1)
+        s = torch.empty(0, dtype=torch.int64, device=device)
+        d = torch.empty(0, dtype=torch.int64, device=device)
+        have, rnd = 0, 0
+        while have < n_directed_target:
+            need = max(per_dir // 8, int((n_directed_target - have) / (2 if symmetrise else 1) * 1.15))
+            s2, d2 = rmat_edges(scale, need, a, b, c, seed=seed + _OFF_GRAPH + 1000 * rnd,
+                                device=device)
+            ok = (s2 != d2) & (s2 < n_vertices) & (d2 < n_vertices)
+            s2, d2 = s2[ok], d2[ok]
+            if symmetrise:  # canonical orientation so that (u,v) and (v,u) are one undirected edge
+                lo, hi = torch.minimum(s2, d2), torch.maximum(s2, d2)
+                s2, d2 = lo, hi
+            k = torch.unique(torch.cat([s * n_vertices + d, s2 * n_vertices + d2]))
+            s = torch.div(k, n_vertices, rounding_mode="floor")
+            d = k - s * n_vertices
+            have = k.numel() * (2 if symmetrise else 1)
+            rnd += 1
+            del k, s2, d2
+    ok = (s < n_vertices) & (d < n_vertices)
+    s, d = s[ok], d[ok]
+    if permute_ids:
+        perm = torch.randperm(n_vertices, generator=_gen(device, seed + _OFF_PERM), device=device)
+        s, d = perm[s], perm[d]
+    return build_csr(s, d, n_vertices, symmetrise=symmetrise, index64=index64)
+
+
+def pmap_random(n_vertices: int, n_splits: int, *, seed: int, device="cpu") -> torch.Tensor:
+    """The 'Rand' partitioner of the paper's splitting-algorithm evaluation: uniform owner."""
+    g = _gen(device, seed + _OFF_PMAP)
+    return torch.randint(0, n_splits, (n_vertices,), generator=g, device=device).to(torch.uint8)
+
+
+def pmap_range(n_vertices: int, n_splits: int, *, device="cpu") -> torch.Tensor:
+    """Contiguous id ranges: owner(v) = floor(v * S / |V|)."""
+    v = torch.arange(n_vertices, dtype=torch.int64, device=device)
+    return torch.div(v * n_splits, n_vertices, rounding_mode="floor").to(torch.uint8)
+
+
+def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) -> torch.Tensor:
+    """Locality map: rank vertices by BFS visit order (from the max-degree vertex, restarting at
+    the smallest unvisited id) and cut the ranking into n_splits equal blocks."""
+    dev = indptr.device
+    n = indptr.numel() - 1
+    ip = indptr.to(torch.int64)
+    deg = ip[1:] - ip[:-1]
+    rank = torch.full((n,), -1, dtype=torch.int64, device=dev)
+    next_rank = 0
+    frontier = torch.argmax(deg).reshape(1)
+    scan_from = 0
+    while next_rank < n:
+        if frontier.numel() == 0:
+            rest = torch.nonzero(rank[scan_from:] < 0)
+            if rest.numel() == 0:
+                break
+            # all remaining unvisited vertices with no edges get ranks in id order at once
+            first = scan_from + int(rest[0])
+            scan_from = first
+            if int(deg[first]) == 0:
+                iso = torch.nonzero((rank < 0) & (deg == 0)).flatten()
+                rank[iso] = next_rank + torch.arange(iso.numel(), device=dev)
+                next_rank += iso.numel()
+                continue
+            frontier = torch.tensor([first], device=dev)
+        new = frontier[rank[frontier] < 0]
+        new = torch.unique(new)
+        rank[new] = next_rank + torch.arange(new.numel(), device=dev)
+        next_rank += new.numel()
+        if new.numel() == 0:
+            frontier = new
+            continue
+        starts, lens = ip[new], deg[new]
+        tot = int(lens.sum())
+        if tot == 0:
+            frontier = new[:0]
+            continue
+        seg = torch.repeat_interleave(torch.arange(new.numel(), device=dev), lens)
+        offs = torch.arange(tot, device=dev) - torch.repeat_interleave(
+            torch.cumsum(lens, 0) - lens, lens)
+        nb = indices[starts[seg] + offs].to(torch.int64)
+        frontier = torch.unique(nb[rank[nb] < 0])
+    return torch.div(rank * n_splits, n, rounding_mode="floor").clamp(0, n_splits - 1).to(torch.uint8)
+
+
+def features(n_vertices: int, dim: int, *, seed: int, device="cpu", dtype=torch.float32,
+             chunk_rows: int = 1 << 22) -> torch.Tensor:
+    """N(0,1) rows, generated in chunks so that the big tables never need a second copy."""
+    g = _gen(device, seed + _OFF_FEAT)
+    out = torch.empty((n_vertices, dim), dtype=dtype, device=device)
+    for r0 in range(0, n_vertices, chunk_rows):
+        r1 = min(n_vertices, r0 + chunk_rows)
+        out[r0:r1] = torch.randn((r1 - r0, dim), generator=g, device=device).to(dtype)
+    return out
+
+
+def labels(n_vertices: int, n_classes: int, *, seed: int, device="cpu") -> torch.Tensor:
+    g = _gen(device, seed + _OFF_LABEL)
+    return torch.randint(0, n_classes, (n_vertices,), generator=g, device=device, dtype=torch.int64)
+
+
+def sage_weights(dims: Sequence[int], *, seed: int, device="cpu"):
+    """Glorot-uniform W_self[l], W_neigh[l] of shape [D_l, D_{l+1}] and a small non-zero bias."""
+    g = _gen(device, seed + _OFF_WEIGHT)
+    w_self, w_neigh, bias = [], [], []
+    for l in range(len(dims) - 1):
+        lim = math.sqrt(6.0 / (dims[l] + dims[l + 1]))
+        for dstl in (w_self, w_neigh):
+            dstl.append(((torch.rand((dims[l], dims[l + 1]), generator=g, device=device) * 2 - 1) * lim)
+                        .contiguous())
+        bias.append(((torch.rand((dims[l + 1],), generator=g, device=device) * 2 - 1) * 0.1).contiguous())
+    return w_self, w_neigh, bias
+
+
+def draw_targets(n_vertices: int, batch: int, *, seed: int, it: int, device="cpu") -> torch.Tensor:
+    """`batch` distinct vertex ids, uniformly, fresh for every iteration number `it`."""
+    g = _gen(device, seed + _OFF_TARGET + 7919 * (it + 1))
+    if n_vertices <= (1 << 24):
+        return torch.randperm(n_vertices, generator=g, device=device)[:batch].to(torch.int32).contiguous()
+    # large id ranges: oversample, dedup keeping first occurrences
+    cand = torch.randint(0, n_vertices, (batch * 2 + 64,), generator=g, device=device)
+    uniq, inv = torch.unique(cand, return_inverse=True)
+    first = torch.full((uniq.numel(),), cand.numel(), dtype=torch.int64, device=device)
+    first.scatter_reduce_(0, inv, torch.arange(cand.numel(), device=device), reduce="amin")
+    order = torch.sort(first).values[:batch]
+    return cand[order].to(torch.int32).contiguous()
+
+
+@dataclass
+class Workload:
+    name: str
+    n_vertices: int
+    indptr: torch.Tensor          # int32 or int64 [n_vertices+1]
+    indices: torch.Tensor         # int32 [n_edges]
+    pmap: torch.Tensor            # uint8 [n_vertices]
+    n_splits: int
+    feat: torch.Tensor            # [n_vertices, dims[0]]
+    labels: torch.Tensor          # int64 [n_vertices]
+    fanouts: List[int]            # fanouts[l] expands layer l+1 into layer l (l = L-1 .. 0)
+    dims: List[int]               # dims[0] = input width ... dims[L] = classes
+    batch: int
+    seed: int = MASTER_SEED
+    w_self: list = field(default_factory=list)
+    w_neigh: list = field(default_factory=list)
+    bias: list = field(default_factory=list)
+
+    @property
+    def n_edges(self) -> int:
+        return int(self.indices.numel())
+
+    @property
+    def n_layers(self) -> int:
+        return len(self.fanouts)
+
+    def targets(self, it: int) -> torch.Tensor:
+        return draw_targets(self.n_vertices, self.batch, seed=self.seed, it=it,
+                            device=self.indptr.device)
+
+    def describe(self) -> dict:
+        return {"workload": self.name, "n_vertices": self.n_vertices, "n_edges": self.n_edges,
+                "n_splits": self.n_splits, "batch": self.batch, "fanouts": list(self.fanouts),
+                "dims": list(self.dims), "feat_dtype": str(self.feat.dtype).replace("torch.", ""),
+                "indptr": str(self.indptr.dtype).replace("torch.", "")}
+
+
+def _finish(name, n, indptr, indices, pmap, n_splits, dims, fanouts, batch, seed, device,
+            feat_dtype=torch.float32) -> Workload:
+    feat = features(n, dims[0], seed=seed, device=device, dtype=feat_dtype)
+    lab = labels(n, dims[-1], seed=seed, device=device)
+    ws, wn, b = sage_weights(dims, seed=seed, device=device)
+    return Workload(name, n, indptr, indices, pmap, n_splits, feat, lab, list(fanouts), list(dims),
+                    batch, seed, ws, wn, b)
+
+
+def tiny(device="cpu", seed: int = MASTER_SEED, n_splits: int = 4) -> Workload:
+    """2**14 vertices, 2**18 R-MAT(.57,.19,.19) draws symmetrised; 64-d features; 16 classes;
+    uniform-random partition map; 1024 targets; fanouts [10, 5]; hidden 64."""
+    n = 1 << 14
+    indptr, indices = rmat_graph(n, 0, (0.57, 0.19, 0.19), seed=seed, symmetrise=True,
+                                 permute_ids=False, index64=False, device=device,
+                                 exact_draws=1 << 18)
+    pmap = pmap_random(n, n_splits, seed=seed, device=device)
+    return _finish("tiny", n, indptr, indices, pmap, n_splits, [64, 64, 16], [10, 5], 1024, seed, device)
+
+
+def medium(device="cpu", seed: int = MASTER_SEED, n_splits: int = 4, scale_down: int = 1) -> Workload:
+    """2.4M vertices, about 124M directed edges (symmetric, average degree about 50); 100-d
+    features; 47 classes; contiguous-range partition map; batch 1024; fanouts [15,10,5];
+    hidden 256.  `scale_down` divides vertex and edge counts (CPU-sized rehearsals only)."""
+    n = 2_400_000 // scale_down
+    m = 124_000_000 // scale_down
+    indptr, indices = rmat_graph(n, m, (0.57, 0.19, 0.19), seed=seed, symmetrise=True,
+                                 permute_ids=True, index64=False, device=device)
+    pmap = pmap_range(n, n_splits, device=device)
+    name = "medium" if scale_down == 1 else f"medium/{scale_down}"
+    return _finish(name, n, indptr, indices, pmap, n_splits, [100, 256, 256, 47], [15, 10, 5], 1024,
+                   seed, device)
+
+
+def custom(n_vertices: int, n_directed: int, *, dims, fanouts, batch, n_splits=4, pmap_kind="random",
+           abc=(0.57, 0.19, 0.19), index64=False, device="cpu", seed: int = MASTER_SEED,
+           permute_ids=True, name="custom") -> Workload:
+    """Free-form workload for parity cases (ragged sizes, int64 indptr, other split counts)."""
+    indptr, indices = rmat_graph(n_vertices, n_directed, abc, seed=seed, symmetrise=True,
+                                 permute_ids=permute_ids, index64=index64, device=device)
+    if pmap_kind == "random":
+        pmap = pmap_random(n_vertices, n_splits, seed=seed, device=device)
+    elif pmap_kind == "range":
+        pmap = pmap_range(n_vertices, n_splits, device=device)
+    elif pmap_kind == "bfs":
+        pmap = pmap_bfs_blocks(indptr, indices, n_splits)
+    else:
+        raise ValueError(pmap_kind)
+    return _finish(name, n_vertices, indptr, indices, pmap, n_splits, dims, fanouts, batch, seed, device)
