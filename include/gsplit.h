@@ -1,0 +1,180 @@
+/*
+ * gsplit.h -- C ABI of the MI355X (gfx950) split-parallel mini-batch hot path.
+ *
+ * One GPU's share of a GSplit training iteration (paper sections 3-5): fanout neighbour sampling
+ * layer by layer, online splitting of every sampled vertex through the precomputed global
+ * partition function f_G, per-split dedup/relabel and shuffle-index construction
+ * (Algorithm 1, `sp_sample`), loading of the layer-0 input features (section 3, "loading step"),
+ * and the GraphSAGE forward and backward passes over the split mini-batch (Algorithm 2,
+ * `sp_forward`, and the backward description after it).  The S splits that the paper places on S
+ * GPUs are S *logical* splits on this one GPU; the per-layer all-to-all shuffles become index
+ * permutations between them.
+ *
+ * Conventions
+ *  - Every `d_*` pointer is a DEVICE pointer owned by the CALLER.  The library never frees or
+ *    reallocates caller memory; caller memory must stay valid until the stream work that uses it
+ *    has completed.  Pointers without the prefix are HOST pointers.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *    enqueued on it; calls return without waiting unless stated otherwise.
+ *  - Every function returns 0 (GSPLIT_OK) or a negative error code.  No exceptions, no abort,
+ *    nothing printed.  After an error the outputs are unspecified, the context stays usable, and
+ *    gsplit_last_error() describes what went wrong.
+ *  - A context is not thread-safe; calls on one context must be issued from one thread at a
+ *    time and on one stream at a time.
+ *  - Layer numbering follows Algorithm 1: local_front[L] are the targets, sampling layer l
+ *    (l = L-1 .. 0) expands local_front[l+1] into layer l using fanouts[l]; forward layer l
+ *    (l = 0 .. L-1) maps width dims[l] to dims[l+1].
+ *  - "cat" arrays hold the S splits one after the other in split order.
+ */
+#ifndef GSPLIT_H
+#define GSPLIT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GSPLIT_OK          0
+#define GSPLIT_EINVAL     -1   /* bad argument */
+#define GSPLIT_ENOMEM     -2   /* device or host allocation failed */
+#define GSPLIT_ECAPACITY  -3   /* input larger than what the context was created for */
+#define GSPLIT_EHIP       -4   /* a HIP runtime call failed */
+#define GSPLIT_ESTATE     -5   /* call out of order (e.g. backward without forward) */
+
+#define GSPLIT_MAX_SPLITS  8
+#define GSPLIT_MAX_LAYERS  8
+#define GSPLIT_MAX_FANOUT  64
+
+#define GSPLIT_F32   0
+#define GSPLIT_BF16  1
+
+typedef struct gsplit_ctx gsplit_ctx;
+
+/* The graph G(V_G, E_G) and the global partition function f_G (section 4).  Row v of the CSR
+ * lists the vertices v aggregates from; rows must be free of duplicates.  All arrays stay
+ * caller-owned and must outlive the context. */
+typedef struct {
+    int64_t        n_vertices;      /* |V_G|;  n_vertices * n_splits must be < 2^32 - 1 */
+    int64_t        n_edges;         /* number of CSR entries, < 2^40 */
+    const void    *d_indptr;        /* [n_vertices + 1], int32 or int64 */
+    int32_t        indptr_is_64;    /* 0: int32 indptr, 1: int64 indptr */
+    const int32_t *d_indices;       /* [n_edges] */
+    const uint8_t *d_pmap;          /* f_G: [n_vertices], values in [0, n_splits) */
+    int32_t        n_splits;        /* S, 1 .. GSPLIT_MAX_SPLITS */
+} gsplit_graph;
+
+typedef struct {
+    int32_t        n_layers;        /* L, 1 .. GSPLIT_MAX_LAYERS */
+    const int32_t *fanouts;         /* HOST array [L]; fanouts[l] in 1 .. GSPLIT_MAX_FANOUT */
+    int64_t        max_targets;     /* largest n_targets any gsplit_sample_split call will pass */
+} gsplit_config;
+
+/* Creates a context on the current HIP device and allocates its workspace, sized from the
+ * no-dedup upper bounds |F_l| <= min(|V|, |F_{l+1}| * (1 + fanouts[l])).  ENOMEM if it does not
+ * fit.  *out is set only on success. */
+int gsplit_create(gsplit_ctx **out, const gsplit_graph *graph, const gsplit_config *config);
+
+/* Waits for the device, then frees everything the context owns.  NULL is accepted. */
+int gsplit_destroy(gsplit_ctx *ctx);
+
+/* Message for the most recent error on this context (context-owned, valid until the next call);
+ * with ctx == NULL, the message of the most recent failed gsplit_create on this thread. */
+const char *gsplit_last_error(const gsplit_ctx *ctx);
+
+/* Upper bound on the number of rows of local_cat[level] (level 0 .. L) that any batch of this
+ * context can have; callers size gather and activation buffers with it.  Returns the bound or a
+ * negative error code. */
+int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
+
+/* Algorithm 1 for all S splits at once.
+ *   d_targets [n_targets]: DISTINCT vertex ids of the mini-batch (all splits' local_targets
+ *   together; the library separates them by f_G keeping the given order).
+ * For l = L-1 .. 0: sample_layer on every local frontier (without replacement, all neighbours in
+ * CSR order when degree <= fanout; random choices are a pure function of
+ * (seed, iter, l, vertex id), so a vertex draws the same neighbours in any split), then split():
+ * dedup into each split's mixed frontier (first-occurrence order, destination vertices first),
+ * edges[l] relabelled to mixed-frontier rows, the sampled part of each mixed frontier bucketed by
+ * owner (stable) and handed to the owners, next local frontiers by first-occurrence dedup of
+ * (own destination vertices, then buckets in sender order), and shuffle_idx[l].
+ * The result (the "batch") lives in the context until the next call.  Asynchronous.
+ * EINVAL for n_targets < 0 or NULL pointers, ECAPACITY for n_targets > max_targets. */
+int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+                        uint64_t seed, uint64_t iter, void *stream);
+
+/* Host-visible sizes of the current batch.  The first call after a gsplit_sample_split waits for
+ * `stream` work of that call to finish (one device-to-host copy); later calls are free.
+ *   n_local  [(L+1) * S]: |local_front[l]_s| at [l * S + s]
+ *   n_mixed  [L * S]    : |mixed_front_s[l]|
+ *   n_edges  [L * S]    : entries of edges[l] held by split s
+ *   bucket   [L * S * S]: ids split s sends to split t at sampling layer l, at [(l*S + s)*S + t]
+ * Any of the four may be NULL. */
+int gsplit_batch_sizes(gsplit_ctx *ctx, int64_t *n_local, int64_t *n_mixed, int64_t *n_edges,
+                       int64_t *bucket);
+
+/* Device views of the current batch (context-owned, valid until the next gsplit_sample_split).
+ * No synchronisation; sizes come from gsplit_batch_sizes. */
+typedef struct {
+    const int32_t *d_local_cat;     /* local_front[level] of all splits, global ids */
+    const int32_t *d_local_off;     /* [S+1] device-side split offsets into d_local_cat */
+} gsplit_level_view;
+
+typedef struct {
+    const int32_t *d_nbr;           /* [n_dst_total * fanout] sampled global ids, -1 padded      */
+    const int32_t *d_cnt;           /* [n_dst_total] min(degree, fanout)                         */
+    const int32_t *d_mixed_cat;     /* mixed frontiers of all splits, global ids                 */
+    const int32_t *d_mixed_off;     /* [S+1] device-side offsets into d_mixed_cat                */
+    const int32_t *d_blk_indptr;    /* [n_dst_total + 1] offsets into d_blk_src (whole layer)    */
+    const int32_t *d_blk_src;       /* edges[l]: row of the owning split's mixed frontier        */
+    const int32_t *d_shuffle_src_row;/* [sum n_mixed] row of local_cat[l] holding that vertex    */
+    const int32_t *d_recv_cat;      /* received buckets: for t, for s: bucket[s->t] (global ids) */
+    const int32_t *d_recv_off;      /* [S+1] device-side offsets of each receiver in d_recv_cat  */
+} gsplit_layer_view;
+
+int gsplit_batch_level(const gsplit_ctx *ctx, int32_t level, gsplit_level_view *out);
+int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_layer_view *out);
+
+/* Loading step (section 3): d_out[r, :] = d_table[local_cat[0][r], :] for every row r of the
+ * current batch's layer-0 local frontiers (splits concatenated).  A pure row copy of
+ * dim * sizeof(dtype) bytes; rows of d_out are dense.  d_out must hold gsplit_max_rows(ctx, 0)
+ * rows (or the exact count from gsplit_batch_sizes).  row_stride_bytes >= row bytes.
+ * dtype: GSPLIT_F32 or GSPLIT_BF16.  Asynchronous. */
+int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int32_t dtype, int64_t dim,
+                           int64_t row_stride_bytes, void *d_out, void *stream);
+
+/* GraphSAGE-mean model: layer l computes, for the destination vertices of every split,
+ *   H_{l+1} = act( H_l[self] * W_self[l] + mean_{u in sampled N(v)} H_l[u] * W_neigh[l] + b[l] ),
+ * act = ReLU except on the last layer; an empty neighbourhood has mean 0.  Weights are row-major
+ * [dims[l] x dims[l+1]] float32 (HOST arrays of DEVICE pointers), biases [dims[l+1]] float32.
+ * dtype selects how activations are stored and multiplied: GSPLIT_F32 (fp32 storage, fp32 MFMA) or
+ * GSPLIT_BF16 (bf16 features/activations/weights into the matrix cores, fp32 accumulation). */
+typedef struct {
+    int32_t             dtype;
+    const int32_t      *dims;        /* HOST [L+1] */
+    const void *const  *d_w_self;    /* HOST [L] of device pointers */
+    const void *const  *d_w_neigh;
+    const void *const  *d_bias;
+} gsplit_sage_params;
+
+/* Algorithm 2 on the current batch.  d_feat_local = output of gsplit_gather_features (dtype as in
+ * params).  d_logits [n_targets x dims[L]] float32; row r belongs to local_cat[L][r], i.e. the
+ * targets grouped by split in the order given (gsplit_batch_level(ctx, L) shows the ids).
+ * Keeps the activations needed by the backward pass inside the context.  Asynchronous. */
+int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const void *d_feat_local,
+                    float *d_logits, void *stream);
+
+/* Backward pass, top layer down, from d_grad_logits [n_targets x dims[L]] (same row order as
+ * d_logits).  Gradients of rows held by other splits travel back through the reversed shuffle
+ * index; weight gradients are summed over all splits (the gradient aggregation of section 2).
+ * Outputs (HOST arrays of DEVICE pointers, each buffer overwritten): d_gw_self[l], d_gw_neigh[l]
+ * [dims[l] x dims[l+1]] float32, d_gbias[l] [dims[l+1]] float32.  No gradient is formed for the
+ * input features.  Needs a preceding gsplit_sage_fwd on the same batch with the same params,
+ * else ESTATE.  Asynchronous. */
+int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const float *d_grad_logits,
+                    float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
+                    void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSPLIT_H */

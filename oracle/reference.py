@@ -14,8 +14,9 @@ Readings of the paper that this file fixes (the paper is silent on them):
     GraphSAGE self term), so both the next local frontier and every mixed frontier start with the
     destination vertices themselves ("the next layer is the union of the new local frontier and
     the previous mixed frontier", section 3).
-  * local numbering everywhere = order of first occurrence; buckets keep stream order; received
-    buckets are concatenated by sending split.
+  * local numbering everywhere = order of first occurrence; what a split hands to owner t is the
+    sampled part of its (already duplicate-free) mixed frontier that t owns, in mixed-frontier
+    order; received buckets are concatenated by sending split.
   * GraphSAGE layer: relu(H_dst W_self + mean(H_nbr) W_neigh + b), no activation on the last layer,
     mean of an empty neighbourhood = 0.
 """
@@ -196,7 +197,7 @@ class Block:
     dst: np.ndarray               # local_front[l+1]_s, global ids (n_dst)
     nbr: np.ndarray               # [n_dst, fan] sampled global ids, -1 padded
     cnt: np.ndarray               # [n_dst]
-    buckets: List[np.ndarray]     # bucket[s->t], t = 0..S-1 (global ids, stream order)
+    buckets: List[np.ndarray]     # bucket[s->t], t = 0..S-1: sampled part of mixed_front owned by t
     mixed_front: np.ndarray       # global ids; first n_dst entries are dst
     blk_indptr: np.ndarray        # int64 [n_dst+1]
     blk_src: np.ndarray           # int32 [nnz] rows of mixed_front
@@ -244,29 +245,31 @@ def sp_sample(indptr, indices, pmap, n_splits: int, fanouts: Sequence[int], targ
 
     for l in range(L - 1, -1, -1):
         fan = int(fanouts[l])
-        sampled, streams, buckets = [], [], []
+        partial = []
         for s in range(S):
-            # mixed_front, edges[l] = sample_layer(local_front[l+1])
-            nbr, cnt = sample_layer(indptr64, indices, local_front[l + 1][s], fan, l, seed, it)
+            dst = local_front[l + 1][s]
+            n_dst = dst.shape[0]
+            # mixed_front, edges[l] = sample_layer(local_front[l+1]): the mixed frontier is the
+            # SET of vertices the layer needs (destination vertices first, then sampled ones in
+            # order of first appearance); edges[l] point at its rows
+            nbr, cnt = sample_layer(indptr64, indices, dst, fan, l, seed, it)
             sigma = slot_stream(nbr, cnt)
-            sampled.append((nbr, cnt))
-            streams.append(sigma)
-            # split(): owner lookup through f_G, stable bucket per owner
-            buckets.append(split_buckets(sigma, pmap, S))
+            mixed, local_ids = unique_first(np.concatenate([dst, sigma]), scratch, want_local=True)
+            blk_src = np.ascontiguousarray(local_ids[n_dst:], np.int32)
+            blk_indptr = np.concatenate([[0], np.cumsum(cnt, dtype=np.int64)]).astype(np.int64)
+            # split(): owner lookup through f_G for the sampled part of the mixed frontier, one
+            # stable bucket per owner (bucket[s->s] is the local part, the others are remote)
+            buckets = split_buckets(np.ascontiguousarray(mixed[n_dst:]), pmap, S)
+            partial.append((dst, nbr, cnt, buckets, mixed, blk_indptr, blk_src))
         # the sampling shuffle: split t receives bucket[s->t] from every s, in order of s
-        recv = [np.concatenate([buckets[s][t] for s in range(S)]) for t in range(S)]
+        recv = [np.concatenate([partial[s][3][t] for s in range(S)]) for t in range(S)]
         # new local frontier: own destination vertices first, then what arrived
         local_front[l] = [unique_first(np.concatenate([local_front[l + 1][t], recv[t]]), scratch)
                           for t in range(S)]
         off = np.concatenate([[0], np.cumsum([f.shape[0] for f in local_front[l]])])
         blocks[l] = []
         for s in range(S):
-            nbr, cnt = sampled[s]
-            dst = local_front[l + 1][s]
-            mixed, local_ids = unique_first(np.concatenate([dst, streams[s]]), scratch,
-                                            want_local=True)
-            local_of = local_ids[dst.shape[0]:]   # edges[l] rewritten to rows of the mixed frontier
-            blk_indptr = np.concatenate([[0], np.cumsum(cnt, dtype=np.int64)]).astype(np.int64)
+            dst, nbr, cnt, buckets, mixed, blk_indptr, blk_src = partial[s]
             # shuffle index: where each mixed-frontier vertex lives in the owners' local frontiers
             src_row = np.empty(mixed.shape[0], np.int32)
             own = pmap[mixed]
@@ -276,8 +279,7 @@ def sp_sample(indptr, indices, pmap, n_splits: int, fanouts: Sequence[int], targ
                     p = positions_in(local_front[l][t], mixed[sel], scratch)
                     assert (p >= 0).all()
                     src_row[sel] = p + off[t]
-            blocks[l].append(Block(dst, nbr, cnt, buckets[s], mixed, blk_indptr,
-                                   np.ascontiguousarray(local_of, np.int32), src_row))
+            blocks[l].append(Block(dst, nbr, cnt, buckets, mixed, blk_indptr, blk_src, src_row))
     return Batch(S, L, local_front, blocks, target_perm)
 
 
@@ -290,7 +292,7 @@ def split_quality(batch: Batch, pmap) -> dict:
     pmap = np.asarray(pmap)
     S = batch.n_splits
     per_split = np.zeros(S, np.int64)
-    cross = total = 0
+    cross = total = sent = 0
     for l in range(batch.n_layers):
         for s in range(S):
             b = batch.blocks[l][s]
@@ -298,10 +300,11 @@ def split_quality(batch: Batch, pmap) -> dict:
             total += n_e
             if l > 0:
                 per_split[s] += n_e
-            cross += int(sum(b.buckets[t].shape[0] for t in range(S) if t != s))
+            cross += int((pmap[b.mixed_front[b.blk_src]] != s).sum())
+            sent += int(sum(b.buckets[t].shape[0] for t in range(S) if t != s))
     imb = float(per_split.max() / per_split.mean()) if per_split.sum() else 1.0
     return {"workload_imbalance": imb, "cross_edge_fraction": cross / max(total, 1),
-            "edges": total}
+            "edges": total, "ids_shuffled": sent}
 
 
 # --------------------------------------------------------------------------------------------

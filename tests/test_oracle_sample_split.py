@@ -147,9 +147,9 @@ def test_buckets_are_stable_and_route_to_owner(tiny_batch):
     for l in range(w.n_layers):
         for s in range(w.n_splits):
             blk = b.blocks[l][s]
-            sigma = R.slot_stream(blk.nbr, blk.cnt)
+            sampled_part = blk.mixed_front[blk.dst.shape[0]:]
             for t in range(w.n_splits):
-                assert (blk.buckets[t] == sigma[pm[sigma] == t]).all()
+                assert (blk.buckets[t] == sampled_part[pm[sampled_part] == t]).all()
         for t in range(w.n_splits):
             recv = np.concatenate([b.blocks[l][s].buckets[t] for s in range(w.n_splits)])
             seq = np.concatenate([b.local_front[l + 1][t], recv])
