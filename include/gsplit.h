@@ -35,6 +35,8 @@
 extern "C" {
 #endif
 
+#define GSPLIT_API __attribute__((visibility("default")))
+
 #define GSPLIT_OK          0
 #define GSPLIT_EINVAL     -1   /* bad argument */
 #define GSPLIT_ENOMEM     -2   /* device or host allocation failed */
@@ -73,19 +75,19 @@ typedef struct {
 /* Creates a context on the current HIP device and allocates its workspace, sized from the
  * no-dedup upper bounds |F_l| <= min(|V|, |F_{l+1}| * (1 + fanouts[l])).  ENOMEM if it does not
  * fit.  *out is set only on success. */
-int gsplit_create(gsplit_ctx **out, const gsplit_graph *graph, const gsplit_config *config);
+GSPLIT_API int gsplit_create(gsplit_ctx **out, const gsplit_graph *graph, const gsplit_config *config);
 
 /* Waits for the device, then frees everything the context owns.  NULL is accepted. */
-int gsplit_destroy(gsplit_ctx *ctx);
+GSPLIT_API int gsplit_destroy(gsplit_ctx *ctx);
 
 /* Message for the most recent error on this context (context-owned, valid until the next call);
  * with ctx == NULL, the message of the most recent failed gsplit_create on this thread. */
-const char *gsplit_last_error(const gsplit_ctx *ctx);
+GSPLIT_API const char *gsplit_last_error(const gsplit_ctx *ctx);
 
 /* Upper bound on the number of rows of local_cat[level] (level 0 .. L) that any batch of this
  * context can have; callers size gather and activation buffers with it.  Returns the bound or a
  * negative error code. */
-int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
+GSPLIT_API int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
 
 /* Algorithm 1 for all S splits at once.
  *   d_targets [n_targets]: DISTINCT vertex ids of the mini-batch (all splits' local_targets
@@ -99,7 +101,7 @@ int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
  * (own destination vertices, then buckets in sender order), and shuffle_idx[l].
  * The result (the "batch") lives in the context until the next call.  Asynchronous.
  * EINVAL for n_targets < 0 or NULL pointers, ECAPACITY for n_targets > max_targets. */
-int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+GSPLIT_API int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                         uint64_t seed, uint64_t iter, void *stream);
 
 /* Host-visible sizes of the current batch.  The first call after a gsplit_sample_split waits for
@@ -109,7 +111,7 @@ int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_tar
  *   n_edges  [L * S]    : entries of edges[l] held by split s
  *   bucket   [L * S * S]: ids split s sends to split t at sampling layer l, at [(l*S + s)*S + t]
  * Any of the four may be NULL. */
-int gsplit_batch_sizes(gsplit_ctx *ctx, int64_t *n_local, int64_t *n_mixed, int64_t *n_edges,
+GSPLIT_API int gsplit_batch_sizes(gsplit_ctx *ctx, int64_t *n_local, int64_t *n_mixed, int64_t *n_edges,
                        int64_t *bucket);
 
 /* Device views of the current batch (context-owned, valid until the next gsplit_sample_split).
@@ -131,15 +133,15 @@ typedef struct {
     const int32_t *d_recv_off;      /* [S+1] device-side offsets of each receiver in d_recv_cat  */
 } gsplit_layer_view;
 
-int gsplit_batch_level(const gsplit_ctx *ctx, int32_t level, gsplit_level_view *out);
-int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_layer_view *out);
+GSPLIT_API int gsplit_batch_level(const gsplit_ctx *ctx, int32_t level, gsplit_level_view *out);
+GSPLIT_API int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_layer_view *out);
 
 /* Loading step (section 3): d_out[r, :] = d_table[local_cat[0][r], :] for every row r of the
  * current batch's layer-0 local frontiers (splits concatenated).  A pure row copy of
  * dim * sizeof(dtype) bytes; rows of d_out are dense.  d_out must hold gsplit_max_rows(ctx, 0)
  * rows (or the exact count from gsplit_batch_sizes).  row_stride_bytes >= row bytes.
  * dtype: GSPLIT_F32 or GSPLIT_BF16.  Asynchronous. */
-int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int32_t dtype, int64_t dim,
+GSPLIT_API int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int32_t dtype, int64_t dim,
                            int64_t row_stride_bytes, void *d_out, void *stream);
 
 /* GraphSAGE-mean model: layer l computes, for the destination vertices of every split,
@@ -160,7 +162,7 @@ typedef struct {
  * params).  d_logits [n_targets x dims[L]] float32; row r belongs to local_cat[L][r], i.e. the
  * targets grouped by split in the order given (gsplit_batch_level(ctx, L) shows the ids).
  * Keeps the activations needed by the backward pass inside the context.  Asynchronous. */
-int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const void *d_feat_local,
+GSPLIT_API int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const void *d_feat_local,
                     float *d_logits, void *stream);
 
 /* Backward pass, top layer down, from d_grad_logits [n_targets x dims[L]] (same row order as
@@ -170,7 +172,7 @@ int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const voi
  * [dims[l] x dims[l+1]] float32, d_gbias[l] [dims[l+1]] float32.  No gradient is formed for the
  * input features.  Needs a preceding gsplit_sage_fwd on the same batch with the same params,
  * else ESTATE.  Asynchronous. */
-int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const float *d_grad_logits,
+GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const float *d_grad_logits,
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
 

@@ -1,0 +1,285 @@
+"""ctypes binding of libgsplit.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point in include/gsplit.h;
+tensors are passed as raw device pointers and the current torch stream as a hipStream_t.  There is
+no computation here and no fallback: if the HIP library is missing or a call fails, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgsplit.so")
+
+GSPLIT_F32, GSPLIT_BF16 = 0, 1
+MAX_SPLITS = 8
+
+EXPORTS = [
+    "gsplit_create", "gsplit_destroy", "gsplit_last_error", "gsplit_max_rows", "gsplit_sample_split",
+    "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
+    "gsplit_sage_fwd", "gsplit_sage_bwd",
+]
+
+
+class GsplitError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gsplit error {code}: {msg}")
+        self.code = code
+
+
+class _Graph(C.Structure):
+    _fields_ = [("n_vertices", C.c_int64), ("n_edges", C.c_int64), ("d_indptr", C.c_void_p),
+                ("indptr_is_64", C.c_int32), ("d_indices", C.c_void_p), ("d_pmap", C.c_void_p),
+                ("n_splits", C.c_int32)]
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("fanouts", C.POINTER(C.c_int32)), ("max_targets", C.c_int64)]
+
+
+class _LevelView(C.Structure):
+    _fields_ = [("d_local_cat", C.c_void_p), ("d_local_off", C.c_void_p)]
+
+
+class _LayerView(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("d_nbr", "d_cnt", "d_mixed_cat", "d_mixed_off", "d_blk_indptr",
+                                          "d_blk_src", "d_shuffle_src_row", "d_recv_cat", "d_recv_off")]
+
+
+class _SageParams(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("d_w_self", C.POINTER(C.c_void_p)),
+                ("d_w_neigh", C.POINTER(C.c_void_p)), ("d_bias", C.POINTER(C.c_void_p))]
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree HIP library; never falls back to anything else."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(hipcc, gfx950) first; there is no non-HIP path")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+    L.gsplit_create.argtypes = [C.POINTER(vp), C.POINTER(_Graph), C.POINTER(_Config)]
+    L.gsplit_destroy.argtypes = [vp]
+    L.gsplit_last_error.argtypes = [vp]
+    L.gsplit_last_error.restype = C.c_char_p
+    L.gsplit_max_rows.argtypes = [vp, i32]
+    L.gsplit_max_rows.restype = i64
+    L.gsplit_sample_split.argtypes = [vp, vp, i64, u64, u64, vp]
+    L.gsplit_batch_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    L.gsplit_batch_level.argtypes = [vp, i32, C.POINTER(_LevelView)]
+    L.gsplit_batch_layer.argtypes = [vp, i32, C.POINTER(_LayerView)]
+    L.gsplit_gather_features.argtypes = [vp, vp, i32, i64, i64, vp, vp]
+    L.gsplit_sage_fwd.argtypes = [vp, C.POINTER(_SageParams), vp, vp, vp]
+    L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
+                                  C.POINTER(vp), vp]
+    for name in EXPORTS:
+        if name not in ("gsplit_last_error", "gsplit_max_rows"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _view_i32(ptr: int, n: int, device) -> torch.Tensor:
+    """Copy n int32 values from a raw device pointer into a fresh tensor (test/inspection only)."""
+    out = torch.empty(max(n, 0), dtype=torch.int32, device=device)
+    if n > 0:
+        hip = _hip_runtime()
+        rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(ptr), C.c_size_t(4 * n), 3)
+        if rc != 0:
+            raise GsplitError(-4, f"hipMemcpy failed ({rc})")
+    return out
+
+
+_hip = None
+
+
+def _hip_runtime():
+    global _hip
+    if _hip is None:
+        for name in ("libamdhip64.so.7", "libamdhip64.so"):   # the runtime torch already loaded
+            try:
+                _hip = C.CDLL(name)
+                break
+            except OSError:
+                continue
+        if _hip is None:
+            raise ImportError("libamdhip64.so not found")
+        _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        _hip.hipMemcpy.restype = C.c_int
+    return _hip
+
+
+class SageParams:
+    """Holds the marshalled gsplit_sage_params block (and keeps the tensors alive)."""
+
+    def __init__(self, dims: Sequence[int], w_self: List[torch.Tensor], w_neigh: List[torch.Tensor],
+                 bias: List[torch.Tensor], dtype: int = GSPLIT_F32):
+        L = len(dims) - 1
+        assert len(w_self) == len(w_neigh) == len(bias) == L
+        for l in range(L):
+            for w in (w_self[l], w_neigh[l]):
+                assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous()
+                assert tuple(w.shape) == (dims[l], dims[l + 1])
+            assert bias[l].is_cuda and bias[l].dtype == torch.float32 and bias[l].numel() == dims[l + 1]
+        self.dims = list(dims)
+        self.tensors = (list(w_self), list(w_neigh), list(bias))
+        self._dims = (C.c_int32 * (L + 1))(*dims)
+        self._ws = (C.c_void_p * L)(*[w.data_ptr() for w in w_self])
+        self._wn = (C.c_void_p * L)(*[w.data_ptr() for w in w_neigh])
+        self._b = (C.c_void_p * L)(*[b.data_ptr() for b in bias])
+        self.c = _SageParams(dtype, self._dims, self._ws, self._wn, self._b)
+        self.dtype = dtype
+
+
+class Context:
+    """gsplit_ctx wrapper.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, indptr: torch.Tensor, indices: torch.Tensor, pmap: torch.Tensor, n_splits: int,
+                 fanouts: Sequence[int], max_targets: int):
+        self.lib = load_library()
+        assert indptr.is_cuda and indices.is_cuda and pmap.is_cuda
+        assert indptr.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32
+        assert pmap.dtype == torch.uint8
+        assert indptr.is_contiguous() and indices.is_contiguous() and pmap.is_contiguous()
+        self.device = indptr.device
+        self.n_vertices = indptr.numel() - 1
+        assert pmap.numel() == self.n_vertices
+        self.S, self.L = int(n_splits), len(fanouts)
+        self.fanouts = list(int(f) for f in fanouts)
+        self._keep = (indptr, indices, pmap)
+        self._fan = (C.c_int32 * self.L)(*self.fanouts)
+        g = _Graph(self.n_vertices, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
+                   indices.data_ptr(), pmap.data_ptr(), self.S)
+        c = _Config(self.L, self._fan, int(max_targets))
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = self.lib.gsplit_create(C.byref(h), C.byref(g), C.byref(c))
+        if rc != 0:
+            raise GsplitError(rc, (self.lib.gsplit_last_error(None) or b"").decode())
+        self.h = h
+
+    # -- plumbing ------------------------------------------------------------------------
+    def _check(self, rc: int):
+        if rc != 0:
+            raise GsplitError(rc, (self.lib.gsplit_last_error(self.h) or b"").decode())
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.gsplit_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- entry points ----------------------------------------------------------------------
+    def gsplit_max_rows(self, level: int) -> int:
+        r = self.lib.gsplit_max_rows(self.h, level)
+        if r < 0:
+            raise GsplitError(int(r), "gsplit_max_rows")
+        return int(r)
+
+    def gsplit_sample_split(self, targets: torch.Tensor, seed: int, it: int):
+        assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
+        self._targets = targets
+        self._check(self.lib.gsplit_sample_split(self.h, targets.data_ptr(), targets.numel(),
+                                                 C.c_uint64(seed), C.c_uint64(it), _stream()))
+
+    def gsplit_batch_sizes(self):
+        S, L = self.S, self.L
+        nl = (C.c_int64 * ((L + 1) * S))()
+        nm = (C.c_int64 * (L * S))()
+        ne = (C.c_int64 * (L * S))()
+        bk = (C.c_int64 * (L * S * S))()
+        self._check(self.lib.gsplit_batch_sizes(self.h, nl, nm, ne, bk))
+        n_local = [[nl[l * S + s] for s in range(S)] for l in range(L + 1)]
+        n_mixed = [[nm[l * S + s] for s in range(S)] for l in range(L)]
+        n_edges = [[ne[l * S + s] for s in range(S)] for l in range(L)]
+        bucket = [[[bk[(l * S + s) * S + t] for t in range(S)] for s in range(S)] for l in range(L)]
+        return n_local, n_mixed, n_edges, bucket
+
+    def gsplit_batch_level(self, level: int) -> _LevelView:
+        v = _LevelView()
+        self._check(self.lib.gsplit_batch_level(self.h, level, C.byref(v)))
+        return v
+
+    def gsplit_batch_layer(self, layer: int) -> _LayerView:
+        v = _LayerView()
+        self._check(self.lib.gsplit_batch_layer(self.h, layer, C.byref(v)))
+        return v
+
+    def gsplit_gather_features(self, table: torch.Tensor, out: torch.Tensor):
+        assert table.is_cuda and out.is_cuda and table.dim() == 2 and table.stride(1) == 1
+        assert out.is_contiguous() and out.dtype == table.dtype and out.shape[1] == table.shape[1]
+        dt = {torch.float32: GSPLIT_F32, torch.bfloat16: GSPLIT_BF16}[table.dtype]
+        self._check(self.lib.gsplit_gather_features(self.h, table.data_ptr(), dt, table.shape[1],
+                                                    table.stride(0) * table.element_size(),
+                                                    out.data_ptr(), _stream()))
+
+    def gsplit_sage_fwd(self, params: SageParams, feat_local: torch.Tensor, logits: torch.Tensor):
+        assert feat_local.is_cuda and feat_local.is_contiguous() and logits.is_cuda and logits.is_contiguous()
+        assert logits.dtype == torch.float32
+        self._fwd_keep = (params, feat_local)
+        self._check(self.lib.gsplit_sage_fwd(self.h, C.byref(params.c), feat_local.data_ptr(),
+                                             logits.data_ptr(), _stream()))
+
+    def gsplit_sage_bwd(self, params: SageParams, grad_logits: torch.Tensor, gw_self, gw_neigh, gbias):
+        L = self.L
+        assert grad_logits.is_cuda and grad_logits.dtype == torch.float32 and grad_logits.is_contiguous()
+        for lst in (gw_self, gw_neigh, gbias):
+            assert len(lst) == L and all(t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+                                         for t in lst)
+        a = (C.c_void_p * L)(*[t.data_ptr() for t in gw_self])
+        b = (C.c_void_p * L)(*[t.data_ptr() for t in gw_neigh])
+        c = (C.c_void_p * L)(*[t.data_ptr() for t in gbias])
+        self._check(self.lib.gsplit_sage_bwd(self.h, C.byref(params.c), grad_logits.data_ptr(), a, b, c,
+                                             _stream()))
+
+    # -- inspection helpers for tests (copies of the device views; they synchronise) -------
+    def fetch_batch(self) -> dict:
+        """Copies the whole current batch to torch tensors, split by split (tests only)."""
+        S, L = self.S, self.L
+        n_local, n_mixed, n_edges, bucket = self.gsplit_batch_sizes()
+        dev = self.device
+        out = {"n_local": n_local, "n_mixed": n_mixed, "n_edges": n_edges, "bucket": bucket,
+               "local_front": [], "layers": []}
+        for l in range(L + 1):
+            v = self.gsplit_batch_level(l)
+            cat = _view_i32(v.d_local_cat, sum(n_local[l]), dev)
+            off = _view_i32(v.d_local_off, S + 1, dev)
+            assert off.tolist() == [sum(n_local[l][:s]) for s in range(S + 1)]
+            out["local_front"].append(list(torch.split(cat, n_local[l])))
+        for l in range(L):
+            v = self.gsplit_batch_layer(l)
+            fan = self.fanouts[l]
+            n_dst = sum(n_local[l + 1])
+            lay = {
+                "nbr": _view_i32(v.d_nbr, n_dst * fan, dev).view(n_dst, fan),
+                "cnt": _view_i32(v.d_cnt, n_dst, dev),
+                "mixed": list(torch.split(_view_i32(v.d_mixed_cat, sum(n_mixed[l]), dev), n_mixed[l])),
+                "blk_indptr": _view_i32(v.d_blk_indptr, n_dst + 1, dev),
+                "blk_src": _view_i32(v.d_blk_src, sum(n_edges[l]), dev),
+                "shuffle_src_row": list(torch.split(_view_i32(v.d_shuffle_src_row, sum(n_mixed[l]), dev),
+                                                    n_mixed[l])),
+                "recv": _view_i32(v.d_recv_cat, sum(sum(r) for r in bucket[l]), dev),
+                "recv_off": _view_i32(v.d_recv_off, S + 1, dev),
+            }
+            out["layers"].append(lay)
+        return out

@@ -1,0 +1,212 @@
+// Context life cycle, workspace sizing and the read-only views of the current batch.
+#include <algorithm>
+#include <cstring>
+
+#include "gsplit_internal.h"
+
+static thread_local std::string g_create_error;
+
+int gs_fail(gsplit_ctx *ctx, int code, const std::string &msg) {
+    if (ctx) ctx->err = msg;
+    else g_create_error = msg;
+    return code;
+}
+
+int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what) {
+    *p = nullptr;
+    if (bytes == 0) bytes = 256;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return gs_fail(ctx, GSPLIT_ENOMEM, std::string("hipMalloc failed for ") + what + " (" +
+                                               std::to_string(bytes) + " bytes)");
+    }
+    ctx->allocs.push_back(*p);
+    return GSPLIT_OK;
+}
+
+static void free_all(gsplit_ctx *ctx) {
+    for (void *p : ctx->allocs) (void)hipFree(p);
+    ctx->allocs.clear();
+    if (ctx->sample_done) (void)hipEventDestroy(ctx->sample_done);
+    ctx->sample_done = nullptr;
+}
+
+static int64_t pow2_at_least(int64_t x) {
+    int64_t p = 1024;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gsplit_config *c) {
+    if (!out || !g || !c) return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: NULL argument");
+    if (g->n_vertices <= 0 || g->n_vertices >= (1ll << 31) || g->n_edges < 0 || !g->d_indptr ||
+        (g->n_edges > 0 && !g->d_indices) || !g->d_pmap)
+        return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: bad graph");
+    if (g->n_splits < 1 || g->n_splits > GSPLIT_MAX_SPLITS)
+        return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: n_splits out of range");
+    if ((unsigned long long)g->n_vertices * (unsigned long long)g->n_splits >= 0xFFFFFFFFull)
+        return gs_fail(nullptr, GSPLIT_ECAPACITY, "gsplit_create: n_vertices * n_splits must be < 2^32 - 1");
+    if (c->n_layers < 1 || c->n_layers > GSPLIT_MAX_LAYERS || !c->fanouts || c->max_targets < 1)
+        return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: bad config");
+    for (int l = 0; l < c->n_layers; ++l)
+        if (c->fanouts[l] < 1 || c->fanouts[l] > GSPLIT_MAX_FANOUT)
+            return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: fanout out of range");
+    if (c->max_targets > g->n_vertices)
+        return gs_fail(nullptr, GSPLIT_EINVAL, "gsplit_create: max_targets exceeds n_vertices");
+
+    gsplit_ctx *ctx = new (std::nothrow) gsplit_ctx();
+    if (!ctx) return gs_fail(nullptr, GSPLIT_ENOMEM, "gsplit_create: host allocation failed");
+    ctx->graph = *g;
+    ctx->L = c->n_layers;
+    ctx->S = g->n_splits;
+    ctx->max_targets = c->max_targets;
+    for (int l = 0; l < ctx->L; ++l) ctx->fan[l] = c->fanouts[l];
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        delete ctx;
+        return gs_fail(nullptr, GSPLIT_EHIP, "gsplit_create: no HIP device");
+    }
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    // no-dedup upper bounds on the frontier sizes
+    const int L = ctx->L;
+    ctx->ub_front[L] = c->max_targets;
+    int64_t tab_cap = 1024;
+    for (int l = L - 1; l >= 0; --l) {
+        const int64_t grown = ctx->ub_front[l + 1] * (1 + ctx->fan[l]);
+        ctx->ub_front[l] = std::min<int64_t>(g->n_vertices, grown);
+        if (grown >= (1ll << 29)) {
+            delete ctx;
+            return gs_fail(nullptr, GSPLIT_ECAPACITY, "gsplit_create: frontier bound exceeds 2^29 slots");
+        }
+        tab_cap = std::max(tab_cap, pow2_at_least(2 * grown));
+    }
+    ctx->tab_cap = tab_cap;
+
+    int rc = GSPLIT_OK;
+    auto A = [&](void **p, size_t bytes, const char *what) {
+        if (rc == GSPLIT_OK) rc = gs_alloc(ctx, p, bytes, what);
+    };
+    for (int l = 0; l <= L; ++l) A((void **)&ctx->front[l], sizeof(int32_t) * ctx->ub_front[l], "front");
+    A((void **)&ctx->target_perm, sizeof(int32_t) * ctx->ub_front[L], "target_perm");
+    for (int l = 0; l < L; ++l) {
+        GsLayerBuf &B = ctx->layer[l];
+        const int64_t nd = ctx->ub_front[l + 1], f = ctx->fan[l];
+        A((void **)&B.nbr, sizeof(int32_t) * nd * f, "nbr");
+        A((void **)&B.cnt, sizeof(int32_t) * nd, "cnt");
+        A((void **)&B.mixed, sizeof(int32_t) * nd * (1 + f), "mixed");
+        A((void **)&B.blk_indptr, sizeof(int32_t) * (nd + 1), "blk_indptr");
+        A((void **)&B.blk_src, sizeof(int32_t) * nd * f, "blk_src");
+        A((void **)&B.recv, sizeof(int32_t) * nd * f, "recv");
+        A((void **)&B.src_row, sizeof(int32_t) * nd * (1 + f), "src_row");
+        A((void **)&B.self_row, sizeof(int32_t) * nd, "self_row");
+        A((void **)&B.edge_row, sizeof(int32_t) * nd * f, "edge_row");
+    }
+    A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
+    for (GsTable *t : {&ctx->tab_local, &ctx->tab_mixed}) {
+        A((void **)&t->keys, sizeof(uint32_t) * tab_cap, "table keys");
+        A((void **)&t->pos, sizeof(int32_t) * tab_cap, "table pos");
+        A((void **)&t->row, sizeof(int32_t) * tab_cap, "table row");
+    }
+    A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 9, "partition histogram");
+    A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 9, "partition bases");
+    if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)
+        rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
+    if (rc == GSPLIT_OK && hipEventCreateWithFlags(&ctx->sample_done, hipEventDisableTiming) != hipSuccess)
+        rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipEventCreate failed");
+    if (rc != GSPLIT_OK) {
+        g_create_error = ctx->err;
+        free_all(ctx);
+        delete ctx;
+        return rc;
+    }
+    std::memset(ctx->h_meta, 0, sizeof(ctx->h_meta));
+    *out = ctx;
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_destroy(gsplit_ctx *ctx) {
+    if (!ctx) return GSPLIT_OK;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+    return GSPLIT_OK;
+}
+
+extern "C" const char *gsplit_last_error(const gsplit_ctx *ctx) {
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+extern "C" int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level) {
+    if (!ctx || level < 0 || level > ctx->L) return GSPLIT_EINVAL;
+    return ctx->ub_front[level];
+}
+
+static int fetch_meta(gsplit_ctx *ctx) {
+    if (ctx->h_meta_valid) return GSPLIT_OK;
+    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "no batch has been sampled yet");
+    GS_HIP(ctx, hipEventSynchronize(ctx->sample_done));
+    GS_HIP(ctx, hipMemcpy(ctx->h_meta, ctx->d_meta, sizeof(GsLevelMeta) * (ctx->L + 1),
+                          hipMemcpyDeviceToHost));
+    if (ctx->h_meta[ctx->L].error != 0)
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split: a target id lies outside the graph");
+    for (int l = 0; l < ctx->L; ++l)
+        if (ctx->h_meta[l].error != 0)
+            return gs_fail(ctx, GSPLIT_ESTATE, "internal: hash table probe failed at layer " +
+                                                   std::to_string(l));
+    ctx->h_meta_valid = true;
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_batch_sizes(gsplit_ctx *ctx, int64_t *n_local, int64_t *n_mixed,
+                                  int64_t *n_edges, int64_t *bucket) {
+    if (!ctx) return GSPLIT_EINVAL;
+    int rc = fetch_meta(ctx);
+    if (rc != GSPLIT_OK) return rc;
+    const int S = ctx->S, L = ctx->L;
+    std::vector<int32_t> indptr_at;  // block CSR offsets at the split boundaries
+    for (int l = 0; l <= L; ++l)
+        for (int s = 0; s < S; ++s)
+            if (n_local) n_local[l * S + s] = ctx->h_meta[l].front_off[s + 1] - ctx->h_meta[l].front_off[s];
+    for (int l = 0; l < L; ++l) {
+        for (int s = 0; s < S; ++s) {
+            if (n_mixed) n_mixed[l * S + s] = ctx->h_meta[l].mixed_off[s + 1] - ctx->h_meta[l].mixed_off[s];
+            if (bucket)
+                for (int t = 0; t < S; ++t)
+                    bucket[(l * S + s) * S + t] = ctx->h_meta[l].bucket_cnt[s * GS_MAXS + t];
+        }
+        if (n_edges) {
+            int32_t cut[GS_MAXS + 1];
+            for (int s = 0; s <= S; ++s)
+                GS_HIP(ctx, hipMemcpy(&cut[s], ctx->layer[l].blk_indptr + ctx->h_meta[l + 1].front_off[s],
+                                      sizeof(int32_t), hipMemcpyDeviceToHost));
+            for (int s = 0; s < S; ++s) n_edges[l * S + s] = cut[s + 1] - cut[s];
+        }
+    }
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_batch_level(const gsplit_ctx *ctx, int32_t level, gsplit_level_view *out) {
+    if (!ctx || !out || level < 0 || level > ctx->L) return GSPLIT_EINVAL;
+    out->d_local_cat = ctx->front[level];
+    out->d_local_off = ctx->d_meta[level].front_off;
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_layer_view *out) {
+    if (!ctx || !out || layer < 0 || layer >= ctx->L) return GSPLIT_EINVAL;
+    const GsLayerBuf &B = ctx->layer[layer];
+    out->d_nbr = B.nbr;
+    out->d_cnt = B.cnt;
+    out->d_mixed_cat = B.mixed;
+    out->d_mixed_off = ctx->d_meta[layer].mixed_off;
+    out->d_blk_indptr = B.blk_indptr;
+    out->d_blk_src = B.blk_src;
+    out->d_shuffle_src_row = B.src_row;
+    out->d_recv_cat = B.recv;
+    out->d_recv_off = ctx->d_meta[layer].recv_off;
+    return GSPLIT_OK;
+}

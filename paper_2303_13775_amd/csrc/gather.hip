@@ -1,0 +1,77 @@
+// Loading step (paper section 3): copy the feature rows of the layer-0 local frontiers from the
+// HBM-resident table into a dense buffer, splits concatenated.  No arithmetic: the kernel is a
+// pure HBM stream (random 256..512-byte row reads, fully coalesced writes), so it moves 16 bytes
+// per lane and keeps several independent loads in flight per lane.
+#include <algorithm>
+
+#include "gsplit_internal.h"
+
+namespace {
+
+template <typename VecT, int UNROLL>
+__global__ __launch_bounds__(256) void k_gather_rows(const uint8_t *__restrict__ table,
+                                                     int64_t row_stride_bytes, int vec_per_row,
+                                                     const int32_t *__restrict__ ids,
+                                                     const GsLevelMeta *__restrict__ meta0, int S,
+                                                     VecT *__restrict__ out) {
+    const int64_t n_rows = meta0->front_off[S];
+    const int64_t total = n_rows * vec_per_row;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    for (; x + (UNROLL - 1) * stride < total; x += UNROLL * stride) {
+        VecT v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t y = x + u * stride;
+            const int64_t r = y / vec_per_row;
+            const int c = (int)(y - r * vec_per_row);
+            v[u] = *reinterpret_cast<const VecT *>(table + (int64_t)ids[r] * row_stride_bytes +
+                                                   (int64_t)c * sizeof(VecT));
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) out[x + u * stride] = v[u];
+    }
+    for (; x < total; x += stride) {
+        const int64_t r = x / vec_per_row;
+        const int c = (int)(x - r * vec_per_row);
+        out[x] = *reinterpret_cast<const VecT *>(table + (int64_t)ids[r] * row_stride_bytes +
+                                                 (int64_t)c * sizeof(VecT));
+    }
+}
+
+}  // namespace
+
+extern "C" int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int32_t dtype, int64_t dim,
+                                      int64_t row_stride_bytes, void *d_out, void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    if (!d_table || !d_out || dim <= 0 || (dtype != GSPLIT_F32 && dtype != GSPLIT_BF16))
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_gather_features: bad argument");
+    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_gather_features: no batch");
+    const int64_t row_bytes = dim * (dtype == GSPLIT_F32 ? 4 : 2);
+    if (row_stride_bytes < row_bytes)
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_gather_features: row stride smaller than a row");
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t ub_rows = ctx->ub_front[0];
+    const GsLevelMeta *m0 = ctx->d_meta;
+    const int grid = (int)std::min<int64_t>((int64_t)ctx->n_cu * 16,
+                                            std::max<int64_t>(1, gs_ceil_div(ub_rows * gs_ceil_div(row_bytes, 16), 256 * 4)));
+    const bool a16 = row_bytes % 16 == 0 && row_stride_bytes % 16 == 0 &&
+                     ((uintptr_t)d_table % 16) == 0 && ((uintptr_t)d_out % 16) == 0;
+    const bool a4 = row_bytes % 4 == 0 && row_stride_bytes % 4 == 0 && ((uintptr_t)d_table % 4) == 0 &&
+                    ((uintptr_t)d_out % 4) == 0;
+    if (a16) {
+        hipLaunchKernelGGL((k_gather_rows<uint4, 4>), dim3(grid), dim3(256), 0, st,
+                           (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 16),
+                           ctx->front[0], m0, ctx->S, (uint4 *)d_out);
+    } else if (a4) {
+        hipLaunchKernelGGL((k_gather_rows<uint32_t, 4>), dim3(grid), dim3(256), 0, st,
+                           (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 4),
+                           ctx->front[0], m0, ctx->S, (uint32_t *)d_out);
+    } else {
+        hipLaunchKernelGGL((k_gather_rows<uint16_t, 4>), dim3(grid), dim3(256), 0, st,
+                           (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 2),
+                           ctx->front[0], m0, ctx->S, (uint16_t *)d_out);
+    }
+    GS_HIP(ctx, hipGetLastError());
+    return GSPLIT_OK;
+}

@@ -1,0 +1,104 @@
+// Internal definitions shared by the HIP translation units of libgsplit (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "gsplit.h"
+
+#define GS_MAXS GSPLIT_MAX_SPLITS
+#define GS_MAXL GSPLIT_MAX_LAYERS
+
+// Device-resident bookkeeping of one level l (0..L) of the current batch.  Every kernel reads its
+// problem sizes from here, so a whole iteration is enqueued without a host round trip.
+//   front_off : split offsets of local_cat[l]            (front_off[S] = |local_cat[l]|)
+// and, for sampling layer l (expanding level l+1 into level l):
+//   mixed_off : split offsets of the concatenated mixed frontiers
+//   recv_off  : receiver offsets of the concatenated received buckets
+//   bucket_cnt: ids split s hands to split t, at [s * GS_MAXS + t]
+//   nnz       : number of sampled edges of the layer
+struct GsLevelMeta {
+    int32_t front_off[GS_MAXS + 1];
+    int32_t mixed_off[GS_MAXS + 1];
+    int32_t recv_off[GS_MAXS + 1];
+    int32_t bucket_cnt[GS_MAXS * GS_MAXS];
+    int32_t nnz;
+    int32_t error;      // set non-zero by a kernel that hit an impossible state (probe overflow)
+    int32_t pad[2];
+};
+
+// Open-addressing table in HBM: key -> (smallest position seen, final row).
+struct GsTable {
+    uint32_t *keys;
+    int32_t  *pos;
+    int32_t  *row;
+};
+
+struct GsLayerBuf {            // sampling layer l
+    int32_t *nbr = nullptr;        // [ub_dst * fan]
+    int32_t *cnt = nullptr;        // [ub_dst]
+    int32_t *mixed = nullptr;      // [ub_dst * (1 + fan)]
+    int32_t *blk_indptr = nullptr; // [ub_dst + 1]
+    int32_t *blk_src = nullptr;    // [ub_dst * fan]
+    int32_t *recv = nullptr;       // [ub_dst * fan]
+    int32_t *src_row = nullptr;    // [ub_dst * (1 + fan)]
+    int32_t *self_row = nullptr;   // [ub_dst]        row of local_cat[l] of each destination vertex
+    int32_t *edge_row = nullptr;   // [ub_dst * fan]  row of local_cat[l] of each edge's source
+};
+
+struct GsSageBuf {             // activations kept between forward and backward
+    bool     ready = false;
+    int32_t  dtype = -1;
+    int32_t  dims[GS_MAXL + 1] = {0};
+    void    *hidden[GS_MAXL + 1] = {nullptr};   // local_cat activations of level 1..L-1
+    void    *mean[GS_MAXL] = {nullptr};         // aggregated neighbourhood means per layer
+    float   *ghid[GS_MAXL + 1] = {nullptr};     // d loss / d hidden of level 1..L
+    float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before scatter
+    void    *wcat[GS_MAXL] = {nullptr};         // stacked [W_self; W_neigh] per layer
+    bool     fwd_done = false;
+    uint64_t fwd_batch = 0;
+};
+
+struct gsplit_ctx {
+    gsplit_graph graph;
+    int32_t  L = 0, S = 0;
+    int32_t  fan[GS_MAXL] = {0};
+    int64_t  max_targets = 0;
+    int64_t  ub_front[GS_MAXL + 1] = {0};   // upper bounds on |local_cat[l]|
+    int      n_cu = 256;
+
+    int32_t     *front[GS_MAXL + 1] = {nullptr};
+    int32_t     *target_perm = nullptr;
+    GsLayerBuf   layer[GS_MAXL];
+    GsLevelMeta *d_meta = nullptr;          // [L + 1]
+    GsLevelMeta  h_meta[GS_MAXL + 1];
+    bool         h_meta_valid = false;
+    GsTable      tab_local, tab_mixed;
+    int64_t      tab_cap = 0;
+    int32_t     *part_hist = nullptr;       // partition scratch
+    int32_t     *part_base = nullptr;
+
+    uint64_t     batch_id = 0;
+    int64_t      n_targets = 0;
+    hipStream_t  last_stream = nullptr;
+    hipEvent_t   sample_done = nullptr;
+
+    GsSageBuf    sage;
+    std::vector<void *> allocs;
+    std::string  err;
+};
+
+int gs_fail(gsplit_ctx *ctx, int code, const std::string &msg);
+int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what);
+
+#define GS_HIP(ctx, call)                                                                  \
+    do {                                                                                   \
+        hipError_t e__ = (call);                                                           \
+        if (e__ != hipSuccess)                                                             \
+            return gs_fail((ctx), GSPLIT_EHIP, std::string(#call) + ": " + hipGetErrorString(e__)); \
+    } while (0)
+
+static inline int64_t gs_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

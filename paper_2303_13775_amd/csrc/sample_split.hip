@@ -1,0 +1,655 @@
+// Split-parallel sampling for all S logical splits at once (paper Algorithm 1, `sp_sample`, with
+// the online splitting of section 4): neighbour sampling, mixed-frontier dedup/relabel, owner
+// buckets, next local frontiers and the shuffle index.  Every kernel takes its problem size from
+// device memory (GsLevelMeta), so one iteration is enqueued without any host synchronisation and
+// the launch shapes depend only on the context's upper bounds.
+#include "gsplit_internal.h"
+
+namespace {
+
+constexpr int PART_NB = 1024;   // chunks of a partition pass (one workgroup each)
+constexpr int PART_BS = 256;
+constexpr int PART_NK = 9;      // up to 8 split classes + 1 auxiliary counter
+constexpr uint32_t EMPTY_KEY = 0xFFFFFFFFu;
+
+// ------------------------------------------------------------------------------------------
+// small device helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+    return (1ull << lane_id()) - 1ull;
+}
+
+// which split a row of a split-concatenated array belongs to (off has S+1 entries)
+__device__ __forceinline__ int split_of(const int32_t *off, int S, int i) {
+    int s = 0;
+    for (int k = 1; k < S; ++k) s += (off[k] <= i) ? 1 : 0;
+    return s;
+}
+
+__device__ __forceinline__ int table_bits(int n_inputs) {
+    // capacity = 2^bits >= 2 * n_inputs, at least 1024 entries
+    int want = n_inputs < 512 ? 1024 : 2 * n_inputs;
+    return 32 - __clz(want - 1);
+}
+
+__device__ __forceinline__ uint32_t table_slot(uint32_t key, int bits) {
+    return (key * 0x9E3779B1u) >> (32 - bits);
+}
+
+// insert key, remember the smallest position that carried it
+__device__ __forceinline__ void table_insert(const GsTable &t, int bits, uint32_t key, int32_t p,
+                                             int32_t *err) {
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t h = table_slot(key, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        uint32_t old = atomicCAS(&t.keys[h], EMPTY_KEY, key);
+        if (old == EMPTY_KEY || old == key) {
+            atomicMin(&t.pos[h], p);
+            return;
+        }
+        h = (h + 1) & mask;
+    }
+    *err = 1;
+}
+
+// slot of a key that is known to be present (-1 and the error flag if it is not)
+__device__ __forceinline__ int table_find(const GsTable &t, int bits, uint32_t key, int32_t *err) {
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t h = table_slot(key, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        uint32_t k = t.keys[h];
+        if (k == key) return (int)h;
+        if (k == EMPTY_KEY) break;
+        h = (h + 1) & mask;
+    }
+    *err = 2;
+    return -1;
+}
+
+// ------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): counter-based generator, 10 rounds.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        c = make_uint4(hi1 ^ c.y ^ k.x, lo1, hi0 ^ c.w ^ k.y, lo0);
+        k.x += 0x9E3779B9u;
+        k.y += 0xBB67AE85u;
+    }
+    return c;
+}
+
+// ------------------------------------------------------------------------------------------
+// sample_layer: G lanes cooperate on one frontier vertex (G = 16, 32 or 64 >= fanout).
+// degree <= fanout: copy the row in CSR order.  Otherwise Floyd's selection: lane q draws
+// t_q in [0, d-fan+q] from its own Philox word; the sequential "already chosen -> take j"
+// rule is resolved with fan-1 rounds of broadcast + ballot inside the lane group.
+// The random word of draw q is word (q mod 4) of Philox(counter = (v, iter lo, iter hi,
+// layer * 65536 + q / 4), key = (seed lo, seed hi)): a function of the global vertex id only.
+// ------------------------------------------------------------------------------------------
+template <int G, typename IndPtrT>
+__global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
+                                                      const int32_t *__restrict__ indices,
+                                                      const int32_t *__restrict__ front,
+                                                      const GsLevelMeta *__restrict__ meta_up, int S,
+                                                      int fan, uint32_t layer, uint64_t seed,
+                                                      uint64_t iter, int32_t *__restrict__ nbr,
+                                                      int32_t *__restrict__ cnt) {
+    const int n1 = meta_up->front_off[S];
+    const int groups_per_block = PART_BS / G;
+    const int q = threadIdx.x % G;
+    const int sub = lane_id() / G;
+    const uint64_t gmask = (G == 64) ? ~0ull : ((1ull << G) - 1ull);
+    const int stride = gridDim.x * groups_per_block;
+    // every lane of a wave runs the same number of iterations (ballots/shuffles need that)
+    const int first = blockIdx.x * groups_per_block + (threadIdx.x / 64) * (64 / G);
+    for (int base = first; base < n1; base += stride) {
+        const int row = base + sub;
+        const bool active = row < n1;
+        int32_t v = 0;
+        int64_t beg = 0;
+        uint32_t d = 0;
+        if (active) {
+            v = front[row];
+            beg = (int64_t)indptr[v];
+            d = (uint32_t)((int64_t)indptr[v + 1] - beg);
+        }
+        int32_t val = -1;
+        const bool floyd = active && d > (uint32_t)fan;
+        uint32_t chosen = 0, t = 0, j = 0;
+        if (floyd && q < fan) {
+            uint4 ctr = make_uint4((uint32_t)v, (uint32_t)iter, (uint32_t)(iter >> 32),
+                                   (layer << 16) | ((uint32_t)q >> 2));
+            uint4 r = philox4x32_10(ctr, make_uint2((uint32_t)seed, (uint32_t)(seed >> 32)));
+            uint32_t w = (q & 3) == 0 ? r.x : (q & 3) == 1 ? r.y : (q & 3) == 2 ? r.z : r.w;
+            j = d - (uint32_t)fan + (uint32_t)q;
+            t = __umulhi(w, j + 1u);
+            chosen = t;
+        }
+        // does any group of this wave need the sequential resolution?
+        if (__ballot(floyd) != 0ull) {
+            for (int s = 1; s < fan; ++s) {
+                const uint32_t ts = __shfl(t, s, G);
+                const bool hit = floyd && q < s && chosen == ts;
+                const uint64_t any = (__ballot(hit) >> (sub * G)) & gmask;
+                if (floyd && q == s && any != 0ull) chosen = j;
+            }
+        }
+        if (active && q < fan) {
+            if (floyd) val = indices[beg + (int64_t)chosen];
+            else if ((uint32_t)q < d) val = indices[beg + q];
+            nbr[(int64_t)row * fan + q] = val;
+            if (q == 0) cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// table reset (sized on the device from the live frontier size) + per-layer counters
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_reset_tables(GsTable a, GsTable b, GsLevelMeta *meta_lo,
+                                                      const GsLevelMeta *meta_up, int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
+    const int64_t cap = 1ll << bits;
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < cap;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        a.keys[i] = EMPTY_KEY; a.pos[i] = 0x7FFFFFFF;
+        b.keys[i] = EMPTY_KEY; b.pos[i] = 0x7FFFFFFF;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < GS_MAXS * GS_MAXS) meta_lo->bucket_cnt[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { meta_lo->error = 0; }
+}
+
+// mixed-frontier table: key (vertex, split) -> first position in (destination vertices, slots)
+__global__ __launch_bounds__(256) void k_insert_mixed(GsTable tab, const int32_t *__restrict__ front,
+                                                      const int32_t *__restrict__ nbr,
+                                                      const int32_t *__restrict__ cnt,
+                                                      GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
+                                                      int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
+    const int64_t total = (int64_t)n1 * (1 + fan);
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
+         x += (int64_t)gridDim.x * blockDim.x) {
+        int32_t id, i;
+        if (x < n1) { i = (int)x; id = front[i]; }
+        else {
+            const int64_t g = x - n1;
+            i = (int)(g / fan);
+            if ((int)(g - (int64_t)i * fan) >= cnt[i]) continue;
+            id = nbr[g];
+        }
+        const int s = split_of(meta_up->front_off, S, i);
+        table_insert(tab, bits, (uint32_t)id * (uint32_t)S + (uint32_t)s, (int32_t)x, &meta_lo->error);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stable multi-class partition: three launches (count per chunk, scan, scatter).
+// A functor F describes the elements:
+//   n()                       number of elements (read from device memory)
+//   classify(g)               bit k set <=> element g counts in class k  (k < F::NK)
+//   key_bases(totals, bases)  run by one thread between the passes: where each class starts
+//   emit(g, mask, rk)         rk[k] = bases[k] + number of class-k elements before g
+//   n_extra(), extra(g)       an independent element-wise epilogue of the scatter pass
+// Elements keep their order inside every class (wave ballots + running chunk counters).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int part_chunk(int n) {
+    int c = (n + PART_NB - 1) / PART_NB;
+    return ((c + PART_BS - 1) / PART_BS) * PART_BS;
+}
+
+template <class F>
+__global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict__ hist) {
+    __shared__ int s_cnt[PART_NK];
+    if (threadIdx.x < PART_NK) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int n = f.n();
+    const int chunk = part_chunk(n);
+    const int64_t beg64 = (int64_t)blockIdx.x * chunk;
+    if (beg64 < n) {
+        const int beg = (int)beg64;
+        const int end = (n - beg < chunk) ? n : beg + chunk;
+        int local[F::NK];
+#pragma unroll
+        for (int k = 0; k < F::NK; ++k) local[k] = 0;
+        for (int g = beg + threadIdx.x; g < end; g += PART_BS) {
+            const unsigned m = f.classify(g);
+#pragma unroll
+            for (int k = 0; k < F::NK; ++k) local[k] += (m >> k) & 1u;
+        }
+#pragma unroll
+        for (int k = 0; k < F::NK; ++k) {
+            int v = local[k];
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+            if (lane_id() == 0 && v) atomicAdd(&s_cnt[k], v);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < F::NK) hist[blockIdx.x * PART_NK + threadIdx.x] = s_cnt[threadIdx.x];
+}
+
+template <class F>
+__global__ __launch_bounds__(PART_NB) void k_part_scan(F f, const int32_t *__restrict__ hist,
+                                                       int32_t *__restrict__ base) {
+    __shared__ int s_wsum[PART_NB / 64];
+    __shared__ int s_tot[PART_NK], s_base[PART_NK];
+    const int b = threadIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
+    int ex[F::NK];
+#pragma unroll
+    for (int k = 0; k < F::NK; ++k) {
+        const int v = hist[b * PART_NK + k];
+        int inc = v;
+        for (int o = 1; o < 64; o <<= 1) {
+            int up = __shfl_up(inc, o);
+            if (lane >= o) inc += up;
+        }
+        if (lane == 63) s_wsum[wave] = inc;
+        __syncthreads();
+        int pre = 0, tot = 0;
+        for (int w = 0; w < PART_NB / 64; ++w) {
+            const int x = s_wsum[w];
+            pre += (w < wave) ? x : 0;
+            tot += x;
+        }
+        ex[k] = pre + inc - v;
+        if (b == 0) s_tot[k] = tot;
+        __syncthreads();
+    }
+    if (b == 0) f.key_bases(s_tot, s_base);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < F::NK; ++k) base[b * PART_NK + k] = s_base[k] + ex[k];
+}
+
+template <class F>
+__global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__restrict__ base) {
+    __shared__ int s_run[PART_NK];
+    __shared__ int s_wcnt[PART_BS / 64][PART_NK];
+    const int n = f.n();
+    const int chunk = part_chunk(n);
+    const int64_t beg64 = (int64_t)blockIdx.x * chunk;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    if (beg64 < n) {
+        const int beg = (int)beg64;
+        const int end = (n - beg < chunk) ? n : beg + chunk;
+        if (threadIdx.x < F::NK) s_run[threadIdx.x] = base[blockIdx.x * PART_NK + threadIdx.x];
+        __syncthreads();
+        for (int tile = beg; tile < end; tile += PART_BS) {
+            const int g = tile + threadIdx.x;
+            const bool in = g < end;
+            const unsigned m = in ? f.classify(g) : 0u;
+            int rk[F::NK];
+#pragma unroll
+            for (int k = 0; k < F::NK; ++k) {
+                const uint64_t bal = __ballot((m >> k) & 1u);
+                rk[k] = __popcll(bal & lanemask_lt());
+                if (lane == 0) s_wcnt[wave][k] = __popcll(bal);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < F::NK; ++k) {
+                int pre = s_run[k];
+                for (int w = 0; w < PART_BS / 64; ++w) pre += (w < wave) ? s_wcnt[w][k] : 0;
+                rk[k] += pre;
+            }
+            if (in) f.emit(g, m, rk);
+            __syncthreads();
+            if (threadIdx.x < F::NK) {
+                int add = 0;
+                for (int w = 0; w < PART_BS / 64; ++w) add += s_wcnt[w][threadIdx.x];
+                s_run[threadIdx.x] += add;
+            }
+            __syncthreads();
+        }
+    }
+    const int64_t nx = f.n_extra();
+    for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < nx;
+         g += (int64_t)gridDim.x * PART_BS)
+        f.extra(g);
+}
+
+// ---- local_front[L] = targets separated by owner, order kept ---------------------------------
+struct PartTargets {
+    static constexpr int NK = GS_MAXS;
+    const int32_t *targets; int n_targets; const uint8_t *pmap; int S; uint32_t n_vertices;
+    int32_t *front; int32_t *perm; GsLevelMeta *meta;
+    __device__ int n() const { return n_targets; }
+    // an id outside the graph is replaced by vertex 0 and reported through the error flag
+    __device__ int32_t target(int g) const {
+        const uint32_t id = (uint32_t)targets[g];
+        if (id < n_vertices) return (int32_t)id;
+        meta->error = 3;
+        return 0;
+    }
+    __device__ unsigned classify(int g) const { return 1u << (pmap[target(g)] & (GS_MAXS - 1)); }
+    __device__ void key_bases(const int *tot, int *bases) const {
+        int acc = 0;
+        for (int k = 0; k < GS_MAXS; ++k) {
+            bases[k] = acc;
+            if (k <= S) meta->front_off[k] = acc;
+            acc += (k < S) ? tot[k] : 0;
+        }
+        meta->front_off[S] = acc;
+    }
+    __device__ void emit(int g, unsigned m, const int *rk) const {
+        const int k = __ffs(m) - 1;
+        front[rk[k]] = target(g);
+        perm[rk[k]] = g;
+    }
+    __device__ int64_t n_extra() const { return 0; }
+    __device__ void extra(int64_t) const {}
+};
+
+// ---- mixed frontiers: destination vertices first, then first occurrences among the slots -----
+// class s (< S): slot is the first occurrence of its vertex in split s; class 8: slot is valid
+// (its exclusive rank is the edge number, which yields the block CSR offsets).
+struct PartMixed {
+    static constexpr int NK = PART_NK;
+    GsTable tab; const int32_t *front; const int32_t *nbr; const int32_t *cnt;
+    int32_t *mixed; int32_t *blk_indptr;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
+    __device__ int n1() const { return meta_up->front_off[S]; }
+    __device__ int n() const { return n1() * fan; }
+    __device__ unsigned classify(int g) const {
+        const int i = g / fan, q = g - i * fan;
+        if (q >= cnt[i]) return 0u;
+        const int s = split_of(meta_up->front_off, S, i);
+        const int bits = table_bits(n1() * (1 + fan));
+        const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        const bool first = h >= 0 && tab.pos[h] == n1() + g;
+        return (1u << 8) | (first ? (1u << s) : 0u);
+    }
+    __device__ void key_bases(const int *tot, int *bases) const {
+        int acc = 0;
+        for (int s = 0; s < GS_MAXS; ++s) {
+            const int n_dst = (s < S) ? meta_up->front_off[s + 1] - meta_up->front_off[s] : 0;
+            if (s <= S) meta_lo->mixed_off[s] = acc;
+            bases[s] = acc + n_dst;
+            acc += n_dst + ((s < S) ? tot[s] : 0);
+        }
+        meta_lo->mixed_off[S] = acc;
+        bases[8] = 0;
+        meta_lo->nnz = tot[8];
+        blk_indptr[n1()] = tot[8];
+    }
+    __device__ void emit(int g, unsigned m, const int *rk) const {
+        const int i = g / fan, q = g - i * fan;
+        if (q == 0) blk_indptr[i] = rk[8];
+        const unsigned sm = m & 0xFFu;
+        if (sm) {
+            const int s = __ffs(sm) - 1;
+            const int bits = table_bits(n1() * (1 + fan));
+            const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+            mixed[rk[s]] = nbr[g];
+            if (h >= 0) tab.row[h] = rk[s] - meta_lo->mixed_off[s];
+        }
+    }
+    // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier
+    __device__ int64_t n_extra() const { return n1(); }
+    __device__ void extra(int64_t x) const {
+        const int i = (int)x;
+        const int s = split_of(meta_up->front_off, S, i);
+        const int loc = i - meta_up->front_off[s];
+        const int bits = table_bits(n1() * (1 + fan));
+        const int32_t id = front[i];
+        const int h = table_find(tab, bits, (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        mixed[meta_lo->mixed_off[s] + loc] = id;
+        if (h >= 0) tab.row[h] = loc;
+    }
+};
+
+// PartMixed::emit writes blk_indptr only for slot 0 of each row; rows exist for every frontier
+// vertex, valid or not, because classify() is evaluated for all n1 * fan slots.
+
+// edges[l] in mixed-frontier rows
+__global__ __launch_bounds__(256) void k_relabel_edges(GsTable tab, const int32_t *__restrict__ nbr,
+                                                       const int32_t *__restrict__ cnt,
+                                                       const int32_t *__restrict__ blk_indptr,
+                                                       int32_t *__restrict__ blk_src,
+                                                       GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
+                                                       int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
+    const int64_t total = (int64_t)n1 * fan;
+    for (int64_t g = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; g < total;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+        if (q >= cnt[i]) continue;
+        const int s = split_of(meta_up->front_off, S, i);
+        const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        blk_src[blk_indptr[i] + q] = h >= 0 ? tab.row[h] : -1;
+    }
+}
+
+// ---- split(): owner buckets of the sampled part of every mixed frontier ----------------------
+// Elements are the rows of the concatenated mixed frontiers; class t = f_G(vertex) for rows beyond
+// the destination prefix.  Partitioning the sender-ordered stream by owner yields, for each
+// receiver t, bucket[0->t] | bucket[1->t] | ... : the send buffers and the received concatenation
+// are the same memory on one GPU.
+struct PartBuckets {
+    static constexpr int NK = GS_MAXS;
+    const int32_t *mixed; const uint8_t *pmap; int32_t *recv;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S;
+    __device__ int n() const { return meta_lo->mixed_off[S]; }
+    __device__ unsigned classify(int j) const {
+        const int s = split_of(meta_lo->mixed_off, S, j);
+        const int n_dst = meta_up->front_off[s + 1] - meta_up->front_off[s];
+        if (j - meta_lo->mixed_off[s] < n_dst) return 0u;
+        return 1u << (pmap[mixed[j]] & (GS_MAXS - 1));
+    }
+    __device__ void key_bases(const int *tot, int *bases) const {
+        int acc = 0;
+        for (int t = 0; t < GS_MAXS; ++t) {
+            bases[t] = acc;
+            if (t <= S) meta_lo->recv_off[t] = acc;
+            acc += (t < S) ? tot[t] : 0;
+        }
+        meta_lo->recv_off[S] = acc;
+    }
+    __device__ void emit(int j, unsigned m, const int *rk) const {
+        if (!m) return;
+        const int t = __ffs(m) - 1;
+        recv[rk[t]] = mixed[j];
+        const int s = split_of(meta_lo->mixed_off, S, j);
+        atomicAdd(&meta_lo->bucket_cnt[s * GS_MAXS + t], 1);
+    }
+    __device__ int64_t n_extra() const { return 0; }
+    __device__ void extra(int64_t) const {}
+};
+
+// local-frontier table: key vertex -> first position in (own destination vertices, received ids)
+__global__ __launch_bounds__(256) void k_insert_local(GsTable tab, const int32_t *__restrict__ front,
+                                                      const int32_t *__restrict__ recv,
+                                                      GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
+                                                      int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
+    const int64_t total = (int64_t)n1 + meta_lo->recv_off[S];
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
+         x += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t id = x < n1 ? front[x] : recv[x - n1];
+        table_insert(tab, bits, (uint32_t)id, (int32_t)x, &meta_lo->error);
+    }
+}
+
+// ---- next local frontiers: own destination vertices, then first occurrences of what arrived --
+struct PartLocal {
+    static constexpr int NK = GS_MAXS;
+    GsTable tab; const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
+    __device__ int n1() const { return meta_up->front_off[S]; }
+    __device__ int n() const { return meta_lo->recv_off[S]; }
+    __device__ unsigned classify(int r) const {
+        const int bits = table_bits(n1() * (1 + fan));
+        const int h = table_find(tab, bits, (uint32_t)recv[r], &meta_lo->error);
+        if (h < 0 || tab.pos[h] != n1() + r) return 0u;
+        return 1u << split_of(meta_lo->recv_off, S, r);
+    }
+    __device__ void key_bases(const int *tot, int *bases) const {
+        int acc = 0;
+        for (int t = 0; t < GS_MAXS; ++t) {
+            const int n_up = (t < S) ? meta_up->front_off[t + 1] - meta_up->front_off[t] : 0;
+            if (t <= S) meta_lo->front_off[t] = acc;
+            bases[t] = acc + n_up;
+            acc += n_up + ((t < S) ? tot[t] : 0);
+        }
+        meta_lo->front_off[S] = acc;
+    }
+    __device__ void emit(int r, unsigned m, const int *rk) const {
+        if (!m) return;
+        const int t = __ffs(m) - 1;
+        const int bits = table_bits(n1() * (1 + fan));
+        const int h = table_find(tab, bits, (uint32_t)recv[r], &meta_lo->error);
+        front_lo[rk[t]] = recv[r];
+        if (h >= 0) tab.row[h] = rk[t];
+    }
+    __device__ int64_t n_extra() const { return n1(); }
+    __device__ void extra(int64_t x) const {
+        const int i = (int)x;
+        const int t = split_of(meta_up->front_off, S, i);
+        const int rowp = meta_lo->front_off[t] + (i - meta_up->front_off[t]);
+        const int bits = table_bits(n1() * (1 + fan));
+        const int32_t id = front_up[i];
+        const int h = table_find(tab, bits, (uint32_t)id, &meta_lo->error);
+        front_lo[rowp] = id;
+        if (h >= 0) tab.row[h] = rowp;
+    }
+};
+
+// shuffle index of every mixed-frontier row, and the same lookup composed with edges[l] for the
+// on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge)
+__global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab, const int32_t *__restrict__ mixed,
+                                                       const int32_t *__restrict__ front_up,
+                                                       const int32_t *__restrict__ nbr,
+                                                       const int32_t *__restrict__ cnt,
+                                                       const int32_t *__restrict__ blk_indptr,
+                                                       int32_t *__restrict__ src_row,
+                                                       int32_t *__restrict__ self_row,
+                                                       int32_t *__restrict__ edge_row,
+                                                       GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
+                                                       int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
+    const int64_t n_mixed = meta_lo->mixed_off[S];
+    const int64_t n_slots = (int64_t)n1 * fan;
+    const int64_t total = n_mixed + n1 + n_slots;
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
+         x += (int64_t)gridDim.x * blockDim.x) {
+        if (x < n_mixed) {
+            const int h = table_find(tab, bits, (uint32_t)mixed[x], &meta_lo->error);
+            src_row[x] = h >= 0 ? tab.row[h] : -1;
+        } else if (x < n_mixed + n1) {
+            const int i = (int)(x - n_mixed);
+            const int h = table_find(tab, bits, (uint32_t)front_up[i], &meta_lo->error);
+            self_row[i] = h >= 0 ? tab.row[h] : -1;
+        } else {
+            const int64_t g = x - n_mixed - n1;
+            const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+            if (q >= cnt[i]) continue;
+            const int h = table_find(tab, bits, (uint32_t)nbr[g], &meta_lo->error);
+            edge_row[blk_indptr[i] + q] = h >= 0 ? tab.row[h] : -1;
+        }
+    }
+}
+
+__global__ void k_clear_error(GsLevelMeta *meta) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) meta->error = 0;
+}
+
+template <class F>
+void run_partition(gsplit_ctx *ctx, const F &f, hipStream_t st) {
+    hipLaunchKernelGGL(k_part_count<F>, dim3(PART_NB), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    hipLaunchKernelGGL(k_part_scan<F>, dim3(1), dim3(PART_NB), 0, st, f, ctx->part_hist, ctx->part_base);
+    hipLaunchKernelGGL(k_part_scatter<F>, dim3(PART_NB), dim3(PART_BS), 0, st, f, ctx->part_base);
+}
+
+int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
+    int64_t want = gs_ceil_div(upper_items, 256);
+    int64_t cap = (int64_t)ctx->n_cu * 8;
+    if (want < 1) want = 1;
+    return (int)(want < cap ? want : cap);
+}
+
+template <typename IndPtrT>
+void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStream_t st) {
+    const int fan = ctx->fan[l];
+    const int64_t ub = ctx->ub_front[l + 1];
+    const GsLevelMeta *mu = ctx->d_meta + (l + 1);
+    const IndPtrT *ip = (const IndPtrT *)ctx->graph.d_indptr;
+    GsLayerBuf &B = ctx->layer[l];
+    if (fan <= 16) {
+        hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, B.nbr, B.cnt);
+    } else if (fan <= 32) {
+        hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, B.nbr, B.cnt);
+    } else {
+        hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, B.nbr, B.cnt);
+    }
+}
+
+}  // namespace
+
+extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+                                   uint64_t seed, uint64_t iter, void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    if (n_targets < 0 || (n_targets > 0 && !d_targets))
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split: bad targets");
+    if (n_targets > ctx->max_targets)
+        return gs_fail(ctx, GSPLIT_ECAPACITY, "gsplit_sample_split: n_targets exceeds max_targets");
+    hipStream_t st = (hipStream_t)stream;
+    const int S = ctx->S, L = ctx->L;
+
+    ctx->batch_id += 1;
+    ctx->n_targets = n_targets;
+    ctx->h_meta_valid = false;
+    ctx->sage.fwd_done = false;
+    ctx->last_stream = st;
+
+    hipLaunchKernelGGL(k_clear_error, dim3(1), dim3(64), 0, st, ctx->d_meta + L);
+    PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
+                   ctx->front[L], ctx->target_perm, ctx->d_meta + L};
+    run_partition(ctx, pt, st);
+
+    for (int l = L - 1; l >= 0; --l) {
+        const int fan = ctx->fan[l];
+        const int64_t ub1 = ctx->ub_front[l + 1];
+        GsLayerBuf &B = ctx->layer[l];
+        GsLevelMeta *ml = ctx->d_meta + l;
+        const GsLevelMeta *mu = ctx->d_meta + (l + 1);
+
+        if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, st);
+        else launch_sample<int32_t>(ctx, l, seed, iter, st);
+
+        hipLaunchKernelGGL(k_reset_tables, dim3(grid_for(ctx, 2 * ub1 * (1 + fan))), dim3(256), 0, st,
+                           ctx->tab_mixed, ctx->tab_local, ml, mu, S, fan);
+        hipLaunchKernelGGL(k_insert_mixed, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
+                           ctx->tab_mixed, ctx->front[l + 1], B.nbr, B.cnt, ml, mu, S, fan);
+        PartMixed pm{ctx->tab_mixed, ctx->front[l + 1], B.nbr, B.cnt, B.mixed, B.blk_indptr, ml, mu, S, fan};
+        run_partition(ctx, pm, st);
+        hipLaunchKernelGGL(k_relabel_edges, dim3(grid_for(ctx, ub1 * fan)), dim3(256), 0, st,
+                           ctx->tab_mixed, B.nbr, B.cnt, B.blk_indptr, B.blk_src, ml, mu, S, fan);
+        PartBuckets pb{B.mixed, ctx->graph.d_pmap, B.recv, ml, mu, S};
+        run_partition(ctx, pb, st);
+        hipLaunchKernelGGL(k_insert_local, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
+                           ctx->tab_local, ctx->front[l + 1], B.recv, ml, mu, S, fan);
+        PartLocal pl{ctx->tab_local, ctx->front[l + 1], B.recv, ctx->front[l], ml, mu, S, fan};
+        run_partition(ctx, pl, st);
+        hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
+                           ctx->tab_local, B.mixed, ctx->front[l + 1], B.nbr, B.cnt, B.blk_indptr,
+                           B.src_row, B.self_row, B.edge_row, ml, mu, S, fan);
+    }
+    GS_HIP(ctx, hipGetLastError());
+    GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
+    return GSPLIT_OK;
+}

@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer outputs (sampling, splits, dedup, relabel, buckets, shuffle index) must be
+bit-exact; fp32 GraphSAGE outputs and gradients within 1e-4 max relative error
+(|a - o| / max(|o|, 1e-3 * max|o|))."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import reference as R
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+def _ctx(w, dev, max_targets=None):
+    from paper_2303_13775_amd import Context
+    return Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts,
+                   max_targets or w.batch)
+
+
+def _oracle_batch(w, tg, seed, it, n_splits=None, pmap=None):
+    pm = w.pmap.cpu().numpy() if pmap is None else pmap
+    return R.sp_sample(w.indptr.cpu().numpy(), w.indices.cpu().numpy(), pm,
+                       n_splits or w.n_splits, w.fanouts, tg.cpu().numpy(), seed, it)
+
+
+def assert_batch_equal(got, ob, S, L):
+    """Every integer output of sample+split, element by element."""
+    for l in range(L + 1):
+        for s in range(S):
+            assert np.array_equal(got["local_front"][l][s].cpu().numpy(), ob.local_front[l][s]), ("front", l, s)
+    for l in range(L):
+        lay = got["layers"][l]
+        nbr = np.concatenate([b.nbr for b in ob.blocks[l]]) if S else np.zeros((0, 1))
+        cnt = np.concatenate([b.cnt for b in ob.blocks[l]])
+        assert np.array_equal(lay["nbr"].cpu().numpy(), nbr), ("nbr", l)
+        assert np.array_equal(lay["cnt"].cpu().numpy(), cnt), ("cnt", l)
+        indptr = lay["blk_indptr"].cpu().numpy()
+        src = lay["blk_src"].cpu().numpy()
+        row0 = 0
+        for s in range(S):
+            b = ob.blocks[l][s]
+            n_dst = b.dst.shape[0]
+            assert np.array_equal(lay["mixed"][s].cpu().numpy(), b.mixed_front), ("mixed", l, s)
+            ip = indptr[row0:row0 + n_dst + 1]
+            assert np.array_equal(ip - ip[0], b.blk_indptr), ("blk_indptr", l, s)
+            assert np.array_equal(src[ip[0]:ip[-1]], b.blk_src), ("blk_src", l, s)
+            assert np.array_equal(lay["shuffle_src_row"][s].cpu().numpy(), b.shuffle_src_row), ("shuffle", l, s)
+            for t in range(S):
+                assert got["bucket"][l][s][t] == b.buckets[t].shape[0], ("bucket size", l, s, t)
+            row0 += n_dst
+        recv = np.concatenate([ob.blocks[l][s].buckets[t] for t in range(S) for s in range(S)]) \
+            if S else np.zeros(0, np.int32)
+        assert np.array_equal(lay["recv"].cpu().numpy(), recv), ("recv", l)
+
+
+CASES = {
+    "tiny": lambda: workloads.tiny(),
+    "ragged-S3": lambda: workloads.custom(3001, 41000, dims=[20, 12, 6], fanouts=[7, 3], batch=257,
+                                          n_splits=3, name="ragged"),
+    "fan32-S8-int64": lambda: workloads.custom(5000, 200000, dims=[8, 8, 8, 4], fanouts=[33, 20, 17],
+                                               batch=100, n_splits=8, index64=True, name="wide"),
+    "S1": lambda: workloads.custom(2000, 30000, dims=[16, 16, 4], fanouts=[5, 5], batch=300, n_splits=1,
+                                   name="s1"),
+    "range-map-deep": lambda: workloads.custom(20000, 600000, dims=[8, 8, 8, 8, 4], fanouts=[4, 3, 3, 2],
+                                               batch=500, n_splits=4, pmap_kind="range", name="deep"),
+    "fan64": lambda: workloads.custom(1500, 120000, dims=[8, 8], fanouts=[64], batch=64, n_splits=2,
+                                      name="fan64"),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_sample_split_bit_exact(name):
+    dev = _dev()
+    w = CASES[name]()
+    ctx = _ctx(w, dev)
+    for it in (0, 1):
+        tg = w.targets(it)
+        ctx.gsplit_sample_split(tg.to(dev), seed=1234 + it, it=it)
+        got = ctx.fetch_batch()
+        ob = _oracle_batch(w, tg, 1234 + it, it)
+        assert_batch_equal(got, ob, w.n_splits, w.n_layers)
+    ctx.close()
+
+
+def test_edge_cases_empty_isolated_and_unowned_split():
+    dev = _dev()
+    w = workloads.custom(500, 1500, dims=[8, 8, 4], fanouts=[3, 2], batch=16, n_splits=4, name="edge")
+    ip = w.indptr.cpu().numpy().astype(np.int64)
+    deg = ip[1:] - ip[:-1]
+    iso = np.nonzero(deg == 0)[0][:5].astype(np.int32)
+    assert iso.shape[0] > 0
+    ctx = _ctx(w, dev)
+    # empty mini-batch
+    ctx.gsplit_sample_split(torch.empty(0, dtype=torch.int32, device=dev), 1, 0)
+    n_local, n_mixed, n_edges, _ = ctx.gsplit_batch_sizes()
+    assert all(x == 0 for row in n_local for x in row) and all(x == 0 for row in n_edges for x in row)
+    # isolated targets only: nothing is sampled, frontiers are the targets themselves
+    tg = torch.from_numpy(iso)
+    ctx.gsplit_sample_split(tg.to(dev), 1, 0)
+    assert_batch_equal(ctx.fetch_batch(), _oracle_batch(w, tg, 1, 0), 4, 2)
+    # targets all owned by one split, so the other splits start with nothing
+    own0 = torch.nonzero(w.pmap == 0).flatten()[:16].to(torch.int32)
+    ctx.gsplit_sample_split(own0.to(dev), 9, 4)
+    assert_batch_equal(ctx.fetch_batch(), _oracle_batch(w, own0, 9, 4), 4, 2)
+    # a single target, and the largest batch the context allows
+    one = w.targets(3)[:1]
+    ctx.gsplit_sample_split(one.to(dev), 2, 2)
+    assert_batch_equal(ctx.fetch_batch(), _oracle_batch(w, one, 2, 2), 4, 2)
+    ctx.close()
+
+
+def test_error_paths():
+    from paper_2303_13775_amd import Context, GsplitError
+    dev = _dev()
+    w = workloads.custom(500, 1500, dims=[8, 8, 4], fanouts=[3, 2], batch=16, n_splits=4, name="err")
+    ctx = _ctx(w, dev)
+    with pytest.raises(GsplitError) as e:
+        ctx.gsplit_sample_split(w.targets(0)[:16].repeat(2).contiguous().to(dev), 0, 0)   # 32 > max_targets
+    assert e.value.code == -3
+    with pytest.raises(GsplitError):
+        ctx.gsplit_max_rows(99)
+    with pytest.raises(GsplitError) as e:
+        Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), 4, [3, 200], 16)   # fanout too large
+    assert e.value.code == -1
+    bad = w.targets(0)[:8].clone(); bad[3] = w.n_vertices + 5            # id outside the graph
+    ctx.gsplit_sample_split(bad.to(dev), 0, 0)
+    with pytest.raises(GsplitError) as e:
+        ctx.gsplit_batch_sizes()
+    assert e.value.code == -1
+    ctx.gsplit_sample_split(w.targets(0).to(dev), 0, 0)                   # the context stays usable
+    ctx.gsplit_batch_sizes()
+    ctx2 = _ctx(w, dev)
+    with pytest.raises(GsplitError) as e:    # gather before any batch
+        ctx2.gsplit_gather_features(w.feat.to(dev), torch.empty((ctx2.gsplit_max_rows(0), 8), device=dev))
+    assert e.value.code == -5
+    ctx.close(); ctx2.close()
+
+
+@pytest.mark.parametrize("dim,dtype", [(64, torch.float32), (100, torch.float32), (128, torch.bfloat16),
+                                       (7, torch.float32), (5, torch.bfloat16), (128, torch.float32)])
+def test_gather_is_exact(dim, dtype):
+    dev = _dev()
+    w = workloads.custom(4000, 60000, dims=[dim, 8, 4], fanouts=[6, 4], batch=333, n_splits=4, name="gather")
+    table = w.feat.to(dtype).to(dev)
+    ctx = _ctx(w, dev)
+    tg = w.targets(0)
+    ctx.gsplit_sample_split(tg.to(dev), 3, 0)
+    out = torch.full((ctx.gsplit_max_rows(0), dim), float("nan"), dtype=dtype, device=dev)
+    ctx.gsplit_gather_features(table, out)
+    ob = _oracle_batch(w, tg, 3, 0)
+    ids = ob.local_cat(0)
+    as_int = torch.int16 if dtype == torch.bfloat16 else torch.int32
+    want = R.gather_rows(table.cpu().view(as_int).numpy(), ids)
+    assert np.array_equal(out[:ids.shape[0]].cpu().view(as_int).numpy(), want)
+    # an independent library routine agrees as well, and rows past the frontier are untouched
+    assert torch.equal(out[:ids.shape[0]], table[torch.from_numpy(ids).long().to(dev)])
+    assert torch.isnan(out[ids.shape[0]:].float()).all()
+    ctx.close()
+
+
+def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None):
+    from paper_2303_13775_amd import Context, SageParams
+    S = n_splits or w.n_splits
+    pm = w.pmap if pmap is None else pmap
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), pm.to(dev), S, w.fanouts, w.batch)
+    tg = w.targets(it)
+    ctx.gsplit_sample_split(tg.to(dev), seed, it)
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), device=dev)
+    ctx.gsplit_gather_features(w.feat.to(dev), x0)
+    params = SageParams(w.dims, [t.to(dev) for t in w.w_self], [t.to(dev) for t in w.w_neigh],
+                        [t.to(dev) for t in w.bias])
+    logits = torch.empty((tg.numel(), w.dims[-1]), device=dev)
+    ctx.gsplit_sage_fwd(params, x0, logits)
+    ob = _oracle_batch(w, tg, seed, it, n_splits=S, pmap=pm.cpu().numpy())
+    op = R.SageParams([t.numpy() for t in w.w_self], [t.numpy() for t in w.w_neigh],
+                      [t.numpy() for t in w.bias])
+    of = R.sp_forward(ob, R.gather_rows(w.feat.numpy(), ob.local_cat(0)), op)
+    lab = w.labels.numpy()[tg.numpy()[ob.target_perm]]
+    _, g = R.softmax_xent(of.logits, lab)
+    gws = [torch.full_like(t, 7.0, device=dev) for t in w.w_self]      # must be overwritten
+    gwn = [torch.full_like(t, 7.0, device=dev) for t in w.w_neigh]
+    gb = [torch.full_like(t, 7.0, device=dev) for t in w.bias]
+    ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
+    torch.cuda.synchronize()
+    obw = R.sp_backward(ob, of, op, g)
+    res = dict(logits=logits.cpu().numpy(), gws=[t.cpu().numpy() for t in gws],
+               gwn=[t.cpu().numpy() for t in gwn], gb=[t.cpu().numpy() for t in gb],
+               perm=ob.target_perm, of=of, ob=obw)
+    ctx.close()
+    return res
+
+
+SAGE_CASES = {
+    "tiny": lambda: workloads.tiny(),
+    "ragged-dims": lambda: workloads.custom(6000, 150000, dims=[100, 72, 47], fanouts=[9, 6], batch=700,
+                                            n_splits=4, name="ragged-dims"),
+    "odd-width": lambda: workloads.custom(3000, 50000, dims=[30, 33, 10, 3], fanouts=[5, 4, 3], batch=129,
+                                          n_splits=3, name="odd"),
+    "wide": lambda: workloads.custom(8000, 200000, dims=[128, 256, 256, 172], fanouts=[6, 5, 4], batch=256,
+                                     n_splits=4, pmap_kind="range", name="wide"),
+}
+
+
+@pytest.mark.parametrize("name", list(SAGE_CASES))
+def test_sage_forward_backward_within_tolerance(name):
+    dev = _dev()
+    w = SAGE_CASES[name]()
+    r = _run_fwd_bwd(w, dev, seed=77, it=2)
+    assert R.max_rel_err(r["logits"], r["of"].logits) < TOL_F32
+    for l in range(w.n_layers):
+        assert R.max_rel_err(r["gws"][l], r["ob"].gw_self[l]) < TOL_F32, ("gw_self", l)
+        assert R.max_rel_err(r["gwn"][l], r["ob"].gw_neigh[l]) < TOL_F32, ("gw_neigh", l)
+        assert R.max_rel_err(r["gb"][l], r["ob"].gbias[l]) < TOL_F32, ("gbias", l)
+
+
+def test_split_equals_unsplit_on_gpu():
+    dev = _dev()
+    w = workloads.tiny()
+    a = _run_fwd_bwd(w, dev, seed=5, it=0)
+    b = _run_fwd_bwd(w, dev, seed=5, it=0, n_splits=1, pmap=torch.zeros_like(w.pmap))
+    la = np.empty_like(a["logits"]); la[a["perm"]] = a["logits"]
+    lb = np.empty_like(b["logits"]); lb[b["perm"]] = b["logits"]
+    assert R.max_rel_err(la, lb) < TOL_F32
+    for l in range(w.n_layers):
+        assert R.max_rel_err(a["gws"][l], b["gws"][l]) < TOL_F32
+
+
+def test_repeatable_across_runs():
+    """Race check: integer outputs of three runs of the same batch are identical."""
+    dev = _dev()
+    w = workloads.tiny()
+    ctx = _ctx(w, dev)
+    tg = w.targets(7).to(dev)
+    ref = None
+    for _ in range(3):
+        ctx.gsplit_sample_split(tg, 42, 7)
+        got = ctx.fetch_batch()
+        flat = [t.cpu() for l in got["local_front"] for t in l] + \
+               [lay[k].cpu() for lay in got["layers"] for k in ("nbr", "blk_src", "recv")]
+        if ref is None:
+            ref = flat
+        else:
+            assert all(torch.equal(x, y) for x, y in zip(ref, flat))
+    ctx.close()
