@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the split-parallel hot path on one MI355X.
+
+One step = one whole iteration over a fresh synthetic mini-batch, all inputs resident in HBM:
+gsplit_sample_split -> gsplit_gather_features -> gsplit_sage_fwd -> softmax cross-entropy
+gradient of the logits (harness, torch) -> gsplit_sage_bwd.  Prints ONE JSON line.
+
+The workload is the "medium" configuration (2.4M-vertex / ~124M-edge R-MAT graph, 100-d fp32
+features, 47 classes, range partition map, 4 logical splits, batch 1024, fanouts [15,10,5],
+hidden 256); `--workload tiny` selects the small case.  All data is synthetic and seeded.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="medium", choices=["medium", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-iters", type=int, default=3)
+    ap.add_argument("--stage-iters", type=int, default=50)
+    return ap.parse_args()
+
+
+class Runner:
+    """Holds the device-resident inputs, the context and the preallocated outputs of a step."""
+
+    def __init__(self, w, dev):
+        import torch
+        from paper_2303_13775_amd import Context, SageParams
+        self.torch = torch
+        self.w, self.dev = w, dev
+        self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
+        self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias)
+        self.x0 = torch.empty((self.ctx.gsplit_max_rows(0), w.dims[0]), dtype=w.feat.dtype, device=dev)
+        self.logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+        self.gws = [torch.empty_like(t) for t in w.w_self]
+        self.gwn = [torch.empty_like(t) for t in w.w_neigh]
+        self.gb = [torch.empty_like(t) for t in w.bias]
+        self.seed = 0xC0FFEE
+
+    def loss_grad(self, targets):
+        """Harness-side loss: mean softmax cross-entropy; returns d loss / d logits."""
+        torch = self.torch
+        ids = self._front_top                     # local_cat[L]: targets grouped by split
+        y = self.w.labels[ids.long()]
+        p = torch.softmax(self.logits, dim=1)
+        p[torch.arange(p.shape[0], device=self.dev), y] -= 1.0
+        return (p / p.shape[0]).contiguous()
+
+    def step(self, targets, it, events=None):
+        torch = self.torch
+        c = self.ctx
+        rec = (lambda k: events[k].record()) if events is not None else (lambda k: None)
+        rec(0)
+        c.gsplit_sample_split(targets, self.seed, it)
+        rec(1)
+        c.gsplit_gather_features(self.w.feat, self.x0)
+        rec(2)
+        c.gsplit_sage_fwd(self.params, self.x0, self.logits)
+        rec(3)
+        # rows of the logits follow local_cat[L]; fetch those ids on the device (no host sync)
+        self._front_top = self._top_ids(targets.numel())
+        g = self.loss_grad(targets)
+        rec(4)
+        c.gsplit_sage_bwd(self.params, g, self.gws, self.gwn, self.gb)
+        rec(5)
+
+    def _top_ids(self, n):
+        # device-to-device copy of local_cat[L] into a torch tensor
+        import ctypes as C
+        from paper_2303_13775_amd.binding import _hip_runtime
+        torch = self.torch
+        if not hasattr(self, "_top_buf"):
+            self._top_buf = torch.empty(self.w.batch, dtype=torch.int32, device=self.dev)
+            hip = _hip_runtime()
+            hip.hipMemcpyAsync.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+            hip.hipMemcpyAsync.restype = C.c_int
+            self._hip = hip
+        v = self.ctx.gsplit_batch_level(self.ctx.L)
+        rc = self._hip.hipMemcpyAsync(C.c_void_p(self._top_buf.data_ptr()), C.c_void_p(v.d_local_cat),
+                                      C.c_size_t(4 * n), 3,
+                                      C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+        return self._top_buf[:n]
+
+
+def cpu_baseline(w_host, iters):
+    """The oracle as it stands, timed on the host cores on `iters` whole iterations."""
+    import numpy as np
+    from oracle import reference as R
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    ip, ix, pm = w_host["indptr"], w_host["indices"], w_host["pmap"]
+    params = R.SageParams(w_host["w_self"], w_host["w_neigh"], w_host["bias"])
+    t0 = time.perf_counter()
+    for it in range(iters):
+        tg = w_host["targets"][it]
+        b = R.sp_sample(ip, ix, pm, w_host["S"], w_host["fanouts"], tg, 0xC0FFEE, it)
+        x0 = R.gather_rows(w_host["feat"], b.local_cat(0))
+        f = R.sp_forward(b, x0, params)
+        _, g = R.softmax_xent(f.logits, w_host["labels"][tg[b.target_perm]])
+        R.sp_backward(b, f, params, g)
+    dt = time.perf_counter() - t0
+    return {"value": iters / dt, "unit": "mini-batches/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{iters} whole iterations of the same workload (C steps single-threaded, "
+                      f"numpy float64 matmuls on {threads} BLAS threads), {dt:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (logical splits share it); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    w = workloads.medium(device=dev) if a.workload == "medium" else workloads.tiny(device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+    r = Runner(w, dev)
+    n_total = a.warmup + a.steps
+    targets = [w.targets(i) for i in range(n_total)]
+    torch.cuda.synchronize()
+
+    for i in range(a.warmup):
+        r.step(targets[i], i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.warmup, n_total):
+        r.step(targets[i], i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+
+    # per-stage device times (separate instrumented pass; events on the stream the kernels run on)
+    n_st = min(a.stage_iters, a.steps)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_st)]
+    sizes = None
+    for i in range(n_st):
+        r.step(targets[a.warmup + i], a.warmup + i, ev[i])
+    torch.cuda.synchronize()
+    names = ["sample_split", "gather", "sage_fwd", "loss_grad", "sage_bwd"]
+    stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / max(n_st, 1)
+                for k, nm in enumerate(names)}
+
+    # gather roofline: algorithmic bytes = rows * (2 * row_bytes + 4) per launch, measured alone
+    # on the last batch with events around the single-kernel entry point
+    n_local, n_mixed, n_edges, bucket = r.ctx.gsplit_batch_sizes()
+    rows0 = sum(n_local[0])
+    row_bytes = w.dims[0] * w.feat.element_size()
+    reps = 50
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tot = 0.0
+    for _ in range(reps):
+        e0.record()
+        r.ctx.gsplit_gather_features(w.feat, r.x0)
+        e1.record()
+        e1.synchronize()
+        tot += e0.elapsed_time(e1)
+    gather_ms = tot / reps
+    gather_bytes = rows0 * (2 * row_bytes + 4)
+    gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "mini-batches/sec (sample+split+gather+SAGE fwd/bwd) at 1 GPU",
+        "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": dict(w.describe(), fanout_order="fanouts[l] expands layer l+1 into layer l",
+                       graph_gen_s=round(t_gen, 1)),
+        "gather_GBps": gather_gbs,
+        "stage_ms": stage_ms,
+        "batch_shape": {"rows_per_level": [sum(x) for x in n_local],
+                        "edges_per_layer": [sum(x) for x in n_edges],
+                        "mixed_rows_per_layer": [sum(x) for x in n_mixed],
+                        "ids_shuffled_per_layer": [sum(b[s][t] for s in range(w.n_splits)
+                                                       for t in range(w.n_splits) if s != t) for b in bucket]},
+        "roofline": {"kernel": "k_gather_rows", "bound": "hbm", "achieved": gather_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": gather_bytes, "launch_ms": gather_ms},
+    }
+
+    if not a.no_cpu_baseline:
+        host = {"indptr": w.indptr.cpu().numpy(), "indices": w.indices.cpu().numpy(),
+                "pmap": w.pmap.cpu().numpy(), "feat": w.feat.cpu().numpy(),
+                "labels": w.labels.cpu().numpy(), "S": w.n_splits, "fanouts": w.fanouts,
+                "w_self": [t.cpu().numpy() for t in w.w_self],
+                "w_neigh": [t.cpu().numpy() for t in w.w_neigh],
+                "bias": [t.cpu().numpy() for t in w.bias],
+                "targets": [targets[a.warmup + i].cpu().numpy() for i in range(a.cpu_iters)]}
+        out["cpu_baseline"] = cpu_baseline(host, a.cpu_iters)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -174,9 +174,17 @@ extern "C" int gsplit_batch_sizes(gsplit_ctx *ctx, int64_t *n_local, int64_t *n_
     for (int l = 0; l < L; ++l) {
         for (int s = 0; s < S; ++s) {
             if (n_mixed) n_mixed[l * S + s] = ctx->h_meta[l].mixed_off[s + 1] - ctx->h_meta[l].mixed_off[s];
-            if (bucket)
-                for (int t = 0; t < S; ++t)
-                    bucket[(l * S + s) * S + t] = ctx->h_meta[l].bucket_cnt[s * GS_MAXS + t];
+            if (bucket) {
+                // bucket[s->t] runs from its start to the start of the next non-empty sender
+                const GsLevelMeta &m = ctx->h_meta[l];
+                const bool empty = m.mixed_off[s + 1] == m.mixed_off[s];
+                int nxt = s + 1;
+                while (nxt < S && m.mixed_off[nxt + 1] == m.mixed_off[nxt]) ++nxt;
+                for (int t = 0; t < S; ++t) {
+                    const int end = nxt < S ? m.bucket_start[nxt * GS_MAXS + t] : m.recv_off[t + 1];
+                    bucket[(l * S + s) * S + t] = empty ? 0 : end - m.bucket_start[s * GS_MAXS + t];
+                }
+            }
         }
         if (n_edges) {
             int32_t cut[GS_MAXS + 1];

@@ -18,13 +18,14 @@
 // and, for sampling layer l (expanding level l+1 into level l):
 //   mixed_off : split offsets of the concatenated mixed frontiers
 //   recv_off  : receiver offsets of the concatenated received buckets
-//   bucket_cnt: ids split s hands to split t, at [s * GS_MAXS + t]
+//   bucket_start: where bucket[s->t] starts inside recv, at [s * GS_MAXS + t] (senders with an
+//               empty mixed frontier are not written)
 //   nnz       : number of sampled edges of the layer
 struct GsLevelMeta {
     int32_t front_off[GS_MAXS + 1];
     int32_t mixed_off[GS_MAXS + 1];
     int32_t recv_off[GS_MAXS + 1];
-    int32_t bucket_cnt[GS_MAXS * GS_MAXS];
+    int32_t bucket_start[GS_MAXS * GS_MAXS];
     int32_t nnz;
     int32_t error;      // set non-zero by a kernel that hit an impossible state (probe overflow)
     int32_t pad[2];

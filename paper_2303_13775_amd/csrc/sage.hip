@@ -14,8 +14,6 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;
-
 // ------------------------------------------------------------------------------------------
 // mean aggregation: M[i,:] = (1/cnt_i) * sum_e H[edge_row[e],:], one lane group per destination
 // row, 4 floats per lane, edges in slot order (deterministic), four row loads in flight.
@@ -78,22 +76,99 @@ __global__ __launch_bounds__(256) void k_mean_aggregate_f32_any(const float *__r
 }
 
 // ------------------------------------------------------------------------------------------
-// Tiled MFMA GEMM core.  C[M x N] = A[M x K] * B[K x N] with element functors:
-//   a(m, k), b(k, n) return the operand element (0 outside the logical matrix);
-//   epi(m, n, value) consumes one result element.
-// Workgroup = 4 waves arranged 2 x 2 over a BM x BN tile; every wave owns (BM/2) x (BN/2) outputs
-// as 32 x 32 MFMA blocks.  Tiles are staged k-major in LDS so that the 32 lanes of an MFMA operand
-// read 32 consecutive words.  A_KCONTIG / B_KCONTIG say which index runs along memory, so that the
-// staging loads are coalesced.
+// Tiled fp32 MFMA GEMM core:  C[M x N] = A[M x K] * B[K x N].
+//
+// Operands are described by accessors  at(outer, inner) -> const float* (or nullptr outside the
+// logical matrix; `inner` runs along memory).  An operand is used either K-contiguous (KC: outer
+// is the M or N index, inner is k) or K-major (KM: outer is k, inner is the M or N index); both
+// are staged into LDS with the layout they have in memory (16-byte copies when VW == 4):
+//   KC: lds[row][k]   (row stride 36 words), MFMA fragments are one 128-bit read per 8 k
+//   KM: lds[k][row]   (row stride ROWS + 4), MFMA fragments are four 32-bit reads per 8 k
+// v_mfma_f32_32x32x2_f32 sums two k-slots (lane / 32 selects the slot).  Within a group of 8 k the
+// lower half-wave takes k = 0..3 and the upper half k = 4..7 over four consecutive MFMAs; A and B
+// use the same assignment, so the sum over k is complete whatever the order.
+//
+// Workgroup = 4 waves as 2 x 2 over a BM x BN tile (wave tile BM/2 x BN/2, 32 x 32 blocks).
+// One LDS buffer; the next k-tile is fetched into registers while the current one is multiplied.
 // ------------------------------------------------------------------------------------------
-template <int BM, int BN, bool A_KCONTIG, bool B_KCONTIG, class AF, class BF, class EF>
-__device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int k_begin, const int k_end,
-                                          const AF &a, const BF &b, const EF &epi) {
-    constexpr int PAD = 4;
-    __shared__ float As[BK][BM + PAD];
-    __shared__ float Bs[BK][BN + PAD];
-    constexpr int MI = BM / 64, NI = BN / 64;     // 32x32 blocks per wave in each direction
+constexpr int BK = 32;
+constexpr int KC_LD = BK + 4;
+
+template <int ROWS>
+constexpr int lds_words() { return ROWS * KC_LD > BK * (ROWS + 4) ? ROWS * KC_LD : BK * (ROWS + 4); }
+
+template <int ROWS, bool KC, int VW, class F>
+struct Stager {
+    static constexpr int NV = ROWS * BK / 4 / 256;
+    float4 reg[NV];
+
+    __device__ __forceinline__ static float4 fetch(const F &f, int outer, int inner, int inner_end) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (VW == 4) {
+            if (inner < inner_end) {
+                const float *p = f.at(outer, inner);
+                if (p) v = *reinterpret_cast<const float4 *>(p);
+            }
+        } else {
+            float t[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float *p = (inner + j < inner_end) ? f.at(outer, inner + j) : nullptr;
+                t[j] = p ? *p : 0.f;
+            }
+            v = make_float4(t[0], t[1], t[2], t[3]);
+        }
+        return v;
+    }
+    // r0: first M/N index of the tile, [k0, k_end): k range still to do, r_end: matrix extent
+    __device__ __forceinline__ void load(const F &f, int r0, int r_end, int k0, int k_end, int tid) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (KC) {
+                const int kq = tid & 7, row = (tid >> 3) + 32 * v;
+                reg[v] = (r0 + row < r_end) ? fetch(f, r0 + row, k0 + 4 * kq, k_end)
+                                            : make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (1024 / ROWS) * v;
+                reg[v] = (k0 + kk < k_end) ? fetch(f, k0 + kk, r0 + 4 * x, r_end)
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(float *lds, int tid) const {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (KC) {
+                const int kq = tid & 7, row = (tid >> 3) + 32 * v;
+                *reinterpret_cast<float4 *>(&lds[row * KC_LD + 4 * kq]) = reg[v];
+            } else {
+                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (1024 / ROWS) * v;
+                *reinterpret_cast<float4 *>(&lds[kk * (ROWS + 4) + 4 * x]) = reg[v];
+            }
+        }
+    }
+};
+
+template <int ROWS, bool KC>
+__device__ __forceinline__ void read_frag(const float *lds, int row, int oct, int half, float out[4]) {
+    if (KC) {
+        const float4 v = *reinterpret_cast<const float4 *>(&lds[row * KC_LD + oct * 8 + 4 * half]);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = lds[(oct * 8 + 4 * half + j) * (ROWS + 4) + row];
+    }
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF>
+__device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int m_end, const int n_end,
+                                          const int k_begin, const int k_end, const AF &a, const BF &b,
+                                          const EF &epi) {
+    __shared__ __attribute__((aligned(16))) float As[lds_words<BM>()];
+    __shared__ __attribute__((aligned(16))) float Bs[lds_words<BN>()];
+    constexpr int MI = BM / 64, NI = BN / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
     floatx16 acc[MI][NI];
 #pragma unroll
@@ -103,47 +178,32 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    Stager<BM, A_KC, VA, AF> sa;
+    Stager<BN, B_KC, VB, BF> sb;
+    sa.load(a, m0, m_end, k_begin, k_end, tid);
+    sb.load(b, n0, n_end, k_begin, k_end, tid);
     for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-        // stage A
-        if (A_KCONTIG) {
-#pragma unroll
-            for (int r = 0; r < (BM * BK) / 256; ++r) {
-                const int kk = tid % BK, mm = tid / BK + r * (256 / BK);
-                As[kk][mm] = (k0 + kk < k_end) ? a(m0 + mm, k0 + kk) : 0.f;
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < (BM * BK) / 256; ++r) {
-                const int mm = tid % BM, kk = tid / BM + r * (256 / BM);
-                As[kk][mm] = (k0 + kk < k_end) ? a(m0 + mm, k0 + kk) : 0.f;
-            }
-        }
-        if (B_KCONTIG) {
-#pragma unroll
-            for (int r = 0; r < (BN * BK) / 256; ++r) {
-                const int kk = tid % BK, nn = tid / BK + r * (256 / BK);
-                Bs[kk][nn] = (k0 + kk < k_end) ? b(k0 + kk, n0 + nn) : 0.f;
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < (BN * BK) / 256; ++r) {
-                const int nn = tid % BN, kk = tid / BN + r * (256 / BN);
-                Bs[kk][nn] = (k0 + kk < k_end) ? b(k0 + kk, n0 + nn) : 0.f;
-            }
-        }
+        sa.store(As, tid);
+        sb.store(Bs, tid);
         __syncthreads();
+        if (k0 + BK < k_end) {
+            sa.load(a, m0, m_end, k0 + BK, k_end, tid);
+            sb.load(b, n0, n_end, k0 + BK, k_end, tid);
+        }
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float av[MI], bv[NI];
+        for (int oct = 0; oct < BK / 8; ++oct) {
+            float af[MI][4], bf[NI][4];
 #pragma unroll
-            for (int i = 0; i < MI; ++i) av[i] = As[kk + (lane >> 5)][wm0 + i * 32 + (lane & 31)];
+            for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, oct, half, af[i]);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) bv[j] = Bs[kk + (lane >> 5)][wn0 + j * 32 + (lane & 31)];
+            for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, oct, half, bf[j]);
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][q], bf[j][q], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
@@ -155,53 +215,42 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                const int n = n0 + wn0 + j * 32 + (lane & 31);
+                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                const int n = n0 + wn0 + j * 32 + l32;
                 epi(m, n, acc[i][j][r]);
             }
 }
 
-// ---- operand and epilogue functors ---------------------------------------------------------
-// [H_l[self] | mean] : the K = 2 * D input of a layer, row i of the destination list
+// ---- operand accessors and epilogues ---------------------------------------------------------
+__device__ const float g_one_then_zero[4] = {1.f, 0.f, 0.f, 0.f};
+
+// plain row-major matrix
+struct MatRows {
+    const float *p; int rows; int cols;
+    __device__ __forceinline__ const float *at(int o, int i) const {
+        return (o < rows && i < cols) ? p + (int64_t)o * cols + i : nullptr;
+    }
+};
+// [H_l[self] | mean] : the 2 * D wide input of a layer for destination row i; with `ones` a
+// column of ones follows at index 2 * D (its product with dZ is the bias gradient)
 struct CatIn {
-    const float *H; const float *Mb; const int32_t *self_row; int D; int n1;
-    __device__ __forceinline__ float operator()(int i, int c) const {
-        if (i >= n1) return 0.f;
-        if (c < D) return H[(int64_t)self_row[i] * D + c];
-        if (c < 2 * D) return Mb[(int64_t)i * D + (c - D)];
-        return 0.f;
+    const float *H; const float *Mb; const int32_t *self_row; int D; int n1; int ones;
+    __device__ __forceinline__ const float *at(int i, int c) const {
+        if (i >= n1) return nullptr;
+        if (c < D) return H + (int64_t)self_row[i] * D + c;
+        if (c < 2 * D) return Mb + (int64_t)i * D + (c - D);
+        if (ones && c == 2 * D) return g_one_then_zero;
+        return nullptr;
     }
 };
-// same, transposed access (feature c, row i), plus a row of ones at c == 2 * D (bias gradient)
-struct CatInT {
-    CatIn in;
-    __device__ __forceinline__ float operator()(int c, int i) const {
-        if (c == 2 * in.D) return i < in.n1 ? 1.f : 0.f;
-        return in(i, c);
-    }
-};
-// [W_self; W_neigh] stacked along K
+// [W_self; W_neigh] stacked: row k of the 2 * D x N matrix
 struct CatW {
     const float *Ws; const float *Wn; int D; int N;
-    __device__ __forceinline__ float operator()(int k, int n) const {
-        if (n >= N) return 0.f;
-        if (k < D) return Ws[(int64_t)k * N + n];
-        if (k < 2 * D) return Wn[(int64_t)(k - D) * N + n];
-        return 0.f;
-    }
-};
-struct CatWT {   // (n, j) -> stacked weight element (j, n)
-    CatW w;
-    __device__ __forceinline__ float operator()(int n, int j) const { return w(j, n); }
-};
-// dZ = dH' masked by the ReLU of the forward output (no mask on the last layer)
-struct GradZ {
-    const float *dH; const float *Hout; int N; int n1; int masked;
-    __device__ __forceinline__ float operator()(int i, int n) const {
-        if (i >= n1 || n >= N) return 0.f;
-        const int64_t x = (int64_t)i * N + n;
-        const float g = dH[x];
-        return (!masked || Hout[x] > 0.f) ? g : 0.f;
+    __device__ __forceinline__ const float *at(int k, int n) const {
+        if (n >= N) return nullptr;
+        if (k < D) return Ws + (int64_t)k * N + n;
+        if (k < 2 * D) return Wn + (int64_t)(k - D) * N + n;
+        return nullptr;
     }
 };
 struct EpiFwd {
@@ -237,35 +286,50 @@ struct EpiGradIn {
     }
 };
 
-template <int BM, int BN>
+constexpr int GBM = 64, GBN = 128;
+
+// Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer
+template <int VA, int VB>
 __global__ __launch_bounds__(256) void k_sage_linear_fwd(CatIn a, CatW b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * BM;
+    const int m0 = blockIdx.x * GBM;
     if (m0 >= n1) return;
     a.n1 = n1; epi.n1 = n1;
-    gemm_tile<BM, BN, true, false>(m0, blockIdx.y * BN, 0, 2 * a.D, a, b, epi);
+    gemm_tile<GBM, GBN, true, false, VA, VB>(m0, blockIdx.y * GBN, n1, b.N, 0, 2 * a.D, a, b, epi);
 }
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_sage_grad_w(CatInT a, GradZ b, EpiGradW epi, int kchunk,
+// [dW_self; dW_neigh; db] += [H_self | mean | 1]^T * dZ over a chunk of destination rows
+template <int VA, int VB>
+__global__ __launch_bounds__(256) void k_sage_grad_w(CatIn a, MatRows dz, EpiGradW epi, int kchunk,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int k_begin = blockIdx.z * kchunk;
     if (k_begin >= n1) return;
-    a.in.n1 = n1; b.n1 = n1;
+    a.n1 = n1; dz.rows = n1;
     const int k_end = min(n1, k_begin + kchunk);
-    gemm_tile<BM, BN, false, false>(blockIdx.x * BM, blockIdx.y * BN, k_begin, k_end, a, b, epi);
+    gemm_tile<GBM, GBN, false, false, VA, VB>(blockIdx.x * GBM, blockIdx.y * GBN, 2 * a.D + 1, dz.cols,
+                                              k_begin, k_end, a, dz, epi);
 }
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_sage_grad_in(GradZ a, CatWT b, EpiGradIn epi,
+// [dH_self | dMean] = dZ * [W_self; W_neigh]^T, scattered through the shuffle index
+template <int VA, int VB>
+__global__ __launch_bounds__(256) void k_sage_grad_in(MatRows dz, CatW w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * BM;
+    const int m0 = blockIdx.x * GBM;
     if (m0 >= n1) return;
-    a.n1 = n1; epi.n1 = n1;
-    gemm_tile<BM, BN, true, true>(m0, blockIdx.y * BN, 0, a.N, a, b, epi);
+    dz.rows = n1; epi.n1 = n1;
+    gemm_tile<GBM, GBN, true, true, VA, VB>(m0, blockIdx.y * GBN, n1, 2 * w.D, 0, dz.cols, dz, w, epi);
+}
+
+// dZ = dH' where the forward output was positive, else 0 (in place)
+__global__ __launch_bounds__(256) void k_relu_mask(float *__restrict__ g, const float *__restrict__ hout,
+                                                   const GsLevelMeta *__restrict__ meta, int S, int width) {
+    const int64_t n = (int64_t)meta->front_off[S] * width;
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n;
+         x += (int64_t)gridDim.x * blockDim.x)
+        if (!(hout[x] > 0.f)) g[x] = 0.f;
 }
 
 // zero `count_rows(meta) * width` floats, or a fixed number when meta == nullptr
@@ -276,6 +340,8 @@ __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, int64_
          x += (int64_t)gridDim.x * blockDim.x)
         p[x] = 0.f;
 }
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 int grid_1d(const gsplit_ctx *ctx, int64_t upper_threads) {
     int64_t want = std::max<int64_t>(1, gs_ceil_div(upper_threads, 256));
@@ -363,17 +429,16 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const GsLayerBuf &B = ctx->layer[l];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
         launch_aggregate(ctx, l, hin, D, st);
-        CatIn a{hin, (const float *)sb.mean[l], B.self_row, D, 0};
+        CatIn a{hin, (const float *)sb.mean[l], B.self_row, D, 0, 0};
         CatW b{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
         EpiFwd epi{hout, (const float *)p->d_bias[l], N, 0, l < L - 1 ? 1 : 0};
-        const int64_t ub = ctx->ub_front[l + 1];
-        if (N > 64) {
-            dim3 grid((unsigned)gs_ceil_div(ub, 128), (unsigned)gs_ceil_div(N, 128));
-            hipLaunchKernelGGL((k_sage_linear_fwd<128, 128>), grid, dim3(256), 0, st, a, b, epi, mu, S);
-        } else {
-            dim3 grid((unsigned)gs_ceil_div(ub, 128), 1);
-            hipLaunchKernelGGL((k_sage_linear_fwd<128, 64>), grid, dim3(256), 0, st, a, b, epi, mu, S);
-        }
+        dim3 grid((unsigned)gs_ceil_div(ctx->ub_front[l + 1], GBM), (unsigned)gs_ceil_div(N, GBN));
+        const bool va = D % 4 == 0 && aligned16(hin) && aligned16(sb.mean[l]);
+        const bool vb = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
+        if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
+        else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
+        else if (vb) hipLaunchKernelGGL((k_sage_linear_fwd<1, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
+        else hipLaunchKernelGGL((k_sage_linear_fwd<1, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
     }
     GS_HIP(ctx, hipGetLastError());
     sb.fwd_done = true;
@@ -413,30 +478,37 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const float *dH = l == L - 1 ? d_grad_logits : sb.ghid[l + 1];
         const float *hout = l == L - 1 ? nullptr : (const float *)sb.hidden[l + 1];
         const int64_t ub = ctx->ub_front[l + 1];
-        GradZ dz{dH, hout, N, 0, l < L - 1 ? 1 : 0};
+        if (l < L - 1)   // dZ = dH' masked by the ReLU of the forward pass, in place
+            hipLaunchKernelGGL(k_relu_mask, dim3(grid_1d(ctx, ub * N)), dim3(256), 0, st, sb.ghid[l + 1], hout,
+                               mu, S, N);
+        MatRows dz{dH, 0, N};
         // weight and bias gradients, summed over all splits (layer 0 reads its input rows from the
         // caller's gathered features, which therefore must still be alive)
-        CatIn in{hin, (const float *)sb.mean[l], B.self_row, D, 0};
-        CatInT at{in};
+        CatIn in{hin, (const float *)sb.mean[l], B.self_row, D, 0, 1};
         EpiGradW ew{d_gw_self[l], d_gw_neigh[l], d_gbias[l], D, N};
-        const int kchunk = 1024;
-        if (N > 64) {
-            dim3 grid((unsigned)gs_ceil_div(2 * D + 1, 128), (unsigned)gs_ceil_div(N, 128),
+        const bool vin = D % 4 == 0 && aligned16(hin) && aligned16(sb.mean[l]);
+        const bool vdz = N % 4 == 0 && aligned16(dH);
+        const bool vw = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
+        {
+            const int kchunk = 512;
+            dim3 grid((unsigned)gs_ceil_div(2 * D + 1, GBM), (unsigned)gs_ceil_div(N, GBN),
                       (unsigned)gs_ceil_div(ub, kchunk));
-            hipLaunchKernelGGL((k_sage_grad_w<128, 128>), grid, dim3(256), 0, st, at, dz, ew, kchunk, mu, S);
-        } else {
-            dim3 grid((unsigned)gs_ceil_div(2 * D + 1, 128), 1, (unsigned)gs_ceil_div(ub, kchunk));
-            hipLaunchKernelGGL((k_sage_grad_w<128, 64>), grid, dim3(256), 0, st, at, dz, ew, kchunk, mu, S);
+            if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
+            else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
+            else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
+            else hipLaunchKernelGGL((k_sage_grad_w<1, 1>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
         }
         if (l > 0) {
             const GsLevelMeta *ml = ctx->d_meta + l;
             hipLaunchKernelGGL(k_fill_zero, dim3(grid_1d(ctx, ctx->ub_front[l] * D)), dim3(256), 0, st,
                                sb.ghid[l], 0, ml, S, D);
             CatW w{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
-            CatWT wt{w};
             EpiGradIn ei{sb.ghid[l], B.self_row, B.edge_row, B.blk_indptr, D, 0};
-            dim3 grid((unsigned)gs_ceil_div(ub, 128), (unsigned)gs_ceil_div(2 * D, 128));
-            hipLaunchKernelGGL((k_sage_grad_in<128, 128>), grid, dim3(256), 0, st, dz, wt, ei, mu, S);
+            dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
+            if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
         }
     }
     GS_HIP(ctx, hipGetLastError());

@@ -161,7 +161,6 @@ __global__ __launch_bounds__(256) void k_reset_tables(GsTable a, GsTable b, GsLe
         a.keys[i] = EMPTY_KEY; a.pos[i] = 0x7FFFFFFF;
         b.keys[i] = EMPTY_KEY; b.pos[i] = 0x7FFFFFFF;
     }
-    if (blockIdx.x == 0 && threadIdx.x < GS_MAXS * GS_MAXS) meta_lo->bucket_cnt[threadIdx.x] = 0;
     if (blockIdx.x == 0 && threadIdx.x == 0) { meta_lo->error = 0; }
 }
 
@@ -453,11 +452,15 @@ struct PartBuckets {
         meta_lo->recv_off[S] = acc;
     }
     __device__ void emit(int j, unsigned m, const int *rk) const {
+        // the first row of a sender's mixed frontier marks where its buckets start at every
+        // receiver (senders are consecutive in the stream); sizes follow by subtraction on the host
+        const int s = split_of(meta_lo->mixed_off, S, j);
+        if (j == meta_lo->mixed_off[s])
+            for (int ss = s; ss >= 0 && meta_lo->mixed_off[ss] == j; --ss)
+                for (int t = 0; t < S; ++t) meta_lo->bucket_start[ss * GS_MAXS + t] = rk[t];
         if (!m) return;
         const int t = __ffs(m) - 1;
         recv[rk[t]] = mixed[j];
-        const int s = split_of(meta_lo->mixed_off, S, j);
-        atomicAdd(&meta_lo->bucket_cnt[s * GS_MAXS + t], 1);
     }
     __device__ int64_t n_extra() const { return 0; }
     __device__ void extra(int64_t) const {}
