@@ -111,8 +111,8 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         A((void **)&t->pos, sizeof(int32_t) * tab_cap, "table pos");
         A((void **)&t->row, sizeof(int32_t) * tab_cap, "table row");
     }
-    A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 9, "partition histogram");
-    A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 9, "partition bases");
+    A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 17, "partition histogram");
+    A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 17, "partition bases");
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
     if (rc == GSPLIT_OK && hipEventCreateWithFlags(&ctx->sample_done, hipEventDisableTiming) != hipSuccess)

@@ -55,7 +55,7 @@ struct GsSageBuf {             // activations kept between forward and backward
     int32_t  dtype = -1;
     int32_t  dims[GS_MAXL + 1] = {0};
     void    *hidden[GS_MAXL + 1] = {nullptr};   // local_cat activations of level 1..L-1
-    void    *mean[GS_MAXL] = {nullptr};         // aggregated neighbourhood means per layer
+    void    *xin[GS_MAXL] = {nullptr};          // assembled layer inputs [rows x 2*dims[l]]: self | mean
     float   *ghid[GS_MAXL + 1] = {nullptr};     // d loss / d hidden of level 1..L
     float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before scatter
     void    *wcat[GS_MAXL] = {nullptr};         // stacked [W_self; W_neigh] per layer

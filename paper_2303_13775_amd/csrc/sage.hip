@@ -15,25 +15,33 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // ------------------------------------------------------------------------------------------
-// mean aggregation: M[i,:] = (1/cnt_i) * sum_e H[edge_row[e],:], one lane group per destination
-// row, 4 floats per lane, edges in slot order (deterministic), four row loads in flight.
+// Layer input assembly: for destination row i
+//   X[i, 0:D]  = H[self_row[i], :]                         (its own lower-layer row)
+//   X[i, D:2D] = (1/cnt_i) * sum_e H[edge_row[e], :]        (mean over its sampled sources)
+// i.e. the training shuffle and the mean aggregation in one gather through the composed shuffle
+// index.  One lane group per destination row, 4 floats per lane, edges in slot order
+// (deterministic), four row loads in flight.  X feeds the forward product and, transposed, the
+// weight-gradient product.
 // ------------------------------------------------------------------------------------------
 template <int LPR>
-__global__ __launch_bounds__(256) void k_mean_aggregate_f32(const float *__restrict__ H, int D,
+__global__ __launch_bounds__(256) void k_assemble_input_f32(const float *__restrict__ H, int D,
                                                             const int32_t *__restrict__ blk_indptr,
                                                             const int32_t *__restrict__ edge_row,
+                                                            const int32_t *__restrict__ self_row,
                                                             const GsLevelMeta *__restrict__ meta_up,
-                                                            int S, float *__restrict__ M) {
+                                                            int S, float *__restrict__ X) {
     const int n1 = meta_up->front_off[S];
     const int nvec = D >> 2;
     const int c0 = threadIdx.x % LPR;
     const int groups = (gridDim.x * blockDim.x) / LPR;
     const float4 *H4 = reinterpret_cast<const float4 *>(H);
-    float4 *M4 = reinterpret_cast<float4 *>(M);
+    float4 *X4 = reinterpret_cast<float4 *>(X);
     for (int row = (blockIdx.x * blockDim.x + threadIdx.x) / LPR; row < n1; row += groups) {
         const int e0 = blk_indptr[row], e1 = blk_indptr[row + 1];
+        const int64_t self = self_row[row];
         const float cnt = (float)(e1 - e0);
         for (int c = c0; c < nvec; c += LPR) {
+            const float4 own = H4[self * nvec + c];
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             int e = e0;
             for (; e + 4 <= e1; e += 4) {
@@ -50,27 +58,31 @@ __global__ __launch_bounds__(256) void k_mean_aggregate_f32(const float *__restr
                 acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
             }
             if (e1 > e0) { acc.x /= cnt; acc.y /= cnt; acc.z /= cnt; acc.w /= cnt; }
-            M4[(int64_t)row * nvec + c] = acc;
+            X4[(int64_t)row * 2 * nvec + c] = own;
+            X4[(int64_t)row * 2 * nvec + nvec + c] = acc;
         }
     }
 }
 
 // scalar variant for widths that are not a multiple of 4
-__global__ __launch_bounds__(256) void k_mean_aggregate_f32_any(const float *__restrict__ H, int D,
+__global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__restrict__ H, int D,
                                                                 const int32_t *__restrict__ blk_indptr,
                                                                 const int32_t *__restrict__ edge_row,
+                                                                const int32_t *__restrict__ self_row,
                                                                 const GsLevelMeta *__restrict__ meta_up,
-                                                                int S, float *__restrict__ M) {
+                                                                int S, float *__restrict__ X) {
     const int n1 = meta_up->front_off[S];
     const int lane = threadIdx.x & 63;
     const int waves = (gridDim.x * blockDim.x) >> 6;
     for (int row = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < n1; row += waves) {
         const int e0 = blk_indptr[row], e1 = blk_indptr[row + 1];
+        const int64_t self = self_row[row];
         for (int c = lane; c < D; c += 64) {
             float acc = 0.f;
             for (int e = e0; e < e1; ++e) acc += H[(int64_t)edge_row[e] * D + c];
             if (e1 > e0) acc /= (float)(e1 - e0);
-            M[(int64_t)row * D + c] = acc;
+            X[(int64_t)row * 2 * D + c] = H[self * D + c];
+            X[(int64_t)row * 2 * D + D + c] = acc;
         }
     }
 }
@@ -231,16 +243,13 @@ struct MatRows {
         return (o < rows && i < cols) ? p + (int64_t)o * cols + i : nullptr;
     }
 };
-// [H_l[self] | mean] : the 2 * D wide input of a layer for destination row i; with `ones` a
-// column of ones follows at index 2 * D (its product with dZ is the bias gradient)
-struct CatIn {
-    const float *H; const float *Mb; const int32_t *self_row; int D; int n1; int ones;
-    __device__ __forceinline__ const float *at(int i, int c) const {
-        if (i >= n1) return nullptr;
-        if (c < D) return H + (int64_t)self_row[i] * D + c;
-        if (c < 2 * D) return Mb + (int64_t)i * D + (c - D);
-        if (ones && c == 2 * D) return g_one_then_zero;
-        return nullptr;
+// plain row-major matrix followed by one column of ones (its product with dZ is the bias gradient)
+struct MatRowsOnes {
+    const float *p; int rows; int cols;
+    __device__ __forceinline__ const float *at(int o, int i) const {
+        if (o >= rows) return nullptr;
+        if (i < cols) return p + (int64_t)o * cols + i;
+        return i == cols ? g_one_then_zero : nullptr;
     }
 };
 // [W_self; W_neigh] stacked: row k of the 2 * D x N matrix
@@ -290,25 +299,25 @@ constexpr int GBM = 64, GBN = 128;
 
 // Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer
 template <int VA, int VB>
-__global__ __launch_bounds__(256) void k_sage_linear_fwd(CatIn a, CatW b, EpiFwd epi,
+__global__ __launch_bounds__(256) void k_sage_linear_fwd(MatRows a, CatW b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int m0 = blockIdx.x * GBM;
     if (m0 >= n1) return;
-    a.n1 = n1; epi.n1 = n1;
-    gemm_tile<GBM, GBN, true, false, VA, VB>(m0, blockIdx.y * GBN, n1, b.N, 0, 2 * a.D, a, b, epi);
+    a.rows = n1; epi.n1 = n1;
+    gemm_tile<GBM, GBN, true, false, VA, VB>(m0, blockIdx.y * GBN, n1, b.N, 0, a.cols, a, b, epi);
 }
 
 // [dW_self; dW_neigh; db] += [H_self | mean | 1]^T * dZ over a chunk of destination rows
 template <int VA, int VB>
-__global__ __launch_bounds__(256) void k_sage_grad_w(CatIn a, MatRows dz, EpiGradW epi, int kchunk,
+__global__ __launch_bounds__(256) void k_sage_grad_w(MatRowsOnes a, MatRows dz, EpiGradW epi, int kchunk,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int k_begin = blockIdx.z * kchunk;
     if (k_begin >= n1) return;
-    a.n1 = n1; dz.rows = n1;
+    a.rows = n1; dz.rows = n1;
     const int k_end = min(n1, k_begin + kchunk);
-    gemm_tile<GBM, GBN, false, false, VA, VB>(blockIdx.x * GBM, blockIdx.y * GBN, 2 * a.D + 1, dz.cols,
+    gemm_tile<GBM, GBN, false, false, VA, VB>(blockIdx.x * GBM, blockIdx.y * GBN, a.cols + 1, dz.cols,
                                               k_begin, k_end, a, dz, epi);
 }
 
@@ -343,6 +352,19 @@ __global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, int64_
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
+// zero up to 3 * GS_MAXL caller buffers in one launch (blockIdx.y selects the buffer)
+struct ZeroList {
+    float *p[3 * GS_MAXL];
+    int64_t n[3 * GS_MAXL];
+};
+__global__ __launch_bounds__(256) void k_zero_buffers(ZeroList z) {
+    float *p = z.p[blockIdx.y];
+    const int64_t n = z.n[blockIdx.y];
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n;
+         x += (int64_t)gridDim.x * blockDim.x)
+        p[x] = 0.f;
+}
+
 int grid_1d(const gsplit_ctx *ctx, int64_t upper_threads) {
     int64_t want = std::max<int64_t>(1, gs_ceil_div(upper_threads, 256));
     return (int)std::min<int64_t>(want, (int64_t)ctx->n_cu * 8);
@@ -362,7 +384,7 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         if (rc) return rc;
     }
     for (int l = 0; l < L; ++l) {
-        int rc = gs_alloc(ctx, &sb.mean[l], sizeof(float) * ctx->ub_front[l + 1] * p->dims[l], "mean");
+        int rc = gs_alloc(ctx, &sb.xin[l], sizeof(float) * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
         if (rc) return rc;
     }
     sb.dtype = p->dtype;
@@ -385,26 +407,26 @@ int check_params(gsplit_ctx *ctx, const gsplit_sage_params *p, const char *who) 
     return GSPLIT_OK;
 }
 
-void launch_aggregate(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st) {
+void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st) {
     const GsLayerBuf &B = ctx->layer[l];
     const GsLevelMeta *mu = ctx->d_meta + (l + 1);
-    float *M = (float *)ctx->sage.mean[l];
+    float *X = (float *)ctx->sage.xin[l];
     const int64_t ub = ctx->ub_front[l + 1];
-    if (D % 4 != 0) {
-        hipLaunchKernelGGL(k_mean_aggregate_f32_any, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, mu, ctx->S, M);
+    if (D % 4 != 0 || !aligned16(hin)) {
+        hipLaunchKernelGGL(k_assemble_input_f32_any, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
         return;
     }
     const int nvec = D / 4;
     if (nvec <= 16)
-        hipLaunchKernelGGL(k_mean_aggregate_f32<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, mu, ctx->S, M);
+        hipLaunchKernelGGL(k_assemble_input_f32<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
     else if (nvec <= 32)
-        hipLaunchKernelGGL(k_mean_aggregate_f32<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, mu, ctx->S, M);
+        hipLaunchKernelGGL(k_assemble_input_f32<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
     else
-        hipLaunchKernelGGL(k_mean_aggregate_f32<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, mu, ctx->S, M);
+        hipLaunchKernelGGL(k_assemble_input_f32<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
 }
 
 }  // namespace
@@ -421,19 +443,18 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
     GsSageBuf &sb = ctx->sage;
-    sb.hidden[0] = const_cast<void *>(d_feat_local);   // caller-owned; read again by the backward pass
     for (int l = 0; l < L; ++l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const float *hin = l == 0 ? (const float *)d_feat_local : (const float *)sb.hidden[l];
         float *hout = l == L - 1 ? d_logits : (float *)sb.hidden[l + 1];
         const GsLayerBuf &B = ctx->layer[l];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
-        launch_aggregate(ctx, l, hin, D, st);
-        CatIn a{hin, (const float *)sb.mean[l], B.self_row, D, 0, 0};
+        launch_assemble(ctx, l, hin, D, st);
+        MatRows a{(const float *)sb.xin[l], 0, 2 * D};
         CatW b{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
         EpiFwd epi{hout, (const float *)p->d_bias[l], N, 0, l < L - 1 ? 1 : 0};
         dim3 grid((unsigned)gs_ceil_div(ctx->ub_front[l + 1], GBM), (unsigned)gs_ceil_div(N, GBN));
-        const bool va = D % 4 == 0 && aligned16(hin) && aligned16(sb.mean[l]);
+        const bool va = D % 2 == 0;   // rows of the assembled input are 2 * D floats: 16-byte aligned
         const bool vb = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
         else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
@@ -462,17 +483,21 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: parameters differ from the forward pass");
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
+    ZeroList zl;
+    int64_t zmax = 1;
     for (int l = 0; l < L; ++l) {
         if (!d_gw_self[l] || !d_gw_neigh[l] || !d_gbias[l])
             return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_bwd: NULL gradient pointer");
         const int64_t nw = (int64_t)p->dims[l] * p->dims[l + 1];
-        hipLaunchKernelGGL(k_fill_zero, dim3(grid_1d(ctx, nw)), dim3(256), 0, st, d_gw_self[l], nw, nullptr, S, 0);
-        hipLaunchKernelGGL(k_fill_zero, dim3(grid_1d(ctx, nw)), dim3(256), 0, st, d_gw_neigh[l], nw, nullptr, S, 0);
-        hipLaunchKernelGGL(k_fill_zero, dim3(1), dim3(256), 0, st, d_gbias[l], (int64_t)p->dims[l + 1], nullptr, S, 0);
+        zl.p[3 * l] = d_gw_self[l];      zl.n[3 * l] = nw;
+        zl.p[3 * l + 1] = d_gw_neigh[l]; zl.n[3 * l + 1] = nw;
+        zl.p[3 * l + 2] = d_gbias[l];    zl.n[3 * l + 2] = p->dims[l + 1];
+        zmax = std::max(zmax, nw);
     }
+    hipLaunchKernelGGL(k_zero_buffers, dim3((unsigned)std::min<int64_t>(64, gs_ceil_div(zmax, 1024)), 3 * L),
+                       dim3(256), 0, st, zl);
     for (int l = L - 1; l >= 0; --l) {
         const int D = p->dims[l], N = p->dims[l + 1];
-        const float *hin = (const float *)sb.hidden[l];
         const GsLayerBuf &B = ctx->layer[l];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
         const float *dH = l == L - 1 ? d_grad_logits : sb.ghid[l + 1];
@@ -482,11 +507,11 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             hipLaunchKernelGGL(k_relu_mask, dim3(grid_1d(ctx, ub * N)), dim3(256), 0, st, sb.ghid[l + 1], hout,
                                mu, S, N);
         MatRows dz{dH, 0, N};
-        // weight and bias gradients, summed over all splits (layer 0 reads its input rows from the
-        // caller's gathered features, which therefore must still be alive)
-        CatIn in{hin, (const float *)sb.mean[l], B.self_row, D, 0, 1};
+        // weight and bias gradients, summed over all splits: [X | 1]^T dZ with the layer input X
+        // assembled by the forward pass
+        MatRowsOnes in{(const float *)sb.xin[l], 0, 2 * D};
         EpiGradW ew{d_gw_self[l], d_gw_neigh[l], d_gbias[l], D, N};
-        const bool vin = D % 4 == 0 && aligned16(hin) && aligned16(sb.mean[l]);
+        const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
         const bool vw = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         {

@@ -3,13 +3,24 @@
 // buckets, next local frontiers and the shuffle index.  Every kernel takes its problem size from
 // device memory (GsLevelMeta), so one iteration is enqueued without any host synchronisation and
 // the launch shapes depend only on the context's upper bounds.
+//
+// Per sampling layer (8 launches):
+//   1 sample_layer            + insert (vertex, split) keys of destinations and slots into tab_mixed
+//   2 partition A: count      + reset tab_local
+//   3 partition A: scan         (mixed-frontier offsets, bucket offsets, edge count)
+//   4 partition A: scatter      mixed frontiers, block CSR offsets, owner buckets = received ids,
+//                             + insert destinations and received ids into tab_local
+//   5 partition B: count      + edges[l] relabelled to mixed-frontier rows
+//   6 partition B: scan         (next local-frontier offsets)
+//   7 partition B: scatter      next local frontiers + reset tab_mixed for the next layer
+//   8 shuffle index (+ its composition with edges[l] for the forward/backward passes)
 #include "gsplit_internal.h"
 
 namespace {
 
-constexpr int PART_NB = 1024;   // chunks of a partition pass (one workgroup each)
-constexpr int PART_BS = 256;
-constexpr int PART_NK = 9;      // up to 8 split classes + 1 auxiliary counter
+constexpr int PART_BS = 256;     // threads of a partition workgroup
+constexpr int PART_NK = 17;     // classes of a partition pass: 8 senders + 8 owners + 1 counter
+constexpr int PART_MAX_NB = 1024;
 constexpr uint32_t EMPTY_KEY = 0xFFFFFFFFu;
 
 // ------------------------------------------------------------------------------------------
@@ -90,20 +101,25 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 // rule is resolved with fan-1 rounds of broadcast + ballot inside the lane group.
 // The random word of draw q is word (q mod 4) of Philox(counter = (v, iter lo, iter hi,
 // layer * 65536 + q / 4), key = (seed lo, seed hi)): a function of the global vertex id only.
+// Every destination vertex (position i) and every sampled slot (position n1 + slot index) is
+// also entered into the mixed-frontier table under the key (vertex, split of the row).
 // ------------------------------------------------------------------------------------------
 template <int G, typename IndPtrT>
 __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
                                                       const int32_t *__restrict__ indices,
                                                       const int32_t *__restrict__ front,
+                                                      GsLevelMeta *meta_lo,
                                                       const GsLevelMeta *__restrict__ meta_up, int S,
                                                       int fan, uint32_t layer, uint64_t seed,
-                                                      uint64_t iter, int32_t *__restrict__ nbr,
+                                                      uint64_t iter, GsTable tab,
+                                                      int32_t *__restrict__ nbr,
                                                       int32_t *__restrict__ cnt) {
     const int n1 = meta_up->front_off[S];
+    const int bits = table_bits(n1 * (1 + fan));
     const int groups_per_block = PART_BS / G;
     const int q = threadIdx.x % G;
     const int sub = lane_id() / G;
-    const uint64_t gmask = (G == 64) ? ~0ull : ((1ull << G) - 1ull);
+    const uint64_t gmask = (G == 64) ? ~0ull : ((1ull << (G & 63)) - 1ull);
     const int stride = gridDim.x * groups_per_block;
     // every lane of a wave runs the same number of iterations (ballots/shuffles need that)
     const int first = blockIdx.x * groups_per_block + (threadIdx.x / 64) * (64 / G);
@@ -142,64 +158,37 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
         if (active && q < fan) {
             if (floyd) val = indices[beg + (int64_t)chosen];
             else if ((uint32_t)q < d) val = indices[beg + q];
-            nbr[(int64_t)row * fan + q] = val;
-            if (q == 0) cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
+            const int64_t g = (int64_t)row * fan + q;
+            nbr[g] = val;
+            const uint32_t sp = (uint32_t)split_of(meta_up->front_off, S, row);
+            if (q == 0) {
+                cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
+                table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, row, &meta_lo->error);
+            }
+            if (val >= 0)
+                table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp, (int32_t)(n1 + g), &meta_lo->error);
         }
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// table reset (sized on the device from the live frontier size) + per-layer counters
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_reset_tables(GsTable a, GsTable b, GsLevelMeta *meta_lo,
-                                                      const GsLevelMeta *meta_up, int S, int fan) {
-    const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
-    const int64_t cap = 1ll << bits;
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < cap;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        a.keys[i] = EMPTY_KEY; a.pos[i] = 0x7FFFFFFF;
-        b.keys[i] = EMPTY_KEY; b.pos[i] = 0x7FFFFFFF;
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) { meta_lo->error = 0; }
-}
-
-// mixed-frontier table: key (vertex, split) -> first position in (destination vertices, slots)
-__global__ __launch_bounds__(256) void k_insert_mixed(GsTable tab, const int32_t *__restrict__ front,
-                                                      const int32_t *__restrict__ nbr,
-                                                      const int32_t *__restrict__ cnt,
-                                                      GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
-                                                      int S, int fan) {
-    const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
-    const int64_t total = (int64_t)n1 * (1 + fan);
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
-         x += (int64_t)gridDim.x * blockDim.x) {
-        int32_t id, i;
-        if (x < n1) { i = (int)x; id = front[i]; }
-        else {
-            const int64_t g = x - n1;
-            i = (int)(g / fan);
-            if ((int)(g - (int64_t)i * fan) >= cnt[i]) continue;
-            id = nbr[g];
-        }
-        const int s = split_of(meta_up->front_off, S, i);
-        table_insert(tab, bits, (uint32_t)id * (uint32_t)S + (uint32_t)s, (int32_t)x, &meta_lo->error);
-    }
+__device__ __forceinline__ void table_reset_entry(const GsTable &t, int64_t i) {
+    t.keys[i] = EMPTY_KEY;
+    t.pos[i] = 0x7FFFFFFF;
 }
 
 // ------------------------------------------------------------------------------------------
-// Stable multi-class partition: three launches (count per chunk, scan, scatter).
+// Stable multi-class partition: three launches (count per chunk, scan, scatter) over `nb` chunks.
 // A functor F describes the elements:
 //   n()                       number of elements (read from device memory)
 //   classify(g)               bit k set <=> element g counts in class k  (k < F::NK)
-//   key_bases(totals, bases)  run by one thread between the passes: where each class starts
+//   key_bases(totals, bases)  run by one thread in the scan: where each class starts
 //   emit(g, mask, rk)         rk[k] = bases[k] + number of class-k elements before g
-//   n_extra(), extra(g)       an independent element-wise epilogue of the scatter pass
+//   n_extra(), extra(g)       independent element-wise work appended to the scatter pass
+//   n_side(), side(g)         independent element-wise work appended to the count pass
 // Elements keep their order inside every class (wave ballots + running chunk counters).
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ int part_chunk(int n) {
-    int c = (n + PART_NB - 1) / PART_NB;
+__device__ __forceinline__ int part_chunk(int n, int nb) {
+    int c = (n + nb - 1) / nb;
     return ((c + PART_BS - 1) / PART_BS) * PART_BS;
 }
 
@@ -209,7 +198,7 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
     if (threadIdx.x < PART_NK) s_cnt[threadIdx.x] = 0;
     __syncthreads();
     const int n = f.n();
-    const int chunk = part_chunk(n);
+    const int chunk = part_chunk(n, gridDim.x);
     const int64_t beg64 = (int64_t)blockIdx.x * chunk;
     if (beg64 < n) {
         const int beg = (int)beg64;
@@ -231,19 +220,25 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
     }
     __syncthreads();
     if (threadIdx.x < F::NK) hist[blockIdx.x * PART_NK + threadIdx.x] = s_cnt[threadIdx.x];
+    const int64_t ns = f.n_side();
+    for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < ns;
+         g += (int64_t)gridDim.x * PART_BS)
+        f.side(g);
 }
 
+// one workgroup of 256 threads; thread t owns chunks t*per .. t*per+per-1 (per = nb / 256)
 template <class F>
-__global__ __launch_bounds__(PART_NB) void k_part_scan(F f, const int32_t *__restrict__ hist,
+__global__ __launch_bounds__(PART_BS) void k_part_scan(F f, int nb, const int32_t *__restrict__ hist,
                                                        int32_t *__restrict__ base) {
-    __shared__ int s_wsum[PART_NB / 64];
+    __shared__ int s_wsum[PART_BS / 64];
     __shared__ int s_tot[PART_NK], s_base[PART_NK];
-    const int b = threadIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
-    int ex[F::NK];
-#pragma unroll
+    const int t = threadIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
+    const int per = nb / PART_BS;
+#pragma unroll 1
     for (int k = 0; k < F::NK; ++k) {
-        const int v = hist[b * PART_NK + k];
-        int inc = v;
+        int mine = 0;
+        for (int j = 0; j < per; ++j) mine += hist[(t * per + j) * PART_NK + k];
+        int inc = mine;
         for (int o = 1; o < 64; o <<= 1) {
             int up = __shfl_up(inc, o);
             if (lane >= o) inc += up;
@@ -251,19 +246,26 @@ __global__ __launch_bounds__(PART_NB) void k_part_scan(F f, const int32_t *__res
         if (lane == 63) s_wsum[wave] = inc;
         __syncthreads();
         int pre = 0, tot = 0;
-        for (int w = 0; w < PART_NB / 64; ++w) {
+        for (int w = 0; w < PART_BS / 64; ++w) {
             const int x = s_wsum[w];
             pre += (w < wave) ? x : 0;
             tot += x;
         }
-        ex[k] = pre + inc - v;
-        if (b == 0) s_tot[k] = tot;
+        int run = pre + inc - mine;
+        for (int j = 0; j < per; ++j) {
+            const int idx = (t * per + j) * PART_NK + k;
+            const int h = hist[idx];
+            base[idx] = run;
+            run += h;
+        }
+        if (t == 0) s_tot[k] = tot;
         __syncthreads();
     }
-    if (b == 0) f.key_bases(s_tot, s_base);
+    if (t == 0) f.key_bases(s_tot, s_base);
     __syncthreads();
-#pragma unroll
-    for (int k = 0; k < F::NK; ++k) base[b * PART_NK + k] = s_base[k] + ex[k];
+    for (int j = 0; j < per; ++j)
+#pragma unroll 1
+        for (int k = 0; k < F::NK; ++k) base[(t * per + j) * PART_NK + k] += s_base[k];
 }
 
 template <class F>
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
     __shared__ int s_run[PART_NK];
     __shared__ int s_wcnt[PART_BS / 64][PART_NK];
     const int n = f.n();
-    const int chunk = part_chunk(n);
+    const int chunk = part_chunk(n, gridDim.x);
     const int64_t beg64 = (int64_t)blockIdx.x * chunk;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     if (beg64 < n) {
@@ -314,10 +316,11 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
 }
 
 // ---- local_front[L] = targets separated by owner, order kept ---------------------------------
+// (+ reset of the mixed-frontier table for the top sampling layer)
 struct PartTargets {
     static constexpr int NK = GS_MAXS;
     const int32_t *targets; int n_targets; const uint8_t *pmap; int S; uint32_t n_vertices;
-    int32_t *front; int32_t *perm; GsLevelMeta *meta;
+    int32_t *front; int32_t *perm; GsLevelMeta *meta; GsTable tab_mixed; int fan_top;
     __device__ int n() const { return n_targets; }
     // an id outside the graph is replaced by vertex 0 and reported through the error flag
     __device__ int32_t target(int g) const {
@@ -341,157 +344,110 @@ struct PartTargets {
         front[rk[k]] = target(g);
         perm[rk[k]] = g;
     }
-    __device__ int64_t n_extra() const { return 0; }
-    __device__ void extra(int64_t) const {}
+    __device__ int64_t n_extra() const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
+    __device__ void extra(int64_t x) const { table_reset_entry(tab_mixed, x); }
+    __device__ int64_t n_side() const { return 0; }
+    __device__ void side(int64_t) const {}
 };
 
-// ---- mixed frontiers: destination vertices first, then first occurrences among the slots -----
-// class s (< S): slot is the first occurrence of its vertex in split s; class 8: slot is valid
-// (its exclusive rank is the edge number, which yields the block CSR offsets).
-struct PartMixed {
+// ---- partition A: mixed frontiers, block CSR offsets and owner buckets in one pass over the
+// slots.  A slot that is the first occurrence of its vertex inside its split s ("winner") gets
+//   class s      -> its row in mixed_front_s (destination vertices occupy the rows before)
+//   class 8 + t  -> its place in bucket[s -> t], t = f_G(vertex): partitioning the sender-ordered
+//                   slot stream by owner yields, for each receiver t, bucket[0->t] | bucket[1->t]
+//                   | ...: on one GPU the send buffers and the received concatenation are the
+//                   same memory.
+// Class 16 counts valid slots: its exclusive rank is the edge number (block CSR offsets).
+// Received ids and destination vertices are entered into the local-frontier table on the fly.
+struct PartMixedBuckets {
     static constexpr int NK = PART_NK;
-    GsTable tab; const int32_t *front; const int32_t *nbr; const int32_t *cnt;
-    int32_t *mixed; int32_t *blk_indptr;
+    GsTable tab_mixed, tab_local;
+    const int32_t *front; const int32_t *nbr; const int32_t *cnt; const uint8_t *pmap;
+    int32_t *mixed; int32_t *blk_indptr; int32_t *recv;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
     __device__ int n1() const { return meta_up->front_off[S]; }
+    __device__ int bits() const { return table_bits(n1() * (1 + fan)); }
     __device__ int n() const { return n1() * fan; }
     __device__ unsigned classify(int g) const {
         const int i = g / fan, q = g - i * fan;
         if (q >= cnt[i]) return 0u;
         const int s = split_of(meta_up->front_off, S, i);
-        const int bits = table_bits(n1() * (1 + fan));
-        const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-        const bool first = h >= 0 && tab.pos[h] == n1() + g;
-        return (1u << 8) | (first ? (1u << s) : 0u);
+        const int32_t id = nbr[g];
+        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        const bool first = h >= 0 && tab_mixed.pos[h] == n1() + g;
+        if (!first) return 1u << 16;
+        return (1u << 16) | (1u << s) | (1u << (8 + (pmap[id] & (GS_MAXS - 1))));
     }
     __device__ void key_bases(const int *tot, int *bases) const {
-        int acc = 0;
+        int acc = 0, racc = 0;
         for (int s = 0; s < GS_MAXS; ++s) {
             const int n_dst = (s < S) ? meta_up->front_off[s + 1] - meta_up->front_off[s] : 0;
-            if (s <= S) meta_lo->mixed_off[s] = acc;
+            if (s <= S) { meta_lo->mixed_off[s] = acc; meta_lo->recv_off[s] = racc; }
             bases[s] = acc + n_dst;
+            bases[8 + s] = racc;
             acc += n_dst + ((s < S) ? tot[s] : 0);
+            racc += (s < S) ? tot[8 + s] : 0;
         }
         meta_lo->mixed_off[S] = acc;
-        bases[8] = 0;
-        meta_lo->nnz = tot[8];
-        blk_indptr[n1()] = tot[8];
+        meta_lo->recv_off[S] = racc;
+        bases[16] = 0;
+        meta_lo->nnz = tot[16];
+        blk_indptr[n1()] = tot[16];
     }
     __device__ void emit(int g, unsigned m, const int *rk) const {
         const int i = g / fan, q = g - i * fan;
-        if (q == 0) blk_indptr[i] = rk[8];
-        const unsigned sm = m & 0xFFu;
-        if (sm) {
-            const int s = __ffs(sm) - 1;
-            const int bits = table_bits(n1() * (1 + fan));
-            const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-            mixed[rk[s]] = nbr[g];
-            if (h >= 0) tab.row[h] = rk[s] - meta_lo->mixed_off[s];
+        if (q == 0) {
+            blk_indptr[i] = rk[16];
+            // the first row of a sender marks where its buckets start at every receiver
+            // (senders are consecutive in the slot stream); sizes follow by subtraction on the host
+            const int s = split_of(meta_up->front_off, S, i);
+            if (i == meta_up->front_off[s])
+                for (int ss = s; ss >= 0 && meta_up->front_off[ss] == i; --ss)
+                    for (int t = 0; t < S; ++t) meta_lo->bucket_start[ss * GS_MAXS + t] = rk[8 + t];
         }
+        const unsigned sm = m & 0xFFu;
+        if (!sm) return;
+        const int s = __ffs(sm) - 1;
+        const int t = __ffs((m >> 8) & 0xFFu) - 1;
+        const int32_t id = nbr[g];
+        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        mixed[rk[s]] = id;
+        if (h >= 0) tab_mixed.row[h] = rk[s] - meta_lo->mixed_off[s];
+        recv[rk[8 + t]] = id;
+        table_insert(tab_local, bits(), (uint32_t)id, n1() + rk[8 + t], &meta_lo->error);
     }
-    // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier
+    // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier and come first
+    // in their owner's next local frontier
     __device__ int64_t n_extra() const { return n1(); }
     __device__ void extra(int64_t x) const {
         const int i = (int)x;
         const int s = split_of(meta_up->front_off, S, i);
         const int loc = i - meta_up->front_off[s];
-        const int bits = table_bits(n1() * (1 + fan));
         const int32_t id = front[i];
-        const int h = table_find(tab, bits, (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
         mixed[meta_lo->mixed_off[s] + loc] = id;
-        if (h >= 0) tab.row[h] = loc;
+        if (h >= 0) tab_mixed.row[h] = loc;
+        table_insert(tab_local, bits(), (uint32_t)id, i, &meta_lo->error);
     }
+    // the count pass also clears the local-frontier table (idle until the scatter pass)
+    __device__ int64_t n_side() const { return 1ll << bits(); }
+    __device__ void side(int64_t x) const { table_reset_entry(tab_local, x); }
 };
 
-// PartMixed::emit writes blk_indptr only for slot 0 of each row; rows exist for every frontier
-// vertex, valid or not, because classify() is evaluated for all n1 * fan slots.
-
-// edges[l] in mixed-frontier rows
-__global__ __launch_bounds__(256) void k_relabel_edges(GsTable tab, const int32_t *__restrict__ nbr,
-                                                       const int32_t *__restrict__ cnt,
-                                                       const int32_t *__restrict__ blk_indptr,
-                                                       int32_t *__restrict__ blk_src,
-                                                       GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
-                                                       int S, int fan) {
-    const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
-    const int64_t total = (int64_t)n1 * fan;
-    for (int64_t g = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; g < total;
-         g += (int64_t)gridDim.x * blockDim.x) {
-        const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
-        if (q >= cnt[i]) continue;
-        const int s = split_of(meta_up->front_off, S, i);
-        const int h = table_find(tab, bits, (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-        blk_src[blk_indptr[i] + q] = h >= 0 ? tab.row[h] : -1;
-    }
-}
-
-// ---- split(): owner buckets of the sampled part of every mixed frontier ----------------------
-// Elements are the rows of the concatenated mixed frontiers; class t = f_G(vertex) for rows beyond
-// the destination prefix.  Partitioning the sender-ordered stream by owner yields, for each
-// receiver t, bucket[0->t] | bucket[1->t] | ... : the send buffers and the received concatenation
-// are the same memory on one GPU.
-struct PartBuckets {
-    static constexpr int NK = GS_MAXS;
-    const int32_t *mixed; const uint8_t *pmap; int32_t *recv;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S;
-    __device__ int n() const { return meta_lo->mixed_off[S]; }
-    __device__ unsigned classify(int j) const {
-        const int s = split_of(meta_lo->mixed_off, S, j);
-        const int n_dst = meta_up->front_off[s + 1] - meta_up->front_off[s];
-        if (j - meta_lo->mixed_off[s] < n_dst) return 0u;
-        return 1u << (pmap[mixed[j]] & (GS_MAXS - 1));
-    }
-    __device__ void key_bases(const int *tot, int *bases) const {
-        int acc = 0;
-        for (int t = 0; t < GS_MAXS; ++t) {
-            bases[t] = acc;
-            if (t <= S) meta_lo->recv_off[t] = acc;
-            acc += (t < S) ? tot[t] : 0;
-        }
-        meta_lo->recv_off[S] = acc;
-    }
-    __device__ void emit(int j, unsigned m, const int *rk) const {
-        // the first row of a sender's mixed frontier marks where its buckets start at every
-        // receiver (senders are consecutive in the stream); sizes follow by subtraction on the host
-        const int s = split_of(meta_lo->mixed_off, S, j);
-        if (j == meta_lo->mixed_off[s])
-            for (int ss = s; ss >= 0 && meta_lo->mixed_off[ss] == j; --ss)
-                for (int t = 0; t < S; ++t) meta_lo->bucket_start[ss * GS_MAXS + t] = rk[t];
-        if (!m) return;
-        const int t = __ffs(m) - 1;
-        recv[rk[t]] = mixed[j];
-    }
-    __device__ int64_t n_extra() const { return 0; }
-    __device__ void extra(int64_t) const {}
-};
-
-// local-frontier table: key vertex -> first position in (own destination vertices, received ids)
-__global__ __launch_bounds__(256) void k_insert_local(GsTable tab, const int32_t *__restrict__ front,
-                                                      const int32_t *__restrict__ recv,
-                                                      GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
-                                                      int S, int fan) {
-    const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
-    const int64_t total = (int64_t)n1 + meta_lo->recv_off[S];
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
-         x += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t id = x < n1 ? front[x] : recv[x - n1];
-        table_insert(tab, bits, (uint32_t)id, (int32_t)x, &meta_lo->error);
-    }
-}
-
-// ---- next local frontiers: own destination vertices, then first occurrences of what arrived --
+// ---- partition B: next local frontiers = own destination vertices, then first occurrences of
+// what arrived (receiver t's ids are contiguous in recv, senders in order) ---------------------
 struct PartLocal {
     static constexpr int NK = GS_MAXS;
-    GsTable tab; const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
+    GsTable tab_local, tab_mixed;
+    const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
+    const int32_t *nbr; const int32_t *cnt; const int32_t *blk_indptr; int32_t *blk_src;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next;
     __device__ int n1() const { return meta_up->front_off[S]; }
+    __device__ int bits() const { return table_bits(n1() * (1 + fan)); }
     __device__ int n() const { return meta_lo->recv_off[S]; }
     __device__ unsigned classify(int r) const {
-        const int bits = table_bits(n1() * (1 + fan));
-        const int h = table_find(tab, bits, (uint32_t)recv[r], &meta_lo->error);
-        if (h < 0 || tab.pos[h] != n1() + r) return 0u;
+        const int h = table_find(tab_local, bits(), (uint32_t)recv[r], &meta_lo->error);
+        if (h < 0 || tab_local.pos[h] != n1() + r) return 0u;
         return 1u << split_of(meta_lo->recv_off, S, r);
     }
     __device__ void key_bases(const int *tot, int *bases) const {
@@ -507,21 +463,33 @@ struct PartLocal {
     __device__ void emit(int r, unsigned m, const int *rk) const {
         if (!m) return;
         const int t = __ffs(m) - 1;
-        const int bits = table_bits(n1() * (1 + fan));
-        const int h = table_find(tab, bits, (uint32_t)recv[r], &meta_lo->error);
+        const int h = table_find(tab_local, bits(), (uint32_t)recv[r], &meta_lo->error);
         front_lo[rk[t]] = recv[r];
-        if (h >= 0) tab.row[h] = rk[t];
+        if (h >= 0) tab_local.row[h] = rk[t];
     }
-    __device__ int64_t n_extra() const { return n1(); }
+    // scatter pass extras: destination vertices keep their order at the head of their owner's
+    // frontier; then the mixed-frontier table is cleared for the next sampling layer
+    __device__ int64_t n_extra() const {
+        return n1() + (fan_next > 0 ? (1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next))) : 0);
+    }
     __device__ void extra(int64_t x) const {
+        if (x >= n1()) { table_reset_entry(tab_mixed, x - n1()); return; }
         const int i = (int)x;
         const int t = split_of(meta_up->front_off, S, i);
         const int rowp = meta_lo->front_off[t] + (i - meta_up->front_off[t]);
-        const int bits = table_bits(n1() * (1 + fan));
         const int32_t id = front_up[i];
-        const int h = table_find(tab, bits, (uint32_t)id, &meta_lo->error);
+        const int h = table_find(tab_local, bits(), (uint32_t)id, &meta_lo->error);
         front_lo[rowp] = id;
-        if (h >= 0) tab.row[h] = rowp;
+        if (h >= 0) tab_local.row[h] = rowp;
+    }
+    // count pass extras: edges[l] rewritten to rows of the owning split's mixed frontier
+    __device__ int64_t n_side() const { return (int64_t)n1() * fan; }
+    __device__ void side(int64_t g) const {
+        const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+        if (q >= cnt[i]) return;
+        const int s = split_of(meta_up->front_off, S, i);
+        const int h = table_find(tab_mixed, bits(), (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        blk_src[blk_indptr[i] + q] = h >= 0 ? tab_mixed.row[h] : -1;
     }
 };
 
@@ -561,15 +529,20 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab, const int32_
     }
 }
 
-__global__ void k_clear_error(GsLevelMeta *meta) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) meta->error = 0;
+__global__ void k_clear_errors(GsLevelMeta *meta, int n_levels) {
+    if (blockIdx.x == 0 && (int)threadIdx.x < n_levels) meta[threadIdx.x].error = 0;
+}
+
+int part_blocks(int64_t upper_items) {
+    return upper_items <= (1 << 18) ? 256 : upper_items <= (1 << 20) ? 512 : PART_MAX_NB;
 }
 
 template <class F>
-void run_partition(gsplit_ctx *ctx, const F &f, hipStream_t st) {
-    hipLaunchKernelGGL(k_part_count<F>, dim3(PART_NB), dim3(PART_BS), 0, st, f, ctx->part_hist);
-    hipLaunchKernelGGL(k_part_scan<F>, dim3(1), dim3(PART_NB), 0, st, f, ctx->part_hist, ctx->part_base);
-    hipLaunchKernelGGL(k_part_scatter<F>, dim3(PART_NB), dim3(PART_BS), 0, st, f, ctx->part_base);
+void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t st) {
+    const int nb = part_blocks(upper_items);
+    hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    hipLaunchKernelGGL(k_part_scan<F>, dim3(1), dim3(PART_BS), 0, st, f, nb, ctx->part_hist, ctx->part_base);
+    hipLaunchKernelGGL(k_part_scatter<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_base);
 }
 
 int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
@@ -583,21 +556,22 @@ template <typename IndPtrT>
 void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStream_t st) {
     const int fan = ctx->fan[l];
     const int64_t ub = ctx->ub_front[l + 1];
+    GsLevelMeta *ml = ctx->d_meta + l;
     const GsLevelMeta *mu = ctx->d_meta + (l + 1);
     const IndPtrT *ip = (const IndPtrT *)ctx->graph.d_indptr;
     GsLayerBuf &B = ctx->layer[l];
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, B.nbr, B.cnt);
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
     } else if (fan <= 32) {
         hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, B.nbr, B.cnt);
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
     } else {
         hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, B.nbr, B.cnt);
+                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
+                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
     }
 }
 
@@ -619,10 +593,10 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
     ctx->sage.fwd_done = false;
     ctx->last_stream = st;
 
-    hipLaunchKernelGGL(k_clear_error, dim3(1), dim3(64), 0, st, ctx->d_meta + L);
+    hipLaunchKernelGGL(k_clear_errors, dim3(1), dim3(64), 0, st, ctx->d_meta, L + 1);
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
-                   ctx->front[L], ctx->target_perm, ctx->d_meta + L};
-    run_partition(ctx, pt, st);
+                   ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1]};
+    run_partition(ctx, pt, ctx->ub_front[L], st);
 
     for (int l = L - 1; l >= 0; --l) {
         const int fan = ctx->fan[l];
@@ -634,20 +608,12 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, st);
         else launch_sample<int32_t>(ctx, l, seed, iter, st);
 
-        hipLaunchKernelGGL(k_reset_tables, dim3(grid_for(ctx, 2 * ub1 * (1 + fan))), dim3(256), 0, st,
-                           ctx->tab_mixed, ctx->tab_local, ml, mu, S, fan);
-        hipLaunchKernelGGL(k_insert_mixed, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
-                           ctx->tab_mixed, ctx->front[l + 1], B.nbr, B.cnt, ml, mu, S, fan);
-        PartMixed pm{ctx->tab_mixed, ctx->front[l + 1], B.nbr, B.cnt, B.mixed, B.blk_indptr, ml, mu, S, fan};
-        run_partition(ctx, pm, st);
-        hipLaunchKernelGGL(k_relabel_edges, dim3(grid_for(ctx, ub1 * fan)), dim3(256), 0, st,
-                           ctx->tab_mixed, B.nbr, B.cnt, B.blk_indptr, B.blk_src, ml, mu, S, fan);
-        PartBuckets pb{B.mixed, ctx->graph.d_pmap, B.recv, ml, mu, S};
-        run_partition(ctx, pb, st);
-        hipLaunchKernelGGL(k_insert_local, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
-                           ctx->tab_local, ctx->front[l + 1], B.recv, ml, mu, S, fan);
-        PartLocal pl{ctx->tab_local, ctx->front[l + 1], B.recv, ctx->front[l], ml, mu, S, fan};
-        run_partition(ctx, pl, st);
+        PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, B.cnt,
+                            ctx->graph.d_pmap, B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
+        run_partition(ctx, pa, ub1 * fan, st);
+        PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
+                     B.nbr, B.cnt, B.blk_indptr, B.blk_src, ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
+        run_partition(ctx, pl, ub1 * fan, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, B.mixed, ctx->front[l + 1], B.nbr, B.cnt, B.blk_indptr,
                            B.src_row, B.self_row, B.edge_row, ml, mu, S, fan);
