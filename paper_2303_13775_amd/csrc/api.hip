@@ -74,9 +74,10 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     // no-dedup upper bounds on the frontier sizes
     const int L = ctx->L;
     ctx->ub_front[L] = c->max_targets;
-    int64_t tab_cap = 1024;
+    int64_t tab_cap = 1024, max_items = 1024;
     for (int l = L - 1; l >= 0; --l) {
         const int64_t grown = ctx->ub_front[l + 1] * (1 + ctx->fan[l]);
+        max_items = std::max(max_items, grown);
         ctx->ub_front[l] = std::min<int64_t>(g->n_vertices, grown);
         if (grown >= (1ll << 29)) {
             delete ctx;
@@ -107,10 +108,13 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
     for (GsTable *t : {&ctx->tab_local, &ctx->tab_mixed}) {
-        A((void **)&t->keys, sizeof(uint32_t) * tab_cap, "table keys");
-        A((void **)&t->pos, sizeof(int32_t) * tab_cap, "table pos");
-        A((void **)&t->row, sizeof(int32_t) * tab_cap, "table row");
+        A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
+        A((void **)&t->row, sizeof(int32_t) * tab_cap, "table rows");
     }
+    A((void **)&ctx->ent_mixed, sizeof(int32_t) * max_items, "ent_mixed");
+    A((void **)&ctx->ent_local, sizeof(int32_t) * max_items, "ent_local");
+    A((void **)&ctx->mixed_ent, sizeof(int32_t) * max_items, "mixed_ent");
+    A((void **)&ctx->cls, sizeof(uint32_t) * max_items, "class masks");
     A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 17, "partition histogram");
     A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 17, "partition bases");
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)

@@ -31,11 +31,10 @@ struct GsLevelMeta {
     int32_t pad[2];
 };
 
-// Open-addressing table in HBM: key -> (smallest position seen, final row).
+// Open-addressing table in HBM: entry = key << 32 | smallest position seen; row = final row.
 struct GsTable {
-    uint32_t *keys;
-    int32_t  *pos;
-    int32_t  *row;
+    unsigned long long *slot;
+    int32_t            *row;
 };
 
 struct GsLayerBuf {            // sampling layer l
@@ -79,6 +78,11 @@ struct gsplit_ctx {
     bool         h_meta_valid = false;
     GsTable      tab_local, tab_mixed;
     int64_t      tab_cap = 0;
+    // per-element scratch of the current sampling layer (sized for the largest layer):
+    int32_t     *ent_mixed = nullptr;       // tab_mixed entry of each destination / slot
+    int32_t     *ent_local = nullptr;       // tab_local entry of each destination / received id
+    int32_t     *mixed_ent = nullptr;       // tab_local entry of each mixed-frontier row
+    uint32_t    *cls = nullptr;             // class mask left by a count pass for its scatter pass
     int32_t     *part_hist = nullptr;       // partition scratch
     int32_t     *part_base = nullptr;
 

@@ -14,6 +14,9 @@
 //   6 partition B: scan         (next local-frontier offsets)
 //   7 partition B: scatter      next local frontiers + reset tab_mixed for the next layer
 //   8 shuffle index (+ its composition with edges[l] for the forward/backward passes)
+// A dependent HBM access costs about a microsecond, and these kernels are chains of them, so every
+// element remembers the table entry it landed in (no second probe sequence) and the count passes
+// leave their classification behind for the scatter passes.
 #include "gsplit_internal.h"
 
 namespace {
@@ -21,7 +24,7 @@ namespace {
 constexpr int PART_BS = 256;     // threads of a partition workgroup
 constexpr int PART_NK = 17;     // classes of a partition pass: 8 senders + 8 owners + 1 counter
 constexpr int PART_MAX_NB = 1024;
-constexpr uint32_t EMPTY_KEY = 0xFFFFFFFFu;
+constexpr unsigned long long EMPTY_ENTRY = ~0ull;
 
 // ------------------------------------------------------------------------------------------
 // small device helpers
@@ -49,33 +52,29 @@ __device__ __forceinline__ uint32_t table_slot(uint32_t key, int bits) {
     return (key * 0x9E3779B1u) >> (32 - bits);
 }
 
-// insert key, remember the smallest position that carried it
-__device__ __forceinline__ void table_insert(const GsTable &t, int bits, uint32_t key, int32_t p,
-                                             int32_t *err) {
+// Open-addressing table with 64-bit entries (key << 32 | position).  Inserting a key keeps the
+// smallest position that carried it: claim an empty entry with one compare-and-swap, otherwise
+// (same key) lower it with a 64-bit atomic min; the entry is read first and the atomic skipped
+// when it cannot change anything, which keeps hub vertices from serialising on one address.
+// Returns the entry index (-1 and the error flag if the table is full, which sizing excludes).
+__device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t key, uint32_t p,
+                                            int32_t *err) {
     const uint32_t mask = (1u << bits) - 1u;
+    const unsigned long long mine = ((unsigned long long)key << 32) | p;
     uint32_t h = table_slot(key, bits);
     for (uint32_t probe = 0; probe <= mask; ++probe) {
-        uint32_t old = atomicCAS(&t.keys[h], EMPTY_KEY, key);
-        if (old == EMPTY_KEY || old == key) {
-            atomicMin(&t.pos[h], p);
-            return;
+        unsigned long long cur = __hip_atomic_load(&t.slot[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cur == EMPTY_ENTRY) {
+            cur = atomicCAS(&t.slot[h], EMPTY_ENTRY, mine);
+            if (cur == EMPTY_ENTRY) return (int)h;
+        }
+        if ((uint32_t)(cur >> 32) == key) {
+            if (mine < cur) atomicMin(&t.slot[h], mine);
+            return (int)h;
         }
         h = (h + 1) & mask;
     }
     *err = 1;
-}
-
-// slot of a key that is known to be present (-1 and the error flag if it is not)
-__device__ __forceinline__ int table_find(const GsTable &t, int bits, uint32_t key, int32_t *err) {
-    const uint32_t mask = (1u << bits) - 1u;
-    uint32_t h = table_slot(key, bits);
-    for (uint32_t probe = 0; probe <= mask; ++probe) {
-        uint32_t k = t.keys[h];
-        if (k == key) return (int)h;
-        if (k == EMPTY_KEY) break;
-        h = (h + 1) & mask;
-    }
-    *err = 2;
     return -1;
 }
 
@@ -102,7 +101,8 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 // The random word of draw q is word (q mod 4) of Philox(counter = (v, iter lo, iter hi,
 // layer * 65536 + q / 4), key = (seed lo, seed hi)): a function of the global vertex id only.
 // Every destination vertex (position i) and every sampled slot (position n1 + slot index) is
-// also entered into the mixed-frontier table under the key (vertex, split of the row).
+// also entered into the mixed-frontier table under the key (vertex, split of the row); the entry
+// index is kept in ent_mixed (destinations first, then slots; -1 for padding slots).
 // ------------------------------------------------------------------------------------------
 template <int G, typename IndPtrT>
 __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
@@ -112,6 +112,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                                                       const GsLevelMeta *__restrict__ meta_up, int S,
                                                       int fan, uint32_t layer, uint64_t seed,
                                                       uint64_t iter, GsTable tab,
+                                                      int32_t *__restrict__ ent_mixed,
                                                       int32_t *__restrict__ nbr,
                                                       int32_t *__restrict__ cnt) {
     const int n1 = meta_up->front_off[S];
@@ -163,24 +164,23 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             const uint32_t sp = (uint32_t)split_of(meta_up->front_off, S, row);
             if (q == 0) {
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
-                table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, row, &meta_lo->error);
+                ent_mixed[row] = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
+                                              &meta_lo->error);
             }
-            if (val >= 0)
-                table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp, (int32_t)(n1 + g), &meta_lo->error);
+            ent_mixed[n1 + g] = val < 0 ? -1
+                                        : table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp,
+                                                       (uint32_t)(n1 + g), &meta_lo->error);
         }
     }
-}
-
-__device__ __forceinline__ void table_reset_entry(const GsTable &t, int64_t i) {
-    t.keys[i] = EMPTY_KEY;
-    t.pos[i] = 0x7FFFFFFF;
 }
 
 // ------------------------------------------------------------------------------------------
 // Stable multi-class partition: three launches (count per chunk, scan, scatter) over `nb` chunks.
 // A functor F describes the elements:
 //   n()                       number of elements (read from device memory)
-//   classify(g)               bit k set <=> element g counts in class k  (k < F::NK)
+//   classify(g)               count pass: bit k set <=> element g counts in class k (k < F::NK);
+//                             may leave the mask behind for the scatter pass
+//   cached(g)                 scatter pass: the same mask
 //   key_bases(totals, bases)  run by one thread in the scan: where each class starts
 //   emit(g, mask, rk)         rk[k] = bases[k] + number of class-k elements before g
 //   n_extra(), extra(g)       independent element-wise work appended to the scatter pass
@@ -226,46 +226,58 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
         f.side(g);
 }
 
-// one workgroup of 256 threads; thread t owns chunks t*per .. t*per+per-1 (per = nb / 256)
-template <class F>
-__global__ __launch_bounds__(PART_BS) void k_part_scan(F f, int nb, const int32_t *__restrict__ hist,
+// one workgroup of 256 threads; thread t owns chunks t*PER .. t*PER+PER-1 (nb = 256 * PER).
+// All histogram words are fetched before anything depends on them.
+template <class F, int PER>
+__global__ __launch_bounds__(PART_BS) void k_part_scan(F f, const int32_t *__restrict__ hist,
                                                        int32_t *__restrict__ base) {
-    __shared__ int s_wsum[PART_BS / 64];
+    __shared__ int s_wsum[F::NK][PART_BS / 64];
     __shared__ int s_tot[PART_NK], s_base[PART_NK];
     const int t = threadIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
-    const int per = nb / PART_BS;
-#pragma unroll 1
+    int v[PER][F::NK];
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+#pragma unroll
+        for (int k = 0; k < F::NK; ++k) v[j][k] = hist[(t * PER + j) * PART_NK + k];
+    int ex[F::NK];
+#pragma unroll
     for (int k = 0; k < F::NK; ++k) {
         int mine = 0;
-        for (int j = 0; j < per; ++j) mine += hist[(t * per + j) * PART_NK + k];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) mine += v[j][k];
         int inc = mine;
+#pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             int up = __shfl_up(inc, o);
             if (lane >= o) inc += up;
         }
-        if (lane == 63) s_wsum[wave] = inc;
-        __syncthreads();
+        if (lane == 63) s_wsum[k][wave] = inc;
+        ex[k] = inc - mine;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < F::NK; ++k) {
         int pre = 0, tot = 0;
+#pragma unroll
         for (int w = 0; w < PART_BS / 64; ++w) {
-            const int x = s_wsum[w];
+            const int x = s_wsum[k][w];
             pre += (w < wave) ? x : 0;
             tot += x;
         }
-        int run = pre + inc - mine;
-        for (int j = 0; j < per; ++j) {
-            const int idx = (t * per + j) * PART_NK + k;
-            const int h = hist[idx];
-            base[idx] = run;
-            run += h;
-        }
+        ex[k] += pre;
         if (t == 0) s_tot[k] = tot;
-        __syncthreads();
     }
     if (t == 0) f.key_bases(s_tot, s_base);
     __syncthreads();
-    for (int j = 0; j < per; ++j)
-#pragma unroll 1
-        for (int k = 0; k < F::NK; ++k) base[(t * per + j) * PART_NK + k] += s_base[k];
+#pragma unroll
+    for (int k = 0; k < F::NK; ++k) {
+        int run = s_base[k] + ex[k];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            base[(t * PER + j) * PART_NK + k] = run;
+            run += v[j][k];
+        }
+    }
 }
 
 template <class F>
@@ -284,7 +296,7 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
         for (int tile = beg; tile < end; tile += PART_BS) {
             const int g = tile + threadIdx.x;
             const bool in = g < end;
-            const unsigned m = in ? f.classify(g) : 0u;
+            const unsigned m = in ? f.cached(g) : 0u;
             int rk[F::NK];
 #pragma unroll
             for (int k = 0; k < F::NK; ++k) {
@@ -330,6 +342,7 @@ struct PartTargets {
         return 0;
     }
     __device__ unsigned classify(int g) const { return 1u << (pmap[target(g)] & (GS_MAXS - 1)); }
+    __device__ unsigned cached(int g) const { return classify(g); }
     __device__ void key_bases(const int *tot, int *bases) const {
         int acc = 0;
         for (int k = 0; k < GS_MAXS; ++k) {
@@ -345,7 +358,7 @@ struct PartTargets {
         perm[rk[k]] = g;
     }
     __device__ int64_t n_extra() const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
-    __device__ void extra(int64_t x) const { table_reset_entry(tab_mixed, x); }
+    __device__ void extra(int64_t x) const { tab_mixed.slot[x] = EMPTY_ENTRY; }
     __device__ int64_t n_side() const { return 0; }
     __device__ void side(int64_t) const {}
 };
@@ -362,22 +375,29 @@ struct PartTargets {
 struct PartMixedBuckets {
     static constexpr int NK = PART_NK;
     GsTable tab_mixed, tab_local;
-    const int32_t *front; const int32_t *nbr; const int32_t *cnt; const uint8_t *pmap;
+    const int32_t *front; const int32_t *nbr; const uint8_t *pmap;
+    const int32_t *ent_mixed; uint32_t *cls; int32_t *ent_local; int32_t *mixed_ent;
     int32_t *mixed; int32_t *blk_indptr; int32_t *recv;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int bits() const { return table_bits(n1() * (1 + fan)); }
     __device__ int n() const { return n1() * fan; }
     __device__ unsigned classify(int g) const {
-        const int i = g / fan, q = g - i * fan;
-        if (q >= cnt[i]) return 0u;
-        const int s = split_of(meta_up->front_off, S, i);
-        const int32_t id = nbr[g];
-        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-        const bool first = h >= 0 && tab_mixed.pos[h] == n1() + g;
-        if (!first) return 1u << 16;
-        return (1u << 16) | (1u << s) | (1u << (8 + (pmap[id] & (GS_MAXS - 1))));
+        const int h = ent_mixed[n1() + g];
+        unsigned m = 0u;
+        if (h >= 0) {
+            const int32_t id = nbr[g];
+            const bool first = (uint32_t)tab_mixed.slot[h] == (uint32_t)(n1() + g);
+            m = 1u << 16;
+            if (first) {
+                const int s = split_of(meta_up->front_off, S, g / fan);
+                m |= (1u << s) | (1u << (8 + (pmap[id] & (GS_MAXS - 1))));
+            }
+        }
+        cls[g] = m;
+        return m;
     }
+    __device__ unsigned cached(int g) const { return cls[g]; }
     __device__ void key_bases(const int *tot, int *bases) const {
         int acc = 0, racc = 0;
         for (int s = 0; s < GS_MAXS; ++s) {
@@ -410,11 +430,14 @@ struct PartMixedBuckets {
         const int s = __ffs(sm) - 1;
         const int t = __ffs((m >> 8) & 0xFFu) - 1;
         const int32_t id = nbr[g];
-        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
+        const int h = ent_mixed[n1() + g];
+        const int r = rk[8 + t];
         mixed[rk[s]] = id;
-        if (h >= 0) tab_mixed.row[h] = rk[s] - meta_lo->mixed_off[s];
-        recv[rk[8 + t]] = id;
-        table_insert(tab_local, bits(), (uint32_t)id, n1() + rk[8 + t], &meta_lo->error);
+        tab_mixed.row[h] = rk[s] - meta_lo->mixed_off[s];
+        recv[r] = id;
+        const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)(n1() + r), &meta_lo->error);
+        ent_local[n1() + r] = hl;
+        mixed_ent[rk[s]] = hl;
     }
     // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier and come first
     // in their owner's next local frontier
@@ -424,14 +447,17 @@ struct PartMixedBuckets {
         const int s = split_of(meta_up->front_off, S, i);
         const int loc = i - meta_up->front_off[s];
         const int32_t id = front[i];
-        const int h = table_find(tab_mixed, bits(), (uint32_t)id * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-        mixed[meta_lo->mixed_off[s] + loc] = id;
+        const int h = ent_mixed[i];
+        const int j = meta_lo->mixed_off[s] + loc;
+        mixed[j] = id;
         if (h >= 0) tab_mixed.row[h] = loc;
-        table_insert(tab_local, bits(), (uint32_t)id, i, &meta_lo->error);
+        const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)i, &meta_lo->error);
+        ent_local[i] = hl;
+        mixed_ent[j] = hl;
     }
     // the count pass also clears the local-frontier table (idle until the scatter pass)
     __device__ int64_t n_side() const { return 1ll << bits(); }
-    __device__ void side(int64_t x) const { table_reset_entry(tab_local, x); }
+    __device__ void side(int64_t x) const { tab_local.slot[x] = EMPTY_ENTRY; }
 };
 
 // ---- partition B: next local frontiers = own destination vertices, then first occurrences of
@@ -440,16 +466,20 @@ struct PartLocal {
     static constexpr int NK = GS_MAXS;
     GsTable tab_local, tab_mixed;
     const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
-    const int32_t *nbr; const int32_t *cnt; const int32_t *blk_indptr; int32_t *blk_src;
+    const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls;
+    const int32_t *blk_indptr; int32_t *blk_src;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next;
     __device__ int n1() const { return meta_up->front_off[S]; }
-    __device__ int bits() const { return table_bits(n1() * (1 + fan)); }
     __device__ int n() const { return meta_lo->recv_off[S]; }
     __device__ unsigned classify(int r) const {
-        const int h = table_find(tab_local, bits(), (uint32_t)recv[r], &meta_lo->error);
-        if (h < 0 || tab_local.pos[h] != n1() + r) return 0u;
-        return 1u << split_of(meta_lo->recv_off, S, r);
+        const int h = ent_local[n1() + r];
+        unsigned m = 0u;
+        if (h >= 0 && (uint32_t)tab_local.slot[h] == (uint32_t)(n1() + r))
+            m = 1u << split_of(meta_lo->recv_off, S, r);
+        cls[r] = m;
+        return m;
     }
+    __device__ unsigned cached(int r) const { return cls[r]; }
     __device__ void key_bases(const int *tot, int *bases) const {
         int acc = 0;
         for (int t = 0; t < GS_MAXS; ++t) {
@@ -463,9 +493,8 @@ struct PartLocal {
     __device__ void emit(int r, unsigned m, const int *rk) const {
         if (!m) return;
         const int t = __ffs(m) - 1;
-        const int h = table_find(tab_local, bits(), (uint32_t)recv[r], &meta_lo->error);
         front_lo[rk[t]] = recv[r];
-        if (h >= 0) tab_local.row[h] = rk[t];
+        tab_local.row[ent_local[n1() + r]] = rk[t];
     }
     // scatter pass extras: destination vertices keep their order at the head of their owner's
     // frontier; then the mixed-frontier table is cleared for the next sampling layer
@@ -473,58 +502,58 @@ struct PartLocal {
         return n1() + (fan_next > 0 ? (1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next))) : 0);
     }
     __device__ void extra(int64_t x) const {
-        if (x >= n1()) { table_reset_entry(tab_mixed, x - n1()); return; }
+        if (x >= n1()) { tab_mixed.slot[x - n1()] = EMPTY_ENTRY; return; }
         const int i = (int)x;
         const int t = split_of(meta_up->front_off, S, i);
         const int rowp = meta_lo->front_off[t] + (i - meta_up->front_off[t]);
-        const int32_t id = front_up[i];
-        const int h = table_find(tab_local, bits(), (uint32_t)id, &meta_lo->error);
-        front_lo[rowp] = id;
+        front_lo[rowp] = front_up[i];
+        const int h = ent_local[i];
         if (h >= 0) tab_local.row[h] = rowp;
     }
     // count pass extras: edges[l] rewritten to rows of the owning split's mixed frontier
     __device__ int64_t n_side() const { return (int64_t)n1() * fan; }
     __device__ void side(int64_t g) const {
+        const int h = ent_mixed[n1() + g];
+        if (h < 0) return;
         const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
-        if (q >= cnt[i]) return;
-        const int s = split_of(meta_up->front_off, S, i);
-        const int h = table_find(tab_mixed, bits(), (uint32_t)nbr[g] * (uint32_t)S + (uint32_t)s, &meta_lo->error);
-        blk_src[blk_indptr[i] + q] = h >= 0 ? tab_mixed.row[h] : -1;
+        blk_src[blk_indptr[i] + q] = tab_mixed.row[h];
     }
 };
 
 // shuffle index of every mixed-frontier row, and the same lookup composed with edges[l] for the
 // on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge)
-__global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab, const int32_t *__restrict__ mixed,
-                                                       const int32_t *__restrict__ front_up,
-                                                       const int32_t *__restrict__ nbr,
-                                                       const int32_t *__restrict__ cnt,
+__global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTable tab_mixed,
+                                                       const int32_t *__restrict__ ent_mixed,
+                                                       const int32_t *__restrict__ ent_local,
+                                                       const int32_t *__restrict__ mixed_ent,
                                                        const int32_t *__restrict__ blk_indptr,
                                                        int32_t *__restrict__ src_row,
                                                        int32_t *__restrict__ self_row,
                                                        int32_t *__restrict__ edge_row,
-                                                       GsLevelMeta *meta_lo, const GsLevelMeta *meta_up,
+                                                       const GsLevelMeta *__restrict__ meta_lo,
+                                                       const GsLevelMeta *__restrict__ meta_up,
                                                        int S, int fan) {
     const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
     const int64_t n_mixed = meta_lo->mixed_off[S];
     const int64_t n_slots = (int64_t)n1 * fan;
     const int64_t total = n_mixed + n1 + n_slots;
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
         if (x < n_mixed) {
-            const int h = table_find(tab, bits, (uint32_t)mixed[x], &meta_lo->error);
-            src_row[x] = h >= 0 ? tab.row[h] : -1;
+            const int h = mixed_ent[x];
+            src_row[x] = h >= 0 ? tab_local.row[h] : -1;
         } else if (x < n_mixed + n1) {
             const int i = (int)(x - n_mixed);
-            const int h = table_find(tab, bits, (uint32_t)front_up[i], &meta_lo->error);
-            self_row[i] = h >= 0 ? tab.row[h] : -1;
+            const int h = ent_local[i];
+            self_row[i] = h >= 0 ? tab_local.row[h] : -1;
         } else {
             const int64_t g = x - n_mixed - n1;
+            const int h = ent_mixed[n1 + g];
+            if (h < 0) continue;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
-            if (q >= cnt[i]) continue;
-            const int h = table_find(tab, bits, (uint32_t)nbr[g], &meta_lo->error);
-            edge_row[blk_indptr[i] + q] = h >= 0 ? tab.row[h] : -1;
+            const int s = split_of(meta_up->front_off, S, i);
+            const int hl = mixed_ent[meta_lo->mixed_off[s] + tab_mixed.row[h]];
+            edge_row[blk_indptr[i] + q] = hl >= 0 ? tab_local.row[hl] : -1;
         }
     }
 }
@@ -541,7 +570,12 @@ template <class F>
 void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t st) {
     const int nb = part_blocks(upper_items);
     hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
-    hipLaunchKernelGGL(k_part_scan<F>, dim3(1), dim3(PART_BS), 0, st, f, nb, ctx->part_hist, ctx->part_base);
+    if (nb == 256)
+        hipLaunchKernelGGL((k_part_scan<F, 1>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
+    else if (nb == 512)
+        hipLaunchKernelGGL((k_part_scan<F, 2>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
+    else
+        hipLaunchKernelGGL((k_part_scan<F, 4>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
     hipLaunchKernelGGL(k_part_scatter<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_base);
 }
 
@@ -563,15 +597,15 @@ void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStre
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
     } else if (fan <= 32) {
         hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
     } else {
         hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
     }
 }
 
@@ -608,15 +642,17 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, st);
         else launch_sample<int32_t>(ctx, l, seed, iter, st);
 
-        PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, B.cnt,
-                            ctx->graph.d_pmap, B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
+        PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
+                            ctx->ent_mixed, ctx->cls, ctx->ent_local, ctx->mixed_ent,
+                            B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
         run_partition(ctx, pa, ub1 * fan, st);
         PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
-                     B.nbr, B.cnt, B.blk_indptr, B.blk_src, ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
+                     ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src,
+                     ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
         run_partition(ctx, pl, ub1 * fan, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
-                           ctx->tab_local, B.mixed, ctx->front[l + 1], B.nbr, B.cnt, B.blk_indptr,
-                           B.src_row, B.self_row, B.edge_row, ml, mu, S, fan);
+                           ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
+                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, ml, mu, S, fan);
     }
     GS_HIP(ctx, hipGetLastError());
     GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
