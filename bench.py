@@ -2,8 +2,8 @@
 """Benchmark of the split-parallel hot path on one MI355X.
 
 One step = one whole iteration over a fresh synthetic mini-batch, all inputs resident in HBM:
-gsplit_sample_split -> gsplit_gather_features -> gsplit_sage_fwd -> softmax cross-entropy
-gradient of the logits (harness, torch) -> gsplit_sage_bwd.  Prints ONE JSON line.
+gsplit_sample_split -> gsplit_gather_features -> gsplit_sage_fwd -> gsplit_softmax_xent (loss
+gradient of the logits) -> gsplit_sage_bwd.  Prints ONE JSON line.
 
 The workload is the "medium" configuration (2.4M-vertex / ~124M-edge R-MAT graph, 100-d fp32
 features, 47 classes, range partition map, 4 logical splits, batch 1024, fanouts [15,10,5],
@@ -49,22 +49,13 @@ class Runner:
         self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias)
         self.x0 = torch.empty((self.ctx.gsplit_max_rows(0), w.dims[0]), dtype=w.feat.dtype, device=dev)
         self.logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+        self.glogits = torch.empty_like(self.logits)
         self.gws = [torch.empty_like(t) for t in w.w_self]
         self.gwn = [torch.empty_like(t) for t in w.w_neigh]
         self.gb = [torch.empty_like(t) for t in w.bias]
         self.seed = 0xC0FFEE
 
-    def loss_grad(self, targets):
-        """Harness-side loss: mean softmax cross-entropy; returns d loss / d logits."""
-        torch = self.torch
-        ids = self._front_top                     # local_cat[L]: targets grouped by split
-        y = self.w.labels[ids.long()]
-        p = torch.softmax(self.logits, dim=1)
-        p[torch.arange(p.shape[0], device=self.dev), y] -= 1.0
-        return (p / p.shape[0]).contiguous()
-
     def step(self, targets, it, events=None):
-        torch = self.torch
         c = self.ctx
         rec = (lambda k: events[k].record()) if events is not None else (lambda k: None)
         rec(0)
@@ -74,30 +65,10 @@ class Runner:
         rec(2)
         c.gsplit_sage_fwd(self.params, self.x0, self.logits)
         rec(3)
-        # rows of the logits follow local_cat[L]; fetch those ids on the device (no host sync)
-        self._front_top = self._top_ids(targets.numel())
-        g = self.loss_grad(targets)
+        c.gsplit_softmax_xent(self.logits, self.w.labels, self.glogits)
         rec(4)
-        c.gsplit_sage_bwd(self.params, g, self.gws, self.gwn, self.gb)
+        c.gsplit_sage_bwd(self.params, self.glogits, self.gws, self.gwn, self.gb)
         rec(5)
-
-    def _top_ids(self, n):
-        # device-to-device copy of local_cat[L] into a torch tensor
-        import ctypes as C
-        from paper_2303_13775_amd.binding import _hip_runtime
-        torch = self.torch
-        if not hasattr(self, "_top_buf"):
-            self._top_buf = torch.empty(self.w.batch, dtype=torch.int32, device=self.dev)
-            hip = _hip_runtime()
-            hip.hipMemcpyAsync.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
-            hip.hipMemcpyAsync.restype = C.c_int
-            self._hip = hip
-        v = self.ctx.gsplit_batch_level(self.ctx.L)
-        rc = self._hip.hipMemcpyAsync(C.c_void_p(self._top_buf.data_ptr()), C.c_void_p(v.d_local_cat),
-                                      C.c_size_t(4 * n), 3,
-                                      C.c_void_p(torch.cuda.current_stream().cuda_stream))
-        assert rc == 0
-        return self._top_buf[:n]
 
 
 def cpu_baseline(w_host, iters):

@@ -176,6 +176,17 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
 
+/* Loss between forward and backward.  The paper only says that the target features "are used to
+ * calculate the loss" (section 2); this is the usual choice for node classification: mean softmax
+ * cross-entropy over the targets.  Row r of d_logits / d_grad_logits belongs to local_cat[L][r];
+ * its label is d_labels[that vertex id] (int64, one entry per graph vertex, values in
+ * [0, n_classes)).  d_grad_logits [n_targets x n_classes] receives d loss / d logits;
+ * d_row_loss (may be NULL) [n_targets] receives the per-target loss terms, whose mean is the loss.
+ * Asynchronous. */
+GSPLIT_API int gsplit_softmax_xent(gsplit_ctx *ctx, const float *d_logits, int32_t n_classes,
+                                   const int64_t *d_labels, float *d_grad_logits, float *d_row_loss,
+                                   void *stream);
+
 #ifdef __cplusplus
 }
 #endif

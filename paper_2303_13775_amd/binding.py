@@ -22,7 +22,7 @@ MAX_SPLITS = 8
 EXPORTS = [
     "gsplit_create", "gsplit_destroy", "gsplit_last_error", "gsplit_max_rows", "gsplit_sample_split",
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
-    "gsplit_sage_fwd", "gsplit_sage_bwd",
+    "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent",
 ]
 
 
@@ -83,6 +83,7 @@ def load_library():
     L.gsplit_sage_fwd.argtypes = [vp, C.POINTER(_SageParams), vp, vp, vp]
     L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
                                   C.POINTER(vp), vp]
+    L.gsplit_softmax_xent.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("gsplit_last_error", "gsplit_max_rows"):
             getattr(L, name).restype = C.c_int
@@ -251,6 +252,19 @@ class Context:
         c = (C.c_void_p * L)(*[t.data_ptr() for t in gbias])
         self._check(self.lib.gsplit_sage_bwd(self.h, C.byref(params.c), grad_logits.data_ptr(), a, b, c,
                                              _stream()))
+
+    def gsplit_softmax_xent(self, logits: torch.Tensor, labels: torch.Tensor, grad_logits: torch.Tensor,
+                            row_loss: Optional[torch.Tensor] = None):
+        assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+        assert labels.is_cuda and labels.dtype == torch.int64 and labels.numel() == self.n_vertices
+        assert grad_logits.is_cuda and grad_logits.dtype == torch.float32 and grad_logits.is_contiguous()
+        assert grad_logits.shape == logits.shape
+        if row_loss is not None:
+            assert row_loss.is_cuda and row_loss.dtype == torch.float32 and row_loss.numel() >= logits.shape[0]
+        self._check(self.lib.gsplit_softmax_xent(self.h, logits.data_ptr(), logits.shape[1], labels.data_ptr(),
+                                                 grad_logits.data_ptr(),
+                                                 row_loss.data_ptr() if row_loss is not None else None,
+                                                 _stream()))
 
     # -- inspection helpers for tests (copies of the device views; they synchronise) -------
     def fetch_batch(self) -> dict:

@@ -105,6 +105,12 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         A((void **)&B.src_row, sizeof(int32_t) * nd * (1 + f), "src_row");
         A((void **)&B.self_row, sizeof(int32_t) * nd, "self_row");
         A((void **)&B.edge_row, sizeof(int32_t) * nd * f, "edge_row");
+        if (l > 0) {
+            A((void **)&B.rev_cnt, sizeof(int32_t) * ctx->ub_front[l], "rev_cnt");
+            A((void **)&B.rev_ptr, sizeof(int32_t) * ctx->ub_front[l], "rev_ptr");
+            A((void **)&B.rev_fill, sizeof(int32_t) * ctx->ub_front[l], "rev_fill");
+            A((void **)&B.rev_list, sizeof(int32_t) * nd * (1 + f), "rev_list");
+        }
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
     for (GsTable *t : {&ctx->tab_local, &ctx->tab_mixed}) {

@@ -28,7 +28,8 @@ struct GsLevelMeta {
     int32_t bucket_start[GS_MAXS * GS_MAXS];
     int32_t nnz;
     int32_t error;      // set non-zero by a kernel that hit an impossible state (probe overflow)
-    int32_t pad[2];
+    int32_t rev_cursor; // allocation cursor of the reverse (scatter) index
+    int32_t pad[1];
 };
 
 // Open-addressing table in HBM: entry = key << 32 | smallest position seen; row = final row.
@@ -47,6 +48,12 @@ struct GsLayerBuf {            // sampling layer l
     int32_t *src_row = nullptr;    // [ub_dst * (1 + fan)]
     int32_t *self_row = nullptr;   // [ub_dst]        row of local_cat[l] of each destination vertex
     int32_t *edge_row = nullptr;   // [ub_dst * fan]  row of local_cat[l] of each edge's source
+    // reverse (scatter) index for the backward pass, layers l >= 1 only: for every row u of
+    // local_cat[l] the destination rows whose input it feeds, as 2 * i (self) or 2 * i + 1 (edge)
+    int32_t *rev_cnt = nullptr;    // [ub_front[l]]
+    int32_t *rev_ptr = nullptr;    // [ub_front[l]]
+    int32_t *rev_fill = nullptr;   // [ub_front[l]]
+    int32_t *rev_list = nullptr;   // [ub_dst * (1 + fan)]
 };
 
 struct GsSageBuf {             // activations kept between forward and backward
@@ -56,7 +63,7 @@ struct GsSageBuf {             // activations kept between forward and backward
     void    *hidden[GS_MAXL + 1] = {nullptr};   // local_cat activations of level 1..L-1
     void    *xin[GS_MAXL] = {nullptr};          // assembled layer inputs [rows x 2*dims[l]]: self | mean
     float   *ghid[GS_MAXL + 1] = {nullptr};     // d loss / d hidden of level 1..L
-    float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before scatter
+    float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before the reverse shuffle
     void    *wcat[GS_MAXL] = {nullptr};         // stacked [W_self; W_neigh] per layer
     bool     fwd_done = false;
     uint64_t fwd_batch = 0;

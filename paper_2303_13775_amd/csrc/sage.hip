@@ -280,18 +280,17 @@ struct EpiGradW {
         else atomicAdd(&gb[n], v);
     }
 };
-// input gradients: the self part goes to the destination's own lower-layer row, the mean part is
-// spread over the row's sampled sources (adjoint of the mean), both through the composed
-// shuffle index -- the reverse shuffle of the backward pass.
+// input gradients per destination row: [dH_self | dMean / cnt]; the reverse shuffle (pull through
+// the scatter side of the shuffle index) follows in k_pull_input_grad
 struct EpiGradIn {
-    float *g; const int32_t *self_row; const int32_t *edge_row; const int32_t *blk_indptr; int D; int n1;
+    float *out; const int32_t *blk_indptr; int D; int n1;
     __device__ __forceinline__ void operator()(int i, int j, float v) const {
         if (i >= n1 || j >= 2 * D) return;
-        if (j < D) { atomicAdd(&g[(int64_t)self_row[i] * D + j], v); return; }
-        const int e0 = blk_indptr[i], e1 = blk_indptr[i + 1];
-        if (e1 == e0) return;
-        const float w = v / (float)(e1 - e0);
-        for (int e = e0; e < e1; ++e) atomicAdd(&g[(int64_t)edge_row[e] * D + (j - D)], w);
+        if (j >= D) {
+            const int c = blk_indptr[i + 1] - blk_indptr[i];
+            v = c > 0 ? v / (float)c : 0.f;
+        }
+        out[(int64_t)i * 2 * D + j] = v;
     }
 };
 
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(256) void k_sage_grad_w(MatRowsOnes a, MatRows dz, 
                                               k_begin, k_end, a, dz, epi);
 }
 
-// [dH_self | dMean] = dZ * [W_self; W_neigh]^T, scattered through the shuffle index
+// [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row
 template <int VA, int VB>
 __global__ __launch_bounds__(256) void k_sage_grad_in(MatRows dz, CatW w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
@@ -332,22 +331,100 @@ __global__ __launch_bounds__(256) void k_sage_grad_in(MatRows dz, CatW w, EpiGra
     gemm_tile<GBM, GBN, true, true, VA, VB>(m0, blockIdx.y * GBN, n1, 2 * w.D, 0, dz.cols, dz, w, epi);
 }
 
-// dZ = dH' where the forward output was positive, else 0 (in place)
-__global__ __launch_bounds__(256) void k_relu_mask(float *__restrict__ g, const float *__restrict__ hout,
-                                                   const GsLevelMeta *__restrict__ meta, int S, int width) {
-    const int64_t n = (int64_t)meta->front_off[S] * width;
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n;
-         x += (int64_t)gridDim.x * blockDim.x)
-        if (!(hout[x] > 0.f)) g[x] = 0.f;
+// Reverse shuffle of the backward pass as a pull: row u of local_cat[l] sums the gradient rows of
+// every destination it fed (its own self term and one mean term per sampled edge), listed by the
+// scatter side of the shuffle index.  The ReLU of the layer below is applied on the way out, so
+// the result is that layer's dZ.  One lane group per row, 4 floats per lane; no atomics, and rows
+// that fed nothing get zeros.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict__ gin, int D,
+                                                         const int32_t *__restrict__ rev_ptr,
+                                                         const int32_t *__restrict__ rev_cnt,
+                                                         const int32_t *__restrict__ rev_list,
+                                                         const float *__restrict__ hact,
+                                                         const GsLevelMeta *__restrict__ meta_lo, int S,
+                                                         float *__restrict__ gout) {
+    const int n_lo = meta_lo->front_off[S];
+    const int nvec = D >> 2;
+    const int c0 = threadIdx.x % LPR;
+    const int groups = (gridDim.x * blockDim.x) / LPR;
+    const float4 *G4 = reinterpret_cast<const float4 *>(gin);
+    const float4 *A4 = reinterpret_cast<const float4 *>(hact);
+    float4 *O4 = reinterpret_cast<float4 *>(gout);
+    for (int u = (blockIdx.x * blockDim.x + threadIdx.x) / LPR; u < n_lo; u += groups) {
+        const int e0 = rev_ptr[u], e1 = e0 + rev_cnt[u];
+        for (int c = c0; c < nvec; c += LPR) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            int e = e0;
+            for (; e + 2 <= e1; e += 2) {
+                const int k0 = rev_list[e], k1 = rev_list[e + 1];
+                const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
+                const float4 b = G4[(int64_t)(k1 >> 1) * 2 * nvec + (k1 & 1) * nvec + c];
+                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
+                acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+            }
+            if (e < e1) {
+                const int k0 = rev_list[e];
+                const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
+                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
+            }
+            const float4 h = A4[(int64_t)u * nvec + c];
+            acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
+            acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
+            O4[(int64_t)u * nvec + c] = acc;
+        }
+    }
 }
 
-// zero `count_rows(meta) * width` floats, or a fixed number when meta == nullptr
-__global__ __launch_bounds__(256) void k_fill_zero(float *__restrict__ p, int64_t fixed_n,
-                                                   const GsLevelMeta *__restrict__ meta, int S, int width) {
-    const int64_t n = meta ? (int64_t)meta->front_off[S] * width : fixed_n;
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n;
-         x += (int64_t)gridDim.x * blockDim.x)
-        p[x] = 0.f;
+__global__ __launch_bounds__(256) void k_pull_input_grad_any(const float *__restrict__ gin, int D,
+                                                             const int32_t *__restrict__ rev_ptr,
+                                                             const int32_t *__restrict__ rev_cnt,
+                                                             const int32_t *__restrict__ rev_list,
+                                                             const float *__restrict__ hact,
+                                                             const GsLevelMeta *__restrict__ meta_lo, int S,
+                                                             float *__restrict__ gout) {
+    const int n_lo = meta_lo->front_off[S];
+    const int lane = threadIdx.x & 63;
+    const int waves = (gridDim.x * blockDim.x) >> 6;
+    for (int u = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; u < n_lo; u += waves) {
+        const int e0 = rev_ptr[u], e1 = e0 + rev_cnt[u];
+        for (int c = lane; c < D; c += 64) {
+            float acc = 0.f;
+            for (int e = e0; e < e1; ++e) {
+                const int k = rev_list[e];
+                acc += gin[(int64_t)(k >> 1) * 2 * D + (k & 1) * D + c];
+            }
+            gout[(int64_t)u * D + c] = hact[(int64_t)u * D + c] > 0.f ? acc : 0.f;
+        }
+    }
+}
+
+// Mean softmax cross-entropy of the target rows and its gradient w.r.t. the logits: one wave per
+// target; the label of row r is labels[local_cat[L][r]].
+__global__ __launch_bounds__(256) void k_softmax_xent(const float *__restrict__ logits, int C,
+                                                      const int64_t *__restrict__ labels,
+                                                      const int32_t *__restrict__ front_top,
+                                                      const GsLevelMeta *__restrict__ meta_top, int S,
+                                                      float *__restrict__ grad, float *__restrict__ row_loss) {
+    const int n = meta_top->front_off[S];
+    const int lane = threadIdx.x & 63;
+    const int waves = (gridDim.x * blockDim.x) >> 6;
+    for (int r = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; r < n; r += waves) {
+        const float *z = logits + (int64_t)r * C;
+        float mx = -3.4e38f;
+        for (int c = lane; c < C; c += 64) mx = fmaxf(mx, z[c]);
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+        for (int c = lane; c < C; c += 64) sum += __expf(z[c] - mx);
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        const int y = (int)labels[front_top[r]];
+        const float inv = 1.f / sum, invn = 1.f / (float)n;
+        for (int c = lane; c < C; c += 64) {
+            const float p = __expf(z[c] - mx) * inv;
+            grad[(int64_t)r * C + c] = (p - (c == y ? 1.f : 0.f)) * invn;
+        }
+        if (row_loss && lane == 0) row_loss[r] = (y >= 0 && y < C) ? (logf(sum) + mx - z[y]) : 0.f;
+    }
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -385,6 +462,12 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
     }
     for (int l = 0; l < L; ++l) {
         int rc = gs_alloc(ctx, &sb.xin[l], sizeof(float) * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
+        if (rc) return rc;
+    }
+    int64_t gtmp_words = 1;
+    for (int l = 1; l < L; ++l) gtmp_words = std::max<int64_t>(gtmp_words, ctx->ub_front[l + 1] * 2 * p->dims[l]);
+    {
+        int rc = gs_alloc(ctx, (void **)&sb.gtmp, sizeof(float) * gtmp_words, "input gradients");
         if (rc) return rc;
     }
     sb.dtype = p->dtype;
@@ -501,11 +584,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const GsLayerBuf &B = ctx->layer[l];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
         const float *dH = l == L - 1 ? d_grad_logits : sb.ghid[l + 1];
-        const float *hout = l == L - 1 ? nullptr : (const float *)sb.hidden[l + 1];
         const int64_t ub = ctx->ub_front[l + 1];
-        if (l < L - 1)   // dZ = dH' masked by the ReLU of the forward pass, in place
-            hipLaunchKernelGGL(k_relu_mask, dim3(grid_1d(ctx, ub * N)), dim3(256), 0, st, sb.ghid[l + 1], hout,
-                               mu, S, N);
         MatRows dz{dH, 0, N};
         // weight and bias gradients, summed over all splits: [X | 1]^T dZ with the layer input X
         // assembled by the forward pass
@@ -525,17 +604,46 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         }
         if (l > 0) {
             const GsLevelMeta *ml = ctx->d_meta + l;
-            hipLaunchKernelGGL(k_fill_zero, dim3(grid_1d(ctx, ctx->ub_front[l] * D)), dim3(256), 0, st,
-                               sb.ghid[l], 0, ml, S, D);
             CatW w{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
-            EpiGradIn ei{sb.ghid[l], B.self_row, B.edge_row, B.blk_indptr, D, 0};
+            EpiGradIn ei{sb.gtmp, B.blk_indptr, D, 0};
             dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
             if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            // reverse shuffle + ReLU of the layer below: dZ of layer l-1
+            const float *hact = (const float *)sb.hidden[l];
+            const int64_t ubl = ctx->ub_front[l];
+            if (D % 4 != 0) {
+                hipLaunchKernelGGL(k_pull_input_grad_any, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+            } else if (D / 4 <= 16) {
+                hipLaunchKernelGGL(k_pull_input_grad<16>, dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+            } else if (D / 4 <= 32) {
+                hipLaunchKernelGGL(k_pull_input_grad<32>, dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+            } else {
+                hipLaunchKernelGGL(k_pull_input_grad<64>, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+            }
         }
     }
+    GS_HIP(ctx, hipGetLastError());
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_softmax_xent(gsplit_ctx *ctx, const float *d_logits, int32_t n_classes,
+                                   const int64_t *d_labels, float *d_grad_logits, float *d_row_loss,
+                                   void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    if (!d_logits || !d_labels || !d_grad_logits || n_classes < 1)
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_softmax_xent: bad argument");
+    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_softmax_xent: no batch");
+    hipStream_t st = (hipStream_t)stream;
+    const int L = ctx->L;
+    hipLaunchKernelGGL(k_softmax_xent, dim3(grid_1d(ctx, ctx->ub_front[L] * 64)), dim3(256), 0, st, d_logits,
+                       n_classes, d_labels, ctx->front[L], ctx->d_meta + L, ctx->S, d_grad_logits, d_row_loss);
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;
 }

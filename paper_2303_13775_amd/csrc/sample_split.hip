@@ -14,6 +14,8 @@
 //   6 partition B: scan         (next local-frontier offsets)
 //   7 partition B: scatter      next local frontiers + reset tab_mixed for the next layer
 //   8 shuffle index (+ its composition with edges[l] for the forward/backward passes)
+//   9-10 (layers above the bottom one) the scatter side of the shuffle index: for every row of
+//        local_cat[l], the destination rows it feeds, so that the backward pass can pull
 // A dependent HBM access costs about a microsecond, and these kernels are chains of them, so every
 // element remembers the table entry it landed in (no second probe sequence) and the count passes
 // leave their classification behind for the scatter passes.
@@ -467,7 +469,7 @@ struct PartLocal {
     GsTable tab_local, tab_mixed;
     const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
     const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls;
-    const int32_t *blk_indptr; int32_t *blk_src;
+    const int32_t *blk_indptr; int32_t *blk_src; int32_t *rev_cnt;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return meta_lo->recv_off[S]; }
@@ -497,12 +499,25 @@ struct PartLocal {
         tab_local.row[ent_local[n1() + r]] = rk[t];
     }
     // scatter pass extras: destination vertices keep their order at the head of their owner's
-    // frontier; then the mixed-frontier table is cleared for the next sampling layer
+    // frontier; then (layers above the bottom one) the mixed-frontier table is cleared for the
+    // next sampling layer and the counters of this layer's reverse index are zeroed
+    __device__ int64_t n_reset() const {
+        return fan_next > 0 ? (1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next))) : 0;
+    }
     __device__ int64_t n_extra() const {
-        return n1() + (fan_next > 0 ? (1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next))) : 0);
+        return n1() + n_reset() + (fan_next > 0 ? meta_lo->front_off[S] : 0);
     }
     __device__ void extra(int64_t x) const {
-        if (x >= n1()) { tab_mixed.slot[x - n1()] = EMPTY_ENTRY; return; }
+        if (x >= n1()) {
+            const int64_t y = x - n1(), nr = n_reset();
+            if (y < nr) {
+                tab_mixed.slot[y] = EMPTY_ENTRY;
+                if (y == 0) meta_lo->rev_cursor = 0;
+            } else {
+                rev_cnt[y - nr] = 0;
+            }
+            return;
+        }
         const int i = (int)x;
         const int t = split_of(meta_up->front_off, S, i);
         const int rowp = meta_lo->front_off[t] + (i - meta_up->front_off[t]);
@@ -530,6 +545,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
                                                        int32_t *__restrict__ src_row,
                                                        int32_t *__restrict__ self_row,
                                                        int32_t *__restrict__ edge_row,
+                                                       int32_t *__restrict__ rev_cnt,
                                                        const GsLevelMeta *__restrict__ meta_lo,
                                                        const GsLevelMeta *__restrict__ meta_up,
                                                        int S, int fan) {
@@ -545,7 +561,9 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
         } else if (x < n_mixed + n1) {
             const int i = (int)(x - n_mixed);
             const int h = ent_local[i];
-            self_row[i] = h >= 0 ? tab_local.row[h] : -1;
+            const int r = h >= 0 ? tab_local.row[h] : -1;
+            self_row[i] = r;
+            if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
         } else {
             const int64_t g = x - n_mixed - n1;
             const int h = ent_mixed[n1 + g];
@@ -553,8 +571,68 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
             const int s = split_of(meta_up->front_off, S, i);
             const int hl = mixed_ent[meta_lo->mixed_off[s] + tab_mixed.row[h]];
-            edge_row[blk_indptr[i] + q] = hl >= 0 ? tab_local.row[hl] : -1;
+            const int r = hl >= 0 ? tab_local.row[hl] : -1;
+            edge_row[blk_indptr[i] + q] = r;
+            if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
         }
+    }
+}
+
+// reverse index, step 2: give every row of local_cat[l] a segment of rev_list (segments need not
+// be in row order: one atomic per wave hands out space)
+__global__ __launch_bounds__(256) void k_rev_alloc(const int32_t *__restrict__ rev_cnt,
+                                                   int32_t *__restrict__ rev_ptr,
+                                                   int32_t *__restrict__ rev_fill,
+                                                   GsLevelMeta *meta_lo, int S) {
+    const int n_lo = meta_lo->front_off[S];
+    const int lane = lane_id();
+    const int stride = gridDim.x * blockDim.x;
+    const int rounds = (n_lo + stride - 1) / stride;
+    for (int it = 0; it < rounds; ++it) {
+        const int u = it * stride + blockIdx.x * blockDim.x + threadIdx.x;
+        const int c = u < n_lo ? rev_cnt[u] : 0;
+        int inc = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            int up = __shfl_up(inc, o);
+            if (lane >= o) inc += up;
+        }
+        int base = 0;
+        if (lane == 63 && inc > 0) base = atomicAdd(&meta_lo->rev_cursor, inc);
+        base = __shfl(base, 63);
+        if (u < n_lo) {
+            rev_ptr[u] = base + inc - c;
+            rev_fill[u] = 0;
+        }
+    }
+}
+
+// reverse index, step 3: list, for every source row, the destination rows it feeds
+__global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ ent_mixed,
+                                                  const int32_t *__restrict__ blk_indptr,
+                                                  const int32_t *__restrict__ self_row,
+                                                  const int32_t *__restrict__ edge_row,
+                                                  const int32_t *__restrict__ rev_ptr,
+                                                  int32_t *__restrict__ rev_fill,
+                                                  int32_t *__restrict__ rev_list,
+                                                  const GsLevelMeta *__restrict__ meta_up, int S, int fan) {
+    const int n1 = meta_up->front_off[S];
+    const int64_t total = (int64_t)n1 * (1 + fan);
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
+         x += (int64_t)gridDim.x * blockDim.x) {
+        int u, code;
+        if (x < n1) {
+            u = self_row[x];
+            code = 2 * (int)x;
+        } else {
+            const int64_t g = x - n1;
+            if (ent_mixed[n1 + g] < 0) continue;
+            const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+            u = edge_row[blk_indptr[i] + q];
+            code = 2 * i + 1;
+        }
+        if (u < 0) continue;
+        const int p = atomicAdd(&rev_fill[u], 1);
+        rev_list[rev_ptr[u] + p] = code;
     }
 }
 
@@ -647,12 +725,20 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
                             B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
         run_partition(ctx, pa, ub1 * fan, st);
         PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
-                     ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src,
+                     ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src, B.rev_cnt,
                      ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
         run_partition(ctx, pl, ub1 * fan, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
-                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, ml, mu, S, fan);
+                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, l > 0 ? B.rev_cnt : nullptr,
+                           ml, mu, S, fan);
+        if (l > 0) {
+            hipLaunchKernelGGL(k_rev_alloc, dim3(grid_for(ctx, ctx->ub_front[l])), dim3(256), 0, st,
+                               B.rev_cnt, B.rev_ptr, B.rev_fill, ml, S);
+            hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
+                               ctx->ent_mixed, B.blk_indptr, B.self_row, B.edge_row, B.rev_ptr, B.rev_fill,
+                               B.rev_list, mu, S, fan);
+        }
     }
     GS_HIP(ctx, hipGetLastError());
     GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));

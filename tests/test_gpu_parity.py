@@ -221,6 +221,25 @@ def test_sage_forward_backward_within_tolerance(name):
         assert R.max_rel_err(r["gb"][l], r["ob"].gbias[l]) < TOL_F32, ("gbias", l)
 
 
+def test_softmax_xent_matches_oracle():
+    dev = _dev()
+    w = workloads.custom(6000, 150000, dims=[16, 16, 47], fanouts=[4, 3], batch=333, n_splits=4, name="loss")
+    ctx = _ctx(w, dev)
+    tg = w.targets(1)
+    ctx.gsplit_sample_split(tg.to(dev), 8, 1)
+    ob = _oracle_batch(w, tg, 8, 1)
+    rng = np.random.default_rng(5)
+    logits = (rng.standard_normal((tg.numel(), 47)) * 3).astype(np.float32)
+    g = torch.empty((tg.numel(), 47), device=dev)
+    rl = torch.empty(tg.numel(), device=dev)
+    ctx.gsplit_softmax_xent(torch.from_numpy(logits).to(dev), w.labels.to(dev), g, rl)
+    y = w.labels.numpy()[tg.numpy()[ob.target_perm]]
+    loss, want = R.softmax_xent(logits.astype(np.float64), y)
+    assert R.max_rel_err(g.cpu().numpy(), want) < TOL_F32
+    assert abs(float(rl.mean()) - loss) < 1e-5 * max(1.0, abs(loss))
+    ctx.close()
+
+
 def test_split_equals_unsplit_on_gpu():
     dev = _dev()
     w = workloads.tiny()
