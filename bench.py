@@ -32,7 +32,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="medium", choices=["medium", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-iters", type=int, default=3)
+    ap.add_argument("--cpu-iters", type=int, default=60)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
     return ap.parse_args()
 
@@ -130,7 +132,6 @@ def main():
     # per-stage device times (separate instrumented pass; events on the stream the kernels run on)
     n_st = min(a.stage_iters, a.steps)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_st)]
-    sizes = None
     for i in range(n_st):
         r.step(targets[a.warmup + i], a.warmup + i, ev[i])
     torch.cuda.synchronize()
@@ -138,24 +139,66 @@ def main():
     stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / max(n_st, 1)
                 for k, nm in enumerate(names)}
 
-    # gather roofline: algorithmic bytes = rows * (2 * row_bytes + 4) per launch, measured alone
-    # on the last batch with events around the single-kernel entry point
-    n_local, n_mixed, n_edges, bucket = r.ctx.gsplit_batch_sizes()
-    rows0 = sum(n_local[0])
+    # per-kernel device times: the library brackets each of its launches with HIP events on the
+    # launch stream; algorithmic bytes / flops are summed over the very same iterations
+    L, S = w.n_layers, w.n_splits
     row_bytes = w.dims[0] * w.feat.element_size()
-    reps = 50
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    tot = 0.0
-    for _ in range(reps):
-        e0.record()
-        r.ctx.gsplit_gather_features(w.feat, r.x0)
-        e1.record()
-        e1.synchronize()
-        tot += e0.elapsed_time(e1)
-    gather_ms = tot / reps
-    gather_bytes = rows0 * (2 * row_bytes + 4)
-    gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9
+    ip_bytes = w.indptr.element_size()
+    work = {}      # label -> [kind, amount]
 
+    def add(label, kind, amount):
+        work.setdefault(label, [kind, 0.0])[1] += amount
+
+    r.ctx.gsplit_timing_enable(True)
+    n_k = max(1, min(a.stage_iters, a.steps))
+    shape = None
+    for i in range(n_k):
+        r.step(targets[a.warmup + i], a.warmup + i)
+        n_local, n_mixed, n_edges, bucket = r.ctx.gsplit_batch_sizes()     # waits for sampling only
+        rows = [sum(x) for x in n_local]
+        edges = [sum(x) for x in n_edges]
+        mixed = [sum(x) for x in n_mixed]
+        shape = (rows, edges, mixed, bucket)
+        add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
+        for l in range(L):
+            D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
+            add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
+            add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N)
+            if l > 0:
+                add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
+                add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
+            # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
+            add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + 4 * D) + nd * (4 + 4 * D) + nd * 8 * D)
+            # per destination: id + two indptr words read, count written; per edge: 4 read, 4 written,
+            # one 8-byte table entry touched
+            add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes) + edges[l] * 16)
+            slots = nd * w.fanouts[l]
+            add(f"mixed_buckets_count.l{l}", "bytes", slots * (4 + 4 + 8 + 4) + edges[l] * 1)
+            add(f"mixed_buckets_scatter.l{l}", "bytes", slots * 4 + edges[l] * 4 + mixed[l] * (4 + 4 + 4 + 8 + 4))
+    torch.cuda.synchronize()
+    ktimes = r.ctx.gsplit_timing_read()
+    r.ctx.gsplit_timing_enable(False)
+    kernel_us = {k: v[1] / max(v[0], 1) * 1e3 for k, v in ktimes.items()}
+    per_step_us = {k: v[1] / n_k * 1e3 for k, v in ktimes.items()}
+    dominant = max(per_step_us, key=per_step_us.get)
+
+    def roofline_of(label):
+        cnt, ms = ktimes[label]
+        kind, amount = work.get(label, ("bytes", 0.0))
+        per_launch = amount / max(cnt, 1)
+        sec = ms / max(cnt, 1) * 1e-3
+        if kind == "flops":
+            ach = per_launch / sec / 1e12
+            return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                    "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
+        ach = per_launch / sec / 1e9
+        return {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": per_launch,
+                "launch_ms": ms / max(cnt, 1)}
+
+    rows, edges, mixed, bucket = shape
+    gather = roofline_of("gather_rows")
     out = {
         "metric": "mini-batches/sec (sample+split+gather+SAGE fwd/bwd) at 1 GPU",
         "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
@@ -163,17 +206,24 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": dict(w.describe(), fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1)),
-        "gather_GBps": gather_gbs,
+        "gather_GBps": gather["achieved"],
         "stage_ms": stage_ms,
-        "batch_shape": {"rows_per_level": [sum(x) for x in n_local],
-                        "edges_per_layer": [sum(x) for x in n_edges],
-                        "mixed_rows_per_layer": [sum(x) for x in n_mixed],
-                        "ids_shuffled_per_layer": [sum(b[s][t] for s in range(w.n_splits)
-                                                       for t in range(w.n_splits) if s != t) for b in bucket]},
-        "roofline": {"kernel": "k_gather_rows", "bound": "hbm", "achieved": gather_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "bytes_per_launch": gather_bytes, "launch_ms": gather_ms},
+        "kernel_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
+        "batch_shape": {"rows_per_level": rows, "edges_per_layer": edges, "mixed_rows_per_layer": mixed,
+                        "ids_shuffled_per_layer": [sum(b[s][t] for s in range(S) for t in range(S) if s != t)
+                                                   for b in bucket]},
+        "roofline": roofline_of(dominant),
+        "roofline_gather": gather,
     }
+
+    if a.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = {"read": src.numel() * 4, "written": dst.numel() * 4}
+        del src, dst
 
     if not a.no_cpu_baseline:
         host = {"indptr": w.indptr.cpu().numpy(), "indices": w.indices.cpu().numpy(),

@@ -176,6 +176,15 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
 
+/* Diagnostics: per-kernel device time.  While enabled, every kernel the library launches is
+ * bracketed by two events on the stream it runs on (this adds a little host work per launch).
+ * gsplit_timing_read waits for the recorded events, writes one line per kernel label
+ * ("<label> <launches> <total milliseconds>\n", labels carry the layer as ".l<k>") into buf as a
+ * NUL-terminated string, resets the totals, and returns the string length; ECAPACITY if buf_bytes is
+ * too small.  For callers that profile (benchmarks); never needed for results. */
+GSPLIT_API int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable);
+GSPLIT_API int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_bytes);
+
 /* Loss between forward and backward.  The paper only says that the target features "are used to
  * calculate the loss" (section 2); this is the usual choice for node classification: mean softmax
  * cross-entropy over the targets.  Row r of d_logits / d_grad_logits belongs to local_cat[L][r];

@@ -22,7 +22,8 @@ MAX_SPLITS = 8
 EXPORTS = [
     "gsplit_create", "gsplit_destroy", "gsplit_last_error", "gsplit_max_rows", "gsplit_sample_split",
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
-    "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent",
+    "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
+    "gsplit_timing_read",
 ]
 
 
@@ -84,8 +85,11 @@ def load_library():
     L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
                                   C.POINTER(vp), vp]
     L.gsplit_softmax_xent.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.gsplit_timing_enable.argtypes = [vp, i32]
+    L.gsplit_timing_read.argtypes = [vp, C.c_char_p, i64]
+    L.gsplit_timing_read.restype = i64
     for name in EXPORTS:
-        if name not in ("gsplit_last_error", "gsplit_max_rows"):
+        if name not in ("gsplit_last_error", "gsplit_max_rows", "gsplit_timing_read"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -265,6 +269,21 @@ class Context:
                                                  grad_logits.data_ptr(),
                                                  row_loss.data_ptr() if row_loss is not None else None,
                                                  _stream()))
+
+    def gsplit_timing_enable(self, enable: bool):
+        self._check(self.lib.gsplit_timing_enable(self.h, int(enable)))
+
+    def gsplit_timing_read(self) -> dict:
+        """{label: (launches, total_ms)} since the last read."""
+        buf = C.create_string_buffer(1 << 16)
+        n = self.lib.gsplit_timing_read(self.h, buf, len(buf))
+        if n < 0:
+            self._check(int(n))
+        out = {}
+        for line in buf.value.decode().splitlines():
+            name, cnt, ms = line.split()
+            out[name] = (int(cnt), float(ms))
+        return out
 
     # -- inspection helpers for tests (copies of the device views; they synchronise) -------
     def fetch_batch(self) -> dict:

@@ -26,6 +26,10 @@ int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what) {
 }
 
 static void free_all(gsplit_ctx *ctx) {
+    for (auto &r : ctx->timer.pending) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t e : ctx->timer.pool) (void)hipEventDestroy(e);
+    ctx->timer.pending.clear();
+    ctx->timer.pool.clear();
     for (void *p : ctx->allocs) (void)hipFree(p);
     ctx->allocs.clear();
     if (ctx->sample_done) (void)hipEventDestroy(ctx->sample_done);
@@ -227,4 +231,34 @@ extern "C" int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_l
     out->d_recv_cat = B.recv;
     out->d_recv_off = ctx->d_meta[layer].recv_off;
     return GSPLIT_OK;
+}
+
+extern "C" int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable) {
+    if (!ctx) return GSPLIT_EINVAL;
+    ctx->timer.enabled = enable != 0;
+    return GSPLIT_OK;
+}
+
+extern "C" int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_bytes) {
+    if (!ctx || !buf || buf_bytes < 1) return GSPLIT_EINVAL;
+    GsTimer &t = ctx->timer;
+    for (auto &r : t.pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            t.total_ms[r.label] += ms;
+            t.count[r.label] += 1;
+        }
+        t.pool.push_back(r.a);
+        t.pool.push_back(r.b);
+    }
+    t.pending.clear();
+    std::string out;
+    for (size_t i = 0; i < t.names.size(); ++i) {
+        out += t.names[i] + " " + std::to_string(t.count[i]) + " " + std::to_string(t.total_ms[i]) + "\n";
+        t.total_ms[i] = 0.0;
+        t.count[i] = 0;
+    }
+    if ((int64_t)out.size() + 1 > buf_bytes) return gs_fail(ctx, GSPLIT_ECAPACITY, "gsplit_timing_read: buffer too small");
+    std::memcpy(buf, out.c_str(), out.size() + 1);
+    return (int64_t)out.size();
 }

@@ -59,6 +59,7 @@ extern "C" int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int3
                      ((uintptr_t)d_table % 16) == 0 && ((uintptr_t)d_out % 16) == 0;
     const bool a4 = row_bytes % 4 == 0 && row_stride_bytes % 4 == 0 && ((uintptr_t)d_table % 4) == 0 &&
                     ((uintptr_t)d_out % 4) == 0;
+    GsTimeScope ts(ctx, "gather_rows", -1, st);
     if (a16) {
         hipLaunchKernelGGL((k_gather_rows<uint4, 4>), dim3(grid), dim3(256), 0, st,
                            (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 16),

@@ -69,6 +69,18 @@ struct GsSageBuf {             // activations kept between forward and backward
     uint64_t fwd_batch = 0;
 };
 
+// Optional per-kernel device timing: when enabled, every kernel launch is bracketed by two events
+// on its stream; gsplit_timing_read() waits for them and reports totals per label.
+struct GsTimer {
+    struct Rec { int label; hipEvent_t a, b; };
+    bool enabled = false;
+    std::vector<std::string> names;
+    std::vector<double> total_ms;
+    std::vector<int64_t> count;
+    std::vector<Rec> pending;
+    std::vector<hipEvent_t> pool;
+};
+
 struct gsplit_ctx {
     gsplit_graph graph;
     int32_t  L = 0, S = 0;
@@ -99,6 +111,7 @@ struct gsplit_ctx {
     hipEvent_t   sample_done = nullptr;
 
     GsSageBuf    sage;
+    GsTimer      timer;
     std::vector<void *> allocs;
     std::string  err;
 };
@@ -112,5 +125,37 @@ int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what);
         if (e__ != hipSuccess)                                                             \
             return gs_fail((ctx), GSPLIT_EHIP, std::string(#call) + ": " + hipGetErrorString(e__)); \
     } while (0)
+
+// brackets the launches issued during its lifetime (exactly one kernel per scope) when timing is on
+struct GsTimeScope {
+    gsplit_ctx *ctx; hipStream_t st; int label; hipEvent_t a;
+    GsTimeScope(gsplit_ctx *c, const char *name, int layer, hipStream_t s) : ctx(c), st(s), label(-1), a(nullptr) {
+        if (!c->timer.enabled) return;
+        GsTimer &t = c->timer;
+        std::string full = layer >= 0 ? std::string(name) + ".l" + std::to_string(layer) : std::string(name);
+        for (size_t i = 0; i < t.names.size(); ++i)
+            if (t.names[i] == full) { label = (int)i; break; }
+        if (label < 0) {
+            label = (int)t.names.size();
+            t.names.push_back(full); t.total_ms.push_back(0.0); t.count.push_back(0);
+        }
+        a = take();
+        if (a) (void)hipEventRecord(a, st);
+    }
+    ~GsTimeScope() {
+        if (label < 0 || !a) return;
+        hipEvent_t b = take();
+        if (!b) return;
+        (void)hipEventRecord(b, st);
+        ctx->timer.pending.push_back({label, a, b});
+    }
+    hipEvent_t take() {
+        GsTimer &t = ctx->timer;
+        if (!t.pool.empty()) { hipEvent_t e = t.pool.back(); t.pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
 
 static inline int64_t gs_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

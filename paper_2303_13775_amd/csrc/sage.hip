@@ -495,6 +495,7 @@ void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_
     const GsLevelMeta *mu = ctx->d_meta + (l + 1);
     float *X = (float *)ctx->sage.xin[l];
     const int64_t ub = ctx->ub_front[l + 1];
+    GsTimeScope ts(ctx, "assemble_input", l, st);
     if (D % 4 != 0 || !aligned16(hin)) {
         hipLaunchKernelGGL(k_assemble_input_f32_any, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
                            B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
@@ -539,6 +540,7 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         dim3 grid((unsigned)gs_ceil_div(ctx->ub_front[l + 1], GBM), (unsigned)gs_ceil_div(N, GBN));
         const bool va = D % 2 == 0;   // rows of the assembled input are 2 * D floats: 16-byte aligned
         const bool vb = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
+        GsTimeScope ts(ctx, "linear_fwd", l, st);
         if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
         else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
         else if (vb) hipLaunchKernelGGL((k_sage_linear_fwd<1, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
@@ -577,8 +579,11 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         zl.p[3 * l + 2] = d_gbias[l];    zl.n[3 * l + 2] = p->dims[l + 1];
         zmax = std::max(zmax, nw);
     }
+    {
+    GsTimeScope ts(ctx, "zero_grads", -1, st);
     hipLaunchKernelGGL(k_zero_buffers, dim3((unsigned)std::min<int64_t>(64, gs_ceil_div(zmax, 1024)), 3 * L),
                        dim3(256), 0, st, zl);
+    }
     for (int l = L - 1; l >= 0; --l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const GsLayerBuf &B = ctx->layer[l];
@@ -597,6 +602,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             const int kchunk = 512;
             dim3 grid((unsigned)gs_ceil_div(2 * D + 1, GBM), (unsigned)gs_ceil_div(N, GBN),
                       (unsigned)gs_ceil_div(ub, kchunk));
+            GsTimeScope ts(ctx, "grad_w", l, st);
             if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
             else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
             else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
@@ -607,10 +613,14 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             CatW w{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
             EpiGradIn ei{sb.gtmp, B.blk_indptr, D, 0};
             dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
+            {
+            GsTimeScope ts(ctx, "grad_in", l, st);
             if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
             else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            }
+            GsTimeScope ts(ctx, "pull_input_grad", l, st);
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
             const float *hact = (const float *)sb.hidden[l];
             const int64_t ubl = ctx->ub_front[l];
@@ -642,6 +652,7 @@ extern "C" int gsplit_softmax_xent(gsplit_ctx *ctx, const float *d_logits, int32
     if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_softmax_xent: no batch");
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L;
+    GsTimeScope ts(ctx, "softmax_xent", -1, st);
     hipLaunchKernelGGL(k_softmax_xent, dim3(grid_1d(ctx, ctx->ub_front[L] * 64)), dim3(256), 0, st, d_logits,
                        n_classes, d_labels, ctx->front[L], ctx->d_meta + L, ctx->S, d_grad_logits, d_row_loss);
     GS_HIP(ctx, hipGetLastError());

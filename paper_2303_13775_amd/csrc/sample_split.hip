@@ -645,15 +645,24 @@ int part_blocks(int64_t upper_items) {
 }
 
 template <class F>
-void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t st) {
+void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t st, const char *name,
+                   int layer) {
     const int nb = part_blocks(upper_items);
-    hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    const std::string nm(name);
+    {
+        GsTimeScope ts(ctx, (nm + "_count").c_str(), layer, st);
+        hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    }
+    {
+    GsTimeScope ts(ctx, (nm + "_scan").c_str(), layer, st);
     if (nb == 256)
         hipLaunchKernelGGL((k_part_scan<F, 1>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
     else if (nb == 512)
         hipLaunchKernelGGL((k_part_scan<F, 2>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
     else
         hipLaunchKernelGGL((k_part_scan<F, 4>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
+    }
+    GsTimeScope ts(ctx, (nm + "_scatter").c_str(), layer, st);
     hipLaunchKernelGGL(k_part_scatter<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_base);
 }
 
@@ -672,6 +681,7 @@ void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStre
     const GsLevelMeta *mu = ctx->d_meta + (l + 1);
     const IndPtrT *ip = (const IndPtrT *)ctx->graph.d_indptr;
     GsLayerBuf &B = ctx->layer[l];
+    GsTimeScope ts(ctx, "sample_layer", l, st);
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
@@ -705,10 +715,13 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
     ctx->sage.fwd_done = false;
     ctx->last_stream = st;
 
-    hipLaunchKernelGGL(k_clear_errors, dim3(1), dim3(64), 0, st, ctx->d_meta, L + 1);
+    {
+        GsTimeScope ts(ctx, "clear_errors", -1, st);
+        hipLaunchKernelGGL(k_clear_errors, dim3(1), dim3(64), 0, st, ctx->d_meta, L + 1);
+    }
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
                    ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1]};
-    run_partition(ctx, pt, ctx->ub_front[L], st);
+    run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
 
     for (int l = L - 1; l >= 0; --l) {
         const int fan = ctx->fan[l];
@@ -723,18 +736,25 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
                             ctx->ent_mixed, ctx->cls, ctx->ent_local, ctx->mixed_ent,
                             B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
-        run_partition(ctx, pa, ub1 * fan, st);
+        run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
         PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
                      ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src, B.rev_cnt,
                      ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
-        run_partition(ctx, pl, ub1 * fan, st);
+        run_partition(ctx, pl, ub1 * fan, st, "local_front", l);
+        {
+        GsTimeScope ts(ctx, "shuffle_index", l, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
                            B.blk_indptr, B.src_row, B.self_row, B.edge_row, l > 0 ? B.rev_cnt : nullptr,
                            ml, mu, S, fan);
+        }
         if (l > 0) {
-            hipLaunchKernelGGL(k_rev_alloc, dim3(grid_for(ctx, ctx->ub_front[l])), dim3(256), 0, st,
-                               B.rev_cnt, B.rev_ptr, B.rev_fill, ml, S);
+            {
+                GsTimeScope ts(ctx, "rev_alloc", l, st);
+                hipLaunchKernelGGL(k_rev_alloc, dim3(grid_for(ctx, ctx->ub_front[l])), dim3(256), 0, st,
+                                   B.rev_cnt, B.rev_ptr, B.rev_fill, ml, S);
+            }
+            GsTimeScope ts(ctx, "rev_fill", l, st);
             hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
                                ctx->ent_mixed, B.blk_indptr, B.self_row, B.edge_row, B.rev_ptr, B.rev_fill,
                                B.rev_list, mu, S, fan);
