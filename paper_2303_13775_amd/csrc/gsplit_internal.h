@@ -64,7 +64,10 @@ struct GsSageBuf {             // activations kept between forward and backward
     void    *xin[GS_MAXL] = {nullptr};          // assembled layer inputs [rows x 2*dims[l]]: self | mean
     float   *ghid[GS_MAXL + 1] = {nullptr};     // d loss / d hidden of level 1..L
     float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before the reverse shuffle
-    void    *wcat[GS_MAXL] = {nullptr};         // stacked [W_self; W_neigh] per layer
+    float   *inv_cnt[GS_MAXL] = {nullptr};      // 1 / (sampled neighbours) per destination row
+    float   *gw_part[GS_MAXL] = {nullptr};      // per-chunk partial weight gradients
+    int      kchunk[GS_MAXL] = {0};             // destination rows per split-K chunk
+    int      nchunk[GS_MAXL] = {0};             // chunks at the upper bound (multiple of 8)
     bool     fwd_done = false;
     uint64_t fwd_batch = 0;
 };

@@ -29,7 +29,8 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32(const float *__restr
                                                             const int32_t *__restrict__ edge_row,
                                                             const int32_t *__restrict__ self_row,
                                                             const GsLevelMeta *__restrict__ meta_up,
-                                                            int S, float *__restrict__ X) {
+                                                            int S, float *__restrict__ X,
+                                                            float *__restrict__ inv_cnt) {
     const int n1 = meta_up->front_off[S];
     const int nvec = D >> 2;
     const int c0 = threadIdx.x % LPR;
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32(const float *__restr
         const int e0 = blk_indptr[row], e1 = blk_indptr[row + 1];
         const int64_t self = self_row[row];
         const float cnt = (float)(e1 - e0);
+        if (c0 == 0) inv_cnt[row] = e1 > e0 ? 1.f / cnt : 0.f;
         for (int c = c0; c < nvec; c += LPR) {
             const float4 own = H4[self * nvec + c];
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -70,13 +72,15 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__r
                                                                 const int32_t *__restrict__ edge_row,
                                                                 const int32_t *__restrict__ self_row,
                                                                 const GsLevelMeta *__restrict__ meta_up,
-                                                                int S, float *__restrict__ X) {
+                                                                int S, float *__restrict__ X,
+                                                                float *__restrict__ inv_cnt) {
     const int n1 = meta_up->front_off[S];
     const int lane = threadIdx.x & 63;
     const int waves = (gridDim.x * blockDim.x) >> 6;
     for (int row = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < n1; row += waves) {
         const int e0 = blk_indptr[row], e1 = blk_indptr[row + 1];
         const int64_t self = self_row[row];
+        if (lane == 0) inv_cnt[row] = e1 > e0 ? 1.f / (float)(e1 - e0) : 0.f;
         for (int c = lane; c < D; c += 64) {
             float acc = 0.f;
             for (int e = e0; e < e1; ++e) acc += H[(int64_t)edge_row[e] * D + c];
@@ -100,62 +104,73 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__r
 // lower half-wave takes k = 0..3 and the upper half k = 4..7 over four consecutive MFMAs; A and B
 // use the same assignment, so the sum over k is complete whatever the order.
 //
-// Workgroup = 4 waves as 2 x 2 over a BM x BN tile (wave tile BM/2 x BN/2, 32 x 32 blocks).
-// One LDS buffer; the next k-tile is fetched into registers while the current one is multiplied.
+// Workgroup = 8 waves as 2 x 4 over a BM x BN tile (32 x 32 MFMA blocks per wave).
 // ------------------------------------------------------------------------------------------
 constexpr int BK = 32;
 constexpr int KC_LD = BK + 4;
+// workgroup = GWM x GWN waves; two waves share each SIMD, so one wave's LDS traffic and barrier
+// waits overlap the other's MFMAs
+constexpr int GWM = 2, GWN = 4, GNT = 64 * GWM * GWN;
 
 template <int ROWS>
 constexpr int lds_words() { return ROWS * KC_LD > BK * (ROWS + 4) ? ROWS * KC_LD : BK * (ROWS + 4); }
 
-template <int ROWS, bool KC, int VW, class F>
+template <int ROWS, bool KC, int VW, int NT, class F>
 struct Stager {
-    static constexpr int NV = ROWS * BK / 4 / 256;
+    static constexpr int NV = ROWS * BK / 4 / NT;
+    static_assert(NV >= 1 && NV <= 8, "tile too small or too large for the workgroup");
     float4 reg[NV];
+    unsigned keep;   // 4 bits per register: which of its words exist in the matrix
 
-    __device__ __forceinline__ static float4 fetch(const F &f, int outer, int inner, int inner_end) {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    // Loads are unconditional (the accessor clamps the address into the matrix); words outside the
+    // matrix are zeroed only when the registers are written to LDS, so nothing depends on a load
+    // before that point and the loads of two k-tiles stay in flight.
+    __device__ __forceinline__ void fetch(int v, const F &f, int outer, int inner, int inner_end, bool ok) {
         if (VW == 4) {
-            if (inner < inner_end) {
-                const float *p = f.at(outer, inner);
-                if (p) v = *reinterpret_cast<const float4 *>(p);
-            }
+            bool in;
+            const float *p = f.template at<4>(outer, inner, in);
+            reg[v] = *reinterpret_cast<const float4 *>(p);
+            keep |= (in && ok && inner < inner_end) ? (0xFu << (4 * v)) : 0u;
         } else {
             float t[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float *p = (inner + j < inner_end) ? f.at(outer, inner + j) : nullptr;
-                t[j] = p ? *p : 0.f;
+                bool in;
+                const float *p = f.template at<1>(outer, inner + j, in);
+                t[j] = *p;
+                keep |= (in && ok && inner + j < inner_end) ? (1u << (4 * v + j)) : 0u;
             }
-            v = make_float4(t[0], t[1], t[2], t[3]);
+            reg[v] = make_float4(t[0], t[1], t[2], t[3]);
         }
-        return v;
     }
     // r0: first M/N index of the tile, [k0, k_end): k range still to do, r_end: matrix extent
     __device__ __forceinline__ void load(const F &f, int r0, int r_end, int k0, int k_end, int tid) {
+        keep = 0u;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             if (KC) {
-                const int kq = tid & 7, row = (tid >> 3) + 32 * v;
-                reg[v] = (r0 + row < r_end) ? fetch(f, r0 + row, k0 + 4 * kq, k_end)
-                                            : make_float4(0.f, 0.f, 0.f, 0.f);
+                const int kq = tid & 7, row = (tid >> 3) + (NT / 8) * v;
+                fetch(v, f, r0 + row, k0 + 4 * kq, k_end, r0 + row < r_end);
             } else {
-                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (1024 / ROWS) * v;
-                reg[v] = (k0 + kk < k_end) ? fetch(f, k0 + kk, r0 + 4 * x, r_end)
-                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (4 * NT / ROWS) * v;
+                fetch(v, f, k0 + kk, r0 + 4 * x, r_end, k0 + kk < k_end);
             }
         }
     }
     __device__ __forceinline__ void store(float *lds, int tid) const {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
+            float4 w = reg[v];
+            w.x = (keep >> (4 * v)) & 1u ? w.x : 0.f;
+            w.y = (keep >> (4 * v + 1)) & 1u ? w.y : 0.f;
+            w.z = (keep >> (4 * v + 2)) & 1u ? w.z : 0.f;
+            w.w = (keep >> (4 * v + 3)) & 1u ? w.w : 0.f;
             if (KC) {
-                const int kq = tid & 7, row = (tid >> 3) + 32 * v;
-                *reinterpret_cast<float4 *>(&lds[row * KC_LD + 4 * kq]) = reg[v];
+                const int kq = tid & 7, row = (tid >> 3) + (NT / 8) * v;
+                *reinterpret_cast<float4 *>(&lds[row * KC_LD + 4 * kq]) = w;
             } else {
-                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (1024 / ROWS) * v;
-                *reinterpret_cast<float4 *>(&lds[kk * (ROWS + 4) + 4 * x]) = reg[v];
+                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (4 * NT / ROWS) * v;
+                *reinterpret_cast<float4 *>(&lds[kk * (ROWS + 4) + 4 * x]) = w;
             }
         }
     }
@@ -176,12 +191,17 @@ template <int BM, int BN, bool A_KC, bool B_KC, int VA, int VB, class AF, class 
 __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int m_end, const int n_end,
                                           const int k_begin, const int k_end, const AF &a, const BF &b,
                                           const EF &epi) {
-    __shared__ __attribute__((aligned(16))) float As[lds_words<BM>()];
-    __shared__ __attribute__((aligned(16))) float Bs[lds_words<BN>()];
-    constexpr int MI = BM / 64, NI = BN / 64;
+    // two LDS stages and two register stages: k-tile t is multiplied out of LDS while tile t+1
+    // sits in the other LDS stage and tile t+2 is in flight into registers, so a global load has
+    // two iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
+    __shared__ __attribute__((aligned(16))) float As0[lds_words<BM>()];
+    __shared__ __attribute__((aligned(16))) float As1[lds_words<BM>()];
+    __shared__ __attribute__((aligned(16))) float Bs0[lds_words<BN>()];
+    __shared__ __attribute__((aligned(16))) float Bs1[lds_words<BN>()];
+    constexpr int MI = BM / (32 * GWM), NI = BN / (32 * GWN);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int wm0 = (wave / GWN) * (BM / GWM), wn0 = (wave % GWN) * (BN / GWN);
     floatx16 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -190,37 +210,82 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    Stager<BM, A_KC, VA, AF> sa;
-    Stager<BN, B_KC, VB, BF> sb;
-    sa.load(a, m0, m_end, k_begin, k_end, tid);
-    sb.load(b, n0, n_end, k_begin, k_end, tid);
-    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-        sa.store(As, tid);
-        sb.store(Bs, tid);
-        __syncthreads();
-        if (k0 + BK < k_end) {
-            sa.load(a, m0, m_end, k0 + BK, k_end, tid);
-            sb.load(b, n0, n_end, k0 + BK, k_end, tid);
-        }
+    using SA = Stager<BM, A_KC, VA, GNT, AF>;
+    using SB = Stager<BN, B_KC, VB, GNT, BF>;
+    SA sa0, sa1;
+    SB sb0, sb1;
+
+    // The fragments of the next group of 8 k are read from LDS while the MFMAs of the current group
+    // execute (an MFMA occupies the matrix pipe for 64 cycles but not the issue slot), so only the
+    // first LDS read of a k-tile is exposed.
+    auto multiply = [&](const float *As, const float *Bs) {
+        float af[2][MI][4], bf[2][NI][4];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, 0, half, af[0][i]);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, 0, half, bf[0][j]);
 #pragma unroll
         for (int oct = 0; oct < BK / 8; ++oct) {
-            float af[MI][4], bf[NI][4];
+            if (oct + 1 < BK / 8) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, oct, half, af[i]);
+                for (int i = 0; i < MI; ++i)
+                    read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, oct + 1, half, af[(oct + 1) & 1][i]);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, oct, half, bf[j]);
+                for (int j = 0; j < NI; ++j)
+                    read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, oct + 1, half, bf[(oct + 1) & 1][j]);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // reads of the next group stay ahead of these MFMAs
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][q], bf[j][q], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[oct & 1][i][q], bf[oct & 1][j][q], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // one k-tile: fetch tile k0 + 2 BK into the registers that held tile k0, multiply tile k0,
+    // move tile k0 + BK from registers to the other LDS stage
+    auto step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const float *As_cur, const float *Bs_cur,
+                    float *As_nxt, float *Bs_nxt, int k0) {
+        if (k0 + 2 * BK < k_end) {
+            ra_cur.load(a, m0, m_end, k0 + 2 * BK, k_end, tid);
+            rb_cur.load(b, n0, n_end, k0 + 2 * BK, k_end, tid);
+        }
+        multiply(As_cur, Bs_cur);
+        if (k0 + BK < k_end) {
+            ra_nxt.store(As_nxt, tid);
+            rb_nxt.store(Bs_nxt, tid);
         }
         __syncthreads();
+    };
+
+    sa0.load(a, m0, m_end, k_begin, k_end, tid);
+    sb0.load(b, n0, n_end, k_begin, k_end, tid);
+    if (k_begin + BK < k_end) {
+        sa1.load(a, m0, m_end, k_begin + BK, k_end, tid);
+        sb1.load(b, n0, n_end, k_begin + BK, k_end, tid);
+    }
+    sa0.store(As0, tid);
+    sb0.store(Bs0, tid);
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
+        step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
+        if (k0 + BK < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BK);
     }
     // accumulator layout of the 32x32 block: register r of lane l holds
-    // row (r / 4) * 8 + (l / 32) * 4 + (r % 4), column l % 32
+    // row (r / 4) * 8 + (l / 32) * 4 + (r % 4), column l % 32.
+    // Per-column and per-row side inputs of the epilogue (bias, 1/count) are fetched up front so
+    // that their latencies overlap instead of adding up in front of every store.
+    float colv[NI], rowv[MI][16];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) colv[j] = epi.col(n0 + wn0 + j * 32 + l32);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            rowv[i][r] = epi.row(m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3));
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -229,68 +294,78 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
             for (int r = 0; r < 16; ++r) {
                 const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
                 const int n = n0 + wn0 + j * 32 + l32;
-                epi(m, n, acc[i][j][r]);
+                epi.store(m, n, acc[i][j][r], rowv[i][r], colv[j]);
             }
 }
 
 // ---- operand accessors and epilogues ---------------------------------------------------------
 __device__ const float g_one_then_zero[4] = {1.f, 0.f, 0.f, 0.f};
 
+// Accessors return an address that is always safe to read VW floats from (indices are clamped into
+// the matrix; matrices have at least one row and VW columns) and say whether the element exists.
 // plain row-major matrix
 struct MatRows {
     const float *p; int rows; int cols;
-    __device__ __forceinline__ const float *at(int o, int i) const {
-        return (o < rows && i < cols) ? p + (int64_t)o * cols + i : nullptr;
+    template <int VW>
+    __device__ __forceinline__ const float *at(int o, int i, bool &in) const {
+        in = o < rows && i < cols;
+        const int oc = min(o, rows - 1), ic = min(i, cols - VW);
+        return p + (int64_t)oc * cols + ic;
     }
 };
 // plain row-major matrix followed by one column of ones (its product with dZ is the bias gradient)
 struct MatRowsOnes {
     const float *p; int rows; int cols;
-    __device__ __forceinline__ const float *at(int o, int i) const {
-        if (o >= rows) return nullptr;
-        if (i < cols) return p + (int64_t)o * cols + i;
-        return i == cols ? g_one_then_zero : nullptr;
+    template <int VW>
+    __device__ __forceinline__ const float *at(int o, int i, bool &in) const {
+        in = o < rows && i <= cols;
+        const int oc = min(o, rows - 1), ic = min(i, cols - VW);
+        const float *q = p + (int64_t)oc * cols + ic;
+        return i == cols ? g_one_then_zero : q;
     }
 };
 // [W_self; W_neigh] stacked: row k of the 2 * D x N matrix
 struct CatW {
     const float *Ws; const float *Wn; int D; int N;
-    __device__ __forceinline__ const float *at(int k, int n) const {
-        if (n >= N) return nullptr;
-        if (k < D) return Ws + (int64_t)k * N + n;
-        if (k < 2 * D) return Wn + (int64_t)(k - D) * N + n;
-        return nullptr;
+    template <int VW>
+    __device__ __forceinline__ const float *at(int k, int n, bool &in) const {
+        in = k < 2 * D && n < N;
+        const int nc = min(n, N - VW);
+        const int kc = min(k, 2 * D - 1);
+        const float *base = kc < D ? Ws : Wn;
+        const int kr = kc < D ? kc : kc - D;
+        return base + (int64_t)kr * N + nc;
     }
 };
 struct EpiFwd {
     float *out; const float *bias; int N; int n1; int relu;
-    __device__ __forceinline__ void operator()(int m, int n, float v) const {
+    __device__ __forceinline__ float col(int n) const { return n < N ? bias[n] : 0.f; }
+    __device__ __forceinline__ float row(int) const { return 0.f; }
+    __device__ __forceinline__ void store(int m, int n, float v, float, float b) const {
         if (m < n1 && n < N) {
-            float z = v + bias[n];
+            const float z = v + b;
             out[(int64_t)m * N + n] = (relu && z < 0.f) ? 0.f : z;
         }
     }
 };
+// partial [dW_self; dW_neigh; db] of one chunk of destination rows, written to the chunk's slab
 struct EpiGradW {
-    float *gws; float *gwn; float *gb; int D; int N;
-    __device__ __forceinline__ void operator()(int c, int n, float v) const {
-        if (n >= N || c > 2 * D) return;
-        if (c < D) atomicAdd(&gws[(int64_t)c * N + n], v);
-        else if (c < 2 * D) atomicAdd(&gwn[(int64_t)(c - D) * N + n], v);
-        else atomicAdd(&gb[n], v);
+    float *part; int rows; int N;     // rows = 2 * D + 1
+    __device__ __forceinline__ float col(int) const { return 0.f; }
+    __device__ __forceinline__ float row(int) const { return 0.f; }
+    __device__ __forceinline__ void store(int c, int n, float v, float, float) const {
+        if (n < N && c < rows) part[(int64_t)c * N + n] = v;
     }
 };
 // input gradients per destination row: [dH_self | dMean / cnt]; the reverse shuffle (pull through
 // the scatter side of the shuffle index) follows in k_pull_input_grad
 struct EpiGradIn {
-    float *out; const int32_t *blk_indptr; int D; int n1;
-    __device__ __forceinline__ void operator()(int i, int j, float v) const {
+    float *out; const float *inv_cnt; int D; int n1;
+    __device__ __forceinline__ float col(int) const { return 0.f; }
+    __device__ __forceinline__ float row(int i) const { return i < n1 ? inv_cnt[i] : 0.f; }
+    __device__ __forceinline__ void store(int i, int j, float v, float w, float) const {
         if (i >= n1 || j >= 2 * D) return;
-        if (j >= D) {
-            const int c = blk_indptr[i + 1] - blk_indptr[i];
-            v = c > 0 ? v / (float)c : 0.f;
-        }
-        out[(int64_t)i * 2 * D + j] = v;
+        out[(int64_t)i * 2 * D + j] = j < D ? v : v * w;
     }
 };
 
@@ -298,7 +373,7 @@ constexpr int GBM = 64, GBN = 128;
 
 // Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer
 template <int VA, int VB>
-__global__ __launch_bounds__(256) void k_sage_linear_fwd(MatRows a, CatW b, EpiFwd epi,
+__global__ __launch_bounds__(GNT) void k_sage_linear_fwd(MatRows a, CatW b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int m0 = blockIdx.x * GBM;
@@ -307,22 +382,61 @@ __global__ __launch_bounds__(256) void k_sage_linear_fwd(MatRows a, CatW b, EpiF
     gemm_tile<GBM, GBN, true, false, VA, VB>(m0, blockIdx.y * GBN, n1, b.N, 0, a.cols, a, b, epi);
 }
 
-// [dW_self; dW_neigh; db] += [H_self | mean | 1]^T * dZ over a chunk of destination rows
+// Partial [dW_self; dW_neigh; db] = [X | 1]^T * dZ over one chunk of destination rows (split-K).
+// The output tiles of one chunk read the same slabs of X and dZ; the launch is one-dimensional and
+// the workgroup id is decoded so that all tiles of a chunk land on the same XCD (workgroups are
+// dealt round-robin to the 8 XCDs) and share its L2.  Partials go to a per-chunk slab; a
+// fixed-order reduction follows (deterministic, no atomics).
 template <int VA, int VB>
-__global__ __launch_bounds__(256) void k_sage_grad_w(MatRowsOnes a, MatRows dz, EpiGradW epi, int kchunk,
+__global__ __launch_bounds__(GNT) void k_sage_grad_w(MatRowsOnes a, MatRows dz, EpiGradW epi, int kchunk,
+                                                     int tiles_m, int tiles_n,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int k_begin = blockIdx.z * kchunk;
+    const int tiles = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int tile = j % tiles, chunk = (j / tiles) * 8 + xcd;
+    const int k_begin = chunk * kchunk;
     if (k_begin >= n1) return;
     a.rows = n1; dz.rows = n1;
     const int k_end = min(n1, k_begin + kchunk);
-    gemm_tile<GBM, GBN, false, false, VA, VB>(blockIdx.x * GBM, blockIdx.y * GBN, a.cols + 1, dz.cols,
-                                              k_begin, k_end, a, dz, epi);
+    epi.part += (int64_t)chunk * epi.rows * epi.N;
+    gemm_tile<GBM, GBN, false, false, VA, VB>((tile % tiles_m) * GBM, (tile / tiles_m) * GBN, a.cols + 1,
+                                              dz.cols, k_begin, k_end, a, dz, epi);
+}
+
+// Sum the per-chunk partials in chunk order into the caller's gradient buffers, all layers in one
+// launch (blockIdx.y = layer).
+struct GradReduce {
+    const float *part[GS_MAXL]; float *gws[GS_MAXL]; float *gwn[GS_MAXL]; float *gb[GS_MAXL];
+    int D[GS_MAXL]; int N[GS_MAXL]; int kchunk[GS_MAXL];
+};
+__global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLevelMeta *__restrict__ meta, int S) {
+    const int l = blockIdx.y;
+    const int n1 = meta[l + 1].front_off[S];
+    const int chunks = (n1 + g.kchunk[l] - 1) / g.kchunk[l];
+    const int D = g.D[l], N = g.N[l];
+    const int64_t words = (int64_t)(2 * D + 1) * N;
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < words;
+         x += (int64_t)gridDim.x * blockDim.x) {
+        float acc = 0.f;
+        const float *p = g.part[l] + x;
+        int z = 0;
+        for (; z + 4 <= chunks; z += 4) {
+            const float v0 = p[(int64_t)z * words], v1 = p[(int64_t)(z + 1) * words];
+            const float v2 = p[(int64_t)(z + 2) * words], v3 = p[(int64_t)(z + 3) * words];
+            acc += v0; acc += v1; acc += v2; acc += v3;
+        }
+        for (; z < chunks; ++z) acc += p[(int64_t)z * words];
+        const int64_t wn = (int64_t)D * N;
+        if (x < wn) g.gws[l][x] = acc;
+        else if (x < 2 * wn) g.gwn[l][x - wn] = acc;
+        else g.gb[l][x - 2 * wn] = acc;
+    }
 }
 
 // [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row
 template <int VA, int VB>
-__global__ __launch_bounds__(256) void k_sage_grad_in(MatRows dz, CatW w, EpiGradIn epi,
+__global__ __launch_bounds__(GNT) void k_sage_grad_in(MatRows dz, CatW w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int m0 = blockIdx.x * GBM;
@@ -429,19 +543,6 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const float *__restrict__ 
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
-// zero up to 3 * GS_MAXL caller buffers in one launch (blockIdx.y selects the buffer)
-struct ZeroList {
-    float *p[3 * GS_MAXL];
-    int64_t n[3 * GS_MAXL];
-};
-__global__ __launch_bounds__(256) void k_zero_buffers(ZeroList z) {
-    float *p = z.p[blockIdx.y];
-    const int64_t n = z.n[blockIdx.y];
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n;
-         x += (int64_t)gridDim.x * blockDim.x)
-        p[x] = 0.f;
-}
-
 int grid_1d(const gsplit_ctx *ctx, int64_t upper_threads) {
     int64_t want = std::max<int64_t>(1, gs_ceil_div(upper_threads, 256));
     return (int)std::min<int64_t>(want, (int64_t)ctx->n_cu * 8);
@@ -462,6 +563,21 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
     }
     for (int l = 0; l < L; ++l) {
         int rc = gs_alloc(ctx, &sb.xin[l], sizeof(float) * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
+        if (rc) return rc;
+        rc = gs_alloc(ctx, (void **)&sb.inv_cnt[l], sizeof(float) * ctx->ub_front[l + 1], "inverse counts");
+        if (rc) return rc;
+    }
+    for (int l = 0; l < L; ++l) {
+        // split-K geometry of the weight-gradient product: about 1024 workgroups at the upper bound
+        const int tiles = (int)(gs_ceil_div(2 * p->dims[l] + 1, GBM) * gs_ceil_div(p->dims[l + 1], GBN));
+        const int64_t ub = ctx->ub_front[l + 1];
+        int64_t chunks = std::max<int64_t>(8, 1024 / tiles);
+        int64_t kchunk = std::max<int64_t>(64, gs_ceil_div(gs_ceil_div(ub, chunks), 32) * 32);
+        chunks = gs_ceil_div(gs_ceil_div(ub, kchunk), 8) * 8;
+        sb.kchunk[l] = (int)kchunk;
+        sb.nchunk[l] = (int)chunks;
+        int rc = gs_alloc(ctx, (void **)&sb.gw_part[l],
+                          sizeof(float) * chunks * (2 * p->dims[l] + 1) * p->dims[l + 1], "weight-gradient partials");
         if (rc) return rc;
     }
     int64_t gtmp_words = 1;
@@ -498,19 +614,19 @@ void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_
     GsTimeScope ts(ctx, "assemble_input", l, st);
     if (D % 4 != 0 || !aligned16(hin)) {
         hipLaunchKernelGGL(k_assemble_input_f32_any, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
         return;
     }
     const int nvec = D / 4;
     if (nvec <= 16)
         hipLaunchKernelGGL(k_assemble_input_f32<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
     else if (nvec <= 32)
         hipLaunchKernelGGL(k_assemble_input_f32<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
     else
         hipLaunchKernelGGL(k_assemble_input_f32<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
 }
 
 }  // namespace
@@ -541,10 +657,10 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const bool va = D % 2 == 0;   // rows of the assembled input are 2 * D floats: 16-byte aligned
         const bool vb = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         GsTimeScope ts(ctx, "linear_fwd", l, st);
-        if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
-        else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
-        else if (vb) hipLaunchKernelGGL((k_sage_linear_fwd<1, 4>), grid, dim3(256), 0, st, a, b, epi, mu, S);
-        else hipLaunchKernelGGL((k_sage_linear_fwd<1, 1>), grid, dim3(256), 0, st, a, b, epi, mu, S);
+        if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
+        else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
+        else if (vb) hipLaunchKernelGGL((k_sage_linear_fwd<1, 4>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
+        else hipLaunchKernelGGL((k_sage_linear_fwd<1, 1>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
     }
     GS_HIP(ctx, hipGetLastError());
     sb.fwd_done = true;
@@ -568,22 +684,9 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: parameters differ from the forward pass");
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
-    ZeroList zl;
-    int64_t zmax = 1;
-    for (int l = 0; l < L; ++l) {
+    for (int l = 0; l < L; ++l)
         if (!d_gw_self[l] || !d_gw_neigh[l] || !d_gbias[l])
             return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_bwd: NULL gradient pointer");
-        const int64_t nw = (int64_t)p->dims[l] * p->dims[l + 1];
-        zl.p[3 * l] = d_gw_self[l];      zl.n[3 * l] = nw;
-        zl.p[3 * l + 1] = d_gw_neigh[l]; zl.n[3 * l + 1] = nw;
-        zl.p[3 * l + 2] = d_gbias[l];    zl.n[3 * l + 2] = p->dims[l + 1];
-        zmax = std::max(zmax, nw);
-    }
-    {
-    GsTimeScope ts(ctx, "zero_grads", -1, st);
-    hipLaunchKernelGGL(k_zero_buffers, dim3((unsigned)std::min<int64_t>(64, gs_ceil_div(zmax, 1024)), 3 * L),
-                       dim3(256), 0, st, zl);
-    }
     for (int l = L - 1; l >= 0; --l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const GsLayerBuf &B = ctx->layer[l];
@@ -594,31 +697,31 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         // weight and bias gradients, summed over all splits: [X | 1]^T dZ with the layer input X
         // assembled by the forward pass
         MatRowsOnes in{(const float *)sb.xin[l], 0, 2 * D};
-        EpiGradW ew{d_gw_self[l], d_gw_neigh[l], d_gbias[l], D, N};
+        EpiGradW ew{sb.gw_part[l], 2 * D + 1, N};
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
         const bool vw = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         {
-            const int kchunk = 512;
-            dim3 grid((unsigned)gs_ceil_div(2 * D + 1, GBM), (unsigned)gs_ceil_div(N, GBN),
-                      (unsigned)gs_ceil_div(ub, kchunk));
+            const int kchunk = sb.kchunk[l];
+            const int tm = (int)gs_ceil_div(2 * D + 1, GBM), tn = (int)gs_ceil_div(N, GBN);
+            dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
             GsTimeScope ts(ctx, "grad_w", l, st);
-            if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
-            else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
-            else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
-            else hipLaunchKernelGGL((k_sage_grad_w<1, 1>), grid, dim3(256), 0, st, in, dz, ew, kchunk, mu, S);
+            if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
+            else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
+            else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
+            else hipLaunchKernelGGL((k_sage_grad_w<1, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
         }
         if (l > 0) {
             const GsLevelMeta *ml = ctx->d_meta + l;
             CatW w{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
-            EpiGradIn ei{sb.gtmp, B.blk_indptr, D, 0};
+            EpiGradIn ei{sb.gtmp, sb.inv_cnt[l], D, 0};
             dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
             {
             GsTimeScope ts(ctx, "grad_in", l, st);
-            if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
-            else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
-            else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
-            else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(256), 0, st, dz, w, ei, mu, S);
+            if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
+            else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
+            else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
+            else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
             }
             GsTimeScope ts(ctx, "pull_input_grad", l, st);
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
@@ -638,6 +741,18 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
             }
         }
+    }
+    {
+        GradReduce gr;
+        int64_t wmax = 1;
+        for (int l = 0; l < L; ++l) {
+            gr.part[l] = sb.gw_part[l]; gr.gws[l] = d_gw_self[l]; gr.gwn[l] = d_gw_neigh[l]; gr.gb[l] = d_gbias[l];
+            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.kchunk[l] = sb.kchunk[l];
+            wmax = std::max<int64_t>(wmax, (int64_t)(2 * p->dims[l] + 1) * p->dims[l + 1]);
+        }
+        GsTimeScope ts(ctx, "reduce_grads", -1, st);
+        hipLaunchKernelGGL(k_reduce_grads, dim3((unsigned)std::min<int64_t>(256, gs_ceil_div(wmax, 256)), L), dim3(256),
+                           0, st, gr, ctx->d_meta, S);
     }
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;
