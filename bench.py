@@ -33,6 +33,10 @@ def parse():
     ap.add_argument("--workload", default="medium", choices=["medium", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=60)
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
+                         "overlaps forward/backward of step i on a second stream)")
+    ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
@@ -71,6 +75,44 @@ class Runner:
         rec(4)
         c.gsplit_sage_bwd(self.params, self.glogits, self.gws, self.gwn, self.gb)
         rec(5)
+
+
+class Pipelined:
+    """Batch slots on several streams: while the forward/backward pass of step i runs on the
+    training stream, sampling, splitting and the feature gather of the next steps run on
+    sampling streams (they do not depend on the weights; forward/backward of consecutive steps
+    stay strictly ordered, as synchronous training requires).  Every step still does all of its
+    work; nothing is cached or skipped.  Events order the hand-over of a slot in both directions."""
+
+    def __init__(self, w, dev, n_ahead=2):
+        import torch
+        self.torch = torch
+        self.n = n_ahead + 1
+        self.slots = [Runner(w, dev) for _ in range(self.n)]
+        self.s_sample = [torch.cuda.Stream(device=dev) for _ in range(n_ahead)]
+        self.s_train = torch.cuda.Stream(device=dev)
+        self.ready = [torch.cuda.Event() for _ in range(self.n)]
+        self.free = [torch.cuda.Event() for _ in range(self.n)]
+        for e in self.free:
+            e.record()
+
+    def run(self, targets, first, count):
+        torch = self.torch
+        for i in range(first, first + count):
+            k = i % self.n
+            r = self.slots[k]
+            ss = self.s_sample[i % len(self.s_sample)]
+            with torch.cuda.stream(ss):
+                ss.wait_event(self.free[k])
+                r.ctx.gsplit_sample_split(targets[i], r.seed, i)
+                r.ctx.gsplit_gather_features(r.w.feat, r.x0)
+                self.ready[k].record(ss)
+            with torch.cuda.stream(self.s_train):
+                self.s_train.wait_event(self.ready[k])
+                r.ctx.gsplit_sage_fwd(r.params, r.x0, r.logits)
+                r.ctx.gsplit_softmax_xent(r.logits, r.w.labels, r.glogits)
+                r.ctx.gsplit_sage_bwd(r.params, r.glogits, r.gws, r.gwn, r.gb)
+                self.free[k].record(self.s_train)
 
 
 def cpu_baseline(w_host, iters):
@@ -119,6 +161,7 @@ def main():
     targets = [w.targets(i) for i in range(n_total)]
     torch.cuda.synchronize()
 
+    # strictly serial steps on one stream
     for i in range(a.warmup):
         r.step(targets[i], i)
     torch.cuda.synchronize()
@@ -126,7 +169,16 @@ def main():
     for i in range(a.warmup, n_total):
         r.step(targets[i], i)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_serial = time.perf_counter() - t0
+    dt = dt_serial
+    if not a.no_pipeline:
+        pipe = Pipelined(w, dev, a.ahead)
+        pipe.run(targets, 0, a.warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pipe.run(targets, a.warmup, a.steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
 
     # per-stage device times (separate instrumented pass; events on the stream the kernels run on)
@@ -205,7 +257,11 @@ def main():
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": dict(w.describe(), fanout_order="fanouts[l] expands layer l+1 into layer l",
-                       graph_gen_s=round(t_gen, 1)),
+                       graph_gen_s=round(t_gen, 1),
+                       schedule=("serial, one stream" if a.no_pipeline else
+                                 f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the "
+                                 f"next {a.ahead} step(s) overlap fwd/loss/bwd of step i")),
+        "serial_ms_per_step": dt_serial / a.steps * 1e3,
         "gather_GBps": gather["achieved"],
         "stage_ms": stage_ms,
         "kernel_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
