@@ -411,6 +411,67 @@ def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.
     return Backward(gws, gwn, gb, ghid)
 
 
+def relu_decision_slack(batch: Batch, fwd: Forward, params: SageParams, bwd: Backward,
+                        rel_tau: float = 1e-5, store_bf16: bool = False):
+    """How much each weight gradient may legitimately differ because of ReLU decisions that the
+    precision of the forward pass cannot settle.
+
+    The backward pass multiplies by [z > 0].  A pre-activation with |z| <= rel_tau * max|z| of its
+    layer is below the rounding noise of a float32 (or bfloat16-input) forward pass, so an
+    implementation that keeps its activations in that precision may take the decision either way
+    and both gradients are valid.  This returns a first-order elementwise bound on the resulting
+    change of (gw_self, gw_neigh, gbias): the backward recursion run on absolute values, where an
+    undecided entry contributes |dH| (it can flip entirely) and a decided one passes the
+    uncertainty it received from above.  Tests add it to their tolerance."""
+    S, L = batch.n_splits, batch.n_layers
+    q = (lambda a: to_bf16_rne(np.asarray(a, np.float32)).astype(np.float64)) if store_bf16 \
+        else (lambda a: np.asarray(a, np.float64))
+    sws = [np.zeros(w.shape, np.float64) for w in params.w_self]
+    swn = [np.zeros(w.shape, np.float64) for w in params.w_neigh]
+    sb = [np.zeros(b.shape, np.float64) for b in params.bias]
+    u_hid: List[Optional[np.ndarray]] = [None] * (L + 1)
+    u_hid[L] = np.zeros(fwd.hidden[L].shape, np.float64)
+    n_undecided = 0
+    for l in range(L - 1, -1, -1):
+        Ws, Wn = np.abs(q(params.w_self[l])), np.abs(q(params.w_neigh[l]))
+        off = batch.local_off(l + 1)
+        if l > 0:
+            u_hid[l] = np.zeros(fwd.hidden[l].shape, np.float64)
+        zmax = max([float(np.abs(z).max()) if z.size else 0.0 for z in fwd.z[l]] + [0.0])
+        for s in range(S):
+            blk = batch.blocks[l][s]
+            n_dst = blk.dst.shape[0]
+            dH = np.abs(bwd.ghidden[l + 1][off[s]:off[s + 1]])
+            uH = u_hid[l + 1][off[s]:off[s + 1]]
+            Z = fwd.z[l][s]
+            if l == L - 1:
+                u_dZ = uH
+            else:
+                undecided = np.abs(Z) <= rel_tau * zmax
+                n_undecided += int(undecided.sum())
+                u_dZ = np.where(undecided, dH + uH, (Z > 0.0) * uH)
+            mixed, M = np.abs(fwd.mixed[l][s]), np.abs(fwd.mean[l][s])
+            sws[l] += mixed[:n_dst].T @ u_dZ
+            swn[l] += M.T @ u_dZ
+            sb[l] += u_dZ.sum(0)
+            if l > 0:
+                u_mixed = mean_aggregate_adjoint(blk.blk_indptr, blk.blk_src, u_dZ @ Wn.T, mixed.shape[0])
+                u_mixed[:n_dst] += u_dZ @ Ws.T
+                rows_add_into(u_hid[l], blk.shuffle_src_row, u_mixed)
+    return sws, swn, sb, n_undecided
+
+
+def grad_err(a: np.ndarray, o: np.ndarray, slack: np.ndarray, floor: float = 1e-2) -> float:
+    """max_rel_err after the part of |a - o| that undecidable ReLU decisions may explain
+    (relu_decision_slack) has been taken off."""
+    a = np.asarray(a, np.float64); o = np.asarray(o, np.float64)
+    if o.size == 0:
+        return 0.0
+    scale = np.maximum(np.abs(o), floor * np.abs(o).max())
+    scale = np.where(scale == 0, 1.0, scale)
+    return float((np.maximum(np.abs(a - o) - slack, 0.0) / scale).max())
+
+
 def softmax_xent(logits: np.ndarray, labels: np.ndarray):
     """Mean softmax cross-entropy and its gradient w.r.t. the logits (the harness-side loss)."""
     z = logits - logits.max(1, keepdims=True)

@@ -773,3 +773,4 @@ extern "C" int gsplit_softmax_xent(gsplit_ctx *ctx, const float *d_logits, int32
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;
 }
+

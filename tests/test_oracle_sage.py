@@ -171,3 +171,32 @@ def test_bf16_storage_forward_close_to_fp32(small):
     c = R.sp_forward(b, x0, p, store_bf16=True).logits
     err = np.abs(c - a).max() / np.abs(a).max()      # bf16 keeps 8 significant bits
     assert 0 < err < 2e-2
+
+
+def test_relu_decision_slack_bounds_a_flipped_decision(small):
+    """The slack must cover what flipping the most nearly undecided ReLU does to the gradients,
+    and must vanish when no pre-activation is near zero."""
+    w, ip, ix, pm, tg, b, u, p = small
+    feat, lab = _np(w.feat), _np(w.labels)
+    x0 = R.gather_rows(feat, b.local_cat(0))
+    y = lab[tg[b.target_perm]]
+    fwd = R.sp_forward(b, x0, p)
+    g = R.softmax_xent(fwd.logits, y)[1]
+    bwd = R.sp_backward(b, fwd, p, g)
+    sws, swn, sb, n0 = R.relu_decision_slack(b, fwd, p, bwd, rel_tau=0.0)
+    assert n0 == 0 and all(float(x.max()) == 0.0 for x in sws + swn + sb)
+    # flip the decision of the entry of layer 0 closest to zero and recompute the gradients
+    l, s = 0, 1
+    z = fwd.z[l][s]
+    i, c = np.unravel_index(np.abs(z).argmin(), z.shape)
+    tau = float(np.abs(z[i, c])) / max(float(np.abs(zz).max()) for zz in fwd.z[l]) * 1.0001
+    sws, swn, sb, n1 = R.relu_decision_slack(b, fwd, p, bwd, rel_tau=tau)
+    assert n1 >= 1
+    flipped = R.Forward(fwd.logits, fwd.hidden, fwd.mixed, fwd.mean, [[zz.copy() for zz in row] for row in fwd.z])
+    flipped.z[l][s][i, c] = -z[i, c]
+    bwd2 = R.sp_backward(b, flipped, p, g)
+    for k in range(w.n_layers):
+        assert (np.abs(bwd2.gw_self[k] - bwd.gw_self[k]) <= sws[k] * (1 + 1e-9) + 1e-18).all()
+        assert (np.abs(bwd2.gw_neigh[k] - bwd.gw_neigh[k]) <= swn[k] * (1 + 1e-9) + 1e-18).all()
+        assert (np.abs(bwd2.gbias[k] - bwd.gbias[k]) <= sb[k] * (1 + 1e-9) + 1e-18).all()
+    assert np.abs(bwd2.gw_self[0] - bwd.gw_self[0]).max() > 0

@@ -35,15 +35,15 @@ def _gen(device, seed: int) -> torch.Generator:
     return g
 
 
-def rmat_edges(scale: int, n_draws: int, a: float, b: float, c: float, *, seed: int,
-               device="cpu", chunk: int = 1 << 25):
-    """Draw `n_draws` directed (src, dst) pairs from the recursive-matrix model on 2**scale ids.
+def rmat_edge_chunks(scale: int, n_draws: int, a: float, b: float, c: float, *, seed: int,
+                     device="cpu", chunk: int = 1 << 26):
+    """Yield `n_draws` directed (src, dst) pairs from the recursive-matrix model on 2**scale ids,
+    `chunk` pairs at a time.
 
     Each of the `scale` bit levels picks one of four quadrants with probabilities (a, b, c, 1-a-b-c):
     a = (0,0), b = (0,1), c = (1,0), d = (1,1) for the (src bit, dst bit) pair.
     """
     g = _gen(device, seed)
-    srcs, dsts = [], []
     done = 0
     while done < n_draws:
         m = min(chunk, n_draws - done)
@@ -55,10 +55,63 @@ def rmat_edges(scale: int, n_draws: int, a: float, b: float, c: float, *, seed: 
             dbit = (((u >= a) & (u < a + b)) | (u >= a + b + c)).to(torch.int64)
             src = (src << 1) | sbit
             dst = (dst << 1) | dbit
-        srcs.append(src)
-        dsts.append(dst)
+        yield src, dst
         done += m
-    return torch.cat(srcs), torch.cat(dsts)
+
+
+def rmat_edges(scale: int, n_draws: int, a: float, b: float, c: float, *, seed: int, device="cpu",
+               chunk: int = 1 << 26):
+    parts = list(rmat_edge_chunks(scale, n_draws, a, b, c, seed=seed, device=device, chunk=chunk))
+    return torch.cat([p[0] for p in parts]), torch.cat([p[1] for p in parts])
+
+
+def _unique_sorted(keys: torch.Tensor, limit: int = (1 << 31) - (1 << 24)) -> torch.Tensor:
+    """torch.unique (sorted) for inputs of any length: the device sort handles fewer than 2**31
+    elements, so longer inputs are cut at splitters taken from a sorted random sample and every
+    part is deduplicated on its own (parts are disjoint value ranges, so concatenation is sorted)."""
+    n = keys.numel()
+    if n <= limit:
+        return torch.unique(keys)
+    parts = 2 * ((n + limit - 1) // limit)
+    g = _gen(keys.device, 12345)
+    sample = keys[torch.randint(0, n, (1 << 20,), generator=g, device=keys.device)]
+    sample = torch.sort(sample).values
+    cuts = sample[torch.arange(1, parts, device=keys.device) * (sample.numel() // parts)]
+    cuts = torch.unique(cuts)
+    out = []
+    lo = None
+    step = 1 << 29
+    for i in range(cuts.numel() + 1):
+        hi = cuts[i] if i < cuts.numel() else None
+        piece = []
+        for s0 in range(0, n, step):                      # select in slices: no op sees 2**31 elements
+            kk = keys[s0:s0 + step]
+            sel = torch.ones(kk.numel(), dtype=torch.bool, device=keys.device) if lo is None else kk >= lo
+            if hi is not None:
+                sel &= kk < hi
+            piece.append(kk[sel])
+        part = torch.cat(piece)
+        del piece
+        assert part.numel() <= limit, "splitters too coarse"
+        out.append(torch.unique(part))
+        del part
+        lo = hi
+    return torch.cat(out)
+
+
+def csr_from_keys(keys: torch.Tensor, n_vertices: int, *, index64: bool):
+    """CSR from sorted, duplicate-free keys src * n_vertices + dst."""
+    bounds = torch.arange(n_vertices + 1, dtype=torch.int64, device=keys.device) * n_vertices
+    indptr = torch.searchsorted(keys, bounds)
+    cols = torch.empty(keys.numel(), dtype=torch.int32, device=keys.device)
+    step = 1 << 29
+    for s0 in range(0, keys.numel(), step):
+        kk = keys[s0:s0 + step]
+        cols[s0:s0 + step] = (kk - torch.div(kk, n_vertices, rounding_mode="floor") * n_vertices).to(torch.int32)
+    if not index64:
+        assert int(indptr[-1]) < 2 ** 31
+        indptr = indptr.to(torch.int32)
+    return indptr.contiguous(), cols
 
 
 def build_csr(src: torch.Tensor, dst: torch.Tensor, n_vertices: int, *, symmetrise: bool,
@@ -68,19 +121,8 @@ def build_csr(src: torch.Tensor, dst: torch.Tensor, n_vertices: int, *, symmetri
     src, dst = src[keep], dst[keep]
     if symmetrise:
         src, dst = torch.cat([src, dst]), torch.cat([dst, src])
-    keys = torch.unique(src * n_vertices + dst)  # sorted ascending => rows sorted, no dups
-    del src, dst
-    rows = torch.div(keys, n_vertices, rounding_mode="floor")
-    cols = (keys - rows * n_vertices).to(torch.int32)
-    del keys
-    deg = torch.bincount(rows, minlength=n_vertices)
-    del rows
-    indptr = torch.zeros(n_vertices + 1, dtype=torch.int64, device=cols.device)
-    indptr[1:] = torch.cumsum(deg, 0)
-    if not index64:
-        assert int(indptr[-1]) < 2 ** 31
-        indptr = indptr.to(torch.int32)
-    return indptr.contiguous(), cols.contiguous()
+    keys = _unique_sorted(src * n_vertices + dst)  # sorted ascending => rows sorted, no dups
+    return csr_from_keys(keys, n_vertices, index64=index64)
 
 
 def rmat_graph(n_vertices: int, n_directed_target: int, abc: Sequence[float], *, seed: int,
@@ -89,40 +131,47 @@ def rmat_graph(n_vertices: int, n_directed_target: int, abc: Sequence[float], *,
     """R-MAT graph with about `n_directed_target` directed edges after clean-up.
 
     ids >= n_vertices are rejected (scale is the next power of two); a seeded random relabelling
-    spreads the hubs over the id range unless permute_ids is False.  If `exact_draws` is given that
-    many pairs are drawn once (the Tiny workload fixes the number of draws, not of edges);
-    otherwise batches are drawn until the cleaned edge count reaches the target.
+    spreads the hubs over the id range unless permute_ids is False; self loops and duplicates are
+    removed; with `symmetrise` every edge is stored in both directions.  If `exact_draws` is given
+    that many pairs are drawn once (the Tiny workload fixes the number of draws, not of edges);
+    otherwise batches are drawn until the cleaned edge count reaches the target.  Everything runs
+    chunk by chunk, so no single tensor op sees more than 2**30 elements.
     """
     scale = max(1, math.ceil(math.log2(n_vertices)))
     a, b, c = abc
-    if exact_draws is not None:
-        s, d = rmat_edges(scale, exact_draws, a, b, c, seed=seed + _OFF_GRAPH, device=device)
-    else:
-        per_dir = n_directed_target // (2 if symmetrise else 1)
-        s = torch.empty(0, dtype=torch.int64, device=device)
-        d = torch.empty(0, dtype=torch.int64, device=device)
-        have, rnd = 0, 0
-        while have < n_directed_target:
-            need = max(per_dir // 8, int((n_directed_target - have) / (2 if symmetrise else 1) * 1.15))
-            s2, d2 = rmat_edges(scale, need, a, b, c, seed=seed + _OFF_GRAPH + 1000 * rnd,
-                                device=device)
+    perm = torch.randperm(n_vertices, generator=_gen(device, seed + _OFF_PERM), device=device) \
+        if permute_ids else None
+    both = 2 if symmetrise else 1
+
+    def clean_keys(n_draws, sd):
+        out = []
+        for s2, d2 in rmat_edge_chunks(scale, n_draws, a, b, c, seed=sd, device=device):
             ok = (s2 != d2) & (s2 < n_vertices) & (d2 < n_vertices)
             s2, d2 = s2[ok], d2[ok]
-            if symmetrise:  # canonical orientation so that (u,v) and (v,u) are one undirected edge
-                lo, hi = torch.minimum(s2, d2), torch.maximum(s2, d2)
-                s2, d2 = lo, hi
-            k = torch.unique(torch.cat([s * n_vertices + d, s2 * n_vertices + d2]))
-            s = torch.div(k, n_vertices, rounding_mode="floor")
-            d = k - s * n_vertices
-            have = k.numel() * (2 if symmetrise else 1)
+            if perm is not None:
+                s2, d2 = perm[s2], perm[d2]
+            if symmetrise:  # canonical orientation: (u,v) and (v,u) are one undirected edge
+                s2, d2 = torch.minimum(s2, d2), torch.maximum(s2, d2)
+            out.append(s2 * n_vertices + d2)
+        return out
+
+    if exact_draws is not None:
+        keys = _unique_sorted(torch.cat(clean_keys(exact_draws, seed + _OFF_GRAPH)))
+    else:
+        keys = torch.empty(0, dtype=torch.int64, device=device)
+        rnd = 0
+        while keys.numel() * both < n_directed_target:
+            need = max(n_directed_target // both // 8,
+                       int((n_directed_target - keys.numel() * both) / both * 1.15))
+            keys = _unique_sorted(torch.cat([keys] + clean_keys(need, seed + _OFF_GRAPH + 1000 * rnd)))
             rnd += 1
-            del k, s2, d2
-    ok = (s < n_vertices) & (d < n_vertices)
-    s, d = s[ok], d[ok]
-    if permute_ids:
-        perm = torch.randperm(n_vertices, generator=_gen(device, seed + _OFF_PERM), device=device)
-        s, d = perm[s], perm[d]
-    return build_csr(s, d, n_vertices, symmetrise=symmetrise, index64=index64)
+    if symmetrise:
+        src = torch.div(keys, n_vertices, rounding_mode="floor")
+        swapped = (keys - src * n_vertices) * n_vertices + src
+        del src
+        keys = _unique_sorted(torch.cat([keys, swapped]))
+        del swapped
+    return csr_from_keys(keys, n_vertices, index64=index64)
 
 
 def pmap_random(n_vertices: int, n_splits: int, *, seed: int, device="cpu") -> torch.Tensor:
@@ -138,8 +187,9 @@ def pmap_range(n_vertices: int, n_splits: int, *, device="cpu") -> torch.Tensor:
 
 
 def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) -> torch.Tensor:
-    """Locality map: rank vertices by BFS visit order (from the max-degree vertex, restarting at
-    the smallest unvisited id) and cut the ranking into n_splits equal blocks."""
+    """Locality map: rank vertices by BFS visit order from the max-degree vertex (ties inside a
+    level by id), vertices the search does not reach follow in id order; the ranking is cut into
+    n_splits equal blocks."""
     dev = indptr.device
     n = indptr.numel() - 1
     ip = indptr.to(torch.int64)
@@ -147,38 +197,35 @@ def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) 
     rank = torch.full((n,), -1, dtype=torch.int64, device=dev)
     next_rank = 0
     frontier = torch.argmax(deg).reshape(1)
-    scan_from = 0
-    while next_rank < n:
-        if frontier.numel() == 0:
-            rest = torch.nonzero(rank[scan_from:] < 0)
-            if rest.numel() == 0:
-                break
-            # all remaining unvisited vertices with no edges get ranks in id order at once
-            first = scan_from + int(rest[0])
-            scan_from = first
-            if int(deg[first]) == 0:
-                iso = torch.nonzero((rank < 0) & (deg == 0)).flatten()
-                rank[iso] = next_rank + torch.arange(iso.numel(), device=dev)
-                next_rank += iso.numel()
-                continue
-            frontier = torch.tensor([first], device=dev)
-        new = frontier[rank[frontier] < 0]
-        new = torch.unique(new)
-        rank[new] = next_rank + torch.arange(new.numel(), device=dev)
-        next_rank += new.numel()
-        if new.numel() == 0:
-            frontier = new
-            continue
-        starts, lens = ip[new], deg[new]
-        tot = int(lens.sum())
-        if tot == 0:
-            frontier = new[:0]
-            continue
-        seg = torch.repeat_interleave(torch.arange(new.numel(), device=dev), lens)
-        offs = torch.arange(tot, device=dev) - torch.repeat_interleave(
-            torch.cumsum(lens, 0) - lens, lens)
-        nb = indices[starts[seg] + offs].to(torch.int64)
-        frontier = torch.unique(nb[rank[nb] < 0])
+    while frontier.numel() > 0:
+        rank[frontier] = next_rank + torch.arange(frontier.numel(), device=dev)
+        next_rank += frontier.numel()
+        # expand the level in slices so that no temporary exceeds about 2**28 entries
+        nxt = []
+        lens_all = deg[frontier]
+        csum = torch.cumsum(lens_all, 0)
+        start = 0
+        while start < frontier.numel():
+            base = int(csum[start - 1]) if start > 0 else 0
+            stop = int(torch.searchsorted(csum, torch.tensor(base + (1 << 28), device=dev), right=True))
+            stop = max(stop, start + 1)
+            f = frontier[start:stop]
+            lens = lens_all[start:stop]
+            tot = int(lens.sum())
+            if tot > 0:
+                seg = torch.repeat_interleave(torch.arange(f.numel(), device=dev), lens)
+                offs = torch.arange(tot, device=dev) - torch.repeat_interleave(torch.cumsum(lens, 0) - lens, lens)
+                nb = indices[ip[f][seg] + offs].to(torch.int64)
+                nb = nb[rank[nb] < 0]
+                if nb.numel():
+                    nxt.append(torch.unique(nb))
+                del seg, offs, nb
+            start = stop
+        frontier = torch.unique(torch.cat(nxt)) if nxt else frontier[:0]
+        if frontier.numel():
+            frontier = frontier[rank[frontier] < 0]
+    rest = torch.nonzero(rank < 0).flatten()
+    rank[rest] = next_rank + torch.arange(rest.numel(), device=dev)
     return torch.div(rank * n_splits, n, rounding_mode="floor").clamp(0, n_splits - 1).to(torch.uint8)
 
 
@@ -293,6 +340,44 @@ def medium(device="cpu", seed: int = MASTER_SEED, n_splits: int = 4, scale_down:
     pmap = pmap_range(n, n_splits, device=device)
     name = "medium" if scale_down == 1 else f"medium/{scale_down}"
     return _finish(name, n, indptr, indices, pmap, n_splits, [100, 256, 256, 47], [15, 10, 5], 1024,
+                   seed, device)
+
+
+def large(device="cuda", seed: int = MASTER_SEED, n_splits: int = 4, feat_dtype=torch.float32,
+          scale_down: int = 1, batch: int = 4096, fanouts=(15, 10, 5), dims=(128, 256, 256, 172),
+          progress=None) -> Workload:
+    """111M vertices, 1.6B directed edges (not symmetrised: row v lists what v aggregates from),
+    int64 indptr; 128-d features (fp32 or bf16), 172 classes; BFS-block partition map; batch 4096;
+    fanouts [15,10,5]; hidden 256.  `scale_down` divides vertex and edge counts."""
+    say = progress or (lambda m: None)
+    n = 111_000_000 // scale_down
+    m = 1_600_000_000 // scale_down
+    say(f"large: drawing about {m} directed edges on {n} vertices")
+    indptr, indices = rmat_graph(n, m, (0.57, 0.19, 0.19), seed=seed, symmetrise=False,
+                                 permute_ids=True, index64=True, device=device)
+    say(f"large: CSR built, {indices.numel()} edges; partition map")
+    pmap = pmap_bfs_blocks(indptr, indices, n_splits)
+    say("large: features")
+    name = "large" if scale_down == 1 else f"large/{scale_down}"
+    return _finish(name, n, indptr, indices, pmap, n_splits, list(dims), list(fanouts), batch, seed,
+                   device, feat_dtype=feat_dtype)
+
+
+def skewed(device="cuda", seed: int = MASTER_SEED, n_splits: int = 4, scale_down: int = 1,
+           progress=None) -> Workload:
+    """65M vertices, 3.6B directed edges (symmetric), R-MAT(.6,.15,.15,.1) without id permutation
+    (hubs stay clustered), int64 indptr; 128-d fp32 features; 64 classes; contiguous-range map;
+    batch 4096; fanouts [20,20,20]; hidden 256."""
+    say = progress or (lambda m: None)
+    n = 65_000_000 // scale_down
+    m = 3_600_000_000 // scale_down
+    say(f"skewed: drawing about {m} directed edges on {n} vertices")
+    indptr, indices = rmat_graph(n, m, (0.6, 0.15, 0.15), seed=seed, symmetrise=True,
+                                 permute_ids=False, index64=True, device=device)
+    say(f"skewed: CSR built, {indices.numel()} edges")
+    pmap = pmap_range(n, n_splits, device=device)
+    name = "skewed" if scale_down == 1 else f"skewed/{scale_down}"
+    return _finish(name, n, indptr, indices, pmap, n_splits, [128, 256, 256, 64], [20, 20, 20], 4096,
                    seed, device)
 
 
