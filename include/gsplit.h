@@ -149,7 +149,11 @@ GSPLIT_API int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int3
  * act = ReLU except on the last layer; an empty neighbourhood has mean 0.  Weights are row-major
  * [dims[l] x dims[l+1]] float32 (HOST arrays of DEVICE pointers), biases [dims[l+1]] float32.
  * dtype selects how activations are stored and multiplied: GSPLIT_F32 (fp32 storage, fp32 MFMA) or
- * GSPLIT_BF16 (bf16 features/activations/weights into the matrix cores, fp32 accumulation). */
+ * GSPLIT_BF16: features, activations between layers, the assembled layer inputs and a converted
+ * copy of the weights are bfloat16 (round to nearest even) and the forward and input-gradient
+ * products run on the bf16 matrix cores with float accumulation; the weight-gradient product,
+ * biases, logits and all gradients stay float.  GSPLIT_BF16 needs dims[0..L-1] to be multiples
+ * of 4 and d_feat_local to hold bfloat16 rows. */
 typedef struct {
     int32_t             dtype;
     const int32_t      *dims;        /* HOST [L+1] */

@@ -338,8 +338,9 @@ def sp_forward(batch: Batch, feat_local_cat: np.ndarray, params: SageParams,
                store_bf16: bool = False) -> Forward:
     """Algorithm 2, bottom-up.  feat_local_cat = input features of local_cat[0] rows.
 
-    With store_bf16 the values the device stores between layers (features, weights, activations)
-    are first rounded to bfloat16; the arithmetic itself stays in float64."""
+    With store_bf16 every value the device holds in bfloat16 (features, weights, activations
+    between layers, and the neighbourhood mean that enters the matrix product) is first rounded to
+    bfloat16; the arithmetic itself stays in float64."""
     S, L = batch.n_splits, batch.n_layers
     q = (lambda a: to_bf16_rne(np.asarray(a, np.float32)).astype(np.float64)) if store_bf16 \
         else (lambda a: np.asarray(a, np.float64))
@@ -355,6 +356,8 @@ def sp_forward(batch: Batch, feat_local_cat: np.ndarray, params: SageParams,
             mixed = rows_take(hidden[l], blk.shuffle_src_row)
             # local_hidden = gnn_layer(edges[l], mixed_hidden)
             M = mean_aggregate(blk.blk_indptr, blk.blk_src, mixed)
+            if store_bf16:          # the mean is an operand of the bf16 matrix product: stored rounded
+                M = q(M)
             Z = mixed[:n_dst] @ Ws + M @ Wn + b
             H = Z if l == L - 1 else np.maximum(Z, 0.0)
             parts.append(H)
@@ -404,9 +407,13 @@ def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.
             gwn[l] += M.T @ dZ
             gb[l] += dZ.sum(0)
             if l > 0:
-                dmixed = mean_aggregate_adjoint(blk.blk_indptr, blk.blk_src, dZ @ Wn.T,
+                # with bf16 storage the input-gradient product runs on the bf16 matrix cores, so
+                # its operand dZ is rounded like every other operand of such a product (the
+                # weight-gradient product above stays in float)
+                dZq = q(dZ) if store_bf16 else dZ
+                dmixed = mean_aggregate_adjoint(blk.blk_indptr, blk.blk_src, dZq @ Wn.T,
                                                 mixed.shape[0])
-                dmixed[:n_dst] += dZ @ Ws.T
+                dmixed[:n_dst] += dZq @ Ws.T
                 rows_add_into(ghid[l], blk.shuffle_src_row, dmixed)
     return Backward(gws, gwn, gb, ghid)
 

@@ -241,6 +241,7 @@ class Context:
     def gsplit_sage_fwd(self, params: SageParams, feat_local: torch.Tensor, logits: torch.Tensor):
         assert feat_local.is_cuda and feat_local.is_contiguous() and logits.is_cuda and logits.is_contiguous()
         assert logits.dtype == torch.float32
+        assert feat_local.dtype == (torch.bfloat16 if params.dtype == GSPLIT_BF16 else torch.float32)
         self._fwd_keep = (params, feat_local)
         self._check(self.lib.gsplit_sage_fwd(self.h, C.byref(params.c), feat_local.data_ptr(),
                                              logits.data_ptr(), _stream()))

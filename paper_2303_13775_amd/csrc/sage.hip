@@ -115,7 +115,16 @@ constexpr int GWM = 2, GWN = 4, GNT = 64 * GWM * GWN;
 template <int ROWS>
 constexpr int lds_words() { return ROWS * KC_LD > BK * (ROWS + 4) ? ROWS * KC_LD : BK * (ROWS + 4); }
 
-template <int ROWS, bool KC, int VW, int NT, class F>
+__device__ __forceinline__ uint16_t f2bf(float f) {          // round to nearest, ties to even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 16); }
+
+// SRC_H: the source matrix holds bfloat16; the raw halves travel through the registers and are
+// widened to float (exactly) when the tile is written to LDS.
+template <int ROWS, bool KC, int VW, int NT, class F, bool SRC_H = false>
 struct Stager {
     static constexpr int NV = ROWS * BK / 4 / NT;
     static_assert(NV >= 1 && NV <= 8, "tile too small or too large for the workgroup");
@@ -128,16 +137,21 @@ struct Stager {
     __device__ __forceinline__ void fetch(int v, const F &f, int outer, int inner, int inner_end, bool ok) {
         if (VW == 4) {
             bool in;
-            const float *p = f.template at<4>(outer, inner, in);
-            reg[v] = *reinterpret_cast<const float4 *>(p);
+            if (SRC_H) {
+                const uint2 raw = *reinterpret_cast<const uint2 *>(f.template at<4>(outer, inner, in));
+                reg[v].x = __uint_as_float(raw.x);
+                reg[v].y = __uint_as_float(raw.y);
+            } else {
+                reg[v] = *reinterpret_cast<const float4 *>(f.template at<4>(outer, inner, in));
+            }
             keep |= (in && ok && inner < inner_end) ? (0xFu << (4 * v)) : 0u;
         } else {
             float t[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 bool in;
-                const float *p = f.template at<1>(outer, inner + j, in);
-                t[j] = *p;
+                if (SRC_H) t[j] = __uint_as_float((uint32_t)*reinterpret_cast<const uint16_t *>(f.template at<1>(outer, inner + j, in)));
+                else t[j] = *reinterpret_cast<const float *>(f.template at<1>(outer, inner + j, in));
                 keep |= (in && ok && inner + j < inner_end) ? (1u << (4 * v + j)) : 0u;
             }
             reg[v] = make_float4(t[0], t[1], t[2], t[3]);
@@ -161,6 +175,15 @@ struct Stager {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             float4 w = reg[v];
+            if (SRC_H) {
+                if (VW == 4) {
+                    const uint32_t lo = __float_as_uint(reg[v].x), hi = __float_as_uint(reg[v].y);
+                    w = make_float4(bf2f(lo & 0xFFFFu), bf2f(lo >> 16), bf2f(hi & 0xFFFFu), bf2f(hi >> 16));
+                } else {
+                    w = make_float4(bf2f(__float_as_uint(reg[v].x)), bf2f(__float_as_uint(reg[v].y)),
+                                    bf2f(__float_as_uint(reg[v].z)), bf2f(__float_as_uint(reg[v].w)));
+                }
+            }
             w.x = (keep >> (4 * v)) & 1u ? w.x : 0.f;
             w.y = (keep >> (4 * v + 1)) & 1u ? w.y : 0.f;
             w.z = (keep >> (4 * v + 2)) & 1u ? w.z : 0.f;
@@ -187,7 +210,7 @@ __device__ __forceinline__ void read_frag(const float *lds, int row, int oct, in
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF>
+template <int BM, int BN, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF, bool A_H = false>
 __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int m_end, const int n_end,
                                           const int k_begin, const int k_end, const AF &a, const BF &b,
                                           const EF &epi) {
@@ -210,7 +233,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    using SA = Stager<BM, A_KC, VA, GNT, AF>;
+    using SA = Stager<BM, A_KC, VA, GNT, AF, A_H>;
     using SB = Stager<BN, B_KC, VB, GNT, BF>;
     SA sa0, sa1;
     SB sb0, sb1;
@@ -300,6 +323,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 
 // ---- operand accessors and epilogues ---------------------------------------------------------
 __device__ const float g_one_then_zero[4] = {1.f, 0.f, 0.f, 0.f};
+__device__ const uint16_t g_one_then_zero_h[4] __attribute__((aligned(8))) = {0x3F80, 0, 0, 0};   // bf16 1, 0, 0, 0
 
 // Accessors return an address that is always safe to read VW floats from (indices are clamped into
 // the matrix; matrices have at least one row and VW columns) and say whether the element exists.
@@ -450,12 +474,12 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_in(MatRows dz, CatW w, EpiGra
 // scatter side of the shuffle index.  The ReLU of the layer below is applied on the way out, so
 // the result is that layer's dZ.  One lane group per row, 4 floats per lane; no atomics, and rows
 // that fed nothing get zeros.
-template <int LPR>
+template <int LPR, bool HACT_H>
 __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict__ gin, int D,
                                                          const int32_t *__restrict__ rev_ptr,
                                                          const int32_t *__restrict__ rev_cnt,
                                                          const int32_t *__restrict__ rev_list,
-                                                         const float *__restrict__ hact,
+                                                         const void *__restrict__ hact,
                                                          const GsLevelMeta *__restrict__ meta_lo, int S,
                                                          float *__restrict__ gout) {
     const int n_lo = meta_lo->front_off[S];
@@ -482,7 +506,13 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
                 const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
                 acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
             }
-            const float4 h = A4[(int64_t)u * nvec + c];
+            float4 h;
+            if (HACT_H) {
+                const uint2 raw = reinterpret_cast<const uint2 *>(hact)[(int64_t)u * nvec + c];
+                h = make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
+            } else {
+                h = A4[(int64_t)u * nvec + c];
+            }
             acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
             acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
             O4[(int64_t)u * nvec + c] = acc;
@@ -541,6 +571,8 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const float *__restrict__ 
     }
 }
 
+#include "sage_bf16.h"
+
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 int grid_1d(const gsplit_ctx *ctx, int64_t upper_threads) {
@@ -555,14 +587,22 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
     for (int l = 0; same && l <= L; ++l) same = sb.dims[l] == p->dims[l];
     if (same) return GSPLIT_OK;
     if (sb.ready) return gs_fail(ctx, GSPLIT_ESTATE, "sage: model shape changed; create a new context");
+    const size_t esz = p->dtype == GSPLIT_BF16 ? 2 : 4;
     for (int l = 1; l < L; ++l) {
-        int rc = gs_alloc(ctx, &sb.hidden[l], sizeof(float) * ctx->ub_front[l] * p->dims[l], "hidden");
+        int rc = gs_alloc(ctx, &sb.hidden[l], esz * ctx->ub_front[l] * p->dims[l], "hidden");
         if (rc) return rc;
         rc = gs_alloc(ctx, (void **)&sb.ghid[l], sizeof(float) * ctx->ub_front[l] * p->dims[l], "ghid");
         if (rc) return rc;
     }
     for (int l = 0; l < L; ++l) {
-        int rc = gs_alloc(ctx, &sb.xin[l], sizeof(float) * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
+        int rc = gs_alloc(ctx, &sb.xin[l], esz * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
+        if (rc) return rc;
+        if (p->dtype == GSPLIT_BF16) {
+            const int64_t np = (p->dims[l + 1] + 7) & ~7;
+            rc = gs_alloc(ctx, (void **)&sb.wstack[l], 2 * (size_t)(2 * p->dims[l]) * np, "bf16 weights");
+            if (rc) return rc;
+            rc = gs_alloc(ctx, (void **)&sb.wtrans[l], 2 * (size_t)p->dims[l + 1] * 2 * p->dims[l], "bf16 weights^T");
+        }
         if (rc) return rc;
         rc = gs_alloc(ctx, (void **)&sb.inv_cnt[l], sizeof(float) * ctx->ub_front[l + 1], "inverse counts");
         if (rc) return rc;
@@ -595,8 +635,13 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
 int check_params(gsplit_ctx *ctx, const gsplit_sage_params *p, const char *who) {
     if (!p || !p->dims || !p->d_w_self || !p->d_w_neigh || !p->d_bias)
         return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": NULL parameter block");
-    if (p->dtype != GSPLIT_F32)
-        return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": only GSPLIT_F32 is available in this build");
+    if (p->dtype != GSPLIT_F32 && p->dtype != GSPLIT_BF16)
+        return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": dtype must be GSPLIT_F32 or GSPLIT_BF16");
+    if (p->dtype == GSPLIT_BF16)
+        for (int l = 0; l < ctx->L; ++l)
+            if (p->dims[l] % 4 != 0)
+                return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": GSPLIT_BF16 needs input and hidden widths "
+                                                                      "that are multiples of 4");
     for (int l = 0; l <= ctx->L; ++l)
         if (p->dims[l] < 1 || p->dims[l] > 4096)
             return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": layer width out of range");
@@ -643,6 +688,53 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
     GsSageBuf &sb = ctx->sage;
+    if (p->dtype == GSPLIT_BF16) {
+        if (!aligned16(d_feat_local)) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_fwd: features must be 16-byte aligned");
+        WeightPrep wp;
+        int64_t wmax = 1;
+        for (int l = 0; l < L; ++l) {
+            wp.ws[l] = (const float *)p->d_w_self[l]; wp.wn[l] = (const float *)p->d_w_neigh[l];
+            wp.stacked[l] = sb.wstack[l]; wp.transposed[l] = sb.wtrans[l];
+            wp.D[l] = p->dims[l]; wp.N[l] = p->dims[l + 1];
+            wmax = std::max<int64_t>(wmax, (int64_t)2 * p->dims[l] * ((p->dims[l + 1] + 7) & ~7));
+        }
+        {
+            GsTimeScope ts(ctx, "prep_weights", -1, st);
+            hipLaunchKernelGGL(k_prep_weights_h, dim3((unsigned)std::min<int64_t>(128, gs_ceil_div(wmax, 256)), L),
+                               dim3(256), 0, st, wp);
+        }
+        for (int l = 0; l < L; ++l) {
+            const int D = p->dims[l], N = p->dims[l + 1];
+            const uint16_t *hin = l == 0 ? (const uint16_t *)d_feat_local : (const uint16_t *)sb.hidden[l];
+            const GsLayerBuf &B = ctx->layer[l];
+            const GsLevelMeta *mu = ctx->d_meta + (l + 1);
+            const int64_t ub = ctx->ub_front[l + 1];
+            {
+                GsTimeScope ts(ctx, "assemble_input", l, st);
+                uint16_t *X = (uint16_t *)sb.xin[l];
+                if (D / 4 <= 16)
+                    hipLaunchKernelGGL(k_assemble_input_h<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
+                                       B.blk_indptr, B.edge_row, B.self_row, mu, S, X, sb.inv_cnt[l]);
+                else if (D / 4 <= 32)
+                    hipLaunchKernelGGL(k_assemble_input_h<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
+                                       B.blk_indptr, B.edge_row, B.self_row, mu, S, X, sb.inv_cnt[l]);
+                else
+                    hipLaunchKernelGGL(k_assemble_input_h<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
+                                       B.blk_indptr, B.edge_row, B.self_row, mu, S, X, sb.inv_cnt[l]);
+            }
+            MatRowsH x{(const uint16_t *)sb.xin[l], 0, 2 * D};
+            MatRowsH wt{sb.wtrans[l], N, 2 * D};
+            EpiFwdH epi{l == L - 1 ? (void *)d_logits : sb.hidden[l + 1], (const float *)p->d_bias[l], N, 0,
+                        l < L - 1 ? 1 : 0, l == L - 1 ? 1 : 0};
+            dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(N, GBN));
+            GsTimeScope ts(ctx, "linear_fwd", l, st);
+            hipLaunchKernelGGL(k_sage_linear_fwd_h, grid, dim3(GNT), 0, st, x, wt, epi, mu, S);
+        }
+        GS_HIP(ctx, hipGetLastError());
+        sb.fwd_done = true;
+        sb.fwd_batch = ctx->batch_id;
+        return GSPLIT_OK;
+    }
     for (int l = 0; l < L; ++l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const float *hin = l == 0 ? (const float *)d_feat_local : (const float *)sb.hidden[l];
@@ -680,7 +772,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
     if (!sb.ready || !sb.fwd_done || sb.fwd_batch != ctx->batch_id)
         return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: needs gsplit_sage_fwd on the current batch first");
     for (int l = 0; l <= ctx->L; ++l)
-        if (sb.dims[l] != p->dims[l])
+        if (sb.dims[l] != p->dims[l] || sb.dtype != p->dtype)
             return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: parameters differ from the forward pass");
     hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
@@ -701,12 +793,16 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
         const bool vw = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
+        const bool h16 = p->dtype == GSPLIT_BF16;
         {
             const int kchunk = sb.kchunk[l];
             const int tm = (int)gs_ceil_div(2 * D + 1, GBM), tn = (int)gs_ceil_div(N, GBN);
             dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
             GsTimeScope ts(ctx, "grad_w", l, st);
-            if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
+            MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
+            if (h16 && vdz) hipLaunchKernelGGL((k_sage_grad_w_h<4, 4>), grid, dim3(GNT), 0, st, inh, dz, ew, kchunk, tm, tn, mu, S);
+            else if (h16) hipLaunchKernelGGL((k_sage_grad_w_h<4, 1>), grid, dim3(GNT), 0, st, inh, dz, ew, kchunk, tm, tn, mu, S);
+            else if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
             else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
             else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
             else hipLaunchKernelGGL((k_sage_grad_w<1, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
@@ -718,26 +814,39 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
             {
             GsTimeScope ts(ctx, "grad_in", l, st);
-            if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
+            MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
+            if (h16 && vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
+            else if (h16) hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
+            else if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
             else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
             else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
             else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
             }
             GsTimeScope ts(ctx, "pull_input_grad", l, st);
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
-            const float *hact = (const float *)sb.hidden[l];
+            const void *hact = sb.hidden[l];
             const int64_t ubl = ctx->ub_front[l];
-            if (D % 4 != 0) {
+            if (h16) {
+                if (D / 4 <= 16)
+                    hipLaunchKernelGGL((k_pull_input_grad<16, true>), dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
+                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                else if (D / 4 <= 32)
+                    hipLaunchKernelGGL((k_pull_input_grad<32, true>), dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
+                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                else
+                    hipLaunchKernelGGL((k_pull_input_grad<64, true>), dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
+                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+            } else if (D % 4 != 0) {
                 hipLaunchKernelGGL(k_pull_input_grad_any, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, (const float *)hact, ml, S, sb.ghid[l]);
             } else if (D / 4 <= 16) {
-                hipLaunchKernelGGL(k_pull_input_grad<16>, dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
+                hipLaunchKernelGGL((k_pull_input_grad<16, false>), dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
             } else if (D / 4 <= 32) {
-                hipLaunchKernelGGL(k_pull_input_grad<32>, dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
+                hipLaunchKernelGGL((k_pull_input_grad<32, false>), dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
             } else {
-                hipLaunchKernelGGL(k_pull_input_grad<64>, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
+                hipLaunchKernelGGL((k_pull_input_grad<64, false>), dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
             }
         }

@@ -14,6 +14,12 @@ from oracle import reference as R
 pytestmark = pytest.mark.gpu
 
 TOL_F32 = 1e-4
+TOL_BF16 = 1e-2
+# bf16 path: a stored operand that the two sides compute to 7 digits can still round to neighbouring
+# bfloat16 values (a 2^-8 relative step); such flips are unavoidable, multiply from layer to layer,
+# and move an output by a few 1e-4 of the largest output whatever its own size.  The error is
+# therefore measured against the largest output (floor 1): max|a - o| / max|o| < 1e-2.
+FLOOR_BF16 = 1.0
 
 
 def _dev():
@@ -168,23 +174,24 @@ def test_gather_is_exact(dim, dtype):
     ctx.close()
 
 
-def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None):
-    from paper_2303_13775_amd import Context, SageParams
+def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None, bf16=False):
+    from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16, GSPLIT_F32
     S = n_splits or w.n_splits
     pm = w.pmap if pmap is None else pmap
     ctx = Context(w.indptr.to(dev), w.indices.to(dev), pm.to(dev), S, w.fanouts, w.batch)
     tg = w.targets(it)
     ctx.gsplit_sample_split(tg.to(dev), seed, it)
-    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), device=dev)
-    ctx.gsplit_gather_features(w.feat.to(dev), x0)
+    table = w.feat.to(torch.bfloat16) if bf16 else w.feat
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=table.dtype, device=dev)
+    ctx.gsplit_gather_features(table.to(dev), x0)
     params = SageParams(w.dims, [t.to(dev) for t in w.w_self], [t.to(dev) for t in w.w_neigh],
-                        [t.to(dev) for t in w.bias])
+                        [t.to(dev) for t in w.bias], dtype=GSPLIT_BF16 if bf16 else GSPLIT_F32)
     logits = torch.empty((tg.numel(), w.dims[-1]), device=dev)
     ctx.gsplit_sage_fwd(params, x0, logits)
     ob = _oracle_batch(w, tg, seed, it, n_splits=S, pmap=pm.cpu().numpy())
     op = R.SageParams([t.numpy() for t in w.w_self], [t.numpy() for t in w.w_neigh],
                       [t.numpy() for t in w.bias])
-    of = R.sp_forward(ob, R.gather_rows(w.feat.numpy(), ob.local_cat(0)), op)
+    of = R.sp_forward(ob, R.gather_rows(table.float().numpy(), ob.local_cat(0)), op, store_bf16=bf16)
     lab = w.labels.numpy()[tg.numpy()[ob.target_perm]]
     _, g = R.softmax_xent(of.logits, lab)
     gws = [torch.full_like(t, 7.0, device=dev) for t in w.w_self]      # must be overwritten
@@ -192,8 +199,8 @@ def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None):
     gb = [torch.full_like(t, 7.0, device=dev) for t in w.bias]
     ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
     torch.cuda.synchronize()
-    obw = R.sp_backward(ob, of, op, g)
-    slack = R.relu_decision_slack(ob, of, op, obw)
+    obw = R.sp_backward(ob, of, op, g, store_bf16=bf16)
+    slack = R.relu_decision_slack(ob, of, op, obw, rel_tau=1e-3 if bf16 else 1e-5, store_bf16=bf16)
     res = dict(logits=logits.cpu().numpy(), gws=[t.cpu().numpy() for t in gws],
                gwn=[t.cpu().numpy() for t in gwn], gb=[t.cpu().numpy() for t in gb],
                perm=ob.target_perm, of=of, ob=obw, slack=slack)
@@ -223,6 +230,32 @@ def test_sage_forward_backward_within_tolerance(name):
         assert R.grad_err(r["gws"][l], r["ob"].gw_self[l], sws[l]) < TOL_F32, ("gw_self", l)
         assert R.grad_err(r["gwn"][l], r["ob"].gw_neigh[l], swn[l]) < TOL_F32, ("gw_neigh", l)
         assert R.grad_err(r["gb"][l], r["ob"].gbias[l], sb[l]) < TOL_F32, ("gbias", l)
+
+
+BF16_CASES = {
+    "tiny": lambda: workloads.tiny(),
+    "wide": lambda: workloads.custom(8000, 200000, dims=[128, 256, 256, 172], fanouts=[6, 5, 4], batch=256,
+                                     n_splits=4, pmap_kind="range", name="wide"),
+    "medium-dims": lambda: workloads.custom(30000, 900000, dims=[100, 256, 256, 47], fanouts=[15, 10, 5],
+                                            batch=512, n_splits=4, pmap_kind="range", name="mdims"),
+    "deep-S8": lambda: workloads.custom(20000, 500000, dims=[128, 256, 256, 256, 172], fanouts=[10, 10, 10, 10],
+                                        batch=300, n_splits=8, name="deep"),
+}
+
+
+@pytest.mark.parametrize("name", list(BF16_CASES))
+def test_sage_bf16_path_within_tolerance(name):
+    """bf16 storage + bf16 MFMA forward and input-gradient products (float accumulation, float
+    weight-gradient product) against the oracle that rounds the same stored values to bf16."""
+    dev = _dev()
+    w = BF16_CASES[name]()
+    r = _run_fwd_bwd(w, dev, seed=31, it=1, bf16=True)
+    assert R.max_rel_err(r["logits"], r["of"].logits, floor=FLOOR_BF16) < TOL_BF16
+    sws, swn, sb, _ = r["slack"]
+    for l in range(w.n_layers):
+        assert R.grad_err(r["gws"][l], r["ob"].gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_self", l)
+        assert R.grad_err(r["gwn"][l], r["ob"].gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_neigh", l)
+        assert R.grad_err(r["gb"][l], r["ob"].gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("gbias", l)
 
 
 def test_softmax_xent_matches_oracle():
