@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+BF16_MFMA_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 
 
 def parse():
@@ -30,7 +31,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="medium", choices=["medium", "tiny"])
+    ap.add_argument("--workload", default="medium", choices=["medium", "tiny", "large", "skewed", "sweep"])
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
+                    help="storage/compute type of the GraphSAGE layers (default f32; sweep: bf16)")
+    ap.add_argument("--splits", type=int, default=4, help="number of logical splits")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=60)
     ap.add_argument("--no-pipeline", action="store_true",
@@ -51,8 +55,10 @@ class Runner:
         from paper_2303_13775_amd import Context, SageParams
         self.torch = torch
         self.w, self.dev = w, dev
+        from paper_2303_13775_amd import GSPLIT_BF16, GSPLIT_F32
         self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
-        self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias)
+        self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias,
+                                 dtype=GSPLIT_BF16 if w.feat.dtype == torch.bfloat16 else GSPLIT_F32)
         self.x0 = torch.empty((self.ctx.gsplit_max_rows(0), w.dims[0]), dtype=w.feat.dtype, device=dev)
         self.logits = torch.empty((w.batch, w.dims[-1]), device=dev)
         self.glogits = torch.empty_like(self.logits)
@@ -153,8 +159,27 @@ def main():
     torch.cuda.set_device(dev)
 
     t0 = time.time()
-    w = workloads.medium(device=dev) if a.workload == "medium" else workloads.tiny(device=dev)
+    dtype = a.dtype or ("bf16" if a.workload == "sweep" else "f32")
+    fdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    say = lambda m: print(f"[bench] {m}", file=sys.stderr, flush=True)
+    if a.workload == "medium":
+        w = workloads.medium(device=dev, n_splits=a.splits)
+    elif a.workload == "tiny":
+        w = workloads.tiny(device=dev, n_splits=a.splits)
+    elif a.workload == "large":
+        w = workloads.large(device=dev, n_splits=a.splits, feat_dtype=fdt, progress=say)
+    elif a.workload == "skewed":
+        w = workloads.skewed(device=dev, n_splits=a.splits, progress=say)
+    else:   # split sweep on the large graph: 4 layers, fanout 10, batch 8192
+        w = workloads.large(device=dev, n_splits=a.splits, feat_dtype=fdt, batch=8192, fanouts=(10, 10, 10, 10),
+                            dims=(128, 256, 256, 256, 172), progress=say)
+        w.name = f"sweep-S{a.splits}"
+    if w.feat.dtype != fdt:
+        w.feat = w.feat.to(fdt)
     torch.cuda.synchronize()
+    torch.cuda.empty_cache()        # hand the generator's scratch back: the library allocates with hipMalloc
+    if a.workload == "sweep":       # tens of GB of buffers per context, kernels that fill the chip: one stream
+        a.no_pipeline = True
     t_gen = time.time() - t0
     r = Runner(w, dev)
     n_total = a.warmup + a.steps
@@ -220,7 +245,8 @@ def main():
                 add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
                 add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
             # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
-            add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + 4 * D) + nd * (4 + 4 * D) + nd * 8 * D)
+            es = w.feat.element_size()
+            add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
             # per destination: id + two indptr words read, count written; per edge: 4 read, 4 written,
             # one 8-byte table entry touched
             add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes) + edges[l] * 16)
@@ -241,8 +267,10 @@ def main():
         sec = ms / max(cnt, 1) * 1e-3
         if kind == "flops":
             ach = per_launch / sec / 1e12
-            return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+            on_bf16 = dtype == "bf16" and not label.startswith("grad_w")    # weight gradients stay on fp32 MFMA
+            peak = BF16_MFMA_PEAK_TFLOPS if on_bf16 else FP32_MFMA_PEAK_TFLOPS
+            return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": peak,
+                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
                     "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
         ach = per_launch / sec / 1e9
         return {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -255,7 +283,7 @@ def main():
         "metric": "mini-batches/sec (sample+split+gather+SAGE fwd/bwd) at 1 GPU",
         "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": dict(w.describe(), fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1),
                        schedule=("serial, one stream" if a.no_pipeline else
