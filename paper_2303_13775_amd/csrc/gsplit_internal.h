@@ -65,11 +65,11 @@ struct GsSageBuf {             // activations kept between forward and backward
     float   *ghid[GS_MAXL + 1] = {nullptr};     // d loss / d hidden of level 1..L
     float   *gtmp = nullptr;                    // [rows x 2*dim] input gradients before the reverse shuffle
     float   *inv_cnt[GS_MAXL] = {nullptr};      // 1 / (sampled neighbours) per destination row
+    float   *wstack32[GS_MAXL] = {nullptr};     // fp32 [2D x Npad] stacked weights, Npad = N rounded up to 4
     uint16_t *wstack[GS_MAXL] = {nullptr};      // bf16 [2D x Npad] stacked weights (bf16 mode)
     uint16_t *wtrans[GS_MAXL] = {nullptr};      // bf16 [N x 2D] transposed stacked weights
     float   *gw_part[GS_MAXL] = {nullptr};      // per-chunk partial weight gradients
-    int      kchunk[GS_MAXL] = {0};             // destination rows per split-K chunk
-    int      nchunk[GS_MAXL] = {0};             // chunks at the upper bound (multiple of 8)
+    int      nchunk[GS_MAXL] = {0};             // slabs of gw_part (multiple of 8)
     bool     fwd_done = false;
     uint64_t fwd_batch = 0;
 };

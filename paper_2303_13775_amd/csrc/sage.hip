@@ -7,6 +7,7 @@
 //
 // Dense products run on the matrix cores: v_mfma_f32_32x32x2_f32 for fp32 storage.
 #include <algorithm>
+#include <type_traits>
 
 #include "gsplit_internal.h"
 
@@ -94,23 +95,39 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__r
 // ------------------------------------------------------------------------------------------
 // Tiled fp32 MFMA GEMM core:  C[M x N] = A[M x K] * B[K x N].
 //
-// Operands are described by accessors  at(outer, inner) -> const float* (or nullptr outside the
-// logical matrix; `inner` runs along memory).  An operand is used either K-contiguous (KC: outer
-// is the M or N index, inner is k) or K-major (KM: outer is k, inner is the M or N index); both
-// are staged into LDS with the layout they have in memory (16-byte copies when VW == 4):
+// Operands are described by accessors  at(outer, inner) -> const float* (clamped into the matrix;
+// `inner` runs along memory).  An operand is used either K-contiguous (KC: outer is the M or N
+// index, inner is k) or K-major (KM: outer is k, inner is the M or N index); both are staged into
+// LDS with the layout they have in memory (16-byte copies when VW == 4):
 //   KC: lds[row][k]   (row stride 36 words), MFMA fragments are one 128-bit read per 8 k
 //   KM: lds[k][row]   (row stride ROWS + 4), MFMA fragments are four 32-bit reads per 8 k
 // v_mfma_f32_32x32x2_f32 sums two k-slots (lane / 32 selects the slot).  Within a group of 8 k the
 // lower half-wave takes k = 0..3 and the upper half k = 4..7 over four consecutive MFMAs; A and B
 // use the same assignment, so the sum over k is complete whatever the order.
 //
-// Workgroup = 8 waves as 2 x 4 over a BM x BN tile (32 x 32 MFMA blocks per wave).
+// A workgroup always has 8 waves.  Tile<BM, BN, WM, WN, KS> lays them out WM x WN over a BM x BN
+// output tile and KS-fold over k: with KS > 1 the groups of 8 k inside every k-tile are dealt to KS
+// wave groups whose accumulators are added through LDS at the end.  Products with few rows use a
+// small tile with KS > 1, which shortens the dependent chain of k-tiles a workgroup walks and
+// yields more workgroups.
 // ------------------------------------------------------------------------------------------
 constexpr int BK = 32;
 constexpr int KC_LD = BK + 4;
-// workgroup = GWM x GWN waves; two waves share each SIMD, so one wave's LDS traffic and barrier
-// waits overlap the other's MFMAs
-constexpr int GWM = 2, GWN = 4, GNT = 64 * GWM * GWN;
+constexpr int GNT = 512;
+
+template <int BM_, int BN_, int WM_, int WN_, int KS_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, KS = KS_;
+    static constexpr int MI = BM / (32 * WM), NI = BN / (32 * WN);
+    static constexpr int NO = BK / 8 / KS;      // groups of 8 k per k-tile and wave
+    static constexpr int OCC = BM * BN >= 8192 ? 2 : 3;   // workgroups one compute unit holds (LDS, registers)
+    static_assert(WM * WN * KS * 64 == GNT, "a workgroup has 8 waves");
+    static_assert(MI >= 1 && NI >= 1 && MI * 32 * WM == BM && NI * 32 * WN == BN, "32 x 32 MFMA blocks");
+    static_assert(KS == 1 || KS == 2 || KS == 4, "k split");
+};
+using TileMid = Tile<64, 128, 2, 4, 1>;
+using TileLow = Tile<32, 128, 1, 4, 2>;
+using TileLowNarrow = Tile<32, 64, 1, 2, 4>;
 
 template <int ROWS>
 constexpr int lds_words() { return ROWS * KC_LD > BK * (ROWS + 4) ? ROWS * KC_LD : BK * (ROWS + 4); }
@@ -126,24 +143,64 @@ __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 
 // widened to float (exactly) when the tile is written to LDS.
 template <int ROWS, bool KC, int VW, int NT, class F, bool SRC_H = false>
 struct Stager {
-    static constexpr int NV = ROWS * BK / 4 / NT;
-    static_assert(NV >= 1 && NV <= 8, "tile too small or too large for the workgroup");
+    static constexpr int TOT = ROWS * BK / 4;                 // 4-word pieces of one tile
+    static constexpr int NV = (TOT + NT - 1) / NT;
+    static_assert(NV >= 1 && NV <= 8, "tile too large for the workgroup");
+    typedef typename std::conditional<SRC_H, uint16_t, float>::type E;
     float4 reg[NV];
     unsigned keep;   // 4 bits per register: which of its words exist in the matrix
+    // what does not change along k, prepared once (16-byte path): the row of a KC piece, the
+    // clamped M/N index of a KM piece
+    const E *fixed_row[KC ? NV : 1];
+    int fixed_tok[KC ? 1 : NV];
 
-    // Loads are unconditional (the accessor clamps the address into the matrix); words outside the
-    // matrix are zeroed only when the registers are written to LDS, so nothing depends on a load
-    // before that point and the loads of two k-tiles stay in flight.
+    // piece v of thread tid: (row, k / 4) for KC, (k, row / 4) for KM; false if the tile has no such piece
+    static __device__ __forceinline__ bool piece(int tid, int v, int &outer, int &inner4) {
+        if (KC) {
+            inner4 = tid & (BK / 4 - 1); outer = tid / (BK / 4) + (NT / (BK / 4)) * v;
+            return TOT % NT == 0 || outer < ROWS;
+        }
+        inner4 = tid % (ROWS / 4); outer = tid / (ROWS / 4) + (4 * NT / ROWS) * v;
+        return TOT % NT == 0 || outer < BK;
+    }
+    __device__ __forceinline__ void init(const F &f, int r0, int tid) {
+        if (VW != 4) return;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int o, i4;
+            piece(tid, v, o, i4);
+            bool in;
+            if (KC) fixed_row[v] = f.template at<4>(r0 + o, 0, in);
+            else fixed_tok[v] = f.tok(r0 + 4 * i4);
+        }
+    }
+    __device__ __forceinline__ void take(int v, const E *src) {
+        if (SRC_H) {
+            const uint2 raw = *reinterpret_cast<const uint2 *>(src);
+            reg[v].x = __uint_as_float(raw.x);
+            reg[v].y = __uint_as_float(raw.y);
+        } else {
+            reg[v] = *reinterpret_cast<const float4 *>(src);
+        }
+    }
+    // A k-tile that lies wholly inside [k_begin, k_end) needs no masking at all: M/N indices past
+    // the matrix read a clamped (valid) address and only feed outputs that are never stored.
+    __device__ __forceinline__ void load_full(const F &f, int k0, int tid) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int o, i4;
+            if (!piece(tid, v, o, i4)) continue;
+            if (KC) take(v, fixed_row[v] + k0 + 4 * i4);
+            else take(v, f.km(k0 + o, fixed_tok[v]));
+        }
+    }
+    // General form: loads are unconditional (the accessor clamps the address into the matrix);
+    // words outside the matrix are zeroed only when the registers are written to LDS, so nothing
+    // depends on a load before that point and the loads of two k-tiles stay in flight.
     __device__ __forceinline__ void fetch(int v, const F &f, int outer, int inner, int inner_end, bool ok) {
         if (VW == 4) {
             bool in;
-            if (SRC_H) {
-                const uint2 raw = *reinterpret_cast<const uint2 *>(f.template at<4>(outer, inner, in));
-                reg[v].x = __uint_as_float(raw.x);
-                reg[v].y = __uint_as_float(raw.y);
-            } else {
-                reg[v] = *reinterpret_cast<const float4 *>(f.template at<4>(outer, inner, in));
-            }
+            take(v, f.template at<4>(outer, inner, in));
             keep |= (in && ok && inner < inner_end) ? (0xFu << (4 * v)) : 0u;
         } else {
             float t[4];
@@ -162,39 +219,36 @@ struct Stager {
         keep = 0u;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            if (KC) {
-                const int kq = tid & 7, row = (tid >> 3) + (NT / 8) * v;
-                fetch(v, f, r0 + row, k0 + 4 * kq, k_end, r0 + row < r_end);
-            } else {
-                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (4 * NT / ROWS) * v;
-                fetch(v, f, k0 + kk, r0 + 4 * x, r_end, k0 + kk < k_end);
-            }
+            int o, i4;
+            if (!piece(tid, v, o, i4)) continue;
+            if (KC) fetch(v, f, r0 + o, k0 + 4 * i4, k_end, r0 + o < r_end);
+            else fetch(v, f, k0 + o, r0 + 4 * i4, r_end, k0 + o < k_end);
         }
     }
+    __device__ __forceinline__ float4 widened(int v) const {
+        if (!SRC_H) return reg[v];
+        if (VW == 4) {
+            const uint32_t lo = __float_as_uint(reg[v].x), hi = __float_as_uint(reg[v].y);
+            return make_float4(bf2f(lo & 0xFFFFu), bf2f(lo >> 16), bf2f(hi & 0xFFFFu), bf2f(hi >> 16));
+        }
+        return make_float4(bf2f(__float_as_uint(reg[v].x)), bf2f(__float_as_uint(reg[v].y)),
+                           bf2f(__float_as_uint(reg[v].z)), bf2f(__float_as_uint(reg[v].w)));
+    }
+    template <bool MASKED>
     __device__ __forceinline__ void store(float *lds, int tid) const {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            float4 w = reg[v];
-            if (SRC_H) {
-                if (VW == 4) {
-                    const uint32_t lo = __float_as_uint(reg[v].x), hi = __float_as_uint(reg[v].y);
-                    w = make_float4(bf2f(lo & 0xFFFFu), bf2f(lo >> 16), bf2f(hi & 0xFFFFu), bf2f(hi >> 16));
-                } else {
-                    w = make_float4(bf2f(__float_as_uint(reg[v].x)), bf2f(__float_as_uint(reg[v].y)),
-                                    bf2f(__float_as_uint(reg[v].z)), bf2f(__float_as_uint(reg[v].w)));
-                }
+            int o, i4;
+            if (!piece(tid, v, o, i4)) continue;
+            float4 w = widened(v);
+            if (MASKED) {
+                w.x = (keep >> (4 * v)) & 1u ? w.x : 0.f;
+                w.y = (keep >> (4 * v + 1)) & 1u ? w.y : 0.f;
+                w.z = (keep >> (4 * v + 2)) & 1u ? w.z : 0.f;
+                w.w = (keep >> (4 * v + 3)) & 1u ? w.w : 0.f;
             }
-            w.x = (keep >> (4 * v)) & 1u ? w.x : 0.f;
-            w.y = (keep >> (4 * v + 1)) & 1u ? w.y : 0.f;
-            w.z = (keep >> (4 * v + 2)) & 1u ? w.z : 0.f;
-            w.w = (keep >> (4 * v + 3)) & 1u ? w.w : 0.f;
-            if (KC) {
-                const int kq = tid & 7, row = (tid >> 3) + (NT / 8) * v;
-                *reinterpret_cast<float4 *>(&lds[row * KC_LD + 4 * kq]) = w;
-            } else {
-                const int x = tid % (ROWS / 4), kk = tid / (ROWS / 4) + (4 * NT / ROWS) * v;
-                *reinterpret_cast<float4 *>(&lds[kk * (ROWS + 4) + 4 * x]) = w;
-            }
+            if (KC) *reinterpret_cast<float4 *>(&lds[o * KC_LD + 4 * i4]) = w;
+            else *reinterpret_cast<float4 *>(&lds[o * (ROWS + 4) + 4 * i4]) = w;
         }
     }
 };
@@ -210,21 +264,23 @@ __device__ __forceinline__ void read_frag(const float *lds, int row, int oct, in
     }
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF, bool A_H = false>
+template <class T, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF, bool A_H = false>
 __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int m_end, const int n_end,
                                           const int k_begin, const int k_end, const AF &a, const BF &b,
                                           const EF &epi) {
+    constexpr int BM = T::BM, BN = T::BN, MI = T::MI, NI = T::NI, KS = T::KS, NO = T::NO;
     // two LDS stages and two register stages: k-tile t is multiplied out of LDS while tile t+1
     // sits in the other LDS stage and tile t+2 is in flight into registers, so a global load has
     // two iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
-    __shared__ __attribute__((aligned(16))) float As0[lds_words<BM>()];
-    __shared__ __attribute__((aligned(16))) float As1[lds_words<BM>()];
-    __shared__ __attribute__((aligned(16))) float Bs0[lds_words<BN>()];
-    __shared__ __attribute__((aligned(16))) float Bs1[lds_words<BN>()];
-    constexpr int MI = BM / (32 * GWM), NI = BN / (32 * GWN);
+    constexpr int AW = lds_words<BM>(), BW = lds_words<BN>();
+    constexpr int RED = (KS - 1) * T::WM * T::WN * MI * NI * 1024;   // accumulators handed over at the end
+    static_assert(RED <= 2 * (AW + BW), "k-split hand-over does not fit the staging area");
+    __shared__ __attribute__((aligned(16))) float lds[2 * (AW + BW)];
+    float *const As0 = lds, *const As1 = lds + AW, *const Bs0 = lds + 2 * AW, *const Bs1 = lds + 2 * AW + BW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int wm0 = (wave / GWN) * (BM / GWM), wn0 = (wave % GWN) * (BN / GWN);
+    const int kg = wave / (T::WM * T::WN), wv = wave % (T::WM * T::WN);
+    const int wm0 = (wv / T::WN) * (BM / T::WM), wn0 = (wv % T::WN) * (BN / T::WN);
     floatx16 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -244,18 +300,18 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     auto multiply = [&](const float *As, const float *Bs) {
         float af[2][MI][4], bf[2][NI][4];
 #pragma unroll
-        for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, 0, half, af[0][i]);
+        for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg, half, af[0][i]);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, 0, half, bf[0][j]);
+        for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg, half, bf[0][j]);
 #pragma unroll
-        for (int oct = 0; oct < BK / 8; ++oct) {
-            if (oct + 1 < BK / 8) {
+        for (int t = 0; t < NO; ++t) {
+            if (t + 1 < NO) {
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
-                    read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, oct + 1, half, af[(oct + 1) & 1][i]);
+                    read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg + KS * (t + 1), half, af[(t + 1) & 1][i]);
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, oct + 1, half, bf[(oct + 1) & 1][j]);
+                    read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg + KS * (t + 1), half, bf[(t + 1) & 1][j]);
             }
             __builtin_amdgcn_sched_barrier(0);   // reads of the next group stay ahead of these MFMAs
 #pragma unroll
@@ -264,61 +320,99 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[oct & 1][i][q], bf[oct & 1][j][q], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][i][q], bf[t & 1][j][q], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    // A k-tile wholly inside the k range takes the unmasked 16-byte path; only the last tile of a
+    // range can be partial (and every tile is treated so when an operand needs scalar loads).
+    auto load_tile = [&](SA &ra, SB &rb, int k0) {
+        const bool full = k0 + BK <= k_end;
+        if (VA == 4 && full) ra.load_full(a, k0, tid);
+        else ra.load(a, m0, m_end, k0, k_end, tid);
+        if (VB == 4 && full) rb.load_full(b, k0, tid);
+        else rb.load(b, n0, n_end, k0, k_end, tid);
+    };
+    auto store_tile = [&](const SA &ra, const SB &rb, float *As, float *Bs, int k0) {
+        const bool full = k0 + BK <= k_end;
+        if (VA == 4 && full) ra.template store<false>(As, tid);
+        else ra.template store<true>(As, tid);
+        if (VB == 4 && full) rb.template store<false>(Bs, tid);
+        else rb.template store<true>(Bs, tid);
     };
     // one k-tile: fetch tile k0 + 2 BK into the registers that held tile k0, multiply tile k0,
     // move tile k0 + BK from registers to the other LDS stage
     auto step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const float *As_cur, const float *Bs_cur,
                     float *As_nxt, float *Bs_nxt, int k0) {
-        if (k0 + 2 * BK < k_end) {
-            ra_cur.load(a, m0, m_end, k0 + 2 * BK, k_end, tid);
-            rb_cur.load(b, n0, n_end, k0 + 2 * BK, k_end, tid);
-        }
+        if (k0 + 2 * BK < k_end) load_tile(ra_cur, rb_cur, k0 + 2 * BK);
         multiply(As_cur, Bs_cur);
-        if (k0 + BK < k_end) {
-            ra_nxt.store(As_nxt, tid);
-            rb_nxt.store(Bs_nxt, tid);
-        }
+        if (k0 + BK < k_end) store_tile(ra_nxt, rb_nxt, As_nxt, Bs_nxt, k0 + BK);
         __syncthreads();
     };
 
-    sa0.load(a, m0, m_end, k_begin, k_end, tid);
-    sb0.load(b, n0, n_end, k_begin, k_end, tid);
-    if (k_begin + BK < k_end) {
-        sa1.load(a, m0, m_end, k_begin + BK, k_end, tid);
-        sb1.load(b, n0, n_end, k_begin + BK, k_end, tid);
-    }
-    sa0.store(As0, tid);
-    sb0.store(Bs0, tid);
+    sa0.init(a, m0, tid); sa1.init(a, m0, tid);
+    sb0.init(b, n0, tid); sb1.init(b, n0, tid);
+    load_tile(sa0, sb0, k_begin);
+    if (k_begin + BK < k_end) load_tile(sa1, sb1, k_begin + BK);
+    store_tile(sa0, sb0, As0, Bs0, k_begin);
     __syncthreads();
     for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
         step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
         if (k0 + BK < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BK);
     }
+    if (KS > 1) {
+        // every wave is past its last LDS read (the k loop ends on a barrier): wave groups 1.. hand
+        // their accumulators to group 0, which adds them in group order
+        constexpr int PER_WAVE = MI * NI * 1024;
+        if (kg > 0) {
+            float *dst = lds + ((kg - 1) * T::WM * T::WN + wv) * PER_WAVE + lane;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) dst[((i * NI + j) * 16 + r) * 64] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int g = 1; g < KS; ++g) {
+                const float *src = lds + ((g - 1) * T::WM * T::WN + wv) * PER_WAVE + lane;
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[i][j][r] += src[((i * NI + j) * 16 + r) * 64];
+            }
+        }
+    }
     // accumulator layout of the 32x32 block: register r of lane l holds
     // row (r / 4) * 8 + (l / 32) * 4 + (r % 4), column l % 32.
     // Per-column and per-row side inputs of the epilogue (bias, 1/count) are fetched up front so
     // that their latencies overlap instead of adding up in front of every store.
-    float colv[NI], rowv[MI][16];
+    if (kg == 0) {
+        float colv[NI], rowv[MI][16];
 #pragma unroll
-    for (int j = 0; j < NI; ++j) colv[j] = epi.col(n0 + wn0 + j * 32 + l32);
+        for (int j = 0; j < NI; ++j) colv[j] = epi.col(n0 + wn0 + j * 32 + l32);
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            rowv[i][r] = epi.row(m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3));
+            for (int r = 0; r < 16; ++r)
+                rowv[i][r] = epi.row(m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3));
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                const int n = n0 + wn0 + j * 32 + l32;
-                epi.store(m, n, acc[i][j][r], rowv[i][r], colv[j]);
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    const int n = n0 + wn0 + j * 32 + l32;
+                    epi.store(m, n, acc[i][j][r], rowv[i][r], colv[j]);
+                }
+    }
+    // the staging area is reused by the caller's next tile
+    if (KS > 1) __syncthreads();
 }
 
 // ---- operand accessors and epilogues ---------------------------------------------------------
@@ -336,6 +430,9 @@ struct MatRows {
         const int oc = min(o, rows - 1), ic = min(i, cols - VW);
         return p + (int64_t)oc * cols + ic;
     }
+    // K-major use, 16-byte pieces: tok() clamps the M/N index once, km() addresses row k < rows
+    __device__ __forceinline__ int tok(int i) const { return min(i, cols - 4); }
+    __device__ __forceinline__ const float *km(int k, int t) const { return p + (int64_t)k * cols + t; }
 };
 // plain row-major matrix followed by one column of ones (its product with dZ is the bias gradient)
 struct MatRowsOnes {
@@ -347,18 +444,9 @@ struct MatRowsOnes {
         const float *q = p + (int64_t)oc * cols + ic;
         return i == cols ? g_one_then_zero : q;
     }
-};
-// [W_self; W_neigh] stacked: row k of the 2 * D x N matrix
-struct CatW {
-    const float *Ws; const float *Wn; int D; int N;
-    template <int VW>
-    __device__ __forceinline__ const float *at(int k, int n, bool &in) const {
-        in = k < 2 * D && n < N;
-        const int nc = min(n, N - VW);
-        const int kc = min(k, 2 * D - 1);
-        const float *base = kc < D ? Ws : Wn;
-        const int kr = kc < D ? kc : kc - D;
-        return base + (int64_t)kr * N + nc;
+    __device__ __forceinline__ int tok(int i) const { return i >= cols ? -1 : min(i, cols - 4); }
+    __device__ __forceinline__ const float *km(int k, int t) const {
+        return t < 0 ? g_one_then_zero : p + (int64_t)k * cols + t;
     }
 };
 struct EpiFwd {
@@ -393,17 +481,45 @@ struct EpiGradIn {
     }
 };
 
-constexpr int GBM = 64, GBN = 128;
+// tile of the bf16 kernels
+constexpr int GBM = 64, GBN = 128, GWM = 2, GWN = 4;
 
-// Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer
-template <int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_linear_fwd(MatRows a, CatW b, EpiFwd epi,
+// Row-block products run as persistent workgroups: the launch has at most as many workgroups as the
+// chip holds at once (the host only knows an upper bound on the rows; workgroups without a tile
+// would otherwise queue behind the working ones and drain after them) and each walks the tiles
+// gid = blockIdx.x, + gridDim.x, ...  The id is decoded so that the column tiles of one row block
+// run on the same XCD (workgroups are dealt round-robin to the 8 XCDs) and share its L2.
+template <class T>
+__device__ __forceinline__ bool next_tile(int gid, int tiles_m, int tiles_n, int &m0, int &n0) {
+    const int xcd = gid & 7, j = gid >> 3;
+    const int tm = (j / tiles_n) * 8 + xcd;
+    m0 = tm * T::BM; n0 = (j % tiles_n) * T::BN;
+    return tm < tiles_m;
+}
+
+// Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer; b is the stacked
+// weight matrix, its columns padded to a multiple of 4
+template <class T, int VA, int VB>
+__global__ __launch_bounds__(GNT) void k_sage_linear_fwd(MatRows a, MatRows b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * GBM;
-    if (m0 >= n1) return;
+    const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (b.cols + T::BN - 1) / T::BN;
+    const int total = ((tiles_m + 7) & ~7) * tiles_n;
     a.rows = n1; epi.n1 = n1;
-    gemm_tile<GBM, GBN, true, false, VA, VB>(m0, blockIdx.y * GBN, n1, b.N, 0, a.cols, a, b, epi);
+    for (int gid = blockIdx.x; gid < total; gid += gridDim.x) {
+        int m0, n0;
+        if (!next_tile<T>(gid, tiles_m, tiles_n, m0, n0)) continue;
+        gemm_tile<T, true, false, VA, VB>(m0, n0, n1, b.cols, 0, a.cols, a, b, epi);
+    }
+}
+
+// Split-K geometry of the weight-gradient product, decided on the device from the actual number
+// of destination rows n1: as many chunks (a multiple of 8, at most nchunk) as keep rows_min rows
+// in each, every chunk a multiple of the k-tile.
+__device__ __forceinline__ int grad_w_chunk_rows(int n1, int nchunk, int rows_min) {
+    const int want = min(nchunk, max(8, ((n1 + rows_min - 1) / rows_min + 7) & ~7));
+    const int per = (n1 + want - 1) / want;
+    return max(BK, (per + BK - 1) & ~(BK - 1));
 }
 
 // Partial [dW_self; dW_neigh; db] = [X | 1]^T * dZ over one chunk of destination rows (split-K).
@@ -411,11 +527,12 @@ __global__ __launch_bounds__(GNT) void k_sage_linear_fwd(MatRows a, CatW b, EpiF
 // the workgroup id is decoded so that all tiles of a chunk land on the same XCD (workgroups are
 // dealt round-robin to the 8 XCDs) and share its L2.  Partials go to a per-chunk slab; a
 // fixed-order reduction follows (deterministic, no atomics).
-template <int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_grad_w(MatRowsOnes a, MatRows dz, EpiGradW epi, int kchunk,
-                                                     int tiles_m, int tiles_n,
+template <class T, int VA, int VB, class AF, bool A_H>
+__global__ __launch_bounds__(GNT) void k_sage_grad_w(AF a, MatRows dz, EpiGradW epi, int nchunk,
+                                                     int rows_min, int tiles_m, int tiles_n,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
+    const int kchunk = grad_w_chunk_rows(n1, nchunk, rows_min);
     const int tiles = tiles_m * tiles_n;
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
     const int tile = j % tiles, chunk = (j / tiles) * 8 + xcd;
@@ -424,20 +541,21 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_w(MatRowsOnes a, MatRows dz, 
     a.rows = n1; dz.rows = n1;
     const int k_end = min(n1, k_begin + kchunk);
     epi.part += (int64_t)chunk * epi.rows * epi.N;
-    gemm_tile<GBM, GBN, false, false, VA, VB>((tile % tiles_m) * GBM, (tile / tiles_m) * GBN, a.cols + 1,
-                                              dz.cols, k_begin, k_end, a, dz, epi);
+    gemm_tile<T, false, false, VA, VB, AF, MatRows, EpiGradW, A_H>(
+        (tile % tiles_m) * T::BM, (tile / tiles_m) * T::BN, a.cols + 1, dz.cols, k_begin, k_end, a, dz, epi);
 }
 
 // Sum the per-chunk partials in chunk order into the caller's gradient buffers, all layers in one
 // launch (blockIdx.y = layer).
 struct GradReduce {
     const float *part[GS_MAXL]; float *gws[GS_MAXL]; float *gwn[GS_MAXL]; float *gb[GS_MAXL];
-    int D[GS_MAXL]; int N[GS_MAXL]; int kchunk[GS_MAXL];
+    int D[GS_MAXL]; int N[GS_MAXL]; int nchunk[GS_MAXL]; int rows_min[GS_MAXL];
 };
 __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLevelMeta *__restrict__ meta, int S) {
     const int l = blockIdx.y;
     const int n1 = meta[l + 1].front_off[S];
-    const int chunks = (n1 + g.kchunk[l] - 1) / g.kchunk[l];
+    const int kchunk = grad_w_chunk_rows(n1, g.nchunk[l], g.rows_min[l]);
+    const int chunks = (n1 + kchunk - 1) / kchunk;
     const int D = g.D[l], N = g.N[l];
     const int64_t words = (int64_t)(2 * D + 1) * N;
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < words;
@@ -458,15 +576,20 @@ __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLeve
     }
 }
 
-// [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row
-template <int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_grad_in(MatRows dz, CatW w, EpiGradIn epi,
+// [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row; w is the stacked weight
+// matrix (2 D rows, columns padded to a multiple of 4), n_k the true number of columns
+template <class T, int VA, int VB>
+__global__ __launch_bounds__(GNT) void k_sage_grad_in(MatRows dz, MatRows w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * GBM;
-    if (m0 >= n1) return;
+    const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (w.rows + T::BN - 1) / T::BN;
+    const int total = ((tiles_m + 7) & ~7) * tiles_n;
     dz.rows = n1; epi.n1 = n1;
-    gemm_tile<GBM, GBN, true, true, VA, VB>(m0, blockIdx.y * GBN, n1, 2 * w.D, 0, dz.cols, dz, w, epi);
+    for (int gid = blockIdx.x; gid < total; gid += gridDim.x) {
+        int m0, n0;
+        if (!next_tile<T>(gid, tiles_m, tiles_n, m0, n0)) continue;
+        gemm_tile<T, true, true, VA, VB>(m0, n0, n1, w.rows, 0, dz.cols, dz, w, epi);
+    }
 }
 
 // Reverse shuffle of the backward pass as a pull: row u of local_cat[l] sums the gradient rows of
@@ -597,7 +720,10 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
     for (int l = 0; l < L; ++l) {
         int rc = gs_alloc(ctx, &sb.xin[l], esz * ctx->ub_front[l + 1] * 2 * p->dims[l], "layer input");
         if (rc) return rc;
-        if (p->dtype == GSPLIT_BF16) {
+        if (p->dtype == GSPLIT_F32) {
+            const int64_t np = (p->dims[l + 1] + 3) & ~3;
+            rc = gs_alloc(ctx, (void **)&sb.wstack32[l], sizeof(float) * 2 * p->dims[l] * np, "stacked weights");
+        } else {
             const int64_t np = (p->dims[l + 1] + 7) & ~7;
             rc = gs_alloc(ctx, (void **)&sb.wstack[l], 2 * (size_t)(2 * p->dims[l]) * np, "bf16 weights");
             if (rc) return rc;
@@ -608,13 +734,10 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         if (rc) return rc;
     }
     for (int l = 0; l < L; ++l) {
-        // split-K geometry of the weight-gradient product: about 1024 workgroups at the upper bound
-        const int tiles = (int)(gs_ceil_div(2 * p->dims[l] + 1, GBM) * gs_ceil_div(p->dims[l + 1], GBN));
-        const int64_t ub = ctx->ub_front[l + 1];
-        int64_t chunks = std::max<int64_t>(8, 1024 / tiles);
-        int64_t kchunk = std::max<int64_t>(64, gs_ceil_div(gs_ceil_div(ub, chunks), 32) * 32);
-        chunks = gs_ceil_div(gs_ceil_div(ub, kchunk), 8) * 8;
-        sb.kchunk[l] = (int)kchunk;
+        // split-K geometry of the weight-gradient product: up to about 512 workgroups; how many of
+        // the chunks are used is decided on the device from the actual row count
+        const int tiles = (int)(gs_ceil_div(2 * p->dims[l] + 1, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
+        const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, 512 / tiles), 8) * 8;
         sb.nchunk[l] = (int)chunks;
         int rc = gs_alloc(ctx, (void **)&sb.gw_part[l],
                           sizeof(float) * chunks * (2 * p->dims[l] + 1) * p->dims[l + 1], "weight-gradient partials");
@@ -649,6 +772,93 @@ int check_params(gsplit_ctx *ctx, const gsplit_sage_params *p, const char *who) 
         if (!p->d_w_self[l] || !p->d_w_neigh[l] || !p->d_bias[l])
             return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": NULL weight pointer");
     return GSPLIT_OK;
+}
+
+// [W_self; W_neigh] stacked into one 2 D x Npad matrix (Npad = N rounded up to 4, padding zeroed),
+// all layers in one launch (blockIdx.y = layer): every product then reads the weights as one plain
+// matrix in 16-byte pieces whatever N is.
+struct WeightStack {
+    const float *ws[GS_MAXL]; const float *wn[GS_MAXL]; float *stacked[GS_MAXL]; int D[GS_MAXL]; int N[GS_MAXL];
+};
+__global__ __launch_bounds__(256) void k_stack_weights(WeightStack w) {
+    const int l = blockIdx.y;
+    const int D = w.D[l], N = w.N[l], np = (N + 3) & ~3;
+    const int64_t words = (int64_t)2 * D * np;
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < words; x += (int64_t)gridDim.x * blockDim.x) {
+        const int k = (int)(x / np), n = (int)(x % np);
+        float v = 0.f;
+        if (n < N) v = k < D ? w.ws[l][(int64_t)k * N + n] : w.wn[l][(int64_t)(k - D) * N + n];
+        w.stacked[l][x] = v;
+    }
+}
+
+// ---- tile choice and launches of the fp32 products ------------------------------------------
+// The tile is chosen from what the host knows: the upper bound on the rows, the output width and
+// the length of the contraction.  The middle tile serves products with enough rows to fill the
+// chip; when even the upper bound gives at most about one workgroup per compute unit, the low
+// tiles with their k split give more and shorter workgroups (a long contraction walked by few
+// workgroups is a chain of dependent k-tiles, not a throughput problem).  Operands that cannot be
+// read in 16-byte pieces take the middle tile with scalar loads.
+constexpr int GRAD_W_ROWS_MIN = 256;
+
+inline bool few_rows(int64_t ub, int n_out, int k) {
+    return ub * gs_ceil_div(n_out, 128) <= 16384 && (k >= 384 || k <= 64);
+}
+
+// persistent launch: no more workgroups than the chip holds, a multiple of 8
+template <class T>
+unsigned row_block_grid(const gsplit_ctx *ctx, int64_t ub, int n_out) {
+    const int64_t want = gs_ceil_div(gs_ceil_div(ub, T::BM), 8) * 8 * gs_ceil_div(n_out, T::BN);
+    return (unsigned)std::min<int64_t>(want, (int64_t)ctx->n_cu * T::OCC / 8 * 8);
+}
+template <class T, int VA, int VB>
+void launch_fwd_t(gsplit_ctx *ctx, hipStream_t st, int64_t ub, const MatRows &a, const MatRows &b, const EpiFwd &epi,
+                  const GsLevelMeta *mu) {
+    hipLaunchKernelGGL((k_sage_linear_fwd<T, VA, VB>), dim3(row_block_grid<T>(ctx, ub, b.cols)), dim3(GNT), 0, st, a, b,
+                       epi, mu, ctx->S);
+}
+// b: stacked weights, always readable in 16-byte pieces
+void launch_fwd(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool va, const MatRows &a, const MatRows &b,
+                const EpiFwd &epi, const GsLevelMeta *mu) {
+    if (!va) launch_fwd_t<TileMid, 1, 4>(ctx, st, ub, a, b, epi, mu);
+    else if (!few_rows(ub, epi.N, a.cols)) launch_fwd_t<TileMid, 4, 4>(ctx, st, ub, a, b, epi, mu);
+    else if (epi.N <= 64) launch_fwd_t<TileLowNarrow, 4, 4>(ctx, st, ub, a, b, epi, mu);
+    else launch_fwd_t<TileLow, 4, 4>(ctx, st, ub, a, b, epi, mu);
+}
+
+template <class T, int VA, int VB>
+void launch_grad_in_t(gsplit_ctx *ctx, hipStream_t st, int64_t ub, const MatRows &dz, const MatRows &w,
+                      const EpiGradIn &epi, const GsLevelMeta *mu) {
+    hipLaunchKernelGGL((k_sage_grad_in<T, VA, VB>), dim3(row_block_grid<T>(ctx, ub, w.rows)), dim3(GNT), 0, st, dz, w,
+                       epi, mu, ctx->S);
+}
+void launch_grad_in(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool vdz, const MatRows &dz, const MatRows &w,
+                    const EpiGradIn &epi, const GsLevelMeta *mu) {
+    const bool few = few_rows(ub, w.rows, dz.cols);
+    if (!vdz) {
+        if (few) launch_grad_in_t<TileLow, 1, 4>(ctx, st, ub, dz, w, epi, mu);
+        else launch_grad_in_t<TileMid, 1, 4>(ctx, st, ub, dz, w, epi, mu);
+    } else if (!few) launch_grad_in_t<TileMid, 4, 4>(ctx, st, ub, dz, w, epi, mu);
+    else if (w.rows <= 64) launch_grad_in_t<TileLowNarrow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
+    else launch_grad_in_t<TileLow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
+}
+
+// vin: rows of the layer input can be read in 16-byte (fp32) or 8-byte (bf16) pieces
+template <int VA, int VB, class AF, bool A_H>
+void launch_grad_w_t(hipStream_t st, int nchunk, const AF &in, const MatRows &dz, const EpiGradW &ew,
+                     const GsLevelMeta *mu, int S) {
+    using T = TileMid;
+    const int tm = (int)gs_ceil_div(ew.rows, T::BM), tn = (int)gs_ceil_div(ew.N, T::BN);
+    hipLaunchKernelGGL((k_sage_grad_w<T, VA, VB, AF, A_H>), dim3((unsigned)(nchunk * tm * tn)), dim3(GNT), 0, st, in, dz,
+                       ew, nchunk, GRAD_W_ROWS_MIN, tm, tn, mu, S);
+}
+template <class AF, bool A_H>
+void launch_grad_w(hipStream_t st, int nchunk, bool vin, bool vdz, const AF &in, const MatRows &dz,
+                   const EpiGradW &ew, const GsLevelMeta *mu, int S) {
+    if (vin && vdz) launch_grad_w_t<4, 4, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
+    else if (vin) launch_grad_w_t<4, 1, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
+    else if (vdz) launch_grad_w_t<1, 4, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
+    else launch_grad_w_t<1, 1, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
 }
 
 void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st) {
@@ -735,24 +945,30 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         sb.fwd_batch = ctx->batch_id;
         return GSPLIT_OK;
     }
+    {
+        WeightStack ws;
+        int64_t wmax = 1;
+        for (int l = 0; l < L; ++l) {
+            ws.ws[l] = (const float *)p->d_w_self[l]; ws.wn[l] = (const float *)p->d_w_neigh[l];
+            ws.stacked[l] = sb.wstack32[l]; ws.D[l] = p->dims[l]; ws.N[l] = p->dims[l + 1];
+            wmax = std::max<int64_t>(wmax, (int64_t)2 * p->dims[l] * ((p->dims[l + 1] + 3) & ~3));
+        }
+        GsTimeScope ts(ctx, "stack_weights", -1, st);
+        hipLaunchKernelGGL(k_stack_weights, dim3((unsigned)std::min<int64_t>(128, gs_ceil_div(wmax, 256)), L), dim3(256),
+                           0, st, ws);
+    }
     for (int l = 0; l < L; ++l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const float *hin = l == 0 ? (const float *)d_feat_local : (const float *)sb.hidden[l];
         float *hout = l == L - 1 ? d_logits : (float *)sb.hidden[l + 1];
-        const GsLayerBuf &B = ctx->layer[l];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
         launch_assemble(ctx, l, hin, D, st);
         MatRows a{(const float *)sb.xin[l], 0, 2 * D};
-        CatW b{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
+        MatRows b{sb.wstack32[l], 2 * D, (N + 3) & ~3};
         EpiFwd epi{hout, (const float *)p->d_bias[l], N, 0, l < L - 1 ? 1 : 0};
-        dim3 grid((unsigned)gs_ceil_div(ctx->ub_front[l + 1], GBM), (unsigned)gs_ceil_div(N, GBN));
         const bool va = D % 2 == 0;   // rows of the assembled input are 2 * D floats: 16-byte aligned
-        const bool vb = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         GsTimeScope ts(ctx, "linear_fwd", l, st);
-        if (va && vb) hipLaunchKernelGGL((k_sage_linear_fwd<4, 4>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
-        else if (va) hipLaunchKernelGGL((k_sage_linear_fwd<4, 1>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
-        else if (vb) hipLaunchKernelGGL((k_sage_linear_fwd<1, 4>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
-        else hipLaunchKernelGGL((k_sage_linear_fwd<1, 1>), grid, dim3(GNT), 0, st, a, b, epi, mu, S);
+        launch_fwd(ctx, st, ctx->ub_front[l + 1], va, a, b, epi, mu);
     }
     GS_HIP(ctx, hipGetLastError());
     sb.fwd_done = true;
@@ -792,35 +1008,30 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         EpiGradW ew{sb.gw_part[l], 2 * D + 1, N};
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
-        const bool vw = N % 4 == 0 && aligned16(p->d_w_self[l]) && aligned16(p->d_w_neigh[l]);
         const bool h16 = p->dtype == GSPLIT_BF16;
         {
-            const int kchunk = sb.kchunk[l];
-            const int tm = (int)gs_ceil_div(2 * D + 1, GBM), tn = (int)gs_ceil_div(N, GBN);
-            dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
             GsTimeScope ts(ctx, "grad_w", l, st);
-            MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
-            if (h16 && vdz) hipLaunchKernelGGL((k_sage_grad_w_h<4, 4>), grid, dim3(GNT), 0, st, inh, dz, ew, kchunk, tm, tn, mu, S);
-            else if (h16) hipLaunchKernelGGL((k_sage_grad_w_h<4, 1>), grid, dim3(GNT), 0, st, inh, dz, ew, kchunk, tm, tn, mu, S);
-            else if (vin && vdz) hipLaunchKernelGGL((k_sage_grad_w<4, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
-            else if (vin) hipLaunchKernelGGL((k_sage_grad_w<4, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
-            else if (vdz) hipLaunchKernelGGL((k_sage_grad_w<1, 4>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
-            else hipLaunchKernelGGL((k_sage_grad_w<1, 1>), grid, dim3(GNT), 0, st, in, dz, ew, kchunk, tm, tn, mu, S);
+            if (h16) {
+                MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
+                launch_grad_w<MatRowsOnesH, true>(st, sb.nchunk[l], true, vdz, inh, dz, ew, mu, S);
+            } else {
+                launch_grad_w<MatRowsOnes, false>(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
+            }
         }
         if (l > 0) {
             const GsLevelMeta *ml = ctx->d_meta + l;
-            CatW w{(const float *)p->d_w_self[l], (const float *)p->d_w_neigh[l], D, N};
             EpiGradIn ei{sb.gtmp, sb.inv_cnt[l], D, 0};
-            dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
             {
-            GsTimeScope ts(ctx, "grad_in", l, st);
-            MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
-            if (h16 && vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
-            else if (h16) hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
-            else if (vdz && vw) hipLaunchKernelGGL((k_sage_grad_in<4, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
-            else if (vdz) hipLaunchKernelGGL((k_sage_grad_in<4, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
-            else if (vw) hipLaunchKernelGGL((k_sage_grad_in<1, 4>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
-            else hipLaunchKernelGGL((k_sage_grad_in<1, 1>), grid, dim3(GNT), 0, st, dz, w, ei, mu, S);
+                GsTimeScope ts(ctx, "grad_in", l, st);
+                if (h16) {
+                    dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
+                    MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
+                    if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
+                    else hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
+                } else {
+                    MatRows w{sb.wstack32[l], 2 * D, (N + 3) & ~3};
+                    launch_grad_in(ctx, st, ub, vdz, dz, w, ei, mu);
+                }
             }
             GsTimeScope ts(ctx, "pull_input_grad", l, st);
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
@@ -856,7 +1067,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         int64_t wmax = 1;
         for (int l = 0; l < L; ++l) {
             gr.part[l] = sb.gw_part[l]; gr.gws[l] = d_gw_self[l]; gr.gwn[l] = d_gw_neigh[l]; gr.gb[l] = d_gbias[l];
-            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.kchunk[l] = sb.kchunk[l];
+            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = GRAD_W_ROWS_MIN;
             wmax = std::max<int64_t>(wmax, (int64_t)(2 * p->dims[l] + 1) * p->dims[l + 1]);
         }
         GsTimeScope ts(ctx, "reduce_grads", -1, st);

@@ -304,21 +304,8 @@ struct MatRowsOnesH {
         const uint16_t *q = p + (int64_t)oc * cols + ic;
         return i == cols ? g_one_then_zero_h : q;
     }
+    __device__ __forceinline__ int tok(int i) const { return i >= cols ? -1 : min(i, cols - 4); }
+    __device__ __forceinline__ const uint16_t *km(int k, int t) const {
+        return t < 0 ? g_one_then_zero_h : p + (int64_t)k * cols + t;
+    }
 };
-
-template <int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, MatRows dz, EpiGradW epi, int kchunk,
-                                                       int tiles_m, int tiles_n,
-                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
-    const int n1 = meta_up->front_off[S];
-    const int tiles = tiles_m * tiles_n;
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int tile = j % tiles, chunk = (j / tiles) * 8 + xcd;
-    const int k_begin = chunk * kchunk;
-    if (k_begin >= n1) return;
-    a.rows = n1; dz.rows = n1;
-    const int k_end = min(n1, k_begin + kchunk);
-    epi.part += (int64_t)chunk * epi.rows * epi.N;
-    gemm_tile<GBM, GBN, false, false, VA, VB, MatRowsOnesH, MatRows, EpiGradW, true>(
-        (tile % tiles_m) * GBM, (tile / tiles_m) * GBN, a.cols + 1, dz.cols, k_begin, k_end, a, dz, epi);
-}
