@@ -103,22 +103,56 @@ class Pipelined:
             e.record()
 
     def run(self, targets, first, count):
+        """Two host threads enqueue (a launch costs the host a few microseconds and a step has
+        about sixty): one feeds the sampling streams, this one the training stream.  The queues only
+        order the host-side event calls: a stream may wait on an event only after the other thread
+        has recorded it for that step."""
+        import queue
+        import threading
         torch = self.torch
-        for i in range(first, first + count):
-            k = i % self.n
-            r = self.slots[k]
-            ss = self.s_sample[i % len(self.s_sample)]
-            with torch.cuda.stream(ss):
-                ss.wait_event(self.free[k])
-                r.ctx.gsplit_sample_split(targets[i], r.seed, i)
-                r.ctx.gsplit_gather_features(r.w.feat, r.x0)
-                self.ready[k].record(ss)
-            with torch.cuda.stream(self.s_train):
-                self.s_train.wait_event(self.ready[k])
-                r.ctx.gsplit_sage_fwd(r.params, r.x0, r.logits)
-                r.ctx.gsplit_softmax_xent(r.logits, r.w.labels, r.glogits)
-                r.ctx.gsplit_sage_bwd(r.params, r.glogits, r.gws, r.gwn, r.gb)
-                self.free[k].record(self.s_train)
+        sampled, freed = queue.Queue(), queue.Queue()
+        for _ in range(self.n):
+            freed.put(None)
+        failure = []
+
+        def sampler():
+            try:
+                torch.cuda.set_device(self.slots[0].dev)
+                for i in range(first, first + count):
+                    freed.get()
+                    k = i % self.n
+                    r = self.slots[k]
+                    ss = self.s_sample[i % len(self.s_sample)]
+                    with torch.cuda.stream(ss):
+                        ss.wait_event(self.free[k])
+                        r.ctx.gsplit_sample_split(targets[i], r.seed, i)
+                        r.ctx.gsplit_gather_features(r.w.feat, r.x0)
+                        self.ready[k].record(ss)
+                    sampled.put(i)
+            except BaseException as e:      # hand the failure to the training thread
+                failure.append(e)
+                sampled.put(-1)
+
+        th = threading.Thread(target=sampler, name="gsplit-sampler")
+        th.start()
+        try:
+            for i in range(first, first + count):
+                got = sampled.get()
+                if got != i:
+                    raise RuntimeError(f"sampling thread failed: {failure}")
+                k = i % self.n
+                r = self.slots[k]
+                with torch.cuda.stream(self.s_train):
+                    self.s_train.wait_event(self.ready[k])
+                    r.ctx.gsplit_sage_fwd(r.params, r.x0, r.logits)
+                    r.ctx.gsplit_softmax_xent(r.logits, r.w.labels, r.glogits)
+                    r.ctx.gsplit_sage_bwd(r.params, r.glogits, r.gws, r.gwn, r.gb)
+                    self.free[k].record(self.s_train)
+                freed.put(None)
+        finally:
+            for _ in range(count):      # a sampler left waiting for a slot can always finish
+                freed.put(None)
+            th.join()
 
 
 def cpu_baseline(w_host, iters):
