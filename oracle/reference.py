@@ -403,14 +403,14 @@ def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.
             dH = ghid[l + 1][off[s]:off[s + 1]]
             dZ = dH if l == L - 1 else dH * (fwd.z[l][s] > 0.0)
             mixed, M = fwd.mixed[l][s], fwd.mean[l][s]
-            gws[l] += mixed[:n_dst].T @ dZ
-            gwn[l] += M.T @ dZ
-            gb[l] += dZ.sum(0)
+            # with bf16 storage every matrix product takes bf16 operands, so dZ enters the
+            # weight-gradient and the input-gradient products rounded like the other operands
+            # (the bias gradient is the product of dZ with a column of ones)
+            dZq = q(dZ) if store_bf16 else dZ
+            gws[l] += mixed[:n_dst].T @ dZq
+            gwn[l] += M.T @ dZq
+            gb[l] += dZq.sum(0)
             if l > 0:
-                # with bf16 storage the input-gradient product runs on the bf16 matrix cores, so
-                # its operand dZ is rounded like every other operand of such a product (the
-                # weight-gradient product above stays in float)
-                dZq = q(dZ) if store_bf16 else dZ
                 dmixed = mean_aggregate_adjoint(blk.blk_indptr, blk.blk_src, dZq @ Wn.T,
                                                 mixed.shape[0])
                 dmixed[:n_dst] += dZq @ Ws.T

@@ -120,7 +120,7 @@ struct Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, KS = KS_;
     static constexpr int MI = BM / (32 * WM), NI = BN / (32 * WN);
     static constexpr int NO = BK / 8 / KS;      // groups of 8 k per k-tile and wave
-    static constexpr int OCC = BM * BN >= 8192 ? 2 : 3;   // workgroups one compute unit holds (LDS, registers)
+    static constexpr int OCC = BM * BN >= 8192 ? 2 : 3;   // workgroups one compute unit holds (registers)
     static_assert(WM * WN * KS * 64 == GNT, "a workgroup has 8 waves");
     static_assert(MI >= 1 && NI >= 1 && MI * 32 * WM == BM && NI * 32 * WN == BN, "32 x 32 MFMA blocks");
     static_assert(KS == 1 || KS == 2 || KS == 4, "k split");
@@ -129,8 +129,8 @@ using TileMid = Tile<64, 128, 2, 4, 1>;
 using TileLow = Tile<32, 128, 1, 4, 2>;
 using TileLowNarrow = Tile<32, 64, 1, 2, 4>;
 
-template <int ROWS>
-constexpr int lds_words() { return ROWS * KC_LD > BK * (ROWS + 4) ? ROWS * KC_LD : BK * (ROWS + 4); }
+template <int ROWS, bool KC>
+constexpr int lds_words() { return KC ? ROWS * KC_LD : BK * (ROWS + 4); }
 
 __device__ __forceinline__ uint16_t f2bf(float f) {          // round to nearest, ties to even
     uint32_t u = __float_as_uint(f);
@@ -272,7 +272,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     // two LDS stages and two register stages: k-tile t is multiplied out of LDS while tile t+1
     // sits in the other LDS stage and tile t+2 is in flight into registers, so a global load has
     // two iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
-    constexpr int AW = lds_words<BM>(), BW = lds_words<BN>();
+    constexpr int AW = lds_words<BM, A_KC>(), BW = lds_words<BN, B_KC>();
     constexpr int RED = (KS - 1) * T::WM * T::WN * MI * NI * 1024;   // accumulators handed over at the end
     static_assert(RED <= 2 * (AW + BW), "k-split hand-over does not fit the staging area");
     __shared__ __attribute__((aligned(16))) float lds[2 * (AW + BW)];
@@ -1013,7 +1013,12 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             GsTimeScope ts(ctx, "grad_w", l, st);
             if (h16) {
                 MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
-                launch_grad_w<MatRowsOnesH, true>(st, sb.nchunk[l], true, vdz, inh, dz, ew, mu, S);
+                const int tm = (int)gs_ceil_div(ew.rows, GBM), tn = (int)gs_ceil_div(ew.N, GBN);
+                dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
+                if (vdz) hipLaunchKernelGGL((k_sage_grad_w_h<4>), grid, dim3(GNT), 0, st, inh, dz, ew, sb.nchunk[l],
+                                            GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                else hipLaunchKernelGGL((k_sage_grad_w_h<1>), grid, dim3(GNT), 0, st, inh, dz, ew, sb.nchunk[l],
+                                        GRAD_W_ROWS_MIN, tm, tn, mu, S);
             } else {
                 launch_grad_w<MatRowsOnes, false>(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
             }

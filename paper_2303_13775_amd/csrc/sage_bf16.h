@@ -1,8 +1,8 @@
 // bfloat16 storage path of the GraphSAGE layers (included by sage.hip, inside its anonymous
 // namespace): features, activations, assembled layer inputs and weights are held in bfloat16 and
 // fed to v_mfma_f32_32x32x16_bf16 with float accumulation; biases, logits and all gradients stay
-// float.  The weight-gradient product keeps the float MFMA path (its operands are k-major in
-// memory, which the 8-k-per-lane bf16 fragments would need transposed) and widens X on the fly.
+// float.  dZ is rounded to bfloat16 where it enters a matrix product (both operands of a bf16 MFMA
+// are bf16).
 #pragma once
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -309,3 +309,164 @@ struct MatRowsOnesH {
         return t < 0 ? g_one_then_zero_h : p + (int64_t)k * cols + t;
     }
 };
+
+// ------------------------------------------------------------------------------------------
+// Weight gradients on the bf16 matrix cores: C[m][n] = sum_k [X | 1][k][m] * bf16(dZ[k][n]) over
+// one chunk of destination rows k (split-K as in the float path, same slabs and reduction).
+// Both operands are k-major in memory while a fragment of v_mfma_f32_32x32x16_bf16 holds 8
+// consecutive k of one m (or n), so tiles are transposed on the way into LDS: a thread loads a
+// 2 (k) x 4 (m or n) patch with coalesced 8- or 16-byte reads, pairs the two k of each column into
+// one 32-bit word and writes four words.  LDS rows are 64 k = 128 bytes without padding; the
+// eight 16-byte granules of row r sit at granule ^ ((r ^ (r >> 2)) & 7), which spreads both the
+// transposed 32-bit writes (lanes along r in steps of 4) and the 128-bit fragment reads (lanes
+// along consecutive r) over all banks.
+// ------------------------------------------------------------------------------------------
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {     // round to nearest even
+    floatx2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ int t_swz(int r) { return (r ^ (r >> 2)) & 7; }
+// 32-bit word of k pair kp (0..31) of row r in a transposed [rows][64 k] bf16 tile
+__device__ __forceinline__ int t_word(int r, int kp) { return r * 32 + ((((kp >> 2) ^ t_swz(r)) << 2) | (kp & 3)); }
+
+// dZ: plain float matrix read k-major; VW = 4 needs N % 4 == 0 and a 16-byte aligned base
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+
+// dZ: plain float matrix read k-major; VW = 4 needs N % 4 == 0 and a 16-byte aligned base
+template <int VW>
+struct PatchDz {
+    floatx4 r00, r01, r10, r11;     // r<pass><k of the pair>
+    static __device__ __forceinline__ floatx4 fetch(const MatRows &dz, int n, int k, int k_end, bool full) {
+        const int kr = min(k, dz.rows - 1);
+        floatx4 v;
+        if (VW == 4) {
+            v = *reinterpret_cast<const floatx4 *>(dz.p + (int64_t)kr * dz.cols + min(n, dz.cols - 4));
+        } else {
+            const float *q = dz.p + (int64_t)kr * dz.cols;
+            v.x = q[min(n, dz.cols - 1)]; v.y = q[min(n + 1, dz.cols - 1)];
+            v.z = q[min(n + 2, dz.cols - 1)]; v.w = q[min(n + 3, dz.cols - 1)];
+        }
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        return (full || k < k_end) ? v : zero;
+    }
+    __device__ __forceinline__ void load(const MatRows &dz, int n0, int k, int k_end, int x, bool full) {
+        r00 = fetch(dz, n0 + 4 * x, k, k_end, full);
+        r01 = fetch(dz, n0 + 4 * x, k + 1, k_end, full);
+        r10 = fetch(dz, n0 + 4 * (x + 16), k, k_end, full);
+        r11 = fetch(dz, n0 + 4 * (x + 16), k + 1, k_end, full);
+    }
+    __device__ __forceinline__ void store(uint32_t *lds, int x, int kp) const {
+        int row = 4 * x;
+        lds[t_word(row, kp)] = pack_bf16(r00.x, r01.x);
+        lds[t_word(row + 1, kp)] = pack_bf16(r00.y, r01.y);
+        lds[t_word(row + 2, kp)] = pack_bf16(r00.z, r01.z);
+        lds[t_word(row + 3, kp)] = pack_bf16(r00.w, r01.w);
+        row = 4 * (x + 16);
+        lds[t_word(row, kp)] = pack_bf16(r10.x, r11.x);
+        lds[t_word(row + 1, kp)] = pack_bf16(r10.y, r11.y);
+        lds[t_word(row + 2, kp)] = pack_bf16(r10.z, r11.z);
+        lds[t_word(row + 3, kp)] = pack_bf16(r10.w, r11.w);
+    }
+};
+// [X | 1]: bf16 matrix with its column of ones, read k-major
+struct PatchX {
+    uintx2 r0, r1;
+    static __device__ __forceinline__ uintx2 fetch(const MatRowsOnesH &a, int tok, int k, int k_end, bool full) {
+        const uintx2 v = *reinterpret_cast<const uintx2 *>(a.km(min(k, a.rows - 1), tok));
+        const uintx2 zero = {0u, 0u};
+        return (full || k < k_end) ? v : zero;
+    }
+    __device__ __forceinline__ void load(const MatRowsOnesH &a, int tok, int k, int k_end, bool full) {
+        r0 = fetch(a, tok, k, k_end, full);
+        r1 = fetch(a, tok, k + 1, k_end, full);
+    }
+    __device__ __forceinline__ void store(uint32_t *lds, int x, int kp) const {
+        const int row = 4 * x;
+        lds[t_word(row, kp)] = (r0.x & 0xFFFFu) | (r1.x << 16);
+        lds[t_word(row + 1, kp)] = (r0.x >> 16) | (r1.x & 0xFFFF0000u);
+        lds[t_word(row + 2, kp)] = (r0.y & 0xFFFFu) | (r1.y << 16);
+        lds[t_word(row + 3, kp)] = (r0.y >> 16) | (r1.y & 0xFFFF0000u);
+    }
+};
+
+template <int VW>
+__global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, MatRows dz, EpiGradW epi, int nchunk,
+                                                       int rows_min, int tiles_m, int tiles_n,
+                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
+    const int n1 = meta_up->front_off[S];
+    const int kchunk = grad_w_chunk_rows(n1, nchunk, rows_min);
+    const int tiles = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7, jb = blockIdx.x >> 3;
+    const int tile = jb % tiles, chunk = (jb / tiles) * 8 + xcd;
+    const int k_begin = chunk * kchunk;
+    if (k_begin >= n1) return;
+    a.rows = n1; dz.rows = n1;
+    const int k_end = min(n1, k_begin + kchunk);
+    epi.part += (int64_t)chunk * epi.rows * epi.N;
+    const int m0 = (tile % tiles_m) * GBM, n0 = (tile / tiles_m) * GBN;
+
+    // [stage][A rows then B rows][32 words]
+    __shared__ __attribute__((aligned(16))) uint32_t lds[2][(GBM + GBN) * 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int wm0 = (wave / GWN) * 32, wn0 = (wave % GWN) * 32;
+    const int x = tid & 15, kp = (tid >> 4);          // patch: rows 4x.., k pair kp (0..31)
+    const int tok = a.tok(m0 + 4 * x);
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    PatchX pa0, pa1;
+    PatchDz<VW> pb0, pb1;
+
+    auto load_tile = [&](PatchX &pa, PatchDz<VW> &pb, int k0) {
+        const bool full = k0 + BKH <= k_end;
+        pa.load(a, tok, k0 + 2 * kp, k_end, full);
+        pb.load(dz, n0, k0 + 2 * kp, k_end, x, full);
+    };
+    auto store_tile = [&](const PatchX &pa, const PatchDz<VW> &pb, uint32_t *buf) {
+        pa.store(buf, x, kp);
+        pb.store(buf + GBM * 32, x, kp);
+    };
+    auto multiply = [&](const uint32_t *buf) {
+        const uint4 *As = reinterpret_cast<const uint4 *>(buf);
+        const uint4 *Bs = reinterpret_cast<const uint4 *>(buf + GBM * 32);
+        const int ra = wm0 + l32, rb = wn0 + l32;
+        uint4 af[BKH / 16], bf[BKH / 16];
+#pragma unroll
+        for (int ks = 0; ks < BKH / 16; ++ks) {
+            af[ks] = As[ra * 8 + ((2 * ks + half) ^ t_swz(ra))];
+            bf[ks] = Bs[rb * 8 + ((2 * ks + half) ^ t_swz(rb))];
+        }
+#pragma unroll
+        for (int ks = 0; ks < BKH / 16; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[ks]),
+                                                          __builtin_bit_cast(bf16x8, bf[ks]), acc, 0, 0, 0);
+    };
+    // one k-tile: the registers that held tile k0 (now in LDS) are refilled with tile k0 + 2 BKH,
+    // tile k0 is multiplied, tile k0 + BKH moves from the other registers to the other LDS stage
+    auto step = [&](PatchX &pa_cur, PatchDz<VW> &pb_cur, const PatchX &pa_nxt, const PatchDz<VW> &pb_nxt,
+                    const uint32_t *buf_cur, uint32_t *buf_nxt, int k0) {
+        if (k0 + 2 * BKH < k_end) load_tile(pa_cur, pb_cur, k0 + 2 * BKH);
+        multiply(buf_cur);
+        if (k0 + BKH < k_end) store_tile(pa_nxt, pb_nxt, buf_nxt);
+        __syncthreads();
+    };
+
+    load_tile(pa0, pb0, k_begin);
+    if (k_begin + BKH < k_end) load_tile(pa1, pb1, k_begin + BKH);
+    store_tile(pa0, pb0, lds[0]);
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * BKH) {
+        step(pa0, pb0, pa1, pb1, lds[0], lds[1], k0);
+        if (k0 + BKH < k_end) step(pa1, pb1, pa0, pb0, lds[1], lds[0], k0 + BKH);
+    }
+    // accumulator layout of the 32x32 block: register r of lane l holds
+    // row (r / 4) * 8 + (l / 32) * 4 + (r % 4), column l % 32
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        epi.store(m0 + wm0 + (r >> 2) * 8 + half * 4 + (r & 3), n0 + wn0 + l32, acc[r], 0.f, 0.f);
+}
