@@ -294,6 +294,22 @@ def main():
     per_step_us = {k: v[1] / n_k * 1e3 for k, v in ktimes.items()}
     dominant = max(per_step_us, key=per_step_us.get)
 
+    def measured_traffic(label):
+        """HBM bytes per launch of this kernel from the committed rocprofv3 counter summary
+        (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration stated there), or None."""
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                            f"{a.workload}_bench_hbm_traffic.txt")
+        if dtype != "f32" or not os.path.exists(path):
+            return None
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 6 and f[0] == label:
+                try:
+                    return (float(f[-2]) + float(f[-1])) * 1024.0
+                except ValueError:
+                    return None
+        return None
+
     def roofline_of(label):
         cnt, ms = ktimes[label]
         kind, amount = work.get(label, ("bytes", 0.0))
@@ -301,14 +317,13 @@ def main():
         sec = ms / max(cnt, 1) * 1e-3
         if kind == "flops":
             ach = per_launch / sec / 1e12
-            on_bf16 = dtype == "bf16" and not label.startswith("grad_w")    # weight gradients stay on fp32 MFMA
-            peak = BF16_MFMA_PEAK_TFLOPS if on_bf16 else FP32_MFMA_PEAK_TFLOPS
+            peak = BF16_MFMA_PEAK_TFLOPS if dtype == "bf16" else FP32_MFMA_PEAK_TFLOPS
             return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": peak,
-                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": measured_traffic(label),
                     "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
         ach = per_launch / sec / 1e9
         return {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": per_launch,
+                "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(label), "bytes_per_launch": per_launch,
                 "launch_ms": ms / max(cnt, 1)}
 
     rows, edges, mixed, bucket = shape
