@@ -115,17 +115,21 @@ constexpr int BK = 32;
 constexpr int KC_LD = BK + 4;
 constexpr int GNT = 512;
 
-template <int BM_, int BN_, int WM_, int WN_, int KS_>
+template <int BM_, int BN_, int WM_, int WN_, int KS_, bool LEAN_ = false>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, KS = KS_;
+    // LEAN: one register stage and no fragment double-buffering, so that three workgroups fit a
+    // compute unit (80 registers a lane); latency is then hidden by the other workgroups' waves
+    static constexpr bool LEAN = LEAN_;
     static constexpr int MI = BM / (32 * WM), NI = BN / (32 * WN);
     static constexpr int NO = BK / 8 / KS;      // groups of 8 k per k-tile and wave
-    static constexpr int OCC = BM * BN >= 8192 ? 2 : 3;   // workgroups one compute unit holds (registers)
+    static constexpr int OCC = (BM * BN >= 8192 && !LEAN) ? 2 : 3;   // workgroups one compute unit holds
     static_assert(WM * WN * KS * 64 == GNT, "a workgroup has 8 waves");
     static_assert(MI >= 1 && NI >= 1 && MI * 32 * WM == BM && NI * 32 * WN == BN, "32 x 32 MFMA blocks");
     static_assert(KS == 1 || KS == 2 || KS == 4, "k split");
 };
 using TileMid = Tile<64, 128, 2, 4, 1>;
+using TileMidLean = Tile<64, 128, 2, 4, 1, true>;
 using TileLow = Tile<32, 128, 1, 4, 2>;
 using TileLowNarrow = Tile<32, 64, 1, 2, 4>;
 
@@ -298,6 +302,24 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     // execute (an MFMA occupies the matrix pipe for 64 cycles but not the issue slot), so only the
     // first LDS read of a k-tile is exposed.
     auto multiply = [&](const float *As, const float *Bs) {
+        if (T::LEAN) {
+            float af[MI][4], bf[NI][4];
+#pragma unroll
+            for (int t = 0; t < NO; ++t) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg + KS * t, half, af[i]);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg + KS * t, half, bf[j]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int j = 0; j < NI; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][q], bf[j][q], acc[i][j], 0, 0, 0);
+            }
+            return;
+        }
         float af[2][MI][4], bf[2][NI][4];
 #pragma unroll
         for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg, half, af[0][i]);
@@ -350,6 +372,23 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         __syncthreads();
     };
 
+    if (T::LEAN) {
+        sa0.init(a, m0, tid);
+        sb0.init(b, n0, tid);
+        load_tile(sa0, sb0, k_begin);
+        store_tile(sa0, sb0, As0, Bs0, k_begin);
+        __syncthreads();
+        auto lean_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int k0) {
+            if (k0 + BK < k_end) load_tile(sa0, sb0, k0 + BK);
+            multiply(As_cur, Bs_cur);
+            if (k0 + BK < k_end) store_tile(sa0, sb0, As_nxt, Bs_nxt, k0 + BK);
+            __syncthreads();
+        };
+        for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
+            lean_step(As0, Bs0, As1, Bs1, k0);
+            if (k0 + BK < k_end) lean_step(As1, Bs1, As0, Bs0, k0 + BK);
+        }
+    } else {
     sa0.init(a, m0, tid); sa1.init(a, m0, tid);
     sb0.init(b, n0, tid); sb1.init(b, n0, tid);
     load_tile(sa0, sb0, k_begin);
@@ -359,6 +398,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
         step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
         if (k0 + BK < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BK);
+    }
     }
     if (KS > 1) {
         // every wave is past its last LDS read (the k loop ends on a barrier): wave groups 1.. hand
@@ -500,7 +540,7 @@ __device__ __forceinline__ bool next_tile(int gid, int tiles_m, int tiles_n, int
 // Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer; b is the stacked
 // weight matrix, its columns padded to a multiple of 4
 template <class T, int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_linear_fwd(MatRows a, MatRows b, EpiFwd epi,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_linear_fwd(MatRows a, MatRows b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (b.cols + T::BN - 1) / T::BN;
@@ -528,7 +568,7 @@ __device__ __forceinline__ int grad_w_chunk_rows(int n1, int nchunk, int rows_mi
 // dealt round-robin to the 8 XCDs) and share its L2.  Partials go to a per-chunk slab; a
 // fixed-order reduction follows (deterministic, no atomics).
 template <class T, int VA, int VB, class AF, bool A_H>
-__global__ __launch_bounds__(GNT) void k_sage_grad_w(AF a, MatRows dz, EpiGradW epi, int nchunk,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_w(AF a, MatRows dz, EpiGradW epi, int nchunk,
                                                      int rows_min, int tiles_m, int tiles_n,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
@@ -563,6 +603,13 @@ __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLeve
         float acc = 0.f;
         const float *p = g.part[l] + x;
         int z = 0;
+        for (; z + 16 <= chunks; z += 16) {     // sixteen loads in flight, added in chunk order
+            float v[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = p[(int64_t)(z + j) * words];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc += v[j];
+        }
         for (; z + 4 <= chunks; z += 4) {
             const float v0 = p[(int64_t)z * words], v1 = p[(int64_t)(z + 1) * words];
             const float v2 = p[(int64_t)(z + 2) * words], v3 = p[(int64_t)(z + 3) * words];
@@ -579,7 +626,7 @@ __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLeve
 // [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row; w is the stacked weight
 // matrix (2 D rows, columns padded to a multiple of 4), n_k the true number of columns
 template <class T, int VA, int VB>
-__global__ __launch_bounds__(GNT) void k_sage_grad_in(MatRows dz, MatRows w, EpiGradIn epi,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_in(MatRows dz, MatRows w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (w.rows + T::BN - 1) / T::BN;
@@ -734,10 +781,11 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         if (rc) return rc;
     }
     for (int l = 0; l < L; ++l) {
-        // split-K geometry of the weight-gradient product: up to about 512 workgroups; how many of
-        // the chunks are used is decided on the device from the actual row count
+        // split-K geometry of the weight-gradient product: about as many workgroups as the chip
+        // holds at once (three per compute unit); how many of the chunks are used is decided on
+        // the device from the actual row count
         const int tiles = (int)(gs_ceil_div(2 * p->dims[l] + 1, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
-        const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, 512 / tiles), 8) * 8;
+        const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
         sb.nchunk[l] = (int)chunks;
         int rc = gs_alloc(ctx, (void **)&sb.gw_part[l],
                           sizeof(float) * chunks * (2 * p->dims[l] + 1) * p->dims[l + 1], "weight-gradient partials");
@@ -821,7 +869,7 @@ void launch_fwd_t(gsplit_ctx *ctx, hipStream_t st, int64_t ub, const MatRows &a,
 void launch_fwd(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool va, const MatRows &a, const MatRows &b,
                 const EpiFwd &epi, const GsLevelMeta *mu) {
     if (!va) launch_fwd_t<TileMid, 1, 4>(ctx, st, ub, a, b, epi, mu);
-    else if (!few_rows(ub, epi.N, a.cols)) launch_fwd_t<TileMid, 4, 4>(ctx, st, ub, a, b, epi, mu);
+    else if (!few_rows(ub, epi.N, a.cols)) launch_fwd_t<TileMidLean, 4, 4>(ctx, st, ub, a, b, epi, mu);
     else if (epi.N <= 64) launch_fwd_t<TileLowNarrow, 4, 4>(ctx, st, ub, a, b, epi, mu);
     else launch_fwd_t<TileLow, 4, 4>(ctx, st, ub, a, b, epi, mu);
 }
@@ -847,7 +895,7 @@ void launch_grad_in(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool vdz, const
 template <int VA, int VB, class AF, bool A_H>
 void launch_grad_w_t(hipStream_t st, int nchunk, const AF &in, const MatRows &dz, const EpiGradW &ew,
                      const GsLevelMeta *mu, int S) {
-    using T = TileMid;
+    using T = TileMidLean;
     const int tm = (int)gs_ceil_div(ew.rows, T::BM), tn = (int)gs_ceil_div(ew.N, T::BN);
     hipLaunchKernelGGL((k_sage_grad_w<T, VA, VB, AF, A_H>), dim3((unsigned)(nchunk * tm * tn)), dim3(GNT), 0, st, in, dz,
                        ew, nchunk, GRAD_W_ROWS_MIN, tm, tn, mu, S);

@@ -177,23 +177,37 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// Stable multi-class partition: three launches (count per chunk, scan, scatter) over `nb` chunks.
+// Stable multi-class partition in two launches over `nb` chunks: count per chunk, then scatter.
+// Every scatter workgroup first turns the chunk histograms into its own bases (the sums over all
+// chunks and over the chunks before it), so no launch sits between the two passes.
 // A functor F describes the elements:
-//   n()                       number of elements (read from device memory)
-//   classify(g)               count pass: bit k set <=> element g counts in class k (k < F::NK);
-//                             may leave the mask behind for the scatter pass
-//   cached(g)                 scatter pass: the same mask
-//   key_bases(totals, bases)  run by one thread in the scan: where each class starts
-//   emit(g, mask, rk)         rk[k] = bases[k] + number of class-k elements before g
-//   n_extra(), extra(g)       independent element-wise work appended to the scatter pass
-//   n_side(), side(g)         independent element-wise work appended to the count pass
+//   n()                          number of elements (read from device memory)
+//   classify(g)                  count pass: bit k set <=> element g counts in class k (k < F::NK);
+//                                may leave the mask behind for the scatter pass
+//   cached(g)                    scatter pass: the same mask
+//   upper_offset(s)              split offset s of the level above (fetched by 9 threads up front)
+//   key_bases(totals, bases, o, up)  where each class starts, and the offsets `o` that follow from
+//                                the totals; pure, run by one thread of every scatter workgroup
+//   publish(o)                   writes those offsets to the batch's device bookkeeping (one thread
+//                                of the whole launch; later launches read them there, this launch
+//                                takes them from `o`)
+//   emit(g, mask, rk, o)         rk[k] = bases[k] + number of class-k elements before g
+//   n_extra(o), extra(g, o)      independent element-wise work appended to the scatter pass
+//   n_side(), side(g)            independent element-wise work appended to the count pass
 // Elements keep their order inside every class (wave ballots + running chunk counters).
 // ------------------------------------------------------------------------------------------
+struct PartOffs {
+    int a[GS_MAXS + 1];     // first offset array of the pass (front_off or mixed_off)
+    int b[GS_MAXS + 1];     // second one (recv_off)
+    int total;              // class-16 total (edges)
+};
+
 __device__ __forceinline__ int part_chunk(int n, int nb) {
     int c = (n + nb - 1) / nb;
     return ((c + PART_BS - 1) / PART_BS) * PART_BS;
 }
 
+// hist is class-major: hist[k * gridDim.x + chunk]
 template <class F>
 __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict__ hist) {
     __shared__ int s_cnt[PART_NK];
@@ -221,80 +235,64 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
         }
     }
     __syncthreads();
-    if (threadIdx.x < F::NK) hist[blockIdx.x * PART_NK + threadIdx.x] = s_cnt[threadIdx.x];
+    if (threadIdx.x < F::NK) hist[threadIdx.x * gridDim.x + blockIdx.x] = s_cnt[threadIdx.x];
     const int64_t ns = f.n_side();
     for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < ns;
          g += (int64_t)gridDim.x * PART_BS)
         f.side(g);
 }
 
-// one workgroup of 256 threads; thread t owns chunks t*PER .. t*PER+PER-1 (nb = 256 * PER).
-// All histogram words are fetched before anything depends on them.
+// gridDim.x = 256 * PER chunks
 template <class F, int PER>
-__global__ __launch_bounds__(PART_BS) void k_part_scan(F f, const int32_t *__restrict__ hist,
-                                                       int32_t *__restrict__ base) {
-    __shared__ int s_wsum[F::NK][PART_BS / 64];
-    __shared__ int s_tot[PART_NK], s_base[PART_NK];
-    const int t = threadIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
-    int v[PER][F::NK];
-#pragma unroll
-    for (int j = 0; j < PER; ++j)
-#pragma unroll
-        for (int k = 0; k < F::NK; ++k) v[j][k] = hist[(t * PER + j) * PART_NK + k];
-    int ex[F::NK];
-#pragma unroll
-    for (int k = 0; k < F::NK; ++k) {
-        int mine = 0;
-#pragma unroll
-        for (int j = 0; j < PER; ++j) mine += v[j][k];
-        int inc = mine;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            int up = __shfl_up(inc, o);
-            if (lane >= o) inc += up;
-        }
-        if (lane == 63) s_wsum[k][wave] = inc;
-        ex[k] = inc - mine;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < F::NK; ++k) {
-        int pre = 0, tot = 0;
-#pragma unroll
-        for (int w = 0; w < PART_BS / 64; ++w) {
-            const int x = s_wsum[k][w];
-            pre += (w < wave) ? x : 0;
-            tot += x;
-        }
-        ex[k] += pre;
-        if (t == 0) s_tot[k] = tot;
-    }
-    if (t == 0) f.key_bases(s_tot, s_base);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < F::NK; ++k) {
-        int run = s_base[k] + ex[k];
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            base[(t * PER + j) * PART_NK + k] = run;
-            run += v[j][k];
-        }
-    }
-}
-
-template <class F>
-__global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__restrict__ base) {
+__global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__restrict__ hist) {
+    __shared__ int s_tot[PART_NK], s_pre[PART_NK], s_base[PART_NK];
     __shared__ int s_run[PART_NK];
     __shared__ int s_wcnt[PART_BS / 64][PART_NK];
+    __shared__ PartOffs s_o;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    // classes are dealt to the four waves; a wave reads a class's histogram row 64 chunks at a time
+    // (all loads issued before any sum) and reduces both sums with one shuffle tree
+    __shared__ int s_up[GS_MAXS + 1];
+    if (threadIdx.x <= GS_MAXS) s_up[threadIdx.x] = f.upper_offset(threadIdx.x);
+    {
+        constexpr int CPW = (F::NK + PART_BS / 64 - 1) / (PART_BS / 64);     // classes per wave
+        constexpr int LPC = PER * 4;                                          // 64-chunk loads per class
+        int v[CPW][LPC];
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const int k = wave + c * (PART_BS / 64);
+#pragma unroll
+            for (int j = 0; j < LPC; ++j)
+                v[c][j] = k < F::NK ? hist[k * (int)gridDim.x + j * 64 + lane] : 0;
+        }
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const int k = wave + c * (PART_BS / 64);
+            int tot = 0, pre = 0;
+#pragma unroll
+            for (int j = 0; j < LPC; ++j) {
+                tot += v[c][j];
+                pre += (j * 64 + lane < (int)blockIdx.x) ? v[c][j] : 0;
+            }
+            for (int o = 32; o > 0; o >>= 1) { tot += __shfl_down(tot, o); pre += __shfl_down(pre, o); }
+            if (lane == 0 && k < F::NK) { s_tot[k] = tot; s_pre[k] = pre; }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        f.key_bases(s_tot, s_base, s_o, s_up);
+        if (blockIdx.x == 0) f.publish(s_o);
+    }
+    __syncthreads();
+    if (threadIdx.x < F::NK) s_run[threadIdx.x] = s_base[threadIdx.x] + s_pre[threadIdx.x];
+    __syncthreads();
+    const PartOffs &o = s_o;
     const int n = f.n();
     const int chunk = part_chunk(n, gridDim.x);
     const int64_t beg64 = (int64_t)blockIdx.x * chunk;
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
     if (beg64 < n) {
         const int beg = (int)beg64;
         const int end = (n - beg < chunk) ? n : beg + chunk;
-        if (threadIdx.x < F::NK) s_run[threadIdx.x] = base[blockIdx.x * PART_NK + threadIdx.x];
-        __syncthreads();
         for (int tile = beg; tile < end; tile += PART_BS) {
             const int g = tile + threadIdx.x;
             const bool in = g < end;
@@ -313,7 +311,7 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
                 for (int w = 0; w < PART_BS / 64; ++w) pre += (w < wave) ? s_wcnt[w][k] : 0;
                 rk[k] += pre;
             }
-            if (in) f.emit(g, m, rk);
+            if (in) f.emit(g, m, rk, o);
             __syncthreads();
             if (threadIdx.x < F::NK) {
                 int add = 0;
@@ -323,10 +321,10 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
             __syncthreads();
         }
     }
-    const int64_t nx = f.n_extra();
+    const int64_t nx = f.n_extra(o);
     for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < nx;
          g += (int64_t)gridDim.x * PART_BS)
-        f.extra(g);
+        f.extra(g, o);
 }
 
 // ---- local_front[L] = targets separated by owner, order kept ---------------------------------
@@ -345,22 +343,26 @@ struct PartTargets {
     }
     __device__ unsigned classify(int g) const { return 1u << (pmap[target(g)] & (GS_MAXS - 1)); }
     __device__ unsigned cached(int g) const { return classify(g); }
-    __device__ void key_bases(const int *tot, int *bases) const {
+    __device__ int upper_offset(int) const { return 0; }
+    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *) const {     // o.a = front_off
         int acc = 0;
         for (int k = 0; k < GS_MAXS; ++k) {
             bases[k] = acc;
-            if (k <= S) meta->front_off[k] = acc;
+            o.a[k] = acc;
             acc += (k < S) ? tot[k] : 0;
         }
-        meta->front_off[S] = acc;
+        o.a[S] = acc;
     }
-    __device__ void emit(int g, unsigned m, const int *rk) const {
+    __device__ void publish(const PartOffs &o) const {
+        for (int k = 0; k <= S; ++k) meta->front_off[k] = o.a[k];
+    }
+    __device__ void emit(int g, unsigned m, const int *rk, const PartOffs &) const {
         const int k = __ffs(m) - 1;
         front[rk[k]] = target(g);
         perm[rk[k]] = g;
     }
-    __device__ int64_t n_extra() const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
-    __device__ void extra(int64_t x) const { tab_mixed.slot[x] = EMPTY_ENTRY; }
+    __device__ int64_t n_extra(const PartOffs &) const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
+    __device__ void extra(int64_t x, const PartOffs &) const { tab_mixed.slot[x] = EMPTY_ENTRY; }
     __device__ int64_t n_side() const { return 0; }
     __device__ void side(int64_t) const {}
 };
@@ -400,23 +402,28 @@ struct PartMixedBuckets {
         return m;
     }
     __device__ unsigned cached(int g) const { return cls[g]; }
-    __device__ void key_bases(const int *tot, int *bases) const {
+    __device__ int upper_offset(int s) const { return meta_up->front_off[s]; }
+    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *up) const {     // o.a = mixed_off, o.b = recv_off
         int acc = 0, racc = 0;
         for (int s = 0; s < GS_MAXS; ++s) {
-            const int n_dst = (s < S) ? meta_up->front_off[s + 1] - meta_up->front_off[s] : 0;
-            if (s <= S) { meta_lo->mixed_off[s] = acc; meta_lo->recv_off[s] = racc; }
+            const int n_dst = (s < S) ? up[s + 1] - up[s] : 0;
+            o.a[s] = acc; o.b[s] = racc;
             bases[s] = acc + n_dst;
             bases[8 + s] = racc;
             acc += n_dst + ((s < S) ? tot[s] : 0);
             racc += (s < S) ? tot[8 + s] : 0;
         }
-        meta_lo->mixed_off[S] = acc;
-        meta_lo->recv_off[S] = racc;
+        o.a[S] = acc;
+        o.b[S] = racc;
         bases[16] = 0;
-        meta_lo->nnz = tot[16];
-        blk_indptr[n1()] = tot[16];
+        o.total = tot[16];
     }
-    __device__ void emit(int g, unsigned m, const int *rk) const {
+    __device__ void publish(const PartOffs &o) const {
+        for (int s = 0; s <= S; ++s) { meta_lo->mixed_off[s] = o.a[s]; meta_lo->recv_off[s] = o.b[s]; }
+        meta_lo->nnz = o.total;
+        blk_indptr[n1()] = o.total;
+    }
+    __device__ void emit(int g, unsigned m, const int *rk, const PartOffs &o) const {
         const int i = g / fan, q = g - i * fan;
         if (q == 0) {
             blk_indptr[i] = rk[16];
@@ -435,7 +442,7 @@ struct PartMixedBuckets {
         const int h = ent_mixed[n1() + g];
         const int r = rk[8 + t];
         mixed[rk[s]] = id;
-        tab_mixed.row[h] = rk[s] - meta_lo->mixed_off[s];
+        tab_mixed.row[h] = rk[s] - o.a[s];
         recv[r] = id;
         const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)(n1() + r), &meta_lo->error);
         ent_local[n1() + r] = hl;
@@ -443,14 +450,14 @@ struct PartMixedBuckets {
     }
     // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier and come first
     // in their owner's next local frontier
-    __device__ int64_t n_extra() const { return n1(); }
-    __device__ void extra(int64_t x) const {
+    __device__ int64_t n_extra(const PartOffs &) const { return n1(); }
+    __device__ void extra(int64_t x, const PartOffs &o) const {
         const int i = (int)x;
         const int s = split_of(meta_up->front_off, S, i);
         const int loc = i - meta_up->front_off[s];
         const int32_t id = front[i];
         const int h = ent_mixed[i];
-        const int j = meta_lo->mixed_off[s] + loc;
+        const int j = o.a[s] + loc;
         mixed[j] = id;
         if (h >= 0) tab_mixed.row[h] = loc;
         const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)i, &meta_lo->error);
@@ -482,17 +489,21 @@ struct PartLocal {
         return m;
     }
     __device__ unsigned cached(int r) const { return cls[r]; }
-    __device__ void key_bases(const int *tot, int *bases) const {
+    __device__ int upper_offset(int t) const { return meta_up->front_off[t]; }
+    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *up) const {     // o.a = front_off of the level below
         int acc = 0;
         for (int t = 0; t < GS_MAXS; ++t) {
-            const int n_up = (t < S) ? meta_up->front_off[t + 1] - meta_up->front_off[t] : 0;
-            if (t <= S) meta_lo->front_off[t] = acc;
+            const int n_up = (t < S) ? up[t + 1] - up[t] : 0;
+            o.a[t] = acc;
             bases[t] = acc + n_up;
             acc += n_up + ((t < S) ? tot[t] : 0);
         }
-        meta_lo->front_off[S] = acc;
+        o.a[S] = acc;
     }
-    __device__ void emit(int r, unsigned m, const int *rk) const {
+    __device__ void publish(const PartOffs &o) const {
+        for (int t = 0; t <= S; ++t) meta_lo->front_off[t] = o.a[t];
+    }
+    __device__ void emit(int r, unsigned m, const int *rk, const PartOffs &) const {
         if (!m) return;
         const int t = __ffs(m) - 1;
         front_lo[rk[t]] = recv[r];
@@ -501,15 +512,15 @@ struct PartLocal {
     // scatter pass extras: destination vertices keep their order at the head of their owner's
     // frontier; then (layers above the bottom one) the mixed-frontier table is cleared for the
     // next sampling layer and the counters of this layer's reverse index are zeroed
-    __device__ int64_t n_reset() const {
-        return fan_next > 0 ? (1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next))) : 0;
+    __device__ int64_t n_reset(const PartOffs &o) const {
+        return fan_next > 0 ? (1ll << table_bits(o.a[S] * (1 + fan_next))) : 0;
     }
-    __device__ int64_t n_extra() const {
-        return n1() + n_reset() + (fan_next > 0 ? meta_lo->front_off[S] : 0);
+    __device__ int64_t n_extra(const PartOffs &o) const {
+        return n1() + n_reset(o) + (fan_next > 0 ? o.a[S] : 0);
     }
-    __device__ void extra(int64_t x) const {
+    __device__ void extra(int64_t x, const PartOffs &o) const {
         if (x >= n1()) {
-            const int64_t y = x - n1(), nr = n_reset();
+            const int64_t y = x - n1(), nr = n_reset(o);
             if (y < nr) {
                 tab_mixed.slot[y] = EMPTY_ENTRY;
                 if (y == 0) meta_lo->rev_cursor = 0;
@@ -520,7 +531,7 @@ struct PartLocal {
         }
         const int i = (int)x;
         const int t = split_of(meta_up->front_off, S, i);
-        const int rowp = meta_lo->front_off[t] + (i - meta_up->front_off[t]);
+        const int rowp = o.a[t] + (i - meta_up->front_off[t]);
         front_lo[rowp] = front_up[i];
         const int h = ent_local[i];
         if (h >= 0) tab_local.row[h] = rowp;
@@ -653,17 +664,13 @@ void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t
         GsTimeScope ts(ctx, (nm + "_count").c_str(), layer, st);
         hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
     }
-    {
-    GsTimeScope ts(ctx, (nm + "_scan").c_str(), layer, st);
-    if (nb == 256)
-        hipLaunchKernelGGL((k_part_scan<F, 1>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
-    else if (nb == 512)
-        hipLaunchKernelGGL((k_part_scan<F, 2>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
-    else
-        hipLaunchKernelGGL((k_part_scan<F, 4>), dim3(1), dim3(PART_BS), 0, st, f, ctx->part_hist, ctx->part_base);
-    }
     GsTimeScope ts(ctx, (nm + "_scatter").c_str(), layer, st);
-    hipLaunchKernelGGL(k_part_scatter<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_base);
+    if (nb == 256)
+        hipLaunchKernelGGL((k_part_scatter<F, 1>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    else if (nb == 512)
+        hipLaunchKernelGGL((k_part_scatter<F, 2>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+    else
+        hipLaunchKernelGGL((k_part_scatter<F, 4>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
 }
 
 int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
