@@ -268,7 +268,11 @@ __device__ __forceinline__ void read_frag(const float *lds, int row, int oct, in
     }
 }
 
-template <class T, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF, bool A_H = false>
+// COLSUM: the workgroups of the first tile row (m0 == 0) also sum the columns of B over their k
+// range, from the tiles they stage in LDS anyway, and hand the sums to epi.colsum(): the
+// weight-gradient product gets the bias gradient without a row of ones in A.
+template <class T, bool A_KC, bool B_KC, int VA, int VB, class AF, class BF, class EF, bool A_H = false,
+          bool COLSUM = false>
 __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int m_end, const int n_end,
                                           const int k_begin, const int k_end, const AF &a, const BF &b,
                                           const EF &epi) {
@@ -297,6 +301,17 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     using SB = Stager<BN, B_KC, VB, GNT, BF>;
     SA sa0, sa1;
     SB sb0, sb1;
+
+    static_assert(!COLSUM || (!B_KC && KS == 1 && GNT % BN == 0 && BK % (GNT / BN) == 0), "column sums need a k-major B");
+    constexpr int CS_KPG = COLSUM ? BK / (GNT / BN) : 1;    // k rows of a tile per thread
+    const bool want_cs = COLSUM && m0 == 0;
+    float csum = 0.f;
+    auto colsum_tile = [&](const float *Bs) {
+        if (!want_cs) return;
+        const int n = tid % BN, g = tid / BN;
+#pragma unroll
+        for (int j = 0; j < CS_KPG; ++j) csum += Bs[(g * CS_KPG + j) * (BN + 4) + n];
+    };
 
     // The fragments of the next group of 8 k are read from LDS while the MFMAs of the current group
     // execute (an MFMA occupies the matrix pipe for 64 cycles but not the issue slot), so only the
@@ -368,6 +383,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
                     float *As_nxt, float *Bs_nxt, int k0) {
         if (k0 + 2 * BK < k_end) load_tile(ra_cur, rb_cur, k0 + 2 * BK);
         multiply(As_cur, Bs_cur);
+        colsum_tile(Bs_cur);
         if (k0 + BK < k_end) store_tile(ra_nxt, rb_nxt, As_nxt, Bs_nxt, k0 + BK);
         __syncthreads();
     };
@@ -381,6 +397,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         auto lean_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int k0) {
             if (k0 + BK < k_end) load_tile(sa0, sb0, k0 + BK);
             multiply(As_cur, Bs_cur);
+            colsum_tile(Bs_cur);
             if (k0 + BK < k_end) store_tile(sa0, sb0, As_nxt, Bs_nxt, k0 + BK);
             __syncthreads();
         };
@@ -399,6 +416,19 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
         if (k0 + BK < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BK);
     }
+    }
+    if constexpr (COLSUM) {
+        if (want_cs) {
+            // every wave is past its last LDS read (the k loop ends on a barrier)
+            lds[tid] = csum;
+            __syncthreads();
+            if (tid < BN) {
+                float sum = 0.f;
+#pragma unroll
+                for (int g = 0; g < GNT / BN; ++g) sum += lds[g * BN + tid];
+                epi.colsum(n0 + tid, sum);
+            }
+        }
     }
     if (KS > 1) {
         // every wave is past its last LDS read (the k loop ends on a barrier): wave groups 1.. hand
@@ -456,7 +486,6 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 }
 
 // ---- operand accessors and epilogues ---------------------------------------------------------
-__device__ const float g_one_then_zero[4] = {1.f, 0.f, 0.f, 0.f};
 __device__ const uint16_t g_one_then_zero_h[4] __attribute__((aligned(8))) = {0x3F80, 0, 0, 0};   // bf16 1, 0, 0, 0
 
 // Accessors return an address that is always safe to read VW floats from (indices are clamped into
@@ -474,21 +503,6 @@ struct MatRows {
     __device__ __forceinline__ int tok(int i) const { return min(i, cols - 4); }
     __device__ __forceinline__ const float *km(int k, int t) const { return p + (int64_t)k * cols + t; }
 };
-// plain row-major matrix followed by one column of ones (its product with dZ is the bias gradient)
-struct MatRowsOnes {
-    const float *p; int rows; int cols;
-    template <int VW>
-    __device__ __forceinline__ const float *at(int o, int i, bool &in) const {
-        in = o < rows && i <= cols;
-        const int oc = min(o, rows - 1), ic = min(i, cols - VW);
-        const float *q = p + (int64_t)oc * cols + ic;
-        return i == cols ? g_one_then_zero : q;
-    }
-    __device__ __forceinline__ int tok(int i) const { return i >= cols ? -1 : min(i, cols - 4); }
-    __device__ __forceinline__ const float *km(int k, int t) const {
-        return t < 0 ? g_one_then_zero : p + (int64_t)k * cols + t;
-    }
-};
 struct EpiFwd {
     float *out; const float *bias; int N; int n1; int relu;
     __device__ __forceinline__ float col(int n) const { return n < N ? bias[n] : 0.f; }
@@ -502,11 +516,14 @@ struct EpiFwd {
 };
 // partial [dW_self; dW_neigh; db] of one chunk of destination rows, written to the chunk's slab
 struct EpiGradW {
-    float *part; int rows; int N;     // rows = 2 * D + 1
+    // rows = 2 * D + 1: the slab's last row holds the bias gradient.  It arrives through colsum()
+    // (own_rows = 2 * D: the product has no row of ones) or as an ordinary row (own_rows = rows)
+    float *part; int rows; int N; int own_rows;
+    __device__ __forceinline__ void colsum(int n, float v) const { if (n < N) part[(int64_t)(rows - 1) * N + n] = v; }
     __device__ __forceinline__ float col(int) const { return 0.f; }
     __device__ __forceinline__ float row(int) const { return 0.f; }
     __device__ __forceinline__ void store(int c, int n, float v, float, float) const {
-        if (n < N && c < rows) part[(int64_t)c * N + n] = v;
+        if (n < N && c < own_rows) part[(int64_t)c * N + n] = v;
     }
 };
 // input gradients per destination row: [dH_self | dMean / cnt]; the reverse shuffle (pull through
@@ -562,13 +579,14 @@ __device__ __forceinline__ int grad_w_chunk_rows(int n1, int nchunk, int rows_mi
     return max(BK, (per + BK - 1) & ~(BK - 1));
 }
 
-// Partial [dW_self; dW_neigh; db] = [X | 1]^T * dZ over one chunk of destination rows (split-K).
+// Partial [dW_self; dW_neigh] = X^T * dZ and db = column sums of dZ over one chunk of destination
+// rows (split-K).
 // The output tiles of one chunk read the same slabs of X and dZ; the launch is one-dimensional and
 // the workgroup id is decoded so that all tiles of a chunk land on the same XCD (workgroups are
 // dealt round-robin to the 8 XCDs) and share its L2.  Partials go to a per-chunk slab; a
 // fixed-order reduction follows (deterministic, no atomics).
-template <class T, int VA, int VB, class AF, bool A_H>
-__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_w(AF a, MatRows dz, EpiGradW epi, int nchunk,
+template <class T, int VA, int VB>
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_w(MatRows a, MatRows dz, EpiGradW epi, int nchunk,
                                                      int rows_min, int tiles_m, int tiles_n,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
@@ -581,8 +599,8 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN 
     a.rows = n1; dz.rows = n1;
     const int k_end = min(n1, k_begin + kchunk);
     epi.part += (int64_t)chunk * epi.rows * epi.N;
-    gemm_tile<T, false, false, VA, VB, AF, MatRows, EpiGradW, A_H>(
-        (tile % tiles_m) * T::BM, (tile / tiles_m) * T::BN, a.cols + 1, dz.cols, k_begin, k_end, a, dz, epi);
+    gemm_tile<T, false, false, VA, VB, MatRows, MatRows, EpiGradW, false, true>(
+        (tile % tiles_m) * T::BM, (tile / tiles_m) * T::BN, a.cols, dz.cols, k_begin, k_end, a, dz, epi);
 }
 
 // Sum the per-chunk partials in chunk order into the caller's gradient buffers, all layers in one
@@ -784,7 +802,8 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         // split-K geometry of the weight-gradient product: about as many workgroups as the chip
         // holds at once (three per compute unit); how many of the chunks are used is decided on
         // the device from the actual row count
-        const int tiles = (int)(gs_ceil_div(2 * p->dims[l] + 1, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
+        const int m_rows = 2 * p->dims[l] + (p->dtype == GSPLIT_BF16 ? 1 : 0);    // bf16: plus the row of ones
+        const int tiles = (int)(gs_ceil_div(m_rows, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
         const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
         sb.nchunk[l] = (int)chunks;
         int rc = gs_alloc(ctx, (void **)&sb.gw_part[l],
@@ -891,22 +910,21 @@ void launch_grad_in(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool vdz, const
     else launch_grad_in_t<TileLow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
 }
 
-// vin: rows of the layer input can be read in 16-byte (fp32) or 8-byte (bf16) pieces
-template <int VA, int VB, class AF, bool A_H>
-void launch_grad_w_t(hipStream_t st, int nchunk, const AF &in, const MatRows &dz, const EpiGradW &ew,
+// vin / vdz: rows of the layer input / of dZ can be read in 16-byte pieces
+template <int VA, int VB>
+void launch_grad_w_t(hipStream_t st, int nchunk, const MatRows &in, const MatRows &dz, const EpiGradW &ew,
                      const GsLevelMeta *mu, int S) {
     using T = TileMidLean;
-    const int tm = (int)gs_ceil_div(ew.rows, T::BM), tn = (int)gs_ceil_div(ew.N, T::BN);
-    hipLaunchKernelGGL((k_sage_grad_w<T, VA, VB, AF, A_H>), dim3((unsigned)(nchunk * tm * tn)), dim3(GNT), 0, st, in, dz,
+    const int tm = (int)gs_ceil_div(ew.own_rows, T::BM), tn = (int)gs_ceil_div(ew.N, T::BN);
+    hipLaunchKernelGGL((k_sage_grad_w<T, VA, VB>), dim3((unsigned)(nchunk * tm * tn)), dim3(GNT), 0, st, in, dz,
                        ew, nchunk, GRAD_W_ROWS_MIN, tm, tn, mu, S);
 }
-template <class AF, bool A_H>
-void launch_grad_w(hipStream_t st, int nchunk, bool vin, bool vdz, const AF &in, const MatRows &dz,
+void launch_grad_w(hipStream_t st, int nchunk, bool vin, bool vdz, const MatRows &in, const MatRows &dz,
                    const EpiGradW &ew, const GsLevelMeta *mu, int S) {
-    if (vin && vdz) launch_grad_w_t<4, 4, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
-    else if (vin) launch_grad_w_t<4, 1, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
-    else if (vdz) launch_grad_w_t<1, 4, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
-    else launch_grad_w_t<1, 1, AF, A_H>(st, nchunk, in, dz, ew, mu, S);
+    if (vin && vdz) launch_grad_w_t<4, 4>(st, nchunk, in, dz, ew, mu, S);
+    else if (vin) launch_grad_w_t<4, 1>(st, nchunk, in, dz, ew, mu, S);
+    else if (vdz) launch_grad_w_t<1, 4>(st, nchunk, in, dz, ew, mu, S);
+    else launch_grad_w_t<1, 1>(st, nchunk, in, dz, ew, mu, S);
 }
 
 void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st) {
@@ -1052,11 +1070,11 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         MatRows dz{dH, 0, N};
         // weight and bias gradients, summed over all splits: [X | 1]^T dZ with the layer input X
         // assembled by the forward pass
-        MatRowsOnes in{(const float *)sb.xin[l], 0, 2 * D};
-        EpiGradW ew{sb.gw_part[l], 2 * D + 1, N};
+        MatRows in{(const float *)sb.xin[l], 0, 2 * D};
+        const bool h16 = p->dtype == GSPLIT_BF16;
+        EpiGradW ew{sb.gw_part[l], 2 * D + 1, N, h16 ? 2 * D + 1 : 2 * D};
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
-        const bool h16 = p->dtype == GSPLIT_BF16;
         {
             GsTimeScope ts(ctx, "grad_w", l, st);
             if (h16) {
@@ -1068,7 +1086,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
                 else hipLaunchKernelGGL((k_sage_grad_w_h<1>), grid, dim3(GNT), 0, st, inh, dz, ew, sb.nchunk[l],
                                         GRAD_W_ROWS_MIN, tm, tn, mu, S);
             } else {
-                launch_grad_w<MatRowsOnes, false>(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
+                launch_grad_w(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
             }
         }
         if (l > 0) {
