@@ -8,6 +8,8 @@
 
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <typename VecT, int UNROLL>
 __global__ __launch_bounds__(256) void k_gather_rows(const uint8_t *__restrict__ table,
                                                      int64_t row_stride_bytes, int vec_per_row,
@@ -53,7 +55,7 @@ extern "C" int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int3
     hipStream_t st = (hipStream_t)stream;
     const int64_t ub_rows = ctx->ub_front[0];
     const GsLevelMeta *m0 = ctx->d_meta;
-    const int grid = (int)std::min<int64_t>((int64_t)ctx->n_cu * 16,
+    const int grid = (int)std::min<int64_t>((int64_t)ctx->n_cu * 32,
                                             std::max<int64_t>(1, gs_ceil_div(ub_rows * gs_ceil_div(row_bytes, 16), 256 * 4)));
     const bool a16 = row_bytes % 16 == 0 && row_stride_bytes % 16 == 0 &&
                      ((uintptr_t)d_table % 16) == 0 && ((uintptr_t)d_out % 16) == 0;
@@ -61,9 +63,9 @@ extern "C" int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int3
                     ((uintptr_t)d_out % 4) == 0;
     GsTimeScope ts(ctx, "gather_rows", -1, st);
     if (a16) {
-        hipLaunchKernelGGL((k_gather_rows<uint4, 4>), dim3(grid), dim3(256), 0, st,
+        hipLaunchKernelGGL((k_gather_rows<u32x4, 4>), dim3(grid), dim3(256), 0, st,
                            (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 16),
-                           ctx->front[0], m0, ctx->S, (uint4 *)d_out);
+                           ctx->front[0], m0, ctx->S, (u32x4 *)d_out);
     } else if (a4) {
         hipLaunchKernelGGL((k_gather_rows<uint32_t, 4>), dim3(grid), dim3(256), 0, st,
                            (const uint8_t *)d_table, row_stride_bytes, (int)(row_bytes / 4),
