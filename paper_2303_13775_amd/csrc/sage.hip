@@ -1002,7 +1002,7 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             MatRowsH wt{sb.wtrans[l], N, 2 * D};
             EpiFwdH epi{l == L - 1 ? (void *)d_logits : sb.hidden[l + 1], (const float *)p->d_bias[l], N, 0,
                         l < L - 1 ? 1 : 0, l == L - 1 ? 1 : 0};
-            dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(N, GBN));
+            dim3 grid(row_block_grid<TileMid>(ctx, ub, N));
             GsTimeScope ts(ctx, "linear_fwd", l, st);
             hipLaunchKernelGGL(k_sage_linear_fwd_h, grid, dim3(GNT), 0, st, x, wt, epi, mu, S);
         }
@@ -1095,7 +1095,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             {
                 GsTimeScope ts(ctx, "grad_in", l, st);
                 if (h16) {
-                    dim3 grid((unsigned)gs_ceil_div(ub, GBM), (unsigned)gs_ceil_div(2 * D, GBN));
+                    dim3 grid(row_block_grid<TileMid>(ctx, ub, 2 * D));
                     MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
                     if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
                     else hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);

@@ -270,15 +270,20 @@ struct EpiFwdH {
     }
 };
 
-// Z = X * [W_self; W_neigh] + b with X bf16 [n1 x 2D] and the transposed bf16 weights [N x 2D]
+// Z = X * [W_self; W_neigh] + b with X bf16 [n1 x 2D] and the transposed bf16 weights [N x 2D].
+// Persistent launch like the float row-block products (tiles gid, gid + gridDim.x, ...).
 __global__ __launch_bounds__(GNT) void k_sage_linear_fwd_h(MatRowsH x, MatRowsH wt, EpiFwdH epi,
                                                            const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * GBM;
-    if (m0 >= n1) return;
+    const int tiles_m = (n1 + GBM - 1) / GBM, tiles_n = (wt.rows + GBN - 1) / GBN;
+    const int total = ((tiles_m + 7) & ~7) * tiles_n;
     x.rows = n1; epi.n1 = n1;
-    gemm_tile_h<GBM, GBN, StagerH<GBM, GNT, MatRowsH>, StagerH<GBN, GNT, MatRowsH>>(
-        m0, blockIdx.y * GBN, n1, wt.rows, x.cols, x, wt, epi);
+    for (int gid = blockIdx.x; gid < total; gid += gridDim.x) {
+        int m0, n0;
+        if (!next_tile<TileMid>(gid, tiles_m, tiles_n, m0, n0)) continue;
+        gemm_tile_h<GBM, GBN, StagerH<GBM, GNT, MatRowsH>, StagerH<GBN, GNT, MatRowsH>>(
+            m0, n0, n1, wt.rows, x.cols, x, wt, epi);
+    }
 }
 
 // [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T with dZ float [n1 x N] (converted on the way
@@ -287,11 +292,15 @@ template <int VW>
 __global__ __launch_bounds__(GNT) void k_sage_grad_in_h(MatRows dz, MatRowsH wstack, EpiGradIn epi,
                                                         const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
-    const int m0 = blockIdx.x * GBM;
-    if (m0 >= n1) return;
+    const int tiles_m = (n1 + GBM - 1) / GBM, tiles_n = (wstack.rows + GBN - 1) / GBN;
+    const int total = ((tiles_m + 7) & ~7) * tiles_n;
     dz.rows = n1; epi.n1 = n1;
-    gemm_tile_h<GBM, GBN, StagerF2H<GBM, GNT, VW, MatRows>, StagerH<GBN, GNT, MatRowsH>>(
-        m0, blockIdx.y * GBN, n1, wstack.rows, dz.cols, dz, wstack, epi);
+    for (int gid = blockIdx.x; gid < total; gid += gridDim.x) {
+        int m0, n0;
+        if (!next_tile<TileMid>(gid, tiles_m, tiles_n, m0, n0)) continue;
+        gemm_tile_h<GBM, GBN, StagerF2H<GBM, GNT, VW, MatRows>, StagerH<GBN, GNT, MatRowsH>>(
+            m0, n0, n1, wstack.rows, dz.cols, dz, wstack, epi);
+    }
 }
 
 // bf16 matrix followed by a column of ones, read by the float weight-gradient product
