@@ -98,9 +98,16 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__r
 // Operands are described by accessors  at(outer, inner) -> const float* (clamped into the matrix;
 // `inner` runs along memory).  An operand is used either K-contiguous (KC: outer is the M or N
 // index, inner is k) or K-major (KM: outer is k, inner is the M or N index); both are staged into
-// LDS with the layout they have in memory (16-byte copies when VW == 4):
-//   KC: lds[row][k]   (row stride 36 words), MFMA fragments are one 128-bit read per 8 k
-//   KM: lds[k][row]   (row stride ROWS + 4), MFMA fragments are four 32-bit reads per 8 k
+// LDS with the layout they have in memory, without padding, so that a tile is a run of 1-KiB
+// pieces each of which one wave can load straight from global memory into LDS (lane L of a
+// global_load_lds_dwordx4 lands at base + 16 L):
+//   KC: lds[row][32 k], the eight 16-byte granules of a row stored at granule ^ ((row >> 1) & 7)
+//       (a lane simply loads the granule that belongs where it writes); MFMA fragments are one
+//       128-bit read per 8 k
+//   KM: lds[k][ROWS], the two 32-word halves of a row swapped when (k >> 2) is odd; MFMA fragments
+//       are four 32-bit reads per 8 k
+// Both permutations are for the 64 LDS banks: sixteen consecutive rows of a KC tile, and the k
+// rows that the two halves of a wave read from a KM tile, fall on different banks.
 // v_mfma_f32_32x32x2_f32 sums two k-slots (lane / 32 selects the slot).  Within a group of 8 k the
 // lower half-wave takes k = 0..3 and the upper half k = 4..7 over four consecutive MFMAs; A and B
 // use the same assignment, so the sum over k is complete whatever the order.
@@ -112,12 +119,15 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32_any(const float *__r
 // yields more workgroups.
 // ------------------------------------------------------------------------------------------
 constexpr int BK = 32;
-constexpr int KC_LD = BK + 4;
 constexpr int GNT = 512;
 
-template <int BM_, int BN_, int WM_, int WN_, int KS_, bool LEAN_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int KS_, bool LEAN_ = false, bool DIRECT_ = false>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, KS = KS_;
+    // DIRECT (lean tiles only): unpadded, permuted LDS layouts and k-tiles loaded straight from
+    // global memory into LDS; otherwise padded layouts filled through registers
+    static constexpr bool DIRECT = DIRECT_;
+    static_assert(!DIRECT_ || LEAN_, "direct loads belong to the lean schedule");
     // LEAN: one register stage and no fragment double-buffering, so that three workgroups fit a
     // compute unit (80 registers a lane); latency is then hidden by the other workgroups' waves
     static constexpr bool LEAN = LEAN_;
@@ -130,11 +140,21 @@ struct Tile {
 };
 using TileMid = Tile<64, 128, 2, 4, 1>;
 using TileMidLean = Tile<64, 128, 2, 4, 1, true>;
+using TileMidDirect = Tile<64, 128, 2, 4, 1, true, true>;
 using TileLow = Tile<32, 128, 1, 4, 2>;
 using TileLowNarrow = Tile<32, 64, 1, 2, 4>;
 
-template <int ROWS, bool KC>
-constexpr int lds_words() { return KC ? ROWS * KC_LD : BK * (ROWS + 4); }
+// PAD: row strides of 36 (KC) and ROWS + 4 (KM) words instead of the permutations
+template <int ROWS, bool KC, bool PAD>
+constexpr int lds_words() { return PAD ? (KC ? ROWS * (BK + 4) : BK * (ROWS + 4)) : ROWS * BK; }
+template <bool PAD>
+__device__ __forceinline__ int kc_word(int row, int granule) {
+    return PAD ? row * (BK + 4) + (granule << 2) : row * BK + ((granule ^ ((row >> 1) & 7)) << 2);
+}
+template <int ROWS, bool PAD>
+__device__ __forceinline__ int km_word(int k, int col) {
+    return PAD ? k * (ROWS + 4) + col : k * ROWS + (ROWS >= 64 ? col ^ (((k >> 2) & 1) << 5) : col);
+}
 
 __device__ __forceinline__ uint16_t f2bf(float f) {          // round to nearest, ties to even
     uint32_t u = __float_as_uint(f);
@@ -145,7 +165,7 @@ __device__ __forceinline__ float bf2f(uint32_t h) { return __uint_as_float(h << 
 
 // SRC_H: the source matrix holds bfloat16; the raw halves travel through the registers and are
 // widened to float (exactly) when the tile is written to LDS.
-template <int ROWS, bool KC, int VW, int NT, class F, bool SRC_H = false>
+template <int ROWS, bool KC, int VW, int NT, class F, bool SRC_H = false, bool PAD = true>
 struct Stager {
     static constexpr int TOT = ROWS * BK / 4;                 // 4-word pieces of one tile
     static constexpr int NV = (TOT + NT - 1) / NT;
@@ -251,20 +271,57 @@ struct Stager {
                 w.z = (keep >> (4 * v + 2)) & 1u ? w.z : 0.f;
                 w.w = (keep >> (4 * v + 3)) & 1u ? w.w : 0.f;
             }
-            if (KC) *reinterpret_cast<float4 *>(&lds[o * KC_LD + 4 * i4]) = w;
-            else *reinterpret_cast<float4 *>(&lds[o * (ROWS + 4) + 4 * i4]) = w;
+            if (KC) *reinterpret_cast<float4 *>(&lds[kc_word<PAD>(o, i4)]) = w;
+            else *reinterpret_cast<float4 *>(&lds[km_word<ROWS, PAD>(o, 4 * i4)]) = w;
         }
     }
 };
 
-template <int ROWS, bool KC>
+// Global memory straight into LDS for a k-tile that needs no masking: the tile is ROWS / 8 pieces
+// of 1 KiB, piece j loaded by wave j mod 8 with one global_load_lds_dwordx4 (16 bytes a lane).
+template <int ROWS, bool KC, class F>
+struct Direct {
+    static constexpr int PIECES = ROWS / 8;
+    static constexpr int PER = (PIECES + 7) / 8;      // pieces per wave
+    const float *fixed_row[KC ? PER : 1];             // KC: row pointer plus the lane's (swizzled) granule
+    int fixed_tok[KC ? 1 : PER];                      // KM: clamped M/N index
+    int fixed_k[KC ? 1 : PER];                        // KM: k row inside the tile
+    __device__ __forceinline__ void init(const F &f, int r0, int wave, int lane) {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int j = wave + 8 * p;
+            if (KC) {
+                const int row = 8 * j + (lane >> 3);
+                bool in;
+                fixed_row[p] = f.template at<4>(r0 + row, 0, in) + 4 * ((lane & 7) ^ ((row >> 1) & 7));
+            } else {
+                constexpr int LPK = ROWS / 4;         // lanes per k row
+                fixed_k[p] = j * (64 / LPK) + lane / LPK;
+                // the lane fills position 4 * (lane % LPK) of row k: it loads the column stored there
+                fixed_tok[p] = f.tok(r0 + (km_word<ROWS, false>(fixed_k[p], 4 * (lane % LPK)) - fixed_k[p] * ROWS));
+            }
+        }
+    }
+    __device__ __forceinline__ void issue(const F &f, float *stage, int k0, int wave) const {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int j = wave + 8 * p;
+            if (PIECES % 8 != 0 && j >= PIECES) continue;
+            const float *src = KC ? fixed_row[p] + k0 : f.km(k0 + fixed_k[p], fixed_tok[p]);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(stage + j * 256), 16, 0, 0);
+        }
+    }
+};
+
+template <int ROWS, bool KC, bool PAD>
 __device__ __forceinline__ void read_frag(const float *lds, int row, int oct, int half, float out[4]) {
     if (KC) {
-        const float4 v = *reinterpret_cast<const float4 *>(&lds[row * KC_LD + oct * 8 + 4 * half]);
+        const float4 v = *reinterpret_cast<const float4 *>(&lds[kc_word<PAD>(row, oct * 2 + half)]);
         out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = lds[(oct * 8 + 4 * half + j) * (ROWS + 4) + row];
+        for (int j = 0; j < 4; ++j) out[j] = lds[km_word<ROWS, PAD>(oct * 8 + 4 * half + j, row)];
     }
 }
 
@@ -280,11 +337,20 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     // two LDS stages and two register stages: k-tile t is multiplied out of LDS while tile t+1
     // sits in the other LDS stage and tile t+2 is in flight into registers, so a global load has
     // two iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
-    constexpr int AW = lds_words<BM, A_KC>(), BW = lds_words<BN, B_KC>();
+    constexpr bool PAD = !T::DIRECT;
+    constexpr int AW = lds_words<BM, A_KC, PAD>(), BW = lds_words<BN, B_KC, PAD>();
     constexpr int RED = (KS - 1) * T::WM * T::WN * MI * NI * 1024;   // accumulators handed over at the end
     static_assert(RED <= 2 * (AW + BW), "k-split hand-over does not fit the staging area");
-    __shared__ __attribute__((aligned(16))) float lds[2 * (AW + BW)];
-    float *const As0 = lds, *const As1 = lds + AW, *const Bs0 = lds + 2 * AW, *const Bs1 = lds + 2 * AW + BW;
+    // A direct tile keeps its four stages in separate LDS objects: the compiler then knows that a
+    // straight-to-LDS load into one stage does not alias the fragment reads of the other and does
+    // not make the reads wait for the load.
+    constexpr bool SPLIT = T::DIRECT;
+    __shared__ __attribute__((aligned(16))) float lds[SPLIT ? (COLSUM ? GNT : 4) : 2 * (AW + BW)];
+    __shared__ __attribute__((aligned(16))) float stA0[SPLIT ? AW : 4], stA1[SPLIT ? AW : 4];
+    __shared__ __attribute__((aligned(16))) float stB0[SPLIT ? BW : 4], stB1[SPLIT ? BW : 4];
+    float *const As0 = SPLIT ? stA0 : lds, *const As1 = SPLIT ? stA1 : lds + AW;
+    float *const Bs0 = SPLIT ? stB0 : lds + 2 * AW, *const Bs1 = SPLIT ? stB1 : lds + 2 * AW + BW;
+    static_assert(!T::LEAN || KS == 1, "a lean tile has no k split");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int kg = wave / (T::WM * T::WN), wv = wave % (T::WM * T::WN);
@@ -297,8 +363,8 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    using SA = Stager<BM, A_KC, VA, GNT, AF, A_H>;
-    using SB = Stager<BN, B_KC, VB, GNT, BF>;
+    using SA = Stager<BM, A_KC, VA, GNT, AF, A_H, PAD>;
+    using SB = Stager<BN, B_KC, VB, GNT, BF, false, PAD>;
     SA sa0, sa1;
     SB sb0, sb1;
 
@@ -310,7 +376,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         if (!want_cs) return;
         const int n = tid % BN, g = tid / BN;
 #pragma unroll
-        for (int j = 0; j < CS_KPG; ++j) csum += Bs[(g * CS_KPG + j) * (BN + 4) + n];
+        for (int j = 0; j < CS_KPG; ++j) csum += Bs[km_word<BN, PAD>(g * CS_KPG + j, n)];
     };
 
     // The fragments of the next group of 8 k are read from LDS while the MFMAs of the current group
@@ -322,9 +388,9 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 #pragma unroll
             for (int t = 0; t < NO; ++t) {
 #pragma unroll
-                for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg + KS * t, half, af[i]);
+                for (int i = 0; i < MI; ++i) read_frag<BM, A_KC, PAD>(As, wm0 + i * 32 + l32, kg + KS * t, half, af[i]);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg + KS * t, half, bf[j]);
+                for (int j = 0; j < NI; ++j) read_frag<BN, B_KC, PAD>(Bs, wn0 + j * 32 + l32, kg + KS * t, half, bf[j]);
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -337,18 +403,18 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         }
         float af[2][MI][4], bf[2][NI][4];
 #pragma unroll
-        for (int i = 0; i < MI; ++i) read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg, half, af[0][i]);
+        for (int i = 0; i < MI; ++i) read_frag<BM, A_KC, PAD>(As, wm0 + i * 32 + l32, kg, half, af[0][i]);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg, half, bf[0][j]);
+        for (int j = 0; j < NI; ++j) read_frag<BN, B_KC, PAD>(Bs, wn0 + j * 32 + l32, kg, half, bf[0][j]);
 #pragma unroll
         for (int t = 0; t < NO; ++t) {
             if (t + 1 < NO) {
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
-                    read_frag<BM, A_KC>(As, wm0 + i * 32 + l32, kg + KS * (t + 1), half, af[(t + 1) & 1][i]);
+                    read_frag<BM, A_KC, PAD>(As, wm0 + i * 32 + l32, kg + KS * (t + 1), half, af[(t + 1) & 1][i]);
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    read_frag<BN, B_KC>(Bs, wn0 + j * 32 + l32, kg + KS * (t + 1), half, bf[(t + 1) & 1][j]);
+                    read_frag<BN, B_KC, PAD>(Bs, wn0 + j * 32 + l32, kg + KS * (t + 1), half, bf[(t + 1) & 1][j]);
             }
             __builtin_amdgcn_sched_barrier(0);   // reads of the next group stay ahead of these MFMAs
 #pragma unroll
@@ -389,16 +455,41 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     };
 
     if (T::LEAN) {
-        sa0.init(a, m0, tid);
-        sb0.init(b, n0, tid);
-        load_tile(sa0, sb0, k_begin);
-        store_tile(sa0, sb0, As0, Bs0, k_begin);
+        // one k-tile ahead: tile k0 + BK goes straight from global memory into the other LDS stage
+        // while tile k0 is multiplied (no staging registers, no LDS store instructions); a masked
+        // or scalar-loaded tile takes the register path into the same layout
+        constexpr bool DA = T::DIRECT && VA == 4 && !A_H, DB = T::DIRECT && VB == 4;
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        Direct<BM, A_KC, AF> da;
+        Direct<BN, B_KC, BF> db;
+        if (DA) da.init(a, m0, wave_u, lane); else sa0.init(a, m0, tid);
+        if (DB) db.init(b, n0, wave_u, lane); else sb0.init(b, n0, tid);
+        auto fetch_tile = [&](float *As, float *Bs, int k0) {
+            const bool full = k0 + BK <= k_end;
+            if (DA && full) da.issue(a, As, k0, wave_u);
+            else if (VA == 4 && full) sa0.load_full(a, k0, tid);
+            else sa0.load(a, m0, m_end, k0, k_end, tid);
+            if (DB && full) db.issue(b, Bs, k0, wave_u);
+            else if (VB == 4 && full) sb0.load_full(b, k0, tid);
+            else sb0.load(b, n0, n_end, k0, k_end, tid);
+        };
+        auto land_tile = [&](float *As, float *Bs, int k0) {
+            const bool full = k0 + BK <= k_end;
+            if (!(DA && full)) {
+                if (VA == 4 && full) sa0.template store<false>(As, tid); else sa0.template store<true>(As, tid);
+            }
+            if (!(DB && full)) {
+                if (VB == 4 && full) sb0.template store<false>(Bs, tid); else sb0.template store<true>(Bs, tid);
+            }
+        };
+        fetch_tile(As0, Bs0, k_begin);
+        land_tile(As0, Bs0, k_begin);
         __syncthreads();
         auto lean_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int k0) {
-            if (k0 + BK < k_end) load_tile(sa0, sb0, k0 + BK);
+            if (k0 + BK < k_end) fetch_tile(As_nxt, Bs_nxt, k0 + BK);
             multiply(As_cur, Bs_cur);
             colsum_tile(Bs_cur);
-            if (k0 + BK < k_end) store_tile(sa0, sb0, As_nxt, Bs_nxt, k0 + BK);
+            if (k0 + BK < k_end) land_tile(As_nxt, Bs_nxt, k0 + BK);
             __syncthreads();
         };
         for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
@@ -557,7 +648,7 @@ __device__ __forceinline__ bool next_tile(int gid, int tiles_m, int tiles_n, int
 // Z = [H_self | mean] * [W_self; W_neigh] + b, ReLU except on the last layer; b is the stacked
 // weight matrix, its columns padded to a multiple of 4
 template <class T, int VA, int VB>
-__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_linear_fwd(MatRows a, MatRows b, EpiFwd epi,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6 : 2, T::LEAN ? 6 : 8))) void k_sage_linear_fwd(MatRows a, MatRows b, EpiFwd epi,
                                                          const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (b.cols + T::BN - 1) / T::BN;
@@ -586,7 +677,7 @@ __device__ __forceinline__ int grad_w_chunk_rows(int n1, int nchunk, int rows_mi
 // dealt round-robin to the 8 XCDs) and share its L2.  Partials go to a per-chunk slab; a
 // fixed-order reduction follows (deterministic, no atomics).
 template <class T, int VA, int VB>
-__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_w(MatRows a, MatRows dz, EpiGradW epi, int nchunk,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6 : 2, T::LEAN ? 6 : 8))) void k_sage_grad_w(MatRows a, MatRows dz, EpiGradW epi, int nchunk,
                                                      int rows_min, int tiles_m, int tiles_n,
                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
@@ -644,7 +735,7 @@ __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLeve
 // [dH_self | dMean / cnt] = dZ * [W_self; W_neigh]^T per destination row; w is the stacked weight
 // matrix (2 D rows, columns padded to a multiple of 4), n_k the true number of columns
 template <class T, int VA, int VB>
-__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(2, T::LEAN ? 6 : 8))) void k_sage_grad_in(MatRows dz, MatRows w, EpiGradIn epi,
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6 : 2, T::LEAN ? 6 : 8))) void k_sage_grad_in(MatRows dz, MatRows w, EpiGradIn epi,
                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
     const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (w.rows + T::BN - 1) / T::BN;
@@ -905,7 +996,7 @@ void launch_grad_in(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool vdz, const
     if (!vdz) {
         if (few) launch_grad_in_t<TileLow, 1, 4>(ctx, st, ub, dz, w, epi, mu);
         else launch_grad_in_t<TileMid, 1, 4>(ctx, st, ub, dz, w, epi, mu);
-    } else if (!few) launch_grad_in_t<TileMid, 4, 4>(ctx, st, ub, dz, w, epi, mu);
+    } else if (!few) launch_grad_in_t<TileMidDirect, 4, 4>(ctx, st, ub, dz, w, epi, mu);
     else if (w.rows <= 64) launch_grad_in_t<TileLowNarrow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
     else launch_grad_in_t<TileLow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
 }
