@@ -19,6 +19,8 @@
 // A dependent HBM access costs about a microsecond, and these kernels are chains of them, so every
 // element remembers the table entry it landed in (no second probe sequence) and the count passes
 // leave their classification behind for the scatter passes.
+#include <algorithm>
+
 #include "gsplit_internal.h"
 
 namespace {
@@ -590,13 +592,17 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
 }
 
 // reverse index, step 2: give every row of local_cat[l] a segment of rev_list (segments need not
-// be in row order: one atomic per wave hands out space)
-__global__ __launch_bounds__(256) void k_rev_alloc(const int32_t *__restrict__ rev_cnt,
-                                                   int32_t *__restrict__ rev_ptr,
-                                                   int32_t *__restrict__ rev_fill,
-                                                   GsLevelMeta *meta_lo, int S) {
+// be in row order: one atomic per workgroup of 1024 rows hands out space; the cursor is a single
+// address, and an atomic on it from every wave of a million-row level took longer than the
+// rest of the kernel)
+__global__ __launch_bounds__(1024) void k_rev_alloc(const int32_t *__restrict__ rev_cnt,
+                                                    int32_t *__restrict__ rev_ptr,
+                                                    int32_t *__restrict__ rev_fill,
+                                                    GsLevelMeta *meta_lo, int S) {
+    __shared__ int s_wave[16];
+    __shared__ int s_base;
     const int n_lo = meta_lo->front_off[S];
-    const int lane = lane_id();
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int stride = gridDim.x * blockDim.x;
     const int rounds = (n_lo + stride - 1) / stride;
     for (int it = 0; it < rounds; ++it) {
@@ -607,13 +613,19 @@ __global__ __launch_bounds__(256) void k_rev_alloc(const int32_t *__restrict__ r
             int up = __shfl_up(inc, o);
             if (lane >= o) inc += up;
         }
-        int base = 0;
-        if (lane == 63 && inc > 0) base = atomicAdd(&meta_lo->rev_cursor, inc);
-        base = __shfl(base, 63);
+        if (lane == 63) s_wave[wave] = inc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int tot = 0;
+            for (int w = 0; w < 16; ++w) { const int x = s_wave[w]; s_wave[w] = tot; tot += x; }
+            s_base = tot > 0 ? atomicAdd(&meta_lo->rev_cursor, tot) : 0;
+        }
+        __syncthreads();
         if (u < n_lo) {
-            rev_ptr[u] = base + inc - c;
+            rev_ptr[u] = s_base + s_wave[wave] + inc - c;
             rev_fill[u] = 0;
         }
+        __syncthreads();
     }
 }
 
@@ -758,7 +770,8 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         if (l > 0) {
             {
                 GsTimeScope ts(ctx, "rev_alloc", l, st);
-                hipLaunchKernelGGL(k_rev_alloc, dim3(grid_for(ctx, ctx->ub_front[l])), dim3(256), 0, st,
+                hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
+                                       (int64_t)ctx->n_cu * 2, gs_ceil_div(ctx->ub_front[l], 1024)))), dim3(1024), 0, st,
                                    B.rev_cnt, B.rev_ptr, B.rev_fill, ml, S);
             }
             GsTimeScope ts(ctx, "rev_fill", l, st);
