@@ -753,14 +753,14 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6
 // scatter side of the shuffle index.  The ReLU of the layer below is applied on the way out, so
 // the result is that layer's dZ.  One lane group per row, 4 floats per lane; no atomics, and rows
 // that fed nothing get zeros.
-template <int LPR, bool HACT_H>
+template <int LPR, bool HACT_H, bool OUT_H = false>
 __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict__ gin, int D,
                                                          const int32_t *__restrict__ rev_ptr,
                                                          const int32_t *__restrict__ rev_cnt,
                                                          const int32_t *__restrict__ rev_list,
                                                          const void *__restrict__ hact,
                                                          const GsLevelMeta *__restrict__ meta_lo, int S,
-                                                         float *__restrict__ gout) {
+                                                         void *__restrict__ gout) {
     const int n_lo = meta_lo->front_off[S];
     const int nvec = D >> 2;
     const int c0 = threadIdx.x % LPR;
@@ -794,7 +794,13 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
             }
             acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
             acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
-            O4[(int64_t)u * nvec + c] = acc;
+            // bf16 storage: dZ is kept as the bf16 value that both backward products consume
+            if (OUT_H)
+                reinterpret_cast<uint2 *>(gout)[(int64_t)u * nvec + c] =
+                    make_uint2((uint32_t)f2bf(acc.x) | ((uint32_t)f2bf(acc.y) << 16),
+                               (uint32_t)f2bf(acc.z) | ((uint32_t)f2bf(acc.w) << 16));
+            else
+                O4[(int64_t)u * nvec + c] = acc;
         }
     }
 }
@@ -1158,11 +1164,14 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
         const float *dH = l == L - 1 ? d_grad_logits : sb.ghid[l + 1];
         const int64_t ub = ctx->ub_front[l + 1];
+        const bool h16 = p->dtype == GSPLIT_BF16;
+        // bf16 storage: below the top level dZ is held in bf16 when its width allows 16-byte rows
+        const bool dz_h = h16 && l < L - 1 && N % 8 == 0;
         MatRows dz{dH, 0, N};
-        // weight and bias gradients, summed over all splits: [X | 1]^T dZ with the layer input X
+        MatRowsH dzh{(const uint16_t *)dH, 0, N};
+        // weight and bias gradients, summed over all splits: X^T dZ with the layer input X
         // assembled by the forward pass
         MatRows in{(const float *)sb.xin[l], 0, 2 * D};
-        const bool h16 = p->dtype == GSPLIT_BF16;
         EpiGradW ew{sb.gw_part[l], 2 * D + 1, N, h16 ? 2 * D + 1 : 2 * D};
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
@@ -1172,10 +1181,15 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
                 MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
                 const int tm = (int)gs_ceil_div(ew.rows, GBM), tn = (int)gs_ceil_div(ew.N, GBN);
                 dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
-                if (vdz) hipLaunchKernelGGL((k_sage_grad_w_h<4>), grid, dim3(GNT), 0, st, inh, dz, ew, sb.nchunk[l],
-                                            GRAD_W_ROWS_MIN, tm, tn, mu, S);
-                else hipLaunchKernelGGL((k_sage_grad_w_h<1>), grid, dim3(GNT), 0, st, inh, dz, ew, sb.nchunk[l],
-                                        GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                if (dz_h)
+                    hipLaunchKernelGGL((k_sage_grad_w_h<PatchDzH, MatRowsH>), grid, dim3(GNT), 0, st, inh, dzh, ew,
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                else if (vdz)
+                    hipLaunchKernelGGL((k_sage_grad_w_h<PatchDz<4>, MatRows>), grid, dim3(GNT), 0, st, inh, dz, ew,
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                else
+                    hipLaunchKernelGGL((k_sage_grad_w_h<PatchDz<1>, MatRows>), grid, dim3(GNT), 0, st, inh, dz, ew,
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
             } else {
                 launch_grad_w(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
             }
@@ -1188,7 +1202,8 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
                 if (h16) {
                     dim3 grid(row_block_grid<TileMid>(ctx, ub, 2 * D));
                     MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
-                    if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
+                    if (dz_h) hipLaunchKernelGGL(k_sage_grad_in_hh, grid, dim3(GNT), 0, st, dzh, wsk, ei, mu, S);
+                    else if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
                     else hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
                 } else {
                     MatRows w{sb.wstack32[l], 2 * D, (N + 3) & ~3};
@@ -1200,27 +1215,33 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             const void *hact = sb.hidden[l];
             const int64_t ubl = ctx->ub_front[l];
             if (h16) {
-                if (D / 4 <= 16)
-                    hipLaunchKernelGGL((k_pull_input_grad<16, true>), dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
-                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
-                else if (D / 4 <= 32)
-                    hipLaunchKernelGGL((k_pull_input_grad<32, true>), dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
-                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
-                else
-                    hipLaunchKernelGGL((k_pull_input_grad<64, true>), dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
-                                       sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                // the level's dZ is held in bf16 under the same condition its consumers test (dz_h)
+                const bool out_h = D % 8 == 0;
+#define GS_PULL_H(LPR)                                                                                          \
+    do {                                                                                                        \
+        if (out_h)                                                                                              \
+            hipLaunchKernelGGL((k_pull_input_grad<LPR, true, true>), dim3(grid_1d(ctx, ubl * LPR)), dim3(256), 0, st, \
+                               sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);  \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_pull_input_grad<LPR, true, false>), dim3(grid_1d(ctx, ubl * LPR)), dim3(256), 0, st, \
+                               sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);  \
+    } while (0)
+                if (D / 4 <= 16) GS_PULL_H(16);
+                else if (D / 4 <= 32) GS_PULL_H(32);
+                else GS_PULL_H(64);
+#undef GS_PULL_H
             } else if (D % 4 != 0) {
                 hipLaunchKernelGGL(k_pull_input_grad_any, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, (const float *)hact, ml, S, sb.ghid[l]);
             } else if (D / 4 <= 16) {
                 hipLaunchKernelGGL((k_pull_input_grad<16, false>), dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
             } else if (D / 4 <= 32) {
                 hipLaunchKernelGGL((k_pull_input_grad<32, false>), dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
             } else {
                 hipLaunchKernelGGL((k_pull_input_grad<64, false>), dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, sb.ghid[l]);
+                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
             }
         }
     }

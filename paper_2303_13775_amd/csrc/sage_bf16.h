@@ -303,6 +303,21 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_in_h(MatRows dz, MatRowsH wst
     }
 }
 
+// the same with dZ already held in bf16 (levels below the top one, width a multiple of 8)
+__global__ __launch_bounds__(GNT) void k_sage_grad_in_hh(MatRowsH dz, MatRowsH wstack, EpiGradIn epi,
+                                                         const GsLevelMeta *__restrict__ meta_up, int S) {
+    const int n1 = meta_up->front_off[S];
+    const int tiles_m = (n1 + GBM - 1) / GBM, tiles_n = (wstack.rows + GBN - 1) / GBN;
+    const int total = ((tiles_m + 7) & ~7) * tiles_n;
+    dz.rows = n1; epi.n1 = n1;
+    for (int gid = blockIdx.x; gid < total; gid += gridDim.x) {
+        int m0, n0;
+        if (!next_tile<TileMid>(gid, tiles_m, tiles_n, m0, n0)) continue;
+        gemm_tile_h<GBM, GBN, StagerH<GBM, GNT, MatRowsH>, StagerH<GBN, GNT, MatRowsH>>(
+            m0, n0, n1, wstack.rows, dz.cols, dz, wstack, epi);
+    }
+}
+
 // bf16 matrix followed by a column of ones, read by the float weight-gradient product
 struct MatRowsOnesH {
     const uint16_t *p; int rows; int cols;
@@ -381,6 +396,31 @@ struct PatchDz {
         lds[t_word(row + 3, kp)] = pack_bf16(r10.w, r11.w);
     }
 };
+// dZ already held in bf16 (cols % 4 == 0)
+struct PatchDzH {
+    uintx2 r00, r01, r10, r11;     // r<pass><k of the pair>
+    static __device__ __forceinline__ uintx2 fetch(const MatRowsH &dz, int n, int k, int k_end, bool full) {
+        const uintx2 v = *reinterpret_cast<const uintx2 *>(dz.p + (int64_t)min(k, dz.rows - 1) * dz.cols + min(n, dz.cols - 4));
+        const uintx2 zero = {0u, 0u};
+        return (full || k < k_end) ? v : zero;
+    }
+    __device__ __forceinline__ void load(const MatRowsH &dz, int n0, int k, int k_end, int x, bool full) {
+        r00 = fetch(dz, n0 + 4 * x, k, k_end, full);
+        r01 = fetch(dz, n0 + 4 * x, k + 1, k_end, full);
+        r10 = fetch(dz, n0 + 4 * (x + 16), k, k_end, full);
+        r11 = fetch(dz, n0 + 4 * (x + 16), k + 1, k_end, full);
+    }
+    static __device__ __forceinline__ void put(uint32_t *lds, int row, int kp, uintx2 a, uintx2 b) {
+        lds[t_word(row, kp)] = (a.x & 0xFFFFu) | (b.x << 16);
+        lds[t_word(row + 1, kp)] = (a.x >> 16) | (b.x & 0xFFFF0000u);
+        lds[t_word(row + 2, kp)] = (a.y & 0xFFFFu) | (b.y << 16);
+        lds[t_word(row + 3, kp)] = (a.y >> 16) | (b.y & 0xFFFF0000u);
+    }
+    __device__ __forceinline__ void store(uint32_t *lds, int x, int kp) const {
+        put(lds, 4 * x, kp, r00, r01);
+        put(lds, 4 * (x + 16), kp, r10, r11);
+    }
+};
 // [X | 1]: bf16 matrix with its column of ones, read k-major
 struct PatchX {
     uintx2 r0, r1;
@@ -402,8 +442,9 @@ struct PatchX {
     }
 };
 
-template <int VW>
-__global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, MatRows dz, EpiGradW epi, int nchunk,
+// PDZ / DZ: PatchDz<4 or 1> with a float dZ (MatRows), PatchDzH with a bf16 dZ (MatRowsH)
+template <class PDZ, class DZ>
+__global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, DZ dz, EpiGradW epi, int nchunk,
                                                        int rows_min, int tiles_m, int tiles_n,
                                                        const GsLevelMeta *__restrict__ meta_up, int S) {
     const int n1 = meta_up->front_off[S];
@@ -429,14 +470,14 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, MatRows d
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     PatchX pa0, pa1;
-    PatchDz<VW> pb0, pb1;
+    PDZ pb0, pb1;
 
-    auto load_tile = [&](PatchX &pa, PatchDz<VW> &pb, int k0) {
+    auto load_tile = [&](PatchX &pa, PDZ &pb, int k0) {
         const bool full = k0 + BKH <= k_end;
         pa.load(a, tok, k0 + 2 * kp, k_end, full);
         pb.load(dz, n0, k0 + 2 * kp, k_end, x, full);
     };
-    auto store_tile = [&](const PatchX &pa, const PatchDz<VW> &pb, uint32_t *buf) {
+    auto store_tile = [&](const PatchX &pa, const PDZ &pb, uint32_t *buf) {
         pa.store(buf, x, kp);
         pb.store(buf + GBM * 32, x, kp);
     };
@@ -457,7 +498,7 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, MatRows d
     };
     // one k-tile: the registers that held tile k0 (now in LDS) are refilled with tile k0 + 2 BKH,
     // tile k0 is multiplied, tile k0 + BKH moves from the other registers to the other LDS stage
-    auto step = [&](PatchX &pa_cur, PatchDz<VW> &pb_cur, const PatchX &pa_nxt, const PatchDz<VW> &pb_nxt,
+    auto step = [&](PatchX &pa_cur, PDZ &pb_cur, const PatchX &pa_nxt, const PDZ &pb_nxt,
                     const uint32_t *buf_cur, uint32_t *buf_nxt, int k0) {
         if (k0 + 2 * BKH < k_end) load_tile(pa_cur, pb_cur, k0 + 2 * BKH);
         multiply(buf_cur);
