@@ -81,6 +81,9 @@ CASES = {
                                                batch=500, n_splits=4, pmap_kind="range", name="deep"),
     "fan64": lambda: workloads.custom(1500, 120000, dims=[8, 8], fanouts=[64], batch=64, n_splits=2,
                                       name="fan64"),
+    # more than 2**20 slots at the upper bound of the bottom layer: the 1024-chunk partition
+    "many-chunks": lambda: workloads.custom(60000, 1500000, dims=[8, 8, 8, 4], fanouts=[15, 10, 5], batch=2048,
+                                            n_splits=4, pmap_kind="range", name="chunks"),
 }
 
 
@@ -240,13 +243,16 @@ BF16_CASES = {
                                             batch=512, n_splits=4, pmap_kind="range", name="mdims"),
     "deep-S8": lambda: workloads.custom(20000, 500000, dims=[128, 256, 256, 256, 172], fanouts=[10, 10, 10, 10],
                                         batch=300, n_splits=8, name="deep"),
+    # hidden widths that are multiples of 4 but not of 8: dZ stays in float below the top level
+    "width-mod-4": lambda: workloads.custom(6000, 150000, dims=[100, 60, 44, 10], fanouts=[8, 6, 4], batch=300,
+                                            n_splits=3, name="mod4"),
 }
 
 
 @pytest.mark.parametrize("name", list(BF16_CASES))
 def test_sage_bf16_path_within_tolerance(name):
-    """bf16 storage + bf16 MFMA forward and input-gradient products (float accumulation, float
-    weight-gradient product) against the oracle that rounds the same stored values to bf16."""
+    """bf16 storage + bf16 MFMA products (float accumulation) against the oracle that rounds the
+    same stored values to bf16."""
     dev = _dev()
     w = BF16_CASES[name]()
     r = _run_fwd_bwd(w, dev, seed=31, it=1, bf16=True)
