@@ -185,7 +185,10 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
  * gsplit_timing_read waits for the recorded events, writes one line per kernel label
  * ("<label> <launches> <total milliseconds>\n", labels carry the layer as ".l<k>") into buf as a
  * NUL-terminated string, resets the totals, and returns the string length; ECAPACITY if buf_bytes is
- * too small.  For callers that profile (benchmarks); never needed for results. */
+ * too small.  An event pair adds a few microseconds to what it brackets; the library measures that
+ * once per context (a bracketed 20-microsecond kernel against the same kernel launched back to
+ * back) and subtracts it, so the totals are kernel durations.  For callers that profile (benchmarks); never
+ * needed for results. */
 GSPLIT_API int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable);
 GSPLIT_API int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_bytes);
 

@@ -239,13 +239,59 @@ extern "C" int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable) {
     return GSPLIT_OK;
 }
 
+// about 20 us of waiting on the 100 MHz wall clock (the loop is bounded by its iteration count too)
+__global__ void k_timing_probe(int ticks) {
+    const long long t0 = wall_clock64();
+    for (int i = 0; i < 100000 && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(8);
+}
+
+// What an event pair adds to the kernel it brackets: (a bracketed kernel) - (the same kernel at
+// back-to-back rate), for a kernel about as long as the ones that matter (part of the event's own
+// processing hides behind a running kernel, so an empty kernel would overstate it).  Measured once
+// per context, on the stream of the last batch.
+static double timing_overhead_ms(gsplit_ctx *ctx) {
+    GsTimer &t = ctx->timer;
+    if (t.overhead_ms >= 0.0) return t.overhead_ms;
+    hipStream_t st = ctx->last_stream;
+    hipEvent_t a = nullptr, b = nullptr;
+    double ovh = 0.0;
+    if (hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+        const int reps = 16, burst = 32, ticks = 2000;
+        double bracket = 0.0;
+        int got = 0;
+        hipLaunchKernelGGL(k_timing_probe, dim3(1), dim3(64), 0, st, ticks);
+        for (int i = 0; i < reps; ++i) {
+            float ms = 0.f;
+            (void)hipEventRecord(a, st);
+            hipLaunchKernelGGL(k_timing_probe, dim3(1), dim3(64), 0, st, ticks);
+            (void)hipEventRecord(b, st);
+            if (hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&ms, a, b) == hipSuccess) { bracket += ms; ++got; }
+        }
+        float total = 0.f;
+        (void)hipEventRecord(a, st);
+        for (int i = 0; i < burst; ++i) hipLaunchKernelGGL(k_timing_probe, dim3(1), dim3(64), 0, st, ticks);
+        (void)hipEventRecord(b, st);
+        if (got == reps && hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&total, a, b) == hipSuccess) {
+            bracket /= reps;
+            const double each = (total - bracket) / (burst - 1);
+            ovh = std::min(0.01, std::max(0.0, bracket - each));
+        }
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    (void)hipGetLastError();
+    t.overhead_ms = ovh;
+    return ovh;
+}
+
 extern "C" int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_bytes) {
     if (!ctx || !buf || buf_bytes < 1) return GSPLIT_EINVAL;
     GsTimer &t = ctx->timer;
+    const double ovh = t.pending.empty() ? 0.0 : timing_overhead_ms(ctx);
     for (auto &r : t.pending) {
         float ms = 0.f;
         if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
-            t.total_ms[r.label] += ms;
+            t.total_ms[r.label] += std::max(0.0, (double)ms - ovh);
             t.count[r.label] += 1;
         }
         t.pool.push_back(r.a);

@@ -79,6 +79,7 @@ struct GsSageBuf {             // activations kept between forward and backward
 struct GsTimer {
     struct Rec { int label; hipEvent_t a, b; };
     bool enabled = false;
+    double overhead_ms = -1.0;     // what an event pair adds to a bracketed kernel; < 0: not measured yet
     std::vector<std::string> names;
     std::vector<double> total_ms;
     std::vector<int64_t> count;
