@@ -86,11 +86,13 @@ void gso_floyd_select(int64_t d, int32_t k, const uint32_t *words, int64_t *chos
 /* section 6.1).  For every vertex of a local frontier take min(deg, fan) distinct neighbours,   */
 /* uniformly without replacement: all of them in CSR order when deg <= fan, otherwise the CSR    */
 /* positions picked by Floyd's algorithm, in insertion order.  Output is slot-padded:            */
-/* nbr[i*fan + q] for q < cnt[i] (remaining slots are set to -1).                                */
+/* nbr[i*fan + q] for q < cnt[i] (remaining slots are set to -1).  epos (may be NULL) receives    */
+/* the CSR position of the edge behind every slot (-1 for padding): the edge identity that the   */
+/* pre-sampling stage of section 4 counts.                                                       */
 /* ------------------------------------------------------------------------------------------ */
 void gso_sample_layer(const int64_t *indptr, const int32_t *indices,
                       const int32_t *frontier, int64_t n_front, int32_t fan, uint32_t layer,
-                      uint64_t seed, uint64_t iter, int32_t *nbr, int32_t *cnt)
+                      uint64_t seed, uint64_t iter, int32_t *nbr, int32_t *cnt, int64_t *epos)
 {
     uint32_t *words = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(fan > 0 ? fan : 1));
     int64_t *chosen = (int64_t *)malloc(sizeof(int64_t) * (size_t)(fan > 0 ? fan : 1));
@@ -98,15 +100,19 @@ void gso_sample_layer(const int64_t *indptr, const int32_t *indices,
         int32_t v = frontier[i];
         int64_t beg = indptr[v], d = indptr[v + 1] - indptr[v];
         int32_t *row = nbr + i * fan;
+        int64_t *prow = epos ? epos + i * fan : NULL;
         for (int32_t q = 0; q < fan; ++q) row[q] = -1;
+        if (prow) for (int32_t q = 0; q < fan; ++q) prow[q] = -1;
         if (d <= fan) {
             for (int64_t q = 0; q < d; ++q) row[q] = indices[beg + q];
+            if (prow) for (int64_t q = 0; q < d; ++q) prow[q] = beg + q;
             cnt[i] = (int32_t)d;
         } else {
             for (int32_t q = 0; q < fan; ++q)
                 words[q] = gso_philox_word(seed, iter, layer, (uint32_t)v, (uint32_t)q);
             gso_floyd_select(d, fan, words, chosen);
             for (int32_t q = 0; q < fan; ++q) row[q] = indices[beg + chosen[q]];
+            if (prow) for (int32_t q = 0; q < fan; ++q) prow[q] = beg + chosen[q];
             cnt[i] = fan;
         }
     }

@@ -64,7 +64,7 @@ def lib():
         L.gso_floyd_select.argtypes = [C.c_int64, C.c_int32, _u32p, _i64p]
         L.gso_floyd_select.restype = None
         L.gso_sample_layer.argtypes = [_i64p, _i32p, _i32p, C.c_int64, C.c_int32, C.c_uint32,
-                                       C.c_uint64, C.c_uint64, _i32p, _i32p]
+                                       C.c_uint64, C.c_uint64, _i32p, _i32p, C.c_void_p]
         L.gso_sample_layer.restype = None
         L.gso_slot_stream.argtypes = [_i32p, _i32p, C.c_int64, C.c_int32, _i32p]
         L.gso_slot_stream.restype = C.c_int64
@@ -108,12 +108,16 @@ def floyd_select(d: int, k: int, words: np.ndarray) -> np.ndarray:
     return chosen
 
 
-def sample_layer(indptr64, indices, frontier, fan, layer, seed, it):
+def sample_layer(indptr64, indices, frontier, fan, layer, seed, it, want_edge_pos=False):
     frontier = np.ascontiguousarray(frontier, np.int32)
     n = frontier.shape[0]
     nbr = np.empty(n * fan, np.int32)
     cnt = np.empty(n, np.int32)
-    lib().gso_sample_layer(indptr64, indices, frontier, n, fan, layer, seed, it, nbr, cnt)
+    epos = np.empty(n * fan, np.int64) if want_edge_pos else None
+    lib().gso_sample_layer(indptr64, indices, frontier, n, fan, layer, seed, it, nbr, cnt,
+                           epos.ctypes.data if want_edge_pos else None)
+    if want_edge_pos:
+        return nbr.reshape(n, fan), cnt, epos.reshape(n, fan)
     return nbr.reshape(n, fan), cnt
 
 
@@ -504,3 +508,35 @@ def max_rel_err(a: np.ndarray, o: np.ndarray, floor: float = 1e-2) -> float:
     scale = np.maximum(np.abs(o), floor * np.abs(o).max())
     scale = np.where(scale == 0, 1.0, scale)
     return float((np.abs(a - o) / scale).max())
+
+
+# ---------------------------------------------------------------------------------------------
+# Offline pre-sampling (section 4, "pre-sampling stage" and the analysis after Eq. 2)
+# ---------------------------------------------------------------------------------------------
+def presample_counts(indptr, indices, fanouts, batches, seed, iters):
+    """Runs the training sampler (the whole mini-batch, no splitting) on every batch and counts
+    k_v = number of (sample, layer l > 0) pairs in which vertex v appears (layers are the levels of
+    Algorithm 1: level L holds the targets, level 0 the input layer, which does not count) and
+    k_e = number of times CSR edge e is sampled, over all samples and layers.  The weights of the
+    weighted graph G_w are w_V = k_v / N and w_E = k_e / N with N = len(batches)."""
+    indptr64 = np.ascontiguousarray(indptr, np.int64)
+    indices = np.ascontiguousarray(indices, np.int32)
+    n_vertices, L = indptr64.shape[0] - 1, len(fanouts)
+    k_v = np.zeros(n_vertices, np.int64)
+    k_e = np.zeros(indices.shape[0], np.int64)
+    scratch = _Scratch(n_vertices)
+    for targets, it in zip(batches, iters):
+        front = np.ascontiguousarray(targets, np.int32)          # level L (distinct ids)
+        k_v[front] += 1
+        for l in range(L - 1, -1, -1):
+            nbr, cnt, epos = sample_layer(indptr64, indices, front, fanouts[l], l, seed, it, want_edge_pos=True)
+            np.add.at(k_e, epos[epos >= 0], 1)
+            front = unique_first(np.concatenate([front, slot_stream(nbr, cnt)]), scratch)   # level l
+            if l > 0:
+                k_v[front] += 1
+    return k_v, k_e
+
+
+def presample_weights(k_v, k_e, n_samples):
+    """w_V(v) = k_v / N, w_E(e) = k_e / N."""
+    return k_v.astype(np.float64) / n_samples, k_e.astype(np.float64) / n_samples
