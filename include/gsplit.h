@@ -70,6 +70,8 @@ typedef struct {
     int32_t        n_layers;        /* L, 1 .. GSPLIT_MAX_LAYERS */
     const int32_t *fanouts;         /* HOST array [L]; fanouts[l] in 1 .. GSPLIT_MAX_FANOUT */
     int64_t        max_targets;     /* largest n_targets any gsplit_sample_split call will pass */
+    int32_t        keep_edge_ids;   /* 1: the sampler also records the CSR position of every sampled
+                                       edge (8 bytes per slot), which gsplit_presample_accumulate needs */
 } gsplit_config;
 
 /* Creates a context on the current HIP device and allocates its workspace, sized from the
@@ -191,6 +193,23 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
  * needed for results. */
 GSPLIT_API int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable);
 GSPLIT_API int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_bytes);
+
+/* Offline pre-sampling (section 4, "pre-sampling" stage; analysis after Eq. 2): adds the current
+ * batch to running counts from which the weighted graph G_w is built.
+ *   d_vertex_count [n_vertices], uint32: += 1 for every level l > 0 (level L holds the targets,
+ *       level 0, the input layer, does not count) whose frontier holds the vertex            (k_v)
+ *   d_edge_count   [n_edges], uint32   : += 1 for every time CSR edge e was sampled, at any
+ *       layer of this batch                                                                  (k_e)
+ * Either pointer may be NULL (that count is skipped).  The counts do not depend on the number of
+ * splits the context was created with.  Needs keep_edge_ids = 1 for d_edge_count (else ESTATE) and
+ * a batch (ESTATE).  Counters wrap at 2^32.  Asynchronous. */
+GSPLIT_API int gsplit_presample_accumulate(gsplit_ctx *ctx, uint32_t *d_vertex_count, uint32_t *d_edge_count,
+                                           void *stream);
+
+/* w[i] = count[i] / n_samples for i < n (w_V = k_v / N, w_E = k_e / N).  EINVAL for NULL pointers,
+ * n < 0 or n_samples < 1.  Asynchronous. */
+GSPLIT_API int gsplit_presample_weights(gsplit_ctx *ctx, const uint32_t *d_count, int64_t n, int64_t n_samples,
+                                        float *d_weight, void *stream);
 
 /* Loss between forward and backward.  The paper only says that the target features "are used to
  * calculate the loss" (section 2); this is the usual choice for node classification: mean softmax

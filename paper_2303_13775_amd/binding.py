@@ -23,7 +23,7 @@ EXPORTS = [
     "gsplit_create", "gsplit_destroy", "gsplit_last_error", "gsplit_max_rows", "gsplit_sample_split",
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
     "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
-    "gsplit_timing_read",
+    "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
 ]
 
 
@@ -40,7 +40,8 @@ class _Graph(C.Structure):
 
 
 class _Config(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("fanouts", C.POINTER(C.c_int32)), ("max_targets", C.c_int64)]
+    _fields_ = [("n_layers", C.c_int32), ("fanouts", C.POINTER(C.c_int32)), ("max_targets", C.c_int64),
+                ("keep_edge_ids", C.c_int32)]
 
 
 class _LevelView(C.Structure):
@@ -88,6 +89,8 @@ def load_library():
     L.gsplit_timing_enable.argtypes = [vp, i32]
     L.gsplit_timing_read.argtypes = [vp, C.c_char_p, i64]
     L.gsplit_timing_read.restype = i64
+    L.gsplit_presample_accumulate.argtypes = [vp, vp, vp, vp]
+    L.gsplit_presample_weights.argtypes = [vp, vp, i64, i64, vp, vp]
     for name in EXPORTS:
         if name not in ("gsplit_last_error", "gsplit_max_rows", "gsplit_timing_read"):
             getattr(L, name).restype = C.c_int
@@ -155,7 +158,7 @@ class Context:
     """gsplit_ctx wrapper.  Methods mirror the C entry points one to one."""
 
     def __init__(self, indptr: torch.Tensor, indices: torch.Tensor, pmap: torch.Tensor, n_splits: int,
-                 fanouts: Sequence[int], max_targets: int):
+                 fanouts: Sequence[int], max_targets: int, keep_edge_ids: bool = False):
         self.lib = load_library()
         assert indptr.is_cuda and indices.is_cuda and pmap.is_cuda
         assert indptr.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32
@@ -170,7 +173,8 @@ class Context:
         self._fan = (C.c_int32 * self.L)(*self.fanouts)
         g = _Graph(self.n_vertices, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
                    indices.data_ptr(), pmap.data_ptr(), self.S)
-        c = _Config(self.L, self._fan, int(max_targets))
+        self.n_edges = indices.numel()
+        c = _Config(self.L, self._fan, int(max_targets), int(keep_edge_ids))
         h = C.c_void_p()
         with torch.cuda.device(self.device):
             rc = self.lib.gsplit_create(C.byref(h), C.byref(g), C.byref(c))
@@ -270,6 +274,22 @@ class Context:
                                                  grad_logits.data_ptr(),
                                                  row_loss.data_ptr() if row_loss is not None else None,
                                                  _stream()))
+
+    def gsplit_presample_accumulate(self, vertex_count: Optional[torch.Tensor], edge_count: Optional[torch.Tensor]):
+        # torch has no unsigned 32-bit arithmetic: int32 tensors carry the uint32 counters
+        for t, n in ((vertex_count, self.n_vertices), (edge_count, self.n_edges)):
+            if t is not None:
+                assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.numel() == n
+        self._check(self.lib.gsplit_presample_accumulate(
+            self.h, vertex_count.data_ptr() if vertex_count is not None else None,
+            edge_count.data_ptr() if edge_count is not None else None, _stream()))
+
+    def gsplit_presample_weights(self, count: torch.Tensor, n_samples: int, weight: torch.Tensor):
+        assert count.is_cuda and count.dtype == torch.int32 and count.is_contiguous()
+        assert weight.is_cuda and weight.dtype == torch.float32 and weight.is_contiguous()
+        assert weight.numel() == count.numel()
+        self._check(self.lib.gsplit_presample_weights(self.h, count.data_ptr(), count.numel(), int(n_samples),
+                                                      weight.data_ptr(), _stream()))
 
     def gsplit_timing_enable(self, enable: bool):
         self._check(self.lib.gsplit_timing_enable(self.h, int(enable)))

@@ -65,6 +65,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     ctx->L = c->n_layers;
     ctx->S = g->n_splits;
     ctx->max_targets = c->max_targets;
+    ctx->keep_edge_ids = c->keep_edge_ids != 0;
     for (int l = 0; l < ctx->L; ++l) ctx->fan[l] = c->fanouts[l];
 
     int dev = 0;
@@ -101,6 +102,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         GsLayerBuf &B = ctx->layer[l];
         const int64_t nd = ctx->ub_front[l + 1], f = ctx->fan[l];
         A((void **)&B.nbr, sizeof(int32_t) * nd * f, "nbr");
+        if (ctx->keep_edge_ids) A((void **)&B.epos, sizeof(int64_t) * nd * f, "edge positions");
         A((void **)&B.cnt, sizeof(int32_t) * nd, "cnt");
         A((void **)&B.mixed, sizeof(int32_t) * nd * (1 + f), "mixed");
         A((void **)&B.blk_indptr, sizeof(int32_t) * (nd + 1), "blk_indptr");

@@ -40,6 +40,7 @@ struct GsTable {
 
 struct GsLayerBuf {            // sampling layer l
     int32_t *nbr = nullptr;        // [ub_dst * fan]
+    int64_t *epos = nullptr;       // [ub_dst * fan]  CSR position behind every slot (keep_edge_ids only)
     int32_t *cnt = nullptr;        // [ub_dst]
     int32_t *mixed = nullptr;      // [ub_dst * (1 + fan)]
     int32_t *blk_indptr = nullptr; // [ub_dst + 1]
@@ -92,6 +93,7 @@ struct gsplit_ctx {
     int32_t  L = 0, S = 0;
     int32_t  fan[GS_MAXL] = {0};
     int64_t  max_targets = 0;
+    bool     keep_edge_ids = false;
     int64_t  ub_front[GS_MAXL + 1] = {0};   // upper bounds on |local_cat[l]|
     int      n_cu = 256;
 

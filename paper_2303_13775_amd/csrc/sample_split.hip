@@ -118,7 +118,8 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                                                       uint64_t iter, GsTable tab,
                                                       int32_t *__restrict__ ent_mixed,
                                                       int32_t *__restrict__ nbr,
-                                                      int32_t *__restrict__ cnt) {
+                                                      int32_t *__restrict__ cnt,
+                                                      int64_t *__restrict__ epos) {
     const int n1 = meta_up->front_off[S];
     const int bits = table_bits(n1 * (1 + fan));
     const int groups_per_block = PART_BS / G;
@@ -161,10 +162,13 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             }
         }
         if (active && q < fan) {
-            if (floyd) val = indices[beg + (int64_t)chosen];
-            else if ((uint32_t)q < d) val = indices[beg + q];
+            int64_t pos = -1;
+            if (floyd) pos = beg + (int64_t)chosen;
+            else if ((uint32_t)q < d) pos = beg + q;
+            if (pos >= 0) val = indices[pos];
             const int64_t g = (int64_t)row * fan + q;
             nbr[g] = val;
+            if (epos) epos[g] = pos;
             const uint32_t sp = (uint32_t)split_of(meta_up->front_off, S, row);
             if (q == 0) {
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
@@ -704,15 +708,15 @@ void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStre
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     } else if (fan <= 32) {
         hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     } else {
         hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt);
+                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     }
 }
 
