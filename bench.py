@@ -41,6 +41,8 @@ def parse():
                     help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
                          "overlaps forward/backward of step i on a second stream)")
     ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
+    ap.add_argument("--presample", action="store_true",
+                    help="measure the offline pre-sampling stage instead (sampling + counting of k_v, k_e)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
@@ -180,6 +182,71 @@ def cpu_baseline(w_host, iters):
                       f"numpy float64 matmuls on {threads} BLAS threads), {dt:.1f} s"}
 
 
+def presample_bench(a, w, dev, t_gen):
+    """Offline pre-sampling (paper section 4): the training sampler plus the counting of k_v and
+    k_e, one sample (mini-batch) per step, serial on one stream."""
+    import torch
+    from paper_2303_13775_amd import Context
+    ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch, keep_edge_ids=True)
+    k_v = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
+    k_e = torch.zeros(w.indices.numel(), dtype=torch.int32, device=dev)
+    n_total = a.warmup + a.steps
+    targets = [w.targets(i) for i in range(n_total)]
+
+    def step(i):
+        ctx.gsplit_sample_split(targets[i], 0xC0FFEE, i)
+        ctx.gsplit_presample_accumulate(k_v, k_e)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.warmup, n_total):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # kernel time of the counting launch and its algorithmic bytes (4-byte id or 8-byte edge
+    # position read, one 4-byte counter touched)
+    ctx.gsplit_timing_enable(True)
+    n_k = min(a.steps, 30)
+    work = 0.0
+    for i in range(a.warmup, a.warmup + n_k):
+        step(i)
+        n_local, _, n_edges, _ = ctx.gsplit_batch_sizes()
+        rows = [sum(x) for x in n_local]
+        slots = sum(rows[l + 1] * w.fanouts[l] for l in range(len(w.fanouts)))
+        work += sum(rows[1:]) * 8 + slots * 8 + sum(sum(x) for x in n_edges) * 4
+    torch.cuda.synchronize()
+    kt = ctx.gsplit_timing_read()
+    cnt, ms = kt["presample_accumulate"]
+    sec = ms / max(cnt, 1) * 1e-3
+    ach = work / n_k / sec / 1e9
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import reference as R
+        R.build_oracle()
+        ip, ix = w.indptr.cpu().numpy(), w.indices.cpu().numpy()
+        n_cpu = max(1, min(a.cpu_iters, 60))
+        tc = time.perf_counter()
+        R.presample_counts(ip, ix, w.fanouts, [targets[i].cpu().numpy() for i in range(n_cpu)], 0xC0FFEE,
+                           list(range(n_cpu)))
+        dtc = time.perf_counter() - tc
+        cpu = {"value": n_cpu / dtc, "unit": "samples/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} samples of the same workload, single-threaded C steps, {dtc:.1f} s"}
+    out = {
+        "metric": "pre-sampling samples/sec (sample + count k_v, k_e) at 1 GPU", "value": a.steps / dt,
+        "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": dt / a.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": dict(w.describe(), graph_gen_s=round(t_gen, 1), schedule="serial, one stream"),
+        "kernel_us_per_step": {k: round(v[1] / n_k * 1e3, 2) for k, v in sorted(kt.items(), key=lambda kv: -kv[1][1])},
+        "roofline": {"kernel": "presample_accumulate", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": work / n_k, "launch_ms": ms / max(cnt, 1)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -215,6 +282,8 @@ def main():
     if a.workload == "sweep":       # tens of GB of buffers per context, kernels that fill the chip: one stream
         a.no_pipeline = True
     t_gen = time.time() - t0
+    if a.presample:
+        return presample_bench(a, w, dev, t_gen)
     r = Runner(w, dev)
     n_total = a.warmup + a.steps
     targets = [w.targets(i) for i in range(n_total)]
