@@ -72,6 +72,8 @@ typedef struct {
     int64_t        max_targets;     /* largest n_targets any gsplit_sample_split call will pass */
     int32_t        keep_edge_ids;   /* 1: the sampler also records the CSR position of every sampled
                                        edge (8 bytes per slot), which gsplit_presample_accumulate needs */
+    int32_t        gat_index;       /* 1: the scatter side of the shuffle index is also built for the bottom
+                                       layer and carries edge ids, which gsplit_gat_bwd needs */
 } gsplit_config;
 
 /* Creates a context on the current HIP device and allocates its workspace, sized from the
@@ -181,6 +183,47 @@ GSPLIT_API int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *params
 GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params, const float *d_grad_logits,
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
+
+/* GAT layer on the split mini-batch: the paper's second model (section 7.1), the layer of
+ * Velickovic et al. (ICLR 2018) that it cites, run as `gnn_layer` of Algorithm 2.  Layer l, head k,
+ * destination i with neighbourhood N(i) = {i} + its sampled neighbours:
+ *     z_j = h_j W^k,   e_ij = LeakyReLU_0.2(a_dst^k . z_i + a_src^k . z_j),
+ *     alpha_ij = softmax_j e_ij,   out_i^k = sum_j alpha_ij z_j
+ *     hidden layers: h'_i = ELU(concat_k out_i^k + b);   last layer: logits_i = mean_k out_i^k + b
+ * F_l = features per head.  dims[0] = input width; dims[l+1] = heads[l] * F_l for hidden layers,
+ * F_l for the last one.  All parameters float32 in DEVICE memory:
+ *   d_w[l]      [dims[l] x heads[l] * F_l] row-major, head k in columns k F_l .. (k+1) F_l - 1
+ *   d_a_src[l], d_a_dst[l]  [heads[l] * F_l]
+ *   d_bias[l]   [dims[l+1]]
+ * Limits: heads[l] <= 64; F_l <= 1024 / p with p = heads[l] rounded up to a power of two;
+ * (1 + fanouts[l]) * (1 + heads[l]) <= 3072.
+ * Needs a context created with gat_index = 1 (else ESTATE). */
+typedef struct gsplit_gat_params {
+    int32_t             dtype;       /* GSPLIT_F32 */
+    const int32_t      *dims;        /* HOST [L+1] */
+    const int32_t      *heads;       /* HOST [L] */
+    const void *const  *d_w;         /* HOST [L] of device pointers */
+    const void *const  *d_a_src;
+    const void *const  *d_a_dst;
+    const void *const  *d_bias;
+} gsplit_gat_params;
+
+/* Forward pass on the current batch.  d_feat_local = output of gsplit_gather_features (float32,
+ * [rows of level 0 x dims[0]]).  d_logits [n_targets x dims[L]] float32, rows as in
+ * gsplit_sage_fwd.  Keeps the transformed rows, the attention coefficients and the activations
+ * inside the context for the backward pass.  Asynchronous. */
+GSPLIT_API int gsplit_gat_fwd(gsplit_ctx *ctx, const gsplit_gat_params *params, const void *d_feat_local,
+                              float *d_logits, void *stream);
+
+/* Backward pass from d_grad_logits [n_targets x dims[L]], top layer down; gradients of rows held
+ * by other splits travel back through the reversed shuffle index, parameter gradients are summed
+ * over all splits.  d_feat_local: the buffer the forward pass read, unchanged.  Outputs (HOST
+ * arrays of DEVICE pointers, each buffer overwritten, float32): d_gw[l] like d_w[l], d_ga_src[l],
+ * d_ga_dst[l] [heads[l] * F_l], d_gbias[l] [dims[l+1]].  No gradient for the input features.  Needs
+ * a preceding gsplit_gat_fwd on the same batch with the same params (ESTATE).  Asynchronous. */
+GSPLIT_API int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *params, const void *d_feat_local,
+                              const float *d_grad_logits, float *const *d_gw, float *const *d_ga_src,
+                              float *const *d_ga_dst, float *const *d_gbias, void *stream);
 
 /* Diagnostics: per-kernel device time.  While enabled, every kernel the library launches is
  * bracketed by two events on the stream it runs on (this adds a little host work per launch).

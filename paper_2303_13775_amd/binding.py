@@ -24,6 +24,7 @@ EXPORTS = [
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
     "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
+    "gsplit_gat_fwd", "gsplit_gat_bwd",
 ]
 
 
@@ -41,7 +42,7 @@ class _Graph(C.Structure):
 
 class _Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("fanouts", C.POINTER(C.c_int32)), ("max_targets", C.c_int64),
-                ("keep_edge_ids", C.c_int32)]
+                ("keep_edge_ids", C.c_int32), ("gat_index", C.c_int32)]
 
 
 class _LevelView(C.Structure):
@@ -56,6 +57,12 @@ class _LayerView(C.Structure):
 class _SageParams(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("d_w_self", C.POINTER(C.c_void_p)),
                 ("d_w_neigh", C.POINTER(C.c_void_p)), ("d_bias", C.POINTER(C.c_void_p))]
+
+
+class _GatParams(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("heads", C.POINTER(C.c_int32)),
+                ("d_w", C.POINTER(C.c_void_p)), ("d_a_src", C.POINTER(C.c_void_p)),
+                ("d_a_dst", C.POINTER(C.c_void_p)), ("d_bias", C.POINTER(C.c_void_p))]
 
 
 _lib = None
@@ -91,6 +98,9 @@ def load_library():
     L.gsplit_timing_read.restype = i64
     L.gsplit_presample_accumulate.argtypes = [vp, vp, vp, vp]
     L.gsplit_presample_weights.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.gsplit_gat_fwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, vp]
+    L.gsplit_gat_bwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                 C.POINTER(vp), vp]
     for name in EXPORTS:
         if name not in ("gsplit_last_error", "gsplit_max_rows", "gsplit_timing_read"):
             getattr(L, name).restype = C.c_int
@@ -154,11 +164,32 @@ class SageParams:
         self.dtype = dtype
 
 
+class GatParams:
+    """Holds the marshalled gsplit_gat_params block (and keeps the tensors alive)."""
+
+    def __init__(self, dims: Sequence[int], heads: Sequence[int], w: List[torch.Tensor], a_src: List[torch.Tensor],
+                 a_dst: List[torch.Tensor], bias: List[torch.Tensor]):
+        L = len(dims) - 1
+        assert len(heads) == len(w) == len(a_src) == len(a_dst) == len(bias) == L
+        for l in range(L):
+            width = heads[l] * dims[l + 1] if l == L - 1 else dims[l + 1]
+            for t, n in ((w[l], dims[l] * width), (a_src[l], width), (a_dst[l], width), (bias[l], dims[l + 1])):
+                assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n
+        self.dims, self.heads = list(dims), list(heads)
+        self.widths = [heads[l] * dims[l + 1] if l == L - 1 else dims[l + 1] for l in range(L)]
+        self.tensors = (list(w), list(a_src), list(a_dst), list(bias))
+        self._dims = (C.c_int32 * (L + 1))(*dims)
+        self._heads = (C.c_int32 * L)(*heads)
+        self._ptrs = [(C.c_void_p * L)(*[t.data_ptr() for t in lst]) for lst in self.tensors]
+        self.c = _GatParams(GSPLIT_F32, self._dims, self._heads, *self._ptrs)
+
+
 class Context:
     """gsplit_ctx wrapper.  Methods mirror the C entry points one to one."""
 
     def __init__(self, indptr: torch.Tensor, indices: torch.Tensor, pmap: torch.Tensor, n_splits: int,
-                 fanouts: Sequence[int], max_targets: int, keep_edge_ids: bool = False):
+                 fanouts: Sequence[int], max_targets: int, keep_edge_ids: bool = False,
+                 gat_index: bool = False):
         self.lib = load_library()
         assert indptr.is_cuda and indices.is_cuda and pmap.is_cuda
         assert indptr.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32
@@ -174,7 +205,7 @@ class Context:
         g = _Graph(self.n_vertices, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
                    indices.data_ptr(), pmap.data_ptr(), self.S)
         self.n_edges = indices.numel()
-        c = _Config(self.L, self._fan, int(max_targets), int(keep_edge_ids))
+        c = _Config(self.L, self._fan, int(max_targets), int(keep_edge_ids), int(gat_index))
         h = C.c_void_p()
         with torch.cuda.device(self.device):
             rc = self.lib.gsplit_create(C.byref(h), C.byref(g), C.byref(c))
@@ -261,6 +292,28 @@ class Context:
         c = (C.c_void_p * L)(*[t.data_ptr() for t in gbias])
         self._check(self.lib.gsplit_sage_bwd(self.h, C.byref(params.c), grad_logits.data_ptr(), a, b, c,
                                              _stream()))
+
+    def gsplit_gat_fwd(self, params: GatParams, feat_local: torch.Tensor, logits: torch.Tensor):
+        assert feat_local.is_cuda and feat_local.is_contiguous() and feat_local.dtype == torch.float32
+        assert feat_local.shape[1] == params.dims[0]
+        assert logits.is_cuda and logits.dtype == torch.float32 and logits.is_contiguous()
+        assert logits.shape[1] == params.dims[-1]
+        self._check(self.lib.gsplit_gat_fwd(self.h, C.byref(params.c), feat_local.data_ptr(), logits.data_ptr(),
+                                            _stream()))
+
+    def gsplit_gat_bwd(self, params: GatParams, feat_local: torch.Tensor, grad_logits: torch.Tensor, gw, ga_src,
+                       ga_dst, gbias):
+        L = self.L
+        assert feat_local.is_cuda and feat_local.is_contiguous() and feat_local.dtype == torch.float32
+        assert grad_logits.is_cuda and grad_logits.dtype == torch.float32 and grad_logits.is_contiguous()
+        for lst in (gw, ga_src, ga_dst, gbias):
+            assert len(lst) == L and all(t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() for t in lst)
+        for l in range(L):
+            assert gw[l].numel() == params.dims[l] * params.widths[l] and gbias[l].numel() == params.dims[l + 1]
+            assert ga_src[l].numel() == params.widths[l] and ga_dst[l].numel() == params.widths[l]
+        ptrs = [(C.c_void_p * L)(*[t.data_ptr() for t in lst]) for lst in (gw, ga_src, ga_dst, gbias)]
+        self._check(self.lib.gsplit_gat_bwd(self.h, C.byref(params.c), feat_local.data_ptr(), grad_logits.data_ptr(),
+                                            *ptrs, _stream()))
 
     def gsplit_softmax_xent(self, logits: torch.Tensor, labels: torch.Tensor, grad_logits: torch.Tensor,
                             row_loss: Optional[torch.Tensor] = None):

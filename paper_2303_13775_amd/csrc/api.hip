@@ -66,6 +66,8 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     ctx->S = g->n_splits;
     ctx->max_targets = c->max_targets;
     ctx->keep_edge_ids = c->keep_edge_ids != 0;
+    ctx->gat_index = c->gat_index != 0;
+    ctx->rev_from = ctx->gat_index ? 0 : 1;
     for (int l = 0; l < ctx->L; ++l) ctx->fan[l] = c->fanouts[l];
 
     int dev = 0;
@@ -111,7 +113,8 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         A((void **)&B.src_row, sizeof(int32_t) * nd * (1 + f), "src_row");
         A((void **)&B.self_row, sizeof(int32_t) * nd, "self_row");
         A((void **)&B.edge_row, sizeof(int32_t) * nd * f, "edge_row");
-        if (l > 0) {
+        if (l >= ctx->rev_from) {
+            if (ctx->gat_index) A((void **)&B.rev_eid, sizeof(int32_t) * nd * (1 + f), "rev_eid");
             A((void **)&B.rev_cnt, sizeof(int32_t) * ctx->ub_front[l], "rev_cnt");
             A((void **)&B.rev_ptr, sizeof(int32_t) * ctx->ub_front[l], "rev_ptr");
             A((void **)&B.rev_fill, sizeof(int32_t) * ctx->ub_front[l], "rev_fill");

@@ -55,6 +55,7 @@ struct GsLayerBuf {            // sampling layer l
     int32_t *rev_ptr = nullptr;    // [ub_front[l]]
     int32_t *rev_fill = nullptr;   // [ub_front[l]]
     int32_t *rev_list = nullptr;   // [ub_dst * (1 + fan)]
+    int32_t *rev_eid = nullptr;    // [ub_dst * (1 + fan)]  edge number of an edge entry, -1 for a self entry (gat_index only)
 };
 
 struct GsSageBuf {             // activations kept between forward and backward
@@ -71,6 +72,28 @@ struct GsSageBuf {             // activations kept between forward and backward
     uint16_t *wtrans[GS_MAXL] = {nullptr};      // bf16 [N x 2D] transposed stacked weights
     float   *gw_part[GS_MAXL] = {nullptr};      // per-chunk partial weight gradients
     int      nchunk[GS_MAXL] = {0};             // slabs of gw_part (multiple of 8)
+    bool     fwd_done = false;
+    uint64_t fwd_batch = 0;
+};
+
+struct GsGatBuf {              // GAT: what the forward pass keeps for the backward pass, and scratch
+    bool     ready = false;
+    int32_t  dims[GS_MAXL + 1] = {0};
+    int32_t  heads[GS_MAXL] = {0};
+    float   *wext[GS_MAXL] = {nullptr};      // [D x ZW]  W | W a_src | W a_dst | zero padding
+    float   *zext[GS_MAXL] = {nullptr};      // [rows of level l x ZW]  z | a_src . z | a_dst . z | padding
+    float   *alpha[GS_MAXL] = {nullptr};     // [(ub_dst * fan + ub_dst) x K]  edge slots, then self slots
+    float   *de[GS_MAXL] = {nullptr};        // same shape: d loss / d (score before the LeakyReLU)
+    float   *der[GS_MAXL] = {nullptr};       // [ub_dst x K]  sum of de over a destination's entries
+    float   *gagg[GS_MAXL] = {nullptr};      // [ub_dst x K F]  d loss / d (aggregated heads)
+    float   *dzext[GS_MAXL] = {nullptr};     // [rows of level l x ZW]  gradient of zext
+    float   *hidden[GS_MAXL + 1] = {nullptr};
+    float   *ghid[GS_MAXL + 1] = {nullptr};
+    float   *gw_part[GS_MAXL] = {nullptr};   // split-K slabs of X^T dzext
+    int      nchunk[GS_MAXL] = {0};
+    float   *gmat[GS_MAXL] = {nullptr};      // [D x ZW]  X^T dzext
+    float   *bias_part[GS_MAXL] = {nullptr}; // [bias_slabs x dims[l+1]]
+    int      bias_slabs[GS_MAXL] = {0};
     bool     fwd_done = false;
     uint64_t fwd_batch = 0;
 };
@@ -94,6 +117,8 @@ struct gsplit_ctx {
     int32_t  fan[GS_MAXL] = {0};
     int64_t  max_targets = 0;
     bool     keep_edge_ids = false;
+    bool     gat_index = false;
+    int      rev_from = 1;             // lowest sampling layer with a reverse index (0 with gat_index)
     int64_t  ub_front[GS_MAXL + 1] = {0};   // upper bounds on |local_cat[l]|
     int      n_cu = 256;
 
@@ -119,6 +144,7 @@ struct gsplit_ctx {
     hipEvent_t   sample_done = nullptr;
 
     GsSageBuf    sage;
+    GsGatBuf     gat;
     GsTimer      timer;
     std::vector<void *> allocs;
     std::string  err;
@@ -167,3 +193,13 @@ struct GsTimeScope {
 };
 
 static inline int64_t gs_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// one-dimensional grid of 256-thread workgroups for grid-stride kernels: enough for upper_threads,
+// at most eight workgroups per compute unit
+static inline int grid_1d(const gsplit_ctx *ctx, int64_t upper_threads) {
+    const int64_t want = gs_ceil_div(upper_threads, 256);
+    const int64_t cap = (int64_t)ctx->n_cu * 8;
+    return (int)(want < 1 ? 1 : want > cap ? cap : want);
+}

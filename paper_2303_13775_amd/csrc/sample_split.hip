@@ -483,7 +483,7 @@ struct PartLocal {
     const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
     const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls;
     const int32_t *blk_indptr; int32_t *blk_src; int32_t *rev_cnt;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next; int rev;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return meta_lo->recv_off[S]; }
     __device__ unsigned classify(int r) const {
@@ -517,22 +517,20 @@ struct PartLocal {
     }
     // scatter pass extras: destination vertices keep their order at the head of their owner's
     // frontier; then (layers above the bottom one) the mixed-frontier table is cleared for the
-    // next sampling layer and the counters of this layer's reverse index are zeroed
+    // next sampling layer and (layers that have one) the counters of this layer's reverse index
+    // are zeroed
     __device__ int64_t n_reset(const PartOffs &o) const {
         return fan_next > 0 ? (1ll << table_bits(o.a[S] * (1 + fan_next))) : 0;
     }
     __device__ int64_t n_extra(const PartOffs &o) const {
-        return n1() + n_reset(o) + (fan_next > 0 ? o.a[S] : 0);
+        return n1() + n_reset(o) + (rev ? o.a[S] : 0);
     }
     __device__ void extra(int64_t x, const PartOffs &o) const {
         if (x >= n1()) {
             const int64_t y = x - n1(), nr = n_reset(o);
-            if (y < nr) {
-                tab_mixed.slot[y] = EMPTY_ENTRY;
-                if (y == 0) meta_lo->rev_cursor = 0;
-            } else {
-                rev_cnt[y - nr] = 0;
-            }
+            if (y < nr) tab_mixed.slot[y] = EMPTY_ENTRY;
+            else rev_cnt[y - nr] = 0;
+            if (y == 0) meta_lo->rev_cursor = 0;
             return;
         }
         const int i = (int)x;
@@ -641,12 +639,13 @@ __global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ en
                                                   const int32_t *__restrict__ rev_ptr,
                                                   int32_t *__restrict__ rev_fill,
                                                   int32_t *__restrict__ rev_list,
+                                                  int32_t *__restrict__ rev_eid,
                                                   const GsLevelMeta *__restrict__ meta_up, int S, int fan) {
     const int n1 = meta_up->front_off[S];
     const int64_t total = (int64_t)n1 * (1 + fan);
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
-        int u, code;
+        int u, code, eid = -1;
         if (x < n1) {
             u = self_row[x];
             code = 2 * (int)x;
@@ -654,12 +653,14 @@ __global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ en
             const int64_t g = x - n1;
             if (ent_mixed[n1 + g] < 0) continue;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
-            u = edge_row[blk_indptr[i] + q];
+            eid = blk_indptr[i] + q;
+            u = edge_row[eid];
             code = 2 * i + 1;
         }
         if (u < 0) continue;
         const int p = atomicAdd(&rev_fill[u], 1);
         rev_list[rev_ptr[u] + p] = code;
+        if (rev_eid) rev_eid[rev_ptr[u] + p] = eid;
     }
 }
 
@@ -762,16 +763,16 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
         PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
                      ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src, B.rev_cnt,
-                     ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0};
+                     ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l >= ctx->rev_from ? 1 : 0};
         run_partition(ctx, pl, ub1 * fan, st, "local_front", l);
         {
         GsTimeScope ts(ctx, "shuffle_index", l, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
-                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, l > 0 ? B.rev_cnt : nullptr,
+                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
                            ml, mu, S, fan);
         }
-        if (l > 0) {
+        if (l >= ctx->rev_from) {
             {
                 GsTimeScope ts(ctx, "rev_alloc", l, st);
                 hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
@@ -781,7 +782,7 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
             GsTimeScope ts(ctx, "rev_fill", l, st);
             hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
                                ctx->ent_mixed, B.blk_indptr, B.self_row, B.edge_row, B.rev_ptr, B.rev_fill,
-                               B.rev_list, mu, S, fan);
+                               B.rev_list, B.rev_eid, mu, S, fan);
         }
     }
     GS_HIP(ctx, hipGetLastError());

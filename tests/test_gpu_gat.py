@@ -1,0 +1,140 @@
+"""GPU parity of the GAT layer (paper section 7.1, second model): gsplit_gat_fwd / gsplit_gat_bwd,
+called through the C ABI, against oracle/gat.py on the same seeded batch, features and parameters.
+Logits and every parameter gradient within 1e-4 of the float64 oracle, measured as
+|a - o| / max(|o|, 1e-2 * max|o|)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import reference as R
+from oracle import gat as G
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+def _run(w, heads, dev, seed, it, n_splits=None, pmap=None, batch_targets=None):
+    from paper_2303_13775_amd import Context, GatParams
+    S = n_splits or w.n_splits
+    pm = w.pmap if pmap is None else pmap
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), pm.to(dev), S, w.fanouts, w.batch, gat_index=True)
+    tg = w.targets(it) if batch_targets is None else batch_targets
+    ctx.gsplit_sample_split(tg.to(dev), seed, it)
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=torch.float32, device=dev)
+    ctx.gsplit_gather_features(w.feat.to(dev), x0)
+    wt, a_s, a_d, b = workloads.gat_weights(w.dims, heads, seed=w.seed)
+    params = GatParams(w.dims, heads, [t.to(dev) for t in wt], [t.to(dev) for t in a_s], [t.to(dev) for t in a_d],
+                       [t.to(dev) for t in b])
+    logits = torch.full((tg.numel(), w.dims[-1]), 7.0, device=dev)
+    ctx.gsplit_gat_fwd(params, x0, logits)
+    ob = R.sp_sample(w.indptr.numpy(), w.indices.numpy(), pm.numpy(), S, w.fanouts, tg.numpy(), seed, it)
+    op = G.GatParams(list(heads), [t.numpy() for t in wt], [t.numpy() for t in a_s], [t.numpy() for t in a_d],
+                     [t.numpy() for t in b])
+    of = G.gat_forward(ob, R.gather_rows(w.feat.numpy(), ob.local_cat(0)), op)
+    lab = w.labels.numpy()[tg.numpy()[ob.target_perm]]
+    _, g = R.softmax_xent(of.logits, lab)
+    gw = [torch.full_like(t, 7.0, device=dev) for t in wt]           # must be overwritten
+    gas = [torch.full_like(t, 7.0, device=dev) for t in a_s]
+    gad = [torch.full_like(t, 7.0, device=dev) for t in a_d]
+    gb = [torch.full_like(t, 7.0, device=dev) for t in b]
+    ctx.gsplit_gat_bwd(params, x0, torch.from_numpy(g.astype(np.float32)).to(dev), gw, gas, gad, gb)
+    torch.cuda.synchronize()
+    obw = G.gat_backward(ob, of, op, g)
+    res = dict(logits=logits.cpu().numpy(), gw=[t.cpu().numpy() for t in gw], gas=[t.cpu().numpy() for t in gas],
+               gad=[t.cpu().numpy() for t in gad], gb=[t.cpu().numpy() for t in gb], of=of, ob=obw)
+    ctx.close()
+    return res
+
+
+def _check(r, L):
+    assert R.max_rel_err(r["logits"], r["of"].logits) < TOL_F32, "logits"
+    for l in range(L):
+        assert R.max_rel_err(r["gw"][l], r["ob"].gw[l]) < TOL_F32, ("gw", l)
+        assert R.max_rel_err(r["gas"][l], r["ob"].ga_src[l]) < TOL_F32, ("ga_src", l)
+        assert R.max_rel_err(r["gad"][l], r["ob"].ga_dst[l]) < TOL_F32, ("ga_dst", l)
+        assert R.max_rel_err(r["gb"][l].reshape(-1), r["ob"].gbias[l].reshape(-1)) < TOL_F32, ("gbias", l)
+
+
+# name -> (workload, heads): widths that take the 16-byte and the scalar lane layouts, head counts
+# that are and are not powers of two, one to sixteen values per lane, S = 1 .. 8
+CASES = {
+    "tiny-2x1": (lambda: workloads.tiny(), None),
+    "heads-4-4-1": (lambda: workloads.custom(6000, 150000, dims=[100, 64, 64, 47], fanouts=[6, 5, 4], batch=300,
+                                             n_splits=4, name="gat-a"), [4, 4, 1]),
+    "heads-3-odd-widths": (lambda: workloads.custom(3000, 50000, dims=[30, 33, 10], fanouts=[5, 4], batch=129,
+                                                    n_splits=3, name="gat-b"), [3, 2]),
+    "wide-single-head": (lambda: workloads.custom(8000, 200000, dims=[128, 512, 172], fanouts=[6, 5], batch=256,
+                                                  n_splits=4, pmap_kind="range", name="gat-c"), [1, 1]),
+    "heads-8-S8-fan20": (lambda: workloads.custom(5000, 200000, dims=[64, 256, 40], fanouts=[20, 15], batch=200,
+                                                  n_splits=8, name="gat-d"), [8, 6]),
+    "S1-scalar-wide": (lambda: workloads.custom(2000, 30000, dims=[18, 250, 7], fanouts=[5, 5], batch=300,
+                                                n_splits=1, name="gat-e"), [2, 5]),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_gat_forward_backward_within_tolerance(name):
+    make, heads = CASES[name]
+    w = make()
+    if heads is None:
+        heads = [2] * (w.n_layers - 1) + [1]
+        assert all(w.dims[l + 1] % heads[l] == 0 for l in range(w.n_layers - 1))
+    r = _run(w, heads, _dev(), seed=55, it=1)
+    _check(r, w.n_layers)
+
+
+def test_gat_edge_cases_isolated_targets_and_one_owner():
+    dev = _dev()
+    w = workloads.custom(500, 1500, dims=[8, 8, 4], fanouts=[3, 2], batch=16, n_splits=4, name="edge")
+    ip = w.indptr.numpy().astype(np.int64)
+    iso = torch.from_numpy(np.nonzero((ip[1:] - ip[:-1]) == 0)[0][:5].astype(np.int32))
+    assert iso.numel() > 0
+    # isolated targets: every neighbourhood is the vertex itself, alpha = 1
+    _check(_run(w, [2, 3], dev, seed=3, it=0, batch_targets=iso), 2)
+    # all targets owned by one split
+    pm = w.pmap.numpy()
+    own = torch.from_numpy(np.nonzero(pm == 2)[0][:16].astype(np.int32))
+    _check(_run(w, [2, 3], dev, seed=3, it=0, batch_targets=own), 2)
+
+
+def test_gat_rejects_bad_arguments():
+    from paper_2303_13775_amd import Context, GatParams, GsplitError
+    dev = _dev()
+    w = workloads.tiny()
+    heads = [2] * (w.n_layers - 1) + [1]
+    wt, a_s, a_d, b = workloads.gat_weights(w.dims, heads, seed=w.seed)
+    params = GatParams(w.dims, heads, [t.to(dev) for t in wt], [t.to(dev) for t in a_s], [t.to(dev) for t in a_d],
+                       [t.to(dev) for t in b])
+    tg = w.targets(0)
+    logits = torch.empty((tg.numel(), w.dims[-1]), device=dev)
+    # a context without the bottom-layer reverse index
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts, w.batch)
+    ctx.gsplit_sample_split(tg.to(dev), 1, 0)
+    x0 = torch.zeros((ctx.gsplit_max_rows(0), w.dims[0]), device=dev)
+    with pytest.raises(GsplitError):
+        ctx.gsplit_gat_fwd(params, x0, logits)
+    ctx.close()
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts, w.batch, gat_index=True)
+    x0 = torch.zeros((ctx.gsplit_max_rows(0), w.dims[0]), device=dev)
+    with pytest.raises(GsplitError):          # no batch yet
+        ctx.gsplit_gat_fwd(params, x0, logits)
+    ctx.gsplit_sample_split(tg.to(dev), 1, 0)
+    gw = [torch.empty_like(t, device=dev) for t in wt]
+    ga = [torch.empty_like(t, device=dev) for t in a_s]
+    gd = [torch.empty_like(t, device=dev) for t in a_d]
+    gb = [torch.empty_like(t, device=dev) for t in b]
+    with pytest.raises(GsplitError):          # backward before forward
+        ctx.gsplit_gat_bwd(params, x0, logits, gw, ga, gd, gb)
+    ctx.gsplit_gat_fwd(params, x0, logits)
+    ctx.gsplit_sample_split(w.targets(1).to(dev), 1, 1)
+    with pytest.raises(GsplitError):          # the forward pass belongs to another batch
+        ctx.gsplit_gat_bwd(params, x0, logits, gw, ga, gd, gb)
+    torch.cuda.synchronize()
+    ctx.close()

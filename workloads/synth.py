@@ -258,6 +258,25 @@ def sage_weights(dims: Sequence[int], *, seed: int, device="cpu"):
     return w_self, w_neigh, bias
 
 
+def gat_weights(dims: Sequence[int], heads: Sequence[int], *, seed: int, device="cpu"):
+    """Glorot-uniform W[l] of shape [D_l, heads_l * F_l] (F_l = dims[l+1] / heads_l on hidden layers,
+    dims[L] on the last, whose heads are averaged), attention vectors a_src[l], a_dst[l] of
+    heads_l * F_l entries, and a small non-zero bias of dims[l+1] entries."""
+    g = _gen(device, seed + _OFF_WEIGHT + 7)
+    L = len(dims) - 1
+    w, a_src, a_dst, bias = [], [], [], []
+    for l in range(L):
+        width = heads[l] * dims[l + 1] if l == L - 1 else dims[l + 1]
+        feat = width // heads[l]
+        lim = math.sqrt(6.0 / (dims[l] + width))
+        w.append(((torch.rand((dims[l], width), generator=g, device=device) * 2 - 1) * lim).contiguous())
+        lim_a = math.sqrt(6.0 / (feat + 1))
+        a_src.append(((torch.rand((width,), generator=g, device=device) * 2 - 1) * lim_a).contiguous())
+        a_dst.append(((torch.rand((width,), generator=g, device=device) * 2 - 1) * lim_a).contiguous())
+        bias.append(((torch.rand((dims[l + 1],), generator=g, device=device) * 2 - 1) * 0.1).contiguous())
+    return w, a_src, a_dst, bias
+
+
 def draw_targets(n_vertices: int, batch: int, *, seed: int, it: int, device="cpu") -> torch.Tensor:
     """`batch` distinct vertex ids, uniformly, fresh for every iteration number `it`."""
     g = _gen(device, seed + _OFF_TARGET + 7919 * (it + 1))
