@@ -3,7 +3,8 @@
 
 One step = one whole iteration over a fresh synthetic mini-batch, all inputs resident in HBM:
 gsplit_sample_split -> gsplit_gather_features -> gsplit_sage_fwd -> gsplit_softmax_xent (loss
-gradient of the logits) -> gsplit_sage_bwd.  Prints ONE JSON line.
+gradient of the logits) -> gsplit_sage_bwd.  Prints ONE JSON line.  `--model gat` runs the paper's
+second model (gsplit_gat_fwd / gsplit_gat_bwd) through the same steps.
 
 The workload is the "medium" configuration (2.4M-vertex / ~124M-edge R-MAT graph, 100-d fp32
 features, 47 classes, range partition map, 4 logical splits, batch 1024, fanouts [15,10,5],
@@ -35,6 +36,8 @@ def parse():
     ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
                     help="storage/compute type of the GraphSAGE layers (default f32; sweep: bf16)")
     ap.add_argument("--splits", type=int, default=4, help="number of logical splits")
+    ap.add_argument("--model", default="sage", choices=["sage", "gat"])
+    ap.add_argument("--heads", type=int, default=4, help="GAT: attention heads of the hidden layers (the last has one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=60)
     ap.add_argument("--no-pipeline", action="store_true",
@@ -52,22 +55,42 @@ def parse():
 class Runner:
     """Holds the device-resident inputs, the context and the preallocated outputs of a step."""
 
-    def __init__(self, w, dev):
+    def __init__(self, w, dev, model="sage", heads=4):
         import torch
-        from paper_2303_13775_amd import Context, SageParams
+        import workloads
+        from paper_2303_13775_amd import Context, SageParams, GatParams
         self.torch = torch
-        self.w, self.dev = w, dev
+        self.w, self.dev, self.model = w, dev, model
         from paper_2303_13775_amd import GSPLIT_BF16, GSPLIT_F32
-        self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
-        self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias,
-                                 dtype=GSPLIT_BF16 if w.feat.dtype == torch.bfloat16 else GSPLIT_F32)
+        self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch, gat_index=model == "gat")
+        if model == "gat":
+            self.heads = [heads] * (w.n_layers - 1) + [1]
+            self.gat_w = workloads.gat_weights(w.dims, self.heads, seed=w.seed, device=dev)
+            self.params = GatParams(w.dims, self.heads, *self.gat_w)
+            self.grads = [[torch.empty_like(t) for t in lst] for lst in self.gat_w]
+        else:
+            self.params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias,
+                                     dtype=GSPLIT_BF16 if w.feat.dtype == torch.bfloat16 else GSPLIT_F32)
+            self.grads = [[torch.empty_like(t) for t in lst] for lst in (w.w_self, w.w_neigh, w.bias)]
         self.x0 = torch.empty((self.ctx.gsplit_max_rows(0), w.dims[0]), dtype=w.feat.dtype, device=dev)
         self.logits = torch.empty((w.batch, w.dims[-1]), device=dev)
         self.glogits = torch.empty_like(self.logits)
-        self.gws = [torch.empty_like(t) for t in w.w_self]
-        self.gwn = [torch.empty_like(t) for t in w.w_neigh]
-        self.gb = [torch.empty_like(t) for t in w.bias]
         self.seed = 0xC0FFEE
+
+    def forward(self):
+        if self.model == "gat":
+            self.ctx.gsplit_gat_fwd(self.params, self.x0, self.logits)
+        else:
+            self.ctx.gsplit_sage_fwd(self.params, self.x0, self.logits)
+
+    def loss(self):
+        self.ctx.gsplit_softmax_xent(self.logits, self.w.labels, self.glogits)
+
+    def backward(self):
+        if self.model == "gat":
+            self.ctx.gsplit_gat_bwd(self.params, self.x0, self.glogits, *self.grads)
+        else:
+            self.ctx.gsplit_sage_bwd(self.params, self.glogits, *self.grads)
 
     def step(self, targets, it, events=None):
         c = self.ctx
@@ -77,11 +100,11 @@ class Runner:
         rec(1)
         c.gsplit_gather_features(self.w.feat, self.x0)
         rec(2)
-        c.gsplit_sage_fwd(self.params, self.x0, self.logits)
+        self.forward()
         rec(3)
-        c.gsplit_softmax_xent(self.logits, self.w.labels, self.glogits)
+        self.loss()
         rec(4)
-        c.gsplit_sage_bwd(self.params, self.glogits, self.gws, self.gwn, self.gb)
+        self.backward()
         rec(5)
 
 
@@ -92,11 +115,11 @@ class Pipelined:
     stay strictly ordered, as synchronous training requires).  Every step still does all of its
     work; nothing is cached or skipped.  Events order the hand-over of a slot in both directions."""
 
-    def __init__(self, w, dev, n_ahead=2):
+    def __init__(self, w, dev, n_ahead=2, model="sage", heads=4):
         import torch
         self.torch = torch
         self.n = n_ahead + 1
-        self.slots = [Runner(w, dev) for _ in range(self.n)]
+        self.slots = [Runner(w, dev, model, heads) for _ in range(self.n)]
         self.s_sample = [torch.cuda.Stream(device=dev) for _ in range(n_ahead)]
         self.s_train = torch.cuda.Stream(device=dev)
         self.ready = [torch.cuda.Event() for _ in range(self.n)]
@@ -146,9 +169,9 @@ class Pipelined:
                 r = self.slots[k]
                 with torch.cuda.stream(self.s_train):
                     self.s_train.wait_event(self.ready[k])
-                    r.ctx.gsplit_sage_fwd(r.params, r.x0, r.logits)
-                    r.ctx.gsplit_softmax_xent(r.logits, r.w.labels, r.glogits)
-                    r.ctx.gsplit_sage_bwd(r.params, r.glogits, r.gws, r.gwn, r.gb)
+                    r.forward()
+                    r.loss()
+                    r.backward()
                     self.free[k].record(self.s_train)
                 freed.put(None)
         finally:
@@ -180,6 +203,26 @@ def cpu_baseline(w_host, iters):
     return {"value": iters / dt, "unit": "mini-batches/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{iters} whole iterations of the same workload (C steps single-threaded, "
                       f"numpy float64 matmuls on {threads} BLAS threads), {dt:.1f} s"}
+
+
+def cpu_baseline_gat(w_host, iters):
+    """The GAT oracle as it stands (numpy float64, a Python loop over destinations), whole iterations."""
+    from oracle import reference as R
+    from oracle import gat as G
+    ip, ix, pm = w_host["indptr"], w_host["indices"], w_host["pmap"]
+    params = G.GatParams(w_host["heads"], *w_host["gat"])
+    t0 = time.perf_counter()
+    for it in range(iters):
+        tg = w_host["targets"][it]
+        b = R.sp_sample(ip, ix, pm, w_host["S"], w_host["fanouts"], tg, 0xC0FFEE, it)
+        x0 = R.gather_rows(w_host["feat"], b.local_cat(0))
+        f = G.gat_forward(b, x0, params)
+        _, g = R.softmax_xent(f.logits, w_host["labels"][tg[b.target_perm]])
+        G.gat_backward(b, f, params, g)
+    dt = time.perf_counter() - t0
+    return {"value": iters / dt, "unit": "mini-batches/s", "cores": 1, "kind": "oracle",
+            "sample": f"{iters} whole iteration(s) of the same workload (C sampling steps, numpy float64 GAT with a "
+                      f"Python loop over destinations), {dt:.1f} s"}
 
 
 def presample_bench(a, w, dev, t_gen):
@@ -284,7 +327,10 @@ def main():
     t_gen = time.time() - t0
     if a.presample:
         return presample_bench(a, w, dev, t_gen)
-    r = Runner(w, dev)
+    if a.model == "gat" and dtype != "f32":
+        print("bench.py: --model gat runs in f32", file=sys.stderr)
+        sys.exit(2)
+    r = Runner(w, dev, a.model, a.heads)
     n_total = a.warmup + a.steps
     targets = [w.targets(i) for i in range(n_total)]
     torch.cuda.synchronize()
@@ -300,7 +346,7 @@ def main():
     dt_serial = time.perf_counter() - t0
     dt = dt_serial
     if not a.no_pipeline:
-        pipe = Pipelined(w, dev, a.ahead)
+        pipe = Pipelined(w, dev, a.ahead, a.model, a.heads)
         pipe.run(targets, 0, a.warmup)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -315,7 +361,7 @@ def main():
     for i in range(n_st):
         r.step(targets[a.warmup + i], a.warmup + i, ev[i])
     torch.cuda.synchronize()
-    names = ["sample_split", "gather", "sage_fwd", "loss_grad", "sage_bwd"]
+    names = ["sample_split", "gather", f"{a.model}_fwd", "loss_grad", f"{a.model}_bwd"]
     stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / max(n_st, 1)
                 for k, nm in enumerate(names)}
 
@@ -340,6 +386,20 @@ def main():
         mixed = [sum(x) for x in n_mixed]
         shape = (rows, edges, mixed, bucket)
         add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
+        for l in range(L if a.model == "gat" else 0):
+            # the transform and both backward products run over the rows of level l; the row kernels
+            # move one transformed (or gradient) row per entry (edge or self) and its coefficients
+            D, nd, n_lo = w.dims[l], rows[l + 1], rows[l]
+            K = r.heads[l]
+            HF = K * w.dims[l + 1] if l == L - 1 else w.dims[l + 1]
+            ent = edges[l] + nd
+            add(f"gat_transform.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+            add(f"gat_grad_w.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+            if l > 0:
+                add(f"gat_grad_in.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+            add(f"gat_aggregate.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * 4 * w.dims[l + 1])
+            add(f"gat_bwd_dst.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * (8 * w.dims[l + 1] + 4 * HF + 4 * K))
+            add(f"gat_bwd_src.l{l}", "bytes", ent * (8 + 4 * HF + 8 * K) + n_lo * (8 + 4 * (HF + 2 * K)))
         for l in range(L):
             D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
             add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
@@ -368,6 +428,8 @@ def main():
         (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration stated there), or None."""
         path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
                             f"{a.workload}_bench_hbm_traffic.txt")
+        if a.model == "gat":
+            path = path.replace("_bench_", "_gat_bench_")
         if dtype != "f32" or not os.path.exists(path):
             return None
         for line in open(path):
@@ -398,11 +460,12 @@ def main():
     rows, edges, mixed, bucket = shape
     gather = roofline_of("gather_rows")
     out = {
-        "metric": "mini-batches/sec (sample+split+gather+SAGE fwd/bwd) at 1 GPU",
+        "metric": f"mini-batches/sec (sample+split+gather+{'GAT' if a.model == 'gat' else 'SAGE'} fwd/bwd) at 1 GPU",
         "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": dict(w.describe(), fanout_order="fanouts[l] expands layer l+1 into layer l",
+        "config": dict(w.describe(), model=a.model, **({"heads": r.heads} if a.model == "gat" else {}),
+                       fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1),
                        schedule=("serial, one stream" if a.no_pipeline else
                                  f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the "
@@ -427,7 +490,15 @@ def main():
         out["calibration_copy_bytes"] = {"read": src.numel() * 4, "written": dst.numel() * 4}
         del src, dst
 
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and a.model == "gat":
+        n_cpu = max(1, min(a.cpu_iters, 2 if a.workload == "medium" else 1))
+        host = {"indptr": w.indptr.cpu().numpy(), "indices": w.indices.cpu().numpy(),
+                "pmap": w.pmap.cpu().numpy(), "feat": w.feat.cpu().numpy(),
+                "labels": w.labels.cpu().numpy(), "S": w.n_splits, "fanouts": w.fanouts,
+                "heads": r.heads, "gat": [[t.cpu().numpy() for t in lst] for lst in r.gat_w],
+                "targets": [targets[a.warmup + i].cpu().numpy() for i in range(n_cpu)]}
+        out["cpu_baseline"] = cpu_baseline_gat(host, n_cpu)
+    elif not a.no_cpu_baseline:
         host = {"indptr": w.indptr.cpu().numpy(), "indices": w.indices.cpu().numpy(),
                 "pmap": w.pmap.cpu().numpy(), "feat": w.feat.cpu().numpy(),
                 "labels": w.labels.cpu().numpy(), "S": w.n_splits, "fanouts": w.fanouts,

@@ -413,7 +413,7 @@ __global__ __launch_bounds__(256) void k_gat_reduce(GatReduce g, const GsLevelMe
     }
 }
 
-// parameter gradients from G and the bias slabs, all layers in one launch
+// d W = G_z + G_src (x) a_src + G_dst (x) a_dst, all layers in one launch
 struct GatFinish {
     const float *gmat[GS_MAXL]; const float *w[GS_MAXL]; const float *a_src[GS_MAXL]; const float *a_dst[GS_MAXL];
     const float *bias_part[GS_MAXL];
@@ -430,21 +430,47 @@ __global__ __launch_bounds__(256) void k_gat_finish(GatFinish g) {
         const float *row = G + (int64_t)dd * ZW;
         g.gw[l][x] = row[c] + row[HF + k] * g.a_src[l][c] + row[HF + K + k] * g.a_dst[l][c];
     }
-    for (int64_t c = tid; c < HF; c += nthr) {
-        const int k = (int)c / F;
-        float s = 0.f, t = 0.f;
-        for (int dd = 0; dd < D; ++dd) {
+}
+
+// d a_src = W^T G_src, d a_dst = W^T G_dst and the bias gradient (sum of the workgroup slabs of
+// k_gat_bwd_dst in slab order): 64 columns per workgroup, the long sums dealt to 16 waves and
+// added in wave order
+__global__ __launch_bounds__(1024) void k_gat_finish_cols(GatFinish g) {
+    __shared__ float red[3][16][64];
+    const int l = blockIdx.y;
+    const int D = g.D[l], K = g.K[l], F = g.F[l], ZW = g.ZW[l], HF = K * F, PW = g.PW[l], slabs = g.slabs[l];
+    const float *G = g.gmat[l];
+    const int x = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + x;
+    if (blockIdx.x * 64 >= HF) return;
+    float s = 0.f, t = 0.f, b = 0.f;
+    if (c < HF) {
+        const int k = c / F;
+        for (int dd = ty; dd < D; dd += 16) {
             const float wv = g.w[l][(int64_t)dd * HF + c];
             s += wv * G[(int64_t)dd * ZW + HF + k];
             t += wv * G[(int64_t)dd * ZW + HF + K + k];
         }
-        g.ga_src[l][c] = s;
-        g.ga_dst[l][c] = t;
     }
-    for (int64_t c = tid; c < PW; c += nthr) {
-        float s = 0.f;
-        for (int z = 0; z < g.slabs[l]; ++z) s += g.bias_part[l][(int64_t)z * PW + c];
-        g.gb[l][c] = s;
+    if (c < PW) {
+        const float *p = g.bias_part[l] + c;
+        int z = ty;
+        for (; z + 7 * 16 < slabs; z += 8 * 16) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = p[(int64_t)(z + 16 * j) * PW];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b += v[j];
+        }
+        for (; z < slabs; z += 16) b += p[(int64_t)z * PW];
+    }
+    red[0][ty][x] = s; red[1][ty][x] = t; red[2][ty][x] = b;
+    __syncthreads();
+    if (ty == 0) {
+        s = t = b = 0.f;
+        for (int j = 0; j < 16; ++j) { s += red[0][j][x]; t += red[1][j][x]; b += red[2][j][x]; }
+        if (c < HF) { g.ga_src[l][c] = s; g.ga_dst[l][c] = t; }
+        if (c < PW) g.gb[l][c] = b;
     }
 }
 
@@ -713,9 +739,15 @@ extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
             gf.slabs[l] = gb.bias_slabs[l];
             wmax = std::max<int64_t>(wmax, (int64_t)p->dims[l] * d.HF);
         }
-        GsTimeScope ts(ctx, "gat_finish", -1, st);
-        hipLaunchKernelGGL(k_gat_finish, dim3((unsigned)std::min<int64_t>(256, gs_ceil_div(wmax, 256)), L), dim3(256), 0, st,
-                           gf);
+        int hf_max = 1;
+        for (int l = 0; l < L; ++l) hf_max = std::max(hf_max, gf.K[l] * gf.F[l]);
+        {
+            GsTimeScope ts(ctx, "gat_finish_w", -1, st);
+            hipLaunchKernelGGL(k_gat_finish, dim3((unsigned)std::min<int64_t>(256, gs_ceil_div(wmax, 256)), L), dim3(256), 0,
+                               st, gf);
+        }
+        GsTimeScope ts(ctx, "gat_finish_cols", -1, st);
+        hipLaunchKernelGGL(k_gat_finish_cols, dim3((unsigned)gs_ceil_div(hf_max, 64), L), dim3(1024), 0, st, gf);
     }
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;
