@@ -12,6 +12,14 @@
 //     G     = h^T dz_ext                (D x (K F + 2 K), split-K on the matrix cores)
 //     d W   = G_z + G_src (x) a_src + G_dst (x) a_dst,   d a_src = W^T G_src,   d a_dst = W^T G_dst
 // so the per-row kernels only form dz_ext and every reduction over rows is a matrix product.
+//
+// The bottom layer needs no input gradient and has several times more source rows than
+// destinations, so (when its shapes allow) it runs in the other order: the attention-weighted sum
+// is taken over the raw input rows per head, P_i^k = sum_j alpha_ij^k h_j, and the transform is a
+// per-head product over the destinations only, out_i^k = P_i^k W^k.  Scores come from
+// h (W a_src), h (W a_dst) (2 K columns), and the backward pass needs neither the scatter side of
+// the shuffle index nor a gradient row per source:  dP^k = dagg^k W^kT,  d alpha_ij = h_j . dP_i^k,
+// d W^k = P^kT dagg^k, and the columns G_src, G_dst of G are sums of d e_ij h_j over entries.
 #include <algorithm>
 
 #include "gsplit_internal.h"
@@ -30,12 +38,20 @@ struct GatDims {
     int64_t self_base;      // slot of destination i's self entry = self_base + i (edge slots come first)
 };
 
+// plain store; with act (the ELU outputs h' at the same positions) the value is first multiplied by
+// ELU'(.) = 1 for h' > 0, else h' + 1
 struct EpiStore {
-    float *out; int ld; int rows; int cols;
+    float *out; int ld; int rows; int cols; const float *act;
     __device__ __forceinline__ float col(int) const { return 0.f; }
     __device__ __forceinline__ float row(int) const { return 0.f; }
     __device__ __forceinline__ void store(int m, int n, float v, float, float) const {
-        if (m < rows && n < cols) out[(int64_t)m * ld + n] = v;
+        if (m < rows && n < cols) {
+            if (act) {
+                const float hv = act[(int64_t)m * ld + n];
+                v *= hv > 0.f ? 1.f : hv + 1.f;
+            }
+            out[(int64_t)m * ld + n] = v;
+        }
     }
 };
 
@@ -80,8 +96,25 @@ __global__ __launch_bounds__(256) void k_gat_prep_weights(GatPrep p) {
     }
 }
 
+// value of another lane through the data-parallel-primitive path of the vector ALU (no LDS
+// traffic): CTRL 0xB1 / 0x4E = lane ^ 1 / lane ^ 2 inside a quad, 0x141 / 0x140 = mirror inside
+// 8 / 16 lanes
+// 0x142 / 0x143 = lane 15 of every row of 16 lanes to the next row / lane 31 to the upper two rows;
+// rows outside ROW_MASK receive zero
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_get(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
+}
+// sum over aligned groups of lph lanes (a power of two), the same bits in every lane of a group:
+// after the quad steps every lane of a quad holds the quad's sum, a mirror then pairs each lane
+// with one of the other half; only groups of 32 and 64 lanes need the LDS crossbar
 __device__ __forceinline__ float head_sum(float v, int lph) {
-    for (int o = lph >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (lph >= 2) v += dpp_get<0xB1>(v);
+    if (lph >= 4) v += dpp_get<0x4E>(v);
+    if (lph >= 8) v += dpp_get<0x141>(v);
+    if (lph >= 16) v += dpp_get<0x140>(v);
+    if (lph >= 32) v += __shfl_xor(v, 16);
+    if (lph >= 64) v += __shfl_xor(v, 32);
     return v;
 }
 __device__ __forceinline__ float head_max(float v, int lph) {
@@ -387,12 +420,499 @@ __global__ __launch_bounds__(256) void k_gat_bwd_src(GatBwdSrcArgs g, GatDims d,
     }
 }
 
+// ---- bottom layer, aggregate-then-transform ---------------------------------------------------
+// window of a row-major matrix: rows x cols at row stride ld (same accessor interface as MatRows)
+struct MatLd {
+    const float *p; int rows; int cols; int ld;
+    template <int VW>
+    __device__ __forceinline__ const float *at(int o, int i, bool &in) const {
+        in = o < rows && i < cols;
+        const int oc = min(o, rows - 1), ic = min(i, cols - VW);
+        return p + (int64_t)oc * ld + ic;
+    }
+    __device__ __forceinline__ int tok(int i) const { return min(i, cols - 4); }
+    __device__ __forceinline__ const float *km(int k, int t) const { return p + (int64_t)k * ld + t; }
+};
+using TileTall = Tile<128, 64, 4, 2, 1, true>;
+
+struct EpiHeadElu {      // hidden[i, off + n] = ELU(v + bias[off + n])
+    float *out; const float *bias; int ld; int rows; int cols; int off;
+    __device__ __forceinline__ float col(int n) const { return n < cols ? bias[off + n] : 0.f; }
+    __device__ __forceinline__ float row(int) const { return 0.f; }
+    __device__ __forceinline__ void store(int m, int n, float v, float, float b) const {
+        if (m < rows && n < cols) {
+            const float z = v + b;
+            out[(int64_t)m * ld + off + n] = z > 0.f ? z : expm1f(z);
+        }
+    }
+};
+struct EpiHeadStore {
+    float *out; int ld; int rows; int cols; int off;
+    __device__ __forceinline__ float col(int) const { return 0.f; }
+    __device__ __forceinline__ float row(int) const { return 0.f; }
+    __device__ __forceinline__ void store(int m, int n, float v, float, float) const {
+        if (m < rows && n < cols) out[(int64_t)m * ld + off + n] = v;
+    }
+};
+
+// one product per head over the destination rows: head k takes the window of a at column
+// k * a_step, of b at column k * b_step, and writes at column k * o_step
+template <class T, bool B_KC, class EF>
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_gat0_head_gemm(MatLd a, MatLd b, EF epi, int heads, int a_step, int b_step, int o_step,
+                      const GsLevelMeta *__restrict__ meta_up, int S) {
+    const int n1 = meta_up->front_off[S];
+    const int n_out = B_KC ? b.rows : b.cols;
+    const int tiles_m = (n1 + T::BM - 1) / T::BM, tiles_n = (n_out + T::BN - 1) / T::BN;
+    const int per_head = ((tiles_m + 7) & ~7) * tiles_n;
+    a.rows = n1; epi.rows = n1;
+    for (int gid = blockIdx.x; gid < per_head * heads; gid += gridDim.x) {
+        const int head = gid / per_head;
+        int m0, n0;
+        if (!next_tile<T>(gid - head * per_head, tiles_m, tiles_n, m0, n0)) continue;
+        MatLd ah = a, bh = b;
+        EF eh = epi;
+        ah.p += head * a_step; bh.p += head * b_step; eh.off = head * o_step;
+        gemm_tile<T, true, B_KC, 4, 4>(m0, n0, n1, n_out, 0, ah.cols, ah, bh, eh);
+    }
+}
+
+// partial d W^k = P^kT dagg^k over one chunk of destination rows (split-K), slab
+// [chunk][head][(D + 1) x F]; the last row of a slab holds the column sums of dagg^k (bias gradient)
+template <class T>
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_gat0_grad_w(MatLd a, MatLd dz, EpiGradW epi, int nchunk, int heads, int tiles_m, int tiles_n,
+                   const GsLevelMeta *__restrict__ meta_up, int S) {
+    const int n1 = meta_up->front_off[S];
+    const int kchunk = grad_w_chunk_rows(n1, nchunk, GRAD_W_ROWS_MIN);
+    const int tiles = tiles_m * tiles_n;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int tile = j % tiles, head = (j / tiles) % heads, chunk = (j / (tiles * heads)) * 8 + xcd;
+    const int k_begin = chunk * kchunk;
+    if (k_begin >= n1) return;
+    a.rows = n1; dz.rows = n1;
+    a.p += head * a.cols; dz.p += head * dz.cols;
+    const int k_end = min(n1, k_begin + kchunk);
+    epi.part += ((int64_t)chunk * heads + head) * epi.rows * epi.N;
+    gemm_tile<T, false, false, 4, 4, MatLd, MatLd, EpiGradW, false, true>(
+        (tile % tiles_m) * T::BM, (tile / tiles_m) * T::BN, a.cols, dz.cols, k_begin, k_end, a, dz, epi);
+}
+
+// sum over the wave without the LDS crossbar; the result is valid in lanes 48..63 only
+__device__ __forceinline__ float wave_sum_top(float v) {
+    v = head_sum(v, 16);                    // every lane: the sum of its row of 16
+    v += dpp_get<0x142, 0xA>(v);            // rows 1 and 3 add the row below them
+    v += dpp_get<0x143, 0xC>(v);            // rows 2 and 3 add lane 31 (rows 0 + 1)
+    return v;
+}
+// lanes with the same lane % kp form a class
+__device__ __forceinline__ float class_sum(float v, int kp) {
+    for (int o = kp; o < 64; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float class_max(float v, int kp) {
+    for (int o = kp; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// score terms of every input row: s0[u, c] = h_u . wa[:, c], c < 2 K (wa = the last columns of
+// W_ext: W a_src per head, then W a_dst per head).  Eight lanes per row, 16 bytes per lane and
+// load, four loads in flight.
+template <int KP>
+__global__ __launch_bounds__(256) void k_gat0_scores(const float *__restrict__ h, int D, const float *__restrict__ wext,
+                                                     int ZW, int HF, int K, float *__restrict__ s0,
+                                                     const GsLevelMeta *__restrict__ meta_lo, int S) {
+    extern __shared__ float s_wa[];        // [2 K][D]
+    for (int x = threadIdx.x; x < 2 * K * D; x += 256) {
+        const int dd = x / (2 * K), c = x - dd * 2 * K;
+        s_wa[c * D + dd] = wext[(int64_t)dd * ZW + HF + c];
+    }
+    __syncthreads();
+    const int n0 = meta_lo->front_off[S];
+    const int sub = threadIdx.x & 7;
+    const int nv4 = D >> 2;
+    for (int u = blockIdx.x * 32 + (threadIdx.x >> 3); u < ((n0 + 31) & ~31); u += gridDim.x * 32) {
+        float acc[2 * KP];
+#pragma unroll
+        for (int c = 0; c < 2 * KP; ++c) acc[c] = 0.f;
+        if (u < n0)
+            for (int v0 = sub; v0 < nv4; v0 += 32) {
+                float4 x[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int v = v0 + 8 * t;
+                    x[t] = v < nv4 ? *reinterpret_cast<const float4 *>(h + (int64_t)u * D + 4 * v) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int v = min(v0 + 8 * t, nv4 - 1);      // a vector past the row is zero: any weights do
+#pragma unroll
+                    for (int c = 0; c < 2 * KP; ++c)
+                        if (c < 2 * K) {
+                            const float4 w = *reinterpret_cast<const float4 *>(s_wa + c * D + 4 * v);
+                            acc[c] += x[t].x * w.x + x[t].y * w.y + x[t].z * w.z + x[t].w * w.w;
+                        }
+                }
+            }
+#pragma unroll
+        for (int c = 0; c < 2 * KP; ++c) acc[c] = head_sum(acc[c], 8);
+        if (u < n0) {
+#pragma unroll
+            for (int c = 0; c < 2 * KP; ++c)
+                if ((c & 7) == sub && c < 2 * K) s0[(int64_t)u * 2 * K + c] = acc[c];
+        }
+    }
+}
+
+struct Gat0Args {
+    const float *h; const float *s0; const int32_t *blk_indptr; const int32_t *edge_row; const int32_t *self_row;
+    float *alpha; float *pagg; const float *dp; float *q_part;
+    int D, K, fan; int64_t self_base;
+    int ch;     // input rows a wave of k_gat0_bwd stages in LDS at a time
+};
+
+// the lane's NV float4 of one input row (lane + 64 t), zeros past the row
+template <int NV>
+__device__ __forceinline__ void load_row4(const float *__restrict__ row, int lane, int nv4, float (&v)[NV * 4]) {
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+        const int c = lane + 64 * t;
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < nv4) x = *reinterpret_cast<const float4 *>(row + 4 * c);
+        v[t * 4] = x.x; v[t * 4 + 1] = x.y; v[t * 4 + 2] = x.z; v[t * 4 + 3] = x.w;
+    }
+}
+
+// edge softmax of the bottom layer and P_i^k = sum_j alpha_ij^k h_j, one wave per destination:
+// entry j and head k sit on lane (j KP + k) mod 64 for the softmax, then the lanes run over the
+// input features and every lane keeps one accumulator per head
+template <int NV, int KP>
+__global__ __launch_bounds__(256) void k_gat0_aggregate(Gat0Args g, const GsLevelMeta *__restrict__ meta_up, int S) {
+    extern __shared__ float smem[];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int per_wave = (1 + g.fan) * (1 + KP);
+    int *s_row = reinterpret_cast<int *>(smem + wave * per_wave);
+    float *s_val = smem + wave * per_wave + (1 + g.fan);
+    const int n1 = meta_up->front_off[S];
+    const int D = g.D, K = g.K, nv4 = D >> 2;
+    const int k = lane % KP;
+    const bool ok = k < K;
+    for (int i = blockIdx.x * 4 + wave; i < n1; i += gridDim.x * 4) {
+        const int e0 = g.blk_indptr[i], e1 = g.blk_indptr[i + 1];
+        const int n_ent = 1 + e1 - e0;
+        const int self = g.self_row[i];
+        const float er = ok ? g.s0[(int64_t)self * 2 * K + K + k] : 0.f;
+        float m = -3.4e38f;
+        for (int idx = lane; idx < n_ent * KP; idx += 64) {
+            const int j = idx / KP;
+            const int row = j == 0 ? self : g.edge_row[e0 + j - 1];
+            if (k == 0) s_row[j] = row;
+            if (ok) {
+                const float raw = er + g.s0[(int64_t)row * 2 * K + k];
+                const float e = raw > 0.f ? raw : NEG_SLOPE * raw;
+                s_val[idx] = e;
+                m = fmaxf(m, e);
+            }
+        }
+        m = class_max(m, KP);
+        float s = 0.f;
+        if (ok)
+            for (int idx = lane; idx < n_ent * KP; idx += 64) {
+                const float p = expf(s_val[idx] - m);
+                s_val[idx] = p;
+                s += p;
+            }
+        s = class_sum(s, KP);
+        if (ok)
+            for (int idx = lane; idx < n_ent * KP; idx += 64) {
+                const int j = idx / KP;
+                const float a = s_val[idx] / s;
+                s_val[idx] = a;
+                const int64_t slot = j == 0 ? g.self_base + i : (int64_t)(e0 + j - 1);
+                g.alpha[slot * K + k] = a;
+            }
+        __builtin_amdgcn_wave_barrier();
+        float acc[KP][NV * 4];
+#pragma unroll
+        for (int kk = 0; kk < KP; ++kk)
+#pragma unroll
+            for (int c = 0; c < NV * 4; ++c) acc[kk][c] = 0.f;
+        for (int j = 0; j < n_ent; j += 4) {
+            float hv[4][NV * 4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = j + q < n_ent ? s_row[j + q] : self;
+                load_row4<NV>(g.h + (int64_t)row * D, lane, nv4, hv[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (j + q < n_ent) {
+#pragma unroll
+                    for (int kk = 0; kk < KP; ++kk) {
+                        const float a = kk < K ? s_val[(j + q) * KP + kk] : 0.f;
+#pragma unroll
+                        for (int c = 0; c < NV * 4; ++c) acc[kk][c] += a * hv[q][c];
+                    }
+                }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int kk = 0; kk < KP; ++kk)
+            if (kk < K) {
+#pragma unroll
+                for (int t = 0; t < NV; ++t) {
+                    const int c = lane + 64 * t;
+                    if (c < nv4)
+                        *reinterpret_cast<float4 *>(g.pagg + ((int64_t)i * K + kk) * D + 4 * c) =
+                            make_float4(acc[kk][t * 4], acc[kk][t * 4 + 1], acc[kk][t * 4 + 2], acc[kk][t * 4 + 3]);
+                }
+            }
+    }
+}
+
+// Backward of the bottom layer over the destinations, one wave each: d alpha_ij^k = h_j . dP_i^k,
+// the softmax and LeakyReLU derivatives d e_ij^k, and the wave's running sums
+//   q_src^k = sum d e_ij^k h_j   (over all entries),   q_dst^k = sum_i (sum_j d e_ij^k) h_i
+// which are the columns G_src, G_dst of G once added over all waves (one slab per wave).
+template <int NV, int KP>
+__global__ __launch_bounds__(256) void k_gat0_bwd(Gat0Args g, const GsLevelMeta *__restrict__ meta_up, int S) {
+    extern __shared__ float smem[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int D = g.D, K = g.K, nv4 = D >> 2, CH = g.ch;
+    // per wave: entry rows | one value per entry and head | per-head sums | CH staged input rows
+    const int w_row = (1 + g.fan + 3) & ~3, w_val = ((1 + g.fan) * KP + 3) & ~3, w_ds = (KP + 3) & ~3;
+    float *base = smem + wave * (w_row + w_val + w_ds + CH * D);
+    int *s_row = reinterpret_cast<int *>(base);
+    float *s_val = base + w_row;
+    float *s_ds = s_val + w_val;
+    float *s_h = s_ds + w_ds;
+    const int n1 = meta_up->front_off[S];
+    const int k = lane % KP;
+    const bool ok = k < K;
+    // Input rows of entries [c0, c0 + nc) straight from global memory into LDS (lane L of a 16-byte
+    // direct load lands at base + 16 L): every row of the chunk is in flight at once and costs no
+    // registers
+    auto stage = [&](int c0, int nc) {
+        for (int q = 0; q < nc; ++q) {
+            const float *src = g.h + (int64_t)s_row[c0 + q] * D;
+#pragma unroll
+            for (int t = 0; t < NV; ++t) {
+                const int c = lane + 64 * t;
+                if (c < nv4)
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + 4 * c),
+                                                     (__attribute__((address_space(3))) void *)(s_h + q * D + 256 * t), 16, 0, 0);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto staged = [&](int q, float (&v)[NV * 4]) {
+#pragma unroll
+        for (int t = 0; t < NV; ++t) {
+            const int c = lane + 64 * t;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c < nv4) x = *reinterpret_cast<const float4 *>(s_h + q * D + 4 * c);
+            v[t * 4] = x.x; v[t * 4 + 1] = x.y; v[t * 4 + 2] = x.z; v[t * 4 + 3] = x.w;
+        }
+    };
+    float qs[KP][NV * 4], qd[KP][NV * 4];
+#pragma unroll
+    for (int kk = 0; kk < KP; ++kk)
+#pragma unroll
+        for (int c = 0; c < NV * 4; ++c) qs[kk][c] = qd[kk][c] = 0.f;
+    for (int i = blockIdx.x * 4 + wave; i < n1; i += gridDim.x * 4) {
+        const int e0 = g.blk_indptr[i], e1 = g.blk_indptr[i + 1];
+        const int n_ent = 1 + e1 - e0;
+        const int self = g.self_row[i];
+        for (int j = lane; j < n_ent; j += 64) s_row[j] = j == 0 ? self : g.edge_row[e0 + j - 1];
+        float dp[KP][NV * 4];
+#pragma unroll
+        for (int kk = 0; kk < KP; ++kk) {
+            if (kk < K) load_row4<NV>(g.dp + ((int64_t)i * K + kk) * D, lane, nv4, dp[kk]);
+            else {
+#pragma unroll
+                for (int c = 0; c < NV * 4; ++c) dp[kk][c] = 0.f;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int c0 = 0; c0 < n_ent; c0 += CH) {
+            const int nc = min(CH, n_ent - c0);
+            stage(c0, nc);
+            for (int q0 = 0; q0 < nc; q0 += 4) {
+                float p[4][KP];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float hv[NV * 4];
+                    staged(min(q0 + q, nc - 1), hv);
+#pragma unroll
+                    for (int kk = 0; kk < KP; ++kk) {
+                        float t = 0.f;
+#pragma unroll
+                        for (int c = 0; c < NV * 4; ++c) t += hv[c] * dp[kk][c];
+                        p[q][kk] = t;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int kk = 0; kk < KP; ++kk) p[q][kk] = wave_sum_top(p[q][kk]);
+                if (lane == 63) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (q0 + q < nc) {
+#pragma unroll
+                            for (int kk = 0; kk < KP; ++kk) s_val[(c0 + q0 + q) * KP + kk] = p[q][kk];
+                        }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();     // the next chunk overwrites the staged rows
+        }
+        const float er = ok ? g.s0[(int64_t)self * 2 * K + K + k] : 0.f;
+        float tsum = 0.f;
+        if (ok)
+            for (int idx = lane; idx < n_ent * KP; idx += 64) {
+                const int j = idx / KP;
+                const int64_t slot = j == 0 ? g.self_base + i : (int64_t)(e0 + j - 1);
+                tsum += g.alpha[slot * K + k] * s_val[idx];
+            }
+        tsum = class_sum(tsum, KP);
+        float dsum = 0.f;
+        if (ok)
+            for (int idx = lane; idx < n_ent * KP; idx += 64) {
+                const int j = idx / KP;
+                const int64_t slot = j == 0 ? g.self_base + i : (int64_t)(e0 + j - 1);
+                const float raw = er + g.s0[(int64_t)s_row[j] * 2 * K + k];
+                const float v = g.alpha[slot * K + k] * (s_val[idx] - tsum) * (raw > 0.f ? 1.f : NEG_SLOPE);
+                s_val[idx] = v;
+                dsum += v;
+            }
+        dsum = class_sum(dsum, KP);
+        if (lane < KP) s_ds[lane] = dsum;
+        __builtin_amdgcn_wave_barrier();
+        for (int c0 = 0; c0 < n_ent; c0 += CH) {
+            const int nc = min(CH, n_ent - c0);
+            if (n_ent > CH) stage(c0, nc);      // a single chunk is still staged
+            for (int q = 0; q < nc; ++q) {
+                float hv[NV * 4];
+                staged(q, hv);
+#pragma unroll
+                for (int kk = 0; kk < KP; ++kk) {
+                    const float de = kk < K ? s_val[(c0 + q) * KP + kk] : 0.f;
+#pragma unroll
+                    for (int c = 0; c < NV * 4; ++c) qs[kk][c] += de * hv[c];
+                }
+                if (c0 + q == 0) {
+#pragma unroll
+                    for (int kk = 0; kk < KP; ++kk) {
+                        const float ds = kk < K ? s_ds[kk] : 0.f;
+#pragma unroll
+                        for (int c = 0; c < NV * 4; ++c) qd[kk][c] += ds * hv[c];
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    // one slab per workgroup: the four waves' sums added in wave order
+    __shared__ float s_red[4][NV * 256];
+    float *slab = g.q_part + (int64_t)blockIdx.x * 2 * K * D;
+#pragma unroll
+    for (int kk = 0; kk < 2 * KP; ++kk) {
+        const int head = kk % KP;
+        if (head >= K) continue;
+        const float(&src)[NV * 4] = kk < KP ? qs[head] : qd[head];
+#pragma unroll
+        for (int c = 0; c < NV * 4; ++c) s_red[wave][c * 64 + lane] = src[c];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int t = 0; t < NV; ++t) {
+                const int c4 = lane + 64 * t;
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int c = (t * 4 + j) * 64 + lane;
+                    v[j] = ((s_red[0][c] + s_red[1][c]) + s_red[2][c]) + s_red[3][c];
+                }
+                if (c4 < nv4)
+                    *reinterpret_cast<float4 *>(slab + ((int64_t)(kk < KP ? 0 : K) + head) * D + 4 * c4) =
+                        make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Sum of column col0 + (tid & 15) over n_slabs slabs of `stride` floats by a workgroup of 1024: slab
+// z is read by lane group z mod 64, eight loads in flight, and the 64 partial sums are added in
+// group order.  Valid in threads 0..15.
+__device__ __forceinline__ float slab_sum_16x64(const float *__restrict__ p, int n_cols, int64_t stride, int n_slabs,
+                                                int col0, float (*red)[16]) {
+    const int x = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int c = col0 + x;
+    float s = 0.f;
+    if (c < n_cols) {
+        const float *q = p + c;
+        int z = ty;
+        for (; z + 7 * 64 < n_slabs; z += 8 * 64) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = q[(int64_t)(z + 64 * j) * stride];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += v[j];
+        }
+        for (; z < n_slabs; z += 64) s += q[(int64_t)z * stride];
+    }
+    __syncthreads();        // red may still be read from a previous call
+    red[ty][x] = s;
+    __syncthreads();
+    s = 0.f;
+    if (ty == 0)
+        for (int j = 0; j < 64; ++j) s += red[j][x];
+    return s;
+}
+
+// G of the bottom layer and its bias gradient: the z columns and the bias from the split-K slabs of
+// the per-head products, the G_src / G_dst columns from the workgroup slabs of k_gat0_bwd
+__global__ __launch_bounds__(1024) void k_gat0_reduce(const float *__restrict__ w_part, int nchunk,
+                                                      const float *__restrict__ q_part, int q_slabs, int D, int K, int F,
+                                                      int ZW, float *__restrict__ gmat, float *__restrict__ gbias,
+                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
+    __shared__ float red[64][16];
+    const int HF = K * F;
+    const int x = threadIdx.x & 15;
+    const int n1 = meta_up->front_off[S];
+    const int kchunk = grad_w_chunk_rows(n1, nchunk, GRAD_W_ROWS_MIN);
+    const int chunks = (n1 + kchunk - 1) / kchunk;
+    const int per_row = (F + 15) / 16;                      // workgroups per row of one head's slab
+    const int n_w = K * (D + 1) * per_row;
+    if ((int)blockIdx.x < n_w) {
+        const int head = blockIdx.x / ((D + 1) * per_row), r = blockIdx.x % ((D + 1) * per_row);
+        const int dd = r / per_row, f0 = (r % per_row) * 16;
+        const float s = slab_sum_16x64(w_part + ((int64_t)head * (D + 1) + dd) * F, F, (int64_t)K * (D + 1) * F, chunks, f0,
+                                       red);
+        if (threadIdx.x < 16 && f0 + x < F) {
+            if (dd < D) gmat[(int64_t)dd * ZW + head * F + f0 + x] = s;
+            else gbias[head * F + f0 + x] = s;
+        }
+        return;
+    }
+    const int e0 = ((int)blockIdx.x - n_w) * 16;             // elements of the [2 K][D] slab
+    const float s = slab_sum_16x64(q_part, 2 * K * D, (int64_t)2 * K * D, q_slabs, e0, red);
+    const int e = e0 + x;
+    if (threadIdx.x < 16 && e < 2 * K * D) {
+        const int c = e / D, dd = e - c * D;
+        gmat[(int64_t)dd * ZW + HF + c] = s;
+    }
+}
+
 // G = sum of the split-K slabs of h^T dz_ext in slab order, all layers in one launch
 struct GatReduce {
     const float *part[GS_MAXL]; float *gmat[GS_MAXL]; int D[GS_MAXL]; int ZW[GS_MAXL]; int nchunk[GS_MAXL];
 };
 __global__ __launch_bounds__(256) void k_gat_reduce(GatReduce g, const GsLevelMeta *__restrict__ meta, int S) {
     const int l = blockIdx.y;
+    if (g.nchunk[l] == 0) return;      // this layer's G comes from k_gat0_reduce
     const int n0 = meta[l].front_off[S];
     const int kchunk = grad_w_chunk_rows(n0, g.nchunk[l], GRAD_W_ROWS_MIN);
     const int chunks = (n0 + kchunk - 1) / kchunk;
@@ -432,46 +952,42 @@ __global__ __launch_bounds__(256) void k_gat_finish(GatFinish g) {
     }
 }
 
-// d a_src = W^T G_src, d a_dst = W^T G_dst and the bias gradient (sum of the workgroup slabs of
-// k_gat_bwd_dst in slab order): 64 columns per workgroup, the long sums dealt to 16 waves and
-// added in wave order
+// d a_src = W^T G_src, d a_dst = W^T G_dst and the bias gradient (sum of the bias slabs in slab
+// order): 16 columns per workgroup, the long sums dealt to 64 lane groups and added in group order
 __global__ __launch_bounds__(1024) void k_gat_finish_cols(GatFinish g) {
-    __shared__ float red[3][16][64];
+    __shared__ float red[64][16];
     const int l = blockIdx.y;
-    const int D = g.D[l], K = g.K[l], F = g.F[l], ZW = g.ZW[l], HF = K * F, PW = g.PW[l], slabs = g.slabs[l];
+    const int D = g.D[l], K = g.K[l], F = g.F[l], ZW = g.ZW[l], HF = K * F, PW = g.PW[l];
     const float *G = g.gmat[l];
-    const int x = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + x;
-    if (blockIdx.x * 64 >= HF) return;
-    float s = 0.f, t = 0.f, b = 0.f;
+    const int x = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + x;
+    if (blockIdx.x * 16 >= HF) return;
+    float s = 0.f, t = 0.f;
     if (c < HF) {
         const int k = c / F;
-        for (int dd = ty; dd < D; dd += 16) {
+        for (int dd = ty; dd < D; dd += 64) {
             const float wv = g.w[l][(int64_t)dd * HF + c];
             s += wv * G[(int64_t)dd * ZW + HF + k];
             t += wv * G[(int64_t)dd * ZW + HF + K + k];
         }
     }
-    if (c < PW) {
-        const float *p = g.bias_part[l] + c;
-        int z = ty;
-        for (; z + 7 * 16 < slabs; z += 8 * 16) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = p[(int64_t)(z + 16 * j) * PW];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) b += v[j];
-        }
-        for (; z < slabs; z += 16) b += p[(int64_t)z * PW];
-    }
-    red[0][ty][x] = s; red[1][ty][x] = t; red[2][ty][x] = b;
+    red[ty][x] = s;
     __syncthreads();
-    if (ty == 0) {
-        s = t = b = 0.f;
-        for (int j = 0; j < 16; ++j) { s += red[0][j][x]; t += red[1][j][x]; b += red[2][j][x]; }
-        if (c < HF) { g.ga_src[l][c] = s; g.ga_dst[l][c] = t; }
-        if (c < PW) g.gb[l][c] = b;
+    if (ty == 0 && c < HF) {
+        s = 0.f;
+        for (int j = 0; j < 64; ++j) s += red[j][x];
+        g.ga_src[l][c] = s;
     }
+    __syncthreads();
+    red[ty][x] = t;
+    __syncthreads();
+    if (ty == 0 && c < HF) {
+        t = 0.f;
+        for (int j = 0; j < 64; ++j) t += red[j][x];
+        g.ga_dst[l][c] = t;
+    }
+    const float b = slab_sum_16x64(g.bias_part[l], PW, PW, g.slabs[l], blockIdx.x * 16, red);
+    if (threadIdx.x < 16 && c < PW) g.gb[l][c] = b;
 }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -512,6 +1028,17 @@ int check_params(gsplit_ctx *ctx, const gsplit_gat_params *p, const char *who) {
     return GSPLIT_OK;
 }
 
+// vectors of four floats per lane that a bottom-layer row needs (lanes run over the input width)
+int rows4_per_lane(int D) { return (int)gs_ceil_div(D, 256); }
+
+// the bottom layer runs aggregate-then-transform when it is not also the last layer and its shapes
+// fit the kernels: widths in 16-byte pieces, at most 8 heads, at most 32 accumulators per lane
+bool agg_first_shapes(const gsplit_ctx *ctx, const gsplit_gat_params *p) {
+    if (ctx->L < 2) return false;
+    const int D = p->dims[0], K = p->heads[0], F = p->dims[1] / K;
+    return D % 4 == 0 && F % 4 == 0 && K <= 8 && pow2_ceil(K) * rows4_per_lane(D) <= 8;
+}
+
 int ensure_buffers(gsplit_ctx *ctx, const gsplit_gat_params *p) {
     GsGatBuf &gb = ctx->gat;
     const int L = ctx->L;
@@ -526,26 +1053,42 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_gat_params *p) {
     auto A = [&](float **q, int64_t words, const char *what) {
         if (rc == GSPLIT_OK) rc = gs_alloc(ctx, (void **)q, sizeof(float) * (size_t)std::max<int64_t>(words, 4), what);
     };
+    gb.agg_first = agg_first_shapes(ctx, p);
     for (int l = 0; l < L; ++l) {
         const GatDims d = dims_of(ctx, p, l);
         const int D = p->dims[l];
         const int64_t n_lo = ctx->ub_front[l], n_up = ctx->ub_front[l + 1];
+        const bool af = l == 0 && gb.agg_first;
         A(&gb.wext[l], (int64_t)D * d.ZW, "GAT extended weights");
-        A(&gb.zext[l], n_lo * d.ZW, "GAT transformed rows");
-        A(&gb.dzext[l], n_lo * d.ZW, "GAT transformed-row gradients");
         A(&gb.alpha[l], (d.self_base + n_up) * d.K, "GAT attention coefficients");
-        A(&gb.de[l], (d.self_base + n_up) * d.K, "GAT score gradients");
-        A(&gb.der[l], n_up * d.K, "GAT destination score gradients");
-        A(&gb.gagg[l], n_up * d.HF, "GAT aggregate gradients");
+        if (!af) A(&gb.gagg[l], n_up * d.HF, "GAT aggregate gradients");     // else ghid[1] holds it
+        A(&gb.gmat[l], (int64_t)D * d.ZW, "GAT weight-gradient product");
         if (l > 0) {
             A(&gb.hidden[l], n_lo * D, "GAT hidden activations");
             A(&gb.ghid[l], n_lo * D, "GAT hidden gradients");
         }
-        const int tiles = (int)(gs_ceil_div(D, TileMid::BM) * gs_ceil_div(d.ZW, TileMid::BN));
-        gb.nchunk[l] = (int)(gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8);
-        A(&gb.gw_part[l], (int64_t)gb.nchunk[l] * (D + 1) * d.ZW, "GAT weight-gradient partials");
-        A(&gb.gmat[l], (int64_t)D * d.ZW, "GAT weight-gradient product");
-        gb.bias_slabs[l] = grid_1d(ctx, n_up * 64);
+        if (af) {
+            A(&gb.s0, n_lo * 2 * d.K, "GAT input-row scores");
+            A(&gb.pagg, n_up * d.K * D, "GAT aggregated inputs");
+            A(&gb.dpagg, n_up * d.K * D, "GAT aggregated-input gradients");
+            // the backward row kernel keeps about a hundred registers a lane: four workgroups a compute unit
+            gb.q_blocks = (int)std::min<int64_t>((int64_t)ctx->n_cu * 4, std::max<int64_t>(1, gs_ceil_div(n_up, 4)));
+            A(&gb.q_part, (int64_t)gb.q_blocks * 2 * d.K * D, "GAT score-gradient sums");
+            const int tiles = (int)(gs_ceil_div(D, TileTall::BM) * gs_ceil_div(d.F, TileTall::BN)) * d.K;
+            gb.nchunk0 = (int)(gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 2 / tiles), 8) * 8);
+            A(&gb.w0_part, (int64_t)gb.nchunk0 * d.K * (D + 1) * d.F, "GAT per-head weight-gradient partials");
+            gb.nchunk[l] = 0;
+            gb.bias_slabs[l] = 1;           // k_gat0_reduce leaves the finished sums in one slab
+        } else {
+            A(&gb.zext[l], n_lo * d.ZW, "GAT transformed rows");
+            A(&gb.dzext[l], n_lo * d.ZW, "GAT transformed-row gradients");
+            A(&gb.de[l], (d.self_base + n_up) * d.K, "GAT score gradients");
+            A(&gb.der[l], n_up * d.K, "GAT destination score gradients");
+            const int tiles = (int)(gs_ceil_div(D, TileMid::BM) * gs_ceil_div(d.ZW, TileMid::BN));
+            gb.nchunk[l] = (int)(gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8);
+            A(&gb.gw_part[l], (int64_t)gb.nchunk[l] * (D + 1) * d.ZW, "GAT weight-gradient partials");
+            gb.bias_slabs[l] = grid_1d(ctx, n_up * 64);
+        }
         A(&gb.bias_part[l], (int64_t)gb.bias_slabs[l] * p->dims[l + 1], "GAT bias-gradient partials");
     }
     if (rc) return rc;
@@ -567,7 +1110,11 @@ void launch_rows_gemm(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool va, cons
                       const EpiStore &epi, const GsLevelMeta *meta_rows) {
     const int n_out = B_KC ? b.rows : b.cols;
     if (!va) launch_rows_gemm_t<TileMid, 1, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
-    else if (!few_rows(ub, n_out, a.cols)) launch_rows_gemm_t<TileMidLean, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
+    else if (!few_rows(ub, n_out, a.cols)) {
+        // both operands k-contiguous: the unpadded direct-to-LDS tile (three workgroups a compute unit)
+        if (B_KC) launch_rows_gemm_t<TileMidDirect, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
+        else launch_rows_gemm_t<TileMidLean, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
+    }
     else if (n_out <= 64) launch_rows_gemm_t<TileLowNarrow, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
     else launch_rows_gemm_t<TileLow, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
 }
@@ -590,6 +1137,96 @@ RowShape row_shape(const GatDims &d) {
             else if ((RS).nv == 4) { CALL(1, 4); } else if ((RS).nv == 8) { CALL(1, 8); } else { CALL(1, 16); } \
         }                                                                             \
     } while (0)
+
+// bottom layer: NV vectors of four floats per lane, KP = heads rounded up to a power of two
+#define GAT0_DISPATCH(NVV, KPV, CALL)                                                              \
+    do {                                                                                           \
+        if ((NVV) == 1) {                                                                          \
+            if ((KPV) == 1) { CALL(1, 1); } else if ((KPV) == 2) { CALL(1, 2); }                   \
+            else if ((KPV) == 4) { CALL(1, 4); } else { CALL(1, 8); }                              \
+        } else {                                                                                   \
+            if ((KPV) == 1) { CALL(2, 1); } else if ((KPV) == 2) { CALL(2, 2); } else { CALL(2, 4); } \
+        }                                                                                          \
+    } while (0)
+
+unsigned head_gemm_grid(const gsplit_ctx *ctx, int64_t ub, int n_out, int heads) {
+    using T = TileTall;
+    const int64_t want = gs_ceil_div(gs_ceil_div(ub, T::BM), 8) * 8 * gs_ceil_div(n_out, T::BN) * heads;
+    return (unsigned)std::min<int64_t>(want, (int64_t)ctx->n_cu * 2 / 8 * 8);     // LDS: two workgroups a compute unit
+}
+
+void gat0_forward(gsplit_ctx *ctx, const gsplit_gat_params *p, const float *x0, hipStream_t st) {
+    GsGatBuf &gb = ctx->gat;
+    const GatDims d = dims_of(ctx, p, 0);
+    const int D = p->dims[0], S = ctx->S, KP = pow2_ceil(d.K), NV = rows4_per_lane(D);
+    const GsLayerBuf &B = ctx->layer[0];
+    const GsLevelMeta *ml = ctx->d_meta, *mu = ctx->d_meta + 1;
+    {
+        const dim3 grid(grid_1d(ctx, ctx->ub_front[0] * 8));
+        const size_t lds = sizeof(float) * 2 * d.K * D;
+        GsTimeScope ts(ctx, "gat0_scores", 0, st);
+#define GAT_CALL(NVV, KPV) hipLaunchKernelGGL((k_gat0_scores<KPV>), grid, dim3(256), lds, st, x0, D, gb.wext[0], d.ZW, d.HF, d.K, gb.s0, ml, S)
+        GAT0_DISPATCH(1, KP, GAT_CALL);
+#undef GAT_CALL
+    }
+    Gat0Args a{x0, gb.s0, B.blk_indptr, B.edge_row, B.self_row, gb.alpha[0], gb.pagg, nullptr, nullptr, D, d.K, d.fan, d.self_base, 0};
+    {
+        const dim3 grid(grid_1d(ctx, ctx->ub_front[1] * 64));
+        const size_t lds = sizeof(float) * 4 * (1 + d.fan) * (1 + KP);
+        GsTimeScope ts(ctx, "gat0_aggregate", 0, st);
+#define GAT_CALL(NVV, KPV) hipLaunchKernelGGL((k_gat0_aggregate<NVV, KPV>), grid, dim3(256), lds, st, a, mu, S)
+        GAT0_DISPATCH(NV, KP, GAT_CALL);
+#undef GAT_CALL
+    }
+    MatLd pa{gb.pagg, 0, D, d.K * D};
+    MatLd w{gb.wext[0], D, d.F, d.ZW};
+    EpiHeadElu epi{gb.hidden[1], (const float *)p->d_bias[0], d.HF, 0, d.F, 0};
+    GsTimeScope ts(ctx, "gat0_transform", 0, st);
+    hipLaunchKernelGGL((k_gat0_head_gemm<TileTall, false, EpiHeadElu>), dim3(head_gemm_grid(ctx, ctx->ub_front[1], d.F, d.K)),
+                       dim3(GNT), 0, st, pa, w, epi, d.K, D, d.F, d.F, mu, S);
+}
+
+void gat0_backward(gsplit_ctx *ctx, const gsplit_gat_params *p, const float *x0, hipStream_t st) {
+    GsGatBuf &gb = ctx->gat;
+    const GatDims d = dims_of(ctx, p, 0);
+    const int D = p->dims[0], S = ctx->S, KP = pow2_ceil(d.K), NV = rows4_per_lane(D);
+    const GsLayerBuf &B = ctx->layer[0];
+    const GsLevelMeta *mu = ctx->d_meta + 1;
+    // dagg of this layer: left in ghid[1] by the input-gradient product of layer 1
+    const float *gagg = gb.ghid[1];
+    {
+        MatLd ga{gagg, 0, d.F, d.HF};
+        MatLd w{gb.wext[0], D, d.F, d.ZW};
+        EpiHeadStore epi{gb.dpagg, d.K * D, 0, D, 0};
+        GsTimeScope ts(ctx, "gat0_grad_p", 0, st);
+        hipLaunchKernelGGL((k_gat0_head_gemm<TileTall, true, EpiHeadStore>), dim3(head_gemm_grid(ctx, ctx->ub_front[1], D, d.K)),
+                           dim3(GNT), 0, st, ga, w, epi, d.K, d.F, d.F, D, mu, S);
+    }
+    {
+        const int ch = std::max(4, std::min(16, 2048 / D));      // at most 8 KiB of staged rows per wave
+        Gat0Args a{x0, gb.s0, B.blk_indptr, B.edge_row, B.self_row, gb.alpha[0], gb.pagg, gb.dpagg, gb.q_part, D, d.K, d.fan,
+                   d.self_base, ch};
+        const dim3 grid(gb.q_blocks);
+        const size_t lds = sizeof(float) * 4 * (((1 + d.fan + 3) & ~3) + (((1 + d.fan) * KP + 3) & ~3) + ((KP + 3) & ~3) + ch * D);
+        GsTimeScope ts(ctx, "gat0_bwd", 0, st);
+#define GAT_CALL(NVV, KPV) hipLaunchKernelGGL((k_gat0_bwd<NVV, KPV>), grid, dim3(256), lds, st, a, mu, S)
+        GAT0_DISPATCH(NV, KP, GAT_CALL);
+#undef GAT_CALL
+    }
+    const int tm = (int)gs_ceil_div(D, TileTall::BM), tn = (int)gs_ceil_div(d.F, TileTall::BN);
+    {
+        MatLd pa{gb.pagg, 0, D, d.K * D};
+        MatLd ga{gagg, 0, d.F, d.HF};
+        EpiGradW ew{gb.w0_part, D + 1, d.F, D};
+        GsTimeScope ts(ctx, "gat0_grad_w", 0, st);
+        hipLaunchKernelGGL((k_gat0_grad_w<TileTall>), dim3((unsigned)(gb.nchunk0 * d.K * tm * tn)), dim3(GNT), 0, st, pa, ga,
+                           ew, gb.nchunk0, d.K, tm, tn, mu, S);
+    }
+    GsTimeScope ts(ctx, "gat0_reduce", 0, st);
+    const unsigned n_w = (unsigned)(d.K * (D + 1) * gs_ceil_div(d.F, 16)), n_q = (unsigned)gs_ceil_div((int64_t)2 * d.K * D, 16);
+    hipLaunchKernelGGL(k_gat0_reduce, dim3(n_w + n_q), dim3(1024), 0, st, gb.w0_part, gb.nchunk0, gb.q_part, gb.q_blocks, D,
+                       d.K, d.F, d.ZW, gb.gmat[0], gb.bias_part[0], mu, S);
+}
 
 }  // namespace
 
@@ -619,15 +1256,21 @@ extern "C" int gsplit_gat_fwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
         hipLaunchKernelGGL(k_gat_prep_weights, dim3((unsigned)std::min<int64_t>(256, gs_ceil_div(wmax, 256)), L), dim3(256),
                            0, st, pp);
     }
+    if (gb.agg_first && !aligned16(d_feat_local))
+        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_gat_fwd: features must be 16-byte aligned");
     for (int l = 0; l < L; ++l) {
         const GatDims d = dims_of(ctx, p, l);
         const int D = p->dims[l];
         const float *hin = l == 0 ? (const float *)d_feat_local : gb.hidden[l];
         const GsLayerBuf &B = ctx->layer[l];
+        if (l == 0 && gb.agg_first) {
+            gat0_forward(ctx, p, hin, st);
+            continue;
+        }
         {
             MatRows a{hin, 0, D};
             MatRows b{gb.wext[l], D, d.ZW};
-            EpiStore epi{gb.zext[l], d.ZW, 0, d.ZW};
+            EpiStore epi{gb.zext[l], d.ZW, 0, d.ZW, nullptr};
             GsTimeScope ts(ctx, "gat_transform", l, st);
             launch_rows_gemm<false>(ctx, st, ctx->ub_front[l], D % 4 == 0 && aligned16(hin), a, b, epi, ctx->d_meta + l);
         }
@@ -675,6 +1318,11 @@ extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
         const bool last = l == L - 1;
         const GsLayerBuf &B = ctx->layer[l];
         const float *hin = l == 0 ? (const float *)d_feat_local : gb.hidden[l];
+        if (l == 0 && gb.agg_first) {
+            if (!aligned16(hin)) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_gat_bwd: features must be 16-byte aligned");
+            gat0_backward(ctx, p, hin, st);
+            continue;
+        }
         const RowShape rs = row_shape(d);
         const size_t lds = sizeof(float) * 4 * (1 + d.fan) * (1 + d.K);
         {
@@ -709,7 +1357,9 @@ extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
         if (l > 0) {
             MatRows dz{gb.dzext[l], 0, d.ZW};
             MatRows w{gb.wext[l], D, d.ZW};
-            EpiStore epi{gb.ghid[l], D, 0, D};
+            // below an aggregate-then-transform bottom layer the ELU derivative is applied here: what
+            // is stored is that layer's dagg
+            EpiStore epi{gb.ghid[l], D, 0, D, (l == 1 && gb.agg_first) ? gb.hidden[1] : nullptr};
             GsTimeScope ts(ctx, "gat_grad_in", l, st);
             launch_rows_gemm<true>(ctx, st, ctx->ub_front[l], true, dz, w, epi, ctx->d_meta + l);
         }
@@ -747,7 +1397,7 @@ extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
                                st, gf);
         }
         GsTimeScope ts(ctx, "gat_finish_cols", -1, st);
-        hipLaunchKernelGGL(k_gat_finish_cols, dim3((unsigned)gs_ceil_div(hf_max, 64), L), dim3(1024), 0, st, gf);
+        hipLaunchKernelGGL(k_gat_finish_cols, dim3((unsigned)gs_ceil_div(hf_max, 16), L), dim3(1024), 0, st, gf);
     }
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;

@@ -94,6 +94,15 @@ struct GsGatBuf {              // GAT: what the forward pass keeps for the backw
     float   *gmat[GS_MAXL] = {nullptr};      // [D x ZW]  X^T dzext
     float   *bias_part[GS_MAXL] = {nullptr}; // [bias_slabs x dims[l+1]]
     int      bias_slabs[GS_MAXL] = {0};
+    // bottom layer run as aggregate-then-transform (no zext / dzext / de / der / gw_part for layer 0)
+    bool     agg_first = false;
+    float   *s0 = nullptr;                   // [rows of level 0 x 2 K]  h . (W a_src) | h . (W a_dst)
+    float   *pagg = nullptr;                 // [ub_dst x K x D]  sum_j alpha_ij^k h_j
+    float   *dpagg = nullptr;                // [ub_dst x K x D]  its gradient
+    float   *q_part = nullptr;               // [q_slabs x 2 K x D]  per-wave sums of d e h
+    int      q_blocks = 0;
+    float   *w0_part = nullptr;              // [nchunk0 x K x D x F]  split-K slabs of P^kT dagg^k
+    int      nchunk0 = 0;
     bool     fwd_done = false;
     uint64_t fwd_batch = 0;
 };

@@ -63,7 +63,9 @@ def _check(r, L):
 
 
 # name -> (workload, heads): widths that take the 16-byte and the scalar lane layouts, head counts
-# that are and are not powers of two, one to sixteen values per lane, S = 1 .. 8
+# that are and are not powers of two, one to sixteen values per lane, S = 1 .. 8; bottom layers
+# that run aggregate-then-transform (input width and features per head multiples of 4) and ones
+# that run transform-then-aggregate like the layers above
 CASES = {
     "tiny-2x1": (lambda: workloads.tiny(), None),
     "heads-4-4-1": (lambda: workloads.custom(6000, 150000, dims=[100, 64, 64, 47], fanouts=[6, 5, 4], batch=300,
@@ -74,6 +76,12 @@ CASES = {
                                                   n_splits=4, pmap_kind="range", name="gat-c"), [1, 1]),
     "heads-8-S8-fan20": (lambda: workloads.custom(5000, 200000, dims=[64, 256, 40], fanouts=[20, 15], batch=200,
                                                   n_splits=8, name="gat-d"), [8, 6]),
+    # 320 input features: two 16-byte vectors per lane in the bottom-layer kernels
+    "input-320": (lambda: workloads.custom(4000, 90000, dims=[320, 64, 10], fanouts=[7, 5], batch=200,
+                                           n_splits=4, name="gat-f"), [2, 2]),
+    # one layer only: the bottom layer is also the last one
+    "single-layer": (lambda: workloads.custom(3000, 60000, dims=[64, 12], fanouts=[9], batch=150,
+                                              n_splits=2, name="gat-g"), [3]),
     "S1-scalar-wide": (lambda: workloads.custom(2000, 30000, dims=[18, 250, 7], fanouts=[5, 5], batch=300,
                                                 n_splits=1, name="gat-e"), [2, 5]),
 }
