@@ -395,14 +395,13 @@ def main():
             ent = edges[l] + nd
             if l == 0:
                 # bottom layer, aggregate-then-transform: per-head products over the destinations; the row
-                # kernels move one input row per entry (twice in the backward kernel)
+                # kernels move one input row per entry
                 add("gat0_transform.l0", "flops", 2.0 * nd * D * HF)
                 add("gat0_grad_p.l0", "flops", 2.0 * nd * D * HF)
                 add("gat0_grad_w.l0", "flops", 2.0 * nd * D * HF)
                 add("gat0_scores.l0", "bytes", n_lo * 4 * (D + 2 * K))
                 add("gat0_aggregate.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
-                add("gat0_bwd.l0", "bytes", ent * (4 + 8 * D + 8 * K) + nd * 4 * K * D)
-                add("gat0_dagg.l0", "bytes", nd * 12 * HF)
+                add("gat0_bwd.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
             add(f"gat_transform.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
             add(f"gat_grad_w.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
             if l > 0:
