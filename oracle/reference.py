@@ -311,6 +311,62 @@ def split_quality(batch: Batch, pmap) -> dict:
             "edges": total, "ids_shuffled": sent}
 
 
+def batch_stats(batch: Batch, pmap):
+    """Per sampling layer and split: the edges the split computes and how many of them are cross
+    edges (source vertex owned by another split).  The two figures of the paper's partitioning
+    evaluation (section 7.3) follow from them: workload imbalance = max over splits of the edges
+    at layers l > 0 divided by their average; communication cost = cross edges / all edges."""
+    pmap = np.asarray(pmap)
+    L, S = batch.n_layers, batch.n_splits
+    edges = np.zeros((L, S), np.int64)
+    cross = np.zeros((L, S), np.int64)
+    for l in range(L):
+        for s in range(S):
+            b = batch.blocks[l][s]
+            for i in range(b.dst.shape[0]):
+                for q in range(int(b.cnt[i])):
+                    edges[l, s] += 1
+                    if pmap[b.nbr[i, q]] != s:
+                        cross[l, s] += 1
+    return edges, cross
+
+
+def quality_from_stats(edges: np.ndarray, cross: np.ndarray) -> dict:
+    upper = edges[1:].sum(0) if edges.shape[0] > 1 else np.zeros(edges.shape[1], np.int64)
+    imb = float(upper.max() / upper.mean()) if upper.sum() else 1.0
+    return {"workload_imbalance": imb, "cross_edge_fraction": float(cross.sum()) / max(int(edges.sum()), 1)}
+
+
+# --------------------------------------------------------------------------------------------
+# data-parallel micro-batches (paper section 2, "Redundant loading and computation", Table 1)
+# --------------------------------------------------------------------------------------------
+def micro_batches(indptr, indices, fanouts: Sequence[int], targets, n_micro: int, seed: int, it: int):
+    """The mini-batch's targets dealt to n_micro micro-batches by position (equal contiguous parts,
+    the remainder to the first ones), each sampled on its own as data-parallel training does:
+    one split, no partition map, and its own random stream (iteration counter it * n_micro + m)."""
+    targets = np.asarray(targets, np.int32)
+    n_vertices = len(indptr) - 1
+    pm = np.zeros(n_vertices, np.uint8)
+    base, rem = divmod(targets.shape[0], n_micro)
+    out, pos = [], 0
+    for m in range(n_micro):
+        n = base + (1 if m < rem else 0)
+        out.append(sp_sample(indptr, indices, pm, 1, fanouts, targets[pos:pos + n], seed, it * n_micro + m))
+        pos += n
+    return out
+
+
+def redundancy_counts(mini: Batch, micro: Sequence[Batch]) -> dict:
+    """Table 1's two columns for one iteration: edges computed (all sampling layers) and feature
+    rows loaded (input layer), for the micro-batches together and for the one mini-batch."""
+    def edges_of(b):
+        return sum(int(blk.blk_indptr[-1]) for layer in b.blocks for blk in layer)
+    def feats_of(b):
+        return int(b.local_cat(0).shape[0])
+    return {"edges_micro": sum(edges_of(b) for b in micro), "edges_mini": edges_of(mini),
+            "features_micro": sum(feats_of(b) for b in micro), "features_mini": feats_of(mini)}
+
+
 # --------------------------------------------------------------------------------------------
 # Algorithm 2 (forward) and the backward pass
 # --------------------------------------------------------------------------------------------
