@@ -249,6 +249,16 @@ GSPLIT_API int64_t gsplit_timing_read(gsplit_ctx *ctx, char *buf, int64_t buf_by
 GSPLIT_API int gsplit_presample_accumulate(gsplit_ctx *ctx, uint32_t *d_vertex_count, uint32_t *d_edge_count,
                                            void *stream);
 
+/* Split statistics (section 7.3, evaluation of the splitting algorithm): adds the current batch to
+ *   d_edges       [L * S], uint64: += edges of sampling layer l computed by split s, at [l * S + s]
+ *   d_cross_edges [L * S], uint64: += those of them whose source vertex another split owns
+ * From the sums the paper's figures follow: workload imbalance = max over s of the edges at layers
+ * l > 0 divided by their average over s; communication cost = cross edges / all edges.  A
+ * data-parallel micro-batch (Table 1) is a context with one split; its edge total and its
+ * level-0 row count (gsplit_batch_sizes) are the "edges computed" and "features loaded" columns.
+ * EINVAL for NULL pointers, ESTATE without a batch.  Asynchronous. */
+GSPLIT_API int gsplit_batch_stats(gsplit_ctx *ctx, uint64_t *d_edges, uint64_t *d_cross_edges, void *stream);
+
 /* w[i] = count[i] / n_samples for i < n (w_V = k_v / N, w_E = k_e / N).  EINVAL for NULL pointers,
  * n < 0 or n_samples < 1.  Asynchronous. */
 GSPLIT_API int gsplit_presample_weights(gsplit_ctx *ctx, const uint32_t *d_count, int64_t n, int64_t n_samples,

@@ -24,7 +24,7 @@ EXPORTS = [
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
     "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
-    "gsplit_gat_fwd", "gsplit_gat_bwd",
+    "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats",
 ]
 
 
@@ -98,6 +98,7 @@ def load_library():
     L.gsplit_timing_read.restype = i64
     L.gsplit_presample_accumulate.argtypes = [vp, vp, vp, vp]
     L.gsplit_presample_weights.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.gsplit_batch_stats.argtypes = [vp, vp, vp, vp]
     L.gsplit_gat_fwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, vp]
     L.gsplit_gat_bwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                  C.POINTER(vp), vp]
@@ -336,6 +337,12 @@ class Context:
         self._check(self.lib.gsplit_presample_accumulate(
             self.h, vertex_count.data_ptr() if vertex_count is not None else None,
             edge_count.data_ptr() if edge_count is not None else None, _stream()))
+
+    def gsplit_batch_stats(self, edges: torch.Tensor, cross_edges: torch.Tensor):
+        # int64 tensors carry the uint64 counters
+        for t in (edges, cross_edges):
+            assert t.is_cuda and t.dtype == torch.int64 and t.is_contiguous() and t.numel() == self.L * self.S
+        self._check(self.lib.gsplit_batch_stats(self.h, edges.data_ptr(), cross_edges.data_ptr(), _stream()))
 
     def gsplit_presample_weights(self, count: torch.Tensor, n_samples: int, weight: torch.Tensor):
         assert count.is_cuda and count.dtype == torch.int32 and count.is_contiguous()

@@ -258,6 +258,18 @@ def sage_weights(dims: Sequence[int], *, seed: int, device="cpu"):
     return w_self, w_neigh, bias
 
 
+def micro_batch_parts(targets: torch.Tensor, n_micro: int):
+    """The targets of one mini-batch dealt to n_micro data-parallel micro-batches by position: equal
+    contiguous parts, the remainder to the first ones."""
+    base, rem = divmod(targets.numel(), n_micro)
+    out, pos = [], 0
+    for m in range(n_micro):
+        n = base + (1 if m < rem else 0)
+        out.append(targets[pos:pos + n])
+        pos += n
+    return out
+
+
 def gat_weights(dims: Sequence[int], heads: Sequence[int], *, seed: int, device="cpu"):
     """Glorot-uniform W[l] of shape [D_l, heads_l * F_l] (F_l = dims[l+1] / heads_l on hidden layers,
     dims[L] on the last, whose heads are averaged), attention vectors a_src[l], a_dst[l] of
