@@ -46,6 +46,10 @@ def parse():
     ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
     ap.add_argument("--presample", action="store_true",
                     help="measure the offline pre-sampling stage instead (sampling + counting of k_v, k_e)")
+    ap.add_argument("--redundancy", action="store_true",
+                    help="data-parallel micro-batch mode against split mode: one mini-batch of splits x batch "
+                         "targets, once split and once as `splits` independent micro-batches (Table 1 counters, "
+                         "workload imbalance, cross-edge share, time per iteration)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
@@ -290,6 +294,108 @@ def presample_bench(a, w, dev, t_gen):
     print(json.dumps(out))
 
 
+def redundancy_bench(a, w, dev, t_gen):
+    """Paper section 2 (Table 1) and section 7.3 on one GPU: every iteration takes one mini-batch of
+    S x batch targets and runs a whole training step on it twice, split S ways (one context with S
+    splits) and as S data-parallel micro-batches of `batch` targets (a context with one split,
+    called S times with its own random stream each).  Same kernels, all work done, serial on one
+    stream."""
+    import copy
+    import numpy as np
+    import torch
+    import workloads
+    S, L = a.splits, w.n_layers
+    w_mini = copy.copy(w)
+    w_mini.batch = w.batch * S
+    w_micro = copy.copy(w)
+    w_micro.n_splits = 1
+    w_micro.pmap = torch.zeros_like(w.pmap)
+    mini, micro = Runner(w_mini, dev, a.model, a.heads), Runner(w_micro, dev, a.model, a.heads)
+    n_total = a.warmup + a.steps
+    targets = [w_mini.targets(i) for i in range(n_total)]
+    parts = [workloads.micro_batch_parts(t, S) for t in targets]
+    torch.cuda.synchronize()
+
+    def run(which, lo, hi):
+        t0 = time.perf_counter()
+        for i in range(lo, hi):
+            if which == "mini":
+                mini.step(targets[i], i)
+            else:
+                for m in range(S):
+                    micro.step(parts[i][m], i * S + m)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run("mini", 0, a.warmup); run("micro", 0, a.warmup)
+    dt_mini = run("mini", a.warmup, n_total)
+    dt_micro = run("micro", a.warmup, n_total)
+
+    # counters over the same iterations (untimed pass: reading sizes waits for the sampler)
+    edges = torch.zeros(L * S, dtype=torch.int64, device=dev)
+    cross = torch.zeros(L * S, dtype=torch.int64, device=dev)
+    tot = {"edges_micro": 0, "edges_mini": 0, "features_micro": 0, "features_mini": 0}
+    imb = []
+    mini.ctx.gsplit_timing_enable(True)
+    slots = 0
+    for i in range(a.warmup, n_total):
+        mini.ctx.gsplit_sample_split(targets[i], mini.seed, i)
+        before = edges.clone()
+        mini.ctx.gsplit_batch_stats(edges, cross)
+        n_local, _, n_edges, _ = mini.ctx.gsplit_batch_sizes()
+        tot["edges_mini"] += int(np.sum(n_edges)); tot["features_mini"] += int(np.sum(n_local[0]))
+        slots += sum(int(np.sum(n_local[l + 1])) * w.fanouts[l] for l in range(L))
+        per_split = (edges - before).view(L, S)[1:].sum(0).double()
+        imb.append(float(per_split.max() / per_split.mean()) if float(per_split.sum()) > 0 else 1.0)
+        for m in range(S):
+            micro.ctx.gsplit_sample_split(parts[i][m], micro.seed, i * S + m)
+            nl, _, ne, _ = micro.ctx.gsplit_batch_sizes()
+            tot["edges_micro"] += int(np.sum(ne)); tot["features_micro"] += int(np.sum(nl[0]))
+    torch.cuda.synchronize()
+    kt = mini.ctx.gsplit_timing_read()
+    cnt, ms = kt["batch_stats"]
+    # per slot: the neighbour id (4 bytes) and, for a sampled one, its owner byte
+    work = slots * 4 + tot["edges_mini"]
+    sec = ms / max(cnt, 1) * 1e-3
+    ach = work / max(cnt, 1) / sec / 1e9
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import reference as R
+        R.build_oracle()
+        ip, ix, pm = w.indptr.cpu().numpy(), w.indices.cpu().numpy(), w.pmap.cpu().numpy()
+        n_cpu = max(1, min(a.cpu_iters, 8))
+        tc = time.perf_counter()
+        for i in range(a.warmup, a.warmup + n_cpu):
+            tg = targets[i].cpu().numpy()
+            mb = R.sp_sample(ip, ix, pm, S, w.fanouts, tg, mini.seed, i)
+            R.redundancy_counts(mb, R.micro_batches(ip, ix, w.fanouts, tg, S, micro.seed, i))
+        dtc = time.perf_counter() - tc
+        cpu = {"value": n_cpu / dtc, "unit": "iterations/s", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} iterations: sampling and counting of the split mini-batch and of its {S} "
+                         f"micro-batches (single-threaded C steps, no training step), {dtc:.1f} s"}
+    e_all, c_all = int(edges.sum()), int(cross.sum())
+    out = {
+        "metric": f"mini-batches/sec of {S * w.batch} targets as {S} data-parallel micro-batches "
+                  f"(sample+gather+{a.model} fwd/bwd each) at 1 GPU",
+        "value": a.steps / dt_micro, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt_micro / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.feat.dtype == torch.float32 else "bf16", "data": "synthetic",
+        "config": dict(w_mini.describe(), model=a.model, micro_batches=S, micro_batch=w.batch, graph_gen_s=round(t_gen, 1),
+                       schedule="serial, one stream"),
+        "split_mode": {"value": a.steps / dt_mini, "ms_per_step": dt_mini / a.steps * 1e3},
+        "time_ratio_micro_over_split": dt_micro / dt_mini,
+        "table1": dict(tot, edges_ratio=tot["edges_micro"] / max(tot["edges_mini"], 1),
+                       features_ratio=tot["features_micro"] / max(tot["features_mini"], 1), iterations=a.steps),
+        "split_quality": {"workload_imbalance_mean": sum(imb) / len(imb), "workload_imbalance_max": max(imb),
+                          "cross_edge_fraction": c_all / max(e_all, 1)},
+        "roofline": {"kernel": "batch_stats", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": work / max(cnt, 1),
+                     "launch_ms": ms / max(cnt, 1)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -327,6 +433,8 @@ def main():
     t_gen = time.time() - t0
     if a.presample:
         return presample_bench(a, w, dev, t_gen)
+    if a.redundancy:
+        return redundancy_bench(a, w, dev, t_gen)
     if a.model == "gat" and dtype != "f32":
         print("bench.py: --model gat runs in f32", file=sys.stderr)
         sys.exit(2)
