@@ -596,3 +596,63 @@ def presample_counts(indptr, indices, fanouts, batches, seed, iters):
 def presample_weights(k_v, k_e, n_samples):
     """w_V(v) = k_v / N, w_E(e) = k_e / N."""
     return k_v.astype(np.float64) / n_samples, k_e.astype(np.float64) / n_samples
+
+
+# --------------------------------------------------------------------------------------------
+# partial feature cache aligned with f_G and the host-memory miss path (sections 3, 4 and 7.1)
+# --------------------------------------------------------------------------------------------
+def input_counts(indptr, indices, fanouts, batches, seed, iters):
+    """k_in[v] = number of samples whose input layer (level 0) holds v: the sampling-frequency
+    criterion by which input features are ranked for caching (section 7.1).  Same unsplit sampler as
+    presample_counts."""
+    indptr64 = np.ascontiguousarray(indptr, np.int64)
+    indices = np.ascontiguousarray(indices, np.int32)
+    n_vertices, L = indptr64.shape[0] - 1, len(fanouts)
+    k_in = np.zeros(n_vertices, np.int64)
+    scratch = _Scratch(n_vertices)
+    for targets, it in zip(batches, iters):
+        front = np.ascontiguousarray(targets, np.int32)
+        for l in range(L - 1, -1, -1):
+            nbr, cnt = sample_layer(indptr64, indices, front, fanouts[l], l, seed, it)[:2]
+            front = unique_first(np.concatenate([front, slot_stream(nbr, cnt)]), scratch)
+        k_in[front] += 1
+    return k_in
+
+
+def cache_select(k_in, pmap, n_splits: int, capacity: Sequence[int]):
+    """Static cache content: split s caches the capacity[s] most frequently sampled vertices among
+    those f_G assigns to it (f_G also decides where a vertex's input features are cached, section
+    4, so that caches are consistent with the splits); ties go to the smaller id; a vertex that
+    was never sampled is not cached.  Returns one id array per split, hottest first."""
+    k_in = np.asarray(k_in, np.int64)
+    pmap = np.asarray(pmap)
+    out = []
+    for s in range(n_splits):
+        own = np.nonzero((pmap == s) & (k_in > 0))[0]
+        order = sorted(own.tolist(), key=lambda v: (-int(k_in[v]), v))
+        out.append(np.asarray(order[:int(capacity[s])], np.int32))
+    return out
+
+
+def cached_gather(host_table: np.ndarray, cache_ids, cache_rows, batch: Batch):
+    """Loading step with a cache: a row of split s's input layer comes from s's cache if s cached
+    that vertex, otherwise from the host table.  Returns the gathered rows (splits concatenated)
+    and the hits and misses per split."""
+    S = batch.n_splits
+    hits, misses = np.zeros(S, np.int64), np.zeros(S, np.int64)
+    parts = []
+    for s in range(S):
+        where = {int(v): j for j, v in enumerate(cache_ids[s])}
+        ids = batch.local_front[0][s]
+        rows = np.empty((ids.shape[0], host_table.shape[1]), host_table.dtype)
+        for r, v in enumerate(ids):
+            j = where.get(int(v))
+            if j is None:
+                rows[r] = host_table[v]
+                misses[s] += 1
+            else:
+                rows[r] = cache_rows[s][j]
+                hits[s] += 1
+        parts.append(rows)
+    out = np.concatenate(parts, 0) if parts else np.zeros((0, host_table.shape[1]), host_table.dtype)
+    return out, hits, misses
