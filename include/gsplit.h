@@ -259,6 +259,38 @@ GSPLIT_API int gsplit_presample_accumulate(gsplit_ctx *ctx, uint32_t *d_vertex_c
  * EINVAL for NULL pointers, ESTATE without a batch.  Asynchronous. */
 GSPLIT_API int gsplit_batch_stats(gsplit_ctx *ctx, uint64_t *d_edges, uint64_t *d_cross_edges, void *stream);
 
+/* Partial feature cache aligned with f_G, and the host-memory miss path (sections 3 and 4: the
+ * features live in host memory, f_G also decides on which GPU a vertex's input features are
+ * statically cached, and the loading step skips what is cached; section 7.1: what to cache is
+ * ranked by sampling frequency).
+ *
+ * gsplit_input_counts_accumulate: d_count[v] += 1 (uint32) for every vertex of the current batch's
+ * input layer (level 0): run over some epochs of sampling it is the ranking criterion.  The
+ * choice of what to cache from the counts is the caller's (an offline step, like the partition
+ * map).  ESTATE without a batch.  Asynchronous.
+ *
+ * gsplit_cache_build: `table` is the full feature table [n_vertices x dim] (dtype, row stride as
+ * in gsplit_gather_features) in memory the device can read: pinned HOST memory (hipHostMalloc,
+ * torch pin_memory) or device memory; it must stay valid and unchanged in the rows that are not
+ * cached for as long as the cache is used.  d_cache_ids (DEVICE) lists the vertices to cache,
+ * grouped by split: first n_cache[0] ids that f_G gives to split 0, then n_cache[1] of split 1, ...
+ * (n_cache: HOST [S]).  Cache row j holds a copy of table row d_cache_ids[j] in HBM.  EINVAL for
+ * an id outside the graph, listed under a split that does not own it, or listed twice, and for a
+ * table the device cannot read.  Synchronises with `stream` (a set-up call).  One cache per
+ * context; building again replaces it (the old buffers are released with the context).
+ *
+ * gsplit_gather_features_cached: the loading step: d_out[r, :] = the cached copy if the vertex of
+ * row r (local_cat[0][r]) is cached, else the row of `table`, read over the host link without a
+ * host round trip.  d_out as in gsplit_gather_features.  d_hits / d_misses (may be NULL): DEVICE
+ * [S] uint64, += rows of split s served by the cache / by the table.  ESTATE without a cache or a
+ * batch.  Asynchronous. */
+GSPLIT_API int gsplit_input_counts_accumulate(gsplit_ctx *ctx, uint32_t *d_count, void *stream);
+GSPLIT_API int gsplit_cache_build(gsplit_ctx *ctx, const void *table, int32_t dtype, int64_t dim,
+                                  int64_t row_stride_bytes, const int32_t *d_cache_ids, const int64_t *n_cache,
+                                  void *stream);
+GSPLIT_API int gsplit_gather_features_cached(gsplit_ctx *ctx, void *d_out, uint64_t *d_hits, uint64_t *d_misses,
+                                             void *stream);
+
 /* w[i] = count[i] / n_samples for i < n (w_V = k_v / N, w_E = k_e / N).  EINVAL for NULL pointers,
  * n < 0 or n_samples < 1.  Asynchronous. */
 GSPLIT_API int gsplit_presample_weights(gsplit_ctx *ctx, const uint32_t *d_count, int64_t n, int64_t n_samples,

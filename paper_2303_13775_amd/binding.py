@@ -25,6 +25,7 @@ EXPORTS = [
     "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats",
+    "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
 ]
 
 
@@ -99,6 +100,9 @@ def load_library():
     L.gsplit_presample_accumulate.argtypes = [vp, vp, vp, vp]
     L.gsplit_presample_weights.argtypes = [vp, vp, i64, i64, vp, vp]
     L.gsplit_batch_stats.argtypes = [vp, vp, vp, vp]
+    L.gsplit_input_counts_accumulate.argtypes = [vp, vp, vp]
+    L.gsplit_cache_build.argtypes = [vp, vp, i32, i64, i64, vp, C.POINTER(i64), vp]
+    L.gsplit_gather_features_cached.argtypes = [vp, vp, vp, vp, vp]
     L.gsplit_gat_fwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, vp]
     L.gsplit_gat_bwd.argtypes = [vp, C.POINTER(_GatParams), vp, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                  C.POINTER(vp), vp]
@@ -343,6 +347,32 @@ class Context:
         for t in (edges, cross_edges):
             assert t.is_cuda and t.dtype == torch.int64 and t.is_contiguous() and t.numel() == self.L * self.S
         self._check(self.lib.gsplit_batch_stats(self.h, edges.data_ptr(), cross_edges.data_ptr(), _stream()))
+
+    def gsplit_input_counts_accumulate(self, count: torch.Tensor):
+        assert count.is_cuda and count.dtype == torch.int32 and count.is_contiguous() and count.numel() == self.n_vertices
+        self._check(self.lib.gsplit_input_counts_accumulate(self.h, count.data_ptr(), _stream()))
+
+    def gsplit_cache_build(self, table: torch.Tensor, cache_ids: torch.Tensor, n_cache: Sequence[int]):
+        """table: [n_vertices, dim] float32 / bfloat16, on the device or in pinned host memory."""
+        assert table.dim() == 2 and table.stride(1) == 1 and table.shape[0] == self.n_vertices
+        assert table.dtype in (torch.float32, torch.bfloat16) and (table.is_cuda or table.is_pinned())
+        assert cache_ids.is_cuda and cache_ids.dtype == torch.int32 and cache_ids.is_contiguous()
+        assert len(n_cache) == self.S and sum(n_cache) == cache_ids.numel()
+        self._cache_keep = (table, cache_ids)
+        self._cache_dim, self._cache_dtype = table.shape[1], table.dtype
+        self._check(self.lib.gsplit_cache_build(
+            self.h, table.data_ptr(), GSPLIT_F32 if table.dtype == torch.float32 else GSPLIT_BF16, table.shape[1],
+            table.stride(0) * table.element_size(), cache_ids.data_ptr(), (C.c_int64 * self.S)(*[int(x) for x in n_cache]),
+            _stream()))
+
+    def gsplit_gather_features_cached(self, out: torch.Tensor, hits: Optional[torch.Tensor] = None,
+                                      misses: Optional[torch.Tensor] = None):
+        assert out.is_cuda and out.is_contiguous() and out.dtype == self._cache_dtype and out.shape[1] == self._cache_dim
+        for t in (hits, misses):      # int64 tensors carry the uint64 counters
+            assert t is None or (t.is_cuda and t.dtype == torch.int64 and t.is_contiguous() and t.numel() == self.S)
+        self._check(self.lib.gsplit_gather_features_cached(
+            self.h, out.data_ptr(), hits.data_ptr() if hits is not None else None,
+            misses.data_ptr() if misses is not None else None, _stream()))
 
     def gsplit_presample_weights(self, count: torch.Tensor, n_samples: int, weight: torch.Tensor):
         assert count.is_cuda and count.dtype == torch.int32 and count.is_contiguous()

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgsplit.so")
-SOURCES = ["api.hip", "sample_split.hip", "gather.hip", "sage.hip", "presample.hip", "gat.hip", "stats.hip"]
+SOURCES = ["api.hip", "sample_split.hip", "gather.hip", "sage.hip", "presample.hip", "gat.hip", "stats.hip", "cache.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

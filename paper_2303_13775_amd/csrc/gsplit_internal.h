@@ -107,6 +107,16 @@ struct GsGatBuf {              // GAT: what the forward pass keeps for the backw
     uint64_t fwd_batch = 0;
 };
 
+struct GsFeatureCache {        // static input-feature cache aligned with f_G
+    bool        ready = false;
+    const void *table = nullptr;   // full table as the device reads it (pinned host or device memory)
+    int32_t     dtype = 0;
+    int64_t     dim = 0, row_stride_bytes = 0, n_rows = 0;
+    int32_t    *slot_of = nullptr; // [n_vertices]  cache row of the vertex, or -1
+    void       *rows = nullptr;    // [n_rows x dim]
+    int32_t    *d_err = nullptr;
+};
+
 // Optional per-kernel device timing: when enabled, every kernel launch is bracketed by two events
 // on its stream; gsplit_timing_read() waits for them and reports totals per label.
 struct GsTimer {
@@ -154,6 +164,7 @@ struct gsplit_ctx {
 
     GsSageBuf    sage;
     GsGatBuf     gat;
+    GsFeatureCache cache;
     GsTimer      timer;
     std::vector<void *> allocs;
     std::string  err;
