@@ -50,6 +50,11 @@ def parse():
                     help="data-parallel micro-batch mode against split mode: one mini-batch of splits x batch "
                          "targets, once split and once as `splits` independent micro-batches (Table 1 counters, "
                          "workload imbalance, cross-edge share, time per iteration)")
+    ap.add_argument("--cache-frac", type=float, default=None,
+                    help="keep the feature table in pinned host memory and cache this fraction of every split's "
+                         "vertices in HBM, ranked by pre-sampled input-layer frequency; the loading step then is "
+                         "gsplit_gather_features_cached (0 = everything over the host link)")
+    ap.add_argument("--cache-presample", type=int, default=200, help="sampling iterations that rank the cache")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
@@ -81,6 +86,20 @@ class Runner:
         self.glogits = torch.empty_like(self.logits)
         self.seed = 0xC0FFEE
 
+    def enable_cache(self, host_table, cache_ids, n_cache):
+        self.ctx.gsplit_cache_build(host_table, cache_ids, n_cache)
+        self.cached = True
+        S = self.w.n_splits
+        self.hits = self.torch.zeros(S, dtype=self.torch.int64, device=self.dev)
+        self.misses = self.torch.zeros(S, dtype=self.torch.int64, device=self.dev)
+
+    def load(self, count=False):
+        if getattr(self, "cached", False):
+            # the hit / miss counters are an extra pass over the rows: only when asked for
+            self.ctx.gsplit_gather_features_cached(self.x0, self.hits if count else None, self.misses if count else None)
+        else:
+            self.ctx.gsplit_gather_features(self.w.feat, self.x0)
+
     def forward(self):
         if self.model == "gat":
             self.ctx.gsplit_gat_fwd(self.params, self.x0, self.logits)
@@ -102,7 +121,7 @@ class Runner:
         rec(0)
         c.gsplit_sample_split(targets, self.seed, it)
         rec(1)
-        c.gsplit_gather_features(self.w.feat, self.x0)
+        self.load()
         rec(2)
         self.forward()
         rec(3)
@@ -155,7 +174,7 @@ class Pipelined:
                     with torch.cuda.stream(ss):
                         ss.wait_event(self.free[k])
                         r.ctx.gsplit_sample_split(targets[i], r.seed, i)
-                        r.ctx.gsplit_gather_features(r.w.feat, r.x0)
+                        r.load()
                         self.ready[k].record(ss)
                     sampled.put(i)
             except BaseException as e:      # hand the failure to the training thread
@@ -439,6 +458,27 @@ def main():
         print("bench.py: --model gat runs in f32", file=sys.stderr)
         sys.exit(2)
     r = Runner(w, dev, a.model, a.heads)
+    cache_info = None
+    if a.cache_frac is not None:
+        # offline: rank every split's vertices by how often the sampler puts them into the input layer
+        # (library kernel), keep the hottest fraction (a sort: the caller's policy step), build the cache
+        host_table = torch.empty(w.feat.shape, dtype=w.feat.dtype, pin_memory=True)
+        host_table.copy_(w.feat)
+        k_in = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
+        for i in range(a.cache_presample):
+            r.ctx.gsplit_sample_split(w.targets(10_000_000 + i), r.seed, 10_000_000 + i)
+            r.ctx.gsplit_input_counts_accumulate(k_in)
+        ids, n_cache = [], []
+        for s_ in range(w.n_splits):
+            own = torch.nonzero((w.pmap == s_) & (k_in > 0)).flatten()
+            order = torch.sort(-k_in[own].long(), stable=True).indices
+            keep = int(a.cache_frac * int((w.pmap == s_).sum()))
+            ids.append(own[order][:keep].int())
+            n_cache.append(int(ids[-1].numel()))
+        cache_ids = torch.cat(ids).contiguous()
+        cache_info = {"host_table": host_table, "ids": cache_ids, "n_cache": n_cache}
+        r.enable_cache(host_table, cache_ids, n_cache)
+        del k_in
     n_total = a.warmup + a.steps
     targets = [w.targets(i) for i in range(n_total)]
     torch.cuda.synchronize()
@@ -455,6 +495,9 @@ def main():
     dt = dt_serial
     if not a.no_pipeline:
         pipe = Pipelined(w, dev, a.ahead, a.model, a.heads)
+        if cache_info:
+            for slot in pipe.slots:
+                slot.enable_cache(cache_info["host_table"], cache_info["ids"], cache_info["n_cache"])
         pipe.run(targets, 0, a.warmup)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -494,6 +537,7 @@ def main():
         mixed = [sum(x) for x in n_mixed]
         shape = (rows, edges, mixed, bucket)
         add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
+        add("gather_cached", "bytes", rows[0] * (2 * row_bytes + 8))
         for l in range(L if a.model == "gat" else 0):
             # the transform and both backward products run over the rows of level l; the row kernels
             # move one transformed (or gradient) row per entry (edge or self) and its coefficients
@@ -575,7 +619,20 @@ def main():
                 "launch_ms": ms / max(cnt, 1)}
 
     rows, edges, mixed, bucket = shape
-    gather = roofline_of("gather_rows")
+    gather = roofline_of("gather_cached" if cache_info else "gather_rows")
+    if cache_info:
+        # hits and misses of the kernel-timing iterations alone (the counters ran since the cache was built)
+        r.hits.zero_(); r.misses.zero_()
+        for i in range(n_k):
+            r.ctx.gsplit_sample_split(targets[a.warmup + i], r.seed, a.warmup + i)
+            r.load(count=True)
+        torch.cuda.synchronize()
+        h, m = int(r.hits.sum()), int(r.misses.sum())
+        PCIE_PEAK_GBS = 64.0       # PCIe 5.0 x16, one direction
+        link = m / n_k * row_bytes / (gather["launch_ms"] * 1e-3) / 1e9
+        gather["cache"] = {"fraction_cached": a.cache_frac, "rows_cached": int(sum(cache_info["n_cache"])),
+                           "hit_rate": h / max(h + m, 1), "miss_bytes_per_launch": m / n_k * row_bytes,
+                           "host_link": {"achieved": link, "peak": PCIE_PEAK_GBS, "unit": "GB/s", "frac": link / PCIE_PEAK_GBS}}
     out = {
         "metric": f"mini-batches/sec (sample+split+gather+{'GAT' if a.model == 'gat' else 'SAGE'} fwd/bwd) at 1 GPU",
         "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
@@ -584,6 +641,7 @@ def main():
         "config": dict(w.describe(), model=a.model, **({"heads": r.heads} if a.model == "gat" else {}),
                        fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1),
+                       **({"features": "pinned host memory", "cache_frac": a.cache_frac} if cache_info else {}),
                        schedule=("serial, one stream" if a.no_pipeline else
                                  f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the "
                                  f"next {a.ahead} step(s) overlap fwd/loss/bwd of step i")),
