@@ -339,15 +339,20 @@ struct PartTargets {
     static constexpr int NK = GS_MAXS;
     const int32_t *targets; int n_targets; const uint8_t *pmap; int S; uint32_t n_vertices;
     int32_t *front; int32_t *perm; GsLevelMeta *meta; GsTable tab_mixed; int fan_top;
+    GsLevelMeta *meta_all; int n_levels;
     __device__ int n() const { return n_targets; }
-    // an id outside the graph is replaced by vertex 0 and reported through the error flag
+    // an id outside the graph is replaced by vertex 0 and reported through the error flag (by the
+    // scatter pass only: the count pass is where the flags of the previous batch are cleared)
     __device__ int32_t target(int g) const {
         const uint32_t id = (uint32_t)targets[g];
         if (id < n_vertices) return (int32_t)id;
         meta->error = 3;
         return 0;
     }
-    __device__ unsigned classify(int g) const { return 1u << (pmap[target(g)] & (GS_MAXS - 1)); }
+    __device__ unsigned classify(int g) const {
+        const uint32_t id = (uint32_t)targets[g];
+        return 1u << (pmap[id < n_vertices ? id : 0u] & (GS_MAXS - 1));
+    }
     __device__ unsigned cached(int g) const { return classify(g); }
     __device__ int upper_offset(int) const { return 0; }
     __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *) const {     // o.a = front_off
@@ -369,8 +374,9 @@ struct PartTargets {
     }
     __device__ int64_t n_extra(const PartOffs &) const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
     __device__ void extra(int64_t x, const PartOffs &) const { tab_mixed.slot[x] = EMPTY_ENTRY; }
-    __device__ int64_t n_side() const { return 0; }
-    __device__ void side(int64_t) const {}
+    // the count pass is the first kernel of a batch: it clears the error flags of every level
+    __device__ int64_t n_side() const { return n_levels; }
+    __device__ void side(int64_t x) const { meta_all[x].error = 0; }
 };
 
 // ---- partition A: mixed frontiers, block CSR offsets and owner buckets in one pass over the
@@ -593,16 +599,27 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
     }
 }
 
-// reverse index, step 2: give every row of local_cat[l] a segment of rev_list (segments need not
-// be in row order: one atomic per workgroup of 1024 rows hands out space; the cursor is a single
-// address, and an atomic on it from every wave of a million-row level took longer than the
-// rest of the kernel)
-__global__ __launch_bounds__(1024) void k_rev_alloc(const int32_t *__restrict__ rev_cnt,
-                                                    int32_t *__restrict__ rev_ptr,
-                                                    int32_t *__restrict__ rev_fill,
-                                                    GsLevelMeta *meta_lo, int S) {
+// reverse index of all layers that have one, two launches (blockIdx.y = layer - first)
+struct RevArgs {
+    const int32_t *rev_cnt[GS_MAXL]; int32_t *rev_ptr[GS_MAXL]; int32_t *rev_fill[GS_MAXL];
+    int32_t *rev_list[GS_MAXL]; int32_t *rev_eid[GS_MAXL];
+    const int32_t *cnt[GS_MAXL]; const int32_t *blk_indptr[GS_MAXL]; const int32_t *self_row[GS_MAXL];
+    const int32_t *edge_row[GS_MAXL];
+    int fan[GS_MAXL];
+    int first;
+};
+
+// step 2: give every row of local_cat[l] a segment of rev_list (segments need not be in row order:
+// one atomic per workgroup of 1024 rows hands out space; the cursor is a single address, and an
+// atomic on it from every wave of a million-row level took longer than the rest of the kernel)
+__global__ __launch_bounds__(1024) void k_rev_alloc(RevArgs a, GsLevelMeta *meta, int S) {
     __shared__ int s_wave[16];
     __shared__ int s_base;
+    const int l = a.first + blockIdx.y;
+    GsLevelMeta *meta_lo = meta + l;
+    const int32_t *__restrict__ rev_cnt = a.rev_cnt[l];
+    int32_t *__restrict__ rev_ptr = a.rev_ptr[l];
+    int32_t *__restrict__ rev_fill = a.rev_fill[l];
     const int n_lo = meta_lo->front_off[S];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int stride = gridDim.x * blockDim.x;
@@ -631,17 +648,20 @@ __global__ __launch_bounds__(1024) void k_rev_alloc(const int32_t *__restrict__ 
     }
 }
 
-// reverse index, step 3: list, for every source row, the destination rows it feeds
-__global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ ent_mixed,
-                                                  const int32_t *__restrict__ blk_indptr,
-                                                  const int32_t *__restrict__ self_row,
-                                                  const int32_t *__restrict__ edge_row,
-                                                  const int32_t *__restrict__ rev_ptr,
-                                                  int32_t *__restrict__ rev_fill,
-                                                  int32_t *__restrict__ rev_list,
-                                                  int32_t *__restrict__ rev_eid,
-                                                  const GsLevelMeta *__restrict__ meta_up, int S, int fan) {
-    const int n1 = meta_up->front_off[S];
+// step 3: list, for every source row, the destination rows it feeds (slot q of destination i is a
+// sampled edge when q < cnt[i])
+__global__ __launch_bounds__(256) void k_rev_fill(RevArgs a, const GsLevelMeta *__restrict__ meta, int S) {
+    const int l = a.first + blockIdx.y;
+    const int fan = a.fan[l];
+    const int32_t *__restrict__ cnt = a.cnt[l];
+    const int32_t *__restrict__ blk_indptr = a.blk_indptr[l];
+    const int32_t *__restrict__ self_row = a.self_row[l];
+    const int32_t *__restrict__ edge_row = a.edge_row[l];
+    const int32_t *__restrict__ rev_ptr = a.rev_ptr[l];
+    int32_t *__restrict__ rev_fill = a.rev_fill[l];
+    int32_t *__restrict__ rev_list = a.rev_list[l];
+    int32_t *__restrict__ rev_eid = a.rev_eid[l];
+    const int n1 = meta[l + 1].front_off[S];
     const int64_t total = (int64_t)n1 * (1 + fan);
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
@@ -651,8 +671,8 @@ __global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ en
             code = 2 * (int)x;
         } else {
             const int64_t g = x - n1;
-            if (ent_mixed[n1 + g] < 0) continue;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+            if (q >= cnt[i]) continue;
             eid = blk_indptr[i] + q;
             u = edge_row[eid];
             code = 2 * i + 1;
@@ -662,10 +682,6 @@ __global__ __launch_bounds__(256) void k_rev_fill(const int32_t *__restrict__ en
         rev_list[rev_ptr[u] + p] = code;
         if (rev_eid) rev_eid[rev_ptr[u] + p] = eid;
     }
-}
-
-__global__ void k_clear_errors(GsLevelMeta *meta, int n_levels) {
-    if (blockIdx.x == 0 && (int)threadIdx.x < n_levels) meta[threadIdx.x].error = 0;
 }
 
 int part_blocks(int64_t upper_items) {
@@ -739,12 +755,9 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
     ctx->sage.fwd_done = false;
     ctx->last_stream = st;
 
-    {
-        GsTimeScope ts(ctx, "clear_errors", -1, st);
-        hipLaunchKernelGGL(k_clear_errors, dim3(1), dim3(64), 0, st, ctx->d_meta, L + 1);
-    }
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
-                   ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1]};
+                   ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1],
+                   ctx->d_meta, L + 1};
     run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
 
     for (int l = L - 1; l >= 0; --l) {
@@ -772,18 +785,28 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
                            B.blk_indptr, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
                            ml, mu, S, fan);
         }
-        if (l >= ctx->rev_from) {
-            {
-                GsTimeScope ts(ctx, "rev_alloc", l, st);
-                hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
-                                       (int64_t)ctx->n_cu * 2, gs_ceil_div(ctx->ub_front[l], 1024)))), dim3(1024), 0, st,
-                                   B.rev_cnt, B.rev_ptr, B.rev_fill, ml, S);
-            }
-            GsTimeScope ts(ctx, "rev_fill", l, st);
-            hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, ub1 * (1 + fan))), dim3(256), 0, st,
-                               ctx->ent_mixed, B.blk_indptr, B.self_row, B.edge_row, B.rev_ptr, B.rev_fill,
-                               B.rev_list, B.rev_eid, mu, S, fan);
+    }
+    if (ctx->rev_from < L) {
+        RevArgs ra{};
+        ra.first = ctx->rev_from;
+        int64_t rows = 1, items = 1;
+        for (int l = ctx->rev_from; l < L; ++l) {
+            const GsLayerBuf &B = ctx->layer[l];
+            ra.rev_cnt[l] = B.rev_cnt; ra.rev_ptr[l] = B.rev_ptr; ra.rev_fill[l] = B.rev_fill; ra.rev_list[l] = B.rev_list;
+            ra.rev_eid[l] = B.rev_eid; ra.cnt[l] = B.cnt; ra.blk_indptr[l] = B.blk_indptr; ra.self_row[l] = B.self_row;
+            ra.edge_row[l] = B.edge_row; ra.fan[l] = ctx->fan[l];
+            rows = std::max<int64_t>(rows, ctx->ub_front[l]);
+            items = std::max<int64_t>(items, ctx->ub_front[l + 1] * (1 + ctx->fan[l]));
         }
+        const unsigned ny = (unsigned)(L - ctx->rev_from);
+        {
+            GsTimeScope ts(ctx, "rev_alloc", -1, st);
+            hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
+                                   (int64_t)ctx->n_cu * 2, gs_ceil_div(rows, 1024))), ny), dim3(1024), 0, st, ra,
+                               ctx->d_meta, S);
+        }
+        GsTimeScope ts(ctx, "rev_fill", -1, st);
+        hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, items), ny), dim3(256), 0, st, ra, ctx->d_meta, S);
     }
     GS_HIP(ctx, hipGetLastError());
     GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
