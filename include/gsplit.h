@@ -108,6 +108,21 @@ GSPLIT_API int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
 GSPLIT_API int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                         uint64_t seed, uint64_t iter, void *stream);
 
+/* The same with the seed and the iteration counter read from DEVICE memory when the kernels run
+ * (d_seed_iter[0] = seed, d_seed_iter[1] = iter), for steps that are captured into a HIP graph
+ * and replayed for successive iterations.
+ *
+ * Stream capture: every asynchronous entry point only enqueues kernels on `stream`, with launch
+ * shapes that depend on the context's upper bounds alone (the sizes of a batch stay in device
+ * memory), so a whole step (this call, gsplit_gather_features, forward, loss, backward) can be
+ * captured with hipStreamBeginCapture / hipStreamEndCapture and replayed.  Before capturing, run the
+ * same step once eagerly: the first forward/backward call sizes the context's internal buffers
+ * (allocation is not possible under capture).  Under capture no timing is taken, and the
+ * host-side queries of a captured batch (gsplit_batch_sizes) wait for the whole device and read the
+ * sizes anew on every call. */
+GSPLIT_API int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+                                       const uint64_t *d_seed_iter, void *stream);
+
 /* Host-visible sizes of the current batch.  The first call after a gsplit_sample_split waits for
  * `stream` work of that call to finish (one device-to-host copy); later calls are free.
  *   n_local  [(L+1) * S]: |local_front[l]_s| at [l * S + s]

@@ -24,7 +24,7 @@ EXPORTS = [
     "gsplit_batch_sizes", "gsplit_batch_level", "gsplit_batch_layer", "gsplit_gather_features",
     "gsplit_sage_fwd", "gsplit_sage_bwd", "gsplit_softmax_xent", "gsplit_timing_enable",
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
-    "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats",
+    "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
 ]
 
@@ -86,6 +86,7 @@ def load_library():
     L.gsplit_max_rows.argtypes = [vp, i32]
     L.gsplit_max_rows.restype = i64
     L.gsplit_sample_split.argtypes = [vp, vp, i64, u64, u64, vp]
+    L.gsplit_sample_split_dev.argtypes = [vp, vp, i64, vp, vp]
     L.gsplit_batch_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_batch_level.argtypes = [vp, i32, C.POINTER(_LevelView)]
     L.gsplit_batch_layer.argtypes = [vp, i32, C.POINTER(_LayerView)]
@@ -246,6 +247,13 @@ class Context:
         self._targets = targets
         self._check(self.lib.gsplit_sample_split(self.h, targets.data_ptr(), targets.numel(),
                                                  C.c_uint64(seed), C.c_uint64(it), _stream()))
+
+    def gsplit_sample_split_dev(self, targets: torch.Tensor, seed_iter: torch.Tensor):
+        """seed_iter: int64 device tensor [seed, iteration] read when the kernels run."""
+        assert targets.is_cuda and targets.dtype == torch.int32 and targets.is_contiguous()
+        assert seed_iter.is_cuda and seed_iter.dtype == torch.int64 and seed_iter.numel() == 2
+        self._check(self.lib.gsplit_sample_split_dev(self.h, targets.data_ptr(), targets.numel(),
+                                                     seed_iter.data_ptr(), _stream()))
 
     def gsplit_batch_sizes(self):
         S, L = self.S, self.L

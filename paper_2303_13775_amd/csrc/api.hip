@@ -167,7 +167,10 @@ extern "C" int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level) {
 static int fetch_meta(gsplit_ctx *ctx) {
     if (ctx->h_meta_valid) return GSPLIT_OK;
     if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "no batch has been sampled yet");
-    GS_HIP(ctx, hipEventSynchronize(ctx->sample_done));
+    // a captured batch has no event and changes with every replay of its graph: wait for the device
+    // and read the sizes again on every call
+    if (ctx->captured) GS_HIP(ctx, hipDeviceSynchronize());
+    else GS_HIP(ctx, hipEventSynchronize(ctx->sample_done));
     GS_HIP(ctx, hipMemcpy(ctx->h_meta, ctx->d_meta, sizeof(GsLevelMeta) * (ctx->L + 1),
                           hipMemcpyDeviceToHost));
     if (ctx->h_meta[ctx->L].error != 0)
@@ -176,7 +179,7 @@ static int fetch_meta(gsplit_ctx *ctx) {
         if (ctx->h_meta[l].error != 0)
             return gs_fail(ctx, GSPLIT_ESTATE, "internal: hash table probe failed at layer " +
                                                    std::to_string(l));
-    ctx->h_meta_valid = true;
+    ctx->h_meta_valid = !ctx->captured;
     return GSPLIT_OK;
 }
 

@@ -158,6 +158,7 @@ struct gsplit_ctx {
     int32_t     *part_base = nullptr;
 
     uint64_t     batch_id = 0;
+    bool         captured = false;          // the current batch was enqueued under stream capture
     int64_t      n_targets = 0;
     hipStream_t  last_stream = nullptr;
     hipEvent_t   sample_done = nullptr;
@@ -184,7 +185,7 @@ int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what);
 struct GsTimeScope {
     gsplit_ctx *ctx; hipStream_t st; int label; hipEvent_t a;
     GsTimeScope(gsplit_ctx *c, const char *name, int layer, hipStream_t s) : ctx(c), st(s), label(-1), a(nullptr) {
-        if (!c->timer.enabled) return;
+        if (!c->timer.enabled || c->captured) return;
         GsTimer &t = c->timer;
         std::string full = layer >= 0 ? std::string(name) + ".l" + std::to_string(layer) : std::string(name);
         for (size_t i = 0; i < t.names.size(); ++i)

@@ -115,11 +115,16 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                                                       GsLevelMeta *meta_lo,
                                                       const GsLevelMeta *__restrict__ meta_up, int S,
                                                       int fan, uint32_t layer, uint64_t seed,
-                                                      uint64_t iter, GsTable tab,
+                                                      uint64_t iter, const uint64_t *__restrict__ seed_iter,
+                                                      GsTable tab,
                                                       int32_t *__restrict__ ent_mixed,
                                                       int32_t *__restrict__ nbr,
                                                       int32_t *__restrict__ cnt,
                                                       int64_t *__restrict__ epos) {
+    if (seed_iter) {        // seed and iteration counter kept in device memory (replayed graphs)
+        seed = seed_iter[0];
+        iter = seed_iter[1];
+    }
     const int n1 = meta_up->front_off[S];
     const int bits = table_bits(n1 * (1 + fan));
     const int groups_per_block = PART_BS / G;
@@ -714,7 +719,7 @@ int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
 }
 
 template <typename IndPtrT>
-void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStream_t st) {
+void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, const uint64_t *d_seed_iter, hipStream_t st) {
     const int fan = ctx->fan[l];
     const int64_t ub = ctx->ub_front[l + 1];
     GsLevelMeta *ml = ctx->d_meta + l;
@@ -725,29 +730,34 @@ void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, hipStre
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     } else if (fan <= 32) {
         hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     } else {
         hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
     }
 }
 
-}  // namespace
-
-extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
-                                   uint64_t seed, uint64_t iter, void *stream) {
-    if (!ctx) return GSPLIT_EINVAL;
+int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, uint64_t seed, uint64_t iter,
+                 const uint64_t *d_seed_iter, void *stream) {
     if (n_targets < 0 || (n_targets > 0 && !d_targets))
         return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split: bad targets");
     if (n_targets > ctx->max_targets)
         return gs_fail(ctx, GSPLIT_ECAPACITY, "gsplit_sample_split: n_targets exceeds max_targets");
     hipStream_t st = (hipStream_t)stream;
     const int S = ctx->S, L = ctx->L;
+    // Under stream capture the calls of a step become nodes of a graph: no event is recorded for the
+    // host-side queries (they synchronise the device instead) and no timing events are taken.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+        (void)hipGetLastError();
+        cap = hipStreamCaptureStatusNone;
+    }
+    ctx->captured = cap == hipStreamCaptureStatusActive;
 
     ctx->batch_id += 1;
     ctx->n_targets = n_targets;
@@ -767,8 +777,8 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         GsLevelMeta *ml = ctx->d_meta + l;
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
 
-        if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, st);
-        else launch_sample<int32_t>(ctx, l, seed, iter, st);
+        if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, d_seed_iter, st);
+        else launch_sample<int32_t>(ctx, l, seed, iter, d_seed_iter, st);
 
         PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
                             ctx->ent_mixed, ctx->cls, ctx->ent_local, ctx->mixed_ent,
@@ -809,6 +819,21 @@ extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
         hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, items), ny), dim3(256), 0, st, ra, ctx->d_meta, S);
     }
     GS_HIP(ctx, hipGetLastError());
-    GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
+    if (!ctx->captured) GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
     return GSPLIT_OK;
+}
+
+}  // namespace
+
+extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+                                   uint64_t seed, uint64_t iter, void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    return sample_split(ctx, d_targets, n_targets, seed, iter, nullptr, stream);
+}
+
+extern "C" int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
+                                       const uint64_t *d_seed_iter, void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    if (!d_seed_iter) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split_dev: NULL seed / iteration buffer");
+    return sample_split(ctx, d_targets, n_targets, 0, 0, d_seed_iter, stream);
 }
