@@ -44,6 +44,10 @@ def parse():
                     help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
                          "overlaps forward/backward of step i on a second stream)")
     ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the timed steps as captured HIP graphs instead of enqueueing every kernel from the "
+                         "host (measured: no faster here, the steps are bound by the device-side kernel boundaries, "
+                         "not by the host's launch rate)")
     ap.add_argument("--presample", action="store_true",
                     help="measure the offline pre-sampling stage instead (sampling + counting of k_v, k_e)")
     ap.add_argument("--redundancy", action="store_true",
@@ -100,6 +104,45 @@ class Runner:
         else:
             self.ctx.gsplit_gather_features(self.w.feat, self.x0)
 
+    # -- captured steps: the targets of step i are row i of one device table, the step counter lives
+    # in device memory and advances with every replay, so a replay needs nothing from the host
+    def prepare_graphs(self, targets_all, stride):
+        torch = self.torch
+        self.targets_all = targets_all
+        self.tg_buf = torch.zeros(self.w.batch, dtype=torch.int32, device=self.dev)
+        self.seed_iter = torch.tensor([self.seed, 0], dtype=torch.int64, device=self.dev)
+        self.step_idx = torch.zeros(1, dtype=torch.int64, device=self.dev)
+        self.stride = stride
+
+    def _next_targets(self):
+        self.tg_buf.view(1, -1).copy_(self.targets_all.index_select(0, self.step_idx))
+        self.seed_iter[1:2].copy_(self.step_idx)
+        self.step_idx.add_(self.stride)
+
+    def _sample_from_device_state(self):
+        self._next_targets()
+        self.ctx.gsplit_sample_split_dev(self.tg_buf, self.seed_iter)
+        self.load()
+
+    def _train(self):
+        self.forward()
+        self.loss()
+        self.backward()
+
+    def capture(self, stream, parts):
+        """One graph per element of parts ('sample', 'train', or 'step' for both)."""
+        torch = self.torch
+        out = {}
+        for part in parts:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                if part in ("sample", "step"):
+                    self._sample_from_device_state()
+                if part in ("train", "step"):
+                    self._train()
+            out[part] = g
+        return out
+
     def forward(self):
         if self.model == "gat":
             self.ctx.gsplit_gat_fwd(self.params, self.x0, self.logits)
@@ -150,6 +193,16 @@ class Pipelined:
         for e in self.free:
             e.record()
 
+    def enable_graphs(self, targets_all):
+        """Captures, per slot, a sampling graph and a training graph (after every slot has run eagerly
+        once, which sizes the library's buffers)."""
+        torch = self.torch
+        self.graphs = []
+        for k, r in enumerate(self.slots):
+            r.prepare_graphs(targets_all, self.n)
+            self.graphs.append(r.capture(self.s_train, ("sample", "train")))
+        torch.cuda.synchronize()
+
     def run(self, targets, first, count):
         """Two host threads enqueue (a launch costs the host a few microseconds and a step has
         about sixty): one feeds the sampling streams, this one the training stream.  The queues only
@@ -162,6 +215,11 @@ class Pipelined:
         for _ in range(self.n):
             freed.put(None)
         failure = []
+        graphs = getattr(self, "graphs", None)
+        if graphs:      # slot k replays steps k, k + n, ...: point its device-side counter at its first one
+            for k, r in enumerate(self.slots):
+                r.step_idx.fill_(first + ((k - first) % self.n))
+            torch.cuda.synchronize()
 
         def sampler():
             try:
@@ -173,8 +231,11 @@ class Pipelined:
                     ss = self.s_sample[i % len(self.s_sample)]
                     with torch.cuda.stream(ss):
                         ss.wait_event(self.free[k])
-                        r.ctx.gsplit_sample_split(targets[i], r.seed, i)
-                        r.load()
+                        if graphs:
+                            graphs[k]["sample"].replay()
+                        else:
+                            r.ctx.gsplit_sample_split(targets[i], r.seed, i)
+                            r.load()
                         self.ready[k].record(ss)
                     sampled.put(i)
             except BaseException as e:      # hand the failure to the training thread
@@ -192,9 +253,12 @@ class Pipelined:
                 r = self.slots[k]
                 with torch.cuda.stream(self.s_train):
                     self.s_train.wait_event(self.ready[k])
-                    r.forward()
-                    r.loss()
-                    r.backward()
+                    if graphs:
+                        graphs[k]["train"].replay()
+                    else:
+                        r.forward()
+                        r.loss()
+                        r.backward()
                     self.free[k].record(self.s_train)
                 freed.put(None)
         finally:
@@ -484,12 +548,35 @@ def main():
     torch.cuda.synchronize()
 
     # strictly serial steps on one stream
+    use_graph = a.graph
+    targets_all = torch.stack(targets).contiguous() if use_graph else None
     for i in range(a.warmup):
         r.step(targets[i], i)
     torch.cuda.synchronize()
+    graph_check = None
+    if use_graph:
+        # the same step as one captured HIP graph; its first replay is checked against the eager step
+        s_cap = torch.cuda.Stream(device=dev)
+        r.prepare_graphs(targets_all, 1)
+        g_step = r.capture(s_cap, ("step",))["step"]
+        torch.cuda.synchronize()
+        r.step(targets[0], 0)
+        torch.cuda.synchronize()
+        want = r.logits.clone()
+        r.step_idx.fill_(0)
+        r.logits.fill_(0.0)
+        g_step.replay()
+        torch.cuda.synchronize()
+        graph_check = bool(torch.equal(want, r.logits))
+        assert graph_check, "a replayed step differs from the eager step"
+        r.step_idx.fill_(a.warmup)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(a.warmup, n_total):
-        r.step(targets[i], i)
+        if use_graph:
+            g_step.replay()
+        else:
+            r.step(targets[i], i)
     torch.cuda.synchronize()
     dt_serial = time.perf_counter() - t0
     dt = dt_serial
@@ -500,6 +587,10 @@ def main():
                 slot.enable_cache(cache_info["host_table"], cache_info["ids"], cache_info["n_cache"])
         pipe.run(targets, 0, a.warmup)
         torch.cuda.synchronize()
+        if use_graph:
+            pipe.enable_graphs(targets_all)
+            pipe.run(targets, 0, a.warmup)
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         pipe.run(targets, a.warmup, a.steps)
         torch.cuda.synchronize()
@@ -642,6 +733,9 @@ def main():
                        fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1),
                        **({"features": "pinned host memory", "cache_frac": a.cache_frac} if cache_info else {}),
+                       launch=("every stream replays captured HIP graphs (the step counter and the targets table "
+                               "stay in device memory)" if use_graph else "kernels enqueued from the host"),
+                       **({"graph_replay_equals_eager": graph_check} if use_graph else {}),
                        schedule=("serial, one stream" if a.no_pipeline else
                                  f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the "
                                  f"next {a.ahead} step(s) overlap fwd/loss/bwd of step i")),
