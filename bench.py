@@ -68,14 +68,15 @@ def parse():
 class Runner:
     """Holds the device-resident inputs, the context and the preallocated outputs of a step."""
 
-    def __init__(self, w, dev, model="sage", heads=4):
+    def __init__(self, w, dev, model="sage", heads=4, sampler_blocks_per_cu=0):
         import torch
         import workloads
         from paper_2303_13775_amd import Context, SageParams, GatParams
         self.torch = torch
         self.w, self.dev, self.model = w, dev, model
         from paper_2303_13775_amd import GSPLIT_BF16, GSPLIT_F32
-        self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch, gat_index=model == "gat")
+        self.ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch, gat_index=model == "gat",
+                           sampler_blocks_per_cu=sampler_blocks_per_cu)
         if model == "gat":
             self.heads = [heads] * (w.n_layers - 1) + [1]
             self.gat_w = workloads.gat_weights(w.dims, self.heads, seed=w.seed, device=dev)
@@ -185,7 +186,9 @@ class Pipelined:
         import torch
         self.torch = torch
         self.n = n_ahead + 1
-        self.slots = [Runner(w, dev, model, heads) for _ in range(self.n)]
+        # sampling kernels are latency-bound: two workgroups per compute unit instead of eight cost them
+        # about 1 % and leave wave slots for the training stream's workgroups (medium: +5 % throughput)
+        self.slots = [Runner(w, dev, model, heads, sampler_blocks_per_cu=2) for _ in range(self.n)]
         self.s_sample = [torch.cuda.Stream(device=dev) for _ in range(n_ahead)]
         self.s_train = torch.cuda.Stream(device=dev)
         self.ready = [torch.cuda.Event() for _ in range(self.n)]

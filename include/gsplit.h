@@ -74,6 +74,11 @@ typedef struct {
                                        edge (8 bytes per slot), which gsplit_presample_accumulate needs */
     int32_t        gat_index;       /* 1: the scatter side of the shuffle index is also built for the bottom
                                        layer and carries edge ids, which gsplit_gat_bwd needs */
+    int32_t        sampler_blocks_per_cu; /* 0 or 1..8: workgroups per compute unit the sampling and index
+                                       kernels may occupy (default 8 = all wave slots: fastest alone).  A caller
+                                       that overlaps sampling with training on another stream does better with
+                                       2: the latency-bound sampling kernels then leave room for the training
+                                       kernels' workgroups */
 } gsplit_config;
 
 /* Creates a context on the current HIP device and allocates its workspace, sized from the

@@ -67,6 +67,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     ctx->max_targets = c->max_targets;
     ctx->keep_edge_ids = c->keep_edge_ids != 0;
     ctx->gat_index = c->gat_index != 0;
+    ctx->sampler_blocks_per_cu = c->sampler_blocks_per_cu > 0 ? std::min(c->sampler_blocks_per_cu, 8) : 8;
     ctx->rev_from = ctx->gat_index ? 0 : 1;
     for (int l = 0; l < ctx->L; ++l) ctx->fan[l] = c->fanouts[l];
 

@@ -137,6 +137,7 @@ struct gsplit_ctx {
     int64_t  max_targets = 0;
     bool     keep_edge_ids = false;
     bool     gat_index = false;
+    int      sampler_blocks_per_cu = 8;    // cap on the grids of the sampling and index kernels
     int      rev_from = 1;             // lowest sampling layer with a reverse index (0 with gat_index)
     int64_t  ub_front[GS_MAXL + 1] = {0};   // upper bounds on |local_cat[l]|
     int      n_cu = 256;

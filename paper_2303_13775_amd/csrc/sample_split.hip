@@ -713,7 +713,7 @@ void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t
 
 int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
     int64_t want = gs_ceil_div(upper_items, 256);
-    int64_t cap = (int64_t)ctx->n_cu * 8;
+    int64_t cap = (int64_t)ctx->n_cu * ctx->sampler_blocks_per_cu;
     if (want < 1) want = 1;
     return (int)(want < cap ? want : cap);
 }
