@@ -1,7 +1,8 @@
 """GPU parity of the GAT layer (paper section 7.1, second model): gsplit_gat_fwd / gsplit_gat_bwd,
 called through the C ABI, against oracle/gat.py on the same seeded batch, features and parameters.
 Logits and every parameter gradient within 1e-4 of the float64 oracle, measured as
-|a - o| / max(|o|, 1e-2 * max|o|)."""
+|a - o| / max(|o|, 1e-2 * max|o|); for the two attention-vector gradients of a layer max|o| is
+taken over both (see attention_grad_err)."""
 import numpy as np
 import pytest
 import torch
@@ -53,12 +54,24 @@ def _run(w, heads, dev, seed, it, n_splits=None, pmap=None, batch_targets=None):
     return res
 
 
+def attention_grad_err(a, o, o_src, o_dst) -> float:
+    """Error of an attention-vector gradient, judged against the common scale of the layer's two
+    attention gradients: d a_dst sums the very terms of d a_src, but over the neighbours of a
+    destination first, where they cancel (with every score in the linear part of the LeakyReLU
+    the softmax does not depend on the destination term at all and d a_dst is identically zero),
+    so its entries are small differences of terms of the size of d a_src."""
+    a = np.asarray(a, np.float64).reshape(-1); o = np.asarray(o, np.float64).reshape(-1)
+    scale = np.maximum(np.abs(o), 1e-2 * max(np.abs(o_src).max(), np.abs(o_dst).max()))
+    return float((np.abs(a - o) / np.where(scale == 0, 1.0, scale)).max())
+
+
 def _check(r, L):
     assert R.max_rel_err(r["logits"], r["of"].logits) < TOL_F32, "logits"
     for l in range(L):
+        o_src, o_dst = r["ob"].ga_src[l], r["ob"].ga_dst[l]
         assert R.max_rel_err(r["gw"][l], r["ob"].gw[l]) < TOL_F32, ("gw", l)
-        assert R.max_rel_err(r["gas"][l], r["ob"].ga_src[l]) < TOL_F32, ("ga_src", l)
-        assert R.max_rel_err(r["gad"][l], r["ob"].ga_dst[l]) < TOL_F32, ("ga_dst", l)
+        assert attention_grad_err(r["gas"][l], o_src, o_src, o_dst) < TOL_F32, ("ga_src", l)
+        assert attention_grad_err(r["gad"][l], o_dst, o_src, o_dst) < TOL_F32, ("ga_dst", l)
         assert R.max_rel_err(r["gb"][l].reshape(-1), r["ob"].gbias[l].reshape(-1)) < TOL_F32, ("gbias", l)
 
 
