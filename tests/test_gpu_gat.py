@@ -107,8 +107,8 @@ def test_gat_forward_backward_within_tolerance(name):
     if heads is None:
         heads = [2] * (w.n_layers - 1) + [1]
         assert all(w.dims[l + 1] % heads[l] == 0 for l in range(w.n_layers - 1))
-    r = _run(w, heads, _dev(), seed=55, it=1)
-    _check(r, w.n_layers)
+    for seed, it in ((55, 1), (333, 3)):
+        _check(_run(w, heads, _dev(), seed=seed, it=it), w.n_layers)
 
 
 def test_gat_edge_cases_isolated_targets_and_one_owner():
