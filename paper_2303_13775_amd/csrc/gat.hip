@@ -30,6 +30,12 @@ namespace {
 
 constexpr float NEG_SLOPE = 0.2f;
 
+// 128 x 64 tile: for products whose output is 64 wide (one head) or just past a multiple of 128
+using TileTall = Tile<128, 64, 4, 2, 1, true>;
+// an output width just past a multiple of 128 (K F + 2 K = 264) leaves the last 128-wide column tile
+// almost empty: 64-wide column tiles then waste 21 % of the matrix-core work instead of 45 %
+inline bool narrow_tail(int n_out) { return n_out > 128 && n_out % 128 > 0 && n_out % 128 <= 64; }
+
 // Per-layer sizes.  A wave owns one row; its 64 lanes are dealt to the heads in groups of
 // lph = 64 / (K rounded up to a power of two) lanes, lane `sub` of head k holding features
 // (sub + lph t) VW + 0..VW-1, t < NV, of that head.
@@ -58,7 +64,7 @@ struct EpiStore {
 // C = A B (B_KC = false: b is K x N) or C = A B^T (B_KC = true: b is N x K) for the rows of one
 // level; persistent row-block tiling
 template <class T, int VA, int VB, bool B_KC>
-__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6 : 2, T::LEAN ? 6 : 8)))
+__global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 2 * T::OCC : 2, T::LEAN ? 2 * T::OCC : 8)))
 void k_gat_rows_gemm(MatRows a, MatRows b, EpiStore epi, const GsLevelMeta *__restrict__ meta_rows, int S) {
     const int n1 = meta_rows->front_off[S];
     const int n_out = B_KC ? b.rows : b.cols;
@@ -433,7 +439,6 @@ struct MatLd {
     __device__ __forceinline__ int tok(int i) const { return min(i, cols - 4); }
     __device__ __forceinline__ const float *km(int k, int t) const { return p + (int64_t)k * ld + t; }
 };
-using TileTall = Tile<128, 64, 4, 2, 1, true>;
 
 struct EpiHeadElu {      // hidden[i, off + n] = ELU(v + bias[off + n])
     float *out; const float *bias; int ld; int rows; int cols; int off;
@@ -1111,8 +1116,9 @@ void launch_rows_gemm(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool va, cons
     const int n_out = B_KC ? b.rows : b.cols;
     if (!va) launch_rows_gemm_t<TileMid, 1, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
     else if (!few_rows(ub, n_out, a.cols)) {
+        if (narrow_tail(n_out)) launch_rows_gemm_t<TileTall, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
         // both operands k-contiguous: the unpadded direct-to-LDS tile (three workgroups a compute unit)
-        if (B_KC) launch_rows_gemm_t<TileMidDirect, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
+        else if (B_KC) launch_rows_gemm_t<TileMidDirect, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
         else launch_rows_gemm_t<TileMidLean, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
     }
     else if (n_out <= 64) launch_rows_gemm_t<TileLowNarrow, 4, B_KC>(ctx, st, ub, n_out, a, b, epi, meta_rows);
@@ -1352,6 +1358,7 @@ extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
             MatRows dz{gb.dzext[l], 0, d.ZW};
             EpiGradW ew{gb.gw_part[l], D + 1, d.ZW, D};
             GsTimeScope ts(ctx, "gat_grad_w", l, st);
+            // (the 128 x 64 tile is no faster here: the split-K chunks are short and the slabs dominate)
             launch_grad_w(st, gb.nchunk[l], D % 4 == 0 && aligned16(hin), true, in, dz, ew, ctx->d_meta + l, S);
         }
         if (l > 0) {

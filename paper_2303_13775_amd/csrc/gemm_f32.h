@@ -46,7 +46,9 @@ struct Tile {
     static constexpr bool LEAN = LEAN_;
     static constexpr int MI = BM / (32 * WM), NI = BN / (32 * WN);
     static constexpr int NO = BK / 8 / KS;      // groups of 8 k per k-tile and wave
-    static constexpr int OCC = (BM * BN >= 8192 && !LEAN) ? 2 : 3;   // workgroups one compute unit holds
+    // workgroups one compute unit holds (registers for the full schedule, LDS for a padded lean tile
+    // of 128 rows: two stages of 128 x 36 + 32 x 68 words are 54 KiB)
+    static constexpr int OCC = (BM * BN >= 8192 && !LEAN) ? 2 : (LEAN && !DIRECT && BM >= 128) ? 2 : 3;
     static_assert(WM * WN * KS * 64 == GNT, "a workgroup has 8 waves");
     static_assert(MI >= 1 && NI >= 1 && MI * 32 * WM == BM && NI * 32 * WN == BN, "32 x 32 MFMA blocks");
     static_assert(KS == 1 || KS == 2 || KS == 4, "k split");
@@ -575,19 +577,19 @@ unsigned row_block_grid(const gsplit_ctx *ctx, int64_t ub, int n_out) {
     return (unsigned)std::min<int64_t>(want, (int64_t)ctx->n_cu * T::OCC / 8 * 8);
 }
 // vin / vdz: rows of the layer input / of dZ can be read in 16-byte pieces
-template <int VA, int VB>
+template <class T, int VA, int VB>
 void launch_grad_w_t(hipStream_t st, int nchunk, const MatRows &in, const MatRows &dz, const EpiGradW &ew,
                      const GsLevelMeta *mu, int S) {
-    using T = TileMidLean;
     const int tm = (int)gs_ceil_div(ew.own_rows, T::BM), tn = (int)gs_ceil_div(ew.N, T::BN);
     hipLaunchKernelGGL((k_sage_grad_w<T, VA, VB>), dim3((unsigned)(nchunk * tm * tn)), dim3(GNT), 0, st, in, dz,
                        ew, nchunk, GRAD_W_ROWS_MIN, tm, tn, mu, S);
 }
+template <class T = TileMidLean>
 void launch_grad_w(hipStream_t st, int nchunk, bool vin, bool vdz, const MatRows &in, const MatRows &dz,
                    const EpiGradW &ew, const GsLevelMeta *mu, int S) {
-    if (vin && vdz) launch_grad_w_t<4, 4>(st, nchunk, in, dz, ew, mu, S);
-    else if (vin) launch_grad_w_t<4, 1>(st, nchunk, in, dz, ew, mu, S);
-    else if (vdz) launch_grad_w_t<1, 4>(st, nchunk, in, dz, ew, mu, S);
-    else launch_grad_w_t<1, 1>(st, nchunk, in, dz, ew, mu, S);
+    if (vin && vdz) launch_grad_w_t<T, 4, 4>(st, nchunk, in, dz, ew, mu, S);
+    else if (vin) launch_grad_w_t<T, 4, 1>(st, nchunk, in, dz, ew, mu, S);
+    else if (vdz) launch_grad_w_t<T, 1, 4>(st, nchunk, in, dz, ew, mu, S);
+    else launch_grad_w_t<T, 1, 1>(st, nchunk, in, dz, ew, mu, S);
 }
 
