@@ -131,8 +131,8 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     A((void **)&ctx->ent_local, sizeof(int32_t) * max_items, "ent_local");
     A((void **)&ctx->mixed_ent, sizeof(int32_t) * max_items, "mixed_ent");
     A((void **)&ctx->cls, sizeof(uint32_t) * max_items, "class masks");
-    A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 17, "partition histogram");
-    A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 17, "partition bases");
+    A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 25, "partition histogram");
+    A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 25, "partition bases");
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
     if (rc == GSPLIT_OK && hipEventCreateWithFlags(&ctx->sample_done, hipEventDisableTiming) != hipSuccess)

@@ -4,18 +4,26 @@
 // device memory (GsLevelMeta), so one iteration is enqueued without any host synchronisation and
 // the launch shapes depend only on the context's upper bounds.
 //
-// Per sampling layer (8 launches):
-//   1 sample_layer            + insert (vertex, split) keys of destinations and slots into tab_mixed
-//   2 partition A: count      + reset tab_local
-//   3 partition A: scan         (mixed-frontier offsets, bucket offsets, edge count)
-//   4 partition A: scatter      mixed frontiers, block CSR offsets, owner buckets = received ids,
-//                             + insert destinations and received ids into tab_local
-//   5 partition B: count      + edges[l] relabelled to mixed-frontier rows
-//   6 partition B: scan         (next local-frontier offsets)
-//   7 partition B: scatter      next local frontiers + reset tab_mixed for the next layer
-//   8 shuffle index (+ its composition with edges[l] for the forward/backward passes)
-//   9-10 (layers above the bottom one) the scatter side of the shuffle index: for every row of
-//        local_cat[l], the destination rows it feeds, so that the backward pass can pull
+// Per sampling layer (4 launches):
+//   1 sample_layer       + insert (vertex, split) keys of destinations and slots into tab_mixed
+//                        and vertex keys into tab_local
+//   2 partition: count     one multi-class pass over the slots: per split its mixed frontier, per
+//   3 partition: scatter   owner its bucket (= received ids) and its new local-frontier members,
+//                          and the edge numbers; + block CSR offsets, destination vertices at the
+//                          head of both frontiers, reset of both tables for the next layer
+//   4 shuffle index (+ its composition with edges[l] for the forward/backward passes, + edges[l]
+//                          relabelled to mixed-frontier rows)
+// and, once after the last layer, two launches for the scatter side of the shuffle index of all
+// layers that have one (for every row of local_cat[l], the destination rows it feeds, so that the
+// backward pass can pull).
+//
+// Why one partition pass serves both frontiers: the rows of a level are ordered by split, so the
+// slot stream in (row, slot) order is the concatenation of the splits' slot streams, and the ids an
+// owner t receives, `for s: bucket[s -> t]`, are the per-split first occurrences owned by t in
+// exactly that global order.  The first occurrence of a vertex among the received ids of its owner
+// is therefore its first occurrence in the whole slot stream (which is always a per-split first
+// occurrence too): a second table keyed by the vertex alone, filled by the sampler with the
+// global slot positions, tells it without a pass over the received ids.
 // A dependent HBM access costs about a microsecond, and these kernels are chains of them, so every
 // element remembers the table entry it landed in (no second probe sequence) and the count passes
 // leave their classification behind for the scatter passes.
@@ -26,7 +34,7 @@
 namespace {
 
 constexpr int PART_BS = 256;     // threads of a partition workgroup
-constexpr int PART_NK = 17;     // classes of a partition pass: 8 senders + 8 owners + 1 counter
+constexpr int PART_NK = 25;     // classes of a partition pass: 8 senders + 8 owners + 1 edge counter + 8 owners (new local)
 constexpr int PART_MAX_NB = 1024;
 constexpr unsigned long long EMPTY_ENTRY = ~0ull;
 
@@ -105,8 +113,9 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 // The random word of draw q is word (q mod 4) of Philox(counter = (v, iter lo, iter hi,
 // layer * 65536 + q / 4), key = (seed lo, seed hi)): a function of the global vertex id only.
 // Every destination vertex (position i) and every sampled slot (position n1 + slot index) is
-// also entered into the mixed-frontier table under the key (vertex, split of the row); the entry
-// index is kept in ent_mixed (destinations first, then slots; -1 for padding slots).
+// also entered into the mixed-frontier table under the key (vertex, split of the row) and into the
+// local-frontier table under the key vertex; the entry indices are kept in ent_mixed / ent_local
+// (destinations first, then slots; -1 for padding slots).
 // ------------------------------------------------------------------------------------------
 template <int G, typename IndPtrT>
 __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
@@ -116,8 +125,9 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                                                       const GsLevelMeta *__restrict__ meta_up, int S,
                                                       int fan, uint32_t layer, uint64_t seed,
                                                       uint64_t iter, const uint64_t *__restrict__ seed_iter,
-                                                      GsTable tab,
+                                                      GsTable tab, GsTable tab_local,
                                                       int32_t *__restrict__ ent_mixed,
+                                                      int32_t *__restrict__ ent_local,
                                                       int32_t *__restrict__ nbr,
                                                       int32_t *__restrict__ cnt,
                                                       int64_t *__restrict__ epos) {
@@ -179,10 +189,15 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
                 ent_mixed[row] = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
                                               &meta_lo->error);
+                ent_local[row] = table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row, &meta_lo->error);
             }
-            ent_mixed[n1 + g] = val < 0 ? -1
-                                        : table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp,
-                                                       (uint32_t)(n1 + g), &meta_lo->error);
+            int hm = -1, hl = -1;
+            if (val >= 0) {
+                hm = table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp, (uint32_t)(n1 + g), &meta_lo->error);
+                hl = table_insert(tab_local, bits, (uint32_t)val, (uint32_t)(n1 + g), &meta_lo->error);
+            }
+            ent_mixed[n1 + g] = hm;
+            ent_local[n1 + g] = hl;
         }
     }
 }
@@ -208,8 +223,9 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
 // Elements keep their order inside every class (wave ballots + running chunk counters).
 // ------------------------------------------------------------------------------------------
 struct PartOffs {
-    int a[GS_MAXS + 1];     // first offset array of the pass (front_off or mixed_off)
-    int b[GS_MAXS + 1];     // second one (recv_off)
+    int a[GS_MAXS + 1];     // first offset array of the pass (front_off of the targets, or mixed_off)
+    int b[GS_MAXS + 1];     // recv_off
+    int c[GS_MAXS + 1];     // front_off of the level below
     int total;              // class-16 total (edges)
 };
 
@@ -344,7 +360,7 @@ struct PartTargets {
     static constexpr int NK = GS_MAXS;
     const int32_t *targets; int n_targets; const uint8_t *pmap; int S; uint32_t n_vertices;
     int32_t *front; int32_t *perm; GsLevelMeta *meta; GsTable tab_mixed; int fan_top;
-    GsLevelMeta *meta_all; int n_levels;
+    GsLevelMeta *meta_all; int n_levels; GsTable tab_local;
     __device__ int n() const { return n_targets; }
     // an id outside the graph is replaced by vertex 0 and reported through the error flag (by the
     // scatter pass only: the count pass is where the flags of the previous batch are cleared)
@@ -377,42 +393,52 @@ struct PartTargets {
         front[rk[k]] = target(g);
         perm[rk[k]] = g;
     }
-    __device__ int64_t n_extra(const PartOffs &) const { return 1ll << table_bits(n_targets * (1 + fan_top)); }
-    __device__ void extra(int64_t x, const PartOffs &) const { tab_mixed.slot[x] = EMPTY_ENTRY; }
+    // both tables are cleared for the top sampling layer
+    __device__ int64_t n_extra(const PartOffs &) const { return 2ll << table_bits(n_targets * (1 + fan_top)); }
+    __device__ void extra(int64_t x, const PartOffs &) const {
+        const int64_t cap = 1ll << table_bits(n_targets * (1 + fan_top));
+        if (x < cap) tab_mixed.slot[x] = EMPTY_ENTRY;
+        else tab_local.slot[x - cap] = EMPTY_ENTRY;
+    }
     // the count pass is the first kernel of a batch: it clears the error flags of every level
     __device__ int64_t n_side() const { return n_levels; }
     __device__ void side(int64_t x) const { meta_all[x].error = 0; }
 };
 
-// ---- partition A: mixed frontiers, block CSR offsets and owner buckets in one pass over the
-// slots.  A slot that is the first occurrence of its vertex inside its split s ("winner") gets
-//   class s      -> its row in mixed_front_s (destination vertices occupy the rows before)
-//   class 8 + t  -> its place in bucket[s -> t], t = f_G(vertex): partitioning the sender-ordered
-//                   slot stream by owner yields, for each receiver t, bucket[0->t] | bucket[1->t]
-//                   | ...: on one GPU the send buffers and the received concatenation are the
-//                   same memory.
+// ---- the partition of a sampling layer: mixed frontiers, block CSR offsets, owner buckets and
+// next local frontiers in one pass over the slots.  A slot that is the first occurrence of its
+// vertex inside its split s ("winner") gets
+//   class s       -> its row in mixed_front_s (destination vertices occupy the rows before)
+//   class 8 + t   -> its place in bucket[s -> t], t = f_G(vertex): partitioning the sender-ordered
+//                    slot stream by owner yields, for each receiver t, bucket[0->t] | bucket[1->t]
+//                    | ...: on one GPU the send buffers and the received concatenation are the
+//                    same memory.
 // Class 16 counts valid slots: its exclusive rank is the edge number (block CSR offsets).
-// Received ids and destination vertices are entered into the local-frontier table on the fly.
-struct PartMixedBuckets {
+// A slot that is the first occurrence of its vertex in the whole stream (and whose vertex is not a
+// destination vertex, which the table decides: destinations hold the smallest positions) gets
+//   class 17 + t  -> its row in local_front[l]_t (the owner's own destination vertices come first).
+struct PartLayer {
     static constexpr int NK = PART_NK;
     GsTable tab_mixed, tab_local;
     const int32_t *front; const int32_t *nbr; const uint8_t *pmap;
-    const int32_t *ent_mixed; uint32_t *cls; int32_t *ent_local; int32_t *mixed_ent;
-    int32_t *mixed; int32_t *blk_indptr; int32_t *recv;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan;
+    const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls; int32_t *mixed_ent;
+    int32_t *mixed; int32_t *blk_indptr; int32_t *recv; int32_t *front_lo; int32_t *rev_cnt;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next; int rev;
     __device__ int n1() const { return meta_up->front_off[S]; }
-    __device__ int bits() const { return table_bits(n1() * (1 + fan)); }
     __device__ int n() const { return n1() * fan; }
     __device__ unsigned classify(int g) const {
         const int h = ent_mixed[n1() + g];
         unsigned m = 0u;
         if (h >= 0) {
             const int32_t id = nbr[g];
-            const bool first = (uint32_t)tab_mixed.slot[h] == (uint32_t)(n1() + g);
+            const uint32_t pos = (uint32_t)(n1() + g);
             m = 1u << 16;
-            if (first) {
+            if ((uint32_t)tab_mixed.slot[h] == pos) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
-                m |= (1u << s) | (1u << (8 + (pmap[id] & (GS_MAXS - 1))));
+                const unsigned t = pmap[id] & (GS_MAXS - 1);
+                m |= (1u << s) | (1u << (8 + t));
+                const int hl = ent_local[n1() + g];
+                if (hl >= 0 && (uint32_t)tab_local.slot[hl] == pos) m |= 1u << (17 + t);
             }
         }
         cls[g] = m;
@@ -420,23 +446,29 @@ struct PartMixedBuckets {
     }
     __device__ unsigned cached(int g) const { return cls[g]; }
     __device__ int upper_offset(int s) const { return meta_up->front_off[s]; }
-    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *up) const {     // o.a = mixed_off, o.b = recv_off
-        int acc = 0, racc = 0;
+    // o.a = mixed_off, o.b = recv_off, o.c = front_off of the level below
+    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *up) const {
+        int acc = 0, racc = 0, lacc = 0;
         for (int s = 0; s < GS_MAXS; ++s) {
             const int n_dst = (s < S) ? up[s + 1] - up[s] : 0;
-            o.a[s] = acc; o.b[s] = racc;
+            o.a[s] = acc; o.b[s] = racc; o.c[s] = lacc;
             bases[s] = acc + n_dst;
             bases[8 + s] = racc;
+            bases[17 + s] = lacc + n_dst;
             acc += n_dst + ((s < S) ? tot[s] : 0);
             racc += (s < S) ? tot[8 + s] : 0;
+            lacc += n_dst + ((s < S) ? tot[17 + s] : 0);
         }
         o.a[S] = acc;
         o.b[S] = racc;
+        o.c[S] = lacc;
         bases[16] = 0;
         o.total = tot[16];
     }
     __device__ void publish(const PartOffs &o) const {
-        for (int s = 0; s <= S; ++s) { meta_lo->mixed_off[s] = o.a[s]; meta_lo->recv_off[s] = o.b[s]; }
+        for (int s = 0; s <= S; ++s) {
+            meta_lo->mixed_off[s] = o.a[s]; meta_lo->recv_off[s] = o.b[s]; meta_lo->front_off[s] = o.c[s];
+        }
         meta_lo->nnz = o.total;
         blk_indptr[n1()] = o.total;
     }
@@ -457,117 +489,60 @@ struct PartMixedBuckets {
         const int t = __ffs((m >> 8) & 0xFFu) - 1;
         const int32_t id = nbr[g];
         const int h = ent_mixed[n1() + g];
-        const int r = rk[8 + t];
+        const int hl = ent_local[n1() + g];
         mixed[rk[s]] = id;
         tab_mixed.row[h] = rk[s] - o.a[s];
-        recv[r] = id;
-        const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)(n1() + r), &meta_lo->error);
-        ent_local[n1() + r] = hl;
         mixed_ent[rk[s]] = hl;
-    }
-    // destination vertices are rows 0 .. n_dst-1 of their split's mixed frontier and come first
-    // in their owner's next local frontier
-    __device__ int64_t n_extra(const PartOffs &) const { return n1(); }
-    __device__ void extra(int64_t x, const PartOffs &o) const {
-        const int i = (int)x;
-        const int s = split_of(meta_up->front_off, S, i);
-        const int loc = i - meta_up->front_off[s];
-        const int32_t id = front[i];
-        const int h = ent_mixed[i];
-        const int j = o.a[s] + loc;
-        mixed[j] = id;
-        if (h >= 0) tab_mixed.row[h] = loc;
-        const int hl = table_insert(tab_local, bits(), (uint32_t)id, (uint32_t)i, &meta_lo->error);
-        ent_local[i] = hl;
-        mixed_ent[j] = hl;
-    }
-    // the count pass also clears the local-frontier table (idle until the scatter pass)
-    __device__ int64_t n_side() const { return 1ll << bits(); }
-    __device__ void side(int64_t x) const { tab_local.slot[x] = EMPTY_ENTRY; }
-};
-
-// ---- partition B: next local frontiers = own destination vertices, then first occurrences of
-// what arrived (receiver t's ids are contiguous in recv, senders in order) ---------------------
-struct PartLocal {
-    static constexpr int NK = GS_MAXS;
-    GsTable tab_local, tab_mixed;
-    const int32_t *front_up; const int32_t *recv; int32_t *front_lo;
-    const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls;
-    const int32_t *blk_indptr; int32_t *blk_src; int32_t *rev_cnt;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next; int rev;
-    __device__ int n1() const { return meta_up->front_off[S]; }
-    __device__ int n() const { return meta_lo->recv_off[S]; }
-    __device__ unsigned classify(int r) const {
-        const int h = ent_local[n1() + r];
-        unsigned m = 0u;
-        if (h >= 0 && (uint32_t)tab_local.slot[h] == (uint32_t)(n1() + r))
-            m = 1u << split_of(meta_lo->recv_off, S, r);
-        cls[r] = m;
-        return m;
-    }
-    __device__ unsigned cached(int r) const { return cls[r]; }
-    __device__ int upper_offset(int t) const { return meta_up->front_off[t]; }
-    __device__ void key_bases(const int *tot, int *bases, PartOffs &o, const int *up) const {     // o.a = front_off of the level below
-        int acc = 0;
-        for (int t = 0; t < GS_MAXS; ++t) {
-            const int n_up = (t < S) ? up[t + 1] - up[t] : 0;
-            o.a[t] = acc;
-            bases[t] = acc + n_up;
-            acc += n_up + ((t < S) ? tot[t] : 0);
+        recv[rk[8 + t]] = id;
+        if ((m >> 17) & 0xFFu) {       // implies hl >= 0
+            front_lo[rk[17 + t]] = id;
+            tab_local.row[hl] = rk[17 + t];
         }
-        o.a[S] = acc;
     }
-    __device__ void publish(const PartOffs &o) const {
-        for (int t = 0; t <= S; ++t) meta_lo->front_off[t] = o.a[t];
-    }
-    __device__ void emit(int r, unsigned m, const int *rk, const PartOffs &) const {
-        if (!m) return;
-        const int t = __ffs(m) - 1;
-        front_lo[rk[t]] = recv[r];
-        tab_local.row[ent_local[n1() + r]] = rk[t];
-    }
-    // scatter pass extras: destination vertices keep their order at the head of their owner's
-    // frontier; then (layers above the bottom one) the mixed-frontier table is cleared for the
-    // next sampling layer and (layers that have one) the counters of this layer's reverse index
-    // are zeroed
+    // scatter pass extras: destination vertices are rows 0 .. n_dst-1 of their split's mixed
+    // frontier and of their owner's next local frontier; then (layers above the bottom one) both
+    // tables are cleared for the next sampling layer and (layers that have one) the counters of
+    // this layer's reverse index are zeroed
     __device__ int64_t n_reset(const PartOffs &o) const {
-        return fan_next > 0 ? (1ll << table_bits(o.a[S] * (1 + fan_next))) : 0;
+        return fan_next > 0 ? (1ll << table_bits(o.c[S] * (1 + fan_next))) : 0;
     }
     __device__ int64_t n_extra(const PartOffs &o) const {
-        return n1() + n_reset(o) + (rev ? o.a[S] : 0);
+        return n1() + 2 * n_reset(o) + (rev ? o.c[S] : 0);
     }
     __device__ void extra(int64_t x, const PartOffs &o) const {
         if (x >= n1()) {
             const int64_t y = x - n1(), nr = n_reset(o);
             if (y < nr) tab_mixed.slot[y] = EMPTY_ENTRY;
-            else rev_cnt[y - nr] = 0;
+            else if (y < 2 * nr) tab_local.slot[y - nr] = EMPTY_ENTRY;
+            else rev_cnt[y - 2 * nr] = 0;
             if (y == 0) meta_lo->rev_cursor = 0;
             return;
         }
         const int i = (int)x;
-        const int t = split_of(meta_up->front_off, S, i);
-        const int rowp = o.a[t] + (i - meta_up->front_off[t]);
-        front_lo[rowp] = front_up[i];
-        const int h = ent_local[i];
-        if (h >= 0) tab_local.row[h] = rowp;
+        const int s = split_of(meta_up->front_off, S, i);
+        const int loc = i - meta_up->front_off[s];
+        const int32_t id = front[i];
+        const int h = ent_mixed[i], hl = ent_local[i];
+        const int j = o.a[s] + loc, rowp = o.c[s] + loc;
+        mixed[j] = id;
+        if (h >= 0) tab_mixed.row[h] = loc;
+        mixed_ent[j] = hl;
+        front_lo[rowp] = id;
+        if (hl >= 0) tab_local.row[hl] = rowp;
     }
-    // count pass extras: edges[l] rewritten to rows of the owning split's mixed frontier
-    __device__ int64_t n_side() const { return (int64_t)n1() * fan; }
-    __device__ void side(int64_t g) const {
-        const int h = ent_mixed[n1() + g];
-        if (h < 0) return;
-        const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
-        blk_src[blk_indptr[i] + q] = tab_mixed.row[h];
-    }
+    __device__ int64_t n_side() const { return 0; }
+    __device__ void side(int64_t) const {}
 };
 
-// shuffle index of every mixed-frontier row, and the same lookup composed with edges[l] for the
-// on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge)
+// shuffle index of every mixed-frontier row, the same lookup composed with edges[l] for the
+// on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge), and edges[l]
+// itself relabelled to rows of the owning split's mixed frontier
 __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTable tab_mixed,
                                                        const int32_t *__restrict__ ent_mixed,
                                                        const int32_t *__restrict__ ent_local,
                                                        const int32_t *__restrict__ mixed_ent,
                                                        const int32_t *__restrict__ blk_indptr,
+                                                       int32_t *__restrict__ blk_src,
                                                        int32_t *__restrict__ src_row,
                                                        int32_t *__restrict__ self_row,
                                                        int32_t *__restrict__ edge_row,
@@ -596,8 +571,10 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
             if (h < 0) continue;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
             const int s = split_of(meta_up->front_off, S, i);
-            const int hl = mixed_ent[meta_lo->mixed_off[s] + tab_mixed.row[h]];
+            const int mrow = tab_mixed.row[h];
+            const int hl = mixed_ent[meta_lo->mixed_off[s] + mrow];
             const int r = hl >= 0 ? tab_local.row[hl] : -1;
+            blk_src[blk_indptr[i] + q] = mrow;          // edges[l] as rows of the split's mixed frontier
             edge_row[blk_indptr[i] + q] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
         }
@@ -730,15 +707,15 @@ void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, const u
     if (fan <= 16) {
         hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
     } else if (fan <= 32) {
         hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
     } else {
         hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
                            ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->ent_mixed, B.nbr, B.cnt, B.epos);
+                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
     }
 }
 
@@ -767,7 +744,7 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
 
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
                    ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1],
-                   ctx->d_meta, L + 1};
+                   ctx->d_meta, L + 1, ctx->tab_local};
     run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
 
     for (int l = L - 1; l >= 0; --l) {
@@ -780,19 +757,16 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, d_seed_iter, st);
         else launch_sample<int32_t>(ctx, l, seed, iter, d_seed_iter, st);
 
-        PartMixedBuckets pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
-                            ctx->ent_mixed, ctx->cls, ctx->ent_local, ctx->mixed_ent,
-                            B.mixed, B.blk_indptr, B.recv, ml, mu, S, fan};
-        run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
-        PartLocal pl{ctx->tab_local, ctx->tab_mixed, ctx->front[l + 1], B.recv, ctx->front[l],
-                     ctx->ent_mixed, ctx->ent_local, ctx->cls, B.blk_indptr, B.blk_src, B.rev_cnt,
+        PartLayer pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
+                     ctx->ent_mixed, ctx->ent_local, ctx->cls, ctx->mixed_ent,
+                     B.mixed, B.blk_indptr, B.recv, ctx->front[l], B.rev_cnt,
                      ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l >= ctx->rev_from ? 1 : 0};
-        run_partition(ctx, pl, ub1 * fan, st, "local_front", l);
+        run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
         {
         GsTimeScope ts(ctx, "shuffle_index", l, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
-                           B.blk_indptr, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
+                           B.blk_indptr, B.blk_src, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
                            ml, mu, S, fan);
         }
     }
