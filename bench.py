@@ -44,6 +44,8 @@ def parse():
                     help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
                          "overlaps forward/backward of step i on a second stream)")
     ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
+    ap.add_argument("--sampler-blocks", type=int, default=2,
+                    help="pipelined schedule: workgroups per compute unit the sampling kernels may occupy")
     ap.add_argument("--graph", action="store_true",
                     help="replay the timed steps as captured HIP graphs instead of enqueueing every kernel from the "
                          "host (measured: no faster here, the steps are bound by the device-side kernel boundaries, "
@@ -182,13 +184,13 @@ class Pipelined:
     stay strictly ordered, as synchronous training requires).  Every step still does all of its
     work; nothing is cached or skipped.  Events order the hand-over of a slot in both directions."""
 
-    def __init__(self, w, dev, n_ahead=2, model="sage", heads=4):
+    def __init__(self, w, dev, n_ahead=2, model="sage", heads=4, sampler_blocks=2):
         import torch
         self.torch = torch
         self.n = n_ahead + 1
         # sampling kernels are latency-bound: two workgroups per compute unit instead of eight cost them
         # about 1 % and leave wave slots for the training stream's workgroups (medium: +5 % throughput)
-        self.slots = [Runner(w, dev, model, heads, sampler_blocks_per_cu=2) for _ in range(self.n)]
+        self.slots = [Runner(w, dev, model, heads, sampler_blocks_per_cu=sampler_blocks) for _ in range(self.n)]
         self.s_sample = [torch.cuda.Stream(device=dev) for _ in range(n_ahead)]
         self.s_train = torch.cuda.Stream(device=dev)
         self.ready = [torch.cuda.Event() for _ in range(self.n)]
@@ -584,7 +586,7 @@ def main():
     dt_serial = time.perf_counter() - t0
     dt = dt_serial
     if not a.no_pipeline:
-        pipe = Pipelined(w, dev, a.ahead, a.model, a.heads)
+        pipe = Pipelined(w, dev, a.ahead, a.model, a.heads, a.sampler_blocks)
         if cache_info:
             for slot in pipe.slots:
                 slot.enable_cache(cache_info["host_table"], cache_info["ids"], cache_info["n_cache"])
