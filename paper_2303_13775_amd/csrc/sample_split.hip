@@ -10,9 +10,13 @@
 //   2 partition: count     one multi-class pass over the slots: per split its mixed frontier, per
 //   3 partition: scatter   owner its bucket (= received ids) and its new local-frontier members,
 //                          and the edge numbers; + block CSR offsets, destination vertices at the
-//                          head of both frontiers, reset of both tables for the next layer
+//                          head of both frontiers
 //   4 shuffle index (+ its composition with edges[l] for the forward/backward passes, + edges[l]
-//                          relabelled to mixed-frontier rows)
+//                          relabelled to mixed-frontier rows, + reset of both tables for the next
+//                          layer)
+// (One workgroup doing count and scatter of a small partition in a single launch was tried for the
+// targets and the top layer: its chains of dependent accesses have nobody to overlap with, 85 us
+// against 21 us for 5120 slots.)
 // and, once after the last layer, two launches for the scatter side of the shuffle index of all
 // layers that have one (for every row of local_cat[l], the destination rows it feeds, so that the
 // backward pass can pull).
@@ -423,7 +427,7 @@ struct PartLayer {
     const int32_t *front; const int32_t *nbr; const uint8_t *pmap;
     const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls; int32_t *mixed_ent;
     int32_t *mixed; int32_t *blk_indptr; int32_t *recv; int32_t *front_lo; int32_t *rev_cnt;
-    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int fan_next; int rev;
+    GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int rev;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return n1() * fan; }
     __device__ unsigned classify(int g) const {
@@ -500,22 +504,13 @@ struct PartLayer {
         }
     }
     // scatter pass extras: destination vertices are rows 0 .. n_dst-1 of their split's mixed
-    // frontier and of their owner's next local frontier; then (layers above the bottom one) both
-    // tables are cleared for the next sampling layer and (layers that have one) the counters of
-    // this layer's reverse index are zeroed
-    __device__ int64_t n_reset(const PartOffs &o) const {
-        return fan_next > 0 ? (1ll << table_bits(o.c[S] * (1 + fan_next))) : 0;
-    }
-    __device__ int64_t n_extra(const PartOffs &o) const {
-        return n1() + 2 * n_reset(o) + (rev ? o.c[S] : 0);
-    }
+    // frontier and of their owner's next local frontier; then (layers that have one) the counters
+    // of this layer's reverse index are zeroed
+    __device__ int64_t n_extra(const PartOffs &o) const { return n1() + (rev ? o.c[S] : 0); }
     __device__ void extra(int64_t x, const PartOffs &o) const {
         if (x >= n1()) {
-            const int64_t y = x - n1(), nr = n_reset(o);
-            if (y < nr) tab_mixed.slot[y] = EMPTY_ENTRY;
-            else if (y < 2 * nr) tab_local.slot[y - nr] = EMPTY_ENTRY;
-            else rev_cnt[y - 2 * nr] = 0;
-            if (y == 0) meta_lo->rev_cursor = 0;
+            rev_cnt[x - n1()] = 0;
+            if (x == n1()) meta_lo->rev_cursor = 0;
             return;
         }
         const int i = (int)x;
@@ -536,7 +531,8 @@ struct PartLayer {
 
 // shuffle index of every mixed-frontier row, the same lookup composed with edges[l] for the
 // on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge), and edges[l]
-// itself relabelled to rows of the owning split's mixed frontier
+// itself relabelled to rows of the owning split's mixed frontier; + reset of both tables for the
+// next sampling layer
 __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTable tab_mixed,
                                                        const int32_t *__restrict__ ent_mixed,
                                                        const int32_t *__restrict__ ent_local,
@@ -549,7 +545,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
                                                        int32_t *__restrict__ rev_cnt,
                                                        const GsLevelMeta *__restrict__ meta_lo,
                                                        const GsLevelMeta *__restrict__ meta_up,
-                                                       int S, int fan) {
+                                                       int S, int fan, int fan_next) {
     const int n1 = meta_up->front_off[S];
     const int64_t n_mixed = meta_lo->mixed_off[S];
     const int64_t n_slots = (int64_t)n1 * fan;
@@ -577,6 +573,16 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
             blk_src[blk_indptr[i] + q] = mrow;          // edges[l] as rows of the split's mixed frontier
             edge_row[blk_indptr[i] + q] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
+        }
+    }
+    // layers above the bottom one: both tables are cleared for the next sampling layer (this kernel
+    // only reads their row arrays, through the entry indices the elements remembered)
+    if (fan_next > 0) {
+        const int64_t nr = 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next));
+        for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < 2 * nr;
+             x += (int64_t)gridDim.x * blockDim.x) {
+            if (x < nr) tab_mixed.slot[x] = EMPTY_ENTRY;
+            else tab_local.slot[x - nr] = EMPTY_ENTRY;
         }
     }
 }
@@ -760,14 +766,14 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         PartLayer pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
                      ctx->ent_mixed, ctx->ent_local, ctx->cls, ctx->mixed_ent,
                      B.mixed, B.blk_indptr, B.recv, ctx->front[l], B.rev_cnt,
-                     ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l >= ctx->rev_from ? 1 : 0};
+                     ml, mu, S, fan, l >= ctx->rev_from ? 1 : 0};
         run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
         {
         GsTimeScope ts(ctx, "shuffle_index", l, st);
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
                            B.blk_indptr, B.blk_src, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
-                           ml, mu, S, fan);
+                           ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0);
         }
     }
     if (ctx->rev_from < L) {
