@@ -297,7 +297,7 @@ GSPLIT_API int gsplit_batch_stats(gsplit_ctx *ctx, uint64_t *d_edges, uint64_t *
  * (n_cache: HOST [S]).  Cache row j holds a copy of table row d_cache_ids[j] in HBM.  EINVAL for
  * an id outside the graph, listed under a split that does not own it, or listed twice, and for a
  * table the device cannot read.  Synchronises with `stream` (a set-up call).  One cache per
- * context; building again replaces it (the old buffers are released with the context).
+ * context; building again replaces it (the old buffers are freed first, which waits for the device).
  *
  * gsplit_gather_features_cached: the loading step: d_out[r, :] = the cached copy if the vertex of
  * row r (local_cat[0][r]) is cached, else the row of `table`, read over the host link without a

@@ -25,6 +25,15 @@ int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what) {
     return GSPLIT_OK;
 }
 
+// Gives one of the context's buffers back (hipFree waits for the device, so no kernel still uses it).
+void gs_release(gsplit_ctx *ctx, void **p) {
+    if (!*p) return;
+    auto it = std::find(ctx->allocs.begin(), ctx->allocs.end(), *p);
+    if (it != ctx->allocs.end()) ctx->allocs.erase(it);
+    (void)hipFree(*p);
+    *p = nullptr;
+}
+
 static void free_all(gsplit_ctx *ctx) {
     for (auto &r : ctx->timer.pending) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t e : ctx->timer.pool) (void)hipEventDestroy(e);

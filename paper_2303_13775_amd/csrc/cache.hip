@@ -169,8 +169,10 @@ extern "C" int gsplit_cache_build(gsplit_ctx *ctx, const void *table, int32_t dt
         return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_cache_build: the table must be device memory or pinned host memory");
     GsFeatureCache &fc = ctx->cache;
     hipStream_t st = (hipStream_t)stream;
-    // a second call replaces the cache: the old buffers stay with the context until it is destroyed
+    // a second call replaces the cache
     fc.ready = false;
+    gs_release(ctx, (void **)&fc.slot_of);
+    gs_release(ctx, (void **)&fc.rows);
     int rc = gs_alloc(ctx, (void **)&fc.slot_of, sizeof(int32_t) * ctx->graph.n_vertices, "cache slot map");
     if (rc) return rc;
     rc = gs_alloc(ctx, (void **)&fc.rows, (size_t)std::max<int64_t>(n, 1) * row_bytes, "cache rows");

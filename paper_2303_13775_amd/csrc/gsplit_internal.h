@@ -174,6 +174,7 @@ struct gsplit_ctx {
 
 int gs_fail(gsplit_ctx *ctx, int code, const std::string &msg);
 int gs_alloc(gsplit_ctx *ctx, void **p, size_t bytes, const char *what);
+void gs_release(gsplit_ctx *ctx, void **p);
 
 #define GS_HIP(ctx, call)                                                                  \
     do {                                                                                   \
