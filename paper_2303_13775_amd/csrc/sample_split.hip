@@ -10,16 +10,17 @@
 //   2 partition: count     one multi-class pass over the slots: per split its mixed frontier, per
 //   3 partition: scatter   owner its bucket (= received ids) and its new local-frontier members,
 //                          and the edge numbers; + block CSR offsets, destination vertices at the
-//                          head of both frontiers
+//                          head of both frontiers; + the reverse index of the layer above
 //   4 shuffle index (+ its composition with edges[l] for the forward/backward passes, + edges[l]
 //                          relabelled to mixed-frontier rows, + reset of both tables for the next
 //                          layer)
 // (One workgroup doing count and scatter of a small partition in a single launch was tried for the
 // targets and the top layer: its chains of dependent accesses have nobody to overlap with, 85 us
 // against 21 us for 5120 slots.)
-// and, once after the last layer, two launches for the scatter side of the shuffle index of all
-// layers that have one (for every row of local_cat[l], the destination rows it feeds, so that the
-// backward pass can pull).
+// The scatter side of the shuffle index (for every row of local_cat[l], the destination rows it
+// feeds, so that the backward pass can pull) of layer l+1 rides on the two partition launches of
+// layer l; only a context that keeps one for the bottom layer pays two launches of its own, after
+// the layer loop.
 //
 // Why one partition pass serves both frontiers: the rows of a level are ordered by split, so the
 // slot stream in (row, slot) order is the concatenation of the splits' slot streams, and the ids an
@@ -223,7 +224,8 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
 //                                takes them from `o`)
 //   emit(g, mask, rk, o)         rk[k] = bases[k] + number of class-k elements before g
 //   n_extra(o), extra(g, o)      independent element-wise work appended to the scatter pass
-//   n_side(), side(g)            independent element-wise work appended to the count pass
+//   n_side(), side(g, n)         independent work appended to the count pass: called by whole
+//                                workgroups, 256 consecutive g at a time (g >= n in the last one)
 // Elements keep their order inside every class (wave ballots + running chunk counters).
 // ------------------------------------------------------------------------------------------
 struct PartOffs {
@@ -267,10 +269,10 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
     }
     __syncthreads();
     if (threadIdx.x < F::NK) hist[threadIdx.x * gridDim.x + blockIdx.x] = s_cnt[threadIdx.x];
+    // every thread of the workgroup makes every call (side may synchronise the workgroup)
     const int64_t ns = f.n_side();
-    for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < ns;
-         g += (int64_t)gridDim.x * PART_BS)
-        f.side(g);
+    for (int64_t base = blockIdx.x * (int64_t)PART_BS; base < ns; base += (int64_t)gridDim.x * PART_BS)
+        f.side(base + threadIdx.x, ns);
 }
 
 // gridDim.x = 256 * PER chunks
@@ -406,7 +408,66 @@ struct PartTargets {
     }
     // the count pass is the first kernel of a batch: it clears the error flags of every level
     __device__ int64_t n_side() const { return n_levels; }
-    __device__ void side(int64_t x) const { meta_all[x].error = 0; }
+    __device__ void side(int64_t x, int64_t ns) const {
+        if (x < ns) meta_all[x].error = 0;
+    }
+};
+
+// The scatter side of the shuffle index of the sampling layer above (layer l+1) is finished while
+// layer l is partitioned: its rows are this layer's destination vertices, and its counters are
+// complete once the shuffle-index kernel of layer l+1 has run.  The count pass hands every row a
+// segment of rev_list (segments need not be in row order: one atomic per workgroup of 256 rows
+// on the cursor, a single address), the scatter pass lists, for every source row, the destination
+// rows it feeds (slot q of destination i is a sampled edge when q < cnt[i]).
+struct RevUp {
+    int on;
+    const int32_t *rev_cnt; int32_t *rev_ptr; int32_t *rev_fill; int32_t *rev_list; int32_t *rev_eid;
+    const int32_t *cnt; const int32_t *blk_indptr; const int32_t *self_row; const int32_t *edge_row;
+    int fan; int32_t *cursor; const GsLevelMeta *meta_up2;
+    __device__ void alloc(int64_t x, int64_t n_rows, int S) const {
+        __shared__ int s_wave[PART_BS / 64];
+        __shared__ int s_base;
+        const int lane = lane_id(), wave = threadIdx.x >> 6;
+        const int c = x < n_rows ? rev_cnt[x] : 0;
+        int inc = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int below = __shfl_up(inc, o);
+            if (lane >= o) inc += below;
+        }
+        if (lane == 63) s_wave[wave] = inc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int tot = 0;
+            for (int w = 0; w < PART_BS / 64; ++w) { const int t = s_wave[w]; s_wave[w] = tot; tot += t; }
+            s_base = tot > 0 ? atomicAdd(cursor, tot) : 0;
+        }
+        __syncthreads();
+        if (x < n_rows) {
+            rev_ptr[x] = s_base + s_wave[wave] + inc - c;
+            rev_fill[x] = 0;
+        }
+        __syncthreads();
+    }
+    __device__ int64_t n_items(int S) const { return on ? (int64_t)meta_up2->front_off[S] * (1 + fan) : 0; }
+    __device__ void fill(int64_t x, int S) const {
+        const int n_dst = meta_up2->front_off[S];
+        int u, code, eid = -1;
+        if (x < n_dst) {
+            u = self_row[x];
+            code = 2 * (int)x;
+        } else {
+            const int64_t g = x - n_dst;
+            const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+            if (q >= cnt[i]) return;
+            eid = blk_indptr[i] + q;
+            u = edge_row[eid];
+            code = 2 * i + 1;
+        }
+        if (u < 0) return;
+        const int p = atomicAdd(&rev_fill[u], 1);
+        rev_list[rev_ptr[u] + p] = code;
+        if (rev_eid) rev_eid[rev_ptr[u] + p] = eid;
+    }
 };
 
 // ---- the partition of a sampling layer: mixed frontiers, block CSR offsets, owner buckets and
@@ -428,6 +489,7 @@ struct PartLayer {
     const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls; int32_t *mixed_ent;
     int32_t *mixed; int32_t *blk_indptr; int32_t *recv; int32_t *front_lo; int32_t *rev_cnt;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int rev;
+    RevUp up;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return n1() * fan; }
     __device__ unsigned classify(int g) const {
@@ -505,9 +567,14 @@ struct PartLayer {
     }
     // scatter pass extras: destination vertices are rows 0 .. n_dst-1 of their split's mixed
     // frontier and of their owner's next local frontier; then (layers that have one) the counters
-    // of this layer's reverse index are zeroed
-    __device__ int64_t n_extra(const PartOffs &o) const { return n1() + (rev ? o.c[S] : 0); }
+    // of this layer's reverse index are zeroed; then the reverse index of the layer above is filled
+    __device__ int64_t n_extra(const PartOffs &o) const { return n1() + (rev ? o.c[S] : 0) + up.n_items(S); }
     __device__ void extra(int64_t x, const PartOffs &o) const {
+        const int64_t own = n1() + (rev ? o.c[S] : 0);
+        if (x >= own) {
+            up.fill(x - own, S);
+            return;
+        }
         if (x >= n1()) {
             rev_cnt[x - n1()] = 0;
             if (x == n1()) meta_lo->rev_cursor = 0;
@@ -525,8 +592,9 @@ struct PartLayer {
         front_lo[rowp] = id;
         if (hl >= 0) tab_local.row[hl] = rowp;
     }
-    __device__ int64_t n_side() const { return 0; }
-    __device__ void side(int64_t) const {}
+    // count pass side work: segments of the reverse index of the layer above
+    __device__ int64_t n_side() const { return up.on ? n1() : 0; }
+    __device__ void side(int64_t x, int64_t ns) const { up.alloc(x, ns, S); }
 };
 
 // shuffle index of every mixed-frontier row, the same lookup composed with edges[l] for the
@@ -587,7 +655,8 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
     }
 }
 
-// reverse index of all layers that have one, two launches (blockIdx.y = layer - first)
+// reverse index as two launches of its own (blockIdx.y = layer - first): used for the bottom layer,
+// which has no partition below it; same steps as RevUp::alloc / RevUp::fill
 struct RevArgs {
     const int32_t *rev_cnt[GS_MAXL]; int32_t *rev_ptr[GS_MAXL]; int32_t *rev_fill[GS_MAXL];
     int32_t *rev_list[GS_MAXL]; int32_t *rev_eid[GS_MAXL];
@@ -766,7 +835,12 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         PartLayer pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
                      ctx->ent_mixed, ctx->ent_local, ctx->cls, ctx->mixed_ent,
                      B.mixed, B.blk_indptr, B.recv, ctx->front[l], B.rev_cnt,
-                     ml, mu, S, fan, l >= ctx->rev_from ? 1 : 0};
+                     ml, mu, S, fan, l >= ctx->rev_from ? 1 : 0, RevUp{}};
+        if (l + 1 < L && l + 1 >= ctx->rev_from) {
+            const GsLayerBuf &U = ctx->layer[l + 1];
+            pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
+                          U.self_row, U.edge_row, ctx->fan[l + 1], &ctx->d_meta[l + 1].rev_cursor, ctx->d_meta + (l + 2)};
+        }
         run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
         {
         GsTimeScope ts(ctx, "shuffle_index", l, st);
@@ -776,11 +850,12 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
                            ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0);
         }
     }
-    if (ctx->rev_from < L) {
+    // the bottom layer's reverse index (contexts that keep one) has no partition below it to ride on
+    if (ctx->rev_from == 0) {
         RevArgs ra{};
-        ra.first = ctx->rev_from;
+        ra.first = 0;
         int64_t rows = 1, items = 1;
-        for (int l = ctx->rev_from; l < L; ++l) {
+        for (int l = 0; l < 1; ++l) {
             const GsLayerBuf &B = ctx->layer[l];
             ra.rev_cnt[l] = B.rev_cnt; ra.rev_ptr[l] = B.rev_ptr; ra.rev_fill[l] = B.rev_fill; ra.rev_list[l] = B.rev_list;
             ra.rev_eid[l] = B.rev_eid; ra.cnt[l] = B.cnt; ra.blk_indptr[l] = B.blk_indptr; ra.self_row[l] = B.self_row;
@@ -788,7 +863,7 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
             rows = std::max<int64_t>(rows, ctx->ub_front[l]);
             items = std::max<int64_t>(items, ctx->ub_front[l + 1] * (1 + ctx->fan[l]));
         }
-        const unsigned ny = (unsigned)(L - ctx->rev_from);
+        const unsigned ny = 1;
         {
             GsTimeScope ts(ctx, "rev_alloc", -1, st);
             hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
