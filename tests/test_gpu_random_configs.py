@@ -75,3 +75,61 @@ def test_random_configuration(k):
         assert R.grad_err(r["gws"][l], r["ob"].gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("bf16 gw_self", l)
         assert R.grad_err(r["gwn"][l], r["ob"].gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("bf16 gw_neigh", l)
         assert R.grad_err(r["gb"][l], r["ob"].gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("bf16 gbias", l)
+
+
+@pytest.mark.parametrize("k", range(0, N_CONFIGS, 2))
+def test_random_configuration_counters_and_cache(k):
+    """The rows built on top of the path, on every other drawn configuration: pre-sampling counts
+    (section 4), split statistics (section 7.2), level-0 frequencies, and the loading step through
+    a cache of the most frequent third of every split's vertices (section 5)."""
+    from paper_2303_13775_amd import Context
+    dev = _dev()
+    w, _ = draw(k)
+    S, L = w.n_splits, w.n_layers
+    ip, ix, pm = w.indptr.numpy(), w.indices.numpy(), w.pmap.numpy()
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), S, w.fanouts, w.batch, keep_edge_ids=True)
+    k_v = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
+    k_e = torch.zeros(max(ix.size, 1), dtype=torch.int32, device=dev)[:ix.size]
+    k_in = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
+    edges = torch.zeros(L * S, dtype=torch.int64, device=dev)
+    cross = torch.zeros(L * S, dtype=torch.int64, device=dev)
+    its = [0, 1, 2]
+    batches = [w.targets(i) for i in its]
+    want_e = np.zeros((L, S), np.int64)
+    want_c = np.zeros((L, S), np.int64)
+    for i, tg in zip(its, batches):
+        ctx.gsplit_sample_split(tg.to(dev), 700 + k, i)
+        ctx.gsplit_presample_accumulate(k_v, k_e)
+        ctx.gsplit_input_counts_accumulate(k_in)
+        ctx.gsplit_batch_stats(edges, cross)
+        e, c = R.batch_stats(R.sp_sample(ip, ix, pm, S, w.fanouts, tg.numpy(), 700 + k, i), pm)
+        want_e += e
+        want_c += c
+    ov, oe = R.presample_counts(ip, ix, w.fanouts, [b.numpy() for b in batches], 700 + k, its)
+    assert np.array_equal(k_v.cpu().numpy().astype(np.int64), ov)
+    assert np.array_equal(k_e.cpu().numpy().astype(np.int64), oe)
+    freq = R.input_counts(ip, ix, w.fanouts, [b.numpy() for b in batches], 700 + k, its)
+    assert np.array_equal(k_in.cpu().numpy().astype(np.int64), freq)
+    assert np.array_equal(edges.cpu().numpy().reshape(L, S), want_e)
+    assert np.array_equal(cross.cpu().numpy().reshape(L, S), want_c)
+    # loading step through a cache
+    own = [int((pm == s).sum()) for s in range(S)]
+    sel = R.cache_select(freq, pm, S, [n // 3 for n in own])
+    table = w.feat
+    host = torch.empty(table.shape, dtype=table.dtype, pin_memory=True)
+    host.copy_(table)
+    ctx.gsplit_cache_build(host, torch.from_numpy(np.concatenate(sel).astype(np.int32)).to(dev),
+                           [x.shape[0] for x in sel])
+    tg = w.targets(5)
+    ctx.gsplit_sample_split(tg.to(dev), 700 + k, 5)
+    out = torch.full((ctx.gsplit_max_rows(0), table.shape[1]), float("nan"), device=dev)
+    hits = torch.zeros(S, dtype=torch.int64, device=dev)
+    misses = torch.zeros(S, dtype=torch.int64, device=dev)
+    ctx.gsplit_gather_features_cached(out, hits, misses)
+    ob = R.sp_sample(ip, ix, pm, S, w.fanouts, tg.numpy(), 700 + k, 5)
+    table_np = table.numpy().view(np.int32)
+    want, wh, wm = R.cached_gather(table_np, sel, [table_np[i] for i in sel], ob)
+    n = want.shape[0]
+    assert np.array_equal(out[:n].cpu().numpy().view(np.int32), want)
+    assert np.array_equal(hits.cpu().numpy(), wh) and np.array_equal(misses.cpu().numpy(), wm)
+    ctx.close()
