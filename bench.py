@@ -197,6 +197,14 @@ class Pipelined:
         self.free = [torch.cuda.Event() for _ in range(self.n)]
         for e in self.free:
             e.record()
+        # HIP binds a stream to one of its four hardware queues at first use, in order of first use,
+        # and which streams end up sharing a queue changes the throughput of this schedule by up to
+        # 20 % (measured: 2410 .. 3045 mini-batches/s over first-use orders).  Fix the order here
+        # instead of leaving it to the race between the two enqueueing threads.
+        for s in [self.s_train] + self.s_sample:
+            with torch.cuda.stream(s):
+                torch.zeros(1, device=dev)
+        torch.cuda.synchronize()
 
     def enable_graphs(self, targets_all):
         """Captures, per slot, a sampling graph and a training graph (after every slot has run eagerly
