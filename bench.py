@@ -675,9 +675,10 @@ def main():
             # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
             es = w.feat.element_size()
             add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
-            # per destination: id + two indptr words read, count written; per edge: 4 read, 4 written,
-            # one 8-byte table entry touched
-            add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes) + edges[l] * 16)
+            # per destination: id + two indptr words read, count written, and like every edge below an
+            # 8-byte entry in each of the two tables and the two 4-byte entry indices it remembers;
+            # per edge: 4 read, 4 written, 2 x 8 table bytes, 2 x 4 index bytes
+            add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes + 24) + edges[l] * 32)
             slots = nd * w.fanouts[l]
             add(f"mixed_buckets_count.l{l}", "bytes", slots * (4 + 4 + 8 + 4) + edges[l] * 1)
             add(f"mixed_buckets_scatter.l{l}", "bytes", slots * 4 + edges[l] * 4 + mixed[l] * (4 + 4 + 4 + 8 + 4))
