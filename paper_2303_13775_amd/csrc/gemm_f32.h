@@ -280,8 +280,15 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
 
     using SA = Stager<BM, A_KC, VA, GNT, AF, A_H, PAD>;
     using SB = Stager<BN, B_KC, VB, GNT, BF, false, PAD>;
-    SA sa0, sa1;
-    SB sb0, sb1;
+    // register stages of the full schedule.  A 32-row tile belongs to a product with few rows: the
+    // launch has about one workgroup per compute unit, nobody else hides its loads, and its k loop
+    // is a chain of global-load latencies (an iteration holds 0.2 us of MFMA work); four tiles in
+    // flight instead of two shorten every link of that chain.
+    constexpr int RS = (!T::LEAN && BM <= 32) ? 4 : 2;
+    SA sa[RS];
+    SB sb[RS];
+    SA &sa0 = sa[0];
+    SB &sb0 = sb[0];
 
     static_assert(!COLSUM || (!B_KC && KS == 1 && GNT % BN == 0 && BK % (GNT / BN) == 0), "column sums need a k-major B");
     constexpr int CS_KPG = COLSUM ? BK / (GNT / BN) : 1;    // k rows of a tile per thread
@@ -358,11 +365,11 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         if (VB == 4 && full) rb.template store<false>(Bs, tid);
         else rb.template store<true>(Bs, tid);
     };
-    // one k-tile: fetch tile k0 + 2 BK into the registers that held tile k0, multiply tile k0,
+    // one k-tile: fetch tile k0 + RS BK into the registers that held tile k0, multiply tile k0,
     // move tile k0 + BK from registers to the other LDS stage
     auto step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const float *As_cur, const float *Bs_cur,
                     float *As_nxt, float *Bs_nxt, int k0) {
-        if (k0 + 2 * BK < k_end) load_tile(ra_cur, rb_cur, k0 + 2 * BK);
+        if (k0 + RS * BK < k_end) load_tile(ra_cur, rb_cur, k0 + RS * BK);
         multiply(As_cur, Bs_cur);
         colsum_tile(Bs_cur);
         if (k0 + BK < k_end) store_tile(ra_nxt, rb_nxt, As_nxt, Bs_nxt, k0 + BK);
@@ -412,15 +419,45 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
             if (k0 + BK < k_end) lean_step(As1, Bs1, As0, Bs0, k0 + BK);
         }
     } else {
-    sa0.init(a, m0, tid); sa1.init(a, m0, tid);
-    sb0.init(b, n0, tid); sb1.init(b, n0, tid);
-    load_tile(sa0, sb0, k_begin);
-    if (k_begin + BK < k_end) load_tile(sa1, sb1, k_begin + BK);
-    store_tile(sa0, sb0, As0, Bs0, k_begin);
+#pragma unroll
+    for (int u = 0; u < RS; ++u) {
+        sa[u].init(a, m0, tid);
+        sb[u].init(b, n0, tid);
+        if (k_begin + u * BK < k_end) load_tile(sa[u], sb[u], k_begin + u * BK);
+    }
+    store_tile(sa[0], sb[0], As0, Bs0, k_begin);
     __syncthreads();
-    for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
-        step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
-        if (k0 + BK < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BK);
+    int k0 = k_begin;
+    // Steady state, free of conditions: every tile a round touches is a whole tile that exists.
+    // Only then does the compiler know how many loads are younger than the ones a step is about
+    // to store to LDS, and waits for those alone; a condition around a load makes it wait for
+    // every load in flight, which puts a full memory latency into each iteration.
+    if (VA == 4 && VB == 4) {
+        auto whole_step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const float *As_cur,
+                              const float *Bs_cur, float *As_nxt, float *Bs_nxt, int kk) {
+            ra_cur.load_full(a, kk + RS * BK, tid);
+            rb_cur.load_full(b, kk + RS * BK, tid);
+            multiply(As_cur, Bs_cur);
+            colsum_tile(Bs_cur);
+            ra_nxt.template store<false>(As_nxt, tid);
+            rb_nxt.template store<false>(Bs_nxt, tid);
+            __syncthreads();
+        };
+        for (; k0 + 2 * RS * BK <= k_end; k0 += RS * BK) {
+#pragma unroll
+            for (int u = 0; u < RS; ++u) {
+                if (u & 1) whole_step(sa[u], sb[u], sa[(u + 1) % RS], sb[(u + 1) % RS], As1, Bs1, As0, Bs0, k0 + u * BK);
+                else whole_step(sa[u], sb[u], sa[(u + 1) % RS], sb[(u + 1) % RS], As0, Bs0, As1, Bs1, k0 + u * BK);
+            }
+        }
+    }
+    for (; k0 < k_end; k0 += RS * BK) {
+#pragma unroll
+        for (int u = 0; u < RS; ++u) {
+            if (k0 + u * BK >= k_end) break;            // uniform over the workgroup
+            if (u & 1) step(sa[u], sb[u], sa[(u + 1) % RS], sb[(u + 1) % RS], As1, Bs1, As0, Bs0, k0 + u * BK);
+            else step(sa[u], sb[u], sa[(u + 1) % RS], sb[(u + 1) % RS], As0, Bs0, As1, Bs1, k0 + u * BK);
+        }
     }
     }
     if constexpr (COLSUM) {
