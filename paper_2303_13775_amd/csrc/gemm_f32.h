@@ -414,7 +414,24 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
             if (k0 + BK < k_end) land_tile(As_nxt, Bs_nxt, k0 + BK);
             __syncthreads();
         };
-        for (int k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
+        int k0 = k_begin;
+        // steady state without conditions: the tile fetched by each step is a whole tile that exists
+        if (VA == 4 && VB == 4) {
+            auto whole_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int kk) {
+                if (DA) da.issue(a, As_nxt, kk + BK, wave_u); else sa0.load_full(a, kk + BK, tid);
+                if (DB) db.issue(b, Bs_nxt, kk + BK, wave_u); else sb0.load_full(b, kk + BK, tid);
+                multiply(As_cur, Bs_cur);
+                colsum_tile(Bs_cur);
+                if (!DA) sa0.template store<false>(As_nxt, tid);
+                if (!DB) sb0.template store<false>(Bs_nxt, tid);
+                __syncthreads();
+            };
+            for (; k0 + 3 * BK <= k_end; k0 += 2 * BK) {
+                whole_step(As0, Bs0, As1, Bs1, k0);
+                whole_step(As1, Bs1, As0, Bs0, k0 + BK);
+            }
+        }
+        for (; k0 < k_end; k0 += 2 * BK) {
             lean_step(As0, Bs0, As1, Bs1, k0);
             if (k0 + BK < k_end) lean_step(As1, Bs1, As0, Bs0, k0 + BK);
         }
