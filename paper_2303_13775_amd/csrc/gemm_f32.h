@@ -249,9 +249,9 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
                                           const int k_begin, const int k_end, const AF &a, const BF &b,
                                           const EF &epi) {
     constexpr int BM = T::BM, BN = T::BN, MI = T::MI, NI = T::NI, KS = T::KS, NO = T::NO;
-    // two LDS stages and two register stages: k-tile t is multiplied out of LDS while tile t+1
-    // sits in the other LDS stage and tile t+2 is in flight into registers, so a global load has
-    // two iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
+    // two LDS stages and RS (two or four) register stages: k-tile t is multiplied out of LDS while
+    // tile t+1 sits in the other LDS stage and tiles t+2 .. t+RS are in flight into registers, so a
+    // global load has RS iterations to land (an HBM round trip is longer than one k-tile of MFMA work)
     constexpr bool PAD = !T::DIRECT;
     constexpr int AW = lds_words<BM, A_KC, PAD>(), BW = lds_words<BN, B_KC, PAD>();
     constexpr int RED = (KS - 1) * T::WM * T::WN * MI * NI * 1024;   // accumulators handed over at the end
