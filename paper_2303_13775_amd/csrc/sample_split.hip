@@ -181,6 +181,16 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 if (floyd && q == s && any != 0ull) chosen = j;
             }
         }
+        // What a lane enters into the two tables: its sampled neighbour (lanes q < fan) with the
+        // slot's global position, or, in the first spare lane of the group, the destination vertex
+        // itself with its row (destinations hold the smallest positions).  All of them go through
+        // the same insert instructions, so the destination's inserts cost the wave no extra round
+        // trips; only a group without a spare lane (fan == G) has lane 0 do them first.
+        const bool spare = fan < G;
+        int32_t key_v = -1;
+        uint32_t pos_v = 0;
+        int64_t out = -1;
+        const uint32_t sp = active ? (uint32_t)split_of(meta_up->front_off, S, row) : 0u;
         if (active && q < fan) {
             int64_t pos = -1;
             if (floyd) pos = beg + (int64_t)chosen;
@@ -189,20 +199,30 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             const int64_t g = (int64_t)row * fan + q;
             nbr[g] = val;
             if (epos) epos[g] = pos;
-            const uint32_t sp = (uint32_t)split_of(meta_up->front_off, S, row);
             if (q == 0) {
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
-                ent_mixed[row] = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
-                                              &meta_lo->error);
-                ent_local[row] = table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row, &meta_lo->error);
+                if (!spare) {
+                    ent_mixed[row] = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
+                                                  &meta_lo->error);
+                    ent_local[row] = table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row, &meta_lo->error);
+                }
             }
+            key_v = val;
+            pos_v = (uint32_t)(n1 + g);
+            out = n1 + g;
+        } else if (active && spare && q == fan) {
+            key_v = v;
+            pos_v = (uint32_t)row;
+            out = row;
+        }
+        if (out >= 0) {
             int hm = -1, hl = -1;
-            if (val >= 0) {
-                hm = table_insert(tab, bits, (uint32_t)val * (uint32_t)S + sp, (uint32_t)(n1 + g), &meta_lo->error);
-                hl = table_insert(tab_local, bits, (uint32_t)val, (uint32_t)(n1 + g), &meta_lo->error);
+            if (key_v >= 0) {
+                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error);
+                hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
             }
-            ent_mixed[n1 + g] = hm;
-            ent_local[n1 + g] = hl;
+            ent_mixed[out] = hm;
+            ent_local[out] = hl;
         }
     }
 }
