@@ -74,8 +74,9 @@ __device__ __forceinline__ uint32_t table_slot(uint32_t key, int bits) {
 // (same key) lower it with a 64-bit atomic min; the entry is read first and the atomic skipped
 // when it cannot change anything, which keeps hub vertices from serialising on one address.
 // Returns the entry index (-1 and the error flag if the table is full, which sizing excludes).
+// *behind (if given) is set when the key was already there with a smaller position.
 __device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t key, uint32_t p,
-                                            int32_t *err) {
+                                            int32_t *err, bool *behind = nullptr) {
     const uint32_t mask = (1u << bits) - 1u;
     const unsigned long long mine = ((unsigned long long)key << 32) | p;
     uint32_t h = table_slot(key, bits);
@@ -87,6 +88,7 @@ __device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t
         }
         if ((uint32_t)(cur >> 32) == key) {
             if (mine < cur) atomicMin(&t.slot[h], mine);
+            else if (behind) *behind = true;
             return (int)h;
         }
         h = (h + 1) & mask;
@@ -218,8 +220,12 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
         if (out >= 0) {
             int hm = -1, hl = -1;
             if (key_v >= 0) {
-                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error);
-                hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
+                // a slot that finds its (vertex, split) key with a smaller position is not the first
+                // occurrence in its split, let alone in the whole stream: nothing will ask for its
+                // entry in the vertex table, so it does not make one
+                bool behind = false;
+                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind);
+                if (!behind) hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
             }
             ent_mixed[out] = hm;
             ent_local[out] = hl;
