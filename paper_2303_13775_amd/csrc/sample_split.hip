@@ -15,8 +15,9 @@
 //                          relabelled to mixed-frontier rows, + reset of both tables for the next
 //                          layer)
 // (One workgroup doing count and scatter of a small partition in a single launch was tried for the
-// targets and the top layer: its chains of dependent accesses have nobody to overlap with, 85 us
-// against 21 us for 5120 slots.)
+// top layer: its chains of dependent accesses have nobody to overlap with, 85 us against 21 us
+// for 5120 slots.  The targets themselves, one lookup each, do take a single workgroup when there
+// are at most 1024 of them.)
 // The scatter side of the shuffle index (for every row of local_cat[l], the destination rows it
 // feeds, so that the backward pass can pull) of layer l+1 rides on the two partition launches of
 // layer l; only a context that keeps one for the bottom layer pays two launches of its own, after
@@ -439,6 +440,54 @@ struct PartTargets {
     }
 };
 
+// A batch of at most 1024 targets takes the whole step in one workgroup, one target per thread:
+// the two launches of the general partition are chains of a few dependent accesses each, and a
+// launch by itself costs about as much as this kernel's work.
+constexpr int TARGETS_SMALL = 1024;
+constexpr int64_t TARGETS_SMALL_TABLE = 65536;     // entries of both tables it still resets by itself
+
+__global__ __launch_bounds__(TARGETS_SMALL) void k_targets_small(PartTargets f) {
+    __shared__ int s_cnt[TARGETS_SMALL / 64][GS_MAXS];
+    __shared__ int s_tot[GS_MAXS], s_base[GS_MAXS];
+    __shared__ PartOffs s_o;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    if (tid < f.n_levels) f.meta_all[tid].error = 0;
+    __syncthreads();                                   // the flags are cleared before target() may set one
+    const bool in = tid < f.n_targets;
+    int32_t id = 0;
+    int k = -1;
+    if (in) {
+        id = f.target(tid);
+        k = f.pmap[id] & (GS_MAXS - 1);
+    }
+    int rank = 0;
+#pragma unroll
+    for (int c = 0; c < GS_MAXS; ++c) {
+        const uint64_t bal = __ballot(k == c);
+        if (k == c) rank = __popcll(bal & lanemask_lt());
+        if (lane == 0) s_cnt[wave][c] = __popcll(bal);
+    }
+    __syncthreads();
+    if (tid < GS_MAXS) {
+        int acc = 0;
+        for (int w = 0; w < TARGETS_SMALL / 64; ++w) { const int x = s_cnt[w][tid]; s_cnt[w][tid] = acc; acc += x; }
+        s_tot[tid] = acc;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        f.key_bases(s_tot, s_base, s_o, nullptr);
+        f.publish(s_o);
+    }
+    __syncthreads();
+    if (in) {
+        const int r = s_base[k] + s_cnt[wave][k] + rank;
+        f.front[r] = id;
+        f.perm[r] = tid;
+    }
+    const int64_t nx = f.n_extra(s_o);
+    for (int64_t x = tid; x < nx; x += TARGETS_SMALL) f.extra(x, s_o);
+}
+
 // The scatter side of the shuffle index of the sampling layer above (layer l+1) is finished while
 // layer l is partitioned: its rows are this layer's destination vertices, and its counters are
 // complete once the shuffle-index kernel of layer l+1 has run.  The count pass hands every row a
@@ -846,7 +895,17 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
                    ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1],
                    ctx->d_meta, L + 1, ctx->tab_local};
-    run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
+    {
+        const int64_t inputs = n_targets * (1 + ctx->fan[L - 1]);
+        int64_t cap = 1024;                             // = 1 << table_bits(inputs)
+        while (cap < 2 * inputs) cap <<= 1;
+        if (n_targets <= TARGETS_SMALL && 2 * cap <= TARGETS_SMALL_TABLE) {
+            GsTimeScope ts(ctx, "targets", -1, st);
+            hipLaunchKernelGGL(k_targets_small, dim3(1), dim3(TARGETS_SMALL), 0, st, pt);
+        } else {
+            run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
+        }
+    }
 
     for (int l = L - 1; l >= 0; --l) {
         const int fan = ctx->fan[l];
