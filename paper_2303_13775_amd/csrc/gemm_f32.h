@@ -304,11 +304,15 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     // The fragments of the next group of 8 k are read from LDS while the MFMAs of the current group
     // execute (an MFMA occupies the matrix pipe for 64 cycles but not the issue slot), so only the
     // first LDS read of a k-tile is exposed.
-    auto multiply = [&](const float *As, const float *Bs) {
+    // kv: k values of the tile that lie inside the k range.  The last tile of a range may hold
+    // fewer than BK, and a group of 8 k that lies wholly outside contributes nothing: it is skipped
+    // (a contraction of 200 runs 25 groups instead of 28, one of 100 runs 13 instead of 16).
+    auto multiply = [&](const float *As, const float *Bs, int kv) {
         if (T::LEAN) {
             float af[MI][4], bf[NI][4];
 #pragma unroll
             for (int t = 0; t < NO; ++t) {
+                if (t > 0 && 8 * (kg + KS * t) >= kv) break;        // uniform over the wave
 #pragma unroll
                 for (int i = 0; i < MI; ++i) read_frag<BM, A_KC, PAD>(As, wm0 + i * 32 + l32, kg + KS * t, half, af[i]);
 #pragma unroll
@@ -339,13 +343,15 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
                     read_frag<BN, B_KC, PAD>(Bs, wn0 + j * 32 + l32, kg + KS * (t + 1), half, bf[(t + 1) & 1][j]);
             }
             __builtin_amdgcn_sched_barrier(0);   // reads of the next group stay ahead of these MFMAs
+            if (t == 0 || 8 * (kg + KS * t) < kv) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int i = 0; i < MI; ++i)
+                    for (int i = 0; i < MI; ++i)
 #pragma unroll
-                    for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][i][q], bf[t & 1][j][q], acc[i][j], 0, 0, 0);
+                        for (int j = 0; j < NI; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[t & 1][i][q], bf[t & 1][j][q], acc[i][j], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -370,7 +376,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
     auto step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const float *As_cur, const float *Bs_cur,
                     float *As_nxt, float *Bs_nxt, int k0) {
         if (k0 + RS * BK < k_end) load_tile(ra_cur, rb_cur, k0 + RS * BK);
-        multiply(As_cur, Bs_cur);
+        multiply(As_cur, Bs_cur, k_end - k0);
         colsum_tile(Bs_cur);
         if (k0 + BK < k_end) store_tile(ra_nxt, rb_nxt, As_nxt, Bs_nxt, k0 + BK);
         __syncthreads();
@@ -409,7 +415,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
         __syncthreads();
         auto lean_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int k0) {
             if (k0 + BK < k_end) fetch_tile(As_nxt, Bs_nxt, k0 + BK);
-            multiply(As_cur, Bs_cur);
+            multiply(As_cur, Bs_cur, k_end - k0);
             colsum_tile(Bs_cur);
             if (k0 + BK < k_end) land_tile(As_nxt, Bs_nxt, k0 + BK);
             __syncthreads();
@@ -420,7 +426,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
             auto whole_step = [&](const float *As_cur, const float *Bs_cur, float *As_nxt, float *Bs_nxt, int kk) {
                 if (DA) da.issue(a, As_nxt, kk + BK, wave_u); else sa0.load_full(a, kk + BK, tid);
                 if (DB) db.issue(b, Bs_nxt, kk + BK, wave_u); else sb0.load_full(b, kk + BK, tid);
-                multiply(As_cur, Bs_cur);
+                multiply(As_cur, Bs_cur, BK);
                 colsum_tile(Bs_cur);
                 if (!DA) sa0.template store<false>(As_nxt, tid);
                 if (!DB) sb0.template store<false>(Bs_nxt, tid);
@@ -454,7 +460,7 @@ __device__ __forceinline__ void gemm_tile(const int m0, const int n0, const int 
                               const float *Bs_cur, float *As_nxt, float *Bs_nxt, int kk) {
             ra_cur.load_full(a, kk + RS * BK, tid);
             rb_cur.load_full(b, kk + RS * BK, tid);
-            multiply(As_cur, Bs_cur);
+            multiply(As_cur, Bs_cur, BK);
             colsum_tile(Bs_cur);
             ra_nxt.template store<false>(As_nxt, tid);
             rb_nxt.template store<false>(Bs_nxt, tid);
