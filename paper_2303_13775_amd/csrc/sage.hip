@@ -30,39 +30,57 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32(const float *__restr
                                                             const int32_t *__restrict__ edge_row,
                                                             const int32_t *__restrict__ self_row,
                                                             const GsLevelMeta *__restrict__ meta_up,
-                                                            int S, float *__restrict__ X,
+                                                            int S, int fan, float *__restrict__ X,
                                                             float *__restrict__ inv_cnt) {
     const int n1 = meta_up->front_off[S];
     const int nvec = D >> 2;
     const int c0 = threadIdx.x % LPR;
     const int groups = (gridDim.x * blockDim.x) / LPR;
+    const int n_c = (nvec + LPR - 1) / LPR;      // column rounds, the same for every lane of a group
     const float4 *H4 = reinterpret_cast<const float4 *>(H);
     float4 *X4 = reinterpret_cast<float4 *>(X);
+    // A row is a chain of dependent accesses (offsets -> source rows of its edges -> their values), and
+    // the kernel's time is the length of that chain, not its bytes.  So the lanes of a group fetch the
+    // source rows of up to LPR edges with one load (lane u takes edge u, the others get it by shuffle)
+    // and keep the values of sixteen edges in flight; the sum still runs in edge order.  Edges a row
+    // does not have are read from its own row (a valid address) and not added.
     for (int row = (blockIdx.x * blockDim.x + threadIdx.x) / LPR; row < n1; row += groups) {
-        const int e0 = blk_indptr[row], e1 = blk_indptr[row + 1];
+        const int e0 = blk_indptr[row];
+        const int m = blk_indptr[row + 1] - e0;
         const int64_t self = self_row[row];
-        const float cnt = (float)(e1 - e0);
-        if (c0 == 0) inv_cnt[row] = e1 > e0 ? 1.f / cnt : 0.f;
-        for (int c = c0; c < nvec; c += LPR) {
-            const float4 own = H4[self * nvec + c];
+        const float cnt = (float)m;
+        if (c0 == 0) inv_cnt[row] = m > 0 ? 1.f / cnt : 0.f;
+        for (int ci = 0; ci < n_c; ++ci) {
+            const int c = c0 + ci * LPR;
+            const bool cv = c < nvec;
+            const int cc = cv ? c : 0;
+            const float4 own = H4[self * nvec + cc];
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            int e = e0;
-            for (; e + 4 <= e1; e += 4) {
-                const int r0 = edge_row[e], r1 = edge_row[e + 1], r2 = edge_row[e + 2], r3 = edge_row[e + 3];
-                const float4 a = H4[(int64_t)r0 * nvec + c], b = H4[(int64_t)r1 * nvec + c];
-                const float4 g = H4[(int64_t)r2 * nvec + c], h = H4[(int64_t)r3 * nvec + c];
-                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
-                acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
-                acc.x += g.x; acc.y += g.y; acc.z += g.z; acc.w += g.w;
-                acc.x += h.x; acc.y += h.y; acc.z += h.z; acc.w += h.w;
+            for (int chunk = 0; chunk < fan; chunk += LPR) {
+                const int mine = chunk + c0 < m ? edge_row[e0 + chunk + c0] : -1;
+#pragma unroll
+                for (int half = 0; half < LPR; half += 16) {
+                    // wave-uniform: does any row of this wave reach this far?
+                    if (__ballot(chunk + half < m) == 0ull) break;
+                    float4 v[16];
+                    unsigned have = 0u;
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const int r = __shfl(mine, half + u, LPR);
+                        have |= (r >= 0 ? 1u : 0u) << u;
+                        v[u] = H4[(r >= 0 ? (int64_t)r : self) * nvec + cc];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        if ((have >> u) & 1u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+                    }
+                }
             }
-            for (; e < e1; ++e) {
-                const float4 a = H4[(int64_t)edge_row[e] * nvec + c];
-                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
+            if (m > 0) { acc.x /= cnt; acc.y /= cnt; acc.z /= cnt; acc.w /= cnt; }
+            if (cv) {
+                X4[(int64_t)row * 2 * nvec + c] = own;
+                X4[(int64_t)row * 2 * nvec + nvec + c] = acc;
             }
-            if (e1 > e0) { acc.x /= cnt; acc.y /= cnt; acc.z /= cnt; acc.w /= cnt; }
-            X4[(int64_t)row * 2 * nvec + c] = own;
-            X4[(int64_t)row * 2 * nvec + nvec + c] = acc;
         }
     }
 }
@@ -445,13 +463,13 @@ void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_
     const int nvec = D / 4;
     if (nvec <= 16)
         hipLaunchKernelGGL(k_assemble_input_f32<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
     else if (nvec <= 32)
         hipLaunchKernelGGL(k_assemble_input_f32<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
     else
         hipLaunchKernelGGL(k_assemble_input_f32<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
 }
 
 }  // namespace
