@@ -231,7 +231,26 @@ __device__ __forceinline__ void gemm_tile_h(const int m0, const int n0, const in
     sa0.store(As0, tid);
     sb0.store(Bs0, tid);
     __syncthreads();
-    for (int k0 = 0; k0 < k_end; k0 += 2 * BKH) {
+    // steady state without conditions around the loads (every tile a round fetches exists), so that
+    // the compiler waits only for the loads a step is about to store and the younger ones stay in
+    // flight; the general loop takes the last tiles
+    int k0 = 0;
+    {
+        auto whole_step = [&](SA &ra_cur, SB &rb_cur, SA &ra_nxt, SB &rb_nxt, const uint4 *As_cur,
+                              const uint4 *Bs_cur, uint4 *As_nxt, uint4 *Bs_nxt, int kk) {
+            ra_cur.load(a, m0, m_end, kk + 2 * BKH, k_end, tid);
+            rb_cur.load(b, n0, n_end, kk + 2 * BKH, k_end, tid);
+            multiply(As_cur, Bs_cur);
+            ra_nxt.store(As_nxt, tid);
+            rb_nxt.store(Bs_nxt, tid);
+            __syncthreads();
+        };
+        for (; k0 + 3 * BKH < k_end; k0 += 2 * BKH) {
+            whole_step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
+            whole_step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BKH);
+        }
+    }
+    for (; k0 < k_end; k0 += 2 * BKH) {
         step(sa0, sb0, sa1, sb1, As0, Bs0, As1, Bs1, k0);
         if (k0 + BKH < k_end) step(sa1, sb1, sa0, sb0, As1, Bs1, As0, Bs0, k0 + BKH);
     }
@@ -510,7 +529,24 @@ __global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, DZ dz, Ep
     if (k_begin + BKH < k_end) load_tile(pa1, pb1, k_begin + BKH);
     store_tile(pa0, pb0, lds[0]);
     __syncthreads();
-    for (int k0 = k_begin; k0 < k_end; k0 += 2 * BKH) {
+    // steady state without conditions around the loads: whole tiles that exist (see the row-block
+    // product above)
+    int k0 = k_begin;
+    {
+        auto whole_step = [&](PatchX &pa_cur, PDZ &pb_cur, const PatchX &pa_nxt, const PDZ &pb_nxt,
+                              const uint32_t *buf_cur, uint32_t *buf_nxt, int kk) {
+            pa_cur.load(a, tok, kk + 2 * BKH + 2 * kp, k_end, true);
+            pb_cur.load(dz, n0, kk + 2 * BKH + 2 * kp, k_end, x, true);
+            multiply(buf_cur);
+            store_tile(pa_nxt, pb_nxt, buf_nxt);
+            __syncthreads();
+        };
+        for (; k0 + 4 * BKH <= k_end; k0 += 2 * BKH) {
+            whole_step(pa0, pb0, pa1, pb1, lds[0], lds[1], k0);
+            whole_step(pa1, pb1, pa0, pb0, lds[1], lds[0], k0 + BKH);
+        }
+    }
+    for (; k0 < k_end; k0 += 2 * BKH) {
         step(pa0, pb0, pa1, pb1, lds[0], lds[1], k0);
         if (k0 + BKH < k_end) step(pa1, pb1, pa0, pb0, lds[1], lds[0], k0 + BKH);
     }
