@@ -18,26 +18,32 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint8_t *__restrict__
                                                      VecT *__restrict__ out) {
     const int64_t n_rows = meta0->front_off[S];
     const int64_t total = n_rows * vec_per_row;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    for (; x + (UNROLL - 1) * stride < total; x += UNROLL * stride) {
-        VecT v[UNROLL];
+    // The launch is sized from an upper bound on the rows, several times the real count.  Only as
+    // many threads work as give each of them at least two pieces (the others leave at once), and
+    // every round of UNROLL is complete: a piece past the end re-reads the thread's first piece (a
+    // valid address) and is not stored.  So a thread fetches the ids of a round together and then
+    // its rows, instead of running id -> row round trips one after the other.  (UNROLL pieces for
+    // every working thread, i.e. fewer threads still, was slower for 400-byte rows.)
+    const int64_t launched = (int64_t)gridDim.x * blockDim.x;
+    const int64_t want = ((total + 1) / 2 + 255) & ~(int64_t)255;
+    const int64_t stride = want < launched ? want : launched;
+    const int64_t x0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (x0 >= stride) return;
+    for (int64_t x = x0; x < total; x += UNROLL * stride) {
+        int64_t off[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const int64_t y = x + u * stride;
+            const int64_t y = x + u * stride < total ? x + u * stride : x;
             const int64_t r = y / vec_per_row;
             const int c = (int)(y - r * vec_per_row);
-            v[u] = *reinterpret_cast<const VecT *>(table + (int64_t)ids[r] * row_stride_bytes +
-                                                   (int64_t)c * sizeof(VecT));
+            off[u] = (int64_t)ids[r] * row_stride_bytes + (int64_t)c * sizeof(VecT);
         }
+        VecT v[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) out[x + u * stride] = v[u];
-    }
-    for (; x < total; x += stride) {
-        const int64_t r = x / vec_per_row;
-        const int c = (int)(x - r * vec_per_row);
-        out[x] = *reinterpret_cast<const VecT *>(table + (int64_t)ids[r] * row_stride_bytes +
-                                                 (int64_t)c * sizeof(VecT));
+        for (int u = 0; u < UNROLL; ++u) v[u] = *reinterpret_cast<const VecT *>(table + off[u]);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (x + u * stride < total) out[x + u * stride] = v[u];
     }
 }
 
