@@ -2,7 +2,8 @@
 57 GB feature table resident in HBM; 65M-vertex / 3.6B-edge skewed graph).  The graphs are generated
 on the GPU in a few seconds each and the whole file runs in about half a minute; it needs about
 80 GB of HBM and 10 GB of host memory.  GSPLIT_SKIP_BIG=1 leaves it out.  The tests print their
-progress."""
+progress.  (The file name puts them last in the GPU suite: they are the tests that depend most
+on what else is using the machine.)"""
 import os
 import time
 
