@@ -132,7 +132,12 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         }
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
-    for (GsTable *t : {&ctx->tab_local, &ctx->tab_mixed}) {
+    // one split: the (vertex, split) key is the vertex key, and one table serves as both
+    for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
+        if (t == &ctx->tab_local && ctx->S == 1) {
+            *t = ctx->tab_mixed;
+            break;
+        }
         A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
         A((void **)&t->row, sizeof(int32_t) * tab_cap, "table rows");
     }

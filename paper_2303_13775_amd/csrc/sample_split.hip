@@ -205,9 +205,11 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             if (q == 0) {
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
                 if (!spare) {
-                    ent_mixed[row] = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
-                                                  &meta_lo->error);
-                    ent_local[row] = table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row, &meta_lo->error);
+                    const int hm = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
+                                                &meta_lo->error);
+                    ent_mixed[row] = hm;
+                    ent_local[row] = S == 1 ? hm : table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row,
+                                                                &meta_lo->error);
                 }
             }
             key_v = val;
@@ -224,9 +226,12 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 // a slot that finds its (vertex, split) key with a smaller position is not the first
                 // occurrence in its split, let alone in the whole stream: nothing will ask for its
                 // entry in the vertex table, so it does not make one
+                // (with a single split the two keys are the same key, the two tables the same table,
+                // and a vertex has the same row in the mixed and in the next local frontier)
                 bool behind = false;
                 hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind);
-                if (!behind) hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
+                if (S == 1) hl = hm;
+                else if (!behind) hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
             }
             ent_mixed[out] = hm;
             ent_local[out] = hl;
