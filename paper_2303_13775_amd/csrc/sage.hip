@@ -15,6 +15,28 @@ namespace {
 
 #include "gemm_f32.h"
 
+// [W_self; W_neigh] stacked into one 2 D x Npad matrix (Npad = N rounded up to 4, padding zeroed):
+// every product then reads the weights as one plain matrix in 16-byte pieces whatever N is.  All
+// layers are stacked by one launch: a launch of its own (blockIdx.y = layer), or, riding on the
+// bottom layer's input assembly, the workgroups behind that kernel's own (it needs the stacked
+// weights no earlier than the product that follows).
+struct WeightStack {
+    const float *ws[GS_MAXL]; const float *wn[GS_MAXL]; float *stacked[GS_MAXL]; int D[GS_MAXL]; int N[GS_MAXL];
+};
+__device__ __forceinline__ void stack_weights(const WeightStack &w, int l, int block, int n_blocks) {
+    const int D = w.D[l], N = w.N[l], np = (N + 3) & ~3;
+    const int64_t words = (int64_t)2 * D * np;
+    for (int64_t x = block * (int64_t)blockDim.x + threadIdx.x; x < words; x += (int64_t)n_blocks * blockDim.x) {
+        const int k = (int)(x / np), n = (int)(x % np);
+        float v = 0.f;
+        if (n < N) v = k < D ? w.ws[l][(int64_t)k * N + n] : w.wn[l][(int64_t)(k - D) * N + n];
+        w.stacked[l][x] = v;
+    }
+}
+__global__ __launch_bounds__(256) void k_stack_weights(WeightStack w) {
+    stack_weights(w, blockIdx.y, blockIdx.x, gridDim.x);
+}
+
 // ------------------------------------------------------------------------------------------
 // Layer input assembly: for destination row i
 //   X[i, 0:D]  = H[self_row[i], :]                         (its own lower-layer row)
@@ -31,11 +53,17 @@ __global__ __launch_bounds__(256) void k_assemble_input_f32(const float *__restr
                                                             const int32_t *__restrict__ self_row,
                                                             const GsLevelMeta *__restrict__ meta_up,
                                                             int S, int fan, float *__restrict__ X,
-                                                            float *__restrict__ inv_cnt) {
+                                                            float *__restrict__ inv_cnt, int n_main,
+                                                            WeightStack wstack, int n_stack) {
+    if ((int)blockIdx.x >= n_main) {        // the workgroups behind the kernel's own stack the weights
+        const int b = (int)blockIdx.x - n_main;
+        stack_weights(wstack, b / n_stack, b % n_stack, n_stack);
+        return;
+    }
     const int n1 = meta_up->front_off[S];
     const int nvec = D >> 2;
     const int c0 = threadIdx.x % LPR;
-    const int groups = (gridDim.x * blockDim.x) / LPR;
+    const int groups = (n_main * blockDim.x) / LPR;
     const int n_c = (nvec + LPR - 1) / LPR;      // column rounds, the same for every lane of a group
     const float4 *H4 = reinterpret_cast<const float4 *>(H);
     float4 *X4 = reinterpret_cast<float4 *>(X);
@@ -392,24 +420,6 @@ int check_params(gsplit_ctx *ctx, const gsplit_sage_params *p, const char *who) 
     return GSPLIT_OK;
 }
 
-// [W_self; W_neigh] stacked into one 2 D x Npad matrix (Npad = N rounded up to 4, padding zeroed),
-// all layers in one launch (blockIdx.y = layer): every product then reads the weights as one plain
-// matrix in 16-byte pieces whatever N is.
-struct WeightStack {
-    const float *ws[GS_MAXL]; const float *wn[GS_MAXL]; float *stacked[GS_MAXL]; int D[GS_MAXL]; int N[GS_MAXL];
-};
-__global__ __launch_bounds__(256) void k_stack_weights(WeightStack w) {
-    const int l = blockIdx.y;
-    const int D = w.D[l], N = w.N[l], np = (N + 3) & ~3;
-    const int64_t words = (int64_t)2 * D * np;
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < words; x += (int64_t)gridDim.x * blockDim.x) {
-        const int k = (int)(x / np), n = (int)(x % np);
-        float v = 0.f;
-        if (n < N) v = k < D ? w.ws[l][(int64_t)k * N + n] : w.wn[l][(int64_t)(k - D) * N + n];
-        w.stacked[l][x] = v;
-    }
-}
-
 // ---- tile choice and launches of the fp32 products ------------------------------------------
 // The tile is chosen from what the host knows: the upper bound on the rows, the output width and
 // the length of the contraction.  The middle tile serves products with enough rows to fill the
@@ -449,7 +459,10 @@ void launch_grad_in(gsplit_ctx *ctx, hipStream_t st, int64_t ub, bool vdz, const
     else launch_grad_in_t<TileLow, 4, 4>(ctx, st, ub, dz, w, epi, mu);
 }
 
-void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st) {
+// ws (may be NULL): weights to stack behind the assembly's own workgroups.  Returns false if they
+// were not stacked (the scalar variant does not carry them).
+bool launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_t st, const WeightStack *ws,
+                     int64_t stack_words) {
     const GsLayerBuf &B = ctx->layer[l];
     const GsLevelMeta *mu = ctx->d_meta + (l + 1);
     float *X = (float *)ctx->sage.xin[l];
@@ -458,18 +471,25 @@ void launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_
     if (D % 4 != 0 || !aligned16(hin)) {
         hipLaunchKernelGGL(k_assemble_input_f32_any, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
                            B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, X, ctx->sage.inv_cnt[l]);
-        return;
+        return false;
     }
     const int nvec = D / 4;
-    if (nvec <= 16)
-        hipLaunchKernelGGL(k_assemble_input_f32<16>, dim3(grid_1d(ctx, ub * 16)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
-    else if (nvec <= 32)
-        hipLaunchKernelGGL(k_assemble_input_f32<32>, dim3(grid_1d(ctx, ub * 32)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
-    else
-        hipLaunchKernelGGL(k_assemble_input_f32<64>, dim3(grid_1d(ctx, ub * 64)), dim3(256), 0, st, hin, D,
-                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X, ctx->sage.inv_cnt[l]);
+    const int n_stack = ws ? (int)std::min<int64_t>(128, gs_ceil_div(stack_words, 256)) : 0;
+    const WeightStack none{};
+    const WeightStack &w = ws ? *ws : none;
+    const int extra = n_stack * ctx->L;
+#define GS_ASSEMBLE(LPR)                                                                                     \
+    do {                                                                                                     \
+        const int n_main = grid_1d(ctx, ub * LPR);                                                           \
+        hipLaunchKernelGGL(k_assemble_input_f32<LPR>, dim3(n_main + extra), dim3(256), 0, st, hin, D,        \
+                           B.blk_indptr, B.edge_row, B.self_row, mu, ctx->S, ctx->fan[l], X,                 \
+                           ctx->sage.inv_cnt[l], n_main, w, n_stack);                                        \
+    } while (0)
+    if (nvec <= 16) GS_ASSEMBLE(16);
+    else if (nvec <= 32) GS_ASSEMBLE(32);
+    else GS_ASSEMBLE(64);
+#undef GS_ASSEMBLE
+    return ws != nullptr;
 }
 
 }  // namespace
@@ -533,24 +553,30 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         sb.fwd_batch = ctx->batch_id;
         return GSPLIT_OK;
     }
+    WeightStack ws{};
+    int64_t stack_words = 1;
     {
-        WeightStack ws;
         int64_t wmax = 1;
         for (int l = 0; l < L; ++l) {
             ws.ws[l] = (const float *)p->d_w_self[l]; ws.wn[l] = (const float *)p->d_w_neigh[l];
             ws.stacked[l] = sb.wstack32[l]; ws.D[l] = p->dims[l]; ws.N[l] = p->dims[l + 1];
             wmax = std::max<int64_t>(wmax, (int64_t)2 * p->dims[l] * ((p->dims[l + 1] + 3) & ~3));
         }
-        GsTimeScope ts(ctx, "stack_weights", -1, st);
-        hipLaunchKernelGGL(k_stack_weights, dim3((unsigned)std::min<int64_t>(128, gs_ceil_div(wmax, 256)), L), dim3(256),
-                           0, st, ws);
+        stack_words = wmax;
     }
     for (int l = 0; l < L; ++l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const float *hin = l == 0 ? (const float *)d_feat_local : (const float *)sb.hidden[l];
         float *hout = l == L - 1 ? d_logits : (float *)sb.hidden[l + 1];
         const GsLevelMeta *mu = ctx->d_meta + (l + 1);
-        launch_assemble(ctx, l, hin, D, st);
+        // the stacked weights are first needed by the bottom layer's product: the bottom layer's
+        // input assembly carries the stacking; if it cannot, a launch of its own does it
+        const bool stacked = launch_assemble(ctx, l, hin, D, st, l == 0 ? &ws : nullptr, stack_words);
+        if (l == 0 && !stacked) {
+            GsTimeScope ts(ctx, "stack_weights", -1, st);
+            hipLaunchKernelGGL(k_stack_weights, dim3((unsigned)std::min<int64_t>(128, gs_ceil_div(stack_words, 256)), L),
+                               dim3(256), 0, st, ws);
+        }
         MatRows a{(const float *)sb.xin[l], 0, 2 * D};
         MatRows b{sb.wstack32[l], 2 * D, (N + 3) & ~3};
         EpiFwd epi{hout, (const float *)p->d_bias[l], N, 0, l < L - 1 ? 1 : 0};
