@@ -260,6 +260,15 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
     for (int u = (blockIdx.x * blockDim.x + threadIdx.x) / LPR; u < n_lo; u += groups) {
         const int e0 = rev_ptr[u], e1 = e0 + rev_cnt[u];
         for (int c = c0; c < nvec; c += LPR) {
+            // the activation that gates the result does not depend on the sum: fetched first, it
+            // travels while the row's entries and their gradient rows are fetched
+            float4 h;
+            if (HACT_H) {
+                const uint2 raw = reinterpret_cast<const uint2 *>(hact)[(int64_t)u * nvec + c];
+                h = make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
+            } else {
+                h = A4[(int64_t)u * nvec + c];
+            }
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             int e = e0;
             for (; e + 2 <= e1; e += 2) {
@@ -273,13 +282,6 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
                 const int k0 = rev_list[e];
                 const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
                 acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
-            }
-            float4 h;
-            if (HACT_H) {
-                const uint2 raw = reinterpret_cast<const uint2 *>(hact)[(int64_t)u * nvec + c];
-                h = make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
-            } else {
-                h = A4[(int64_t)u * nvec + c];
             }
             acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
             acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
