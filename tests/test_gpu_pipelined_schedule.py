@@ -1,0 +1,59 @@
+"""The schedule bench.py times, checked as it is timed: three batch slots (contexts whose sampling
+kernels may occupy two workgroups per compute unit), two sampling streams and a training stream,
+two host threads, events handing the slots over in both directions, on the benchmark workload at
+its full size.  After a run every slot still holds its last step: the integer outputs, the
+gathered rows, the logits and every gradient of those steps against the oracle (GraphSAGE), and
+for both models the logits against a strictly serial run of the same steps on one stream
+(bit-equal: same kernels, same inputs)."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+import workloads
+from oracle import reference as R
+from test_gpu_parity import TOL_F32, assert_batch_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("model", ["sage", "gat"])
+def test_pipelined_schedule_leaves_the_oracles_results_in_every_slot(model):
+    assert torch.cuda.is_available(), "needs the MI355X"
+    dev = torch.device("cuda:0")
+    w = workloads.medium(device=dev)
+    n_steps = 11                                    # not a multiple of the three slots
+    targets = [w.targets(i) for i in range(n_steps)]
+    pipe = bench.Pipelined(w, dev, 2, model, 4, 2)
+    pipe.run(targets, 0, n_steps)
+    torch.cuda.synchronize()
+    host = dict(indptr=w.indptr.cpu().numpy(), indices=w.indices.cpu().numpy(), pmap=w.pmap.cpu().numpy())
+    op = R.SageParams([t.cpu().numpy() for t in w.w_self], [t.cpu().numpy() for t in w.w_neigh],
+                      [t.cpu().numpy() for t in w.bias])
+    serial = bench.Runner(w, dev, model, 4)
+    for i in range(n_steps - pipe.n, n_steps):      # the last step of every slot
+        r = pipe.slots[i % pipe.n]
+        tg = targets[i]
+        ob = R.sp_sample(host["indptr"], host["indices"], host["pmap"], w.n_splits, w.fanouts,
+                         tg.cpu().numpy(), r.seed, i)
+        assert_batch_equal(r.ctx.fetch_batch(), ob, w.n_splits, w.n_layers)
+        ids = torch.from_numpy(ob.local_cat(0)).long().to(dev)
+        assert torch.equal(r.x0[:ids.numel()], w.feat[ids]), ("gathered rows", i)
+        serial.step(tg, i)
+        torch.cuda.synchronize()
+        assert torch.equal(serial.logits, r.logits), ("serial and pipelined logits differ", i)
+        if model != "sage":         # the GAT kernels' own parity at this size is test_gpu_medium_rows'
+            continue
+        of = R.sp_forward(ob, w.feat[ids].cpu().numpy(), op)
+        y = w.labels[torch.from_numpy(tg.cpu().numpy()[ob.target_perm]).to(dev).long()].cpu().numpy()
+        _, g = R.softmax_xent(of.logits, y)
+        obw = R.sp_backward(ob, of, op, g)
+        sws, swn, sb, _ = R.relu_decision_slack(ob, of, op, obw)
+        assert R.max_rel_err(r.logits.cpu().numpy(), of.logits) < TOL_F32, ("logits", i)
+        gws, gwn, gb = r.grads
+        for l in range(w.n_layers):
+            assert R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l]) < TOL_F32, ("gw_self", i, l)
+            assert R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l]) < TOL_F32, ("gw_neigh", i, l)
+            assert R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l]) < TOL_F32, ("gbias", i, l)
+    for r in pipe.slots + [serial]:
+        r.ctx.close()
