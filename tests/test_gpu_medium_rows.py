@@ -1,7 +1,7 @@
 """The rows built on top of the hot path, at the size and in the configuration bench.py times them:
 the medium workload (2.4M vertices, about 131M edges, fanouts [15,10,5], 100-256-256-47).  GAT
 forward/backward (heads 4-4-1), the split statistics and the micro-batch counters (4096 targets as
-4 x 1024), and the cached loading step with the table in pinned host memory, all against the
+4 x 1024), the cached loading step with the table in pinned host memory, and the bf16 path, all against the
 oracle on the same batch."""
 import numpy as np
 import pytest
@@ -118,4 +118,45 @@ def test_cached_loading_medium_full_size(medium):
     assert np.array_equal(out[:want.shape[0]].cpu().numpy().view(np.int32), want.view(np.int32))
     assert np.array_equal(hits.cpu().numpy(), wh) and np.array_equal(misses.cpu().numpy(), wm)
     assert wh.sum() > 0 and wm.sum() > 0
+    ctx.close()
+
+
+def test_bf16_path_medium_full_size(medium):
+    """`bench.py --dtype bf16` on the benchmark workload: bf16 features, activations and stacked
+    weights, bf16 MFMA products with float accumulation, against the oracle that rounds the same
+    stored values to bf16."""
+    from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16
+    from test_gpu_parity import FLOOR_BF16, TOL_BF16
+    w, dev, host = medium
+    ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
+    table = w.feat.to(torch.bfloat16)
+    params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias, dtype=GSPLIT_BF16)
+    op = R.SageParams([t.cpu().numpy() for t in w.w_self], [t.cpu().numpy() for t in w.w_neigh],
+                      [t.cpu().numpy() for t in w.bias])
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=torch.bfloat16, device=dev)
+    logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+    glog = torch.empty_like(logits)
+    gws = [torch.empty_like(t) for t in w.w_self]
+    gwn = [torch.empty_like(t) for t in w.w_neigh]
+    gb = [torch.empty_like(t) for t in w.bias]
+    it = 3
+    tg = w.targets(it)
+    ctx.gsplit_sample_split(tg, 99, it)
+    ctx.gsplit_gather_features(table, x0)
+    ctx.gsplit_sage_fwd(params, x0, logits)
+    ob = R.sp_sample(host["indptr"], host["indices"], host["pmap"], w.n_splits, w.fanouts, tg.cpu().numpy(), 99, it)
+    ids = torch.from_numpy(ob.local_cat(0)).long().to(dev)
+    assert torch.equal(x0[:ids.numel()].view(torch.int16), table[ids].view(torch.int16))
+    of = R.sp_forward(ob, table[ids].float().cpu().numpy(), op, store_bf16=True)
+    y = w.labels[torch.from_numpy(tg.cpu().numpy()[ob.target_perm]).to(dev).long()].cpu().numpy()
+    _, g = R.softmax_xent(of.logits, y)
+    ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
+    torch.cuda.synchronize()
+    obw = R.sp_backward(ob, of, op, g, store_bf16=True)
+    sws, swn, sb, _ = R.relu_decision_slack(ob, of, op, obw, rel_tau=1e-3, store_bf16=True)
+    assert R.max_rel_err(logits.cpu().numpy(), of.logits, floor=FLOOR_BF16) < TOL_BF16
+    for l in range(w.n_layers):
+        assert R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_self", l)
+        assert R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_neigh", l)
+        assert R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("gbias", l)
     ctx.close()
