@@ -1,7 +1,8 @@
 """The rows built on top of the hot path, at the size and in the configuration bench.py times them:
 the medium workload (2.4M vertices, about 131M edges, fanouts [15,10,5], 100-256-256-47).  GAT
 forward/backward (heads 4-4-1), the split statistics and the micro-batch counters (4096 targets as
-4 x 1024), the cached loading step with the table in pinned host memory, and the bf16 path, all against the
+4 x 1024), the cached loading step with the table in pinned host memory, the pre-sampling counts and the
+bf16 path, all against the
 oracle on the same batch."""
 import numpy as np
 import pytest
@@ -159,4 +160,28 @@ def test_bf16_path_medium_full_size(medium):
         assert R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_self", l)
         assert R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_neigh", l)
         assert R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("gbias", l)
+    ctx.close()
+
+
+def test_presample_counts_medium_full_size(medium):
+    """`bench.py --presample` on the benchmark workload: vertex and edge counts of three sampled
+    batches bit-exact, weights as count / N."""
+    from paper_2303_13775_amd import Context
+    w, dev, host = medium
+    ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch, keep_edge_ids=True)
+    k_v = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
+    k_e = torch.zeros(w.indices.numel(), dtype=torch.int32, device=dev)
+    its = [0, 1, 2]
+    batches = [w.targets(i) for i in its]
+    for i, tg in zip(its, batches):
+        ctx.gsplit_sample_split(tg, 4242, i)
+        ctx.gsplit_presample_accumulate(k_v, k_e)
+    ov, oe = R.presample_counts(host["indptr"], host["indices"], w.fanouts, [b.cpu().numpy() for b in batches],
+                                4242, its)
+    assert np.array_equal(k_v.cpu().numpy().astype(np.int64), ov)
+    assert np.array_equal(k_e.cpu().numpy().astype(np.int64), oe)
+    w_v = torch.empty(w.n_vertices, dtype=torch.float32, device=dev)
+    ctx.gsplit_presample_weights(k_v, len(its), w_v)
+    want_v, _ = R.presample_weights(ov, oe, len(its))
+    assert np.abs(w_v.cpu().numpy() - want_v).max() <= 1e-6 * max(1.0, want_v.max())
     ctx.close()
