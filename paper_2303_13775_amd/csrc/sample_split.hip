@@ -43,6 +43,7 @@ constexpr int PART_BS = 256;     // threads of a partition workgroup
 constexpr int PART_NK = 25;     // classes of a partition pass: 8 senders + 8 owners + 1 edge counter + 8 owners (new local)
 constexpr int PART_MAX_NB = 1024;
 constexpr unsigned long long EMPTY_ENTRY = ~0ull;
+constexpr int CLAIM_FIRST_MAX = 1 << 16;     // destinations + slots up to which inserts claim before they read
 
 // ------------------------------------------------------------------------------------------
 // small device helpers
@@ -76,16 +77,25 @@ __device__ __forceinline__ uint32_t table_slot(uint32_t key, int bits) {
 // when it cannot change anything, which keeps hub vertices from serialising on one address.
 // Returns the entry index (-1 and the error flag if the table is full, which sizing excludes).
 // *behind (if given) is set when the key was already there with a smaller position.
+// claim_first: try the compare-and-swap without reading first.  One access instead of two when the
+// entry is free, which is what a small layer's path through this function consists of; only where
+// few elements share a key, since every attempt on a taken entry is then an atomic on it.
 __device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t key, uint32_t p,
-                                            int32_t *err, bool *behind = nullptr) {
+                                            int32_t *err, bool *behind = nullptr, bool claim_first = false) {
     const uint32_t mask = (1u << bits) - 1u;
     const unsigned long long mine = ((unsigned long long)key << 32) | p;
     uint32_t h = table_slot(key, bits);
     for (uint32_t probe = 0; probe <= mask; ++probe) {
-        unsigned long long cur = __hip_atomic_load(&t.slot[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (cur == EMPTY_ENTRY) {
+        unsigned long long cur;
+        if (claim_first) {
             cur = atomicCAS(&t.slot[h], EMPTY_ENTRY, mine);
             if (cur == EMPTY_ENTRY) return (int)h;
+        } else {
+            cur = __hip_atomic_load(&t.slot[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (cur == EMPTY_ENTRY) {
+                cur = atomicCAS(&t.slot[h], EMPTY_ENTRY, mine);
+                if (cur == EMPTY_ENTRY) return (int)h;
+            }
         }
         if ((uint32_t)(cur >> 32) == key) {
             if (mine < cur) atomicMin(&t.slot[h], mine);
@@ -145,6 +155,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
     }
     const int n1 = meta_up->front_off[S];
     const int bits = table_bits(n1 * (1 + fan));
+    const bool claim_first = n1 * (1 + fan) <= CLAIM_FIRST_MAX;
     const int groups_per_block = PART_BS / G;
     const int q = threadIdx.x % G;
     const int sub = lane_id() / G;
@@ -229,9 +240,11 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 // (with a single split the two keys are the same key, the two tables the same table,
                 // and a vertex has the same row in the mixed and in the next local frontier)
                 bool behind = false;
-                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind);
+                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind,
+                                  claim_first);
                 if (S == 1) hl = hm;
-                else if (!behind) hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error);
+                else if (!behind)
+                    hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error, nullptr, claim_first);
             }
             ent_mixed[out] = hm;
             ent_local[out] = hl;
