@@ -43,7 +43,7 @@ constexpr int PART_BS = 256;     // threads of a partition workgroup
 constexpr int PART_NK = 25;     // classes of a partition pass: 8 senders + 8 owners + 1 edge counter + 8 owners (new local)
 constexpr int PART_MAX_NB = 1024;
 constexpr unsigned long long EMPTY_ENTRY = ~0ull;
-constexpr int CLAIM_FIRST_MAX = 1 << 16;     // destinations + slots up to which inserts claim before they read
+constexpr int CLAIM_FIRST_MAX = 1 << 18;     // destinations + slots up to which inserts claim before they read
 
 // ------------------------------------------------------------------------------------------
 // small device helpers
