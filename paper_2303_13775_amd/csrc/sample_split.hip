@@ -314,9 +314,11 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
     }
     __syncthreads();
     if (threadIdx.x < F::NK) hist[threadIdx.x * gridDim.x + blockIdx.x] = s_cnt[threadIdx.x];
-    // every thread of the workgroup makes every call (side may synchronise the workgroup)
+    // every thread of the workgroup makes every call (side may synchronise the workgroup).  The
+    // side work is dealt from the last workgroup backwards: in a small layer the first workgroups
+    // hold all the elements and the rest are idle, so the two run side by side.
     const int64_t ns = f.n_side();
-    for (int64_t base = blockIdx.x * (int64_t)PART_BS; base < ns; base += (int64_t)gridDim.x * PART_BS)
+    for (int64_t base = (int64_t)(gridDim.x - 1 - blockIdx.x) * PART_BS; base < ns; base += (int64_t)gridDim.x * PART_BS)
         f.side(base + threadIdx.x, ns);
 }
 
@@ -399,8 +401,9 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
             __syncthreads();
         }
     }
+    // (dealt from the last workgroup backwards, like the count pass's side work)
     const int64_t nx = f.n_extra(o);
-    for (int64_t g = blockIdx.x * (int64_t)PART_BS + threadIdx.x; g < nx;
+    for (int64_t g = (int64_t)(gridDim.x - 1 - blockIdx.x) * PART_BS + threadIdx.x; g < nx;
          g += (int64_t)gridDim.x * PART_BS)
         f.extra(g, o);
 }
