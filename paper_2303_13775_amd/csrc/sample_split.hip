@@ -334,6 +334,16 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
     // (all loads issued before any sum) and reduces both sums with one shuffle tree
     __shared__ int s_up[GS_MAXS + 1];
     if (threadIdx.x <= GS_MAXS) s_up[threadIdx.x] = f.upper_offset(threadIdx.x);
+    // the class mask of this thread's first element does not depend on the histograms: it is
+    // fetched now and travels while they are read and summed
+    const int n = f.n();
+    const int chunk = part_chunk(n, gridDim.x);
+    const int64_t beg64 = (int64_t)blockIdx.x * chunk;
+    unsigned m_first = 0u;
+    if (beg64 < n) {
+        const int end0 = (n - (int)beg64 < chunk) ? n : (int)beg64 + chunk;
+        if ((int)beg64 + (int)threadIdx.x < end0) m_first = f.cached((int)beg64 + threadIdx.x);
+    }
     {
         constexpr int CPW = (F::NK + PART_BS / 64 - 1) / (PART_BS / 64);     // classes per wave
         constexpr int LPC = PER * 4;                                          // 64-chunk loads per class
@@ -367,16 +377,13 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
     if (threadIdx.x < F::NK) s_run[threadIdx.x] = s_base[threadIdx.x] + s_pre[threadIdx.x];
     __syncthreads();
     const PartOffs &o = s_o;
-    const int n = f.n();
-    const int chunk = part_chunk(n, gridDim.x);
-    const int64_t beg64 = (int64_t)blockIdx.x * chunk;
     if (beg64 < n) {
         const int beg = (int)beg64;
         const int end = (n - beg < chunk) ? n : beg + chunk;
         for (int tile = beg; tile < end; tile += PART_BS) {
             const int g = tile + threadIdx.x;
             const bool in = g < end;
-            const unsigned m = in ? f.cached(g) : 0u;
+            const unsigned m = tile == beg ? m_first : in ? f.cached(g) : 0u;
             int rk[F::NK];
 #pragma unroll
             for (int k = 0; k < F::NK; ++k) {
