@@ -149,6 +149,10 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 25, "partition bases");
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
+    // every table entry empty (all bits set): a batch starts on clean tables, and leaves them so
+    for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local})
+        if (rc == GSPLIT_OK && hipMemset(t->slot, 0xFF, sizeof(unsigned long long) * tab_cap) != hipSuccess)
+            rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
     if (rc == GSPLIT_OK && hipEventCreateWithFlags(&ctx->sample_done, hipEventDisableTiming) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipEventCreate failed");
     if (rc != GSPLIT_OK) {

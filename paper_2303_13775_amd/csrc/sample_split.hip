@@ -416,7 +416,6 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
 }
 
 // ---- local_front[L] = targets separated by owner, order kept ---------------------------------
-// (+ reset of the mixed-frontier table for the top sampling layer)
 struct PartTargets {
     static constexpr int NK = GS_MAXS;
     const int32_t *targets; int n_targets; const uint8_t *pmap; int S; uint32_t n_vertices;
@@ -454,13 +453,10 @@ struct PartTargets {
         front[rk[k]] = target(g);
         perm[rk[k]] = g;
     }
-    // both tables are cleared for the top sampling layer
-    __device__ int64_t n_extra(const PartOffs &) const { return 2ll << table_bits(n_targets * (1 + fan_top)); }
-    __device__ void extra(int64_t x, const PartOffs &) const {
-        const int64_t cap = 1ll << table_bits(n_targets * (1 + fan_top));
-        if (x < cap) tab_mixed.slot[x] = EMPTY_ENTRY;
-        else tab_local.slot[x - cap] = EMPTY_ENTRY;
-    }
+    // (the tables are clean when a batch starts: the last kernel of the previous batch cleared the
+    // part a top layer of max_targets targets can use, gsplit_create all of them)
+    __device__ int64_t n_extra(const PartOffs &) const { return 0; }
+    __device__ void extra(int64_t, const PartOffs &) const {}
     // the count pass is the first kernel of a batch: it clears the error flags of every level
     __device__ int64_t n_side() const { return n_levels; }
     __device__ void side(int64_t x, int64_t ns) const {
@@ -472,7 +468,6 @@ struct PartTargets {
 // the two launches of the general partition are chains of a few dependent accesses each, and a
 // launch by itself costs about as much as this kernel's work.
 constexpr int TARGETS_SMALL = 1024;
-constexpr int64_t TARGETS_SMALL_TABLE = 65536;     // entries of both tables it still resets by itself
 
 __global__ __launch_bounds__(TARGETS_SMALL) void k_targets_small(PartTargets f) {
     __shared__ int s_cnt[TARGETS_SMALL / 64][GS_MAXS];
@@ -716,7 +711,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
                                                        int32_t *__restrict__ rev_cnt,
                                                        const GsLevelMeta *__restrict__ meta_lo,
                                                        const GsLevelMeta *__restrict__ meta_up,
-                                                       int S, int fan, int fan_next) {
+                                                       int S, int fan, int fan_next, int64_t top_cap) {
     const int n1 = meta_up->front_off[S];
     const int64_t n_mixed = meta_lo->mixed_off[S];
     const int64_t n_slots = (int64_t)n1 * fan;
@@ -748,8 +743,11 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
     }
     // layers above the bottom one: both tables are cleared for the next sampling layer (this kernel
     // only reads their row arrays, through the entry indices the elements remembered)
-    if (fan_next > 0) {
-        const int64_t nr = 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next));
+    // the bottom layer: cleared for the top layer of the next batch instead (top_cap entries cover
+    // max_targets targets), so that the batch's first kernel, a single workgroup for a small batch,
+    // does not have to
+    if (fan_next > 0 || top_cap > 0) {
+        const int64_t nr = fan_next > 0 ? 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next)) : top_cap;
         for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < 2 * nr;
              x += (int64_t)gridDim.x * blockDim.x) {
             if (x < nr) tab_mixed.slot[x] = EMPTY_ENTRY;
@@ -923,11 +921,10 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
     PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
                    ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1],
                    ctx->d_meta, L + 1, ctx->tab_local};
+    int64_t top_cap = 1024;                             // = 1 << table_bits(max_targets * (1 + fan_top))
+    while (top_cap < 2 * ctx->max_targets * (1 + ctx->fan[L - 1])) top_cap <<= 1;
     {
-        const int64_t inputs = n_targets * (1 + ctx->fan[L - 1]);
-        int64_t cap = 1024;                             // = 1 << table_bits(inputs)
-        while (cap < 2 * inputs) cap <<= 1;
-        if (n_targets <= TARGETS_SMALL && 2 * cap <= TARGETS_SMALL_TABLE) {
+        if (n_targets <= TARGETS_SMALL) {
             GsTimeScope ts(ctx, "targets", -1, st);
             hipLaunchKernelGGL(k_targets_small, dim3(1), dim3(TARGETS_SMALL), 0, st, pt);
         } else {
@@ -960,7 +957,7 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
                            ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
                            B.blk_indptr, B.blk_src, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
-                           ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0);
+                           ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l == 0 ? top_cap : 0);
         }
     }
     // the bottom layer's reverse index (contexts that keep one) has no partition below it to ride on
