@@ -258,6 +258,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
 // chunks and over the chunks before it), so no launch sits between the two passes.
 // A functor F describes the elements:
 //   n()                          number of elements (read from device memory)
+//   used(k)                      whether class k can occur at all (uniform; the others are skipped)
 //   classify(g)                  count pass: bit k set <=> element g counts in class k (k < F::NK);
 //                                may leave the mask behind for the scatter pass
 //   cached(g)                    scatter pass: the same mask
@@ -307,6 +308,7 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
         }
 #pragma unroll
         for (int k = 0; k < F::NK; ++k) {
+            if (!f.used(k)) continue;               // uniform: classes of splits the context does not have
             int v = local[k];
             for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
             if (lane_id() == 0 && v) atomicAdd(&s_cnt[k], v);
@@ -387,6 +389,8 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
             int rk[F::NK];
 #pragma unroll
             for (int k = 0; k < F::NK; ++k) {
+                rk[k] = 0;
+                if (!f.used(k)) continue;           // uniform: classes of splits the context does not have
                 const uint64_t bal = __ballot((m >> k) & 1u);
                 rk[k] = __popcll(bal & lanemask_lt());
                 if (lane == 0) s_wcnt[wave][k] = __popcll(bal);
@@ -394,13 +398,14 @@ __global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__
             __syncthreads();
 #pragma unroll
             for (int k = 0; k < F::NK; ++k) {
+                if (!f.used(k)) continue;
                 int pre = s_run[k];
                 for (int w = 0; w < PART_BS / 64; ++w) pre += (w < wave) ? s_wcnt[w][k] : 0;
                 rk[k] += pre;
             }
             if (in) f.emit(g, m, rk, o);
             __syncthreads();
-            if (threadIdx.x < F::NK) {
+            if (threadIdx.x < F::NK && f.used(threadIdx.x)) {
                 int add = 0;
                 for (int w = 0; w < PART_BS / 64; ++w) add += s_wcnt[w][threadIdx.x];
                 s_run[threadIdx.x] += add;
@@ -422,6 +427,7 @@ struct PartTargets {
     int32_t *front; int32_t *perm; GsLevelMeta *meta; GsTable tab_mixed; int fan_top;
     GsLevelMeta *meta_all; int n_levels; GsTable tab_local;
     __device__ int n() const { return n_targets; }
+    __device__ bool used(int k) const { return k < S; }
     // an id outside the graph is replaced by vertex 0 and reported through the error flag (by the
     // scatter pass only: the count pass is where the flags of the previous batch are cleared)
     __device__ int32_t target(int g) const {
@@ -590,6 +596,8 @@ struct PartLayer {
     RevUp up;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return n1() * fan; }
+    // classes s and 8 + t and 17 + t exist for the splits the context has, class 16 always
+    __device__ bool used(int k) const { return k < 8 ? k < S : k < 16 ? k - 8 < S : k == 16 || k - 17 < S; }
     __device__ unsigned classify(int g) const {
         const int h = ent_mixed[n1() + g];
         unsigned m = 0u;
