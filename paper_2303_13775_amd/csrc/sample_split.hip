@@ -133,7 +133,8 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 // Every destination vertex (position i) and every sampled slot (position n1 + slot index) is
 // also entered into the mixed-frontier table under the key (vertex, split of the row) and into the
 // local-frontier table under the key vertex; the entry indices are kept in ent_mixed / ent_local
-// (destinations first, then slots; -1 for padding slots).
+// (destinations first, then slots; -1 for padding slots, -2 - index for a slot that found its
+// (vertex, split) key already there with a smaller position).
 // ------------------------------------------------------------------------------------------
 template <int G, typename IndPtrT>
 __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
@@ -233,20 +234,22 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
         }
         if (out >= 0) {
             int hm = -1, hl = -1;
+            bool behind = false;
             if (key_v >= 0) {
                 // a slot that finds its (vertex, split) key with a smaller position is not the first
                 // occurrence in its split, let alone in the whole stream: nothing will ask for its
                 // entry in the vertex table, so it does not make one
                 // (with a single split the two keys are the same key, the two tables the same table,
                 // and a vertex has the same row in the mixed and in the next local frontier)
-                bool behind = false;
                 hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind,
                                   claim_first);
                 if (S == 1) hl = hm;
                 else if (!behind)
                     hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error, nullptr, claim_first);
             }
-            ent_mixed[out] = hm;
+            // a slot known not to be the first of its key says so in its entry index (-2 - index):
+            // the partition then classifies it without looking the entry up again
+            ent_mixed[out] = (behind && out >= n1) ? -2 - hm : hm;
             ent_local[out] = hl;
         }
     }
@@ -600,7 +603,7 @@ struct PartLayer {
     __device__ bool used(int k) const { return k < 8 ? k < S : k < 16 ? k - 8 < S : k == 16 || k - 17 < S; }
     __device__ unsigned classify(int g) const {
         const int h = ent_mixed[n1() + g];
-        unsigned m = 0u;
+        unsigned m = h < -1 ? 1u << 16 : 0u;      // h < -1: a valid slot the sampler saw behind another
         if (h >= 0) {
             const int32_t id = nbr[g];
             const uint32_t pos = (uint32_t)(n1() + g);
@@ -737,8 +740,9 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
         } else {
             const int64_t g = x - n_mixed - n1;
-            const int h = ent_mixed[n1 + g];
-            if (h < 0) continue;
+            int h = ent_mixed[n1 + g];
+            if (h == -1) continue;
+            if (h < -1) h = -2 - h;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
             const int s = split_of(meta_up->front_off, S, i);
             const int mrow = tab_mixed.row[h];
