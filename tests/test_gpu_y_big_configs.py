@@ -75,6 +75,13 @@ def _run(w, dev, iters=(0, 1)):
         e_b = max(max(e) for e in errs)
         say(f"max rel err: logits {e_f:.2e}, gradients {e_b:.2e}")
         assert e_f < TOL_F32 and e_b < TOL_F32
+        # the same gradients as whole matrices, without the allowance for undecidable ReLU decisions
+        # (a few flipped decisions among millions of rows do not move a norm)
+        fro = lambda x, o: float(np.linalg.norm(x.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300))
+        norms = [(fro(gws[l], obw.gw_self[l]), fro(gwn[l], obw.gw_neigh[l]), fro(gb[l], obw.gbias[l]))
+                 for l in range(w.n_layers)]
+        say("relative Frobenius errors per layer: " + str([tuple(f"{x:.1e}" for x in e) for e in norms]))
+        assert max(max(e) for e in norms) < TOL_F32
     ctx.close()
 
 
@@ -158,4 +165,65 @@ def test_large_gat_statistics_and_counts_full_size():
                 R.max_rel_err(gb[l].cpu().numpy().reshape(-1), obw.gbias[l].reshape(-1)))
         say(f"layer {l} (w, a_src, a_dst, bias) errors: " + ", ".join(f"{x:.1e}" for x in errs))
         assert max(errs) < TOL_F32, l
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_splits", [1, 8])
+def test_sweep_bf16_full_size(n_splits):
+    """The split sweep of `bench.py --workload sweep`: the large graph, 8192 targets, four layers of
+    fanout 10, bf16 storage, with one split (both keys of a vertex are the same key and one table
+    serves) and with eight (every class of the partition in use).  Every integer output of the
+    sampled batch is compared, and the bf16 forward pass with the loss gradient's backward pass
+    against the oracle that rounds the same stored values."""
+    from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16
+    from test_gpu_parity import FLOOR_BF16, TOL_BF16
+    dev = torch.device("cuda:0")
+    w = workloads.large(device=dev, n_splits=n_splits, feat_dtype=torch.bfloat16, batch=8192,
+                        fanouts=(10, 10, 10, 10), dims=(128, 256, 256, 256, 172), progress=say)
+    say(str(w.describe()))
+    ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
+    host = dict(indptr=w.indptr.cpu().numpy(), indices=w.indices.cpu().numpy(), pmap=w.pmap.cpu().numpy())
+    params = SageParams(w.dims, w.w_self, w.w_neigh, w.bias, dtype=GSPLIT_BF16)
+    op = R.SageParams([t.cpu().numpy() for t in w.w_self], [t.cpu().numpy() for t in w.w_neigh],
+                      [t.cpu().numpy() for t in w.bias])
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=torch.bfloat16, device=dev)
+    logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+    gws = [torch.empty_like(t) for t in w.w_self]
+    gwn = [torch.empty_like(t) for t in w.w_neigh]
+    gb = [torch.empty_like(t) for t in w.bias]
+    it = 1
+    tg = w.targets(it)
+    ctx.gsplit_sample_split(tg, 777, it)
+    ctx.gsplit_gather_features(w.feat, x0)
+    ctx.gsplit_sage_fwd(params, x0, logits)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    ob = R.sp_sample(host["indptr"], host["indices"], host["pmap"], w.n_splits, w.fanouts, tg.cpu().numpy(), 777, it)
+    say(f"oracle sampled the batch in {time.time() - t0:.1f} s; rows/level {[len(ob.local_cat(l)) for l in range(w.n_layers + 1)]}")
+    assert_batch_equal(ctx.fetch_batch(), ob, w.n_splits, w.n_layers)
+    ids = torch.from_numpy(ob.local_cat(0)).long().to(dev)
+    assert torch.equal(x0[:ids.numel()].view(torch.int16), w.feat[ids].view(torch.int16))
+    t0 = time.time()
+    of = R.sp_forward(ob, w.feat[ids].float().cpu().numpy(), op, store_bf16=True)
+    y = w.labels[torch.from_numpy(tg.cpu().numpy()[ob.target_perm]).to(dev).long()].cpu().numpy()
+    _, g = R.softmax_xent(of.logits, y)
+    ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
+    torch.cuda.synchronize()
+    obw = R.sp_backward(ob, of, op, g, store_bf16=True)
+    sws, swn, sb, _ = R.relu_decision_slack(ob, of, op, obw, rel_tau=1e-3, store_bf16=True)
+    say(f"oracle forward/backward in {time.time() - t0:.1f} s")
+    e_f = R.max_rel_err(logits.cpu().numpy(), of.logits, floor=FLOOR_BF16)
+    errs = [(R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16),
+             R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16),
+             R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16)) for l in range(w.n_layers)]
+    say(f"max rel err: logits {e_f:.2e}; per layer " + str([tuple(f"{x:.1e}" for x in e) for e in errs]))
+    assert e_f < TOL_BF16 and max(max(e) for e in errs) < TOL_BF16
+    # With millions of rows the undecidable ReLU decisions explain most elementwise differences of
+    # the lower layers' gradients, so those are also compared as whole matrices, without that
+    # allowance: a handful of flipped decisions does not move a norm over millions of rows.
+    fro = lambda a, o: float(np.linalg.norm(a.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300))
+    norms = [(fro(gws[l], obw.gw_self[l]), fro(gwn[l], obw.gw_neigh[l]), fro(gb[l], obw.gbias[l]))
+             for l in range(w.n_layers)]
+    say("relative Frobenius errors per layer: " + str([tuple(f"{x:.1e}" for x in e) for e in norms]))
+    assert max(max(e) for e in norms) < TOL_BF16
     ctx.close()
