@@ -160,6 +160,13 @@ def test_bf16_path_medium_full_size(medium):
         assert R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_self", l)
         assert R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_neigh", l)
         assert R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("gbias", l)
+    # and as whole matrices without the allowance for undecidable ReLU decisions, which at bfloat16
+    # resolution covers a good part of the elementwise differences
+    for l in range(w.n_layers):
+        for name, a, o in (("gw_self", gws[l], obw.gw_self[l]), ("gw_neigh", gwn[l], obw.gw_neigh[l]),
+                           ("gbias", gb[l], obw.gbias[l])):
+            rel = np.linalg.norm(a.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300)
+            assert rel < TOL_BF16, (name, l, rel)
     ctx.close()
 
 
