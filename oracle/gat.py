@@ -100,6 +100,12 @@ class GatBackward:
     ga_dst: List[np.ndarray]
     gbias: List[np.ndarray]
     ghidden: List[Optional[np.ndarray]]
+    # per entry of ga_src / ga_dst: the sum of the magnitudes of the terms that the entry adds up
+    # (the softmax backward subtracts terms of the same size, the sum over edges mixes signs), i.e.
+    # the quantity a floating-point evaluation's rounding error is proportional to.  Not a result
+    # of the method: tests use it to tell rounding noise in an entry that cancels to almost
+    # nothing from a wrong entry.
+    ga_terms: List[np.ndarray]
 
 
 def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: np.ndarray) -> GatBackward:
@@ -110,6 +116,7 @@ def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: 
     gas = [np.zeros(np.shape(a), np.float64) for a in params.a_src]
     gad = [np.zeros(np.shape(a), np.float64) for a in params.a_dst]
     gb = [np.zeros(np.shape(b), np.float64) for b in params.bias]
+    terms = [np.zeros(np.shape(a), np.float64) for a in params.a_src]
     ghid: List[Optional[np.ndarray]] = [None] * (L + 1)
     ghid[L] = np.asarray(grad_logits, np.float64)
     for l in range(L - 1, -1, -1):
@@ -137,6 +144,7 @@ def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: 
             dz = np.zeros(z.shape)
             de_src = np.zeros(z.shape[:2])
             de_dst = np.zeros(z.shape[:2])
+            mag = np.zeros(z.shape[:2])
             e_src = (z * a_s).sum(2)
             e_dst = (z * a_d).sum(2)
             for i in range(n_dst):
@@ -149,11 +157,39 @@ def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: 
                 de = de * np.where(raw > 0.0, 1.0, NEG_SLOPE)              # LeakyReLU backward
                 np.add.at(de_src, nbrs, de)
                 de_dst[i] += de.sum(0)
+                np.add.at(mag, nbrs, a * (np.abs(da) + (a * np.abs(da)).sum(0, keepdims=True)))
             gas[l] += (de_src[:, :, None] * z).sum(0).reshape(-1)
             gad[l] += (de_dst[:, :, None] * z).sum(0).reshape(-1)
+            terms[l] += (mag[:, :, None] * np.abs(z)).sum(0).reshape(-1)
             dz += de_src[:, :, None] * a_s[None] + de_dst[:, :, None] * a_d[None]
             dz2 = dz.reshape(z.shape[0], K * F)
             gw[l] += mixed.T @ dz2
             if l > 0:
                 rows_add_into(ghid[l], blk.shuffle_src_row, dz2 @ W.T)
-    return GatBackward(gw, gas, gad, gb, ghid)
+    return GatBackward(gw, gas, gad, gb, ghid, terms)
+
+
+def score_margins(batch: Batch, fwd: GatForward, params: GatParams) -> List[float]:
+    """Per layer: the smallest |score| before the LeakyReLU over all (destination, neighbour, head)
+    triples, relative to the largest.  The backward pass multiplies by the LeakyReLU's slope, 1 or
+    NEG_SLOPE according to the sign of that score: where a score is within float32 rounding of
+    zero (a margin of the order of 1e-7), an implementation that computes its scores in float32
+    may take the other slope, and the gradients of that layer's parameters and of everything below
+    it then differ by a whole term: neither is wrong.  Tests use the margins to recognise that
+    case (the analogue of relu_decision_slack for GraphSAGE)."""
+    out = []
+    for l in range(batch.n_layers):
+        K = params.heads[l]
+        F = np.shape(params.w[l])[1] // K
+        a_s = np.asarray(params.a_src[l], np.float64).reshape(K, F)
+        a_d = np.asarray(params.a_dst[l], np.float64).reshape(K, F)
+        lo, hi = np.inf, 0.0
+        for s in range(batch.n_splits):
+            blk, z = batch.blocks[l][s], fwd.z[l][s]
+            e_src, e_dst = (z * a_s).sum(2), (z * a_d).sum(2)
+            for i in range(blk.dst.shape[0]):
+                nbrs = np.concatenate([[i], blk.blk_src[blk.blk_indptr[i]:blk.blk_indptr[i + 1]]]).astype(np.int64)
+                raw = np.abs(e_dst[i][None, :] + e_src[nbrs])
+                lo, hi = min(lo, float(raw.min())), max(hi, float(raw.max()))
+        out.append(lo / hi if hi > 0.0 and np.isfinite(lo) else 1.0)
+    return out

@@ -49,12 +49,13 @@ def _run(w, heads, dev, seed, it, n_splits=None, pmap=None, batch_targets=None):
     torch.cuda.synchronize()
     obw = G.gat_backward(ob, of, op, g)
     res = dict(logits=logits.cpu().numpy(), gw=[t.cpu().numpy() for t in gw], gas=[t.cpu().numpy() for t in gas],
-               gad=[t.cpu().numpy() for t in gad], gb=[t.cpu().numpy() for t in gb], of=of, ob=obw)
+               gad=[t.cpu().numpy() for t in gad], gb=[t.cpu().numpy() for t in gb], of=of, ob=obw,
+               margins=G.score_margins(ob, of, op))
     ctx.close()
     return res
 
 
-def attention_grad_err(a, o, o_src, o_dst) -> float:
+def attention_grad_err(a, o, o_src, o_dst, terms=None) -> float:
     """Error of an attention-vector gradient, judged against the common scale of the layer's two
     attention gradients: d a_dst sums the very terms of d a_src, but over the neighbours of a
     destination first, where they cancel (with every score in the linear part of the LeakyReLU
@@ -62,17 +63,43 @@ def attention_grad_err(a, o, o_src, o_dst) -> float:
     so its entries are small differences of terms of the size of d a_src."""
     a = np.asarray(a, np.float64).reshape(-1); o = np.asarray(o, np.float64).reshape(-1)
     scale = np.maximum(np.abs(o), 1e-2 * max(np.abs(o_src).max(), np.abs(o_dst).max()))
-    return float((np.abs(a - o) / np.where(scale == 0, 1.0, scale)).max())
+    # Both gradients are sums of terms that cancel (inside the softmax backward, then over the
+    # edges): with few neighbours and near-uniform attention d a_src cancels to 10^-4 of its terms
+    # as well.  A float32 sum carries a rounding error proportional to the magnitudes summed
+    # (|fl(sum x) - sum x| <= gamma_n sum |x|), which the oracle reports per entry; that much of the
+    # difference is rounding, whatever the size of the result (measured: up to 2 units of 2^-24).
+    noise = 0.0 if terms is None else 8.0 * 2.0 ** -24 * np.asarray(terms, np.float64).reshape(-1)
+    return float((np.maximum(np.abs(a - o) - noise, 0.0) / np.where(scale == 0, 1.0, scale)).max())
 
 
-def _check(r, L):
+# a LeakyReLU argument closer to zero than this (relative to the layer's largest) is not decided
+# by a float32 evaluation of the scores
+UNDECIDED_MARGIN = 2e-6
+
+
+def _check(r, L, allow_undecided=False):
+    """Logits and every parameter gradient against the oracle.  allow_undecided: a gradient that
+    misses the tolerance is excused when its layer, or one above it, holds a LeakyReLU argument
+    within float32 rounding of zero (oracle score_margins): the two sides may then have taken
+    different slopes, and the gradients of that layer and of everything below it differ by a whole
+    term without either being wrong.  About one drawn configuration in a thousand does; the named
+    cases and the kept random configurations are checked without the excuse."""
     assert R.max_rel_err(r["logits"], r["of"].logits) < TOL_F32, "logits"
+    undecided = [l for l in range(L) if r["margins"][l] < UNDECIDED_MARGIN]
+    excused_below = max(undecided) + 1 if (undecided and allow_undecided) else 0
     for l in range(L):
         o_src, o_dst = r["ob"].ga_src[l], r["ob"].ga_dst[l]
-        assert R.max_rel_err(r["gw"][l], r["ob"].gw[l]) < TOL_F32, ("gw", l)
-        assert attention_grad_err(r["gas"][l], o_src, o_src, o_dst) < TOL_F32, ("ga_src", l)
-        assert attention_grad_err(r["gad"][l], o_dst, o_src, o_dst) < TOL_F32, ("ga_dst", l)
-        assert R.max_rel_err(r["gb"][l].reshape(-1), r["ob"].gbias[l].reshape(-1)) < TOL_F32, ("gbias", l)
+        terms = r["ob"].ga_terms[l]
+        errs = {"gw": R.max_rel_err(r["gw"][l], r["ob"].gw[l]),
+                "ga_src": attention_grad_err(r["gas"][l], o_src, o_src, o_dst, terms),
+                "ga_dst": attention_grad_err(r["gad"][l], o_dst, o_src, o_dst, terms),
+                "gbias": R.max_rel_err(r["gb"][l].reshape(-1), r["ob"].gbias[l].reshape(-1))}
+        bad = {k: v for k, v in errs.items() if not v < TOL_F32}
+        if bad and l < excused_below:
+            print(f"[gat] layer {l}: {bad} excused, layers {undecided} hold a score within float32 rounding of zero "
+                  f"(margins {r['margins']})", flush=True)
+            continue
+        assert not bad, (l, bad)
 
 
 # name -> (workload, heads): widths that take the 16-byte and the scalar lane layouts, head counts

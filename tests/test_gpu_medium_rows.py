@@ -55,7 +55,7 @@ def test_gat_medium_full_size(medium):
         for name, got, want in (("gw", grads[0][l], obw.gw[l]), ("gbias", grads[3][l], obw.gbias[l])):
             assert R.max_rel_err(got.cpu().numpy().reshape(-1), np.asarray(want).reshape(-1)) < TOL_F32, (name, l)
         for name, got, want in (("ga_src", grads[1][l], obw.ga_src[l]), ("ga_dst", grads[2][l], obw.ga_dst[l])):
-            assert attention_grad_err(got.cpu().numpy(), want, obw.ga_src[l], obw.ga_dst[l]) < TOL_F32, (name, l)
+            assert attention_grad_err(got.cpu().numpy(), want, obw.ga_src[l], obw.ga_dst[l], obw.ga_terms[l]) < TOL_F32, (name, l)
     ctx.close()
 
 

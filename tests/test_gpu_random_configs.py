@@ -47,7 +47,9 @@ def draw(k: int):
     return w, heads
 
 
-@pytest.mark.parametrize("k", range(N_CONFIGS))
+# 261: a top layer of fanout 2 under near-uniform attention, where the gradient of a_src cancels to
+# 10^-4 of the terms it sums (found by drawing more configurations than this file keeps)
+@pytest.mark.parametrize("k", list(range(N_CONFIGS)) + [261])
 def test_random_configuration(k):
     dev = _dev()
     w, heads = draw(k)
@@ -68,7 +70,8 @@ def test_random_configuration(k):
         assert R.grad_err(r["gws"][l], r["ob"].gw_self[l], sws[l]) < TOL_F32, ("sage gw_self", l)
         assert R.grad_err(r["gwn"][l], r["ob"].gw_neigh[l], swn[l]) < TOL_F32, ("sage gw_neigh", l)
         assert R.grad_err(r["gb"][l], r["ob"].gbias[l], sb[l]) < TOL_F32, ("sage gbias", l)
-    check_gat(run_gat(w, heads, dev, seed=500 + k, it=1), w.n_layers)
+    # (configurations beyond the kept ones, drawn by a longer search, may hold an undecidable slope)
+    check_gat(run_gat(w, heads, dev, seed=500 + k, it=1), w.n_layers, allow_undecided=k >= N_CONFIGS and k != 261)
     if any(d % 4 for d in w.dims[:-1]):
         return                     # the bf16 path takes input and hidden widths that are multiples of 4
     r = _run_fwd_bwd(w, dev, seed=500 + k, it=0, bf16=True)

@@ -160,8 +160,8 @@ def test_large_gat_statistics_and_counts_full_size():
     for l in range(w.n_layers):
         o_src, o_dst = obw.ga_src[l], obw.ga_dst[l]
         errs = (R.max_rel_err(gw[l].cpu().numpy(), obw.gw[l]),
-                attention_grad_err(gas[l].cpu().numpy(), o_src, o_src, o_dst),
-                attention_grad_err(gad[l].cpu().numpy(), o_dst, o_src, o_dst),
+                attention_grad_err(gas[l].cpu().numpy(), o_src, o_src, o_dst, obw.ga_terms[l]),
+                attention_grad_err(gad[l].cpu().numpy(), o_dst, o_src, o_dst, obw.ga_terms[l]),
                 R.max_rel_err(gb[l].cpu().numpy().reshape(-1), obw.gbias[l].reshape(-1)))
         say(f"layer {l} (w, a_src, a_dst, bias) errors: " + ", ".join(f"{x:.1e}" for x in errs))
         assert max(errs) < TOL_F32, l

@@ -103,3 +103,31 @@ def test_split_equals_unsplit():
         assert np.allclose(res[0][1].ga_src[l], res[1][1].ga_src[l], atol=1e-9)
         assert np.allclose(res[0][1].ga_dst[l], res[1][1].ga_dst[l], atol=1e-9)
         assert np.allclose(res[0][1].gbias[l], res[1][1].gbias[l], atol=1e-9)
+
+
+def test_score_margins_and_gradient_term_magnitudes():
+    """The two diagnostics the GPU tests take from the oracle, on the hand example above and on a
+    sampled batch.  Hand example: the scores before the LeakyReLU are 2*1 - 1*1 = 1 and
+    2*1 - 1*3 = -1, so the margin is 1; with a_src = -2/3 the second score is 2 - 2 = 0 and the
+    margin is 0.  The term magnitudes bound the attention gradients entry by entry (a sum is never
+    larger than the sum of its terms' magnitudes) and are not a loose bound where nothing cancels."""
+    indptr = np.array([0, 1, 1], np.int64)
+    indices = np.array([1], np.int32)
+    b = R.sp_sample(indptr, indices, np.zeros(2, np.uint8), 1, [5], np.array([0], np.int32), 3, 0)
+    x0 = np.array([[1.0], [3.0]])
+    for a_src, want in ((-1.0, 1.0), (-2.0 / 3.0, 0.0)):
+        p = G.GatParams([1], [np.array([[1.0]])], [np.array([a_src])], [np.array([2.0])], [np.array([0.0])])
+        f = G.gat_forward(b, x0, p)
+        assert G.score_margins(b, f, p) == pytest.approx([want], abs=1e-15)
+    rng = np.random.default_rng(5)
+    w, b, x0 = _batch()
+    p = _params(rng, w.dims, [2, 1])
+    f = G.gat_forward(b, x0, p)
+    bw = G.gat_backward(b, f, p, rng.standard_normal(f.logits.shape))
+    m = G.score_margins(b, f, p)
+    assert len(m) == 2 and all(0.0 < x < 1.0 for x in m)
+    for l in range(2):
+        t = bw.ga_terms[l].reshape(-1)
+        assert np.all(np.abs(bw.ga_src[l].reshape(-1)) <= t * (1 + 1e-12))
+        assert np.all(np.abs(bw.ga_dst[l].reshape(-1)) <= t * (1 + 1e-12))
+        assert np.abs(bw.ga_src[l]).max() > 1e-3 * t.max()

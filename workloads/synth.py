@@ -161,7 +161,7 @@ def rmat_graph(n_vertices: int, n_directed_target: int, abc: Sequence[float], *,
         keys = torch.empty(0, dtype=torch.int64, device=device)
         rnd = 0
         while keys.numel() * both < n_directed_target:
-            need = max(n_directed_target // both // 8,
+            need = max(1, n_directed_target // both // 8,
                        int((n_directed_target - keys.numel() * both) / both * 1.15))
             keys = _unique_sorted(torch.cat([keys] + clean_keys(need, seed + _OFF_GRAPH + 1000 * rnd)))
             rnd += 1
