@@ -108,9 +108,14 @@ class GatBackward:
     ga_terms: List[np.ndarray]
 
 
-def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: np.ndarray) -> GatBackward:
+def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: np.ndarray,
+                 slope_positive=None) -> GatBackward:
     """Top layer down; gradients of remote rows go back through the reversed shuffle index; weight
-    gradients are summed over the splits.  No gradient for the input features."""
+    gradients are summed over the splits.  No gradient for the input features.
+
+    slope_positive (optional): slope_positive[l][s][i], a boolean array [1 + cnt_i, K], replaces
+    [score > 0] in the LeakyReLU derivative of destination i (see conditioned_slopes); None keeps
+    this pass's own decisions."""
     S, L = batch.n_splits, batch.n_layers
     gw = [np.zeros(np.shape(w), np.float64) for w in params.w]
     gas = [np.zeros(np.shape(a), np.float64) for a in params.a_src]
@@ -154,7 +159,8 @@ def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: 
                 da = (z[nbrs] * dagg[i][None, :, :]).sum(2)                # [n, K]
                 de = a * (da - (a * da).sum(0, keepdims=True))             # softmax backward
                 raw = e_dst[i][None, :] + e_src[nbrs]
-                de = de * np.where(raw > 0.0, 1.0, NEG_SLOPE)              # LeakyReLU backward
+                pos = raw > 0.0 if slope_positive is None else slope_positive[l][s][i]
+                de = de * np.where(pos, 1.0, NEG_SLOPE)                    # LeakyReLU backward
                 np.add.at(de_src, nbrs, de)
                 de_dst[i] += de.sum(0)
                 np.add.at(mag, nbrs, a * (np.abs(da) + (a * np.abs(da)).sum(0, keepdims=True)))
@@ -169,27 +175,55 @@ def gat_backward(batch: Batch, fwd: GatForward, params: GatParams, grad_logits: 
     return GatBackward(gw, gas, gad, gb, ghid, terms)
 
 
-def score_margins(batch: Batch, fwd: GatForward, params: GatParams) -> List[float]:
-    """Per layer: the smallest |score| before the LeakyReLU over all (destination, neighbour, head)
-    triples, relative to the largest.  The backward pass multiplies by the LeakyReLU's slope, 1 or
-    NEG_SLOPE according to the sign of that score: where a score is within float32 rounding of
-    zero (a margin of the order of 1e-7), an implementation that computes its scores in float32
-    may take the other slope, and the gradients of that layer's parameters and of everything below
-    it then differ by a whole term: neither is wrong.  Tests use the margins to recognise that
-    case (the analogue of relu_decision_slack for GraphSAGE)."""
-    out = []
+def conditioned_slopes(batch: Batch, fwd: GatForward, params: GatParams, device_terms, rel_tau: float):
+    """LeakyReLU slope decisions for a backward pass that is compared with a device's, conditioned
+    on the decisions the device took where a score is zero to the rounding of its forward pass.
+
+    The derivative of the LeakyReLU is 1 or NEG_SLOPE according to the sign of the score
+    a_dst . z_i + a_src . z_j.  This oracle forms it in float64; a device that forms it in float32
+    may land on the other side of zero when |score| <= rel_tau * (largest |score| of the layer), and
+    the gradients of that layer and of everything below it then differ by a whole term without
+    either being wrong.  There the device's decision is taken: device_terms[l] = (src, dst), the two
+    float32 terms it stored per row of local_cat[l] and head ([rows, K] each), whose float32 sum is
+    the score it used.  Everywhere else the oracle's own sign stands; a disagreement outside the
+    band is a wrong result on the device and is counted, not excused.
+
+    Returns (slope_positive, report): slope_positive[l][s][i] boolean [1 + cnt_i, K]; report = per
+    layer (scores in the band, of which the device decided the other way, disagreements outside)."""
+    out, report = [], []
     for l in range(batch.n_layers):
         K = params.heads[l]
         F = np.shape(params.w[l])[1] // K
         a_s = np.asarray(params.a_src[l], np.float64).reshape(K, F)
         a_d = np.asarray(params.a_dst[l], np.float64).reshape(K, F)
-        lo, hi = np.inf, 0.0
+        d_src = np.asarray(device_terms[l][0], np.float32)
+        d_dst = np.asarray(device_terms[l][1], np.float32)
+        raws, devs = [], []
+        hi = 0.0
         for s in range(batch.n_splits):
             blk, z = batch.blocks[l][s], fwd.z[l][s]
             e_src, e_dst = (z * a_s).sum(2), (z * a_d).sum(2)
+            rows = blk.shuffle_src_row            # row of local_cat[l] behind every mixed row
+            r_s, d_s = [], []
             for i in range(blk.dst.shape[0]):
                 nbrs = np.concatenate([[i], blk.blk_src[blk.blk_indptr[i]:blk.blk_indptr[i + 1]]]).astype(np.int64)
-                raw = np.abs(e_dst[i][None, :] + e_src[nbrs])
-                lo, hi = min(lo, float(raw.min())), max(hi, float(raw.max()))
-        out.append(lo / hi if hi > 0.0 and np.isfinite(lo) else 1.0)
-    return out
+                raw = e_dst[i][None, :] + e_src[nbrs]
+                dev = d_dst[rows[i]][None, :] + d_src[rows[nbrs]]          # float32 sum, as on the device
+                hi = max(hi, float(np.abs(raw).max()))
+                r_s.append(raw); d_s.append(dev)
+            raws.append(r_s); devs.append(d_s)
+        n_band = n_flip = n_bad = 0
+        layer = []
+        for r_s, d_s in zip(raws, devs):
+            per = []
+            for raw, dev in zip(r_s, d_s):
+                own, theirs = raw > 0.0, dev > np.float32(0.0)
+                band = np.abs(raw) <= rel_tau * hi
+                n_band += int(band.sum())
+                n_flip += int((band & (own != theirs)).sum())
+                n_bad += int((~band & (own != theirs)).sum())
+                per.append(np.where(band, theirs, own))
+            layer.append(per)
+        out.append(layer)
+        report.append((n_band, n_flip, n_bad))
+    return out, report

@@ -440,10 +440,13 @@ class Backward:
 
 
 def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.ndarray,
-                store_bf16: bool = False) -> Backward:
+                store_bf16: bool = False, relu_mask=None) -> Backward:
     """Top layer down.  Gradients of remote rows travel back through the same shuffle index,
     reversed; weight gradients are summed over splits (the gradient aggregation step).  No
-    gradient is formed for the input features."""
+    gradient is formed for the input features.
+
+    relu_mask (optional): relu_mask[l][s], a boolean array like fwd.z[l][s], replaces [z > 0] of
+    layer l (see conditioned_relu_masks); None keeps this pass's own decisions."""
     S, L = batch.n_splits, batch.n_layers
     q = (lambda a: to_bf16_rne(np.asarray(a, np.float32)).astype(np.float64)) if store_bf16 \
         else (lambda a: np.asarray(a, np.float64))
@@ -461,7 +464,10 @@ def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.
             blk = batch.blocks[l][s]
             n_dst = blk.dst.shape[0]
             dH = ghid[l + 1][off[s]:off[s + 1]]
-            dZ = dH if l == L - 1 else dH * (fwd.z[l][s] > 0.0)
+            if l == L - 1:
+                dZ = dH
+            else:
+                dZ = dH * (fwd.z[l][s] > 0.0 if relu_mask is None else relu_mask[l][s])
             mixed, M = fwd.mixed[l][s], fwd.mean[l][s]
             # with bf16 storage every matrix product takes bf16 operands, so dZ enters the
             # weight-gradient and the input-gradient products rounded like the other operands
@@ -478,65 +484,43 @@ def sp_backward(batch: Batch, fwd: Forward, params: SageParams, grad_logits: np.
     return Backward(gws, gwn, gb, ghid)
 
 
-def relu_decision_slack(batch: Batch, fwd: Forward, params: SageParams, bwd: Backward,
-                        rel_tau: float = 1e-5, store_bf16: bool = False):
-    """How much each weight gradient may legitimately differ because of ReLU decisions that the
-    precision of the forward pass cannot settle.
+def conditioned_relu_masks(batch: Batch, fwd: Forward, device_act: Sequence[Optional[np.ndarray]],
+                           rel_tau: float):
+    """ReLU decisions for a backward pass that is compared with a device's, conditioned on the
+    decisions the device took where the sign of a pre-activation is below the forward pass's
+    rounding noise.
 
-    The backward pass multiplies by [z > 0].  A pre-activation with |z| <= rel_tau * max|z| of its
-    layer is below the rounding noise of a float32 (or bfloat16-input) forward pass, so an
-    implementation that keeps its activations in that precision may take the decision either way
-    and both gradients are valid.  This returns a first-order elementwise bound on the resulting
-    change of (gw_self, gw_neigh, gbias): the backward recursion run on absolute values, where an
-    undecided entry contributes |dH| (it can flip entirely) and a decided one passes the
-    uncertainty it received from above.  Tests add it to their tolerance."""
+    The backward pass multiplies by [z > 0].  This oracle forms z in float64, a device in float32
+    (or from bfloat16 operands): where |z| <= rel_tau * max|z| of the layer the two may legitimately
+    land on different sides of zero, and one flipped decision moves a whole gradient row.  There
+    the device's own decision is taken (device_act[l + 1] > 0: the activations it stored for
+    local_cat[l + 1], rows in the order of that level); everywhere else the oracle's.  A
+    disagreement outside the band is a wrong result on the device and is counted, not excused.
+
+    Returns (masks, report): masks[l][s] a boolean array like fwd.z[l][s] for l < L - 1 (None for the
+    last layer, which has no activation); report = per layer (entries in the band, of which the
+    device decided the other way, disagreements outside the band)."""
     S, L = batch.n_splits, batch.n_layers
-    q = (lambda a: to_bf16_rne(np.asarray(a, np.float32)).astype(np.float64)) if store_bf16 \
-        else (lambda a: np.asarray(a, np.float64))
-    sws = [np.zeros(w.shape, np.float64) for w in params.w_self]
-    swn = [np.zeros(w.shape, np.float64) for w in params.w_neigh]
-    sb = [np.zeros(b.shape, np.float64) for b in params.bias]
-    u_hid: List[Optional[np.ndarray]] = [None] * (L + 1)
-    u_hid[L] = np.zeros(fwd.hidden[L].shape, np.float64)
-    n_undecided = 0
-    for l in range(L - 1, -1, -1):
-        Ws, Wn = np.abs(q(params.w_self[l])), np.abs(q(params.w_neigh[l]))
+    masks: List[Optional[List[np.ndarray]]] = [None] * L
+    report = []
+    for l in range(L - 1):
         off = batch.local_off(l + 1)
-        if l > 0:
-            u_hid[l] = np.zeros(fwd.hidden[l].shape, np.float64)
         zmax = max([float(np.abs(z).max()) if z.size else 0.0 for z in fwd.z[l]] + [0.0])
+        act = np.asarray(device_act[l + 1])
+        assert act.shape[0] == off[-1], "device activations do not match the level's row count"
+        masks[l] = []
+        n_band = n_flip = n_bad = 0
         for s in range(S):
-            blk = batch.blocks[l][s]
-            n_dst = blk.dst.shape[0]
-            dH = np.abs(bwd.ghidden[l + 1][off[s]:off[s + 1]])
-            uH = u_hid[l + 1][off[s]:off[s + 1]]
-            Z = fwd.z[l][s]
-            if l == L - 1:
-                u_dZ = uH
-            else:
-                undecided = np.abs(Z) <= rel_tau * zmax
-                n_undecided += int(undecided.sum())
-                u_dZ = np.where(undecided, dH + uH, (Z > 0.0) * uH)
-            mixed, M = np.abs(fwd.mixed[l][s]), np.abs(fwd.mean[l][s])
-            sws[l] += mixed[:n_dst].T @ u_dZ
-            swn[l] += M.T @ u_dZ
-            sb[l] += u_dZ.sum(0)
-            if l > 0:
-                u_mixed = mean_aggregate_adjoint(blk.blk_indptr, blk.blk_src, u_dZ @ Wn.T, mixed.shape[0])
-                u_mixed[:n_dst] += u_dZ @ Ws.T
-                rows_add_into(u_hid[l], blk.shuffle_src_row, u_mixed)
-    return sws, swn, sb, n_undecided
-
-
-def grad_err(a: np.ndarray, o: np.ndarray, slack: np.ndarray, floor: float = 1e-2) -> float:
-    """max_rel_err after the part of |a - o| that undecidable ReLU decisions may explain
-    (relu_decision_slack) has been taken off."""
-    a = np.asarray(a, np.float64); o = np.asarray(o, np.float64)
-    if o.size == 0:
-        return 0.0
-    scale = np.maximum(np.abs(o), floor * np.abs(o).max())
-    scale = np.where(scale == 0, 1.0, scale)
-    return float((np.maximum(np.abs(a - o) - slack, 0.0) / scale).max())
+            z = fwd.z[l][s]
+            own = z > 0.0
+            dev = act[off[s]:off[s + 1]] > 0
+            band = np.abs(z) <= rel_tau * zmax
+            n_band += int(band.sum())
+            n_flip += int((band & (own != dev)).sum())
+            n_bad += int((~band & (own != dev)).sum())
+            masks[l].append(np.where(band, dev, own))
+        report.append((n_band, n_flip, n_bad))
+    return masks, report
 
 
 def softmax_xent(logits: np.ndarray, labels: np.ndarray):

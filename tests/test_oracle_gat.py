@@ -105,27 +105,83 @@ def test_split_equals_unsplit():
         assert np.allclose(res[0][1].gbias[l], res[1][1].gbias[l], atol=1e-9)
 
 
-def test_score_margins_and_gradient_term_magnitudes():
-    """The two diagnostics the GPU tests take from the oracle, on the hand example above and on a
-    sampled batch.  Hand example: the scores before the LeakyReLU are 2*1 - 1*1 = 1 and
-    2*1 - 1*3 = -1, so the margin is 1; with a_src = -2/3 the second score is 2 - 2 = 0 and the
-    margin is 0.  The term magnitudes bound the attention gradients entry by entry (a sum is never
-    larger than the sum of its terms' magnitudes) and are not a loose bound where nothing cancels."""
-    indptr = np.array([0, 1, 1], np.int64)
-    indices = np.array([1], np.int32)
-    b = R.sp_sample(indptr, indices, np.zeros(2, np.uint8), 1, [5], np.array([0], np.int32), 3, 0)
-    x0 = np.array([[1.0], [3.0]])
-    for a_src, want in ((-1.0, 1.0), (-2.0 / 3.0, 0.0)):
-        p = G.GatParams([1], [np.array([[1.0]])], [np.array([a_src])], [np.array([2.0])], [np.array([0.0])])
-        f = G.gat_forward(b, x0, p)
-        assert G.score_margins(b, f, p) == pytest.approx([want], abs=1e-15)
+def _local_terms(b, f, p, l):
+    """What a device stores per row of local_cat[l]: a_src . z and a_dst . z per head, in float32."""
+    K = p.heads[l]
+    W = np.asarray(p.w[l], np.float64)
+    F = W.shape[1] // K
+    z = (f.hidden[l] @ W).reshape(-1, K, F)
+    src = (z * np.asarray(p.a_src[l]).reshape(K, F)).sum(2).astype(np.float32)
+    dst = (z * np.asarray(p.a_dst[l]).reshape(K, F)).sum(2).astype(np.float32)
+    return src, dst
+
+
+def test_conditioned_slopes_and_gradient_term_magnitudes():
+    """The two things the GPU tests take from the oracle besides its results.  (i) LeakyReLU slope
+    decisions conditioned on a device's stored score terms: with the oracle's own terms nothing
+    changes; a score inside the band that the device puts on the other side of zero takes the
+    device's slope (the gradients then equal those of a run whose score has that sign); outside the
+    band the same disagreement is counted as an error.  Hand example: scores 2*1 - 1*1 = 1 and
+    2*1 + a_src*3, which a_src = -2/3 puts at zero.  (ii) The term magnitudes bound the attention
+    gradients entry by entry and are not a loose bound where nothing cancels."""
     rng = np.random.default_rng(5)
     w, b, x0 = _batch()
     p = _params(rng, w.dims, [2, 1])
     f = G.gat_forward(b, x0, p)
-    bw = G.gat_backward(b, f, p, rng.standard_normal(f.logits.shape))
-    m = G.score_margins(b, f, p)
-    assert len(m) == 2 and all(0.0 < x < 1.0 for x in m)
+    g = rng.standard_normal(f.logits.shape)
+    bw = G.gat_backward(b, f, p, g)
+    terms = [_local_terms(b, f, p, l) for l in range(2)]
+    slopes, rep = G.conditioned_slopes(b, f, p, terms, rel_tau=1e-6)
+    assert all(r[1] == 0 and r[2] == 0 for r in rep)
+    same = G.gat_backward(b, f, p, g, slope_positive=slopes)
+    for l in range(2):
+        assert np.array_equal(same.gw[l], bw.gw[l]) and np.array_equal(same.ga_src[l], bw.ga_src[l])
+    # the device's dst term of one destination is shifted so that its smallest score changes sign
+    l, s = 0, 0
+    blk = b.blocks[l][s]
+    K = p.heads[l]
+    F = np.shape(p.w[l])[1] // K
+    z = f.z[l][s]
+    e_src = (z * np.asarray(p.a_src[l]).reshape(K, F)).sum(2)
+    e_dst = (z * np.asarray(p.a_dst[l]).reshape(K, F)).sum(2)
+    i = int(np.argmax(blk.cnt))          # a destination with several neighbours: its softmax has a gradient
+    assert blk.cnt[i] >= 2
+    nbrs = np.concatenate([[i], blk.blk_src[blk.blk_indptr[i]:blk.blk_indptr[i + 1]]]).astype(np.int64)
+    raw = e_dst[i][None, :] + e_src[nbrs]
+    j, k = np.unravel_index(np.abs(raw).argmin(), raw.shape)
+    dev = [(t[0].copy(), t[1].copy()) for t in terms]
+    dev[l][1][blk.shuffle_src_row[i], k] -= np.float32(2.0 * raw[j, k])
+    slopes, rep = G.conditioned_slopes(b, f, p, dev, rel_tau=1.0)     # band = everything: the device decides
+    assert rep[l][1] >= 1 and rep[l][2] == 0
+    assert bool(slopes[l][s][i][j, k]) == (not raw[j, k] > 0.0)
+    got = G.gat_backward(b, f, p, g, slope_positive=slopes)
+    assert np.abs(got.ga_src[l] - bw.ga_src[l]).max() > 0
+    slopes0, rep0 = G.conditioned_slopes(b, f, p, dev, rel_tau=0.0)   # no band: every disagreement is an error
+    assert rep0[l][2] >= 1 and bool(slopes0[l][s][i][j, k]) == bool(raw[j, k] > 0.0)
+    # hand example: with a_src = -2/3 the second score is 2 - 2 = 0; a device that computed +1e-9 there
+    indptr = np.array([0, 1, 1], np.int64)
+    indices = np.array([1], np.int32)
+    hb = R.sp_sample(indptr, indices, np.zeros(2, np.uint8), 1, [5], np.array([0], np.int32), 3, 0)
+    hx = np.array([[1.0], [3.0]])[hb.local_cat(0)]
+    hp = G.GatParams([1], [np.array([[1.0]])], [np.array([-2.0 / 3.0])], [np.array([2.0])], [np.array([0.0])])
+    hf = G.gat_forward(hb, hx, hp)
+    rows = {int(v): r for r, v in enumerate(hb.local_cat(0))}
+    src = np.zeros((2, 1), np.float32); dst = np.zeros((2, 1), np.float32)
+    src[rows[0]], src[rows[1]] = -2.0 / 3.0, -2.0
+    dst[rows[0]], dst[rows[1]] = 2.0, 6.0
+    src[rows[1]] = np.float32(-2.0) + np.float32(1e-6)
+    hs, hrep = G.conditioned_slopes(hb, hf, hp, [(src, dst)], rel_tau=1e-5)
+    assert hrep[0] == (1, 1, 0)
+    assert hs[0][0][0].reshape(-1).tolist() == [True, True]
+    g1 = np.array([[1.0]])
+    own = G.gat_backward(hb, hf, hp, g1)
+    cond = G.gat_backward(hb, hf, hp, g1, slope_positive=hs)
+    # slope 1 instead of 0.2 on the neighbour's score: its share of d a_src grows fivefold
+    a = hf.alpha[0][0][0][:, 0]
+    da = np.array([1.0, 3.0]) * 1.0
+    de = a * (da - (a * da).sum())
+    assert np.isclose(own.ga_src[0][0], de[0] * 1.0 * 1.0 + de[1] * 0.2 * 3.0)
+    assert np.isclose(cond.ga_src[0][0], de[0] * 1.0 * 1.0 + de[1] * 1.0 * 3.0)
     for l in range(2):
         t = bw.ga_terms[l].reshape(-1)
         assert np.all(np.abs(bw.ga_src[l].reshape(-1)) <= t * (1 + 1e-12))
