@@ -160,6 +160,30 @@ typedef struct {
 GSPLIT_API int gsplit_batch_level(const gsplit_ctx *ctx, int32_t level, gsplit_level_view *out);
 GSPLIT_API int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_layer_view *out);
 
+/* The shuffle index as the training passes use it (section 3: the shuffle index "consists of gather
+ * and scatter indexes"; Algorithm 2 and the backward description after it).  Gather side, composed
+ * with edges[l]: for destination row i of sampling layer `layer` (a row of local_cat[layer + 1]) and
+ * for each of its sampled edges e (numbered d_blk_indptr[i] .. d_blk_indptr[i + 1] - 1), the row of
+ * local_cat[layer] that holds the vertex.  Scatter side (the transpose, which the backward shuffle
+ * follows): for every row u of local_cat[layer], d_rev_cnt[u] entries starting at
+ * d_rev_list[d_rev_ptr[u]]; an entry is 2 * i for "u is destination i's own row" and 2 * i + 1 for
+ * "u is the source of one sampled edge of destination i"; d_rev_eid holds the edge number of such an
+ * entry (-1 for a self entry).  The entries of a row come in no particular order, and neither do
+ * the segments of different rows.
+ * The scatter side exists for layers >= 1, and for layer 0 too in a context created with
+ * gat_index = 1 (which alone has d_rev_eid); pointers of absent parts are NULL.
+ * Views are context-owned, valid until the next gsplit_sample_split; no synchronisation. */
+typedef struct {
+    const int32_t *d_self_row;      /* [n_dst_total]                                   */
+    const int32_t *d_edge_row;      /* [number of sampled edges of the layer]          */
+    const int32_t *d_rev_ptr;       /* [rows of local_cat[layer]]                      */
+    const int32_t *d_rev_cnt;       /* [rows of local_cat[layer]]                      */
+    const int32_t *d_rev_list;      /* [n_dst_total + number of sampled edges]         */
+    const int32_t *d_rev_eid;       /* like d_rev_list, or NULL                        */
+} gsplit_shuffle_view;
+
+GSPLIT_API int gsplit_batch_shuffle(const gsplit_ctx *ctx, int32_t layer, gsplit_shuffle_view *out);
+
 /* Loading step (section 3): d_out[r, :] = d_table[local_cat[0][r], :] for every row r of the
  * current batch's layer-0 local frontiers (splits concatenated).  A pure row copy of
  * dim * sizeof(dtype) bytes; rows of d_out are dense.  d_out must hold gsplit_max_rows(ctx, 0)
@@ -204,6 +228,14 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
 
+/* View of the activations the last gsplit_sage_fwd stored for local_cat[level], level 1 .. L-1:
+ * [rows of that level x dims[level]], float32 or bfloat16 as the forward pass's dtype says, after the
+ * ReLU.  The backward pass of layer level - 1 multiplies by [activation > 0] (Algorithm 2's layers in
+ * reverse): a parity check reads from this view which way the device decided a ReLU whose argument is
+ * zero to rounding.  Context-owned, valid until the next forward pass; no synchronisation.  ESTATE
+ * without a forward pass on the current batch, EINVAL for a level outside 1 .. L-1. */
+GSPLIT_API int gsplit_sage_activations(const gsplit_ctx *ctx, int32_t level, const void **d_act);
+
 /* GAT layer on the split mini-batch: the paper's second model (section 7.1), the layer of
  * Velickovic et al. (ICLR 2018) that it cites, run as `gnn_layer` of Algorithm 2.  Layer l, head k,
  * destination i with neighbourhood N(i) = {i} + its sampled neighbours:
@@ -244,6 +276,15 @@ GSPLIT_API int gsplit_gat_fwd(gsplit_ctx *ctx, const gsplit_gat_params *params, 
 GSPLIT_API int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *params, const void *d_feat_local,
                               const float *d_grad_logits, float *const *d_gw, float *const *d_ga_src,
                               float *const *d_ga_dst, float *const *d_gbias, void *stream);
+
+/* View of the two score terms the last gsplit_gat_fwd stored per row of local_cat[layer] and head k:
+ *   a_src^k . z_r^k at d_terms[r * row_stride + src_col + k],  a_dst^k . z_r^k at [... + dst_col + k]
+ * (float32).  Both passes form the argument of the LeakyReLU of an entry (destination i, source j) as
+ * the float32 sum of i's dst term and j's src term, so a parity check can tell from this view which
+ * slope the device took where that argument is zero to rounding.  Context-owned, valid until the next
+ * forward pass; no synchronisation.  ESTATE without a forward pass on the current batch. */
+GSPLIT_API int gsplit_gat_score_terms(const gsplit_ctx *ctx, int32_t layer, const float **d_terms,
+                                      int64_t *row_stride, int64_t *src_col, int64_t *dst_col);
 
 /* Diagnostics: per-kernel device time.  While enabled, every kernel the library launches is
  * bracketed by two events on the stream it runs on (this adds a little host work per launch).

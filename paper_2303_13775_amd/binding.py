@@ -26,6 +26,7 @@ EXPORTS = [
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
+    "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms",
 ]
 
 
@@ -53,6 +54,11 @@ class _LevelView(C.Structure):
 class _LayerView(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("d_nbr", "d_cnt", "d_mixed_cat", "d_mixed_off", "d_blk_indptr",
                                           "d_blk_src", "d_shuffle_src_row", "d_recv_cat", "d_recv_off")]
+
+
+class _ShuffleView(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("d_self_row", "d_edge_row", "d_rev_ptr", "d_rev_cnt", "d_rev_list",
+                                          "d_rev_eid")]
 
 
 class _SageParams(C.Structure):
@@ -90,6 +96,9 @@ def load_library():
     L.gsplit_batch_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_batch_level.argtypes = [vp, i32, C.POINTER(_LevelView)]
     L.gsplit_batch_layer.argtypes = [vp, i32, C.POINTER(_LayerView)]
+    L.gsplit_batch_shuffle.argtypes = [vp, i32, C.POINTER(_ShuffleView)]
+    L.gsplit_sage_activations.argtypes = [vp, i32, C.POINTER(vp)]
+    L.gsplit_gat_score_terms.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_gather_features.argtypes = [vp, vp, i32, i64, i64, vp, vp]
     L.gsplit_sage_fwd.argtypes = [vp, C.POINTER(_SageParams), vp, vp, vp]
     L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
@@ -118,15 +127,19 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def _view_i32(ptr: int, n: int, device) -> torch.Tensor:
-    """Copy n int32 values from a raw device pointer into a fresh tensor (test/inspection only)."""
-    out = torch.empty(max(n, 0), dtype=torch.int32, device=device)
+def _view(ptr: int, n: int, device, dtype=torch.int32) -> torch.Tensor:
+    """Copy n values from a raw device pointer into a fresh tensor (test/inspection only)."""
+    out = torch.empty(max(n, 0), dtype=dtype, device=device)
     if n > 0:
         hip = _hip_runtime()
-        rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(ptr), C.c_size_t(4 * n), 3)
+        rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(ptr), C.c_size_t(out.element_size() * n), 3)
         if rc != 0:
             raise GsplitError(-4, f"hipMemcpy failed ({rc})")
     return out
+
+
+def _view_i32(ptr: int, n: int, device) -> torch.Tensor:
+    return _view(ptr, n, device, torch.int32)
 
 
 _hip = None
@@ -277,6 +290,23 @@ class Context:
         v = _LayerView()
         self._check(self.lib.gsplit_batch_layer(self.h, layer, C.byref(v)))
         return v
+
+    def gsplit_batch_shuffle(self, layer: int) -> _ShuffleView:
+        v = _ShuffleView()
+        self._check(self.lib.gsplit_batch_shuffle(self.h, layer, C.byref(v)))
+        return v
+
+    def gsplit_sage_activations(self, level: int) -> int:
+        """Raw device pointer of the stored activations of local_cat[level]."""
+        p = C.c_void_p()
+        self._check(self.lib.gsplit_sage_activations(self.h, level, C.byref(p)))
+        return int(p.value or 0)
+
+    def gsplit_gat_score_terms(self, layer: int):
+        """(raw device pointer, row stride, column of the src terms, column of the dst terms)."""
+        p, st, sc, dc = C.c_void_p(), C.c_int64(), C.c_int64(), C.c_int64()
+        self._check(self.lib.gsplit_gat_score_terms(self.h, layer, C.byref(p), C.byref(st), C.byref(sc), C.byref(dc)))
+        return int(p.value or 0), int(st.value), int(sc.value), int(dc.value)
 
     def gsplit_gather_features(self, table: torch.Tensor, out: torch.Tensor):
         assert table.is_cuda and out.is_cuda and table.dim() == 2 and table.stride(1) == 1
@@ -435,3 +465,33 @@ class Context:
             }
             out["layers"].append(lay)
         return out
+
+    def fetch_shuffle(self, layer: int) -> dict:
+        """Copies of the composed gather side and of the scatter side of shuffle_idx[layer] (tests only)."""
+        n_local, _, n_edges, _ = self.gsplit_batch_sizes()
+        dev = self.device
+        v = self.gsplit_batch_shuffle(layer)
+        n_dst, nnz, n_lo = sum(n_local[layer + 1]), sum(n_edges[layer]), sum(n_local[layer])
+        out = {"self_row": _view_i32(v.d_self_row, n_dst, dev), "edge_row": _view_i32(v.d_edge_row, nnz, dev),
+               "rev_ptr": None, "rev_cnt": None, "rev_list": None, "rev_eid": None}
+        if v.d_rev_list:
+            out["rev_ptr"] = _view_i32(v.d_rev_ptr, n_lo, dev)
+            out["rev_cnt"] = _view_i32(v.d_rev_cnt, n_lo, dev)
+            out["rev_list"] = _view_i32(v.d_rev_list, n_dst + nnz, dev)
+            if v.d_rev_eid:
+                out["rev_eid"] = _view_i32(v.d_rev_eid, n_dst + nnz, dev)
+        return out
+
+    def fetch_sage_activations(self, level: int, width: int, dtype=torch.float32) -> torch.Tensor:
+        """Copy of the stored activations of local_cat[level] as [rows, width] (tests only)."""
+        n_local, _, _, _ = self.gsplit_batch_sizes()
+        rows = sum(n_local[level])
+        return _view(self.gsplit_sage_activations(level), rows * width, self.device, dtype).view(rows, width)
+
+    def fetch_gat_score_terms(self, layer: int, heads: int):
+        """Copies of the per-row score terms of a GAT layer: (src [rows, K], dst [rows, K]) (tests only)."""
+        n_local, _, _, _ = self.gsplit_batch_sizes()
+        rows = sum(n_local[layer])
+        ptr, stride, sc, dc = self.gsplit_gat_score_terms(layer)
+        raw = _view(ptr, rows * stride, self.device, torch.float32).view(rows, stride)
+        return raw[:, sc:sc + heads].contiguous(), raw[:, dc:dc + heads].contiguous()

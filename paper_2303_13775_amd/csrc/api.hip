@@ -260,6 +260,26 @@ extern "C" int gsplit_batch_layer(const gsplit_ctx *ctx, int32_t layer, gsplit_l
     return GSPLIT_OK;
 }
 
+extern "C" int gsplit_batch_shuffle(const gsplit_ctx *ctx, int32_t layer, gsplit_shuffle_view *out) {
+    if (!ctx || !out || layer < 0 || layer >= ctx->L) return GSPLIT_EINVAL;
+    const GsLayerBuf &B = ctx->layer[layer];
+    out->d_self_row = B.self_row;
+    out->d_edge_row = B.edge_row;
+    out->d_rev_ptr = B.rev_ptr;
+    out->d_rev_cnt = B.rev_cnt;
+    out->d_rev_list = B.rev_list;
+    out->d_rev_eid = B.rev_eid;
+    return GSPLIT_OK;
+}
+
+extern "C" int gsplit_sage_activations(const gsplit_ctx *ctx, int32_t level, const void **d_act) {
+    if (!ctx || !d_act || level < 1 || level >= ctx->L) return GSPLIT_EINVAL;
+    const GsSageBuf &sb = ctx->sage;
+    if (!sb.ready || !sb.fwd_done || sb.fwd_batch != ctx->batch_id) return GSPLIT_ESTATE;
+    *d_act = sb.hidden[level];
+    return GSPLIT_OK;
+}
+
 extern "C" int gsplit_timing_enable(gsplit_ctx *ctx, int32_t enable) {
     if (!ctx) return GSPLIT_EINVAL;
     ctx->timer.enabled = enable != 0;

@@ -1299,6 +1299,21 @@ extern "C" int gsplit_gat_fwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const
     return GSPLIT_OK;
 }
 
+extern "C" int gsplit_gat_score_terms(const gsplit_ctx *ctx, int32_t layer, const float **d_terms,
+                                      int64_t *row_stride, int64_t *src_col, int64_t *dst_col) {
+    if (!ctx || !d_terms || !row_stride || !src_col || !dst_col || layer < 0 || layer >= ctx->L) return GSPLIT_EINVAL;
+    const GsGatBuf &gb = ctx->gat;
+    if (!gb.ready || !gb.fwd_done || gb.fwd_batch != ctx->batch_id) return GSPLIT_ESTATE;
+    const int K = gb.heads[layer];
+    if (layer == 0 && gb.agg_first) {       // [rows x 2 K]: src terms, then dst terms
+        *d_terms = gb.s0; *row_stride = 2 * K; *src_col = 0; *dst_col = K;
+    } else {                                // extended transformed rows: z | src terms | dst terms | padding
+        const int F = layer == ctx->L - 1 ? gb.dims[layer + 1] : gb.dims[layer + 1] / K;
+        *d_terms = gb.zext[layer]; *row_stride = zw_of(K, F); *src_col = K * F; *dst_col = K * F + K;
+    }
+    return GSPLIT_OK;
+}
+
 extern "C" int gsplit_gat_bwd(gsplit_ctx *ctx, const gsplit_gat_params *p, const void *d_feat_local,
                               const float *d_grad_logits, float *const *d_gw, float *const *d_ga_src,
                               float *const *d_ga_dst, float *const *d_gbias, void *stream) {

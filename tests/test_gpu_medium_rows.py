@@ -11,8 +11,9 @@ import torch
 import workloads
 from oracle import reference as R
 from oracle import gat as G
-from test_gpu_parity import assert_batch_equal, TOL_F32
-from test_gpu_gat import attention_grad_err
+from test_gpu_parity import assert_batch_equal, check_sage, TOL_F32
+import sage_check as SC
+from test_gpu_gat import attention_grad_err, conditioned_gat_backward
 
 pytestmark = pytest.mark.gpu
 
@@ -49,7 +50,7 @@ def test_gat_medium_full_size(medium):
     of = G.gat_forward(ob, w.feat[ids].cpu().numpy(), op)
     y = w.labels[torch.from_numpy(tg.cpu().numpy()[ob.target_perm]).to(dev).long()].cpu().numpy()
     _, g = R.softmax_xent(of.logits, y)
-    obw = G.gat_backward(ob, of, op, g)
+    obw, _ = conditioned_gat_backward(ctx, ob, of, op, g, heads, who="gat")
     assert R.max_rel_err(logits.cpu().numpy(), of.logits) < TOL_F32
     for l in range(w.n_layers):
         for name, got, want in (("gw", grads[0][l], obw.gw[l]), ("gbias", grads[3][l], obw.gbias[l])):
@@ -127,7 +128,6 @@ def test_bf16_path_medium_full_size(medium):
     weights, bf16 MFMA products with float accumulation, against the oracle that rounds the same
     stored values to bf16."""
     from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16
-    from test_gpu_parity import FLOOR_BF16, TOL_BF16
     w, dev, host = medium
     ctx = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
     table = w.feat.to(torch.bfloat16)
@@ -153,20 +153,13 @@ def test_bf16_path_medium_full_size(medium):
     _, g = R.softmax_xent(of.logits, y)
     ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
     torch.cuda.synchronize()
-    obw = R.sp_backward(ob, of, op, g, store_bf16=True)
-    sws, swn, sb, _ = R.relu_decision_slack(ob, of, op, obw, rel_tau=1e-3, store_bf16=True)
-    assert R.max_rel_err(logits.cpu().numpy(), of.logits, floor=FLOOR_BF16) < TOL_BF16
-    for l in range(w.n_layers):
-        assert R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_self", l)
-        assert R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16) < TOL_BF16, ("gw_neigh", l)
-        assert R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16) < TOL_BF16, ("gbias", l)
-    # and as whole matrices without the allowance for undecidable ReLU decisions, which at bfloat16
-    # resolution covers a good part of the elementwise differences
-    for l in range(w.n_layers):
-        for name, a, o in (("gw_self", gws[l], obw.gw_self[l]), ("gw_neigh", gwn[l], obw.gw_neigh[l]),
-                           ("gbias", gb[l], obw.gbias[l])):
-            rel = np.linalg.norm(a.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300)
-            assert rel < TOL_BF16, (name, l, rel)
+    rows = table[ids].float().cpu().numpy()
+    r = dict(logits=logits.cpu().numpy(), gws=[t.cpu().numpy() for t in gws], gwn=[t.cpu().numpy() for t in gwn],
+             gb=[t.cpu().numpy() for t in gb], of=of, batch=ob, op=op, rows=rows, g=g,
+             act=SC.device_activations(ctx, w.dims, True))
+    r["ob"], r["report"] = SC.conditioned_backward(ob, of, op, g, r["act"], SC.TAU_BF16_ROUNDED, store_bf16=True,
+                                                   who="medium bf16")
+    check_sage(r, w.n_layers, bf16=True, tag="medium")
     ctx.close()
 
 

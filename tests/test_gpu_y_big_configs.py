@@ -13,7 +13,8 @@ import torch
 
 import workloads
 from oracle import reference as R
-from test_gpu_parity import assert_batch_equal, TOL_F32
+from test_gpu_parity import assert_batch_equal, check_sage, TOL_F32
+import sage_check as SC
 
 pytestmark = [pytest.mark.gpu,
               pytest.mark.skipif(os.environ.get("GSPLIT_SKIP_BIG") == "1", reason="GSPLIT_SKIP_BIG=1")]
@@ -64,24 +65,19 @@ def _run(w, dev, iters=(0, 1)):
         of = R.sp_forward(ob, w.feat[ids].float().cpu().numpy(), op)
         y = w.labels[torch.from_numpy(tg.cpu().numpy()[ob.target_perm]).to(dev).long()].cpu().numpy()
         _, g = R.softmax_xent(of.logits, y)
-        obw = R.sp_backward(ob, of, op, g)
+        obw, report = SC.conditioned_backward(ob, of, op, g, SC.device_activations(ctx, w.dims, False), SC.TAU_F32,
+                                              who=f"{w.name} it {it}")
         e_f = R.max_rel_err(logits.cpu().numpy(), of.logits)
-        sws, swn, sb, n_und = R.relu_decision_slack(ob, of, op, obw)
-        say(f"{n_und} pre-activations are too close to zero for float32 to decide their ReLU")
-        errs = [(R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l]),
-                 R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l]),
-                 R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l])) for l in range(w.n_layers)]
-        say("per layer (w_self, w_neigh, bias) errors: " + str([tuple(f"{x:.1e}" for x in e) for e in errs]))
+        say(f"ReLU band per layer (entries with |z| <= {SC.TAU_F32:g} max|z|, decided otherwise by the device, "
+            f"disagreements outside): {report}")
+        errs = SC.grad_errors(gws, gwn, gb, obw)
+        say("per layer (w_self, w_neigh, bias) elementwise errors, no allowance: " + SC.fmt(errs))
         e_b = max(max(e) for e in errs)
         say(f"max rel err: logits {e_f:.2e}, gradients {e_b:.2e}")
         assert e_f < TOL_F32 and e_b < TOL_F32
-        # the same gradients as whole matrices, without the allowance for undecidable ReLU decisions
-        # (a few flipped decisions among millions of rows do not move a norm)
-        fro = lambda x, o: float(np.linalg.norm(x.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300))
-        norms = [(fro(gws[l], obw.gw_self[l]), fro(gwn[l], obw.gw_neigh[l]), fro(gb[l], obw.gbias[l]))
-                 for l in range(w.n_layers)]
-        say("relative Frobenius errors per layer: " + str([tuple(f"{x:.1e}" for x in e) for e in norms]))
-        assert max(max(e) for e in norms) < TOL_F32
+        for l in range(w.n_layers):
+            SC.assert_shuffle_index_equal(ctx, ob, l, has_rev=l >= 1)
+        say("both sides of the shuffle index equal the oracle's")
     ctx.close()
 
 
@@ -105,7 +101,7 @@ def test_large_gat_statistics_and_counts_full_size():
     against the oracle on one full-size batch."""
     from paper_2303_13775_amd import Context, GatParams
     from oracle import gat as G
-    from test_gpu_gat import attention_grad_err
+    from test_gpu_gat import attention_grad_err, conditioned_gat_backward
     dev = torch.device("cuda:0")
     w = workloads.large(device=dev, progress=say)
     say(str(w.describe()))
@@ -155,7 +151,7 @@ def test_large_gat_statistics_and_counts_full_size():
     ctx.gsplit_gat_bwd(params, x0, torch.from_numpy(g.astype(np.float32)).to(dev), gw, gas, gad, gb)
     torch.cuda.synchronize()
     t0 = time.time()
-    obw = G.gat_backward(ob, of, op, g)
+    obw, _ = conditioned_gat_backward(ctx, ob, of, op, g, heads, who="gat")
     say(f"oracle backward in {time.time() - t0:.1f} s")
     for l in range(w.n_layers):
         o_src, o_dst = obw.ga_src[l], obw.ga_dst[l]
@@ -168,7 +164,7 @@ def test_large_gat_statistics_and_counts_full_size():
     ctx.close()
 
 
-@pytest.mark.parametrize("n_splits", [1, 8])
+@pytest.mark.parametrize("n_splits", [1, 2, 4, 8])
 def test_sweep_bf16_full_size(n_splits):
     """The split sweep of `bench.py --workload sweep`: the large graph, 8192 targets, four layers of
     fanout 10, bf16 storage, with one split (both keys of a vertex are the same key and one table
@@ -176,7 +172,6 @@ def test_sweep_bf16_full_size(n_splits):
     sampled batch is compared, and the bf16 forward pass with the loss gradient's backward pass
     against the oracle that rounds the same stored values."""
     from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16
-    from test_gpu_parity import FLOOR_BF16, TOL_BF16
     dev = torch.device("cuda:0")
     w = workloads.large(device=dev, n_splits=n_splits, feat_dtype=torch.bfloat16, batch=8192,
                         fanouts=(10, 10, 10, 10), dims=(128, 256, 256, 256, 172), progress=say)
@@ -209,21 +204,14 @@ def test_sweep_bf16_full_size(n_splits):
     _, g = R.softmax_xent(of.logits, y)
     ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
     torch.cuda.synchronize()
-    obw = R.sp_backward(ob, of, op, g, store_bf16=True)
-    sws, swn, sb, _ = R.relu_decision_slack(ob, of, op, obw, rel_tau=1e-3, store_bf16=True)
+    rows = w.feat[ids].float().cpu().numpy()
+    r = dict(logits=logits.cpu().numpy(), gws=[t.cpu().numpy() for t in gws], gwn=[t.cpu().numpy() for t in gwn],
+             gb=[t.cpu().numpy() for t in gb], of=of, batch=ob, op=op, rows=rows, g=g,
+             act=SC.device_activations(ctx, w.dims, True))
+    r["ob"], r["report"] = SC.conditioned_backward(ob, of, op, g, r["act"], SC.TAU_BF16_ROUNDED, store_bf16=True,
+                                                   who=w.name)
     say(f"oracle forward/backward in {time.time() - t0:.1f} s")
-    e_f = R.max_rel_err(logits.cpu().numpy(), of.logits, floor=FLOOR_BF16)
-    errs = [(R.grad_err(gws[l].cpu().numpy(), obw.gw_self[l], sws[l], floor=FLOOR_BF16),
-             R.grad_err(gwn[l].cpu().numpy(), obw.gw_neigh[l], swn[l], floor=FLOOR_BF16),
-             R.grad_err(gb[l].cpu().numpy(), obw.gbias[l], sb[l], floor=FLOOR_BF16)) for l in range(w.n_layers)]
-    say(f"max rel err: logits {e_f:.2e}; per layer " + str([tuple(f"{x:.1e}" for x in e) for e in errs]))
-    assert e_f < TOL_BF16 and max(max(e) for e in errs) < TOL_BF16
-    # With millions of rows the undecidable ReLU decisions explain most elementwise differences of
-    # the lower layers' gradients, so those are also compared as whole matrices, without that
-    # allowance: a handful of flipped decisions does not move a norm over millions of rows.
-    fro = lambda a, o: float(np.linalg.norm(a.cpu().numpy().astype(np.float64) - o) / max(np.linalg.norm(o), 1e-300))
-    norms = [(fro(gws[l], obw.gw_self[l]), fro(gwn[l], obw.gw_neigh[l]), fro(gb[l], obw.gbias[l]))
-             for l in range(w.n_layers)]
-    say("relative Frobenius errors per layer: " + str([tuple(f"{x:.1e}" for x in e) for e in norms]))
-    assert max(max(e) for e in norms) < TOL_BF16
+    check_sage(r, w.n_layers, bf16=True, tag=f"sweep-S{n_splits}")
+    for l in range(w.n_layers):
+        SC.assert_shuffle_index_equal(ctx, ob, l, has_rev=l >= 1)
     ctx.close()
