@@ -128,6 +128,51 @@ GSPLIT_API int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, in
 GSPLIT_API int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                                        const uint64_t *d_seed_iter, void *stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): gsplit_sample_split without a context.  The graph, the configuration and the
+ * targets are passed as to gsplit_create / gsplit_sample_split (keep_edge_ids and gat_index must be
+ * 0); the outputs are the caller's DEVICE buffers; every piece of working memory (hash tables, entry
+ * indices, class masks, histograms, level bookkeeping) comes out of one static device array of
+ * GSPLIT_NOALLOC_SCRATCH_MIB MiB that every GPU the library runs on holds until the process ends.  The
+ * call allocates nothing, frees nothing and enqueues only kernels on `stream`.
+ *
+ * Capacity: with B = max_l max_targets * prod_{k >= l} (1 + fanouts[k]) (the no-dedup bound on the
+ * destinations plus slots of a layer) the call needs 24 bytes per element of B plus 24 bytes per
+ * entry of its two tables (12 with one split), which have the next power of two above 2 * B entries.
+ * ECAPACITY, with the figures in gsplit_last_error(NULL), when that exceeds the array (1024 targets
+ * with fanouts [10, 5] take 8 MiB and fit; with [15, 10, 5] they would take 120 MiB and do not).
+ *
+ * Output sizes (entries, with ub[L] = max_targets, ub[l] = min(n_vertices, ub[l+1] * (1 + fanouts[l]))):
+ *   d_local_cat[l] ub[l] (l = 0 .. L);  d_nbr[l], d_blk_src[l], d_recv_cat[l] ub[l+1] * fanouts[l];
+ *   d_cnt[l] ub[l+1];  d_blk_indptr[l] ub[l+1] + 1;  d_mixed_cat[l], d_shuffle_src_row[l]
+ *   ub[l+1] * (1 + fanouts[l]);  d_local_off (L+1) * (S+1);  d_mixed_off, d_recv_off L * (S+1).
+ * Contents are those of gsplit_batch_level / gsplit_batch_layer after gsplit_sample_split with the
+ * same arguments, bit for bit; d_local_off[l * (S+1) + s] etc. are the split offsets (the live sizes:
+ * rows past them are not written).
+ *
+ * All calls on one GPU share that GPU's array, which keeps what the last call left (this call clears
+ * what it needs first): calls that overlap in time on one GPU race, also from different threads or
+ * streams; run them one after the other.  Errors are reported through gsplit_last_error(NULL). */
+#define GSPLIT_NOALLOC_SCRATCH_MIB 16
+
+typedef struct {
+    int32_t *d_local_cat[GSPLIT_MAX_LAYERS + 1];
+    int32_t *d_local_off;
+    int32_t *d_nbr[GSPLIT_MAX_LAYERS];
+    int32_t *d_cnt[GSPLIT_MAX_LAYERS];
+    int32_t *d_mixed_cat[GSPLIT_MAX_LAYERS];
+    int32_t *d_mixed_off;
+    int32_t *d_blk_indptr[GSPLIT_MAX_LAYERS];
+    int32_t *d_blk_src[GSPLIT_MAX_LAYERS];
+    int32_t *d_shuffle_src_row[GSPLIT_MAX_LAYERS];
+    int32_t *d_recv_cat[GSPLIT_MAX_LAYERS];
+    int32_t *d_recv_off;
+} gsplit_batch_out;
+
+GSPLIT_API int gsplit_sample_split_noalloc(const gsplit_graph *graph, const gsplit_config *config,
+                                           const int32_t *d_targets, int64_t n_targets, uint64_t seed,
+                                           uint64_t iter, const gsplit_batch_out *out, void *stream);
+
 /* Host-visible sizes of the current batch.  The first call after a gsplit_sample_split waits for
  * `stream` work of that call to finish (one device-to-host copy); later calls are free.
  *   n_local  [(L+1) * S]: |local_front[l]_s| at [l * S + s]

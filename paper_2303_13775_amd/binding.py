@@ -26,7 +26,7 @@ EXPORTS = [
     "gsplit_timing_read", "gsplit_presample_accumulate", "gsplit_presample_weights",
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
-    "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms",
+    "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms", "gsplit_sample_split_noalloc",
 ]
 
 
@@ -59,6 +59,18 @@ class _LayerView(C.Structure):
 class _ShuffleView(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("d_self_row", "d_edge_row", "d_rev_ptr", "d_rev_cnt", "d_rev_list",
                                           "d_rev_eid")]
+
+
+MAX_LAYERS = 8
+
+
+class _BatchOut(C.Structure):
+    _fields_ = [("d_local_cat", C.c_void_p * (MAX_LAYERS + 1)), ("d_local_off", C.c_void_p),
+                ("d_nbr", C.c_void_p * MAX_LAYERS), ("d_cnt", C.c_void_p * MAX_LAYERS),
+                ("d_mixed_cat", C.c_void_p * MAX_LAYERS), ("d_mixed_off", C.c_void_p),
+                ("d_blk_indptr", C.c_void_p * MAX_LAYERS), ("d_blk_src", C.c_void_p * MAX_LAYERS),
+                ("d_shuffle_src_row", C.c_void_p * MAX_LAYERS), ("d_recv_cat", C.c_void_p * MAX_LAYERS),
+                ("d_recv_off", C.c_void_p)]
 
 
 class _SageParams(C.Structure):
@@ -96,6 +108,8 @@ def load_library():
     L.gsplit_batch_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_batch_level.argtypes = [vp, i32, C.POINTER(_LevelView)]
     L.gsplit_batch_layer.argtypes = [vp, i32, C.POINTER(_LayerView)]
+    L.gsplit_sample_split_noalloc.argtypes = [C.POINTER(_Graph), C.POINTER(_Config), vp, i64, u64, u64,
+                                              C.POINTER(_BatchOut), vp]
     L.gsplit_batch_shuffle.argtypes = [vp, i32, C.POINTER(_ShuffleView)]
     L.gsplit_sage_activations.argtypes = [vp, i32, C.POINTER(vp)]
     L.gsplit_gat_score_terms.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
@@ -159,6 +173,55 @@ def _hip_runtime():
         _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
         _hip.hipMemcpy.restype = C.c_int
     return _hip
+
+
+def noalloc_output_sizes(n_vertices: int, n_splits: int, fanouts: Sequence[int], max_targets: int) -> dict:
+    """Entries of every output buffer of gsplit_sample_split_noalloc, as include/gsplit.h states them."""
+    L, S = len(fanouts), n_splits
+    ub = [0] * (L + 1)
+    ub[L] = max_targets
+    for l in range(L - 1, -1, -1):
+        ub[l] = min(n_vertices, ub[l + 1] * (1 + fanouts[l]))
+    return {"local_cat": ub, "local_off": (L + 1) * (S + 1), "mixed_off": L * (S + 1), "recv_off": L * (S + 1),
+            "nbr": [ub[l + 1] * fanouts[l] for l in range(L)], "cnt": [ub[l + 1] for l in range(L)],
+            "blk_indptr": [ub[l + 1] + 1 for l in range(L)], "blk_src": [ub[l + 1] * fanouts[l] for l in range(L)],
+            "recv_cat": [ub[l + 1] * fanouts[l] for l in range(L)],
+            "mixed_cat": [ub[l + 1] * (1 + fanouts[l]) for l in range(L)],
+            "shuffle_src_row": [ub[l + 1] * (1 + fanouts[l]) for l in range(L)]}
+
+
+def gsplit_sample_split_noalloc(indptr: torch.Tensor, indices: torch.Tensor, pmap: torch.Tensor, n_splits: int,
+                                fanouts: Sequence[int], max_targets: int, targets: torch.Tensor, seed: int, it: int,
+                                out: dict):
+    """gsplit_sample_split without a context and without any allocation inside the library.  `out` maps
+    the field names of gsplit_batch_out (without the d_ prefix) to int32 device tensors (lists of
+    tensors for the per-level / per-layer fields), sized as noalloc_output_sizes says."""
+    lib = load_library()
+    L = len(fanouts)
+    assert indptr.is_cuda and indices.is_cuda and pmap.is_cuda and targets.is_cuda
+    assert indptr.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32 and pmap.dtype == torch.uint8
+    assert targets.dtype == torch.int32 and targets.is_contiguous()
+    want = noalloc_output_sizes(indptr.numel() - 1, n_splits, fanouts, max_targets)
+    o = _BatchOut()
+    for name, sizes in want.items():
+        t = out[name]
+        if isinstance(sizes, list):
+            assert len(t) == len(sizes)
+            for k, (x, n) in enumerate(zip(t, sizes)):
+                assert x.is_cuda and x.dtype == torch.int32 and x.is_contiguous() and x.numel() >= n, (name, k)
+                getattr(o, "d_" + name)[k] = x.data_ptr()
+        else:
+            assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.numel() >= sizes, name
+            setattr(o, "d_" + name, t.data_ptr())
+    fan = (C.c_int32 * L)(*[int(f) for f in fanouts])
+    g = _Graph(indptr.numel() - 1, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
+               indices.data_ptr(), pmap.data_ptr(), int(n_splits))
+    c = _Config(L, fan, int(max_targets), 0, 0, 0)
+    with torch.cuda.device(indptr.device):
+        rc = lib.gsplit_sample_split_noalloc(C.byref(g), C.byref(c), targets.data_ptr(), targets.numel(),
+                                             C.c_uint64(seed), C.c_uint64(it), C.byref(o), _stream())
+    if rc != 0:
+        raise GsplitError(rc, (lib.gsplit_last_error(None) or b"").decode())
 
 
 class SageParams:

@@ -34,6 +34,7 @@
 // element remembers the table entry it landed in (no second probe sequence) and the count passes
 // leave their classification behind for the scatter passes.
 #include <algorithm>
+#include <mutex>
 
 #include "gsplit_internal.h"
 
@@ -996,11 +997,168 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, items), ny), dim3(256), 0, st, ra, ctx->d_meta, S);
     }
     GS_HIP(ctx, hipGetLastError());
-    if (!ctx->captured) GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
+    if (!ctx->captured && ctx->sample_done) GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
     return GSPLIT_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// The same step without any allocation: everything a context would own (tables, per-element entry
+// indices, class masks, histograms, level bookkeeping) lives in one static device array, carved up
+// per call.  Each GPU holds its own copy of the array at its own address, taken once per device.
+// ------------------------------------------------------------------------------------------
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)GSPLIT_NOALLOC_SCRATCH_MIB << 20;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+struct NoAllocDevice { unsigned char *ptr = nullptr; int n_cu = 0; };
+NoAllocDevice g_noalloc[NOALLOC_MAX_DEVICES];
+std::mutex g_noalloc_mutex;
+
+// device address of this GPU's copy of the array (and its compute-unit count), taken on the first
+// call with that device current
+int noalloc_device(NoAllocDevice **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES)
+        return gs_fail(nullptr, GSPLIT_EHIP, "gsplit_sample_split_noalloc: no current HIP device");
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    NoAllocDevice &d = g_noalloc[dev];
+    if (!d.ptr) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return gs_fail(nullptr, GSPLIT_EHIP, std::string("gsplit_sample_split_noalloc: hipGetSymbolAddress: ") +
+                                                     hipGetErrorString(e));
+        int n_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
+        d.n_cu = n_cu;
+        d.ptr = (unsigned char *)p;
+    }
+    *out = &d;
+    return GSPLIT_OK;
+}
+
+// every table entry of the part a call can use starts empty, the level bookkeeping at zero (a fill
+// kernel, not a memset: the call may be recorded into a graph)
+__global__ __launch_bounds__(256) void k_noalloc_reset(GsTable a, GsTable b, int64_t n_entries, int32_t *meta_words,
+                                                       int n_meta_words) {
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n_entries; x += (int64_t)gridDim.x * blockDim.x) {
+        a.slot[x] = EMPTY_ENTRY;
+        if (b.slot != a.slot) b.slot[x] = EMPTY_ENTRY;
+    }
+    if (blockIdx.x == 0)
+        for (int x = threadIdx.x; x < n_meta_words; x += blockDim.x) meta_words[x] = 0;
+}
+
+// split offsets of every level and layer, from the internal bookkeeping to the caller's arrays
+__global__ void k_noalloc_export(const GsLevelMeta *__restrict__ meta, int L, int S, int32_t *local_off,
+                                 int32_t *mixed_off, int32_t *recv_off) {
+    const int per = S + 1;
+    for (int x = threadIdx.x; x < (L + 1) * per; x += blockDim.x) local_off[x] = meta[x / per].front_off[x % per];
+    for (int x = threadIdx.x; x < L * per; x += blockDim.x) {
+        mixed_off[x] = meta[x / per].mixed_off[x % per];
+        recv_off[x] = meta[x / per].recv_off[x % per];
+    }
+}
+
 }  // namespace
+
+extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_config *c, const int32_t *d_targets,
+                                           int64_t n_targets, uint64_t seed, uint64_t iter,
+                                           const gsplit_batch_out *out, void *stream) {
+    const char *who = "gsplit_sample_split_noalloc: ";
+    if (!g || !c || !out) return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "NULL argument");
+    if (g->n_vertices <= 0 || g->n_vertices >= (1ll << 31) || g->n_edges < 0 || !g->d_indptr ||
+        (g->n_edges > 0 && !g->d_indices) || !g->d_pmap || g->n_splits < 1 || g->n_splits > GSPLIT_MAX_SPLITS ||
+        (unsigned long long)g->n_vertices * (unsigned long long)g->n_splits >= 0xFFFFFFFFull)
+        return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "bad graph");
+    if (c->n_layers < 1 || c->n_layers > GSPLIT_MAX_LAYERS || !c->fanouts || c->max_targets < 1 ||
+        c->max_targets > g->n_vertices)
+        return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "bad config");
+    if (c->keep_edge_ids || c->gat_index)
+        return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "keep_edge_ids and gat_index need a context");
+    for (int l = 0; l < c->n_layers; ++l)
+        if (c->fanouts[l] < 1 || c->fanouts[l] > GSPLIT_MAX_FANOUT)
+            return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "fanout out of range");
+    if (n_targets < 0 || (n_targets > 0 && !d_targets)) return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "bad targets");
+    if (n_targets > c->max_targets) return gs_fail(nullptr, GSPLIT_ECAPACITY, std::string(who) + "n_targets exceeds max_targets");
+    const int L = c->n_layers, S = g->n_splits;
+    if (!out->d_local_off || !out->d_mixed_off || !out->d_recv_off)
+        return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "NULL output");
+    for (int l = 0; l <= L; ++l)
+        if (!out->d_local_cat[l]) return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "NULL output");
+    for (int l = 0; l < L; ++l)
+        if (!out->d_nbr[l] || !out->d_cnt[l] || !out->d_mixed_cat[l] || !out->d_blk_indptr[l] || !out->d_blk_src[l] ||
+            !out->d_shuffle_src_row[l] || !out->d_recv_cat[l])
+            return gs_fail(nullptr, GSPLIT_EINVAL, std::string(who) + "NULL output");
+
+    // a context on the host stack whose buffers are the caller's outputs and pieces of the static array
+    gsplit_ctx ctx;
+    ctx.graph = *g;
+    ctx.L = L; ctx.S = S;
+    ctx.max_targets = c->max_targets;
+    ctx.sampler_blocks_per_cu = c->sampler_blocks_per_cu > 0 ? std::min(c->sampler_blocks_per_cu, 8) : 8;
+    ctx.rev_from = L;                     // no scatter side: it serves the training passes of a context
+    for (int l = 0; l < L; ++l) ctx.fan[l] = c->fanouts[l];
+    ctx.ub_front[L] = c->max_targets;
+    int64_t tab_cap = 1024, max_items = 1024;
+    for (int l = L - 1; l >= 0; --l) {
+        const int64_t grown = ctx.ub_front[l + 1] * (1 + ctx.fan[l]);
+        max_items = std::max(max_items, grown);
+        ctx.ub_front[l] = std::min<int64_t>(g->n_vertices, grown);
+        while (tab_cap < 2 * grown) tab_cap <<= 1;
+        if (grown >= (1ll << 29)) { max_items = 1ll << 40; break; }
+    }
+    ctx.tab_cap = tab_cap;
+    size_t need = 0;
+    auto carve = [&](size_t bytes) { const size_t at = need; need += (bytes + 255) & ~(size_t)255; return at; };
+    const size_t o_meta = carve(sizeof(GsLevelMeta) * (L + 1));
+    const size_t o_mslot = carve(sizeof(unsigned long long) * tab_cap), o_mrow = carve(sizeof(int32_t) * tab_cap);
+    const size_t o_lslot = S == 1 ? o_mslot : carve(sizeof(unsigned long long) * tab_cap);
+    const size_t o_lrow = S == 1 ? o_mrow : carve(sizeof(int32_t) * tab_cap);
+    const size_t o_em = carve(sizeof(int32_t) * max_items), o_el = carve(sizeof(int32_t) * max_items);
+    const size_t o_me = carve(sizeof(int32_t) * max_items), o_cls = carve(sizeof(uint32_t) * max_items);
+    const size_t o_self = carve(sizeof(int32_t) * max_items), o_edge = carve(sizeof(int32_t) * max_items);
+    const size_t o_hist = carve(sizeof(int32_t) * PART_MAX_NB * PART_NK);
+    const size_t o_perm = carve(sizeof(int32_t) * ctx.ub_front[L]);
+    if (max_items >= (1ll << 29) || need > NOALLOC_SCRATCH_BYTES)
+        return gs_fail(nullptr, GSPLIT_ECAPACITY,
+                       std::string(who) + "max_targets and fanouts need " + std::to_string(need >> 10) +
+                           " KiB of working memory, the static array holds " +
+                           std::to_string(NOALLOC_SCRATCH_BYTES >> 10) + " KiB; use a context (gsplit_create)");
+    NoAllocDevice *dev = nullptr;
+    int rc = noalloc_device(&dev);
+    if (rc != GSPLIT_OK) return rc;
+    unsigned char *base = dev->ptr;       // this GPU's copy of the array (never the array's name on the host)
+    ctx.n_cu = dev->n_cu;
+    ctx.d_meta = (GsLevelMeta *)(base + o_meta);
+    ctx.tab_mixed = GsTable{(unsigned long long *)(base + o_mslot), (int32_t *)(base + o_mrow)};
+    ctx.tab_local = GsTable{(unsigned long long *)(base + o_lslot), (int32_t *)(base + o_lrow)};
+    ctx.ent_mixed = (int32_t *)(base + o_em); ctx.ent_local = (int32_t *)(base + o_el);
+    ctx.mixed_ent = (int32_t *)(base + o_me); ctx.cls = (uint32_t *)(base + o_cls);
+    ctx.part_hist = (int32_t *)(base + o_hist);
+    ctx.target_perm = (int32_t *)(base + o_perm);
+    for (int l = 0; l <= L; ++l) ctx.front[l] = out->d_local_cat[l];
+    for (int l = 0; l < L; ++l) {
+        GsLayerBuf &B = ctx.layer[l];
+        B.nbr = out->d_nbr[l]; B.cnt = out->d_cnt[l]; B.mixed = out->d_mixed_cat[l]; B.blk_indptr = out->d_blk_indptr[l];
+        B.blk_src = out->d_blk_src[l]; B.recv = out->d_recv_cat[l]; B.src_row = out->d_shuffle_src_row[l];
+        // the shuffle index composed with edges[l] is a by-product nobody reads here: one region for all layers
+        B.self_row = (int32_t *)(base + o_self); B.edge_row = (int32_t *)(base + o_edge);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // the array keeps what the last call left: clear the table entries this call can touch and the
+    // level bookkeeping before the first kernel reads them
+    hipLaunchKernelGGL(k_noalloc_reset, dim3((unsigned)std::min<int64_t>(1024, gs_ceil_div(tab_cap, 256))), dim3(256), 0, st,
+                       ctx.tab_mixed, ctx.tab_local, tab_cap, (int32_t *)ctx.d_meta,
+                       (int)(sizeof(GsLevelMeta) * (L + 1) / sizeof(int32_t)));
+    rc = sample_split(&ctx, d_targets, n_targets, seed, iter, nullptr, stream);
+    if (rc != GSPLIT_OK) return gs_fail(nullptr, rc, std::string(who) + ctx.err);
+    hipLaunchKernelGGL(k_noalloc_export, dim3(1), dim3(64), 0, st, ctx.d_meta, L, S, out->d_local_off, out->d_mixed_off,
+                       out->d_recv_off);
+    if (hipGetLastError() != hipSuccess) return gs_fail(nullptr, GSPLIT_EHIP, std::string(who) + "kernel launch failed");
+    return GSPLIT_OK;
+}
 
 extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                                    uint64_t seed, uint64_t iter, void *stream) {
