@@ -64,6 +64,11 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     ap.add_argument("--stage-iters", type=int, default=50)
+    ap.add_argument("--extra-configs", dest="extra_configs", action="store_true", default=None,
+                    help="after the benchmark workload also time large (f32, bf16), skewed and the split sweep "
+                         "(S = 1, 2, 4, 8), serially, and report them under extra_configs (default: on for the "
+                         "default medium / sage / f32 run)")
+    ap.add_argument("--no-extra-configs", dest="extra_configs", action="store_false")
     return ap.parse_args()
 
 
@@ -280,34 +285,45 @@ class Pipelined:
             th.join()
 
 
-def cpu_baseline(w_host, iters):
-    """The oracle as it stands, timed on the host cores on `iters` whole iterations."""
-    import numpy as np
+def cpu_baseline(w_host, iters, budget_s=14.0):
+    """The oracle as it stands, timed on the host cores on whole iterations of the same workload:
+    once as it runs by default (C steps on one thread, numpy float64 products on all BLAS threads)
+    and once held to a single thread throughout."""
     from oracle import reference as R
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
+        threadpool_limits = None
         threads = 1
     ip, ix, pm = w_host["indptr"], w_host["indices"], w_host["pmap"]
     params = R.SageParams(w_host["w_self"], w_host["w_neigh"], w_host["bias"])
-    t0 = time.perf_counter()
-    done = 0
-    for it in range(iters):
-        tg = w_host["targets"][it]
-        b = R.sp_sample(ip, ix, pm, w_host["S"], w_host["fanouts"], tg, 0xC0FFEE, it)
-        x0 = R.gather_rows(w_host["feat"], b.local_cat(0))
-        f = R.sp_forward(b, x0, params)
-        _, g = R.softmax_xent(f.logits, w_host["labels"][tg[b.target_perm]])
-        R.sp_backward(b, f, params, g)
-        done += 1
-        if time.perf_counter() - t0 > 30.0:      # the sample stays bounded on the larger workloads
-            break
-    iters = done
-    dt = time.perf_counter() - t0
-    return {"value": iters / dt, "unit": "mini-batches/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{iters} whole iterations of the same workload (C steps single-threaded, "
-                      f"numpy float64 matmuls on {threads} BLAS threads), {dt:.1f} s"}
+
+    def run(limit_s):
+        t0 = time.perf_counter()
+        done = 0
+        for it in range(iters):
+            tg = w_host["targets"][it]
+            b = R.sp_sample(ip, ix, pm, w_host["S"], w_host["fanouts"], tg, 0xC0FFEE, it)
+            x0 = R.gather_rows(w_host["feat"], b.local_cat(0))
+            f = R.sp_forward(b, x0, params)
+            _, g = R.softmax_xent(f.logits, w_host["labels"][tg[b.target_perm]])
+            R.sp_backward(b, f, params, g)
+            done += 1
+            if time.perf_counter() - t0 > limit_s:      # the sample stays bounded
+                break
+        return done, time.perf_counter() - t0
+
+    n_all, dt_all = run(budget_s)
+    out = {"value": n_all / dt_all, "unit": "mini-batches/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"{n_all} whole iterations of the same workload (C steps single-threaded, "
+                     f"numpy float64 matmuls on {threads} BLAS threads), {dt_all:.1f} s"}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            n_one, dt_one = run(budget_s * 0.6)
+        out["one_thread"] = {"value": n_one / dt_one, "unit": "mini-batches/s", "cores": 1,
+                             "sample": f"{n_one} whole iterations, every step on one thread, {dt_one:.1f} s"}
+    return out
 
 
 def cpu_baseline_gat(w_host, iters):
@@ -497,6 +513,342 @@ def redundancy_bench(a, w, dev, t_gen):
     print(json.dumps(out))
 
 
+def algorithmic_work(w, model, heads, rows, edges, mixed, row_bytes, ip_bytes, S):
+    """Algorithmic bytes / flops of one launch of every kernel of a step, from the live sizes of a batch.
+
+    HBM-bound rows follow the per-unit figures of the scope table: sampling = per destination vertex
+    its id and two row pointers read and the count written, per sampled edge 4 bytes read and 4
+    written; the kernel also makes the hash-table entries of the dedup step (one 8-byte entry per
+    element in each table it enters), which are counted with it.  What a kernel moves beyond that
+    for its own bookkeeping (the entry indices every element remembers) is returned separately."""
+    L = w.n_layers
+    work, extra = {}, {}
+
+    def add(label, kind, amount, own=0.0):
+        work[label] = (kind, amount)
+        if own:
+            extra[label] = own
+
+    add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
+    add("gather_cached", "bytes", rows[0] * (2 * row_bytes + 8))
+    es = w.feat.element_size()
+    for l in range(L if model == "gat" else 0):
+        D, nd, n_lo = w.dims[l], rows[l + 1], rows[l]
+        K = heads[l]
+        HF = K * w.dims[l + 1] if l == L - 1 else w.dims[l + 1]
+        ent = edges[l] + nd
+        if l == 0:
+            add("gat0_transform.l0", "flops", 2.0 * nd * D * HF)
+            add("gat0_grad_p.l0", "flops", 2.0 * nd * D * HF)
+            add("gat0_grad_w.l0", "flops", 2.0 * nd * D * HF)
+            add("gat0_scores.l0", "bytes", n_lo * 4 * (D + 2 * K))
+            add("gat0_aggregate.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
+            add("gat0_bwd.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
+        add(f"gat_transform.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+        add(f"gat_grad_w.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+        if l > 0:
+            add(f"gat_grad_in.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
+        add(f"gat_aggregate.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * 4 * w.dims[l + 1])
+        add(f"gat_bwd_dst.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * (8 * w.dims[l + 1] + 4 * HF + 4 * K))
+        add(f"gat_bwd_src.l{l}", "bytes", ent * (8 + 4 * HF + 8 * K) + n_lo * (8 + 4 * (HF + 2 * K)))
+    n_tab = 2 if S > 1 else 1
+    for l in range(L):
+        D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
+        add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
+        add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N)
+        if l > 0:
+            add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
+            add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
+        # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
+        add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
+        items = nd + edges[l]
+        add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes) + edges[l] * 8 + items * 8 * n_tab, own=items * 8)
+        slots = nd * w.fanouts[l]
+        # split assignment and buckets: per sampled id 1 (owner byte) + 4 read + 4 written; the dedup's table
+        # look-ups of the same pass 8 bytes per table; own: the entry indices and class masks
+        add(f"mixed_buckets_count.l{l}", "bytes", edges[l] * (1 + 4 + 8 * n_tab), own=slots * 12)
+        add(f"mixed_buckets_scatter.l{l}", "bytes", edges[l] * 4 + mixed[l] * (4 + 4 + 4 * n_tab) + rows[l] * 4,
+            own=slots * 4 + mixed[l] * 4)
+        add(f"shuffle_index.l{l}", "bytes", (mixed[l] + nd) * 8 + edges[l] * (4 * n_tab + 8), own=slots * 8 + mixed[l] * 4)
+    return work, extra
+
+
+def percentile(xs, q):
+    xs = sorted(xs)
+    if not xs:
+        return None
+    k = (len(xs) - 1) * q
+    lo, hi = int(k), min(int(k) + 1, len(xs) - 1)
+    return xs[lo] + (xs[hi] - xs[lo]) * (k - lo)
+
+
+def profile_traffic(workload, dtype, model, label):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE + WRITE_SIZE scaled by the copy calibration stated in that file), with the file it
+    came from; (None, None) when there is no summary for this workload and type."""
+    here = os.path.dirname(os.path.abspath(__file__))
+    tag = workload if dtype == "f32" else f"{workload}_{dtype}"
+    name = f"{tag}_{'gat_' if model == 'gat' else ''}bench_hbm_traffic.txt"
+    path = os.path.join(here, "profiles", name)
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 6 and f[0] == label:
+            try:
+                return (float(f[-2]) + float(f[-1])) * 1024.0, "profiles/" + name
+            except ValueError:
+                return None, None
+    return None, None
+
+
+def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup, pipeline, stage_iters,
+            cache=None, use_graph=False):
+    """All timings of one configuration: K steps pipelined (if asked) and K steps serial between two
+    device synchronisations, K steps with one synchronisation per step (mean / p50 / p95), per-stage
+    and per-kernel device times, and the rooflines that follow from them."""
+    import torch
+    r = Runner(w, dev, model, heads)
+    if cache:
+        r.enable_cache(cache["host_table"], cache["ids"], cache["n_cache"])
+    n_total = warmup + steps
+    targets = [w.targets(i) for i in range(n_total)]
+    torch.cuda.synchronize()
+    targets_all = torch.stack(targets).contiguous() if use_graph else None
+    for i in range(warmup):
+        r.step(targets[i], i)
+    torch.cuda.synchronize()
+    graph_check = None
+    if use_graph:
+        # the same step as one captured HIP graph; its first replay is checked against the eager step
+        s_cap = torch.cuda.Stream(device=dev)
+        r.prepare_graphs(targets_all, 1)
+        g_step = r.capture(s_cap, ("step",))["step"]
+        torch.cuda.synchronize()
+        r.step(targets[0], 0)
+        torch.cuda.synchronize()
+        want = r.logits.clone()
+        r.step_idx.fill_(0)
+        r.logits.fill_(0.0)
+        g_step.replay()
+        torch.cuda.synchronize()
+        graph_check = bool(torch.equal(want, r.logits))
+        assert graph_check, "a replayed step differs from the eager step"
+        r.step_idx.fill_(warmup)
+        torch.cuda.synchronize()
+    # (1) K steps back to back on one stream, one synchronisation on each side
+    t0 = time.perf_counter()
+    for i in range(warmup, n_total):
+        if use_graph:
+            g_step.replay()
+        else:
+            r.step(targets[i], i)
+    torch.cuda.synchronize()
+    dt_serial = time.perf_counter() - t0
+    # (2) the same steps with one synchronisation at the end of every step: wall time per step
+    per_step = []
+    if not use_graph:
+        for i in range(warmup, n_total):
+            t1 = time.perf_counter()
+            r.step(targets[i], i)
+            torch.cuda.synchronize()
+            per_step.append((time.perf_counter() - t1) * 1e3)
+    # (3) sampling + splitting + loading of the next steps on sampling streams beside the training stream
+    dt = dt_serial
+    if pipeline:
+        pipe = Pipelined(w, dev, a.ahead, model, heads, a.sampler_blocks)
+        if cache:
+            for slot in pipe.slots:
+                slot.enable_cache(cache["host_table"], cache["ids"], cache["n_cache"])
+        pipe.run(targets, 0, warmup)
+        torch.cuda.synchronize()
+        if use_graph:
+            pipe.enable_graphs(targets_all)
+            pipe.run(targets, 0, warmup)
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pipe.run(targets, warmup, steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        for slot in pipe.slots:
+            slot.ctx.close()
+        del pipe
+
+    # per-stage device times (separate instrumented pass; events on the stream the kernels run on)
+    n_st = max(1, min(stage_iters, steps))
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_st)]
+    for i in range(n_st):
+        r.step(targets[warmup + i], warmup + i, ev[i])
+    torch.cuda.synchronize()
+    names = ["sample_split", "gather", f"{model}_fwd", "loss_grad", f"{model}_bwd"]
+    stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / n_st for k, nm in enumerate(names)}
+
+    # per-kernel device times: the library brackets each of its launches with HIP events on the
+    # launch stream; algorithmic bytes / flops are summed over the very same iterations
+    L, S = w.n_layers, w.n_splits
+    row_bytes = w.dims[0] * w.feat.element_size()
+    ip_bytes = w.indptr.element_size()
+    totals, own_totals = {}, {}
+    r.ctx.gsplit_timing_enable(True)
+    n_k = n_st
+    shape = None
+    for i in range(n_k):
+        r.step(targets[warmup + i], warmup + i)
+        n_local, n_mixed, n_edges, bucket = r.ctx.gsplit_batch_sizes()     # waits for sampling only
+        rows = [sum(x) for x in n_local]
+        edges = [sum(x) for x in n_edges]
+        mixed = [sum(x) for x in n_mixed]
+        shape = (rows, edges, mixed, bucket)
+        work, own = algorithmic_work(w, model, getattr(r, "heads", None), rows, edges, mixed, row_bytes, ip_bytes, S)
+        for k, (kind, amount) in work.items():
+            t = totals.setdefault(k, [kind, 0.0])
+            t[1] += amount
+        for k, amount in own.items():
+            own_totals[k] = own_totals.get(k, 0.0) + amount
+    torch.cuda.synchronize()
+    ktimes = r.ctx.gsplit_timing_read()
+    r.ctx.gsplit_timing_enable(False)
+    per_step_us = {k: v[1] / n_k * 1e3 for k, v in ktimes.items()}
+
+    def roofline_of(label):
+        cnt, ms = ktimes[label]
+        kind, amount = totals.get(label, ("bytes", 0.0))
+        per_launch = amount / max(cnt, 1)
+        sec = ms / max(cnt, 1) * 1e-3
+        traffic, src = profile_traffic(workload, dtype, model, label)
+        if kind == "flops":
+            ach = per_launch / sec / 1e12
+            peak = BF16_MFMA_PEAK_TFLOPS if dtype == "bf16" else FP32_MFMA_PEAK_TFLOPS
+            out = {"kernel": label, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                   "traffic": traffic, "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
+        else:
+            ach = per_launch / sec / 1e9
+            out = {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                   "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_launch": per_launch,
+                   "launch_ms": ms / max(cnt, 1)}
+            if label in own_totals:     # what the kernel moves for its own bookkeeping, not counted above
+                out["bookkeeping_bytes_per_launch"] = own_totals[label] / max(cnt, 1)
+        if traffic is not None:
+            out["traffic_source"] = src + " (a committed rocprofv3 --pmc summary, not measured in this run)"
+            out["traffic_GBps"] = traffic / sec / 1e9
+        return out
+
+    rows, edges, mixed, bucket = shape
+    dominant = max(per_step_us, key=per_step_us.get)
+    gather = roofline_of("gather_cached" if cache else "gather_rows")
+    sampling = [k for k in per_step_us if k.startswith(("sample_layer", "mixed_buckets", "shuffle_index"))]
+    out = {
+        "value": steps / dt, "ms_per_step": dt / steps * 1e3,
+        "schedule": ("serial, one stream" if not pipeline else
+                     f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the next {a.ahead} "
+                     f"step(s) overlap fwd/loss/bwd of step i; every step does all of its work"),
+        "serial": {"value": steps / dt_serial, "ms_per_step": dt_serial / steps * 1e3,
+                   "schedule": "one stream, steps enqueued back to back, one device synchronisation after the last"},
+        "serial_ms_per_step": dt_serial / steps * 1e3,
+        "gather_GBps": gather["achieved"], "stage_ms": stage_ms,
+        "kernel_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
+        "kernels_per_step": sum(v[0] for v in ktimes.values()) / n_k,
+        "batch_shape": {"rows_per_level": rows, "edges_per_layer": edges, "mixed_rows_per_layer": mixed,
+                        "ids_shuffled_per_layer": [sum(b[s][t] for s in range(S) for t in range(S) if s != t)
+                                                   for b in bucket]},
+        "roofline": roofline_of(dominant), "roofline_gather": gather,
+        "launch": ("every stream replays captured HIP graphs (the step counter and the targets table stay in device "
+                   "memory)" if use_graph else "kernels enqueued from the host"),
+    }
+    if per_step:
+        mean = sum(per_step) / len(per_step)
+        out["serial_sync"] = {"value": 1e3 / mean, "mean_ms": mean, "p50_ms": percentile(per_step, 0.5),
+                              "p95_ms": percentile(per_step, 0.95), "steps": len(per_step),
+                              "schedule": "one stream, one device synchronisation at the end of every step (host wall time per step)"}
+    if sampling:
+        big = max(sampling, key=per_step_us.get)
+        out["roofline_sampling"] = roofline_of(big)
+        out["sampling_target"] = {"target_frac_of_hbm_peak": 0.6, "achieved_frac": out["roofline_sampling"]["frac"],
+                                  "note": "algorithmic bytes of a word-granular random-access kernel; every such access "
+                                          "moves a whole 128-byte line (traffic, where a profile exists, is the hardware view)"}
+    if model == "sage":
+        out["roofline_linear"] = [roofline_of(k) for k in sorted(per_step_us)
+                                  if k.startswith(("linear_fwd", "grad_w", "grad_in"))]
+    if graph_check is not None:
+        out["graph_replay_equals_eager"] = graph_check
+    if cache:
+        # hits and misses of the kernel-timing iterations alone (the counters ran since the cache was built)
+        r.hits.zero_(); r.misses.zero_()
+        for i in range(n_k):
+            r.ctx.gsplit_sample_split(targets[warmup + i], r.seed, warmup + i)
+            r.load(count=True)
+        torch.cuda.synchronize()
+        h, m = int(r.hits.sum()), int(r.misses.sum())
+        PCIE_PEAK_GBS = 64.0       # PCIe 5.0 x16, one direction
+        link = m / n_k * row_bytes / (gather["launch_ms"] * 1e-3) / 1e9
+        gather["cache"] = {"fraction_cached": a.cache_frac, "rows_cached": int(sum(cache["n_cache"])),
+                           "hit_rate": h / max(h + m, 1), "miss_bytes_per_launch": m / n_k * row_bytes,
+                           "host_link": {"achieved": link, "peak": PCIE_PEAK_GBS, "unit": "GB/s", "frac": link / PCIE_PEAK_GBS}}
+    out["_runner"] = r
+    return out
+
+
+def extra_configs(a, dev, say):
+    """The other configurations, each timed serially on one stream with its own rooflines: large in
+    float32 and in bf16, skewed, and the split sweep on the large graph (1, 2, 4, 8 logical splits;
+    every stage also as a ratio to one split).  A configuration that fails reports its error and the
+    others still run."""
+    import torch
+    import workloads
+    out = {}
+
+    def run(tag, w, workload, dtype, steps=20, warmup=3):
+        t0 = time.time()
+        try:
+            torch.cuda.empty_cache()
+            m = measure(a, w, dev, workload=workload, dtype=dtype, steps=steps, warmup=warmup, pipeline=False,
+                        stage_iters=min(steps, 10))
+            m.pop("_runner").ctx.close()
+            m["config"] = w.describe()
+            m["dtype"] = dtype
+            m["wall_s"] = round(time.time() - t0, 1)
+            out[tag] = m
+            say(f"extra config {tag}: {m['serial_sync']['mean_ms']:.3f} ms per step, {m['wall_s']} s in all")
+        except Exception as e:                     # noqa: BLE001 - reported in the JSON line
+            out[tag] = {"error": f"{type(e).__name__}: {e}"}
+            say(f"extra config {tag} failed: {out[tag]['error']}")
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+
+    try:
+        w = workloads.large(device=dev, n_splits=4, feat_dtype=torch.float32, progress=say)
+        run("large_f32", w, "large", "f32")
+        w.feat = w.feat.to(torch.bfloat16)
+        torch.cuda.empty_cache()
+        run("large_bf16", w, "large", "bf16")
+        rank = workloads.bfs_rank(w.indptr, w.indices)
+        sweep = {}
+        for S in (1, 2, 4, 8):
+            v = workloads.variant(w, n_splits=S, pmap_kind="bfs", rank=rank, batch=8192, fanouts=(10, 10, 10, 10),
+                                  dims=(128, 256, 256, 256, 172), name=f"sweep-S{S}")
+            run(f"sweep_S{S}", v, "sweep", "bf16")
+            sweep[S] = out[f"sweep_S{S}"]
+            del v
+        if all("error" not in sweep[S] for S in sweep):
+            base = sweep[1]
+            out["sweep_relative_to_one_split"] = {
+                f"S{S}": dict({k: sweep[S]["stage_ms"][k] / base["stage_ms"][k] for k in base["stage_ms"]},
+                              step=sweep[S]["serial_sync"]["mean_ms"] / base["serial_sync"]["mean_ms"])
+                for S in sweep}
+        del w, rank, sweep
+    except Exception as e:                         # noqa: BLE001
+        out["large_graph_error"] = f"{type(e).__name__}: {e}"
+    torch.cuda.empty_cache()
+    try:
+        w = workloads.skewed(device=dev, n_splits=4, progress=say)
+        run("skewed_f32", w, "skewed", "f32")
+        del w
+    except Exception as e:                         # noqa: BLE001
+        out["skewed_graph_error"] = f"{type(e).__name__}: {e}"
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -539,17 +891,18 @@ def main():
     if a.model == "gat" and dtype != "f32":
         print("bench.py: --model gat runs in f32", file=sys.stderr)
         sys.exit(2)
-    r = Runner(w, dev, a.model, a.heads)
     cache_info = None
     if a.cache_frac is not None:
         # offline: rank every split's vertices by how often the sampler puts them into the input layer
         # (library kernel), keep the hottest fraction (a sort: the caller's policy step), build the cache
+        from paper_2303_13775_amd import Context
+        pre = Context(w.indptr, w.indices, w.pmap, w.n_splits, w.fanouts, w.batch)
         host_table = torch.empty(w.feat.shape, dtype=w.feat.dtype, pin_memory=True)
         host_table.copy_(w.feat)
         k_in = torch.zeros(w.n_vertices, dtype=torch.int32, device=dev)
         for i in range(a.cache_presample):
-            r.ctx.gsplit_sample_split(w.targets(10_000_000 + i), r.seed, 10_000_000 + i)
-            r.ctx.gsplit_input_counts_accumulate(k_in)
+            pre.gsplit_sample_split(w.targets(10_000_000 + i), 0xC0FFEE, 10_000_000 + i)
+            pre.gsplit_input_counts_accumulate(k_in)
         ids, n_cache = [], []
         for s_ in range(w.n_splits):
             own = torch.nonzero((w.pmap == s_) & (k_in > 0)).flatten()
@@ -559,215 +912,26 @@ def main():
             n_cache.append(int(ids[-1].numel()))
         cache_ids = torch.cat(ids).contiguous()
         cache_info = {"host_table": host_table, "ids": cache_ids, "n_cache": n_cache}
-        r.enable_cache(host_table, cache_ids, n_cache)
+        pre.close()
         del k_in
-    n_total = a.warmup + a.steps
-    targets = [w.targets(i) for i in range(n_total)]
-    torch.cuda.synchronize()
 
-    # strictly serial steps on one stream
-    use_graph = a.graph
-    targets_all = torch.stack(targets).contiguous() if use_graph else None
-    for i in range(a.warmup):
-        r.step(targets[i], i)
-    torch.cuda.synchronize()
-    graph_check = None
-    if use_graph:
-        # the same step as one captured HIP graph; its first replay is checked against the eager step
-        s_cap = torch.cuda.Stream(device=dev)
-        r.prepare_graphs(targets_all, 1)
-        g_step = r.capture(s_cap, ("step",))["step"]
-        torch.cuda.synchronize()
-        r.step(targets[0], 0)
-        torch.cuda.synchronize()
-        want = r.logits.clone()
-        r.step_idx.fill_(0)
-        r.logits.fill_(0.0)
-        g_step.replay()
-        torch.cuda.synchronize()
-        graph_check = bool(torch.equal(want, r.logits))
-        assert graph_check, "a replayed step differs from the eager step"
-        r.step_idx.fill_(a.warmup)
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(a.warmup, n_total):
-        if use_graph:
-            g_step.replay()
-        else:
-            r.step(targets[i], i)
-    torch.cuda.synchronize()
-    dt_serial = time.perf_counter() - t0
-    dt = dt_serial
-    if not a.no_pipeline:
-        pipe = Pipelined(w, dev, a.ahead, a.model, a.heads, a.sampler_blocks)
-        if cache_info:
-            for slot in pipe.slots:
-                slot.enable_cache(cache_info["host_table"], cache_info["ids"], cache_info["n_cache"])
-        pipe.run(targets, 0, a.warmup)
-        torch.cuda.synchronize()
-        if use_graph:
-            pipe.enable_graphs(targets_all)
-            pipe.run(targets, 0, a.warmup)
-            torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        pipe.run(targets, a.warmup, a.steps)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-    ms_per_step = dt / a.steps * 1e3
-
-    # per-stage device times (separate instrumented pass; events on the stream the kernels run on)
-    n_st = min(a.stage_iters, a.steps)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_st)]
-    for i in range(n_st):
-        r.step(targets[a.warmup + i], a.warmup + i, ev[i])
-    torch.cuda.synchronize()
-    names = ["sample_split", "gather", f"{a.model}_fwd", "loss_grad", f"{a.model}_bwd"]
-    stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / max(n_st, 1)
-                for k, nm in enumerate(names)}
-
-    # per-kernel device times: the library brackets each of its launches with HIP events on the
-    # launch stream; algorithmic bytes / flops are summed over the very same iterations
-    L, S = w.n_layers, w.n_splits
-    row_bytes = w.dims[0] * w.feat.element_size()
-    ip_bytes = w.indptr.element_size()
-    work = {}      # label -> [kind, amount]
-
-    def add(label, kind, amount):
-        work.setdefault(label, [kind, 0.0])[1] += amount
-
-    r.ctx.gsplit_timing_enable(True)
-    n_k = max(1, min(a.stage_iters, a.steps))
-    shape = None
-    for i in range(n_k):
-        r.step(targets[a.warmup + i], a.warmup + i)
-        n_local, n_mixed, n_edges, bucket = r.ctx.gsplit_batch_sizes()     # waits for sampling only
-        rows = [sum(x) for x in n_local]
-        edges = [sum(x) for x in n_edges]
-        mixed = [sum(x) for x in n_mixed]
-        shape = (rows, edges, mixed, bucket)
-        add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
-        add("gather_cached", "bytes", rows[0] * (2 * row_bytes + 8))
-        for l in range(L if a.model == "gat" else 0):
-            # the transform and both backward products run over the rows of level l; the row kernels
-            # move one transformed (or gradient) row per entry (edge or self) and its coefficients
-            D, nd, n_lo = w.dims[l], rows[l + 1], rows[l]
-            K = r.heads[l]
-            HF = K * w.dims[l + 1] if l == L - 1 else w.dims[l + 1]
-            ent = edges[l] + nd
-            if l == 0:
-                # bottom layer, aggregate-then-transform: per-head products over the destinations; the row
-                # kernels move one input row per entry
-                add("gat0_transform.l0", "flops", 2.0 * nd * D * HF)
-                add("gat0_grad_p.l0", "flops", 2.0 * nd * D * HF)
-                add("gat0_grad_w.l0", "flops", 2.0 * nd * D * HF)
-                add("gat0_scores.l0", "bytes", n_lo * 4 * (D + 2 * K))
-                add("gat0_aggregate.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
-                add("gat0_bwd.l0", "bytes", ent * (4 + 4 * D + 8 * K) + nd * 4 * K * D)
-            add(f"gat_transform.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
-            add(f"gat_grad_w.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
-            if l > 0:
-                add(f"gat_grad_in.l{l}", "flops", 2.0 * n_lo * D * (HF + 2 * K))
-            add(f"gat_aggregate.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * 4 * w.dims[l + 1])
-            add(f"gat_bwd_dst.l{l}", "bytes", ent * (4 + 4 * HF + 8 * K) + nd * (8 * w.dims[l + 1] + 4 * HF + 4 * K))
-            add(f"gat_bwd_src.l{l}", "bytes", ent * (8 + 4 * HF + 8 * K) + n_lo * (8 + 4 * (HF + 2 * K)))
-        for l in range(L):
-            D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
-            add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
-            add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N)
-            if l > 0:
-                add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
-                add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
-            # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
-            es = w.feat.element_size()
-            add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
-            # per destination: id + two indptr words read, count written, and like every edge below an
-            # 8-byte entry in each of the two tables and the two 4-byte entry indices it remembers;
-            # per edge: 4 read, 4 written, 2 x 8 table bytes, 2 x 4 index bytes
-            add(f"sample_layer.l{l}", "bytes", nd * (8 + 2 * ip_bytes + 24) + edges[l] * 32)
-            slots = nd * w.fanouts[l]
-            add(f"mixed_buckets_count.l{l}", "bytes", slots * (4 + 4 + 8 + 4) + edges[l] * 1)
-            add(f"mixed_buckets_scatter.l{l}", "bytes", slots * 4 + edges[l] * 4 + mixed[l] * (4 + 4 + 4 + 8 + 4))
-    torch.cuda.synchronize()
-    ktimes = r.ctx.gsplit_timing_read()
-    r.ctx.gsplit_timing_enable(False)
-    kernel_us = {k: v[1] / max(v[0], 1) * 1e3 for k, v in ktimes.items()}
-    per_step_us = {k: v[1] / n_k * 1e3 for k, v in ktimes.items()}
-    dominant = max(per_step_us, key=per_step_us.get)
-
-    def measured_traffic(label):
-        """HBM bytes per launch of this kernel from the committed rocprofv3 counter summary
-        (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration stated there), or None."""
-        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                            f"{a.workload}_bench_hbm_traffic.txt")
-        if a.model == "gat":
-            path = path.replace("_bench_", "_gat_bench_")
-        if dtype != "f32" or not os.path.exists(path):
-            return None
-        for line in open(path):
-            f = line.split()
-            if len(f) >= 6 and f[0] == label:
-                try:
-                    return (float(f[-2]) + float(f[-1])) * 1024.0
-                except ValueError:
-                    return None
-        return None
-
-    def roofline_of(label):
-        cnt, ms = ktimes[label]
-        kind, amount = work.get(label, ("bytes", 0.0))
-        per_launch = amount / max(cnt, 1)
-        sec = ms / max(cnt, 1) * 1e-3
-        if kind == "flops":
-            ach = per_launch / sec / 1e12
-            peak = BF16_MFMA_PEAK_TFLOPS if dtype == "bf16" else FP32_MFMA_PEAK_TFLOPS
-            return {"kernel": label, "bound": "mfma", "achieved": ach, "peak": peak,
-                    "unit": "TFLOP/s", "frac": ach / peak, "traffic": measured_traffic(label),
-                    "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
-        ach = per_launch / sec / 1e9
-        return {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(label), "bytes_per_launch": per_launch,
-                "launch_ms": ms / max(cnt, 1)}
-
-    rows, edges, mixed, bucket = shape
-    gather = roofline_of("gather_cached" if cache_info else "gather_rows")
-    if cache_info:
-        # hits and misses of the kernel-timing iterations alone (the counters ran since the cache was built)
-        r.hits.zero_(); r.misses.zero_()
-        for i in range(n_k):
-            r.ctx.gsplit_sample_split(targets[a.warmup + i], r.seed, a.warmup + i)
-            r.load(count=True)
-        torch.cuda.synchronize()
-        h, m = int(r.hits.sum()), int(r.misses.sum())
-        PCIE_PEAK_GBS = 64.0       # PCIe 5.0 x16, one direction
-        link = m / n_k * row_bytes / (gather["launch_ms"] * 1e-3) / 1e9
-        gather["cache"] = {"fraction_cached": a.cache_frac, "rows_cached": int(sum(cache_info["n_cache"])),
-                           "hit_rate": h / max(h + m, 1), "miss_bytes_per_launch": m / n_k * row_bytes,
-                           "host_link": {"achieved": link, "peak": PCIE_PEAK_GBS, "unit": "GB/s", "frac": link / PCIE_PEAK_GBS}}
+    m = measure(a, w, dev, workload=a.workload, dtype=dtype, model=a.model, heads=a.heads, steps=a.steps,
+                warmup=a.warmup, pipeline=not a.no_pipeline, stage_iters=a.stage_iters, cache=cache_info,
+                use_graph=a.graph)
+    r = m.pop("_runner")
     out = {
         "metric": f"mini-batches/sec (sample+split+gather+{'GAT' if a.model == 'gat' else 'SAGE'} fwd/bwd) at 1 GPU",
-        "value": a.steps / dt, "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
-        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": m.pop("value"), "unit": "mini-batches/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": m.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "value_schedule": m["schedule"],
         "config": dict(w.describe(), model=a.model, **({"heads": r.heads} if a.model == "gat" else {}),
                        fanout_order="fanouts[l] expands layer l+1 into layer l",
                        graph_gen_s=round(t_gen, 1),
                        **({"features": "pinned host memory", "cache_frac": a.cache_frac} if cache_info else {}),
-                       launch=("every stream replays captured HIP graphs (the step counter and the targets table "
-                               "stay in device memory)" if use_graph else "kernels enqueued from the host"),
-                       **({"graph_replay_equals_eager": graph_check} if use_graph else {}),
-                       schedule=("serial, one stream" if a.no_pipeline else
-                                 f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the "
-                                 f"next {a.ahead} step(s) overlap fwd/loss/bwd of step i")),
-        "serial_ms_per_step": dt_serial / a.steps * 1e3,
-        "gather_GBps": gather["achieved"],
-        "stage_ms": stage_ms,
-        "kernel_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
-        "batch_shape": {"rows_per_level": rows, "edges_per_layer": edges, "mixed_rows_per_layer": mixed,
-                        "ids_shuffled_per_layer": [sum(b[s][t] for s in range(S) for t in range(S) if s != t)
-                                                   for b in bucket]},
-        "roofline": roofline_of(dominant),
-        "roofline_gather": gather,
+                       launch=m.pop("launch"), schedule=m.pop("schedule")),
     }
+    out.update(m)
 
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -788,13 +952,22 @@ def main():
         out["cpu_baseline"] = cpu_baseline_gat(host, n_cpu)
     elif not a.no_cpu_baseline:
         host = {"indptr": w.indptr.cpu().numpy(), "indices": w.indices.cpu().numpy(),
-                "pmap": w.pmap.cpu().numpy(), "feat": w.feat.cpu().numpy(),
+                "pmap": w.pmap.cpu().numpy(), "feat": w.feat.float().cpu().numpy(),
                 "labels": w.labels.cpu().numpy(), "S": w.n_splits, "fanouts": w.fanouts,
                 "w_self": [t.cpu().numpy() for t in w.w_self],
                 "w_neigh": [t.cpu().numpy() for t in w.w_neigh],
                 "bias": [t.cpu().numpy() for t in w.bias],
                 "targets": [w.targets(a.warmup + i).cpu().numpy() for i in range(a.cpu_iters)]}
         out["cpu_baseline"] = cpu_baseline(host, a.cpu_iters)
+        del host
+    r.ctx.close()
+    if a.extra_configs is None:
+        a.extra_configs = (a.workload == "medium" and a.model == "sage" and dtype == "f32" and cache_info is None
+                           and not a.graph and not a.no_pipeline)
+    if a.extra_configs:
+        del w, r
+        torch.cuda.empty_cache()
+        out["extra_configs"] = extra_configs(a, dev, say)
     print(json.dumps(out))
 
 

@@ -186,10 +186,9 @@ def pmap_range(n_vertices: int, n_splits: int, *, device="cpu") -> torch.Tensor:
     return torch.div(v * n_splits, n_vertices, rounding_mode="floor").to(torch.uint8)
 
 
-def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) -> torch.Tensor:
-    """Locality map: rank vertices by BFS visit order from the max-degree vertex (ties inside a
-    level by id), vertices the search does not reach follow in id order; the ranking is cut into
-    n_splits equal blocks."""
+def bfs_rank(indptr: torch.Tensor, indices: torch.Tensor) -> torch.Tensor:
+    """Rank of every vertex in BFS visit order from the max-degree vertex (ties inside a level by
+    id); vertices the search does not reach follow in id order."""
     dev = indptr.device
     n = indptr.numel() - 1
     ip = indptr.to(torch.int64)
@@ -226,7 +225,18 @@ def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) 
             frontier = frontier[rank[frontier] < 0]
     rest = torch.nonzero(rank < 0).flatten()
     rank[rest] = next_rank + torch.arange(rest.numel(), device=dev)
+    return rank
+
+
+def pmap_from_rank(rank: torch.Tensor, n_splits: int) -> torch.Tensor:
+    """A ranking of the vertices cut into n_splits equal blocks."""
+    n = rank.numel()
     return torch.div(rank * n_splits, n, rounding_mode="floor").clamp(0, n_splits - 1).to(torch.uint8)
+
+
+def pmap_bfs_blocks(indptr: torch.Tensor, indices: torch.Tensor, n_splits: int) -> torch.Tensor:
+    """Locality map: the BFS ranking (bfs_rank) cut into n_splits equal blocks."""
+    return pmap_from_rank(bfs_rank(indptr, indices), n_splits)
 
 
 def features(n_vertices: int, dim: int, *, seed: int, device="cpu", dtype=torch.float32,
@@ -427,3 +437,37 @@ def custom(n_vertices: int, n_directed: int, *, dims, fanouts, batch, n_splits=4
     else:
         raise ValueError(pmap_kind)
     return _finish(name, n_vertices, indptr, indices, pmap, n_splits, dims, fanouts, batch, seed, device)
+
+
+def variant(w: Workload, *, n_splits: Optional[int] = None, batch: Optional[int] = None, fanouts=None, dims=None,
+            feat_dtype=None, pmap_kind: Optional[str] = None, name: Optional[str] = None, rank=None) -> Workload:
+    """The same graph, features and labels under another model / batch / split configuration (the
+    split sweep runs on the large graph): new weights for new dims, a new partition map for a new
+    number of splits (pmap_kind 'bfs' cuts `rank`, or a fresh BFS ranking, into blocks; 'range' cuts
+    the id range).  Input width and class count must stay what they are.  The tensors that do not
+    change are shared, not copied."""
+    import copy
+    v = copy.copy(w)
+    dev = w.indptr.device
+    if dims is not None:
+        assert dims[0] == w.dims[0] and dims[-1] == w.dims[-1], "features and labels are kept"
+        v.dims = list(dims)
+        v.w_self, v.w_neigh, v.bias = sage_weights(v.dims, seed=w.seed, device=dev)
+    if fanouts is not None:
+        v.fanouts = list(fanouts)
+    if batch is not None:
+        v.batch = int(batch)
+    if n_splits is not None and (n_splits != w.n_splits or pmap_kind is not None):
+        v.n_splits = int(n_splits)
+        kind = pmap_kind or "bfs"
+        if kind == "bfs":
+            v.pmap = pmap_from_rank(rank if rank is not None else bfs_rank(w.indptr, w.indices), v.n_splits)
+        elif kind == "range":
+            v.pmap = pmap_range(w.n_vertices, v.n_splits, device=dev)
+        else:
+            v.pmap = pmap_random(w.n_vertices, v.n_splits, seed=w.seed, device=dev)
+    if feat_dtype is not None and feat_dtype != w.feat.dtype:
+        v.feat = w.feat.to(feat_dtype)
+    if name:
+        v.name = name
+    return v
