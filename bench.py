@@ -43,7 +43,10 @@ def parse():
     ap.add_argument("--no-pipeline", action="store_true",
                     help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
                          "overlaps forward/backward of step i on a second stream)")
-    ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead)")
+    ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead); used with --multi 1")
+    ap.add_argument("--multi", type=int, default=4,
+                    help="mini-batches sampled per gsplit_sample_split_multi call (sampling does not depend on the "
+                         "weights: the batches of the next K steps go through one set of launches); 1 = one call per step")
     ap.add_argument("--sampler-blocks", type=int, default=2,
                     help="pipelined schedule: workgroups per compute unit the sampling kernels may occupy")
     ap.add_argument("--graph", action="store_true",
@@ -281,6 +284,94 @@ class Pipelined:
                 freed.put(None)
         finally:
             for _ in range(count):      # a sampler left waiting for a slot can always finish
+                freed.put(None)
+            th.join()
+
+
+class PipelinedGroups:
+    """The overlap schedule with sampling in groups: the mini-batches of the next K steps are sampled
+    and split by one gsplit_sample_split_multi call (one set of launches for all K) and loaded on a
+    sampling stream, while the training stream runs forward / loss / backward of the K steps of the
+    group before, one after the other (synchronous training: consecutive steps stay ordered).  Two
+    groups of K batch slots alternate; events hand a group over in both directions.  Every step
+    does all of its work."""
+
+    def __init__(self, w, dev, k, model="sage", heads=4, sampler_blocks=2):
+        import torch
+        self.torch = torch
+        self.k = k
+        self.groups = [[Runner(w, dev, model, heads, sampler_blocks_per_cu=sampler_blocks) for _ in range(k)]
+                       for _ in range(2)]
+        self.slots = [r for g in self.groups for r in g]
+        self.s_sample = torch.cuda.Stream(device=dev)
+        self.s_train = torch.cuda.Stream(device=dev)
+        self.ready = [torch.cuda.Event() for _ in range(2)]
+        self.free = [torch.cuda.Event() for _ in range(2)]
+        for e in self.free:
+            e.record()
+        # a fixed order of first use fixes which hardware queue each stream gets
+        for s in (self.s_train, self.s_sample):
+            with torch.cuda.stream(s):
+                torch.zeros(1, device=dev)
+        torch.cuda.synchronize()
+
+    def slot_of_step(self, i, first):
+        j = (i - first) // self.k
+        return self.groups[j % 2][(i - first) % self.k]
+
+    def run(self, targets, first, count):
+        import queue
+        import threading
+        from paper_2303_13775_amd import gsplit_sample_split_multi
+        torch = self.torch
+        k = self.k
+        n_groups = (count + k - 1) // k
+        sampled, freed = queue.Queue(), queue.Queue()
+        for _ in range(2):
+            freed.put(None)
+        failure = []
+
+        def sampler():
+            try:
+                torch.cuda.set_device(self.slots[0].dev)
+                for j in range(n_groups):
+                    freed.get()
+                    g = j % 2
+                    lo = first + j * k
+                    n = min(k, first + count - lo)
+                    rs = self.groups[g][:n]
+                    with torch.cuda.stream(self.s_sample):
+                        self.s_sample.wait_event(self.free[g])
+                        gsplit_sample_split_multi([r.ctx for r in rs], [targets[lo + b] for b in range(n)], rs[0].seed,
+                                                  [lo + b for b in range(n)])
+                        for r in rs:
+                            r.load()
+                        self.ready[g].record(self.s_sample)
+                    sampled.put(j)
+            except BaseException as e:      # hand the failure to the training thread
+                failure.append(e)
+                sampled.put(-1)
+
+        th = threading.Thread(target=sampler, name="gsplit-sampler")
+        th.start()
+        try:
+            for j in range(n_groups):
+                got = sampled.get()
+                if got != j:
+                    raise RuntimeError(f"sampling thread failed: {failure}")
+                g = j % 2
+                lo = first + j * k
+                n = min(k, first + count - lo)
+                with torch.cuda.stream(self.s_train):
+                    self.s_train.wait_event(self.ready[g])
+                    for r in self.groups[g][:n]:
+                        r.forward()
+                        r.loss()
+                        r.backward()
+                    self.free[g].record(self.s_train)
+                freed.put(None)
+        finally:
+            for _ in range(n_groups):
                 freed.put(None)
             th.join()
 
@@ -653,10 +744,46 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
             r.step(targets[i], i)
             torch.cuda.synchronize()
             per_step.append((time.perf_counter() - t1) * 1e3)
-    # (3) sampling + splitting + loading of the next steps on sampling streams beside the training stream
+    # (2b) one stream, sampling in groups: the next K mini-batches through one set of launches, then
+    # the K training steps one after the other
+    K = max(1, min(getattr(a, "multi", 1), steps))
+    serial_multi = None
+    if K > 1 and not use_graph:
+        from paper_2303_13775_amd import gsplit_sample_split_multi
+        rs = [r] + [Runner(w, dev, model, heads) for _ in range(K - 1)]
+        if cache:
+            for x in rs[1:]:
+                x.enable_cache(cache["host_table"], cache["ids"], cache["n_cache"])
+
+        def run_groups(lo, hi):
+            for g0 in range(lo, hi, K):
+                n = min(K, hi - g0)
+                gsplit_sample_split_multi([x.ctx for x in rs[:n]], [targets[g0 + b] for b in range(n)], r.seed,
+                                          [g0 + b for b in range(n)])
+                for x in rs[:n]:
+                    x.load()
+                for x in rs[:n]:
+                    x.forward(); x.loss(); x.backward()
+
+        run_groups(0, warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_groups(warmup, n_total)
+        torch.cuda.synchronize()
+        dt_multi = time.perf_counter() - t0
+        serial_multi = {"value": steps / dt_multi, "ms_per_step": dt_multi / steps * 1e3, "batches_per_sampling_call": K,
+                        "schedule": f"one stream; the mini-batches of the next {K} steps are sampled and split by one "
+                                    f"gsplit_sample_split_multi call, then loaded and trained one after the other"}
+        for x in rs[1:]:
+            x.ctx.close()
+        del rs
+    # (3) sampling + splitting + loading of the next steps on a sampling stream beside the training stream
     dt = dt_serial
     if pipeline:
-        pipe = Pipelined(w, dev, a.ahead, model, heads, a.sampler_blocks)
+        if K > 1 and not use_graph:
+            pipe = PipelinedGroups(w, dev, K, model, heads, a.sampler_blocks)
+        else:
+            pipe = Pipelined(w, dev, a.ahead, model, heads, a.sampler_blocks)
         if cache:
             for slot in pipe.slots:
                 slot.enable_cache(cache["host_table"], cache["ids"], cache["n_cache"])
@@ -740,6 +867,9 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
     out = {
         "value": steps / dt, "ms_per_step": dt / steps * 1e3,
         "schedule": ("serial, one stream" if not pipeline else
+                     (f"1 sampling stream + 1 training stream: sample+split (one gsplit_sample_split_multi call for "
+                      f"{K} mini-batches) and gather of the next {K} steps overlap fwd/loss/bwd of the current {K}; "
+                      f"every step does all of its work") if K > 1 and not use_graph else
                      f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the next {a.ahead} "
                      f"step(s) overlap fwd/loss/bwd of step i; every step does all of its work"),
         "serial": {"value": steps / dt_serial, "ms_per_step": dt_serial / steps * 1e3,
@@ -755,6 +885,8 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         "launch": ("every stream replays captured HIP graphs (the step counter and the targets table stay in device "
                    "memory)" if use_graph else "kernels enqueued from the host"),
     }
+    if serial_multi:
+        out["serial_multi"] = serial_multi
     if per_step:
         mean = sum(per_step) / len(per_step)
         out["serial_sync"] = {"value": 1e3 / mean, "mean_ms": mean, "p50_ms": percentile(per_step, 0.5),

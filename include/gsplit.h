@@ -47,6 +47,7 @@ extern "C" {
 #define GSPLIT_MAX_SPLITS  8
 #define GSPLIT_MAX_LAYERS  8
 #define GSPLIT_MAX_FANOUT  64
+#define GSPLIT_MAX_MULTI   8    /* mini-batches one gsplit_sample_split_multi call can take */
 
 #define GSPLIT_F32   0
 #define GSPLIT_BF16  1
@@ -112,6 +113,21 @@ GSPLIT_API int64_t gsplit_max_rows(const gsplit_ctx *ctx, int32_t level);
  * EINVAL for n_targets < 0 or NULL pointers, ECAPACITY for n_targets > max_targets. */
 GSPLIT_API int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                         uint64_t seed, uint64_t iter, void *stream);
+
+/* Algorithm 1 for several mini-batches in one set of launches.  Sampling depends on the graph, the
+ * targets and the random stream, not on the model's weights, so the mini-batches of the next steps
+ * can be sampled ahead of the training steps that consume them; n_batches of them go through the
+ * same kernels together (one launch serves all of them), which hides the chains of dependent
+ * memory accesses that a single small mini-batch consists of.  ctxs: HOST array of n_batches
+ * DISTINCT contexts created for the same graph arrays and the same configuration (1 ..
+ * GSPLIT_MAX_MULTI); batch b is sampled into ctxs[b] from d_targets[b] (HOST array of DEVICE
+ * pointers), n_targets[b] and iters[b] (HOST arrays) exactly as gsplit_sample_split(ctxs[b],
+ * d_targets[b], n_targets[b], seed, iters[b], stream) would: every output is bit-equal.
+ * Afterwards each context holds its batch and is used on its own.  Errors are reported on
+ * ctxs[0].  Asynchronous. */
+GSPLIT_API int gsplit_sample_split_multi(gsplit_ctx *const *ctxs, int32_t n_batches,
+                                         const int32_t *const *d_targets, const int64_t *n_targets,
+                                         uint64_t seed, const uint64_t *iters, void *stream);
 
 /* The same with the seed and the iteration counter read from DEVICE memory when the kernels run
  * (d_seed_iter[0] = seed, d_seed_iter[1] = iter), for steps that are captured into a HIP graph

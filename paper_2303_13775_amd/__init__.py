@@ -4,4 +4,5 @@ The package is a thin binding over libgsplit.so (hand-written HIP for gfx950).  
 not load the library; constructing a Context does, and fails loudly if the library is missing.
 """
 from .binding import (Context, SageParams, GatParams, GsplitError, load_library, LIB_PATH, EXPORTS,  # noqa: F401
-                      GSPLIT_F32, GSPLIT_BF16, gsplit_sample_split_noalloc, noalloc_output_sizes)
+                      GSPLIT_F32, GSPLIT_BF16, gsplit_sample_split_noalloc, noalloc_output_sizes,
+                      gsplit_sample_split_multi)

@@ -27,6 +27,7 @@ EXPORTS = [
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
     "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms", "gsplit_sample_split_noalloc",
+    "gsplit_sample_split_multi",
 ]
 
 
@@ -108,6 +109,7 @@ def load_library():
     L.gsplit_batch_sizes.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_batch_level.argtypes = [vp, i32, C.POINTER(_LevelView)]
     L.gsplit_batch_layer.argtypes = [vp, i32, C.POINTER(_LayerView)]
+    L.gsplit_sample_split_multi.argtypes = [C.POINTER(vp), i32, C.POINTER(vp), C.POINTER(i64), u64, C.POINTER(u64), vp]
     L.gsplit_sample_split_noalloc.argtypes = [C.POINTER(_Graph), C.POINTER(_Config), vp, i64, u64, u64,
                                               C.POINTER(_BatchOut), vp]
     L.gsplit_batch_shuffle.argtypes = [vp, i32, C.POINTER(_ShuffleView)]
@@ -222,6 +224,23 @@ def gsplit_sample_split_noalloc(indptr: torch.Tensor, indices: torch.Tensor, pma
                                              C.c_uint64(seed), C.c_uint64(it), C.byref(o), _stream())
     if rc != 0:
         raise GsplitError(rc, (lib.gsplit_last_error(None) or b"").decode())
+
+
+def gsplit_sample_split_multi(ctxs, targets, seed: int, iters):
+    """Samples targets[b] into ctxs[b] for all b in one set of launches (contexts over the same graph
+    and configuration)."""
+    n = len(ctxs)
+    assert n >= 1 and len(targets) == n and len(iters) == n
+    for t in targets:
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+    hs = (C.c_void_p * n)(*[c.h.value for c in ctxs])
+    tg = (C.c_void_p * n)(*[t.data_ptr() for t in targets])
+    nt = (C.c_int64 * n)(*[t.numel() for t in targets])
+    its = (C.c_uint64 * n)(*[int(i) for i in iters])
+    for c, t in zip(ctxs, targets):
+        c._targets = t
+    rc = ctxs[0].lib.gsplit_sample_split_multi(hs, n, tg, nt, C.c_uint64(seed), its, _stream())
+    ctxs[0]._check(rc)
 
 
 class SageParams:

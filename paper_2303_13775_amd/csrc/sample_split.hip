@@ -137,23 +137,39 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
 // (destinations first, then slots; -1 for padding slots, -2 - index for a slot that found its
 // (vertex, split) key already there with a smaller position).
 // ------------------------------------------------------------------------------------------
+// Arguments of one mini-batch of a launch.  Every sampling kernel serves up to GS_MAXB independent
+// mini-batches (contexts over the same graph) at once, blockIdx.y = batch: the kernels of a small
+// layer are chains of dependent accesses that leave the chip idle, and the chains of several batches
+// overlap (sampling does not depend on the weights, so the batches of the next steps are known).
+constexpr int GS_MAXB = GSPLIT_MAX_MULTI;
+
+struct SampleArgs {
+    const int32_t *front; GsLevelMeta *meta_lo; const GsLevelMeta *meta_up;
+    GsTable tab, tab_local;
+    int32_t *ent_mixed, *ent_local, *nbr, *cnt; int64_t *epos;
+    uint64_t iter; const uint64_t *seed_iter;
+};
+struct SampleArgsSet { SampleArgs b[GS_MAXB]; };
+
 template <int G, typename IndPtrT>
 __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict__ indptr,
                                                       const int32_t *__restrict__ indices,
-                                                      const int32_t *__restrict__ front,
-                                                      GsLevelMeta *meta_lo,
-                                                      const GsLevelMeta *__restrict__ meta_up, int S,
-                                                      int fan, uint32_t layer, uint64_t seed,
-                                                      uint64_t iter, const uint64_t *__restrict__ seed_iter,
-                                                      GsTable tab, GsTable tab_local,
-                                                      int32_t *__restrict__ ent_mixed,
-                                                      int32_t *__restrict__ ent_local,
-                                                      int32_t *__restrict__ nbr,
-                                                      int32_t *__restrict__ cnt,
-                                                      int64_t *__restrict__ epos) {
-    if (seed_iter) {        // seed and iteration counter kept in device memory (replayed graphs)
-        seed = seed_iter[0];
-        iter = seed_iter[1];
+                                                      SampleArgsSet set, int S,
+                                                      int fan, uint32_t layer, uint64_t seed) {
+    const SampleArgs &a = set.b[blockIdx.y];
+    const int32_t *__restrict__ front = a.front;
+    GsLevelMeta *meta_lo = a.meta_lo;
+    const GsLevelMeta *__restrict__ meta_up = a.meta_up;
+    const GsTable tab = a.tab, tab_local = a.tab_local;
+    int32_t *__restrict__ ent_mixed = a.ent_mixed;
+    int32_t *__restrict__ ent_local = a.ent_local;
+    int32_t *__restrict__ nbr = a.nbr;
+    int32_t *__restrict__ cnt = a.cnt;
+    int64_t *__restrict__ epos = a.epos;
+    uint64_t iter = a.iter;
+    if (a.seed_iter) {      // seed and iteration counter kept in device memory (replayed graphs)
+        seed = a.seed_iter[0];
+        iter = a.seed_iter[1];
     }
     const int n1 = meta_up->front_off[S];
     const int bits = table_bits(n1 * (1 + fan));
@@ -290,9 +306,15 @@ __device__ __forceinline__ int part_chunk(int n, int nb) {
     return ((c + PART_BS - 1) / PART_BS) * PART_BS;
 }
 
+// one functor and one histogram per mini-batch of the launch (blockIdx.y = batch)
+template <class F>
+struct PartSet { F f[GS_MAXB]; int32_t *hist[GS_MAXB]; };
+
 // hist is class-major: hist[k * gridDim.x + chunk]
 template <class F>
-__global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict__ hist) {
+__global__ __launch_bounds__(PART_BS) void k_part_count(PartSet<F> set) {
+    const F &f = set.f[blockIdx.y];
+    int32_t *__restrict__ hist = set.hist[blockIdx.y];
     __shared__ int s_cnt[PART_NK];
     if (threadIdx.x < PART_NK) s_cnt[threadIdx.x] = 0;
     __syncthreads();
@@ -330,7 +352,9 @@ __global__ __launch_bounds__(PART_BS) void k_part_count(F f, int32_t *__restrict
 
 // gridDim.x = 256 * PER chunks
 template <class F, int PER>
-__global__ __launch_bounds__(PART_BS) void k_part_scatter(F f, const int32_t *__restrict__ hist) {
+__global__ __launch_bounds__(PART_BS) void k_part_scatter(PartSet<F> set) {
+    const F &f = set.f[blockIdx.y];
+    const int32_t *__restrict__ hist = set.hist[blockIdx.y];
     __shared__ int s_tot[PART_NK], s_pre[PART_NK], s_base[PART_NK];
     __shared__ int s_run[PART_NK];
     __shared__ int s_wcnt[PART_BS / 64][PART_NK];
@@ -479,7 +503,10 @@ struct PartTargets {
 // launch by itself costs about as much as this kernel's work.
 constexpr int TARGETS_SMALL = 1024;
 
-__global__ __launch_bounds__(TARGETS_SMALL) void k_targets_small(PartTargets f) {
+struct TargetsSet { PartTargets f[GS_MAXB]; };
+
+__global__ __launch_bounds__(TARGETS_SMALL) void k_targets_small(TargetsSet set) {
+    const PartTargets &f = set.f[blockIdx.x];
     __shared__ int s_cnt[TARGETS_SMALL / 64][GS_MAXS];
     __shared__ int s_tot[GS_MAXS], s_base[GS_MAXS];
     __shared__ PartOffs s_o;
@@ -711,19 +738,28 @@ struct PartLayer {
 // on-GPU forward/backward (rows of local_cat[l] per destination vertex and per edge), and edges[l]
 // itself relabelled to rows of the owning split's mixed frontier; + reset of both tables for the
 // next sampling layer
-__global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTable tab_mixed,
-                                                       const int32_t *__restrict__ ent_mixed,
-                                                       const int32_t *__restrict__ ent_local,
-                                                       const int32_t *__restrict__ mixed_ent,
-                                                       const int32_t *__restrict__ blk_indptr,
-                                                       int32_t *__restrict__ blk_src,
-                                                       int32_t *__restrict__ src_row,
-                                                       int32_t *__restrict__ self_row,
-                                                       int32_t *__restrict__ edge_row,
-                                                       int32_t *__restrict__ rev_cnt,
-                                                       const GsLevelMeta *__restrict__ meta_lo,
-                                                       const GsLevelMeta *__restrict__ meta_up,
-                                                       int S, int fan, int fan_next, int64_t top_cap) {
+struct ShuffleArgs {
+    GsTable tab_local, tab_mixed;
+    const int32_t *ent_mixed, *ent_local, *mixed_ent, *blk_indptr;
+    int32_t *blk_src, *src_row, *self_row, *edge_row, *rev_cnt;
+    const GsLevelMeta *meta_lo, *meta_up;
+};
+struct ShuffleArgsSet { ShuffleArgs b[GS_MAXB]; };
+
+__global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S, int fan, int fan_next, int64_t top_cap) {
+    const ShuffleArgs &a = set.b[blockIdx.y];
+    const GsTable tab_local = a.tab_local, tab_mixed = a.tab_mixed;
+    const int32_t *__restrict__ ent_mixed = a.ent_mixed;
+    const int32_t *__restrict__ ent_local = a.ent_local;
+    const int32_t *__restrict__ mixed_ent = a.mixed_ent;
+    const int32_t *__restrict__ blk_indptr = a.blk_indptr;
+    int32_t *__restrict__ blk_src = a.blk_src;
+    int32_t *__restrict__ src_row = a.src_row;
+    int32_t *__restrict__ self_row = a.self_row;
+    int32_t *__restrict__ edge_row = a.edge_row;
+    int32_t *__restrict__ rev_cnt = a.rev_cnt;
+    const GsLevelMeta *__restrict__ meta_lo = a.meta_lo;
+    const GsLevelMeta *__restrict__ meta_up = a.meta_up;
     const int n1 = meta_up->front_off[S];
     const int64_t n_mixed = meta_lo->mixed_off[S];
     const int64_t n_slots = (int64_t)n1 * fan;
@@ -772,25 +808,23 @@ __global__ __launch_bounds__(256) void k_shuffle_index(GsTable tab_local, GsTabl
 // reverse index as two launches of its own (blockIdx.y = layer - first): used for the bottom layer,
 // which has no partition below it; same steps as RevUp::alloc / RevUp::fill
 struct RevArgs {
-    const int32_t *rev_cnt[GS_MAXL]; int32_t *rev_ptr[GS_MAXL]; int32_t *rev_fill[GS_MAXL];
-    int32_t *rev_list[GS_MAXL]; int32_t *rev_eid[GS_MAXL];
-    const int32_t *cnt[GS_MAXL]; const int32_t *blk_indptr[GS_MAXL]; const int32_t *self_row[GS_MAXL];
-    const int32_t *edge_row[GS_MAXL];
-    int fan[GS_MAXL];
-    int first;
+    const int32_t *rev_cnt; int32_t *rev_ptr; int32_t *rev_fill; int32_t *rev_list; int32_t *rev_eid;
+    const int32_t *cnt; const int32_t *blk_indptr; const int32_t *self_row; const int32_t *edge_row;
+    GsLevelMeta *meta;          // the batch's level bookkeeping, [L + 1]
 };
+struct RevArgsSet { RevArgs b[GS_MAXB]; };
 
 // step 2: give every row of local_cat[l] a segment of rev_list (segments need not be in row order:
 // one atomic per workgroup of 1024 rows hands out space; the cursor is a single address, and an
 // atomic on it from every wave of a million-row level took longer than the rest of the kernel)
-__global__ __launch_bounds__(1024) void k_rev_alloc(RevArgs a, GsLevelMeta *meta, int S) {
+__global__ __launch_bounds__(1024) void k_rev_alloc(RevArgsSet set, int l, int S) {
     __shared__ int s_wave[16];
     __shared__ int s_base;
-    const int l = a.first + blockIdx.y;
-    GsLevelMeta *meta_lo = meta + l;
-    const int32_t *__restrict__ rev_cnt = a.rev_cnt[l];
-    int32_t *__restrict__ rev_ptr = a.rev_ptr[l];
-    int32_t *__restrict__ rev_fill = a.rev_fill[l];
+    const RevArgs &a = set.b[blockIdx.y];
+    GsLevelMeta *meta_lo = a.meta + l;
+    const int32_t *__restrict__ rev_cnt = a.rev_cnt;
+    int32_t *__restrict__ rev_ptr = a.rev_ptr;
+    int32_t *__restrict__ rev_fill = a.rev_fill;
     const int n_lo = meta_lo->front_off[S];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int stride = gridDim.x * blockDim.x;
@@ -821,18 +855,17 @@ __global__ __launch_bounds__(1024) void k_rev_alloc(RevArgs a, GsLevelMeta *meta
 
 // step 3: list, for every source row, the destination rows it feeds (slot q of destination i is a
 // sampled edge when q < cnt[i])
-__global__ __launch_bounds__(256) void k_rev_fill(RevArgs a, const GsLevelMeta *__restrict__ meta, int S) {
-    const int l = a.first + blockIdx.y;
-    const int fan = a.fan[l];
-    const int32_t *__restrict__ cnt = a.cnt[l];
-    const int32_t *__restrict__ blk_indptr = a.blk_indptr[l];
-    const int32_t *__restrict__ self_row = a.self_row[l];
-    const int32_t *__restrict__ edge_row = a.edge_row[l];
-    const int32_t *__restrict__ rev_ptr = a.rev_ptr[l];
-    int32_t *__restrict__ rev_fill = a.rev_fill[l];
-    int32_t *__restrict__ rev_list = a.rev_list[l];
-    int32_t *__restrict__ rev_eid = a.rev_eid[l];
-    const int n1 = meta[l + 1].front_off[S];
+__global__ __launch_bounds__(256) void k_rev_fill(RevArgsSet set, int l, int fan, int S) {
+    const RevArgs &a = set.b[blockIdx.y];
+    const int32_t *__restrict__ cnt = a.cnt;
+    const int32_t *__restrict__ blk_indptr = a.blk_indptr;
+    const int32_t *__restrict__ self_row = a.self_row;
+    const int32_t *__restrict__ edge_row = a.edge_row;
+    const int32_t *__restrict__ rev_ptr = a.rev_ptr;
+    int32_t *__restrict__ rev_fill = a.rev_fill;
+    int32_t *__restrict__ rev_list = a.rev_list;
+    int32_t *__restrict__ rev_eid = a.rev_eid;
+    const int n1 = a.meta[l + 1].front_off[S];
     const int64_t total = (int64_t)n1 * (1 + fan);
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
@@ -859,61 +892,76 @@ int part_blocks(int64_t upper_items) {
     return upper_items <= (1 << 18) ? 256 : upper_items <= (1 << 20) ? 512 : PART_MAX_NB;
 }
 
+// kernel arguments are limited to 4 KiB
+static_assert(sizeof(PartSet<PartLayer>) <= 4096 && sizeof(PartSet<PartTargets>) <= 4096 && sizeof(TargetsSet) <= 4096 &&
+              sizeof(SampleArgsSet) <= 3072 && sizeof(ShuffleArgsSet) <= 3072 && sizeof(RevArgsSet) <= 3072,
+              "argument block of a multi-batch launch too large");
+
 template <class F>
-void run_partition(gsplit_ctx *ctx, const F &f, int64_t upper_items, hipStream_t st, const char *name,
-                   int layer) {
+void run_partition(gsplit_ctx *const *ctxs, int nbat, const PartSet<F> &set, int64_t upper_items, hipStream_t st,
+                   const char *name, int layer) {
+    gsplit_ctx *ctx = ctxs[0];
     const int nb = part_blocks(upper_items);
     const std::string nm(name);
     {
         GsTimeScope ts(ctx, (nm + "_count").c_str(), layer, st);
-        hipLaunchKernelGGL(k_part_count<F>, dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+        hipLaunchKernelGGL(k_part_count<F>, dim3(nb, nbat), dim3(PART_BS), 0, st, set);
     }
     GsTimeScope ts(ctx, (nm + "_scatter").c_str(), layer, st);
     if (nb == 256)
-        hipLaunchKernelGGL((k_part_scatter<F, 1>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+        hipLaunchKernelGGL((k_part_scatter<F, 1>), dim3(nb, nbat), dim3(PART_BS), 0, st, set);
     else if (nb == 512)
-        hipLaunchKernelGGL((k_part_scatter<F, 2>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+        hipLaunchKernelGGL((k_part_scatter<F, 2>), dim3(nb, nbat), dim3(PART_BS), 0, st, set);
     else
-        hipLaunchKernelGGL((k_part_scatter<F, 4>), dim3(nb), dim3(PART_BS), 0, st, f, ctx->part_hist);
+        hipLaunchKernelGGL((k_part_scatter<F, 4>), dim3(nb, nbat), dim3(PART_BS), 0, st, set);
 }
 
-int grid_for(const gsplit_ctx *ctx, int64_t upper_items) {
+// grid of a grid-stride kernel over upper_items elements; with several batches in the launch the
+// cap on resident workgroups is shared between them
+int grid_for(const gsplit_ctx *ctx, int64_t upper_items, int nbat = 1) {
     int64_t want = gs_ceil_div(upper_items, 256);
-    int64_t cap = (int64_t)ctx->n_cu * ctx->sampler_blocks_per_cu;
+    int64_t cap = std::max<int64_t>(1, (int64_t)ctx->n_cu * ctx->sampler_blocks_per_cu / nbat);
     if (want < 1) want = 1;
     return (int)(want < cap ? want : cap);
 }
 
 template <typename IndPtrT>
-void launch_sample(gsplit_ctx *ctx, int l, uint64_t seed, uint64_t iter, const uint64_t *d_seed_iter, hipStream_t st) {
+void launch_sample(gsplit_ctx *const *ctxs, int nbat, int l, uint64_t seed, const uint64_t *iters,
+                   const uint64_t *d_seed_iter, hipStream_t st) {
+    gsplit_ctx *ctx = ctxs[0];
     const int fan = ctx->fan[l];
     const int64_t ub = ctx->ub_front[l + 1];
-    GsLevelMeta *ml = ctx->d_meta + l;
-    const GsLevelMeta *mu = ctx->d_meta + (l + 1);
     const IndPtrT *ip = (const IndPtrT *)ctx->graph.d_indptr;
-    GsLayerBuf &B = ctx->layer[l];
+    SampleArgsSet set{};
+    for (int b = 0; b < nbat; ++b) {
+        gsplit_ctx *c = ctxs[b];
+        GsLayerBuf &B = c->layer[l];
+        set.b[b] = SampleArgs{c->front[l + 1], c->d_meta + l, c->d_meta + (l + 1), c->tab_mixed, c->tab_local,
+                              c->ent_mixed, c->ent_local, B.nbr, B.cnt, B.epos, iters[b], d_seed_iter};
+    }
     GsTimeScope ts(ctx, "sample_layer", l, st);
     if (fan <= 16) {
-        hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
+        hipLaunchKernelGGL((k_sample_layer<16, IndPtrT>), dim3(grid_for(ctx, ub * 16, nbat), nbat), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, set, ctx->S, fan, (uint32_t)l, seed);
     } else if (fan <= 32) {
-        hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
+        hipLaunchKernelGGL((k_sample_layer<32, IndPtrT>), dim3(grid_for(ctx, ub * 32, nbat), nbat), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, set, ctx->S, fan, (uint32_t)l, seed);
     } else {
-        hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64)), dim3(256), 0, st,
-                           ip, ctx->graph.d_indices, ctx->front[l + 1], ml, mu, ctx->S, fan, (uint32_t)l,
-                           seed, iter, d_seed_iter, ctx->tab_mixed, ctx->tab_local, ctx->ent_mixed, ctx->ent_local, B.nbr, B.cnt, B.epos);
+        hipLaunchKernelGGL((k_sample_layer<64, IndPtrT>), dim3(grid_for(ctx, ub * 64, nbat), nbat), dim3(256), 0, st,
+                           ip, ctx->graph.d_indices, set, ctx->S, fan, (uint32_t)l, seed);
     }
 }
 
-int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, uint64_t seed, uint64_t iter,
-                 const uint64_t *d_seed_iter, void *stream) {
-    if (n_targets < 0 || (n_targets > 0 && !d_targets))
-        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split: bad targets");
-    if (n_targets > ctx->max_targets)
-        return gs_fail(ctx, GSPLIT_ECAPACITY, "gsplit_sample_split: n_targets exceeds max_targets");
+// Algorithm 1 for nbat mini-batches at once, one context each (same graph, same configuration)
+int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targets, const int64_t *n_targets,
+                 uint64_t seed, const uint64_t *iters, const uint64_t *d_seed_iter, void *stream) {
+    gsplit_ctx *ctx = ctxs[0];
+    for (int b = 0; b < nbat; ++b) {
+        if (n_targets[b] < 0 || (n_targets[b] > 0 && !d_targets[b]))
+            return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split: bad targets");
+        if (n_targets[b] > ctxs[b]->max_targets)
+            return gs_fail(ctx, GSPLIT_ECAPACITY, "gsplit_sample_split: n_targets exceeds max_targets");
+    }
     hipStream_t st = (hipStream_t)stream;
     const int S = ctx->S, L = ctx->L;
     // Under stream capture the calls of a step become nodes of a graph: no event is recorded for the
@@ -923,81 +971,96 @@ int sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets, u
         (void)hipGetLastError();
         cap = hipStreamCaptureStatusNone;
     }
-    ctx->captured = cap == hipStreamCaptureStatusActive;
+    bool all_small = true;
+    for (int b = 0; b < nbat; ++b) {
+        gsplit_ctx *c = ctxs[b];
+        c->captured = cap == hipStreamCaptureStatusActive;
+        c->batch_id += 1;
+        c->n_targets = n_targets[b];
+        c->h_meta_valid = false;
+        c->sage.fwd_done = false;
+        c->last_stream = st;
+        all_small = all_small && n_targets[b] <= TARGETS_SMALL;
+    }
 
-    ctx->batch_id += 1;
-    ctx->n_targets = n_targets;
-    ctx->h_meta_valid = false;
-    ctx->sage.fwd_done = false;
-    ctx->last_stream = st;
-
-    PartTargets pt{d_targets, (int)n_targets, ctx->graph.d_pmap, S, (uint32_t)ctx->graph.n_vertices,
-                   ctx->front[L], ctx->target_perm, ctx->d_meta + L, ctx->tab_mixed, ctx->fan[L - 1],
-                   ctx->d_meta, L + 1, ctx->tab_local};
     int64_t top_cap = 1024;                             // = 1 << table_bits(max_targets * (1 + fan_top))
     while (top_cap < 2 * ctx->max_targets * (1 + ctx->fan[L - 1])) top_cap <<= 1;
     {
-        if (n_targets <= TARGETS_SMALL) {
+        auto targets_of = [&](int b) {
+            gsplit_ctx *c = ctxs[b];
+            return PartTargets{d_targets[b], (int)n_targets[b], c->graph.d_pmap, S, (uint32_t)c->graph.n_vertices,
+                               c->front[L], c->target_perm, c->d_meta + L, c->tab_mixed, c->fan[L - 1],
+                               c->d_meta, L + 1, c->tab_local};
+        };
+        if (all_small) {
+            TargetsSet set{};
+            for (int b = 0; b < nbat; ++b) set.f[b] = targets_of(b);
             GsTimeScope ts(ctx, "targets", -1, st);
-            hipLaunchKernelGGL(k_targets_small, dim3(1), dim3(TARGETS_SMALL), 0, st, pt);
+            hipLaunchKernelGGL(k_targets_small, dim3(nbat), dim3(TARGETS_SMALL), 0, st, set);
         } else {
-            run_partition(ctx, pt, ctx->ub_front[L], st, "targets", -1);
+            PartSet<PartTargets> set{};
+            for (int b = 0; b < nbat; ++b) { set.f[b] = targets_of(b); set.hist[b] = ctxs[b]->part_hist; }
+            run_partition(ctxs, nbat, set, ctx->ub_front[L], st, "targets", -1);
         }
     }
 
     for (int l = L - 1; l >= 0; --l) {
         const int fan = ctx->fan[l];
         const int64_t ub1 = ctx->ub_front[l + 1];
-        GsLayerBuf &B = ctx->layer[l];
-        GsLevelMeta *ml = ctx->d_meta + l;
-        const GsLevelMeta *mu = ctx->d_meta + (l + 1);
 
-        if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctx, l, seed, iter, d_seed_iter, st);
-        else launch_sample<int32_t>(ctx, l, seed, iter, d_seed_iter, st);
+        if (ctx->graph.indptr_is_64) launch_sample<int64_t>(ctxs, nbat, l, seed, iters, d_seed_iter, st);
+        else launch_sample<int32_t>(ctxs, nbat, l, seed, iters, d_seed_iter, st);
 
-        PartLayer pa{ctx->tab_mixed, ctx->tab_local, ctx->front[l + 1], B.nbr, ctx->graph.d_pmap,
-                     ctx->ent_mixed, ctx->ent_local, ctx->cls, ctx->mixed_ent,
-                     B.mixed, B.blk_indptr, B.recv, ctx->front[l], B.rev_cnt,
-                     ml, mu, S, fan, l >= ctx->rev_from ? 1 : 0, RevUp{}};
-        if (l + 1 < L && l + 1 >= ctx->rev_from) {
-            const GsLayerBuf &U = ctx->layer[l + 1];
-            pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
-                          U.self_row, U.edge_row, ctx->fan[l + 1], &ctx->d_meta[l + 1].rev_cursor, ctx->d_meta + (l + 2)};
+        PartSet<PartLayer> pset{};
+        ShuffleArgsSet sset{};
+        for (int b = 0; b < nbat; ++b) {
+            gsplit_ctx *c = ctxs[b];
+            GsLayerBuf &B = c->layer[l];
+            GsLevelMeta *ml = c->d_meta + l;
+            const GsLevelMeta *mu = c->d_meta + (l + 1);
+            PartLayer pa{c->tab_mixed, c->tab_local, c->front[l + 1], B.nbr, c->graph.d_pmap,
+                         c->ent_mixed, c->ent_local, c->cls, c->mixed_ent,
+                         B.mixed, B.blk_indptr, B.recv, c->front[l], B.rev_cnt,
+                         ml, mu, S, fan, l >= c->rev_from ? 1 : 0, RevUp{}};
+            if (l + 1 < L && l + 1 >= c->rev_from) {
+                const GsLayerBuf &U = c->layer[l + 1];
+                pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
+                              U.self_row, U.edge_row, c->fan[l + 1], &c->d_meta[l + 1].rev_cursor, c->d_meta + (l + 2)};
+            }
+            pset.f[b] = pa;
+            pset.hist[b] = c->part_hist;
+            sset.b[b] = ShuffleArgs{c->tab_local, c->tab_mixed, c->ent_mixed, c->ent_local, c->mixed_ent, B.blk_indptr,
+                                    B.blk_src, B.src_row, B.self_row, B.edge_row, l >= c->rev_from ? B.rev_cnt : nullptr,
+                                    ml, mu};
         }
-        run_partition(ctx, pa, ub1 * fan, st, "mixed_buckets", l);
+        run_partition(ctxs, nbat, pset, ub1 * fan, st, "mixed_buckets", l);
         {
-        GsTimeScope ts(ctx, "shuffle_index", l, st);
-        hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan))), dim3(256), 0, st,
-                           ctx->tab_local, ctx->tab_mixed, ctx->ent_mixed, ctx->ent_local, ctx->mixed_ent,
-                           B.blk_indptr, B.blk_src, B.src_row, B.self_row, B.edge_row, l >= ctx->rev_from ? B.rev_cnt : nullptr,
-                           ml, mu, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l == 0 ? top_cap : 0);
+            GsTimeScope ts(ctx, "shuffle_index", l, st);
+            hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan), nbat), nbat), dim3(256), 0, st,
+                               sset, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l == 0 ? top_cap : 0);
         }
     }
     // the bottom layer's reverse index (contexts that keep one) has no partition below it to ride on
     if (ctx->rev_from == 0) {
-        RevArgs ra{};
-        ra.first = 0;
-        int64_t rows = 1, items = 1;
-        for (int l = 0; l < 1; ++l) {
-            const GsLayerBuf &B = ctx->layer[l];
-            ra.rev_cnt[l] = B.rev_cnt; ra.rev_ptr[l] = B.rev_ptr; ra.rev_fill[l] = B.rev_fill; ra.rev_list[l] = B.rev_list;
-            ra.rev_eid[l] = B.rev_eid; ra.cnt[l] = B.cnt; ra.blk_indptr[l] = B.blk_indptr; ra.self_row[l] = B.self_row;
-            ra.edge_row[l] = B.edge_row; ra.fan[l] = ctx->fan[l];
-            rows = std::max<int64_t>(rows, ctx->ub_front[l]);
-            items = std::max<int64_t>(items, ctx->ub_front[l + 1] * (1 + ctx->fan[l]));
+        RevArgsSet ra{};
+        for (int b = 0; b < nbat; ++b) {
+            const GsLayerBuf &B = ctxs[b]->layer[0];
+            ra.b[b] = RevArgs{B.rev_cnt, B.rev_ptr, B.rev_fill, B.rev_list, B.rev_eid, B.cnt, B.blk_indptr, B.self_row,
+                              B.edge_row, ctxs[b]->d_meta};
         }
-        const unsigned ny = 1;
+        const int64_t rows = std::max<int64_t>(1, ctx->ub_front[0]);
+        const int64_t items = std::max<int64_t>(1, ctx->ub_front[1] * (1 + ctx->fan[0]));
         {
             GsTimeScope ts(ctx, "rev_alloc", -1, st);
             hipLaunchKernelGGL(k_rev_alloc, dim3((unsigned)std::max<int64_t>(1, std::min<int64_t>(
-                                   (int64_t)ctx->n_cu * 2, gs_ceil_div(rows, 1024))), ny), dim3(1024), 0, st, ra,
-                               ctx->d_meta, S);
+                                   (int64_t)ctx->n_cu * 2, gs_ceil_div(rows, 1024))), nbat), dim3(1024), 0, st, ra, 0, S);
         }
         GsTimeScope ts(ctx, "rev_fill", -1, st);
-        hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, items), ny), dim3(256), 0, st, ra, ctx->d_meta, S);
+        hipLaunchKernelGGL(k_rev_fill, dim3(grid_for(ctx, items, nbat), nbat), dim3(256), 0, st, ra, 0, ctx->fan[0], S);
     }
     GS_HIP(ctx, hipGetLastError());
-    if (!ctx->captured && ctx->sample_done) GS_HIP(ctx, hipEventRecord(ctx->sample_done, st));
+    for (int b = 0; b < nbat; ++b)
+        if (!ctxs[b]->captured && ctxs[b]->sample_done) GS_HIP(ctx, hipEventRecord(ctxs[b]->sample_done, st));
     return GSPLIT_OK;
 }
 
@@ -1152,7 +1215,8 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     hipLaunchKernelGGL(k_noalloc_reset, dim3((unsigned)std::min<int64_t>(1024, gs_ceil_div(tab_cap, 256))), dim3(256), 0, st,
                        ctx.tab_mixed, ctx.tab_local, tab_cap, (int32_t *)ctx.d_meta,
                        (int)(sizeof(GsLevelMeta) * (L + 1) / sizeof(int32_t)));
-    rc = sample_split(&ctx, d_targets, n_targets, seed, iter, nullptr, stream);
+    gsplit_ctx *one = &ctx;
+    rc = sample_split(&one, 1, &d_targets, &n_targets, seed, &iter, nullptr, stream);
     if (rc != GSPLIT_OK) return gs_fail(nullptr, rc, std::string(who) + ctx.err);
     hipLaunchKernelGGL(k_noalloc_export, dim3(1), dim3(64), 0, st, ctx.d_meta, L, S, out->d_local_off, out->d_mixed_off,
                        out->d_recv_off);
@@ -1163,12 +1227,38 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
 extern "C" int gsplit_sample_split(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                                    uint64_t seed, uint64_t iter, void *stream) {
     if (!ctx) return GSPLIT_EINVAL;
-    return sample_split(ctx, d_targets, n_targets, seed, iter, nullptr, stream);
+    return sample_split(&ctx, 1, &d_targets, &n_targets, seed, &iter, nullptr, stream);
+}
+
+extern "C" int gsplit_sample_split_multi(gsplit_ctx *const *ctxs, int32_t n_batches, const int32_t *const *d_targets,
+                                         const int64_t *n_targets, uint64_t seed, const uint64_t *iters, void *stream) {
+    if (!ctxs || n_batches < 1 || !ctxs[0]) return GSPLIT_EINVAL;
+    gsplit_ctx *first = ctxs[0];
+    if (n_batches > GSPLIT_MAX_MULTI)
+        return gs_fail(first, GSPLIT_ECAPACITY, "gsplit_sample_split_multi: more than GSPLIT_MAX_MULTI batches");
+    if (!d_targets || !n_targets || !iters) return gs_fail(first, GSPLIT_EINVAL, "gsplit_sample_split_multi: NULL argument");
+    for (int b = 0; b < n_batches; ++b) {
+        const gsplit_ctx *c = ctxs[b];
+        if (!c) return gs_fail(first, GSPLIT_EINVAL, "gsplit_sample_split_multi: NULL context");
+        for (int a = 0; a < b; ++a)
+            if (ctxs[a] == c) return gs_fail(first, GSPLIT_EINVAL, "gsplit_sample_split_multi: a context is listed twice");
+        bool same = c->L == first->L && c->S == first->S && c->max_targets == first->max_targets &&
+                    c->keep_edge_ids == first->keep_edge_ids && c->gat_index == first->gat_index &&
+                    c->sampler_blocks_per_cu == first->sampler_blocks_per_cu &&
+                    c->graph.d_indptr == first->graph.d_indptr && c->graph.d_indices == first->graph.d_indices &&
+                    c->graph.d_pmap == first->graph.d_pmap && c->graph.n_vertices == first->graph.n_vertices &&
+                    c->graph.indptr_is_64 == first->graph.indptr_is_64;
+        for (int l = 0; same && l < first->L; ++l) same = c->fan[l] == first->fan[l];
+        if (!same)
+            return gs_fail(first, GSPLIT_EINVAL, "gsplit_sample_split_multi: the contexts differ in graph or configuration");
+    }
+    return sample_split(ctxs, n_batches, d_targets, n_targets, seed, iters, nullptr, stream);
 }
 
 extern "C" int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets, int64_t n_targets,
                                        const uint64_t *d_seed_iter, void *stream) {
     if (!ctx) return GSPLIT_EINVAL;
     if (!d_seed_iter) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sample_split_dev: NULL seed / iteration buffer");
-    return sample_split(ctx, d_targets, n_targets, 0, 0, d_seed_iter, stream);
+    const uint64_t zero = 0;
+    return sample_split(&ctx, 1, &d_targets, &n_targets, 0, &zero, d_seed_iter, stream);
 }

@@ -117,6 +117,38 @@ def test_shuffle_index_scatter_side_with_edge_ids(name):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,n_batches", [("tiny", 4), ("ragged-S3", 3), ("fan32-S8-int64", 8), ("S1", 2),
+                                            ("many-chunks", 2)])
+def test_multi_batch_sampling_bit_exact(name, n_batches):
+    """gsplit_sample_split_multi: several mini-batches through one set of launches, every one of them
+    bit-equal to the oracle's (and hence to gsplit_sample_split's), batches of different sizes
+    (the last one empty when there are more than two), both sides of the shuffle index included;
+    then a training step on one of them."""
+    from paper_2303_13775_amd import Context, GsplitError, gsplit_sample_split_multi
+    dev = _dev()
+    w = CASES[name]()
+    gi, gx, gp = w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev)
+    ctxs = [Context(gi, gx, gp, w.n_splits, w.fanouts, w.batch) for _ in range(n_batches)]
+    for rnd in (0, 1):
+        its = [10 * rnd + b for b in range(n_batches)]
+        tgs = [w.targets(it)[:max(0, w.batch - 37 * b)] for b, it in enumerate(its)]
+        if n_batches > 2:
+            tgs[-1] = tgs[-1][:0]
+        gsplit_sample_split_multi(ctxs, [t.to(dev) for t in tgs], 777, its)
+        for b in range(n_batches):
+            ob = _oracle_batch(w, tgs[b], 777, its[b])
+            assert_batch_equal(ctxs[b].fetch_batch(), ob, w.n_splits, w.n_layers)
+            for l in range(w.n_layers):
+                SC.assert_shuffle_index_equal(ctxs[b], ob, l, has_rev=l >= 1)
+    with pytest.raises(GsplitError):                       # the same context twice
+        gsplit_sample_split_multi([ctxs[0], ctxs[0]], [tgs[0].to(dev)] * 2, 1, [0, 1])
+    other = Context(gi, gx, gp, w.n_splits, w.fanouts, max(1, w.batch // 2))
+    with pytest.raises(GsplitError):                       # another configuration
+        gsplit_sample_split_multi([ctxs[0], other], [tgs[0].to(dev)[:1]] * 2, 1, [0, 1])
+    for c in ctxs + [other]:
+        c.close()
+
+
 def test_edge_cases_empty_isolated_and_unowned_split():
     dev = _dev()
     w = workloads.custom(500, 1500, dims=[8, 8, 4], fanouts=[3, 2], batch=16, n_splits=4, name="edge")

@@ -1,7 +1,9 @@
-"""The schedule bench.py times, checked as it is timed: three batch slots (contexts whose sampling
-kernels may occupy two workgroups per compute unit), two sampling streams and a training stream,
-two host threads, events handing the slots over in both directions, on the benchmark workload at
-its full size.  After a run every slot still holds its last step: the integer outputs, the
+"""The schedules bench.py times, checked as they are timed, on the benchmark workload at its full
+size: (groups, the default) two groups of four batch slots, the mini-batches of a group sampled by
+one gsplit_sample_split_multi call on a sampling stream while the training stream works through
+the group before; (streams, `--multi 1`) three batch slots, two sampling streams and a training
+stream.  Contexts whose sampling kernels may occupy two workgroups per compute unit, two host
+threads, events handing the slots over in both directions.  After a run every slot still holds its last step: the integer outputs, the
 gathered rows, the logits and every gradient of those steps against the oracle (GraphSAGE), and
 for both models the logits against a strictly serial run of the same steps on one stream
 (bit-equal: same kernels, same inputs)."""
@@ -18,22 +20,32 @@ import sage_check as SC
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("model", ["sage", "gat"])
-def test_pipelined_schedule_leaves_the_oracles_results_in_every_slot(model):
+@pytest.mark.parametrize("model,schedule", [("sage", "groups"), ("sage", "streams"), ("gat", "groups"), ("gat", "streams")])
+def test_pipelined_schedule_leaves_the_oracles_results_in_every_slot(model, schedule):
     assert torch.cuda.is_available(), "needs the MI355X"
     dev = torch.device("cuda:0")
     w = workloads.medium(device=dev)
-    n_steps = 11                                    # not a multiple of the three slots
+    n_steps = 11                                    # not a multiple of the slots, the last group is partial
     targets = [w.targets(i) for i in range(n_steps)]
-    pipe = bench.Pipelined(w, dev, 2, model, 4, 2)
+    torch.cuda.synchronize()
+    if schedule == "groups":
+        pipe = bench.PipelinedGroups(w, dev, 4, model, 4, 2)
+        slot_of = lambda i: pipe.slot_of_step(i, 0)
+    else:
+        pipe = bench.Pipelined(w, dev, 2, model, 4, 2)
+        slot_of = lambda i: pipe.slots[i % pipe.n]
     pipe.run(targets, 0, n_steps)
     torch.cuda.synchronize()
+    last = {}                                       # the last step every slot worked on
+    for i in range(n_steps):
+        last[id(slot_of(i))] = i
     host = dict(indptr=w.indptr.cpu().numpy(), indices=w.indices.cpu().numpy(), pmap=w.pmap.cpu().numpy())
     op = R.SageParams([t.cpu().numpy() for t in w.w_self], [t.cpu().numpy() for t in w.w_neigh],
                       [t.cpu().numpy() for t in w.bias])
     serial = bench.Runner(w, dev, model, 4)
-    for i in range(n_steps - pipe.n, n_steps):      # the last step of every slot
-        r = pipe.slots[i % pipe.n]
+    assert len(last) >= 3
+    for i in sorted(last.values()):
+        r = slot_of(i)
         tg = targets[i]
         ob = R.sp_sample(host["indptr"], host["indices"], host["pmap"], w.n_splits, w.fanouts,
                          tg.cpu().numpy(), r.seed, i)
