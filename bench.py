@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--splits", type=int, default=4, help="number of logical splits")
     ap.add_argument("--model", default="sage", choices=["sage", "gat"])
     ap.add_argument("--heads", type=int, default=4, help="GAT: attention heads of the hidden layers (the last has one)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="GraphSAGE: forward, loss and backward as three calls (gsplit_sage_fwd, gsplit_softmax_xent, "
+                         "gsplit_sage_bwd) instead of gsplit_sage_step, which runs the top layer as one kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=120)
     ap.add_argument("--no-pipeline", action="store_true",
@@ -77,6 +80,8 @@ def parse():
 
 class Runner:
     """Holds the device-resident inputs, the context and the preallocated outputs of a step."""
+
+    separate_calls = False      # set from --separate-calls
 
     def __init__(self, w, dev, model="sage", heads=4, sampler_blocks_per_cu=0):
         import torch
@@ -136,9 +141,16 @@ class Runner:
         self.load()
 
     def _train(self):
-        self.forward()
-        self.loss()
-        self.backward()
+        self.train()
+
+    def train(self):
+        """Forward, loss and backward of the current batch: one call for GraphSAGE unless told otherwise."""
+        if self.model == "sage" and not Runner.separate_calls:
+            self.ctx.gsplit_sage_step(self.params, self.x0, self.w.labels, self.logits, *self.grads)
+        else:
+            self.forward()
+            self.loss()
+            self.backward()
 
     def capture(self, stream, parts):
         """One graph per element of parts ('sample', 'train', or 'step' for both)."""
@@ -177,6 +189,10 @@ class Runner:
         rec(1)
         self.load()
         rec(2)
+        if self.model == "sage" and not Runner.separate_calls:
+            self.train()
+            rec(3)
+            return
         self.forward()
         rec(3)
         self.loss()
@@ -277,9 +293,7 @@ class Pipelined:
                     if graphs:
                         graphs[k]["train"].replay()
                     else:
-                        r.forward()
-                        r.loss()
-                        r.backward()
+                        r.train()
                     self.free[k].record(self.s_train)
                 freed.put(None)
         finally:
@@ -365,9 +379,7 @@ class PipelinedGroups:
                 with torch.cuda.stream(self.s_train):
                     self.s_train.wait_event(self.ready[g])
                     for r in self.groups[g][:n]:
-                        r.forward()
-                        r.loss()
-                        r.backward()
+                        r.train()
                     self.free[g].record(self.s_train)
                 freed.put(None)
         finally:
@@ -646,6 +658,8 @@ def algorithmic_work(w, model, heads, rows, edges, mixed, row_bytes, ip_bytes, S
     for l in range(L):
         D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
         add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
+        if l == L - 1:      # the fused top layer: forward, weight-gradient and input-gradient products (plain FMAs)
+            add(f"top_fused.l{l}", "flops", 2.0 * nd * (2 * D) * N * 2 + 2.0 * nd * (2 * D + 1) * N)
         add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N)
         if l > 0:
             add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
@@ -763,7 +777,7 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
                 for x in rs[:n]:
                     x.load()
                 for x in rs[:n]:
-                    x.forward(); x.loss(); x.backward()
+                    x.train()
 
         run_groups(0, warmup)
         torch.cuda.synchronize()
@@ -808,6 +822,8 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         r.step(targets[warmup + i], warmup + i, ev[i])
     torch.cuda.synchronize()
     names = ["sample_split", "gather", f"{model}_fwd", "loss_grad", f"{model}_bwd"]
+    if model == "sage" and not Runner.separate_calls:
+        names = ["sample_split", "gather", "sage_step"]
     stage_ms = {nm: sum(ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(n_st)) / n_st for k, nm in enumerate(names)}
 
     # per-kernel device times: the library brackets each of its launches with HIP events on the
@@ -846,7 +862,10 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         if kind == "flops":
             ach = per_launch / sec / 1e12
             peak = BF16_MFMA_PEAK_TFLOPS if dtype == "bf16" else FP32_MFMA_PEAK_TFLOPS
-            out = {"kernel": label, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+            alu = label.startswith("top_fused")      # plain float32 FMAs (vector peak 157.3 TFLOP/s), not the matrix cores
+            if alu:
+                peak = FP32_MFMA_PEAK_TFLOPS
+            out = {"kernel": label, "bound": "alu" if alu else "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
                    "traffic": traffic, "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
         else:
             ach = per_launch / sec / 1e9
@@ -983,6 +1002,7 @@ def extra_configs(a, dev, say):
 
 def main():
     a = parse()
+    Runner.separate_calls = a.separate_calls
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (logical splits share it); --gpus must be 1",
               file=sys.stderr)

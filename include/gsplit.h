@@ -289,7 +289,22 @@ GSPLIT_API int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *params
                     float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
                     void *stream);
 
-/* View of the activations the last gsplit_sage_fwd stored for local_cat[level], level 1 .. L-1:
+/* The model part of one training step in one call: Algorithm 2's forward pass, the mean softmax
+ * cross-entropy of the targets (as gsplit_softmax_xent: the label of row r is d_labels[vertex of
+ * row r], int64, one entry per graph vertex) and the backward pass.  Same inputs and outputs as
+ * gsplit_sage_fwd + gsplit_softmax_xent + gsplit_sage_bwd in this order, within float rounding of
+ * them (sums run in another order); d_row_loss may be NULL.  With float32 storage, at least two
+ * layers, at most 64 classes and a top-layer input width that is a multiple of 4 and at most 384,
+ * the top layer's input assembly, forward product, loss and both backward products run as one
+ * kernel (they are a few microseconds of work behind five kernel boundaries otherwise); other
+ * shapes run the three steps one after the other.  Asynchronous.  A separate gsplit_sage_bwd
+ * afterwards needs a gsplit_sage_fwd of its own (ESTATE). */
+GSPLIT_API int gsplit_sage_step(gsplit_ctx *ctx, const gsplit_sage_params *params, const void *d_feat_local,
+                                const int64_t *d_labels, float *d_logits, float *d_row_loss,
+                                float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
+                                void *stream);
+
+/* View of the activations the last gsplit_sage_fwd (or gsplit_sage_step) stored for local_cat[level], level 1 .. L-1:
  * [rows of that level x dims[level]], float32 or bfloat16 as the forward pass's dtype says, after the
  * ReLU.  The backward pass of layer level - 1 multiplies by [activation > 0] (Algorithm 2's layers in
  * reverse): a parity check reads from this view which way the device decided a ReLU whose argument is

@@ -27,7 +27,7 @@ EXPORTS = [
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
     "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms", "gsplit_sample_split_noalloc",
-    "gsplit_sample_split_multi",
+    "gsplit_sample_split_multi", "gsplit_sage_step",
 ]
 
 
@@ -120,6 +120,8 @@ def load_library():
     L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
                                   C.POINTER(vp), vp]
     L.gsplit_softmax_xent.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.gsplit_sage_step.argtypes = [vp, C.POINTER(_SageParams), vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp),
+                                   C.POINTER(vp), vp]
     L.gsplit_timing_enable.argtypes = [vp, i32]
     L.gsplit_timing_read.argtypes = [vp, C.c_char_p, i64]
     L.gsplit_timing_read.restype = i64
@@ -417,6 +419,25 @@ class Context:
         c = (C.c_void_p * L)(*[t.data_ptr() for t in gbias])
         self._check(self.lib.gsplit_sage_bwd(self.h, C.byref(params.c), grad_logits.data_ptr(), a, b, c,
                                              _stream()))
+
+    def gsplit_sage_step(self, params: SageParams, feat_local: torch.Tensor, labels: torch.Tensor, logits: torch.Tensor,
+                         gw_self, gw_neigh, gbias, row_loss: Optional[torch.Tensor] = None):
+        L = self.L
+        assert feat_local.is_cuda and feat_local.is_contiguous() and logits.is_cuda and logits.is_contiguous()
+        assert logits.dtype == torch.float32
+        assert feat_local.dtype == (torch.bfloat16 if params.dtype == GSPLIT_BF16 else torch.float32)
+        assert labels.is_cuda and labels.dtype == torch.int64 and labels.numel() == self.n_vertices
+        for lst in (gw_self, gw_neigh, gbias):
+            assert len(lst) == L and all(t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() for t in lst)
+        if row_loss is not None:
+            assert row_loss.is_cuda and row_loss.dtype == torch.float32 and row_loss.numel() >= logits.shape[0]
+        a = (C.c_void_p * L)(*[t.data_ptr() for t in gw_self])
+        b = (C.c_void_p * L)(*[t.data_ptr() for t in gw_neigh])
+        c = (C.c_void_p * L)(*[t.data_ptr() for t in gbias])
+        self._fwd_keep = (params, feat_local)
+        self._check(self.lib.gsplit_sage_step(self.h, C.byref(params.c), feat_local.data_ptr(), labels.data_ptr(),
+                                              logits.data_ptr(), row_loss.data_ptr() if row_loss is not None else None,
+                                              a, b, c, _stream()))
 
     def gsplit_gat_fwd(self, params: GatParams, feat_local: torch.Tensor, logits: torch.Tensor):
         assert feat_local.is_cuda and feat_local.is_contiguous() and feat_local.dtype == torch.float32

@@ -275,7 +275,8 @@ extern "C" int gsplit_batch_shuffle(const gsplit_ctx *ctx, int32_t layer, gsplit
 extern "C" int gsplit_sage_activations(const gsplit_ctx *ctx, int32_t level, const void **d_act) {
     if (!ctx || !d_act || level < 1 || level >= ctx->L) return GSPLIT_EINVAL;
     const GsSageBuf &sb = ctx->sage;
-    if (!sb.ready || !sb.fwd_done || sb.fwd_batch != ctx->batch_id) return GSPLIT_ESTATE;
+    // (the activations below the top level are there after a forward pass or a whole step on this batch)
+    if (!sb.ready || sb.fwd_batch != ctx->batch_id) return GSPLIT_ESTATE;
     *d_act = sb.hidden[level];
     return GSPLIT_OK;
 }

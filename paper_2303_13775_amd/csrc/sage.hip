@@ -188,12 +188,13 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6
 struct GradReduce {
     const float *part[GS_MAXL]; float *gws[GS_MAXL]; float *gwn[GS_MAXL]; float *gb[GS_MAXL];
     int D[GS_MAXL]; int N[GS_MAXL]; int nchunk[GS_MAXL]; int rows_min[GS_MAXL];
+    int fixed_chunks[GS_MAXL];      // > 0: the layer's slabs were written by that many workgroups, all of them
 };
 __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLevelMeta *__restrict__ meta, int S) {
     const int l = blockIdx.y;
     const int n1 = meta[l + 1].front_off[S];
     const int kchunk = grad_w_chunk_rows(n1, g.nchunk[l], g.rows_min[l]);
-    const int chunks = (n1 + kchunk - 1) / kchunk;
+    const int chunks = g.fixed_chunks[l] > 0 ? g.fixed_chunks[l] : (n1 + kchunk - 1) / kchunk;
     const int D = g.D[l], N = g.N[l];
     const int64_t words = (int64_t)(2 * D + 1) * N;
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < words;
@@ -347,6 +348,204 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const float *__restrict__ 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The top layer of a training step in one launch.  Its products are tiny (n_targets x 2 D x classes:
+// 49 MFLOP each for 1024 targets, 512 inputs, 47 classes) and as separate launches the chain
+//   input assembly -> forward product -> loss -> weight-gradient product -> input-gradient product
+// is five kernel boundaries around a few microseconds of work.  Here a workgroup takes TOP_R
+// destination rows at a time through all of it: the assembled rows [H_self | mean] and dZ stay in LDS, the
+// stacked weights (at most 2 D x 64 floats) are read from the L2 by every workgroup, the
+// weight-gradient partial of the workgroup goes to its own slab (summed in slab order by
+// k_reduce_grads: deterministic, no atomics).  Plain FMAs: at these sizes the matrix cores would
+// idle on the launch edges anyway.
+// ------------------------------------------------------------------------------------------
+// Destination rows a workgroup takes per round.  The kernel's arithmetic is bound by the FMA rate of
+// the compute units it occupies, so fewer rows per workgroup (more workgroups) shorten it, while
+// every workgroup costs one weight-gradient slab that k_reduce_grads has to read: measured on 1024
+// targets x 512 x 47, kernel + reduction 16 rows 40 + 9 us, 8 rows 25 + 10 us, 4 rows 22 + 14 us.
+constexpr int TOP_ROWS = 8;
+constexpr int TOP_NMAX = 64;       // classes the kernel takes (one lane per class)
+constexpr int TOP_DMAX = 384;      // input width it takes (TOP_R x 2 D floats of LDS)
+
+struct TopArgs {
+    const float *H; int D; int N; int Npad;
+    const int32_t *blk_indptr; const int32_t *edge_row; const int32_t *self_row;
+    const float *W; const float *bias;
+    const int64_t *labels; const int32_t *front_top;
+    float *logits; float *row_loss;
+    float *gin; float *part;
+    const GsLevelMeta *meta_up; int S;
+};
+
+constexpr int TOP_W = 8;           // waves of a workgroup
+constexpr int TOP_T = 64 * TOP_W;
+
+// LDS of the kernel in 4-byte words: rows, per-wave partial logits, dZ, edge rows, per-row scalars
+__host__ __device__ inline size_t top_lds_words(int D, int R) {
+    return (size_t)R * 2 * D + (size_t)TOP_W * R * 64 + (size_t)R * 64 + (size_t)R * 64 + 4 * R;
+}
+
+template <int TOP_R>
+__global__ __launch_bounds__(TOP_T) void k_sage_top_fused(TopArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float s_mem[];
+    const int D = a.D, N = a.N, Npad = a.Npad, D2 = 2 * D, nvec = D >> 2;
+    float *s_x = s_mem;                                         // [TOP_R][2 D]
+    float *s_p = s_x + (size_t)TOP_R * D2;                      // [TOP_W][TOP_R][64]
+    float *s_dz = s_p + TOP_W * TOP_R * 64;                     // [TOP_R][64]
+    int *s_e = reinterpret_cast<int *>(s_dz + TOP_R * 64);      // [TOP_R][64]
+    int *s_e0 = s_e + TOP_R * 64, *s_m = s_e0 + TOP_R, *s_self = s_m + TOP_R;
+    float *s_inv = reinterpret_cast<float *>(s_self + TOP_R);
+    const int n1 = a.meta_up->front_off[a.S];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float4 *H4 = reinterpret_cast<const float4 *>(a.H);
+    const float inv_n = n1 > 0 ? 1.f / (float)n1 : 0.f;
+    float *slab = a.part + (int64_t)blockIdx.x * (D2 + 1) * N;
+    // Every phase is one or two round trips to memory for the whole workgroup: what a thread needs is
+    // fetched with independent loads, never one after the other.
+    int round = 0;
+    for (int r0 = blockIdx.x * TOP_R; round == 0 || r0 < n1; r0 += gridDim.x * TOP_R, ++round) {
+        const int rows = max(0, min(TOP_R, n1 - r0));
+        __syncthreads();                           // the previous round has finished with the LDS
+        // (1) layer input: own lower-layer row | mean over the sampled sources, edges in slot order
+        if ((int)threadIdx.x < rows) {
+            const int row = r0 + threadIdx.x;
+            const int e0 = a.blk_indptr[row], m = min(64, a.blk_indptr[row + 1] - e0);
+            s_e0[threadIdx.x] = e0; s_m[threadIdx.x] = m; s_self[threadIdx.x] = a.self_row[row];
+            s_inv[threadIdx.x] = m > 0 ? 1.f / (float)m : 0.f;
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TOP_R * 64; idx += TOP_T) {
+            const int r = idx >> 6, e = idx & 63;
+            if (r < rows && e < s_m[r]) s_e[idx] = a.edge_row[s_e0[r] + e];
+        }
+        __syncthreads();
+        for (int r = wave; r < rows; r += TOP_W) {
+            const int m = s_m[r];
+            const int64_t self = s_self[r];
+            for (int c = lane; c < nvec; c += 64) {
+                const float4 own = H4[self * nvec + c];
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int e = 0; e < m; e += 8) {
+                    float4 v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = H4[(int64_t)(e + u < m ? s_e[r * 64 + e + u] : (int)self) * nvec + c];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (e + u < m) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+                }
+                if (m > 0) { const float cnt = (float)m; acc.x /= cnt; acc.y /= cnt; acc.z /= cnt; acc.w /= cnt; }
+                float4 *x4 = reinterpret_cast<float4 *>(s_x + (size_t)r * D2);
+                x4[c] = own;
+                x4[nvec + c] = acc;
+            }
+        }
+        __syncthreads();
+        // (2) logits: the contraction is dealt to the waves (2 D / 8 inputs each, lane = class); the
+        // partial sums meet in LDS and are added in wave order
+        {
+            float acc[TOP_R];
+#pragma unroll
+            for (int r = 0; r < TOP_R; ++r) acc[r] = 0.f;
+            const int per = ((D2 / TOP_W + 3) >> 2) << 2;      // a multiple of 4: 16-byte aligned LDS reads below
+            const int nn = lane < Npad ? lane : 0;
+            const float *wcol = a.W + nn;
+            const int kend = min(D2, (wave + 1) * per);
+            for (int k0 = wave * per; k0 < kend; k0 += 32) {
+                float w[32];
+#pragma unroll
+                for (int u = 0; u < 32; ++u) w[u] = wcol[(int64_t)(k0 + u < kend ? k0 + u : k0) * Npad];
+                // (the rows are read from LDS four inputs at a time: one LDS instruction per four FMAs)
+#pragma unroll
+                for (int u = 0; u < 32; u += 4) {
+                    if (k0 + u + 3 < kend) {
+#pragma unroll
+                        for (int r = 0; r < TOP_R; ++r) {
+                            const float4 x = *reinterpret_cast<const float4 *>(s_x + (size_t)r * D2 + k0 + u);
+                            acc[r] += x.x * w[u] + x.y * w[u + 1] + x.z * w[u + 2] + x.w * w[u + 3];
+                        }
+                    }       // (k0, kend and 2 D are multiples of 4: there are no partial groups)
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < TOP_R; ++r) s_p[(wave * TOP_R + r) * 64 + lane] = acc[r];
+        }
+        __syncthreads();
+        for (int r = wave; r < TOP_R; r += TOP_W) {
+            const bool live = r < rows;
+            float zsum = lane < N ? a.bias[lane] : 0.f;
+            if (live) {
+#pragma unroll
+                for (int w = 0; w < TOP_W; ++w) zsum += s_p[(w * TOP_R + r) * 64 + lane];
+            }
+            const float z = (live && lane < N) ? zsum : -3.4e38f;
+            float mx = z;
+            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            const float e = (live && lane < N) ? __expf(z - mx) : 0.f;
+            float sum = e;
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            float dz = 0.f;
+            if (live) {
+                const int row = r0 + r;
+                const int y = (int)a.labels[a.front_top[row]];
+                if (lane < N) {
+                    a.logits[(int64_t)row * N + lane] = z;
+                    dz = (e / sum - (lane == y ? 1.f : 0.f)) * inv_n;
+                }
+                const float zy = __shfl(z, (y >= 0 && y < N) ? y : 0);
+                if (lane == 0 && a.row_loss) a.row_loss[row] = (y >= 0 && y < N) ? (logf(sum) + mx - zy) : 0.f;
+            }
+            s_dz[r * 64 + lane] = dz;
+        }
+        __syncthreads();
+        // (3a) input gradients of the rows: [dH_self | dMean / cnt] = dZ W^T, one input k per thread
+        for (int k = threadIdx.x; k < D2; k += TOP_T) {
+            float w[TOP_NMAX];
+            const float4 *w4 = reinterpret_cast<const float4 *>(a.W + (int64_t)k * Npad);
+#pragma unroll
+            for (int q = 0; q < TOP_NMAX / 4; ++q) {
+                const float4 v = 4 * q < Npad ? w4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+            }
+            for (int r = 0; r < rows; ++r) {
+                float sacc = 0.f;
+#pragma unroll
+                for (int n = 0; n < TOP_NMAX; n += 4) {
+                    const float4 d = *reinterpret_cast<const float4 *>(s_dz + r * 64 + n);
+                    sacc += d.x * w[n] + d.y * w[n + 1] + d.z * w[n + 2] + d.w * w[n + 3];
+                }
+                a.gin[(int64_t)(r0 + r) * D2 + k] = k < D ? sacc : sacc * s_inv[r];
+            }
+        }
+        // (3b) this workgroup's share of X^T dZ and of the column sums of dZ, into its slab
+        if (lane < N) {
+            float dzr[TOP_R];
+#pragma unroll
+            for (int r = 0; r < TOP_R; ++r) dzr[r] = r < rows ? s_dz[r * 64 + lane] : 0.f;
+            // four inputs per thread and step, read from LDS with one instruction per row
+            for (int k = 4 * wave; k < D2; k += 4 * TOP_W) {
+                float4 sacc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int r = 0; r < TOP_R; ++r) {
+                    if (r < rows) {
+                        const float4 x = *reinterpret_cast<const float4 *>(s_x + (size_t)r * D2 + k);
+                        sacc.x += x.x * dzr[r]; sacc.y += x.y * dzr[r]; sacc.z += x.z * dzr[r]; sacc.w += x.w * dzr[r];
+                    }
+                }
+                float *dst = slab + (int64_t)k * N + lane;
+                if (round == 0) { dst[0] = sacc.x; dst[N] = sacc.y; dst[2 * N] = sacc.z; dst[3 * N] = sacc.w; }
+                else { dst[0] += sacc.x; dst[N] += sacc.y; dst[2 * N] += sacc.z; dst[3 * N] += sacc.w; }
+            }
+            if (wave == 0) {                       // column sums of dZ: the bias gradient
+                float sacc = 0.f;
+#pragma unroll
+                for (int r = 0; r < TOP_R; ++r) sacc += dzr[r];
+                float *dst = slab + (int64_t)D2 * N + lane;
+                *dst = round == 0 ? sacc : *dst + sacc;
+            }
+        }
+    }
+}
+
 #include "sage_bf16.h"
 
 int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
@@ -387,8 +586,18 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         const int tiles = (int)(gs_ceil_div(m_rows, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
         const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
         sb.nchunk[l] = (int)chunks;
+        // the fused top-layer kernel writes one slab per workgroup: TOP_R rows each, at most 256 of them
+        int64_t slabs = chunks;
+        if (l == L - 1) {
+            sb.top_chunks = (int)std::min<int64_t>(256, std::max<int64_t>(32, gs_ceil_div(ctx->ub_front[L], TOP_ROWS)));
+            slabs = std::max<int64_t>(slabs, sb.top_chunks);
+        }
         int rc = gs_alloc(ctx, (void **)&sb.gw_part[l],
-                          sizeof(float) * chunks * (2 * p->dims[l] + 1) * p->dims[l + 1], "weight-gradient partials");
+                          sizeof(float) * slabs * (2 * p->dims[l] + 1) * p->dims[l + 1], "weight-gradient partials");
+        if (rc) return rc;
+    }
+    {
+        int rc = gs_alloc(ctx, (void **)&sb.glog, sizeof(float) * ctx->ub_front[L] * p->dims[L], "loss gradient");
         if (rc) return rc;
     }
     int64_t gtmp_words = 1;
@@ -397,6 +606,9 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         int rc = gs_alloc(ctx, (void **)&sb.gtmp, sizeof(float) * gtmp_words, "input gradients");
         if (rc) return rc;
     }
+    // the fused top-layer kernel takes up to 89 KiB of dynamic LDS (a gfx950 workgroup may use all 160 KiB)
+    GS_HIP(ctx, hipFuncSetAttribute((const void *)k_sage_top_fused<TOP_ROWS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(sizeof(float) * top_lds_words(TOP_DMAX, TOP_ROWS))));
     sb.dtype = p->dtype;
     for (int l = 0; l <= L; ++l) sb.dims[l] = p->dims[l];
     sb.ready = true;
@@ -496,16 +708,11 @@ bool launch_assemble(gsplit_ctx *ctx, int l, const float *hin, int D, hipStream_
 
 }  // namespace
 
-extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_feat_local,
-                               float *d_logits, void *stream) {
-    if (!ctx) return GSPLIT_EINVAL;
-    int rc = check_params(ctx, p, "gsplit_sage_fwd");
-    if (rc) return rc;
-    if (!d_feat_local || !d_logits) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_fwd: NULL buffer");
-    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_fwd: no batch");
-    rc = ensure_buffers(ctx, p);
-    if (rc) return rc;
-    hipStream_t st = (hipStream_t)stream;
+namespace {
+
+// forward layers 0 .. l_end - 1 (l_end = L: the whole pass, logits included)
+int sage_forward(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_feat_local, float *d_logits,
+                 hipStream_t st, int l_end) {
     const int L = ctx->L, S = ctx->S;
     GsSageBuf &sb = ctx->sage;
     if (p->dtype == GSPLIT_BF16) {
@@ -523,7 +730,7 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             hipLaunchKernelGGL(k_prep_weights_h, dim3((unsigned)std::min<int64_t>(128, gs_ceil_div(wmax, 256)), L),
                                dim3(256), 0, st, wp);
         }
-        for (int l = 0; l < L; ++l) {
+        for (int l = 0; l < l_end; ++l) {
             const int D = p->dims[l], N = p->dims[l + 1];
             const uint16_t *hin = l == 0 ? (const uint16_t *)d_feat_local : (const uint16_t *)sb.hidden[l];
             const GsLayerBuf &B = ctx->layer[l];
@@ -551,7 +758,7 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
             hipLaunchKernelGGL(k_sage_linear_fwd_h, grid, dim3(GNT), 0, st, x, wt, epi, mu, S);
         }
         GS_HIP(ctx, hipGetLastError());
-        sb.fwd_done = true;
+        sb.fwd_done = l_end == L;
         sb.fwd_batch = ctx->batch_id;
         return GSPLIT_OK;
     }
@@ -566,7 +773,7 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         }
         stack_words = wmax;
     }
-    for (int l = 0; l < L; ++l) {
+    for (int l = 0; l < l_end; ++l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const float *hin = l == 0 ? (const float *)d_feat_local : (const float *)sb.hidden[l];
         float *hout = l == L - 1 ? d_logits : (float *)sb.hidden[l + 1];
@@ -587,30 +794,34 @@ extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         launch_fwd(ctx, st, ctx->ub_front[l + 1], va, a, b, epi, mu);
     }
     GS_HIP(ctx, hipGetLastError());
-    sb.fwd_done = true;
+    sb.fwd_done = l_end == L;
     sb.fwd_batch = ctx->batch_id;
     return GSPLIT_OK;
 }
 
-extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_grad_logits,
-                               float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
-                               void *stream) {
+}  // namespace
+
+extern "C" int gsplit_sage_fwd(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_feat_local,
+                               float *d_logits, void *stream) {
     if (!ctx) return GSPLIT_EINVAL;
-    int rc = check_params(ctx, p, "gsplit_sage_bwd");
+    int rc = check_params(ctx, p, "gsplit_sage_fwd");
     if (rc) return rc;
-    if (!d_grad_logits || !d_gw_self || !d_gw_neigh || !d_gbias)
-        return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_bwd: NULL buffer");
+    if (!d_feat_local || !d_logits) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_fwd: NULL buffer");
+    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_fwd: no batch");
+    rc = ensure_buffers(ctx, p);
+    if (rc) return rc;
+    return sage_forward(ctx, p, d_feat_local, d_logits, (hipStream_t)stream, ctx->L);
+}
+
+
+namespace {
+
+// backward pass, top layer down.  top_chunks > 0: the fused top-layer kernel has already left the top
+// layer's input gradients in gtmp and its weight-gradient partials in that many slabs.
+int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_grad_logits, float *const *d_gw_self,
+                  float *const *d_gw_neigh, float *const *d_gbias, hipStream_t st, int top_chunks) {
     GsSageBuf &sb = ctx->sage;
-    if (!sb.ready || !sb.fwd_done || sb.fwd_batch != ctx->batch_id)
-        return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: needs gsplit_sage_fwd on the current batch first");
-    for (int l = 0; l <= ctx->L; ++l)
-        if (sb.dims[l] != p->dims[l] || sb.dtype != p->dtype)
-            return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: parameters differ from the forward pass");
-    hipStream_t st = (hipStream_t)stream;
     const int L = ctx->L, S = ctx->S;
-    for (int l = 0; l < L; ++l)
-        if (!d_gw_self[l] || !d_gw_neigh[l] || !d_gbias[l])
-            return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_bwd: NULL gradient pointer");
     for (int l = L - 1; l >= 0; --l) {
         const int D = p->dims[l], N = p->dims[l + 1];
         const GsLayerBuf &B = ctx->layer[l];
@@ -628,7 +839,8 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         EpiGradW ew{sb.gw_part[l], 2 * D + 1, N, h16 ? 2 * D + 1 : 2 * D};
         const bool vin = D % 2 == 0;
         const bool vdz = N % 4 == 0 && aligned16(dH);
-        {
+        const bool done_above = top_chunks > 0 && l == L - 1;
+        if (!done_above) {
             GsTimeScope ts(ctx, "grad_w", l, st);
             if (h16) {
                 MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
@@ -650,7 +862,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         if (l > 0) {
             const GsLevelMeta *ml = ctx->d_meta + l;
             EpiGradIn ei{sb.gtmp, sb.inv_cnt[l], D, 0};
-            {
+            if (!done_above) {
                 GsTimeScope ts(ctx, "grad_in", l, st);
                 if (h16) {
                     dim3 grid(row_block_grid<TileMid>(ctx, ub, 2 * D));
@@ -704,6 +916,7 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
         for (int l = 0; l < L; ++l) {
             gr.part[l] = sb.gw_part[l]; gr.gws[l] = d_gw_self[l]; gr.gwn[l] = d_gw_neigh[l]; gr.gb[l] = d_gbias[l];
             gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = GRAD_W_ROWS_MIN;
+            gr.fixed_chunks[l] = l == L - 1 ? top_chunks : 0;
             wmax = std::max<int64_t>(wmax, (int64_t)(2 * p->dims[l] + 1) * p->dims[l + 1]);
         }
         GsTimeScope ts(ctx, "reduce_grads", -1, st);
@@ -712,6 +925,90 @@ extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, con
     }
     GS_HIP(ctx, hipGetLastError());
     return GSPLIT_OK;
+}
+
+int check_grad_outputs(gsplit_ctx *ctx, float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
+                       const char *who) {
+    if (!d_gw_self || !d_gw_neigh || !d_gbias) return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": NULL buffer");
+    for (int l = 0; l < ctx->L; ++l)
+        if (!d_gw_self[l] || !d_gw_neigh[l] || !d_gbias[l])
+            return gs_fail(ctx, GSPLIT_EINVAL, std::string(who) + ": NULL gradient pointer");
+    return GSPLIT_OK;
+}
+
+// can the top layer of this model run as k_sage_top_fused?
+bool top_fusable(const gsplit_ctx *ctx, const gsplit_sage_params *p, const void *top_input) {
+    const int L = ctx->L;
+    if (p->dtype != GSPLIT_F32 || L < 2) return false;
+    const int D = p->dims[L - 1], N = p->dims[L];
+    return N <= TOP_NMAX && D % 4 == 0 && D <= TOP_DMAX && aligned16(top_input);
+}
+
+}  // namespace
+
+extern "C" int gsplit_sage_bwd(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_grad_logits,
+                               float *const *d_gw_self, float *const *d_gw_neigh, float *const *d_gbias,
+                               void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    int rc = check_params(ctx, p, "gsplit_sage_bwd");
+    if (rc) return rc;
+    if (!d_grad_logits) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_bwd: NULL buffer");
+    rc = check_grad_outputs(ctx, d_gw_self, d_gw_neigh, d_gbias, "gsplit_sage_bwd");
+    if (rc) return rc;
+    GsSageBuf &sb = ctx->sage;
+    if (!sb.ready || !sb.fwd_done || sb.fwd_batch != ctx->batch_id)
+        return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: needs gsplit_sage_fwd on the current batch first");
+    for (int l = 0; l <= ctx->L; ++l)
+        if (sb.dims[l] != p->dims[l] || sb.dtype != p->dtype)
+            return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_bwd: parameters differ from the forward pass");
+    return sage_backward(ctx, p, d_grad_logits, d_gw_self, d_gw_neigh, d_gbias, (hipStream_t)stream, 0);
+}
+
+extern "C" int gsplit_sage_step(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_feat_local,
+                                const int64_t *d_labels, float *d_logits, float *d_row_loss, float *const *d_gw_self,
+                                float *const *d_gw_neigh, float *const *d_gbias, void *stream) {
+    if (!ctx) return GSPLIT_EINVAL;
+    int rc = check_params(ctx, p, "gsplit_sage_step");
+    if (rc) return rc;
+    if (!d_feat_local || !d_labels || !d_logits) return gs_fail(ctx, GSPLIT_EINVAL, "gsplit_sage_step: NULL buffer");
+    rc = check_grad_outputs(ctx, d_gw_self, d_gw_neigh, d_gbias, "gsplit_sage_step");
+    if (rc) return rc;
+    if (ctx->batch_id == 0) return gs_fail(ctx, GSPLIT_ESTATE, "gsplit_sage_step: no batch");
+    rc = ensure_buffers(ctx, p);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    GsSageBuf &sb = ctx->sage;
+    const int L = ctx->L, S = ctx->S;
+    const int N = p->dims[L];
+    if (!top_fusable(ctx, p, sb.hidden[L - 1])) {
+        // the three steps one after the other, the loss gradient in the context's own buffer
+        rc = sage_forward(ctx, p, d_feat_local, d_logits, st, L);
+        if (rc) return rc;
+        {
+            GsTimeScope ts(ctx, "softmax_xent", -1, st);
+            hipLaunchKernelGGL(k_softmax_xent, dim3(grid_1d(ctx, ctx->ub_front[L] * 64)), dim3(256), 0, st, d_logits, N,
+                               d_labels, ctx->front[L], ctx->d_meta + L, S, sb.glog, d_row_loss);
+        }
+        rc = sage_backward(ctx, p, sb.glog, d_gw_self, d_gw_neigh, d_gbias, st, 0);
+        sb.fwd_done = false;
+        return rc;
+    }
+    rc = sage_forward(ctx, p, d_feat_local, d_logits, st, L - 1);
+    if (rc) return rc;
+    const int l = L - 1, D = p->dims[l];
+    const GsLayerBuf &B = ctx->layer[l];
+    const int chunks = sb.top_chunks;
+    {
+        TopArgs ta{(const float *)sb.hidden[l], D, N, (N + 3) & ~3, B.blk_indptr, B.edge_row, B.self_row, sb.wstack32[l],
+                   (const float *)p->d_bias[l], d_labels, ctx->front[L], d_logits, d_row_loss, sb.gtmp, sb.gw_part[l],
+                   ctx->d_meta + L, S};
+        GsTimeScope ts(ctx, "top_fused", l, st);
+        hipLaunchKernelGGL(k_sage_top_fused<TOP_ROWS>, dim3(chunks), dim3(TOP_T), sizeof(float) * top_lds_words(D, TOP_ROWS),
+                           st, ta);
+    }
+    rc = sage_backward(ctx, p, nullptr, d_gw_self, d_gw_neigh, d_gbias, st, chunks);
+    sb.fwd_done = false;        // the step is complete: a separate backward call needs a forward call of its own
+    return rc;
 }
 
 extern "C" int gsplit_softmax_xent(gsplit_ctx *ctx, const float *d_logits, int32_t n_classes,

@@ -225,7 +225,7 @@ def test_gather_is_exact(dim, dtype):
     ctx.close()
 
 
-def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None, bf16=False):
+def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None, bf16=False, step=False):
     """One iteration on the device and on the oracle.  The device's backward pass is fed the
     oracle's loss gradient; the oracle's backward pass is conditioned on the device's ReLU
     decisions inside the rounding band (sage_check.conditioned_backward)."""
@@ -241,18 +241,26 @@ def _run_fwd_bwd(w, dev, seed, it, n_splits=None, pmap=None, bf16=False):
     params = SageParams(w.dims, [t.to(dev) for t in w.w_self], [t.to(dev) for t in w.w_neigh],
                         [t.to(dev) for t in w.bias], dtype=GSPLIT_BF16 if bf16 else GSPLIT_F32)
     logits = torch.empty((tg.numel(), w.dims[-1]), device=dev)
-    ctx.gsplit_sage_fwd(params, x0, logits)
+    gws = [torch.full_like(t, 7.0, device=dev) for t in w.w_self]      # must be overwritten
+    gwn = [torch.full_like(t, 7.0, device=dev) for t in w.w_neigh]
+    gb = [torch.full_like(t, 7.0, device=dev) for t in w.bias]
+    row_loss = torch.full((tg.numel(),), 7.0, device=dev)
+    if step:        # forward, loss and backward as one call (the device forms the loss gradient itself)
+        ctx.gsplit_sage_step(params, x0, w.labels.to(dev), logits, gws, gwn, gb, row_loss)
+    else:
+        ctx.gsplit_sage_fwd(params, x0, logits)
     ob = _oracle_batch(w, tg, seed, it, n_splits=S, pmap=pm.cpu().numpy())
     op = R.SageParams([t.numpy() for t in w.w_self], [t.numpy() for t in w.w_neigh],
                       [t.numpy() for t in w.bias])
     rows = R.gather_rows(table.float().numpy(), ob.local_cat(0))
     of = R.sp_forward(ob, rows, op, store_bf16=bf16)
     lab = w.labels.numpy()[tg.numpy()[ob.target_perm]]
-    _, g = R.softmax_xent(of.logits, lab)
-    gws = [torch.full_like(t, 7.0, device=dev) for t in w.w_self]      # must be overwritten
-    gwn = [torch.full_like(t, 7.0, device=dev) for t in w.w_neigh]
-    gb = [torch.full_like(t, 7.0, device=dev) for t in w.bias]
-    ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
+    loss, g = R.softmax_xent(of.logits, lab)
+    if step:
+        got_loss = float(row_loss.double().mean()) if tg.numel() else 0.0
+        assert abs(got_loss - loss) <= (2e-2 if bf16 else 1e-5) * max(1.0, abs(loss)), ("loss", got_loss, loss)
+    else:
+        ctx.gsplit_sage_bwd(params, torch.from_numpy(g.astype(np.float32)).to(dev), gws, gwn, gb)
     torch.cuda.synchronize()
     act = SC.device_activations(ctx, w.dims, bf16)
     obw, report = SC.conditioned_backward(ob, of, op, g, act, SC.TAU_BF16_ROUNDED if bf16 else SC.TAU_F32,
@@ -324,6 +332,43 @@ def test_sage_forward_backward_within_tolerance(name):
     dev = _dev()
     w = SAGE_CASES[name]()
     check_sage(_run_fwd_bwd(w, dev, seed=77, it=2), w.n_layers, tag=name)
+
+
+# gsplit_sage_step: the top layer as one fused kernel (tiny: 16 classes; ragged-dims: 47 classes, 72 inputs; wide and
+# the bf16 run: shapes it does not take, which run the three steps one after the other); several rounds of
+# rows per workgroup ("many-targets": 6000 targets over 256 workgroups of 8 rows)
+STEP_CASES = dict(SAGE_CASES)
+STEP_CASES["many-targets"] = lambda: workloads.custom(20000, 400000, dims=[16, 32, 40], fanouts=[3, 2], batch=6000,
+                                                      n_splits=4, name="many-targets")
+STEP_CASES["top-width-384"] = lambda: workloads.custom(4000, 80000, dims=[24, 384, 64], fanouts=[4, 3], batch=333,
+                                                       n_splits=2, name="top-384")
+
+
+@pytest.mark.parametrize("name", list(STEP_CASES))
+def test_sage_step_within_tolerance(name):
+    dev = _dev()
+    w = STEP_CASES[name]()
+    check_sage(_run_fwd_bwd(w, dev, seed=78, it=3, step=True), w.n_layers, tag=name + " step")
+    if name == "tiny":
+        check_sage(_run_fwd_bwd(w, dev, seed=78, it=3, step=True, bf16=True), w.n_layers, bf16=True, tag=name + " step")
+
+
+def test_sage_step_then_backward_needs_a_forward():
+    from paper_2303_13775_amd import Context, SageParams, GsplitError
+    dev = _dev()
+    w = workloads.tiny()
+    ctx = _ctx(w, dev)
+    ctx.gsplit_sample_split(w.targets(0).to(dev), 1, 0)
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), device=dev)
+    ctx.gsplit_gather_features(w.feat.to(dev), x0)
+    params = SageParams(w.dims, [t.to(dev) for t in w.w_self], [t.to(dev) for t in w.w_neigh], [t.to(dev) for t in w.bias])
+    logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+    grads = [[torch.empty_like(t, device=dev) for t in lst] for lst in (w.w_self, w.w_neigh, w.bias)]
+    ctx.gsplit_sage_step(params, x0, w.labels.to(dev), logits, *grads)
+    with pytest.raises(GsplitError) as e:
+        ctx.gsplit_sage_bwd(params, logits, *grads)
+    assert e.value.code == -5
+    ctx.close()
 
 
 BF16_CASES = {
