@@ -708,7 +708,7 @@ def profile_traffic(workload, dtype, model, label):
 
 
 def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup, pipeline, stage_iters,
-            cache=None, use_graph=False):
+            cache=None, use_graph=False, multi=None):
     """All timings of one configuration: K steps pipelined (if asked) and K steps serial between two
     device synchronisations, K steps with one synchronisation per step (mean / p50 / p95), per-stage
     and per-kernel device times, and the rooflines that follow from them."""
@@ -760,7 +760,7 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
             per_step.append((time.perf_counter() - t1) * 1e3)
     # (2b) one stream, sampling in groups: the next K mini-batches through one set of launches, then
     # the K training steps one after the other
-    K = max(1, min(getattr(a, "multi", 1), steps))
+    K = max(1, min(a.multi if multi is None else multi, steps))
     serial_multi = None
     if K > 1 and not use_graph:
         from paper_2303_13775_amd import gsplit_sample_split_multi
@@ -948,12 +948,14 @@ def extra_configs(a, dev, say):
     import workloads
     out = {}
 
-    def run(tag, w, workload, dtype, steps=20, warmup=3):
+    def run(tag, w, workload, dtype, steps=20, warmup=3, multi=1):
+        # (a context of the sweep or the skewed configuration holds tens of GB of buffers sized from the
+        # no-dedup bounds: those run with one context, i.e. without the grouped-sampling figure)
         t0 = time.time()
         try:
             torch.cuda.empty_cache()
             m = measure(a, w, dev, workload=workload, dtype=dtype, steps=steps, warmup=warmup, pipeline=False,
-                        stage_iters=min(steps, 10))
+                        stage_iters=min(steps, 10), multi=multi)
             m.pop("_runner").ctx.close()
             m["config"] = w.describe()
             m["dtype"] = dtype
@@ -968,10 +970,10 @@ def extra_configs(a, dev, say):
 
     try:
         w = workloads.large(device=dev, n_splits=4, feat_dtype=torch.float32, progress=say)
-        run("large_f32", w, "large", "f32")
+        run("large_f32", w, "large", "f32", multi=a.multi)
         w.feat = w.feat.to(torch.bfloat16)
         torch.cuda.empty_cache()
-        run("large_bf16", w, "large", "bf16")
+        run("large_bf16", w, "large", "bf16", multi=a.multi)
         rank = workloads.bfs_rank(w.indptr, w.indices)
         sweep = {}
         for S in (1, 2, 4, 8):
