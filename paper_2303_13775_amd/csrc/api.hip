@@ -129,6 +129,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
             A((void **)&B.rev_ptr, sizeof(int32_t) * ctx->ub_front[l], "rev_ptr");
             A((void **)&B.rev_fill, sizeof(int32_t) * ctx->ub_front[l], "rev_fill");
             A((void **)&B.rev_list, sizeof(int32_t) * nd * (1 + f), "rev_list");
+            A((void **)&B.rev_long, sizeof(int32_t) * (nd * (1 + f) / GS_REV_LONG + 1), "rev_long");
         }
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");

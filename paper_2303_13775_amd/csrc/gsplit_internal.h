@@ -9,6 +9,9 @@
 
 #include "gsplit.h"
 
+// a row of the reverse index with more entries than one wave holds in registers (four per lane) is a
+// "long" row: the backward pass hands those to whole workgroups
+#define GS_REV_LONG 256
 #define GS_MAXS GSPLIT_MAX_SPLITS
 #define GS_MAXL GSPLIT_MAX_LAYERS
 
@@ -29,7 +32,7 @@ struct GsLevelMeta {
     int32_t nnz;
     int32_t error;      // set non-zero by a kernel that hit an impossible state (probe overflow)
     int32_t rev_cursor; // allocation cursor of the reverse (scatter) index
-    int32_t pad[1];
+    int32_t n_long;     // rows of the level with more than GS_REV_LONG entries in the reverse index
 };
 
 // Open-addressing table in HBM: entry = key << 32 | smallest position seen; row = final row.
@@ -56,6 +59,7 @@ struct GsLayerBuf {            // sampling layer l
     int32_t *rev_fill = nullptr;   // [ub_front[l]]
     int32_t *rev_list = nullptr;   // [ub_dst * (1 + fan)]
     int32_t *rev_eid = nullptr;    // [ub_dst * (1 + fan)]  edge number of an edge entry, -1 for a self entry (gat_index only)
+    int32_t *rev_long = nullptr;   // [ub_dst * (1 + fan) / GS_REV_LONG + 1]  rows with more than GS_REV_LONG entries
 };
 
 struct GsSageBuf {             // activations kept between forward and backward

@@ -241,62 +241,240 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6
 // Reverse shuffle of the backward pass as a pull: row u of local_cat[l] sums the gradient rows of
 // every destination it fed (its own self term and one mean term per sampled edge), listed by the
 // scatter side of the shuffle index.  The ReLU of the layer below is applied on the way out, so
-// the result is that layer's dZ.  One lane group per row, 4 floats per lane; no atomics, and rows
-// that fed nothing get zeros.
+// the result is that layer's dZ.  No atomics; rows that fed nothing get zeros.
+//
+// The entries of a row sit in its segment in the order an atomic cursor handed them out, which
+// differs from run to run; a float sum in that order would too.  So the sum runs in ascending order
+// of the entry codes (2 * destination [+ 1]), whatever the segment's order: one wave per row, one
+// entry per lane, sorted across the wave with a bitonic network of shuffles (21 exchange steps, no
+// memory traffic); then LPR lanes cover a gradient row 4 floats each, the 64 / LPR lane groups of
+// the wave take every (64 / LPR)-th entry of the sorted list, and their partial sums are added in
+// a fixed tree.  A row with up to 256 entries keeps four per lane (the same network over registers and
+// lanes).  Gradients are bit-reproducible.
+// A row with more than 256 entries (a hub: tens of thousands of destinations can sample the same
+// vertex) is left to the workgroups behind the launch's own (blockIdx.x >= n_main), which walk the
+// list of such rows that the sampler made: codes sorted in LDS (bitonic, up to PULL_LONG_CAP at a
+// time), the four waves sum a quarter of the sorted list each, partial sums added in wave order.
+// (Only a row with more than PULL_LONG_CAP entries is summed segment by segment in list order,
+// i.e. not reproducibly in the last bits.)
+constexpr int PULL_LONG_CAP = 4096;
+constexpr int PULL_LONG_BLOCKS = 1024;
+
+// Bitonic sort across a wave, ascending, of the first p2 lanes' values (p2 a power of two; the lanes
+// behind hold INT_MAX padding and stay where they are): log2(p2) * (log2(p2) + 1) / 2 exchange steps, so
+// the common rows with two or three entries cost one or three shuffles, not the 21 of a full wave.
+__device__ __forceinline__ int wave_sort_ascending(int v, int p2) {
+    const int lane = threadIdx.x & 63;
+    for (int k = 2; k <= p2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const int o = __shfl_xor(v, j);
+            v = (((lane & j) == 0) == ((lane & k) == 0)) ? min(v, o) : max(v, o);
+        }
+    }
+    return v;
+}
+
+// The same for 256 values, four per lane: element r * 64 + lane lives in v[r].  Exchanges at a distance
+// of 64 or 128 elements are between registers of one lane, the others between lanes.
+__device__ __forceinline__ void wave_sort4_ascending(int (&v)[4]) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 2; k <= 256; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (j >= 64) {
+                const int jr = j >> 6;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if ((r & jr) == 0) {
+                        const bool asc = ((r * 64 + lane) & k) == 0;
+                        const int a = v[r], b = v[r | jr];
+                        if ((a > b) == asc) { v[r] = b; v[r | jr] = a; }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int o = __shfl_xor(v[r], j);
+                    const bool asc = ((r * 64 + lane) & k) == 0;
+                    v[r] = (((lane & j) == 0) == asc) ? min(v[r], o) : max(v[r], o);
+                }
+            }
+        }
+    }
+}
+
+template <bool HACT_H>
+__device__ __forceinline__ float4 load_act4(const void *__restrict__ hact, int64_t idx) {
+    if (HACT_H) {
+        const uint2 raw = reinterpret_cast<const uint2 *>(hact)[idx];
+        return make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
+    }
+    return reinterpret_cast<const float4 *>(hact)[idx];
+}
+
+template <bool OUT_H>
+__device__ __forceinline__ void store_masked4(void *__restrict__ gout, int64_t idx, float4 acc, float4 h) {
+    acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
+    acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
+    // bf16 storage: dZ is kept as the bf16 value that both backward products consume
+    if (OUT_H)
+        reinterpret_cast<uint2 *>(gout)[idx] = make_uint2((uint32_t)f2bf(acc.x) | ((uint32_t)f2bf(acc.y) << 16),
+                                                          (uint32_t)f2bf(acc.z) | ((uint32_t)f2bf(acc.w) << 16));
+    else
+        reinterpret_cast<float4 *>(gout)[idx] = acc;
+}
+
+__device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+
 template <int LPR, bool HACT_H, bool OUT_H = false>
 __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict__ gin, int D,
                                                          const int32_t *__restrict__ rev_ptr,
                                                          const int32_t *__restrict__ rev_cnt,
                                                          const int32_t *__restrict__ rev_list,
+                                                         const int32_t *__restrict__ rev_long,
                                                          const void *__restrict__ hact,
                                                          const GsLevelMeta *__restrict__ meta_lo, int S,
-                                                         void *__restrict__ gout) {
+                                                         void *__restrict__ gout, int n_main) {
     const int n_lo = meta_lo->front_off[S];
     const int nvec = D >> 2;
-    const int c0 = threadIdx.x % LPR;
-    const int groups = (gridDim.x * blockDim.x) / LPR;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float4 *G4 = reinterpret_cast<const float4 *>(gin);
-    const float4 *A4 = reinterpret_cast<const float4 *>(hact);
-    float4 *O4 = reinterpret_cast<float4 *>(gout);
-    for (int u = (blockIdx.x * blockDim.x + threadIdx.x) / LPR; u < n_lo; u += groups) {
-        const int e0 = rev_ptr[u], e1 = e0 + rev_cnt[u];
-        for (int c = c0; c < nvec; c += LPR) {
+    if ((int)blockIdx.x >= n_main) {
+        // ---- long rows: one workgroup per row
+        __shared__ int s_code[PULL_LONG_CAP];
+        __shared__ float4 s_part[4][64];
+        const int n_long = meta_lo->n_long;
+        for (int i = (int)blockIdx.x - n_main; i < n_long; i += (int)gridDim.x - n_main) {
+            const int u = rev_long[i];
+            const int n = rev_cnt[u], e0 = rev_ptr[u];
+            for (int cb = 0; cb < nvec; cb += 64) {
+                const int c = cb + lane;
+                const bool cv = c < nvec;
+                const float4 h = cv ? load_act4<HACT_H>(hact, (int64_t)u * nvec + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+                float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int seg = 0; seg < n; seg += PULL_LONG_CAP) {
+                    const int m = min(PULL_LONG_CAP, n - seg);
+                    int p2 = 64;
+                    while (p2 < m) p2 <<= 1;
+                    __syncthreads();
+                    for (int t = threadIdx.x; t < p2; t += 256) s_code[t] = t < m ? rev_list[e0 + seg + t] : 0x7FFFFFFF;
+                    __syncthreads();
+                    for (int k = 2; k <= p2; k <<= 1) {
+                        for (int j = k >> 1; j > 0; j >>= 1) {
+                            for (int t = threadIdx.x; t < (p2 >> 1); t += 256) {
+                                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                                const int x = s_code[lo], y = s_code[hi];
+                                const bool asc = (lo & k) == 0;
+                                if ((x > y) == asc) { s_code[lo] = y; s_code[hi] = x; }
+                            }
+                            __syncthreads();
+                        }
+                    }
+                    // the four waves sum a quarter of the sorted codes each, eight gradient rows in flight
+                    const int q = (m + 3) >> 2;
+                    const int jb = wave * q, je = min(m, jb + q);
+                    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int j = jb; j < je; j += 8) {
+                        float4 v[8];
+#pragma unroll
+                        for (int x = 0; x < 8; ++x) {
+                            const int code = s_code[min(j + x, je - 1)];
+                            v[x] = cv ? G4[(int64_t)(code >> 1) * 2 * nvec + (code & 1) * nvec + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+#pragma unroll
+                        for (int x = 0; x < 8; ++x)
+                            if (j + x < je) add4(acc, v[x]);
+                    }
+                    s_part[wave][lane] = acc;
+                    __syncthreads();
+                    if (wave == 0) {
+                        float4 t = s_part[0][lane];
+                        add4(t, s_part[1][lane]); add4(t, s_part[2][lane]); add4(t, s_part[3][lane]);
+                        add4(total, t);
+                    }
+                }
+                if (wave == 0 && cv) store_masked4<OUT_H>(gout, (int64_t)u * nvec + c, total, h);
+            }
+        }
+        return;
+    }
+    constexpr int G = 64 / LPR;                 // lane groups of a wave: entries summed side by side
+    const int sub = lane / LPR, c0 = lane % LPR;
+    const int waves = (n_main * (int)blockDim.x) >> 6;
+    const int n_c = (nvec + LPR - 1) / LPR;      // column rounds, the same for every lane
+    // A row is a chain of three dependent accesses (segment -> codes -> gradient rows), and with one
+    // row per wave at a time the kernel runs at the rate of that chain, not of the memory.  So a wave
+    // looks two rows ahead: while it sums row u it already holds the codes of its next row and the
+    // segment of the one after, and only the gradient rows themselves are waited for.
+    const int u_first = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    int n_a = 0, e_a = 0, n_b = 0, e_b = 0, code_a = 0x7FFFFFFF;
+    if (u_first < n_lo) { n_a = rev_cnt[u_first]; e_a = rev_ptr[u_first]; }
+    if (u_first + waves < n_lo) { n_b = rev_cnt[u_first + waves]; e_b = rev_ptr[u_first + waves]; }
+    if (lane < min(n_a, 64)) code_a = rev_list[e_a + lane];
+    for (int u = u_first; u < n_lo; u += waves) {
+        int n_c2 = 0, e_c2 = 0, code_b = 0x7FFFFFFF;
+        if (u + 2 * waves < n_lo) { n_c2 = rev_cnt[u + 2 * waves]; e_c2 = rev_ptr[u + 2 * waves]; }
+        if (u + waves < n_lo && lane < min(n_b, 64)) code_b = rev_list[e_b + lane];
+        const int n = n_a, e0 = e_a;
+        int v4[4];
+        v4[0] = code_a;
+        n_a = n_b; e_a = e_b; n_b = n_c2; e_b = e_c2; code_a = code_b;
+        if (n > GS_REV_LONG) continue;          // a workgroup behind the launch's own takes it
+        // the row's codes in registers, sorted: entry j of the sorted list is v[j / 64] of lane j % 64
+        const int n_reg = (n + 63) >> 6;          // registers in use (uniform)
+        if (n <= 64) {
+            if (n > 1) {
+                int p2 = 2;
+                while (p2 < n) p2 <<= 1;
+                v4[0] = wave_sort_ascending(v4[0], p2);
+            }
+        } else {
+#pragma unroll
+            for (int r = 1; r < 4; ++r) v4[r] = r * 64 + lane < n ? rev_list[e0 + r * 64 + lane] : 0x7FFFFFFF;
+            wave_sort4_ascending(v4);
+        }
+        for (int ci = 0; ci < n_c; ++ci) {
+            const int c = c0 + ci * LPR;
+            const bool cv = c < nvec;
             // the activation that gates the result does not depend on the sum: fetched first, it
-            // travels while the row's entries and their gradient rows are fetched
-            float4 h;
-            if (HACT_H) {
-                const uint2 raw = reinterpret_cast<const uint2 *>(hact)[(int64_t)u * nvec + c];
-                h = make_float4(bf2f(raw.x & 0xFFFFu), bf2f(raw.x >> 16), bf2f(raw.y & 0xFFFFu), bf2f(raw.y >> 16));
-            } else {
-                h = A4[(int64_t)u * nvec + c];
-            }
+            // travels while the gradient rows are fetched
+            const float4 h = cv ? load_act4<HACT_H>(hact, (int64_t)u * nvec + c) : make_float4(0.f, 0.f, 0.f, 0.f);
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            int e = e0;
-            for (; e + 2 <= e1; e += 2) {
-                const int k0 = rev_list[e], k1 = rev_list[e + 1];
-                const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
-                const float4 b = G4[(int64_t)(k1 >> 1) * 2 * nvec + (k1 & 1) * nvec + c];
-                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
-                acc.x += b.x; acc.y += b.y; acc.z += b.z; acc.w += b.w;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (r >= n_reg) break;
+                const int code = v4[r];
+                const int m = min(64, n - r * 64);
+                for (int j0 = 0; j0 < m; j0 += 4 * G) {
+                    float4 v[4];
+                    bool have[4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const int j = j0 + x * G + sub;
+                        const int k = __shfl(code, j < 64 ? j : 63);
+                        have[x] = j < m && cv;
+                        v[x] = have[x] ? G4[(int64_t)(k >> 1) * 2 * nvec + (k & 1) * nvec + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (have[x]) add4(acc, v[x]);
+                }
             }
-            if (e < e1) {
-                const int k0 = rev_list[e];
-                const float4 a = G4[(int64_t)(k0 >> 1) * 2 * nvec + (k0 & 1) * nvec + c];
-                acc.x += a.x; acc.y += a.y; acc.z += a.z; acc.w += a.w;
+            // the lane groups' partial sums, added in a fixed tree
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) {
+                acc.x += __shfl_xor(acc.x, o); acc.y += __shfl_xor(acc.y, o);
+                acc.z += __shfl_xor(acc.z, o); acc.w += __shfl_xor(acc.w, o);
             }
-            acc.x = h.x > 0.f ? acc.x : 0.f; acc.y = h.y > 0.f ? acc.y : 0.f;
-            acc.z = h.z > 0.f ? acc.z : 0.f; acc.w = h.w > 0.f ? acc.w : 0.f;
-            // bf16 storage: dZ is kept as the bf16 value that both backward products consume
-            if (OUT_H)
-                reinterpret_cast<uint2 *>(gout)[(int64_t)u * nvec + c] =
-                    make_uint2((uint32_t)f2bf(acc.x) | ((uint32_t)f2bf(acc.y) << 16),
-                               (uint32_t)f2bf(acc.z) | ((uint32_t)f2bf(acc.w) << 16));
-            else
-                O4[(int64_t)u * nvec + c] = acc;
+            if (sub == 0 && cv) store_masked4<OUT_H>(gout, (int64_t)u * nvec + c, acc, h);
         }
     }
 }
 
+// widths that are not a multiple of 4: one wave per row, one float per lane; entries in ascending
+// code order when the row has at most 64 of them (longer rows of such a model: in list order, i.e.
+// not reproducibly in the last bits)
 __global__ __launch_bounds__(256) void k_pull_input_grad_any(const float *__restrict__ gin, int D,
                                                              const int32_t *__restrict__ rev_ptr,
                                                              const int32_t *__restrict__ rev_cnt,
@@ -308,14 +486,29 @@ __global__ __launch_bounds__(256) void k_pull_input_grad_any(const float *__rest
     const int lane = threadIdx.x & 63;
     const int waves = (gridDim.x * blockDim.x) >> 6;
     for (int u = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; u < n_lo; u += waves) {
-        const int e0 = rev_ptr[u], e1 = e0 + rev_cnt[u];
-        for (int c = lane; c < D; c += 64) {
+        const int e0 = rev_ptr[u], n = rev_cnt[u];
+        int code = lane < n ? rev_list[e0 + lane] : 0x7FFFFFFF;
+        if (n > 1 && n <= 64) {
+            int p2 = 2;
+            while (p2 < n) p2 <<= 1;
+            code = wave_sort_ascending(code, p2);
+        }
+        const int n_c = (D + 63) >> 6;
+        for (int ci = 0; ci < n_c; ++ci) {
+            const int c = lane + 64 * ci;
             float acc = 0.f;
-            for (int e = e0; e < e1; ++e) {
-                const int k = rev_list[e];
-                acc += gin[(int64_t)(k >> 1) * 2 * D + (k & 1) * D + c];
+            if (n <= 64) {
+                for (int j = 0; j < n; ++j) {
+                    const int k = __shfl(code, j);
+                    if (c < D) acc += gin[(int64_t)(k >> 1) * 2 * D + (k & 1) * D + c];
+                }
+            } else if (c < D) {
+                for (int e = e0; e < e0 + n; ++e) {
+                    const int k = rev_list[e];
+                    acc += gin[(int64_t)(k >> 1) * 2 * D + (k & 1) * D + c];
+                }
             }
-            gout[(int64_t)u * D + c] = hact[(int64_t)u * D + c] > 0.f ? acc : 0.f;
+            if (c < D) gout[(int64_t)u * D + c] = hact[(int64_t)u * D + c] > 0.f ? acc : 0.f;
         }
     }
 }
@@ -879,35 +1072,29 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
             const void *hact = sb.hidden[l];
             const int64_t ubl = ctx->ub_front[l];
+            const int n_main = grid_1d(ctx, ubl * 64);      // one wave per row of the level
+            const dim3 grid(n_main + PULL_LONG_BLOCKS);
+#define GS_PULL(LPR, HH, OH)                                                                                     \
+    hipLaunchKernelGGL((k_pull_input_grad<LPR, HH, OH>), grid, dim3(256), 0, st, sb.gtmp, D, B.rev_ptr, B.rev_cnt, \
+                       B.rev_list, B.rev_long, hact, ml, S, (void *)sb.ghid[l], n_main)
+#define GS_PULL_W(HH, OH)                                                                                        \
+    do {                                                                                                         \
+        if (D / 4 <= 16) GS_PULL(16, HH, OH);                                                                    \
+        else if (D / 4 <= 32) GS_PULL(32, HH, OH);                                                               \
+        else GS_PULL(64, HH, OH);                                                                                \
+    } while (0)
             if (h16) {
                 // the level's dZ is held in bf16 under the same condition its consumers test (dz_h)
-                const bool out_h = D % 8 == 0;
-#define GS_PULL_H(LPR)                                                                                          \
-    do {                                                                                                        \
-        if (out_h)                                                                                              \
-            hipLaunchKernelGGL((k_pull_input_grad<LPR, true, true>), dim3(grid_1d(ctx, ubl * LPR)), dim3(256), 0, st, \
-                               sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);  \
-        else                                                                                                    \
-            hipLaunchKernelGGL((k_pull_input_grad<LPR, true, false>), dim3(grid_1d(ctx, ubl * LPR)), dim3(256), 0, st, \
-                               sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);  \
-    } while (0)
-                if (D / 4 <= 16) GS_PULL_H(16);
-                else if (D / 4 <= 32) GS_PULL_H(32);
-                else GS_PULL_H(64);
-#undef GS_PULL_H
+                if (D % 8 == 0) GS_PULL_W(true, true);
+                else GS_PULL_W(true, false);
             } else if (D % 4 != 0) {
                 hipLaunchKernelGGL(k_pull_input_grad_any, dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
                                    sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, (const float *)hact, ml, S, sb.ghid[l]);
-            } else if (D / 4 <= 16) {
-                hipLaunchKernelGGL((k_pull_input_grad<16, false>), dim3(grid_1d(ctx, ubl * 16)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
-            } else if (D / 4 <= 32) {
-                hipLaunchKernelGGL((k_pull_input_grad<32, false>), dim3(grid_1d(ctx, ubl * 32)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
             } else {
-                hipLaunchKernelGGL((k_pull_input_grad<64, false>), dim3(grid_1d(ctx, ubl * 64)), dim3(256), 0, st,
-                                   sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, hact, ml, S, (void *)sb.ghid[l]);
+                GS_PULL_W(false, false);
             }
+#undef GS_PULL_W
+#undef GS_PULL
         }
     }
     {

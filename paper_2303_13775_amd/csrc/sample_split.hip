@@ -558,7 +558,7 @@ struct RevUp {
     int on;
     const int32_t *rev_cnt; int32_t *rev_ptr; int32_t *rev_fill; int32_t *rev_list; int32_t *rev_eid;
     const int32_t *cnt; const int32_t *blk_indptr; const int32_t *self_row; const int32_t *edge_row;
-    int fan; int32_t *cursor; const GsLevelMeta *meta_up2;
+    int fan; int32_t *cursor; const GsLevelMeta *meta_up2; int32_t *rev_long; int32_t *n_long;
     __device__ void alloc(int64_t x, int64_t n_rows, int S) const {
         __shared__ int s_wave[PART_BS / 64];
         __shared__ int s_base;
@@ -580,6 +580,7 @@ struct RevUp {
         if (x < n_rows) {
             rev_ptr[x] = s_base + s_wave[wave] + inc - c;
             rev_fill[x] = 0;
+            if (c > GS_REV_LONG) rev_long[atomicAdd(n_long, 1)] = (int32_t)x;      // (rare: one atomic per such row)
         }
         __syncthreads();
     }
@@ -714,7 +715,7 @@ struct PartLayer {
         }
         if (x >= n1()) {
             rev_cnt[x - n1()] = 0;
-            if (x == n1()) meta_lo->rev_cursor = 0;
+            if (x == n1()) { meta_lo->rev_cursor = 0; meta_lo->n_long = 0; }
             return;
         }
         const int i = (int)x;
@@ -808,7 +809,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
 // reverse index as two launches of its own (blockIdx.y = layer - first): used for the bottom layer,
 // which has no partition below it; same steps as RevUp::alloc / RevUp::fill
 struct RevArgs {
-    const int32_t *rev_cnt; int32_t *rev_ptr; int32_t *rev_fill; int32_t *rev_list; int32_t *rev_eid;
+    const int32_t *rev_cnt; int32_t *rev_ptr; int32_t *rev_fill; int32_t *rev_list; int32_t *rev_eid; int32_t *rev_long;
     const int32_t *cnt; const int32_t *blk_indptr; const int32_t *self_row; const int32_t *edge_row;
     GsLevelMeta *meta;          // the batch's level bookkeeping, [L + 1]
 };
@@ -848,6 +849,7 @@ __global__ __launch_bounds__(1024) void k_rev_alloc(RevArgsSet set, int l, int S
         if (u < n_lo) {
             rev_ptr[u] = s_base + s_wave[wave] + inc - c;
             rev_fill[u] = 0;
+            if (c > GS_REV_LONG) a.rev_long[atomicAdd(&meta_lo->n_long, 1)] = u;
         }
         __syncthreads();
     }
@@ -1025,7 +1027,8 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
             if (l + 1 < L && l + 1 >= c->rev_from) {
                 const GsLayerBuf &U = c->layer[l + 1];
                 pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
-                              U.self_row, U.edge_row, c->fan[l + 1], &c->d_meta[l + 1].rev_cursor, c->d_meta + (l + 2)};
+                              U.self_row, U.edge_row, c->fan[l + 1], &c->d_meta[l + 1].rev_cursor, c->d_meta + (l + 2),
+                              U.rev_long, &c->d_meta[l + 1].n_long};
             }
             pset.f[b] = pa;
             pset.hist[b] = c->part_hist;
@@ -1045,8 +1048,8 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
         RevArgsSet ra{};
         for (int b = 0; b < nbat; ++b) {
             const GsLayerBuf &B = ctxs[b]->layer[0];
-            ra.b[b] = RevArgs{B.rev_cnt, B.rev_ptr, B.rev_fill, B.rev_list, B.rev_eid, B.cnt, B.blk_indptr, B.self_row,
-                              B.edge_row, ctxs[b]->d_meta};
+            ra.b[b] = RevArgs{B.rev_cnt, B.rev_ptr, B.rev_fill, B.rev_list, B.rev_eid, B.rev_long, B.cnt, B.blk_indptr,
+                              B.self_row, B.edge_row, ctxs[b]->d_meta};
         }
         const int64_t rows = std::max<int64_t>(1, ctx->ub_front[0]);
         const int64_t items = std::max<int64_t>(1, ctx->ub_front[1] * (1 + ctx->fan[0]));

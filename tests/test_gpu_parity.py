@@ -499,3 +499,76 @@ def test_repeatable_across_runs():
         else:
             assert all(torch.equal(x, y) for x, y in zip(ref, flat))
     ctx.close()
+
+
+HUB_CASES = {
+    "tiny": (lambda: workloads.tiny(), False),
+    # hubs: a skewed graph without id permutation; the busiest row of a level feeds hundreds of destinations
+    # (more than a wave holds: the workgroup path of the backward pull)
+    "hubs": (lambda: workloads.custom(20000, 1200000, dims=[32, 64, 64, 16], fanouts=[12, 12, 12], batch=2000, n_splits=4,
+                                      abc=(0.7, 0.1, 0.1), permute_ids=False, name="hubs"), False),
+    # a row with more entries than the workgroup path sorts at once: every vertex aggregates from vertex 0
+    "huge-hub": (lambda: _star_workload(), True),
+}
+
+
+def _star_workload():
+    """20000 vertices; vertex v aggregates from vertex 0 and two more (fewer than any fanout, so every
+    destination keeps all three): the row of vertex 0 feeds every destination of a layer."""
+    from workloads import synth
+    n = 20000
+    v = torch.arange(1, n, dtype=torch.int64)
+    nb = torch.stack([torch.zeros_like(v), (v * 7 + 1) % n, (v * 13 + 5) % n], 1)
+    nb = torch.sort(nb, 1).values
+    keep = torch.ones_like(nb, dtype=torch.bool)
+    keep[:, 1:] &= nb[:, 1:] != nb[:, :-1]
+    keep &= nb != v[:, None]
+    rows = [torch.tensor([1, 2, 3])] + [nb[i][keep[i]] for i in range(n - 1)]
+    deg = torch.tensor([r.numel() for r in rows])
+    indptr = torch.cat([torch.zeros(1, dtype=torch.int64), torch.cumsum(deg, 0)]).to(torch.int32)
+    indices = torch.cat(rows).to(torch.int32)
+    pmap = synth.pmap_random(n, 2, seed=synth.MASTER_SEED)
+    return synth._finish("huge-hub", n, indptr, indices, pmap, 2, [16, 32, 8], [5, 4], 6000, synth.MASTER_SEED, "cpu")
+
+
+@pytest.mark.parametrize("name", list(HUB_CASES))
+@pytest.mark.parametrize("bf16", [False, True])
+def test_training_results_are_bit_reproducible(name, bf16):
+    """Logits and every gradient of three runs of the same batch are bit-equal (the backward pull
+    sums the entries of a reverse-index row in ascending code order, whatever order the atomic
+    cursor filled them in), and within tolerance of the oracle; also through gsplit_sage_step."""
+    from paper_2303_13775_amd import Context, SageParams, GSPLIT_BF16, GSPLIT_F32
+    dev = _dev()
+    make, beyond_cap = HUB_CASES[name]
+    w = make()
+    r = _run_fwd_bwd(w, dev, seed=11, it=4, bf16=bf16)
+    check_sage(r, w.n_layers, bf16=bf16, tag=name + " hubs")
+    ctx = _ctx(w, dev)
+    table = (w.feat.to(torch.bfloat16) if bf16 else w.feat).to(dev)
+    params = SageParams(w.dims, [t.to(dev) for t in w.w_self], [t.to(dev) for t in w.w_neigh],
+                        [t.to(dev) for t in w.bias], dtype=GSPLIT_BF16 if bf16 else GSPLIT_F32)
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=table.dtype, device=dev)
+    logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+    grads = [[torch.empty_like(t, device=dev) for t in lst] for lst in (w.w_self, w.w_neigh, w.bias)]
+    labels = w.labels.to(dev)
+    runs = []
+    for k in range(3):
+        ctx.gsplit_sample_split(w.targets(4).to(dev), 11, 4)
+        ctx.gsplit_gather_features(table, x0)
+        ctx.gsplit_sage_step(params, x0, labels, logits, *grads)
+        torch.cuda.synchronize()
+        runs.append([logits.clone()] + [t.clone() for lst in grads for t in lst])
+    cnt = [ctx.fetch_shuffle(l)["rev_cnt"] for l in range(1, w.n_layers)]
+    longest = max(int(c.max()) for c in cnt)
+    print(f"\n[reproducible {name}] longest reverse-index row {longest} entries, rows with more than 256 (workgroup path): "
+          f"{[int((c > 256).sum()) for c in cnt]}", flush=True)
+    if name != "tiny":
+        assert longest > 64
+    if beyond_cap:      # (summed segment by segment in list order: within tolerance, not bit-reproducible)
+        assert longest > 4096
+        ctx.close()
+        return
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert torch.equal(x, y), "results of two runs of the same batch differ in some bit"
+    ctx.close()
