@@ -80,6 +80,10 @@ typedef struct {
                                        that overlaps sampling with training on another stream does better with
                                        2: the latency-bound sampling kernels then leave room for the training
                                        kernels' workgroups */
+    int32_t        table_mode;      /* dedup tables of the split step: 0 = the library chooses, 1 = hashed (open
+                                       addressing, sized for the largest layer), 2 = direct (indexed by the key
+                                       itself: 12 bytes per vertex and split plus 12 per vertex, one atomic per
+                                       insert; needs n_vertices * n_splits < 2^30).  Same results either way */
 } gsplit_config;
 
 /* Creates a context on the current HIP device and allocates its workspace, sized from the

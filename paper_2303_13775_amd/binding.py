@@ -45,7 +45,8 @@ class _Graph(C.Structure):
 
 class _Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("fanouts", C.POINTER(C.c_int32)), ("max_targets", C.c_int64),
-                ("keep_edge_ids", C.c_int32), ("gat_index", C.c_int32), ("sampler_blocks_per_cu", C.c_int32)]
+                ("keep_edge_ids", C.c_int32), ("gat_index", C.c_int32), ("sampler_blocks_per_cu", C.c_int32),
+                ("table_mode", C.c_int32)]
 
 
 class _LevelView(C.Structure):
@@ -220,7 +221,7 @@ def gsplit_sample_split_noalloc(indptr: torch.Tensor, indices: torch.Tensor, pma
     fan = (C.c_int32 * L)(*[int(f) for f in fanouts])
     g = _Graph(indptr.numel() - 1, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
                indices.data_ptr(), pmap.data_ptr(), int(n_splits))
-    c = _Config(L, fan, int(max_targets), 0, 0, 0)
+    c = _Config(L, fan, int(max_targets), 0, 0, 0, 0)
     with torch.cuda.device(indptr.device):
         rc = lib.gsplit_sample_split_noalloc(C.byref(g), C.byref(c), targets.data_ptr(), targets.numel(),
                                              C.c_uint64(seed), C.c_uint64(it), C.byref(o), _stream())
@@ -292,7 +293,7 @@ class Context:
 
     def __init__(self, indptr: torch.Tensor, indices: torch.Tensor, pmap: torch.Tensor, n_splits: int,
                  fanouts: Sequence[int], max_targets: int, keep_edge_ids: bool = False,
-                 gat_index: bool = False, sampler_blocks_per_cu: int = 0):
+                 gat_index: bool = False, sampler_blocks_per_cu: int = 0, table_mode: int = 0):
         self.lib = load_library()
         assert indptr.is_cuda and indices.is_cuda and pmap.is_cuda
         assert indptr.dtype in (torch.int32, torch.int64) and indices.dtype == torch.int32
@@ -308,7 +309,8 @@ class Context:
         g = _Graph(self.n_vertices, indices.numel(), indptr.data_ptr(), int(indptr.dtype == torch.int64),
                    indices.data_ptr(), pmap.data_ptr(), self.S)
         self.n_edges = indices.numel()
-        c = _Config(self.L, self._fan, int(max_targets), int(keep_edge_ids), int(gat_index), int(sampler_blocks_per_cu))
+        c = _Config(self.L, self._fan, int(max_targets), int(keep_edge_ids), int(gat_index), int(sampler_blocks_per_cu),
+                    int(table_mode))
         h = C.c_void_p()
         with torch.cuda.device(self.device):
             rc = self.lib.gsplit_create(C.byref(h), C.byref(g), C.byref(c))

@@ -45,6 +45,16 @@ static void free_all(gsplit_ctx *ctx) {
     ctx->sample_done = nullptr;
 }
 
+// Direct tables take 12 bytes per key of the whole key space; the hashed ones 12 bytes per entry of a
+// table sized for the largest layer.  Measured: direct tables shorten the sampler of a layer (one atomic
+// per insert, no probing) as long as their key space stays inside the memory-side cache (256 MB); over a
+// key space of GBs every lookup of the later passes misses it, and the hashed tables, which are
+// compact, win.
+static bool direct_tables_pay(int64_t keys_m, int64_t tab_cap) {
+    (void)tab_cap;
+    return keys_m * 12 <= (192ll << 20);
+}
+
 static int64_t pow2_at_least(int64_t x) {
     int64_t p = 1024;
     while (p < x) p <<= 1;
@@ -134,13 +144,23 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
     // one split: the (vertex, split) key is the vertex key, and one table serves as both
+    const int64_t keys_m = g->n_vertices * (int64_t)g->n_splits, keys_l = g->n_vertices;
+    ctx->direct_tables = c->table_mode == 2 || (c->table_mode == 0 && direct_tables_pay(keys_m, tab_cap));
+    if (ctx->direct_tables && keys_m >= (1ll << 30)) ctx->direct_tables = false;     // entry indices are 31-bit
     for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
         if (t == &ctx->tab_local && ctx->S == 1) {
             *t = ctx->tab_mixed;
             break;
         }
-        A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
-        A((void **)&t->row, sizeof(int32_t) * tab_cap, "table rows");
+        t->slot = nullptr; t->row = nullptr; t->pos = nullptr;
+        if (ctx->direct_tables) {
+            const int64_t keys = t == &ctx->tab_mixed ? keys_m : keys_l;
+            A((void **)&t->pos, sizeof(unsigned long long) * keys, "direct table entries");
+            A((void **)&t->row, sizeof(int32_t) * keys, "direct table rows");
+        } else {
+            A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
+            A((void **)&t->row, sizeof(int32_t) * tab_cap, "table rows");
+        }
     }
     A((void **)&ctx->ent_mixed, sizeof(int32_t) * max_items, "ent_mixed");
     A((void **)&ctx->ent_local, sizeof(int32_t) * max_items, "ent_local");
@@ -151,9 +171,13 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
     // every table entry empty (all bits set): a batch starts on clean tables, and leaves them so
-    for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local})
-        if (rc == GSPLIT_OK && hipMemset(t->slot, 0xFF, sizeof(unsigned long long) * tab_cap) != hipSuccess)
-            rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
+    for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
+        if (rc != GSPLIT_OK) break;
+        const int64_t keys = t == &ctx->tab_mixed ? keys_m : keys_l;
+        const hipError_t e = ctx->direct_tables ? hipMemset(t->pos, 0xFF, sizeof(unsigned long long) * keys)
+                                                : hipMemset(t->slot, 0xFF, sizeof(unsigned long long) * tab_cap);
+        if (e != hipSuccess) rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
+    }
     if (rc == GSPLIT_OK && hipEventCreateWithFlags(&ctx->sample_done, hipEventDisableTiming) != hipSuccess)
         rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipEventCreate failed");
     if (rc != GSPLIT_OK) {

@@ -33,12 +33,22 @@ struct GsLevelMeta {
     int32_t error;      // set non-zero by a kernel that hit an impossible state (probe overflow)
     int32_t rev_cursor; // allocation cursor of the reverse (scatter) index
     int32_t n_long;     // rows of the level with more than GS_REV_LONG entries in the reverse index
+    uint32_t batches;   // (level 0 only) batches sampled by this context so far: the source of the direct tables' stamps
+    int32_t pad[3];
 };
 
-// Open-addressing table in HBM: entry = key << 32 | smallest position seen; row = final row.
+// Dedup table in HBM, in one of two forms.
+//   hashed: open addressing, entry = key << 32 | smallest position seen; row = final row of the key.
+//   direct (pos != nullptr): one 64-bit entry and one row per possible key, indexed by the key itself:
+//   an insert is a single atomic min, no probing, no key compare, and nothing is ever reset: the
+//   entry is stamp << 32 | smallest position seen, where the stamp of a (batch, layer) is smaller than
+//   every stamp before it, so whatever an older layer left behind loses against the first insert of
+//   the current one.  Takes 12 bytes per key of the key space (|V| * S for (vertex, split) keys, |V|
+//   for vertex keys).
 struct GsTable {
     unsigned long long *slot;
     int32_t            *row;
+    unsigned long long *pos;
 };
 
 struct GsLayerBuf {            // sampling layer l
@@ -144,6 +154,7 @@ struct gsplit_ctx {
     bool     keep_edge_ids = false;
     bool     gat_index = false;
     int      sampler_blocks_per_cu = 8;    // cap on the grids of the sampling and index kernels
+    bool     direct_tables = false;    // dedup tables indexed by the key itself (see GsTable)
     int      rev_from = 1;             // lowest sampling layer with a reverse index (0 with gat_index)
     int64_t  ub_front[GS_MAXL + 1] = {0};   // upper bounds on |local_cat[l]|
     int      n_cu = 256;

@@ -83,6 +83,12 @@ __device__ __forceinline__ uint32_t table_slot(uint32_t key, int bits) {
 // few elements share a key, since every attempt on a taken entry is then an atomic on it.
 __device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t key, uint32_t p,
                                             int32_t *err, bool *behind = nullptr, bool claim_first = false) {
+    if (t.pos) {        // direct table: the key is its own entry index (bits carries the layer's stamp)
+        const unsigned long long mine = ((unsigned long long)(uint32_t)bits << 32) | p;
+        const unsigned long long old = atomicMin(&t.pos[key], mine);
+        if (behind && (uint32_t)(old >> 32) == (uint32_t)bits && (uint32_t)old < p) *behind = true;
+        return (int)key;
+    }
     const uint32_t mask = (1u << bits) - 1u;
     const unsigned long long mine = ((unsigned long long)key << 32) | p;
     uint32_t h = table_slot(key, bits);
@@ -107,6 +113,17 @@ __device__ __forceinline__ int table_insert(const GsTable &t, int bits, uint32_t
     }
     *err = 1;
     return -1;
+}
+
+// smallest position an entry has seen (the entry's key is known to be the caller's)
+__device__ __forceinline__ uint32_t table_pos(const GsTable &t, int h) {
+    return t.pos ? (uint32_t)t.pos[h] : (uint32_t)t.slot[h];
+}
+
+// Stamp of the direct tables for sampling layer `layer` of the batch a context is working on: falls
+// with every batch and, inside a batch, from the top layer down (8 = GSPLIT_MAX_LAYERS per batch).
+__device__ __forceinline__ uint32_t table_stamp(const GsLevelMeta *meta_level0, uint32_t layer) {
+    return 0xFFFFFFF0u - (meta_level0->batches * 8u + (7u - layer));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -172,7 +189,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
         iter = a.seed_iter[1];
     }
     const int n1 = meta_up->front_off[S];
-    const int bits = table_bits(n1 * (1 + fan));
+    const int bits = tab.pos ? (int)table_stamp(meta_lo - layer, layer) : table_bits(n1 * (1 + fan));
     const bool claim_first = n1 * (1 + fan) <= CLAIM_FIRST_MAX;
     const int groups_per_block = PART_BS / G;
     const int q = threadIdx.x % G;
@@ -495,6 +512,7 @@ struct PartTargets {
     __device__ int64_t n_side() const { return n_levels; }
     __device__ void side(int64_t x, int64_t ns) const {
         if (x < ns) meta_all[x].error = 0;
+        if (x == 0) meta_all[0].batches += 1;
     }
 };
 
@@ -512,6 +530,7 @@ __global__ __launch_bounds__(TARGETS_SMALL) void k_targets_small(TargetsSet set)
     __shared__ PartOffs s_o;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     if (tid < f.n_levels) f.meta_all[tid].error = 0;
+    if (tid == 0) f.meta_all[0].batches += 1;
     __syncthreads();                                   // the flags are cleared before target() may set one
     const bool in = tid < f.n_targets;
     int32_t id = 0;
@@ -637,12 +656,12 @@ struct PartLayer {
             const int32_t id = nbr[g];
             const uint32_t pos = (uint32_t)(n1() + g);
             m = 1u << 16;
-            if ((uint32_t)tab_mixed.slot[h] == pos) {
+            if (table_pos(tab_mixed, h) == pos) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
                 const unsigned t = pmap[id] & (GS_MAXS - 1);
                 m |= (1u << s) | (1u << (8 + t));
                 const int hl = ent_local[n1() + g];
-                if (hl >= 0 && (uint32_t)tab_local.slot[hl] == pos) m |= 1u << (17 + t);
+                if (hl >= 0 && table_pos(tab_local, hl) == pos) m |= 1u << (17 + t);
             }
         }
         cls[g] = m;
@@ -776,6 +795,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
             const int r = h >= 0 ? tab_local.row[h] : -1;
             self_row[i] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
+
         } else {
             const int64_t g = x - n_mixed - n1;
             int h = ent_mixed[n1 + g];
@@ -789,6 +809,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
             blk_src[blk_indptr[i] + q] = mrow;          // edges[l] as rows of the split's mixed frontier
             edge_row[blk_indptr[i] + q] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
+
         }
     }
     // layers above the bottom one: both tables are cleared for the next sampling layer (this kernel
@@ -796,7 +817,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
     // the bottom layer: cleared for the top layer of the next batch instead (top_cap entries cover
     // max_targets targets), so that the batch's first kernel, a single workgroup for a small batch,
     // does not have to
-    if (fan_next > 0 || top_cap > 0) {
+    if (!tab_local.pos && (fan_next > 0 || top_cap > 0)) {
         const int64_t nr = fan_next > 0 ? 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next)) : top_cap;
         for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < 2 * nr;
              x += (int64_t)gridDim.x * blockDim.x) {
@@ -1198,8 +1219,8 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     unsigned char *base = dev->ptr;       // this GPU's copy of the array (never the array's name on the host)
     ctx.n_cu = dev->n_cu;
     ctx.d_meta = (GsLevelMeta *)(base + o_meta);
-    ctx.tab_mixed = GsTable{(unsigned long long *)(base + o_mslot), (int32_t *)(base + o_mrow)};
-    ctx.tab_local = GsTable{(unsigned long long *)(base + o_lslot), (int32_t *)(base + o_lrow)};
+    ctx.tab_mixed = GsTable{(unsigned long long *)(base + o_mslot), (int32_t *)(base + o_mrow), nullptr};
+    ctx.tab_local = GsTable{(unsigned long long *)(base + o_lslot), (int32_t *)(base + o_lrow), nullptr};
     ctx.ent_mixed = (int32_t *)(base + o_em); ctx.ent_local = (int32_t *)(base + o_el);
     ctx.mixed_ent = (int32_t *)(base + o_me); ctx.cls = (uint32_t *)(base + o_cls);
     ctx.part_hist = (int32_t *)(base + o_hist);
@@ -1247,7 +1268,7 @@ extern "C" int gsplit_sample_split_multi(gsplit_ctx *const *ctxs, int32_t n_batc
             if (ctxs[a] == c) return gs_fail(first, GSPLIT_EINVAL, "gsplit_sample_split_multi: a context is listed twice");
         bool same = c->L == first->L && c->S == first->S && c->max_targets == first->max_targets &&
                     c->keep_edge_ids == first->keep_edge_ids && c->gat_index == first->gat_index &&
-                    c->sampler_blocks_per_cu == first->sampler_blocks_per_cu &&
+                    c->sampler_blocks_per_cu == first->sampler_blocks_per_cu && c->direct_tables == first->direct_tables &&
                     c->graph.d_indptr == first->graph.d_indptr && c->graph.d_indices == first->graph.d_indices &&
                     c->graph.d_pmap == first->graph.d_pmap && c->graph.n_vertices == first->graph.n_vertices &&
                     c->graph.indptr_is_64 == first->graph.indptr_is_64;

@@ -24,10 +24,10 @@ def _dev():
     return torch.device("cuda:0")
 
 
-def _ctx(w, dev, max_targets=None):
+def _ctx(w, dev, max_targets=None, table_mode=0):
     from paper_2303_13775_amd import Context
     return Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts,
-                   max_targets or w.batch)
+                   max_targets or w.batch, table_mode=table_mode)
 
 
 def _oracle_batch(w, tg, seed, it, n_splits=None, pmap=None):
@@ -84,11 +84,13 @@ CASES = {
 }
 
 
+@pytest.mark.parametrize("table_mode", [1, 2], ids=["hashed", "direct"])
 @pytest.mark.parametrize("name", list(CASES))
-def test_sample_split_bit_exact(name):
+def test_sample_split_bit_exact(name, table_mode):
+    """Both forms of the dedup tables (hashed; indexed by the key itself) give the oracle's batch."""
     dev = _dev()
     w = CASES[name]()
-    ctx = _ctx(w, dev)
+    ctx = _ctx(w, dev, table_mode=table_mode)
     for it in (0, 1):
         tg = w.targets(it)
         ctx.gsplit_sample_split(tg.to(dev), seed=1234 + it, it=it)
@@ -128,7 +130,7 @@ def test_multi_batch_sampling_bit_exact(name, n_batches):
     dev = _dev()
     w = CASES[name]()
     gi, gx, gp = w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev)
-    ctxs = [Context(gi, gx, gp, w.n_splits, w.fanouts, w.batch) for _ in range(n_batches)]
+    ctxs = [Context(gi, gx, gp, w.n_splits, w.fanouts, w.batch, table_mode=1 + n_batches % 2) for _ in range(n_batches)]
     for rnd in (0, 1):
         its = [10 * rnd + b for b in range(n_batches)]
         tgs = [w.targets(it)[:max(0, w.batch - 37 * b)] for b, it in enumerate(its)]
@@ -142,7 +144,7 @@ def test_multi_batch_sampling_bit_exact(name, n_batches):
                 SC.assert_shuffle_index_equal(ctxs[b], ob, l, has_rev=l >= 1)
     with pytest.raises(GsplitError):                       # the same context twice
         gsplit_sample_split_multi([ctxs[0], ctxs[0]], [tgs[0].to(dev)] * 2, 1, [0, 1])
-    other = Context(gi, gx, gp, w.n_splits, w.fanouts, max(1, w.batch // 2))
+    other = Context(gi, gx, gp, w.n_splits, w.fanouts, max(1, w.batch // 2), table_mode=1 + n_batches % 2)
     with pytest.raises(GsplitError):                       # another configuration
         gsplit_sample_split_multi([ctxs[0], other], [tgs[0].to(dev)[:1]] * 2, 1, [0, 1])
     for c in ctxs + [other]:

@@ -57,7 +57,7 @@ def test_random_configuration(k):
     from paper_2303_13775_amd import Context
     # the cap on the sampling kernels' grids takes every value it can over the configurations
     ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts, w.batch,
-                  sampler_blocks_per_cu=1 + k % 8)
+                  sampler_blocks_per_cu=1 + k % 8, table_mode=1 + (k // 2) % 2)      # hashed and direct dedup tables
     for it in (0, 1):
         tg = w.targets(it).to(dev)
         ctx.gsplit_sample_split(tg, 500 + k, it)
