@@ -699,7 +699,7 @@ def profile_traffic(workload, dtype, model, label):
         return None, None
     for line in open(path):
         f = line.split()
-        if len(f) >= 6 and f[0] == label:
+        if len(f) >= 5 and f[0] == label:
             try:
                 return (float(f[-2]) + float(f[-1])) * 1024.0, "profiles/" + name
             except ValueError:
@@ -897,6 +897,7 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         "gather_GBps": gather["achieved"], "stage_ms": stage_ms,
         "kernel_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
         "kernels_per_step": sum(v[0] for v in ktimes.values()) / n_k,
+        "kernel_launch_order": list(ktimes.keys()),
         "batch_shape": {"rows_per_level": rows, "edges_per_layer": edges, "mixed_rows_per_layer": mixed,
                         "ids_shuffled_per_layer": [sum(b[s][t] for s in range(S) for t in range(S) if s != t)
                                                    for b in bucket]},
@@ -1028,9 +1029,11 @@ def main():
     elif a.workload == "skewed":
         w = workloads.skewed(device=dev, n_splits=a.splits, progress=say)
     else:   # split sweep on the large graph: 4 layers, fanout 10, batch 8192
-        w = workloads.large(device=dev, n_splits=a.splits, feat_dtype=fdt, batch=8192, fanouts=(10, 10, 10, 10),
-                            dims=(128, 256, 256, 256, 172), progress=say)
-        w.name = f"sweep-S{a.splits}"
+        base = workloads.large(device=dev, n_splits=4, feat_dtype=fdt, progress=say)
+        w = workloads.variant(base, n_splits=a.splits, pmap_kind="bfs", rank=workloads.bfs_rank(base.indptr, base.indices),
+                              batch=8192, fanouts=(10, 10, 10, 10), dims=(128, 256, 256, 256, 172),
+                              name=f"sweep-S{a.splits}")
+        del base
     if w.feat.dtype != fdt:
         w.feat = w.feat.to(fdt)
     torch.cuda.synchronize()
