@@ -254,9 +254,8 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6
 // A row with more than 256 entries (a hub: tens of thousands of destinations can sample the same
 // vertex) is left to the workgroups behind the launch's own (blockIdx.x >= n_main), which walk the
 // list of such rows that the sampler made: codes sorted in LDS (bitonic, up to PULL_LONG_CAP at a
-// time), the four waves sum a quarter of the sorted list each, partial sums added in wave order.
-// (Only a row with more than PULL_LONG_CAP entries is summed segment by segment in list order,
-// i.e. not reproducibly in the last bits.)
+// time: a longer row in windows of ascending values), the four waves sum a quarter of the sorted
+// window each, partial sums added in wave order, windows in ascending order.
 constexpr int PULL_LONG_CAP = 4096;
 constexpr int PULL_LONG_BLOCKS = 1024;
 
@@ -344,6 +343,7 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
         // ---- long rows: one workgroup per row
         __shared__ int s_code[PULL_LONG_CAP];
         __shared__ float4 s_part[4][64];
+        __shared__ int s_cnt;
         const int n_long = meta_lo->n_long;
         for (int i = (int)blockIdx.x - n_main; i < n_long; i += (int)gridDim.x - n_main) {
             const int u = rev_long[i];
@@ -353,20 +353,63 @@ __global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict
                 const bool cv = c < nvec;
                 const float4 h = cv ? load_act4<HACT_H>(hact, (int64_t)u * nvec + c) : make_float4(0.f, 0.f, 0.f, 0.f);
                 float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
-                for (int seg = 0; seg < n; seg += PULL_LONG_CAP) {
-                    const int m = min(PULL_LONG_CAP, n - seg);
+                // A row of at most PULL_LONG_CAP entries is one window.  A longer one is taken in windows of
+                // values (lo, T]: the codes of a row are distinct, so the largest T with at most
+                // PULL_LONG_CAP codes inside (found by bisection over the values, one counting pass over
+                // the row per step) yields the next PULL_LONG_CAP codes in ascending order whatever
+                // order the row was filled in.
+                int lo = -1;
+                for (int taken = 0; taken < n;) {
+                    int T = 0x7FFFFFFE;
+                    if (n > PULL_LONG_CAP) {
+                        int a = lo + 1, b = 0x7FFFFFFE;
+                        while (a < b) {
+                            const int mid = a + ((b - a + 1) >> 1);
+                            __syncthreads();
+                            if (threadIdx.x == 0) s_cnt = 0;
+                            __syncthreads();
+                            int cnt = 0;
+                            for (int t = threadIdx.x; t < n; t += 256) {
+                                const int code = rev_list[e0 + t];
+                                cnt += (code > lo && code <= mid) ? 1 : 0;
+                            }
+                            for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+                            if (lane == 0 && cnt) atomicAdd(&s_cnt, cnt);
+                            __syncthreads();
+                            if (s_cnt <= PULL_LONG_CAP) a = mid; else b = mid - 1;
+                        }
+                        T = a;
+                    }
+                    __syncthreads();
+                    if (threadIdx.x == 0) s_cnt = 0;
+                    __syncthreads();
+                    if (n > PULL_LONG_CAP) {
+                        for (int t = threadIdx.x; t < n; t += 256) {
+                            const int code = rev_list[e0 + t];
+                            if (code > lo && code <= T) {
+                                const int at = atomicAdd(&s_cnt, 1);
+                                if (at < PULL_LONG_CAP) s_code[at] = code;
+                            }
+                        }
+                    } else {
+                        for (int t = threadIdx.x; t < n; t += 256) s_code[t] = rev_list[e0 + t];
+                        if (threadIdx.x == 0) s_cnt = n;
+                    }
+                    __syncthreads();
+                    const int m = min(s_cnt, PULL_LONG_CAP);
                     int p2 = 64;
                     while (p2 < m) p2 <<= 1;
+                    for (int t = m + threadIdx.x; t < p2; t += 256) s_code[t] = 0x7FFFFFFF;
                     __syncthreads();
-                    for (int t = threadIdx.x; t < p2; t += 256) s_code[t] = t < m ? rev_list[e0 + seg + t] : 0x7FFFFFFF;
-                    __syncthreads();
+                    lo = T;
+                    taken += max(m, 1);         // (a window is never empty; the loop ends whatever the row holds)
                     for (int k = 2; k <= p2; k <<= 1) {
                         for (int j = k >> 1; j > 0; j >>= 1) {
                             for (int t = threadIdx.x; t < (p2 >> 1); t += 256) {
-                                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
-                                const int x = s_code[lo], y = s_code[hi];
-                                const bool asc = (lo & k) == 0;
-                                if ((x > y) == asc) { s_code[lo] = y; s_code[hi] = x; }
+                                const int ia = ((t & ~(j - 1)) << 1) | (t & (j - 1)), ib = ia | j;
+                                const int x = s_code[ia], y = s_code[ib];
+                                const bool asc = (ia & k) == 0;
+                                if ((x > y) == asc) { s_code[ia] = y; s_code[ib] = x; }
                             }
                             __syncthreads();
                         }

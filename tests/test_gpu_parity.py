@@ -509,7 +509,7 @@ HUB_CASES = {
     # (more than a wave holds: the workgroup path of the backward pull)
     "hubs": (lambda: workloads.custom(20000, 1200000, dims=[32, 64, 64, 16], fanouts=[12, 12, 12], batch=2000, n_splits=4,
                                       abc=(0.7, 0.1, 0.1), permute_ids=False, name="hubs"), False),
-    # a row with more entries than the workgroup path sorts at once: every vertex aggregates from vertex 0
+    # a row with more entries than the workgroup path sorts at once (two windows): every vertex aggregates from vertex 0
     "huge-hub": (lambda: _star_workload(), True),
 }
 
@@ -566,10 +566,8 @@ def test_training_results_are_bit_reproducible(name, bf16):
           f"{[int((c > 256).sum()) for c in cnt]}", flush=True)
     if name != "tiny":
         assert longest > 64
-    if beyond_cap:      # (summed segment by segment in list order: within tolerance, not bit-reproducible)
+    if beyond_cap:      # (taken in windows of ascending values, 4096 codes at a time)
         assert longest > 4096
-        ctx.close()
-        return
     for other in runs[1:]:
         for x, y in zip(runs[0], other):
             assert torch.equal(x, y), "results of two runs of the same batch differ in some bit"
