@@ -783,6 +783,26 @@ __global__ __launch_bounds__(TOP_T) void k_sage_top_fused(TopArgs a) {
 }
 
 #include "sage_bf16.h"
+#include "gemm_bf16_rows.h"
+
+// The streaming bf16 row-block kernel takes a product when the contraction is 256 or 512, the output
+// rows are whole 16-byte granules and the level is large enough (by its bound) to fill the chip.
+constexpr int64_t RB_MIN_ROWS = 32768;
+bool rows_gemm_fits(int64_t ub_rows, int K, int NB, int granule) {
+    return (K == 256 || K == 512) && NB % granule == 0 && ub_rows >= RB_MIN_ROWS;
+}
+// weight gradients of layer l through the streaming kernel: dZ held in bf16 (a level below the top
+// one whose width allows 16-byte rows), whole 16-byte column groups, a level that fills the chip
+bool grad_w_streams(const gsplit_sage_params *p, int l, int L, int64_t ub_rows) {
+    const int D = p->dims[l], N = p->dims[l + 1];
+    return p->dtype == GSPLIT_BF16 && l < L - 1 && N % 8 == 0 && N >= 128 && (2 * D) % 8 == 0 && 2 * D >= 128 &&
+           ub_rows >= RB_MIN_ROWS;
+}
+// one workgroup per compute unit, a multiple of (8 XCDs x column blocks)
+unsigned rows_gemm_grid(const gsplit_ctx *ctx, int NB, int BN) {
+    const int nb = (NB + BN - 1) / BN;
+    return (unsigned)(std::max(1, ctx->n_cu / (8 * nb)) * 8 * nb);
+}
 
 int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
     GsSageBuf &sb = ctx->sage;
@@ -811,7 +831,7 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
             rc = gs_alloc(ctx, (void **)&sb.wtrans[l], 2 * (size_t)p->dims[l + 1] * 2 * p->dims[l], "bf16 weights^T");
         }
         if (rc) return rc;
-        rc = gs_alloc(ctx, (void **)&sb.inv_cnt[l], sizeof(float) * ctx->ub_front[l + 1], "inverse counts");
+        rc = gs_alloc(ctx, (void **)&sb.inv_cnt[l], sizeof(float) * (ctx->ub_front[l + 1] + RB_BM), "inverse counts");
         if (rc) return rc;
     }
     for (int l = 0; l < L; ++l) {
@@ -820,7 +840,15 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         // the device from the actual row count
         const int m_rows = 2 * p->dims[l] + (p->dtype == GSPLIT_BF16 ? 1 : 0);    // bf16: plus the row of ones
         const int tiles = (int)(gs_ceil_div(m_rows, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
-        const int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
+        int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
+        sb.rows_min[l] = GRAD_W_ROWS_MIN;
+        // a large bf16 level below the top one: one workgroup per compute unit, each a whole 256 x 256 block
+        sb.gw_stream[l] = grad_w_streams(p, l, L, ctx->ub_front[l + 1]);
+        if (sb.gw_stream[l]) {
+            const int big = (int)(gs_ceil_div(2 * p->dims[l], GWH_B) * gs_ceil_div(p->dims[l + 1], GWH_B));
+            chunks = std::max(8, ctx->n_cu / big / 8 * 8);
+            sb.rows_min[l] = GWH_ROWS_MIN;
+        }
         sb.nchunk[l] = (int)chunks;
         // the fused top-layer kernel writes one slab per workgroup: TOP_R rows each, at most 256 of them
         int64_t slabs = chunks;
@@ -989,9 +1017,19 @@ int sage_forward(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_fea
             MatRowsH wt{sb.wtrans[l], N, 2 * D};
             EpiFwdH epi{l == L - 1 ? (void *)d_logits : sb.hidden[l + 1], (const float *)p->d_bias[l], N, 0,
                         l < L - 1 ? 1 : 0, l == L - 1 ? 1 : 0};
-            dim3 grid(row_block_grid<TileMid>(ctx, ub, N));
             GsTimeScope ts(ctx, "linear_fwd", l, st);
-            hipLaunchKernelGGL(k_sage_linear_fwd_h, grid, dim3(GNT), 0, st, x, wt, epi, mu, S);
+            if (l < L - 1 && rows_gemm_fits(ub, 2 * D, N, 8)) {
+                RbEpi re{sb.hidden[l + 1], N, (const float *)p->d_bias[l], nullptr, 0, 1};
+                if (2 * D == 256)
+                    hipLaunchKernelGGL((k_rows_gemm_hb<16, false>), dim3(rows_gemm_grid(ctx, N, 256)), dim3(GNT), 0, st,
+                                       x.p, wt.p, N, re, mu, S);
+                else
+                    hipLaunchKernelGGL((k_rows_gemm_hb<32, false>), dim3(rows_gemm_grid(ctx, N, 128)), dim3(GNT), 0, st,
+                                       x.p, wt.p, N, re, mu, S);
+            } else {
+                dim3 grid(row_block_grid<TileMid>(ctx, ub, N));
+                hipLaunchKernelGGL(k_sage_linear_fwd_h, grid, dim3(GNT), 0, st, x, wt, epi, mu, S);
+            }
         }
         GS_HIP(ctx, hipGetLastError());
         sb.fwd_done = l_end == L;
@@ -1082,7 +1120,11 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
                 MatRowsOnesH inh{(const uint16_t *)sb.xin[l], 0, 2 * D};
                 const int tm = (int)gs_ceil_div(ew.rows, GBM), tn = (int)gs_ceil_div(ew.N, GBN);
                 dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
-                if (dz_h)
+                if (sb.gw_stream[l]) {
+                    const int bm = (int)gs_ceil_div(2 * D, GWH_B), bn = (int)gs_ceil_div(N, GWH_B);
+                    hipLaunchKernelGGL(k_grad_w_hb, dim3((unsigned)(sb.nchunk[l] * bm * bn)), dim3(GWH_NT), 0, st, inh.p, 2 * D,
+                                       dzh.p, N, sb.gw_part[l], sb.nchunk[l], sb.rows_min[l], bm, bn, mu, S);
+                } else if (dz_h)
                     hipLaunchKernelGGL((k_sage_grad_w_h<PatchDzH, MatRowsH>), grid, dim3(GNT), 0, st, inh, dzh, ew,
                                        sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
                 else if (vdz)
@@ -1103,7 +1145,15 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
                 if (h16) {
                     dim3 grid(row_block_grid<TileMid>(ctx, ub, 2 * D));
                     MatRowsH wsk{sb.wstack[l], 2 * D, (N + 7) & ~7};
-                    if (dz_h) hipLaunchKernelGGL(k_sage_grad_in_hh, grid, dim3(GNT), 0, st, dzh, wsk, ei, mu, S);
+                    if (dz_h && rows_gemm_fits(ub, N, 2 * D, 4)) {
+                        RbEpi re{sb.gtmp, 2 * D, nullptr, sb.inv_cnt[l], D, 0};
+                        if (N == 256)
+                            hipLaunchKernelGGL((k_rows_gemm_hb<16, true>), dim3(rows_gemm_grid(ctx, 2 * D, 256)), dim3(GNT), 0,
+                                               st, dzh.p, wsk.p, 2 * D, re, mu, S);
+                        else
+                            hipLaunchKernelGGL((k_rows_gemm_hb<32, true>), dim3(rows_gemm_grid(ctx, 2 * D, 128)), dim3(GNT), 0,
+                                               st, dzh.p, wsk.p, 2 * D, re, mu, S);
+                    } else if (dz_h) hipLaunchKernelGGL(k_sage_grad_in_hh, grid, dim3(GNT), 0, st, dzh, wsk, ei, mu, S);
                     else if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
                     else hipLaunchKernelGGL((k_sage_grad_in_h<1>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
                 } else {
@@ -1145,7 +1195,7 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
         int64_t wmax = 1;
         for (int l = 0; l < L; ++l) {
             gr.part[l] = sb.gw_part[l]; gr.gws[l] = d_gw_self[l]; gr.gwn[l] = d_gw_neigh[l]; gr.gb[l] = d_gbias[l];
-            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = GRAD_W_ROWS_MIN;
+            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = sb.rows_min[l];
             gr.fixed_chunks[l] = l == L - 1 ? top_chunks : 0;
             wmax = std::max<int64_t>(wmax, (int64_t)(2 * p->dims[l] + 1) * p->dims[l + 1]);
         }

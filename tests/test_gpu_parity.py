@@ -381,6 +381,12 @@ BF16_CASES = {
                                             batch=512, n_splits=4, pmap_kind="range", name="mdims"),
     "deep-S8": lambda: workloads.custom(20000, 500000, dims=[128, 256, 256, 256, 172], fanouts=[10, 10, 10, 10],
                                         batch=300, n_splits=8, name="deep"),
+    # levels of more than 32768 rows (by their bound) with contractions of 256 and 512: the streaming
+    # row-block kernel (weights in registers, rows through LDS) for forward and input-gradient products
+    "streamed": lambda: workloads.custom(200000, 3000000, dims=[128, 256, 256, 256, 64], fanouts=[4, 5, 6, 6],
+                                         batch=700, n_splits=4, pmap_kind="range", name="streamed"),
+    "streamed-512": lambda: workloads.custom(150000, 2500000, dims=[128, 256, 512, 64], fanouts=[5, 10, 10],
+                                             batch=3000, n_splits=3, name="streamed512"),
     # hidden widths that are multiples of 4 but not of 8: dZ stays in float below the top level
     "width-mod-4": lambda: workloads.custom(6000, 150000, dims=[100, 60, 44, 10], fanouts=[8, 6, 4], batch=300,
                                             n_splits=3, name="mod4"),
