@@ -256,8 +256,19 @@ __global__ __launch_bounds__(GNT) __attribute__((amdgpu_waves_per_eu(T::LEAN ? 6
 // list of such rows that the sampler made: codes sorted in LDS (bitonic, up to PULL_LONG_CAP at a
 // time: a longer row in windows of ascending values), the four waves sum a quarter of the sorted
 // window each, partial sums added in wave order, windows in ascending order.
-constexpr int PULL_LONG_CAP = 4096;
+constexpr int PULL_LONG_CAP = 2048;
 constexpr int PULL_LONG_BLOCKS = 1024;
+
+// workgroups of 256 threads of a kernel that one compute unit holds at once (asked once per kernel)
+template <class K>
+int resident_blocks(K kernel) {
+    static const int blocks = [kernel] {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb < 1) nb = 4;
+        return std::min(nb, 8);
+    }();
+    return blocks;
+}
 
 // Bitonic sort across a wave, ascending, of the first p2 lanes' values (p2 a power of two; the lanes
 // behind hold INT_MAX padding and stay where they are): log2(p2) * (log2(p2) + 1) / 2 exchange steps, so
@@ -327,7 +338,7 @@ __device__ __forceinline__ void store_masked4(void *__restrict__ gout, int64_t i
 __device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
 
 template <int LPR, bool HACT_H, bool OUT_H = false>
-__global__ __launch_bounds__(256) void k_pull_input_grad(const float *__restrict__ gin, int D,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OUT_H ? 8 : 4, 8))) void k_pull_input_grad(const float *__restrict__ gin, int D,
                                                          const int32_t *__restrict__ rev_ptr,
                                                          const int32_t *__restrict__ rev_cnt,
                                                          const int32_t *__restrict__ rev_list,
@@ -1165,11 +1176,17 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
             // reverse shuffle + ReLU of the layer below: dZ of layer l-1
             const void *hact = sb.hidden[l];
             const int64_t ubl = ctx->ub_front[l];
-            const int n_main = grid_1d(ctx, ubl * 64);      // one wave per row of the level
-            const dim3 grid(n_main + PULL_LONG_BLOCKS);
+            // one wave per row of the level, and no more workgroups than stay resident at once: the waves
+            // stride over the rows, and workgroups that had to queue behind the resident ones would run
+            // their whole share after them on a nearly empty chip
 #define GS_PULL(LPR, HH, OH)                                                                                     \
-    hipLaunchKernelGGL((k_pull_input_grad<LPR, HH, OH>), grid, dim3(256), 0, st, sb.gtmp, D, B.rev_ptr, B.rev_cnt, \
-                       B.rev_list, B.rev_long, hact, ml, S, (void *)sb.ghid[l], n_main)
+    do {                                                                                                         \
+        const int n_main = (int)std::min<int64_t>(grid_1d(ctx, ubl * 64),                                        \
+                                                  (int64_t)ctx->n_cu * resident_blocks(k_pull_input_grad<LPR, HH, OH>)); \
+        hipLaunchKernelGGL((k_pull_input_grad<LPR, HH, OH>), dim3(n_main + PULL_LONG_BLOCKS), dim3(256), 0, st,  \
+                           sb.gtmp, D, B.rev_ptr, B.rev_cnt, B.rev_list, B.rev_long, hact, ml, S,                \
+                           (void *)sb.ghid[l], n_main);                                                          \
+    } while (0)
 #define GS_PULL_W(HH, OH)                                                                                        \
     do {                                                                                                         \
         if (D / 4 <= 16) GS_PULL(16, HH, OH);                                                                    \
