@@ -627,10 +627,12 @@ def algorithmic_work(w, model, heads, rows, edges, mixed, row_bytes, ip_bytes, S
     L = w.n_layers
     work, extra = {}, {}
 
-    def add(label, kind, amount, own=0.0):
+    def add(label, kind, amount, own=0.0, io=0.0):
         work[label] = (kind, amount)
         if own:
             extra[label] = own
+        if io:      # a matrix product's operand and result bytes (its memory-side ceiling)
+            extra["io:" + label] = io
 
     add("gather_rows", "bytes", rows[0] * (2 * row_bytes + 4))
     add("gather_cached", "bytes", rows[0] * (2 * row_bytes + 8))
@@ -657,12 +659,18 @@ def algorithmic_work(w, model, heads, rows, edges, mixed, row_bytes, ip_bytes, S
     n_tab = 2 if S > 1 else 1
     for l in range(L):
         D, N, nd = w.dims[l], w.dims[l + 1], rows[l + 1]
-        add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N)
-        if l == L - 1:      # the fused top layer: forward, weight-gradient and input-gradient products (plain FMAs)
+        # operand bytes: activations and dZ below the top level in the storage type (dZ in bf16 only where
+        # its rows are whole 16-byte pieces), logits and input-gradient rows in float, the weights once
+        top = l == L - 1
+        e_out = 4 if top else es
+        e_dz = 4 if (top or es == 4 or N % 8) else 2
+        wbytes = 2 * D * N * es
+        add(f"linear_fwd.l{l}", "flops", 2.0 * nd * (2 * D) * N, io=nd * (2 * D * es + N * e_out) + wbytes)
+        if top:      # the fused top layer: forward, weight-gradient and input-gradient products (plain FMAs)
             add(f"top_fused.l{l}", "flops", 2.0 * nd * (2 * D) * N * 2 + 2.0 * nd * (2 * D + 1) * N)
-        add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N)
+        add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N, io=nd * (2 * D * es + N * e_dz))
         if l > 0:
-            add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D))
+            add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D), io=nd * (N * e_dz + 2 * D * 4) + wbytes)
             add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
         # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
         add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
@@ -867,6 +875,14 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
                 peak = FP32_MFMA_PEAK_TFLOPS
             out = {"kernel": label, "bound": "alu" if alu else "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
                    "traffic": traffic, "flops_per_launch": per_launch, "launch_ms": ms / max(cnt, 1)}
+            if "io:" + label in own_totals:
+                # the same launch against the memory side: operands read once, results written once
+                io = own_totals["io:" + label] / max(cnt, 1)
+                t_mem, t_mfma = io / (HBM_PEAK_GBS * 1e9), per_launch / (peak * 1e12)
+                out["memory_side"] = {"bytes_per_launch": io, "achieved": io / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": io / sec / 1e9 / HBM_PEAK_GBS,
+                                      "binding_ceiling": "hbm" if t_mem > t_mfma else "mfma",
+                                      "frac_of_binding_ceiling": max(t_mem, t_mfma) / sec}
         else:
             ach = per_launch / sec / 1e9
             out = {"kernel": label, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -382,6 +382,21 @@ struct GatBwdSrcArgs {
 // Reverse shuffle of the backward pass as a pull, one wave per row u of local_cat[l]: over the
 // destinations it fed (scatter side of the shuffle index) it sums alpha * dagg and d e_src; its own
 // destination (self entry), if it has one, contributes d e_dst.  Rows that fed nothing get zeros.
+// The entries of a row were filled through an atomic cursor, in no fixed order; they are taken in
+// ascending order of their codes (2 * destination, + 1 for an edge; distinct within a row), so the
+// sums do not depend on it: the wave sorts (code, place) pairs across its lanes, at most 64 at a
+// time; a longer row is taken in windows of ascending values whose upper ends bisection finds.
+__device__ __forceinline__ unsigned long long wave_sort_pairs(unsigned long long v, int p2) {
+    const int lane = threadIdx.x & 63;
+    for (int k = 2; k <= p2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const unsigned long long o = __shfl_xor(v, j);
+            v = (((lane & j) == 0) == ((lane & k) == 0)) ? (v < o ? v : o) : (v > o ? v : o);
+        }
+    }
+    return v;
+}
+
 template <int VW, int NV>
 __global__ __launch_bounds__(256) void k_gat_bwd_src(GatBwdSrcArgs g, GatDims d, const GsLevelMeta *__restrict__ meta_lo, int S) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -389,32 +404,84 @@ __global__ __launch_bounds__(256) void k_gat_bwd_src(GatBwdSrcArgs g, GatDims d,
     const int K = d.K, F = d.F, HF = d.HF, ZW = d.ZW, lph = d.lph;
     const int k = lane / lph, sub = lane % lph;
     const bool ok = k < K;
+    constexpr unsigned long long PAD = ~0ull;
     for (int u = blockIdx.x * 4 + wave; u < n0; u += gridDim.x * 4) {
         const int p0 = g.rev_ptr[u], cnt = g.rev_cnt[u];
         float acc[NV * VW];
 #pragma unroll
         for (int c = 0; c < NV * VW; ++c) acc[c] = 0.f;
         float dsrc = 0.f, ddst = 0.f;
-        for (int x = 0; x < cnt; x += 4) {
-            float gv[4][NV * VW], a[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const bool in = x + q < cnt;
-                const int code = in ? g.rev_list[p0 + x + q] : 0;
-                const int i = code >> 1;
-                const int64_t slot = (code & 1) ? (int64_t)g.rev_eid[p0 + x + q] : d.self_base + i;
-                a[q] = 0.f;
-                if (in && ok) {
-                    a[q] = g.alpha[slot * K + k];
-                    dsrc += g.de[slot * K + k];
-                    if (!(code & 1)) ddst = g.der[(int64_t)i * K + k];
+        int lo = -1;
+        for (int taken = 0; taken < cnt;) {
+            int T = 0x7FFFFFFE;
+            if (cnt > 64) {
+                // largest T with at most 64 codes in (lo, T]
+                int a = lo + 1, b = 0x7FFFFFFE;
+                while (a < b) {
+                    const int mid = a + ((b - a + 1) >> 1);
+                    int inside = 0;
+                    for (int t = lane; t < cnt; t += 64) {
+                        const int code = g.rev_list[p0 + t];
+                        inside += (code > lo && code <= mid) ? 1 : 0;
+                    }
+                    for (int o = 32; o > 0; o >>= 1) inside += __shfl_xor(inside, o);
+                    if (inside <= 64) a = mid; else b = mid - 1;
                 }
-                load_cols<VW, NV>(g.gagg + (int64_t)i * HF + k * F, sub, lph, F, ok && in, gv[q]);
+                T = a;
             }
+            // the window's (code, place) pairs, one per lane, sorted by code
+            unsigned long long mine = PAD;
+            int m = 0;
+            if (cnt <= 64) {
+                if (lane < cnt) mine = ((unsigned long long)(uint32_t)g.rev_list[p0 + lane] << 32) | (uint32_t)(p0 + lane);
+                m = cnt;
+            } else {
+                for (int t0 = 0; t0 < cnt; t0 += 64) {
+                    const int t = t0 + lane;
+                    const int code = t < cnt ? g.rev_list[p0 + t] : 0;
+                    const bool in = t < cnt && code > lo && code <= T;
+                    const unsigned long long bal = __ballot(in);
+                    // hand the pair to lane `at` of the window (at most 64 in all)
+                    const unsigned long long pair = ((unsigned long long)(uint32_t)code << 32) | (uint32_t)(p0 + t);
+                    for (int src = 0; src < 64; ++src) {
+                        const bool has = (bal >> src) & 1ull;
+                        if (!has) continue;                     // uniform: bal is the same in every lane
+                        const int dst = m + __popcll(bal & ((1ull << src) - 1ull));
+                        const unsigned long long v = __shfl(pair, src);
+                        if (lane == dst) mine = v;
+                    }
+                    m += __popcll(bal);
+                }
+                m = min(m, 64);
+            }
+            int p2 = 1;
+            while (p2 < m) p2 <<= 1;
+            const unsigned long long sorted = p2 > 1 ? wave_sort_pairs(mine, p2) : mine;
+            for (int x = 0; x < m; x += 4) {
+                float gv[4][NV * VW], a[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q) {
+                    const bool in = x + q < m;
+                    const unsigned long long pr = __shfl(sorted, min(x + q, 63));
+                    const int code = in ? (int)(uint32_t)(pr >> 32) : 0;
+                    const int place = in ? (int)(uint32_t)pr : p0;
+                    const int i = code >> 1;
+                    const int64_t slot = (code & 1) ? (int64_t)g.rev_eid[place] : d.self_base + i;
+                    a[q] = 0.f;
+                    if (in && ok) {
+                        a[q] = g.alpha[slot * K + k];
+                        dsrc += g.de[slot * K + k];
+                        if (!(code & 1)) ddst = g.der[(int64_t)i * K + k];
+                    }
+                    load_cols<VW, NV>(g.gagg + (int64_t)i * HF + k * F, sub, lph, F, ok && in, gv[q]);
+                }
 #pragma unroll
-                for (int c = 0; c < NV * VW; ++c) acc[c] += a[q] * gv[q][c];
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int c = 0; c < NV * VW; ++c) acc[c] += a[q] * gv[q][c];
+            }
+            lo = T;
+            taken += max(m, 1);         // (a window is never empty; the loop ends whatever the row holds)
         }
         float *out = g.dzext + (int64_t)u * ZW;
         store_cols<VW, NV>(out + k * F, sub, lph, F, ok, acc);

@@ -141,6 +141,53 @@ def test_gat_forward_backward_within_tolerance(name):
         _check(_run(w, heads, _dev(), seed=seed, it=it), w.n_layers)
 
 
+def _hub_workloads():
+    from test_gpu_parity import _star_workload
+    return {
+        # a skewed graph without id permutation: the busiest rows feed hundreds of destinations (more than a
+        # wave sorts at once: windows of ascending codes)
+        "hubs": (lambda: workloads.custom(20000, 1200000, dims=[32, 64, 64, 16], fanouts=[12, 12, 12], batch=2000,
+                                          n_splits=4, abc=(0.7, 0.1, 0.1), permute_ids=False, name="gat-hubs"), [2, 2, 1]),
+        # every vertex aggregates from vertex 0: one row with thousands of entries
+        "huge-hub": (_star_workload, [2, 1]),
+    }
+
+
+@pytest.mark.parametrize("name", ["hubs", "huge-hub"])
+def test_gat_gradients_are_bit_reproducible(name):
+    """Three backward passes over the same batch give bit-equal gradients (the pull over the scatter
+    side of the shuffle index sums a row's entries in ascending code order, whatever order the atomic
+    cursor filled them in), and they are within tolerance of the oracle."""
+    from paper_2303_13775_amd import Context, GatParams
+    dev = _dev()
+    make, heads = _hub_workloads()[name]
+    w = make()
+    _check(_run(w, heads, dev, seed=9, it=2), w.n_layers)
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts, w.batch, gat_index=True)
+    wt, a_s, a_d, b = workloads.gat_weights(w.dims, heads, seed=w.seed)
+    params = GatParams(w.dims, heads, [t.to(dev) for t in wt], [t.to(dev) for t in a_s], [t.to(dev) for t in a_d],
+                       [t.to(dev) for t in b])
+    x0 = torch.empty((ctx.gsplit_max_rows(0), w.dims[0]), dtype=torch.float32, device=dev)
+    logits = torch.empty((w.batch, w.dims[-1]), device=dev)
+    glog = torch.randn((w.batch, w.dims[-1]), generator=torch.Generator().manual_seed(5)).to(dev)
+    outs = [[torch.empty_like(t, device=dev) for t in lst] for lst in (wt, a_s, a_d, b)]
+    runs = []
+    for _ in range(3):
+        ctx.gsplit_sample_split(w.targets(2).to(dev), 9, 2)
+        ctx.gsplit_gather_features(w.feat.to(dev), x0)
+        ctx.gsplit_gat_fwd(params, x0, logits)
+        ctx.gsplit_gat_bwd(params, x0, glog, *outs)
+        torch.cuda.synchronize()
+        runs.append([logits.clone()] + [t.clone() for lst in outs for t in lst])
+    longest = max(int(ctx.fetch_shuffle(l)["rev_cnt"].max()) for l in range(w.n_layers))
+    print(f"\n[gat reproducible {name}] longest reverse-index row {longest} entries", flush=True)
+    assert longest > 64
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert torch.equal(x, y), "results of two runs of the same batch differ in some bit"
+    ctx.close()
+
+
 def test_gat_edge_cases_isolated_targets_and_one_owner():
     dev = _dev()
     w = workloads.custom(500, 1500, dims=[8, 8, 4], fanouts=[3, 2], batch=16, n_splits=4, name="edge")
