@@ -47,7 +47,7 @@ def parse():
                     help="time strictly serial steps on one stream (default: sampling+gather of step i+1 "
                          "overlaps forward/backward of step i on a second stream)")
     ap.add_argument("--ahead", type=int, default=2, help="sampling streams (steps sampled ahead); used with --multi 1")
-    ap.add_argument("--multi", type=int, default=4,
+    ap.add_argument("--multi", type=int, default=8,
                     help="mini-batches sampled per gsplit_sample_split_multi call (sampling does not depend on the "
                          "weights: the batches of the next K steps go through one set of launches); 1 = one call per step")
     ap.add_argument("--sampler-blocks", type=int, default=2,

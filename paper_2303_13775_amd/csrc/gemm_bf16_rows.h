@@ -234,6 +234,8 @@ constexpr int GWH_B = 256;                 // columns of an operand tile (rows /
 constexpr int GWH_TILE4 = GWH_B * 8;       // 16-byte words of an operand tile: 2048 (32 KiB)
 constexpr int GWH_NT = 1024;               // threads of a workgroup
 constexpr int GWH_ROWS_MIN = 1024;
+constexpr int GWH_MIN_ROWS = 131072;       // levels with fewer rows leave too few chunks of that size: the tiled kernel takes them
+                                           // (default; the environment variable GSPLIT_GRADW_STREAM_ROWS overrides it)
 
 __device__ __forceinline__ int gwh_word(int c, int kg) {
     return kg * GWH_B + ((c & ~15) | ((c & 15) ^ ((c >> 4) & 3)));
@@ -242,9 +244,10 @@ __device__ __forceinline__ int gwh_word(int c, int kg) {
 __global__ __launch_bounds__(GWH_NT) void k_grad_w_hb(const uint16_t *__restrict__ X, int M2,
                                                       const uint16_t *__restrict__ dZ, int N, float *__restrict__ part,
                                                       int nchunk, int rows_min, int tiles_m, int tiles_n,
-                                                      const GsLevelMeta *__restrict__ meta_up, int S) {
+                                                      const GsLevelMeta *__restrict__ meta_up, int S, int take_from) {
     __shared__ __attribute__((aligned(16))) uint4 sA0[GWH_TILE4], sB0[GWH_TILE4], sA1[GWH_TILE4], sB1[GWH_TILE4];
     const int n1 = meta_up->front_off[S];
+    if (n1 < take_from) return;                          // a smaller level is the tiled kernel's
     const int kchunk = grad_w_chunk_rows(n1, nchunk, rows_min);
     const int tiles = tiles_m * tiles_n;
     const int xcd = blockIdx.x & 7, jb = blockIdx.x >> 3;

@@ -86,7 +86,8 @@ struct GsSageBuf {             // activations kept between forward and backward
     uint16_t *wtrans[GS_MAXL] = {nullptr};      // bf16 [N x 2D] transposed stacked weights
     float   *gw_part[GS_MAXL] = {nullptr};      // per-chunk partial weight gradients
     int      nchunk[GS_MAXL] = {0};             // slabs of gw_part (multiple of 8)
-    int      rows_min[GS_MAXL] = {0};           // fewest rows of a split-K chunk
+    int      stream_nchunk[GS_MAXL] = {0};      // chunks of the streaming weight-gradient kernel
+    int      stream_rows = 0;                   // rows of a level from which that kernel takes the weight gradients
     bool     gw_stream[GS_MAXL] = {false};      // the layer's weight gradients take the streaming bf16 kernel
     int      top_chunks = 0;                    // workgroups (= slabs) of the fused top-layer kernel
     float   *glog = nullptr;                    // [n_targets x classes] loss gradient of gsplit_sage_step

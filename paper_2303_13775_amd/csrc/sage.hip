@@ -7,6 +7,7 @@
 //
 // Dense products run on the matrix cores: v_mfma_f32_32x32x2_f32 for fp32 storage.
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 #include "gsplit_internal.h"
@@ -189,11 +190,16 @@ struct GradReduce {
     const float *part[GS_MAXL]; float *gws[GS_MAXL]; float *gwn[GS_MAXL]; float *gb[GS_MAXL];
     int D[GS_MAXL]; int N[GS_MAXL]; int nchunk[GS_MAXL]; int rows_min[GS_MAXL];
     int fixed_chunks[GS_MAXL];      // > 0: the layer's slabs were written by that many workgroups, all of them
+    // a level of at least stream_rows rows (> 0) had its slabs written by the streaming bf16 kernel,
+    // whose chunks follow (stream_nchunk, stream_rows_min)
+    int stream_rows[GS_MAXL]; int stream_nchunk[GS_MAXL]; int stream_rows_min[GS_MAXL];
 };
 __global__ __launch_bounds__(256) void k_reduce_grads(GradReduce g, const GsLevelMeta *__restrict__ meta, int S) {
     const int l = blockIdx.y;
     const int n1 = meta[l + 1].front_off[S];
-    const int kchunk = grad_w_chunk_rows(n1, g.nchunk[l], g.rows_min[l]);
+    const bool streamed = g.stream_rows[l] > 0 && n1 >= g.stream_rows[l];
+    const int kchunk = streamed ? grad_w_chunk_rows(n1, g.stream_nchunk[l], g.stream_rows_min[l])
+                                : grad_w_chunk_rows(n1, g.nchunk[l], g.rows_min[l]);
     const int chunks = g.fixed_chunks[l] > 0 ? g.fixed_chunks[l] : (n1 + kchunk - 1) / kchunk;
     const int D = g.D[l], N = g.N[l];
     const int64_t words = (int64_t)(2 * D + 1) * N;
@@ -852,15 +858,23 @@ int ensure_buffers(gsplit_ctx *ctx, const gsplit_sage_params *p) {
         const int m_rows = 2 * p->dims[l] + (p->dtype == GSPLIT_BF16 ? 1 : 0);    // bf16: plus the row of ones
         const int tiles = (int)(gs_ceil_div(m_rows, TileMid::BM) * gs_ceil_div(p->dims[l + 1], TileMid::BN));
         int64_t chunks = gs_ceil_div(std::max<int64_t>(8, (int64_t)ctx->n_cu * 3 / tiles), 8) * 8;
-        sb.rows_min[l] = GRAD_W_ROWS_MIN;
-        // a large bf16 level below the top one: one workgroup per compute unit, each a whole 256 x 256 block
+        sb.nchunk[l] = (int)chunks;
+        // a bf16 level below the top one that can reach GWH_MIN_ROWS rows: when it does (decided on the
+        // device), one workgroup per compute unit forms a whole 256 x 256 block over its chunk of rows
+        if (l == 0) {
+            sb.stream_rows = GWH_MIN_ROWS;
+            if (const char *e = std::getenv("GSPLIT_GRADW_STREAM_ROWS")) {
+                const long v = std::strtol(e, nullptr, 10);
+                if (v >= 64 && v <= (1l << 30)) sb.stream_rows = (int)v;
+            }
+        }
         sb.gw_stream[l] = grad_w_streams(p, l, L, ctx->ub_front[l + 1]);
+        sb.stream_nchunk[l] = 0;
         if (sb.gw_stream[l]) {
             const int big = (int)(gs_ceil_div(2 * p->dims[l], GWH_B) * gs_ceil_div(p->dims[l + 1], GWH_B));
-            chunks = std::max(8, ctx->n_cu / big / 8 * 8);
-            sb.rows_min[l] = GWH_ROWS_MIN;
+            sb.stream_nchunk[l] = std::max(8, ctx->n_cu / big / 8 * 8);
+            chunks = std::max<int64_t>(chunks, sb.stream_nchunk[l]);
         }
-        sb.nchunk[l] = (int)chunks;
         // the fused top-layer kernel writes one slab per workgroup: TOP_R rows each, at most 256 of them
         int64_t slabs = chunks;
         if (l == L - 1) {
@@ -1132,18 +1146,21 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
                 const int tm = (int)gs_ceil_div(ew.rows, GBM), tn = (int)gs_ceil_div(ew.N, GBN);
                 dim3 grid((unsigned)(sb.nchunk[l] * tm * tn));
                 if (sb.gw_stream[l]) {
+                    // two launches, one of which finds the level on its side of GWH_MIN_ROWS and works
                     const int bm = (int)gs_ceil_div(2 * D, GWH_B), bn = (int)gs_ceil_div(N, GWH_B);
-                    hipLaunchKernelGGL(k_grad_w_hb, dim3((unsigned)(sb.nchunk[l] * bm * bn)), dim3(GWH_NT), 0, st, inh.p, 2 * D,
-                                       dzh.p, N, sb.gw_part[l], sb.nchunk[l], sb.rows_min[l], bm, bn, mu, S);
-                } else if (dz_h)
+                    hipLaunchKernelGGL(k_grad_w_hb, dim3((unsigned)(sb.stream_nchunk[l] * bm * bn)), dim3(GWH_NT), 0, st, inh.p,
+                                       2 * D, dzh.p, N, sb.gw_part[l], sb.stream_nchunk[l], GWH_ROWS_MIN, bm, bn, mu, S,
+                                       sb.stream_rows);
+                }
+                if (dz_h)
                     hipLaunchKernelGGL((k_sage_grad_w_h<PatchDzH, MatRowsH>), grid, dim3(GNT), 0, st, inh, dzh, ew,
-                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S, sb.gw_stream[l] ? sb.stream_rows : 0);
                 else if (vdz)
                     hipLaunchKernelGGL((k_sage_grad_w_h<PatchDz<4>, MatRows>), grid, dim3(GNT), 0, st, inh, dz, ew,
-                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S, 0);
                 else
                     hipLaunchKernelGGL((k_sage_grad_w_h<PatchDz<1>, MatRows>), grid, dim3(GNT), 0, st, inh, dz, ew,
-                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S);
+                                       sb.nchunk[l], GRAD_W_ROWS_MIN, tm, tn, mu, S, 0);
             } else {
                 launch_grad_w(st, sb.nchunk[l], vin, vdz, in, dz, ew, mu, S);
             }
@@ -1212,7 +1229,9 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
         int64_t wmax = 1;
         for (int l = 0; l < L; ++l) {
             gr.part[l] = sb.gw_part[l]; gr.gws[l] = d_gw_self[l]; gr.gwn[l] = d_gw_neigh[l]; gr.gb[l] = d_gbias[l];
-            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = sb.rows_min[l];
+            gr.D[l] = p->dims[l]; gr.N[l] = p->dims[l + 1]; gr.nchunk[l] = sb.nchunk[l]; gr.rows_min[l] = GRAD_W_ROWS_MIN;
+            gr.stream_rows[l] = sb.gw_stream[l] ? sb.stream_rows : 0; gr.stream_nchunk[l] = sb.stream_nchunk[l];
+            gr.stream_rows_min[l] = GWH_ROWS_MIN;
             gr.fixed_chunks[l] = l == L - 1 ? top_chunks : 0;
             wmax = std::max<int64_t>(wmax, (int64_t)(2 * p->dims[l] + 1) * p->dims[l + 1]);
         }

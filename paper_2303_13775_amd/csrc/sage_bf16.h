@@ -465,8 +465,9 @@ struct PatchX {
 template <class PDZ, class DZ>
 __global__ __launch_bounds__(GNT) void k_sage_grad_w_h(MatRowsOnesH a, DZ dz, EpiGradW epi, int nchunk,
                                                        int rows_min, int tiles_m, int tiles_n,
-                                                       const GsLevelMeta *__restrict__ meta_up, int S) {
+                                                       const GsLevelMeta *__restrict__ meta_up, int S, int leave_from) {
     const int n1 = meta_up->front_off[S];
+    if (leave_from > 0 && n1 >= leave_from) return;      // a level this large is the streaming kernel's
     const int kchunk = grad_w_chunk_rows(n1, nchunk, rows_min);
     const int tiles = tiles_m * tiles_n;
     const int xcd = blockIdx.x & 7, jb = blockIdx.x >> 3;
