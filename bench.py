@@ -796,6 +796,38 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         serial_multi = {"value": steps / dt_multi, "ms_per_step": dt_multi / steps * 1e3, "batches_per_sampling_call": K,
                         "schedule": f"one stream; the mini-batches of the next {K} steps are sampled and split by one "
                                     f"gsplit_sample_split_multi call, then loaded and trained one after the other"}
+        # the sampling kernels of a grouped call, timed by the library on the first context of the group:
+        # one launch then carries the K mini-batches' work
+        n_g = max(1, min(stage_iters, steps) // K)
+        rs[0].ctx.gsplit_timing_enable(True)
+        rs[0].ctx.gsplit_timing_read()
+        grouped_work = {}
+        for gi in range(n_g):
+            g0 = warmup + gi * K
+            n = min(K, n_total - g0)
+            gsplit_sample_split_multi([x.ctx for x in rs[:n]], [targets[g0 + b] for b in range(n)], r.seed,
+                                      [g0 + b for b in range(n)])
+            for x in rs[:n]:
+                nl, nm, ne, _ = x.ctx.gsplit_batch_sizes()
+                wk, _own = algorithmic_work(w, model, getattr(r, "heads", None), [sum(v) for v in nl], [sum(v) for v in ne],
+                                            [sum(v) for v in nm], w.feat.shape[1] * w.feat.element_size(),
+                                            w.indptr.element_size(), w.n_splits)
+                for kk, (kind, amount) in wk.items():
+                    if kk.startswith(("sample_layer", "mixed_buckets", "shuffle_index")):
+                        grouped_work[kk] = grouped_work.get(kk, 0.0) + amount
+        torch.cuda.synchronize()
+        gt = rs[0].ctx.gsplit_timing_read()
+        rs[0].ctx.gsplit_timing_enable(False)
+        cand = {kk: v for kk, v in gt.items() if kk in grouped_work and v[0] > 0}
+        if cand:
+            big = max(cand, key=lambda kk: cand[kk][1])
+            cnt, ms = cand[big]
+            ach = grouped_work[big] / (ms * 1e-3) / 1e9
+            serial_multi["roofline_sampling_grouped"] = {
+                "kernel": big, "batches_per_launch": K, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "bytes_per_launch": grouped_work[big] / cnt, "launch_ms": ms / cnt}
+            serial_multi["sampling_kernel_us_per_batch"] = {kk: round(v[1] / v[0] / K * 1e3, 2) for kk, v in
+                                                            sorted(cand.items(), key=lambda kv: -kv[1][1])}
         for x in rs[1:]:
             x.ctx.close()
         del rs

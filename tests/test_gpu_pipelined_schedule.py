@@ -1,5 +1,5 @@
 """The schedules bench.py times, checked as they are timed, on the benchmark workload at its full
-size: (groups, the default) two groups of four batch slots, the mini-batches of a group sampled by
+size: (groups, the default) two groups of eight batch slots, the mini-batches of a group sampled by
 one gsplit_sample_split_multi call on a sampling stream while the training stream works through
 the group before; (streams, `--multi 1`) three batch slots, two sampling streams and a training
 stream.  Contexts whose sampling kernels may occupy two workgroups per compute unit, two host
@@ -25,11 +25,11 @@ def test_pipelined_schedule_leaves_the_oracles_results_in_every_slot(model, sche
     assert torch.cuda.is_available(), "needs the MI355X"
     dev = torch.device("cuda:0")
     w = workloads.medium(device=dev)
-    n_steps = 11                                    # not a multiple of the slots, the last group is partial
+    n_steps = 19 if schedule == "groups" else 11     # not a multiple of the slots, the last group is partial
     targets = [w.targets(i) for i in range(n_steps)]
     torch.cuda.synchronize()
     if schedule == "groups":
-        pipe = bench.PipelinedGroups(w, dev, 4, model, 4, 2)
+        pipe = bench.PipelinedGroups(w, dev, 8, model, 4, 2)
         slot_of = lambda i: pipe.slot_of_step(i, 0)
     else:
         pipe = bench.Pipelined(w, dev, 2, model, 4, 2)
