@@ -45,14 +45,14 @@ static void free_all(gsplit_ctx *ctx) {
     ctx->sample_done = nullptr;
 }
 
-// Direct tables take 12 bytes per key of the whole key space; the hashed ones 12 bytes per entry of a
+// Direct tables take 8 bytes per key of the whole key space; the hashed ones 8 bytes per entry of a
 // table sized for the largest layer.  Measured: direct tables shorten the sampler of a layer (one atomic
 // per insert, no probing) as long as their key space stays inside the memory-side cache (256 MB); over a
 // key space of GBs every lookup of the later passes misses it, and the hashed tables, which are
 // compact, win.
 static bool direct_tables_pay(int64_t keys_m, int64_t tab_cap) {
     (void)tab_cap;
-    return keys_m * 12 <= (192ll << 20);
+    return keys_m * 8 <= (128ll << 20);
 }
 
 static int64_t pow2_at_least(int64_t x) {
@@ -156,11 +156,11 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         if (ctx->direct_tables) {
             const int64_t keys = t == &ctx->tab_mixed ? keys_m : keys_l;
             A((void **)&t->pos, sizeof(unsigned long long) * keys, "direct table entries");
-            A((void **)&t->row, sizeof(int32_t) * keys, "direct table rows");
         } else {
             A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
-            A((void **)&t->row, sizeof(int32_t) * tab_cap, "table rows");
         }
+        // rows are handed out by position in the slot stream, not by table entry
+        A((void **)&t->row, sizeof(int32_t) * max_items, "rows by position");
     }
     A((void **)&ctx->ent_mixed, sizeof(int32_t) * max_items, "ent_mixed");
     A((void **)&ctx->ent_local, sizeof(int32_t) * max_items, "ent_local");

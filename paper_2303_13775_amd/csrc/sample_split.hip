@@ -641,7 +641,7 @@ struct PartLayer {
     static constexpr int NK = PART_NK;
     GsTable tab_mixed, tab_local;
     const int32_t *front; const int32_t *nbr; const uint8_t *pmap;
-    const int32_t *ent_mixed; const int32_t *ent_local; uint32_t *cls; int32_t *mixed_ent;
+    int32_t *ent_mixed; int32_t *ent_local; uint32_t *cls; int32_t *mixed_ent;
     int32_t *mixed; int32_t *blk_indptr; int32_t *recv; int32_t *front_lo; int32_t *rev_cnt;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int rev;
     RevUp up;
@@ -649,19 +649,34 @@ struct PartLayer {
     __device__ int n() const { return n1() * fan; }
     // classes s and 8 + t and 17 + t exist for the splits the context has, class 16 always
     __device__ bool used(int k) const { return k < 8 ? k < S : k < 16 ? k - 8 < S : k == 16 || k - 17 < S; }
+    // From here on an element's ent_mixed / ent_local no longer name table entries but the position
+    // of the first occurrence of its key (what the entries hold): the rows are handed out by
+    // position (tab.row is indexed by it), so the later passes read two small dense arrays instead
+    // of following every element into the tables again.
     __device__ unsigned classify(int g) const {
-        const int h = ent_mixed[n1() + g];
-        unsigned m = h < -1 ? 1u << 16 : 0u;      // h < -1: a valid slot the sampler saw behind another
+        const int at = n1() + g;
+        const int h = ent_mixed[at];
+        unsigned m = 0u;
+        if (h < -1) {       // a valid slot the sampler saw behind another occurrence of its key (entry -2 - h): no winner
+            m = 1u << 16;
+            ent_mixed[at] = (int32_t)table_pos(tab_mixed, -2 - h);
+        }
         if (h >= 0) {
             const int32_t id = nbr[g];
-            const uint32_t pos = (uint32_t)(n1() + g);
+            const uint32_t pos = (uint32_t)at;
             m = 1u << 16;
-            if (table_pos(tab_mixed, h) == pos) {
+            const uint32_t first = table_pos(tab_mixed, h);
+            ent_mixed[at] = (int32_t)first;
+            if (first == pos) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
                 const unsigned t = pmap[id] & (GS_MAXS - 1);
                 m |= (1u << s) | (1u << (8 + t));
-                const int hl = ent_local[n1() + g];
-                if (hl >= 0 && table_pos(tab_local, hl) == pos) m |= 1u << (17 + t);
+                const int hl = ent_local[at];
+                if (hl >= 0) {
+                    const uint32_t lfirst = table_pos(tab_local, hl);
+                    ent_local[at] = (int32_t)lfirst;
+                    if (lfirst == pos) m |= 1u << (17 + t);
+                }
             }
         }
         cls[g] = m;
@@ -711,15 +726,14 @@ struct PartLayer {
         const int s = __ffs(sm) - 1;
         const int t = __ffs((m >> 8) & 0xFFu) - 1;
         const int32_t id = nbr[g];
-        const int h = ent_mixed[n1() + g];
-        const int hl = ent_local[n1() + g];
+        const int at = n1() + g;               // a winner: the first occurrence of its (vertex, split) key
         mixed[rk[s]] = id;
-        tab_mixed.row[h] = rk[s] - o.a[s];
-        mixed_ent[rk[s]] = hl;
+        tab_mixed.row[at] = rk[s] - o.a[s];
+        mixed_ent[rk[s]] = ent_local[at];      // where the vertex first occurs in the whole stream (-1: no entry)
         recv[rk[8 + t]] = id;
-        if ((m >> 17) & 0xFFu) {       // implies hl >= 0
+        if ((m >> 17) & 0xFFu) {               // that place is this one
             front_lo[rk[17 + t]] = id;
-            tab_local.row[hl] = rk[17 + t];
+            tab_local.row[at] = rk[17 + t];
         }
     }
     // scatter pass extras: destination vertices are rows 0 .. n_dst-1 of their split's mixed
@@ -741,13 +755,14 @@ struct PartLayer {
         const int s = split_of(meta_up->front_off, S, i);
         const int loc = i - meta_up->front_off[s];
         const int32_t id = front[i];
-        const int h = ent_mixed[i], hl = ent_local[i];
+        const int hl = ent_local[i];
         const int j = o.a[s] + loc, rowp = o.c[s] + loc;
+        // a destination vertex holds the smallest position of both of its keys: position i
         mixed[j] = id;
-        if (h >= 0) tab_mixed.row[h] = loc;
-        mixed_ent[j] = hl;
+        tab_mixed.row[i] = loc;
+        mixed_ent[j] = hl >= 0 ? i : -1;
         front_lo[rowp] = id;
-        if (hl >= 0) tab_local.row[hl] = rowp;
+        tab_local.row[i] = rowp;
     }
     // count pass side work: segments of the reverse index of the layer above
     __device__ int64_t n_side() const { return up.on ? n1() : 0; }
@@ -787,25 +802,24 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
         if (x < n_mixed) {
-            const int h = mixed_ent[x];
-            src_row[x] = h >= 0 ? tab_local.row[h] : -1;
+            const int p = mixed_ent[x];
+            src_row[x] = p >= 0 ? tab_local.row[p] : -1;
         } else if (x < n_mixed + n1) {
             const int i = (int)(x - n_mixed);
             const int h = ent_local[i];
-            const int r = h >= 0 ? tab_local.row[h] : -1;
+            const int r = h >= 0 ? tab_local.row[i] : -1;
             self_row[i] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
 
         } else {
             const int64_t g = x - n_mixed - n1;
-            int h = ent_mixed[n1 + g];
-            if (h == -1) continue;
-            if (h < -1) h = -2 - h;
+            const int first = ent_mixed[n1 + g];     // where the slot's key first occurs (left by the count pass)
+            if (first < 0) continue;
             const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
             const int s = split_of(meta_up->front_off, S, i);
-            const int mrow = tab_mixed.row[h];
-            const int hl = mixed_ent[meta_lo->mixed_off[s] + mrow];
-            const int r = hl >= 0 ? tab_local.row[hl] : -1;
+            const int mrow = tab_mixed.row[first];
+            const int pl = mixed_ent[meta_lo->mixed_off[s] + mrow];
+            const int r = pl >= 0 ? tab_local.row[pl] : -1;
             blk_src[blk_indptr[i] + q] = mrow;          // edges[l] as rows of the split's mixed frontier
             edge_row[blk_indptr[i] + q] = r;
             if (rev_cnt && r >= 0) atomicAdd(&rev_cnt[r], 1);
@@ -1200,9 +1214,9 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     size_t need = 0;
     auto carve = [&](size_t bytes) { const size_t at = need; need += (bytes + 255) & ~(size_t)255; return at; };
     const size_t o_meta = carve(sizeof(GsLevelMeta) * (L + 1));
-    const size_t o_mslot = carve(sizeof(unsigned long long) * tab_cap), o_mrow = carve(sizeof(int32_t) * tab_cap);
+    const size_t o_mslot = carve(sizeof(unsigned long long) * tab_cap), o_mrow = carve(sizeof(int32_t) * max_items);
     const size_t o_lslot = S == 1 ? o_mslot : carve(sizeof(unsigned long long) * tab_cap);
-    const size_t o_lrow = S == 1 ? o_mrow : carve(sizeof(int32_t) * tab_cap);
+    const size_t o_lrow = S == 1 ? o_mrow : carve(sizeof(int32_t) * max_items);
     const size_t o_em = carve(sizeof(int32_t) * max_items), o_el = carve(sizeof(int32_t) * max_items);
     const size_t o_me = carve(sizeof(int32_t) * max_items), o_cls = carve(sizeof(uint32_t) * max_items);
     const size_t o_self = carve(sizeof(int32_t) * max_items), o_edge = carve(sizeof(int32_t) * max_items);
