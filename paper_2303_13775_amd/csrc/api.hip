@@ -144,7 +144,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     }
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
     // one split: the (vertex, split) key is the vertex key, and one table serves as both
-    const int64_t keys_m = g->n_vertices * (int64_t)g->n_splits, keys_l = g->n_vertices;
+    const int64_t keys_m = g->n_vertices * (int64_t)g->n_splits;
     ctx->direct_tables = c->table_mode == 2 || (c->table_mode == 0 && direct_tables_pay(keys_m, tab_cap));
     if (ctx->direct_tables && keys_m >= (1ll << 30)) ctx->direct_tables = false;     // entry indices are 31-bit
     for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
@@ -154,8 +154,9 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
         }
         t->slot = nullptr; t->row = nullptr; t->pos = nullptr;
         if (ctx->direct_tables) {
-            const int64_t keys = t == &ctx->tab_mixed ? keys_m : keys_l;
-            A((void **)&t->pos, sizeof(unsigned long long) * keys, "direct table entries");
+            // (vertex, split) keys only: the entries of a vertex lie side by side, which answers the
+            // questions a table keyed by the vertex alone would
+            if (t == &ctx->tab_mixed) A((void **)&t->pos, sizeof(unsigned long long) * keys_m, "direct table entries");
         } else {
             A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
         }
@@ -173,8 +174,9 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     // every table entry empty (all bits set): a batch starts on clean tables, and leaves them so
     for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
         if (rc != GSPLIT_OK) break;
-        const int64_t keys = t == &ctx->tab_mixed ? keys_m : keys_l;
-        const hipError_t e = ctx->direct_tables ? hipMemset(t->pos, 0xFF, sizeof(unsigned long long) * keys)
+        if (ctx->direct_tables && !t->pos) continue;
+        if (t == &ctx->tab_local && t->slot == ctx->tab_mixed.slot && t->pos == ctx->tab_mixed.pos) continue;   // one split: one table
+        const hipError_t e = ctx->direct_tables ? hipMemset(t->pos, 0xFF, sizeof(unsigned long long) * keys_m)
                                                 : hipMemset(t->slot, 0xFF, sizeof(unsigned long long) * tab_cap);
         if (e != hipSuccess) rc = gs_fail(ctx, GSPLIT_EHIP, "gsplit_create: hipMemset failed");
     }

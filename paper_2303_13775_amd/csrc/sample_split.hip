@@ -178,6 +178,9 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
     GsLevelMeta *meta_lo = a.meta_lo;
     const GsLevelMeta *__restrict__ meta_up = a.meta_up;
     const GsTable tab = a.tab, tab_local = a.tab_local;
+    // direct tables with several splits: the (vertex, split) entries of a vertex are neighbours in
+    // memory, the partition reads them together, and there is no table keyed by the vertex alone
+    const bool no_local = !tab_local.pos && !tab_local.slot;
     int32_t *__restrict__ ent_mixed = a.ent_mixed;
     int32_t *__restrict__ ent_local = a.ent_local;
     int32_t *__restrict__ nbr = a.nbr;
@@ -254,8 +257,8 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                     const int hm = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
                                                 &meta_lo->error);
                     ent_mixed[row] = hm;
-                    ent_local[row] = S == 1 ? hm : table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row,
-                                                                &meta_lo->error);
+                    ent_local[row] = (S == 1 || no_local) ? hm : table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row,
+                                                                              &meta_lo->error);
                 }
             }
             key_v = val;
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 // and a vertex has the same row in the mixed and in the next local frontier)
                 hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind,
                                   claim_first);
-                if (S == 1) hl = hm;
+                if (S == 1 || no_local) hl = hm;
                 else if (!behind)
                     hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error, nullptr, claim_first);
             }
@@ -645,6 +648,7 @@ struct PartLayer {
     int32_t *mixed; int32_t *blk_indptr; int32_t *recv; int32_t *front_lo; int32_t *rev_cnt;
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int rev;
     RevUp up;
+    int layer;
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return n1() * fan; }
     // classes s and 8 + t and 17 + t exist for the splits the context has, class 16 always
@@ -673,7 +677,20 @@ struct PartLayer {
                 m |= (1u << s) | (1u << (8 + t));
                 const int hl = ent_local[at];
                 if (hl >= 0) {
-                    const uint32_t lfirst = table_pos(tab_local, hl);
+                    uint32_t lfirst = pos;
+                    if (!tab_local.pos && !tab_local.slot) {
+                        // no table of the vertices: the first occurrence in the whole stream is the first of
+                        // the vertex's occurrences in the single splits, whose entries lie side by side
+                        // (entries of this layer carry its stamp)
+                        const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
+                        const unsigned long long *e = tab_mixed.pos + (size_t)(uint32_t)id * (uint32_t)S;
+                        for (int ss = 0; ss < S; ++ss) {
+                            const unsigned long long v = e[ss];
+                            if ((uint32_t)(v >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v);
+                        }
+                    } else {
+                        lfirst = table_pos(tab_local, hl);
+                    }
                     ent_local[at] = (int32_t)lfirst;
                     if (lfirst == pos) m |= 1u << (17 + t);
                 }
@@ -831,7 +848,7 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
     // the bottom layer: cleared for the top layer of the next batch instead (top_cap entries cover
     // max_targets targets), so that the batch's first kernel, a single workgroup for a small batch,
     // does not have to
-    if (!tab_local.pos && (fan_next > 0 || top_cap > 0)) {
+    if (!tab_mixed.pos && (fan_next > 0 || top_cap > 0)) {
         const int64_t nr = fan_next > 0 ? 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next)) : top_cap;
         for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < 2 * nr;
              x += (int64_t)gridDim.x * blockDim.x) {
@@ -1058,7 +1075,7 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
             PartLayer pa{c->tab_mixed, c->tab_local, c->front[l + 1], B.nbr, c->graph.d_pmap,
                          c->ent_mixed, c->ent_local, c->cls, c->mixed_ent,
                          B.mixed, B.blk_indptr, B.recv, c->front[l], B.rev_cnt,
-                         ml, mu, S, fan, l >= c->rev_from ? 1 : 0, RevUp{}};
+                         ml, mu, S, fan, l >= c->rev_from ? 1 : 0, RevUp{}, l};
             if (l + 1 < L && l + 1 >= c->rev_from) {
                 const GsLayerBuf &U = c->layer[l + 1];
                 pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
