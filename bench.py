@@ -671,7 +671,10 @@ def algorithmic_work(w, model, heads, rows, edges, mixed, row_bytes, ip_bytes, S
         add(f"grad_w.l{l}", "flops", 2.0 * nd * (2 * D + 1) * N, io=nd * (2 * D * es + N * e_dz))
         if l > 0:
             add(f"grad_in.l{l}", "flops", 2.0 * nd * N * (2 * D), io=nd * (N * e_dz + 2 * D * 4) + wbytes)
-            add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + 8 * D))
+            # float input-gradient rows per entry; per row of the level the stored activation (ReLU mask) read and
+            # dZ written, both in the storage type (dZ in bf16 only where its rows are whole 16-byte pieces)
+            e_dzl = 2 if (es == 2 and D % 8 == 0) else 4
+            add(f"pull_input_grad.l{l}", "bytes", (nd + edges[l]) * (4 + 4 * D) + rows[l] * (8 + (es + e_dzl) * D))
         # no-reuse model: one source row per edge, one self row and one [self | mean] row per destination
         add(f"assemble_input.l{l}", "bytes", edges[l] * (4 + es * D) + nd * (4 + es * D) + nd * 2 * es * D)
         items = nd + edges[l]
