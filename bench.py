@@ -992,8 +992,8 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
 
 
 def extra_configs(a, dev, say):
-    """The other configurations, each timed serially on one stream with its own rooflines: large in
-    float32 and in bf16, skewed, and the split sweep on the large graph (1, 2, 4, 8 logical splits;
+    """The other configurations, each timed serially on one stream with its own rooflines: medium in
+    bf16, large in float32 and in bf16, skewed, and the split sweep on the large graph (1, 2, 4, 8 logical splits;
     every stage also as a ratio to one split).  A configuration that fails reports its error and the
     others still run."""
     import torch
@@ -1020,6 +1020,14 @@ def extra_configs(a, dev, say):
         torch.cuda.synchronize()
         torch.cuda.empty_cache()
 
+    try:
+        w = workloads.medium(device=dev, n_splits=4)
+        w.feat = w.feat.to(torch.bfloat16)
+        run("medium_bf16", w, "medium", "bf16", steps=100, warmup=10, multi=a.multi)
+        del w
+    except Exception as e:                         # noqa: BLE001
+        out["medium_bf16_error"] = f"{type(e).__name__}: {e}"
+    torch.cuda.empty_cache()
     try:
         w = workloads.large(device=dev, n_splits=4, feat_dtype=torch.float32, progress=say)
         run("large_f32", w, "large", "f32", multi=a.multi)
