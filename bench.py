@@ -972,6 +972,25 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
     if model == "sage":
         out["roofline_linear"] = [roofline_of(k) for k in sorted(per_step_us)
                                   if k.startswith(("linear_fwd", "grad_w", "grad_in"))]
+        # mean aggregation (the input assembly of every layer) and its mirror in the backward pass (the pull):
+        # against the no-reuse model (one source row per edge), with the perfect-reuse floor beside it
+        # (every row of the level below read once)
+        agg = []
+        for k in sorted(per_step_us):
+            if not k.startswith(("assemble_input", "pull_input_grad")):
+                continue
+            ro = roofline_of(k)
+            l = int(k.rsplit(".l", 1)[1])
+            D, es = w.dims[l], w.feat.element_size()
+            nd, n_lo = rows[l + 1], rows[l]
+            if k.startswith("assemble_input"):
+                floor_bytes = n_lo * es * D + nd * (4 + 2 * es * D) + edges[l] * 4
+            else:
+                floor_bytes = nd * 2 * D * 4 + (nd + edges[l]) * 4 + n_lo * (8 + 2 * es * D)
+            ro["perfect_reuse_floor_bytes"] = floor_bytes
+            ro["perfect_reuse_floor_us"] = floor_bytes / (HBM_PEAK_GBS * 1e9) * 1e6
+            agg.append(ro)
+        out["roofline_aggregation"] = agg
     if graph_check is not None:
         out["graph_replay_equals_eager"] = graph_check
     if cache:
