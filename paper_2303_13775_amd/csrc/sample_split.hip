@@ -659,38 +659,56 @@ struct PartLayer {
     // of following every element into the tables again.
     __device__ unsigned classify(int g) const {
         const int at = n1() + g;
+        // what the branches below may need is fetched side by side, the owner byte beside the table
+        // entries (read for a slot that turns out not to need it, too: the kernel is a chain of
+        // dependent accesses, and every level taken out of the chain shortens it)
         const int h = ent_mixed[at];
+        const int32_t id = nbr[g];                          // -1 in an empty slot
+        const int hl = ent_local[at];
+        const uint32_t idc = id >= 0 ? (uint32_t)id : 0u;
+        const unsigned t = pmap[idc] & (GS_MAXS - 1);
+        const uint32_t pos = (uint32_t)at;
         unsigned m = 0u;
+        if (!tab_local.pos && !tab_local.slot) {
+            // one direct table of (vertex, split) keys: the vertex's entries for the single splits lie side
+            // by side; the slot's own one tells where its key first occurs, the smallest of those that
+            // carry this layer's stamp where the vertex first occurs in the whole stream
+            if (h != -1) {
+                const int s = split_of(meta_up->front_off, S, g / fan);
+                const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
+                const unsigned long long *e = tab_mixed.pos + (size_t)idc * (uint32_t)S;
+                uint32_t first = pos, lfirst = pos;
+                for (int ss = 0; ss < S; ++ss) {
+                    const unsigned long long v = e[ss];
+                    if (ss == s) first = (uint32_t)v;
+                    if ((uint32_t)(v >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v);
+                }
+                m = 1u << 16;
+                ent_mixed[at] = (int32_t)first;
+                if (h >= 0 && first == pos) {
+                    m |= (1u << s) | (1u << (8 + t));
+                    if (hl >= 0) {
+                        ent_local[at] = (int32_t)lfirst;
+                        if (lfirst == pos) m |= 1u << (17 + t);
+                    }
+                }
+            }
+            cls[g] = m;
+            return m;
+        }
         if (h < -1) {       // a valid slot the sampler saw behind another occurrence of its key (entry -2 - h): no winner
             m = 1u << 16;
             ent_mixed[at] = (int32_t)table_pos(tab_mixed, -2 - h);
         }
         if (h >= 0) {
-            const int32_t id = nbr[g];
-            const uint32_t pos = (uint32_t)at;
             m = 1u << 16;
             const uint32_t first = table_pos(tab_mixed, h);
             ent_mixed[at] = (int32_t)first;
             if (first == pos) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
-                const unsigned t = pmap[id] & (GS_MAXS - 1);
                 m |= (1u << s) | (1u << (8 + t));
-                const int hl = ent_local[at];
                 if (hl >= 0) {
-                    uint32_t lfirst = pos;
-                    if (!tab_local.pos && !tab_local.slot) {
-                        // no table of the vertices: the first occurrence in the whole stream is the first of
-                        // the vertex's occurrences in the single splits, whose entries lie side by side
-                        // (entries of this layer carry its stamp)
-                        const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
-                        const unsigned long long *e = tab_mixed.pos + (size_t)(uint32_t)id * (uint32_t)S;
-                        for (int ss = 0; ss < S; ++ss) {
-                            const unsigned long long v = e[ss];
-                            if ((uint32_t)(v >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v);
-                        }
-                    } else {
-                        lfirst = table_pos(tab_local, hl);
-                    }
+                    const uint32_t lfirst = table_pos(tab_local, hl);
                     ent_local[at] = (int32_t)lfirst;
                     if (lfirst == pos) m |= 1u << (17 + t);
                 }
