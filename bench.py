@@ -302,6 +302,17 @@ class Pipelined:
             th.join()
 
 
+def load_group(rs):
+    """Loading step of a group of runners: one launch for all of them (the cached loading step, which
+    reads host memory, stays one call per batch)."""
+    if len(rs) == 1 or getattr(rs[0], "cached", False):
+        for r in rs:
+            r.load()
+        return
+    from paper_2303_13775_amd import gsplit_gather_features_multi
+    gsplit_gather_features_multi([r.ctx for r in rs], rs[0].w.feat, [r.x0 for r in rs])
+
+
 class PipelinedGroups:
     """The overlap schedule with sampling in groups: the mini-batches of the next K steps are sampled
     and split by one gsplit_sample_split_multi call (one set of launches for all K) and loaded on a
@@ -358,8 +369,7 @@ class PipelinedGroups:
                         self.s_sample.wait_event(self.free[g])
                         gsplit_sample_split_multi([r.ctx for r in rs], [targets[lo + b] for b in range(n)], rs[0].seed,
                                                   [lo + b for b in range(n)])
-                        for r in rs:
-                            r.load()
+                        load_group(rs)
                         self.ready[g].record(self.s_sample)
                     sampled.put(j)
             except BaseException as e:      # hand the failure to the training thread
@@ -785,8 +795,7 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
                 n = min(K, hi - g0)
                 gsplit_sample_split_multi([x.ctx for x in rs[:n]], [targets[g0 + b] for b in range(n)], r.seed,
                                           [g0 + b for b in range(n)])
-                for x in rs[:n]:
-                    x.load()
+                load_group(rs[:n])
                 for x in rs[:n]:
                     x.train()
 
@@ -798,7 +807,8 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         dt_multi = time.perf_counter() - t0
         serial_multi = {"value": steps / dt_multi, "ms_per_step": dt_multi / steps * 1e3, "batches_per_sampling_call": K,
                         "schedule": f"one stream; the mini-batches of the next {K} steps are sampled and split by one "
-                                    f"gsplit_sample_split_multi call, then loaded and trained one after the other"}
+                                    f"gsplit_sample_split_multi call and loaded by one gsplit_gather_features_multi call, "
+                                    f"then trained one after the other"}
         # the sampling kernels of a grouped call, timed by the library on the first context of the group:
         # one launch then carries the K mini-batches' work
         n_g = max(1, min(stage_iters, steps) // K)
@@ -810,17 +820,25 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
             n = min(K, n_total - g0)
             gsplit_sample_split_multi([x.ctx for x in rs[:n]], [targets[g0 + b] for b in range(n)], r.seed,
                                       [g0 + b for b in range(n)])
+            load_group(rs[:n])
             for x in rs[:n]:
                 nl, nm, ne, _ = x.ctx.gsplit_batch_sizes()
                 wk, _own = algorithmic_work(w, model, getattr(r, "heads", None), [sum(v) for v in nl], [sum(v) for v in ne],
                                             [sum(v) for v in nm], w.feat.shape[1] * w.feat.element_size(),
                                             w.indptr.element_size(), w.n_splits)
                 for kk, (kind, amount) in wk.items():
-                    if kk.startswith(("sample_layer", "mixed_buckets", "shuffle_index")):
+                    if kk.startswith(("sample_layer", "mixed_buckets", "shuffle_index")) or kk == "gather_rows":
                         grouped_work[kk] = grouped_work.get(kk, 0.0) + amount
         torch.cuda.synchronize()
         gt = rs[0].ctx.gsplit_timing_read()
         rs[0].ctx.gsplit_timing_enable(False)
+        if "gather_rows" in gt and gt["gather_rows"][0] > 0 and not cache:
+            cnt, ms = gt.pop("gather_rows")
+            ach = grouped_work.pop("gather_rows") / (ms * 1e-3) / 1e9
+            serial_multi["roofline_gather_grouped"] = {
+                "kernel": "gather_rows", "batches_per_launch": K, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "launch_ms": ms / cnt}
+        grouped_work.pop("gather_rows", None)
         cand = {kk: v for kk, v in gt.items() if kk in grouped_work and v[0] > 0}
         if cand:
             big = max(cand, key=lambda kk: cand[kk][1])
@@ -938,7 +956,8 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         "value": steps / dt, "ms_per_step": dt / steps * 1e3,
         "schedule": ("serial, one stream" if not pipeline else
                      (f"1 sampling stream + 1 training stream: sample+split (one gsplit_sample_split_multi call for "
-                      f"{K} mini-batches) and gather of the next {K} steps overlap fwd/loss/bwd of the current {K}; "
+                      f"{K} mini-batches) and gather (one gsplit_gather_features_multi call) of the next {K} steps overlap "
+                      f"fwd/loss/bwd of the current {K}; "
                       f"every step does all of its work") if K > 1 and not use_graph else
                      f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the next {a.ahead} "
                      f"step(s) overlap fwd/loss/bwd of step i; every step does all of its work"),

@@ -258,6 +258,14 @@ GSPLIT_API int gsplit_batch_shuffle(const gsplit_ctx *ctx, int32_t layer, gsplit
 GSPLIT_API int gsplit_gather_features(gsplit_ctx *ctx, const void *d_table, int32_t dtype, int64_t dim,
                            int64_t row_stride_bytes, void *d_out, void *stream);
 
+/* The loading step (section 3) of up to GSPLIT_MAX_MULTI contexts of one graph and configuration in
+ * one launch (the companion of gsplit_sample_split_multi): d_outs[b] (HOST array of device
+ * pointers) receives the rows of ctxs[b]'s current batch, exactly as gsplit_gather_features would
+ * write them.  One table for all.  Errors are reported on ctxs[0].  Asynchronous. */
+GSPLIT_API int gsplit_gather_features_multi(gsplit_ctx *const *ctxs, int32_t n_batches, const void *d_table,
+                                            int32_t dtype, int64_t dim, int64_t row_stride_bytes,
+                                            void *const *d_outs, void *stream);
+
 /* GraphSAGE-mean model: layer l computes, for the destination vertices of every split,
  *   H_{l+1} = act( H_l[self] * W_self[l] + mean_{u in sampled N(v)} H_l[u] * W_neigh[l] + b[l] ),
  * act = ReLU except on the last layer; an empty neighbourhood has mean 0.  Weights are row-major

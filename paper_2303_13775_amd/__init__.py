@@ -5,4 +5,4 @@ not load the library; constructing a Context does, and fails loudly if the libra
 """
 from .binding import (Context, SageParams, GatParams, GsplitError, load_library, LIB_PATH, EXPORTS,  # noqa: F401
                       GSPLIT_F32, GSPLIT_BF16, gsplit_sample_split_noalloc, noalloc_output_sizes,
-                      gsplit_sample_split_multi)
+                      gsplit_sample_split_multi, gsplit_gather_features_multi)

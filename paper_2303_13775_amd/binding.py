@@ -27,7 +27,7 @@ EXPORTS = [
     "gsplit_gat_fwd", "gsplit_gat_bwd", "gsplit_batch_stats", "gsplit_sample_split_dev",
     "gsplit_input_counts_accumulate", "gsplit_cache_build", "gsplit_gather_features_cached",
     "gsplit_batch_shuffle", "gsplit_sage_activations", "gsplit_gat_score_terms", "gsplit_sample_split_noalloc",
-    "gsplit_sample_split_multi", "gsplit_sage_step",
+    "gsplit_sample_split_multi", "gsplit_sage_step", "gsplit_gather_features_multi",
 ]
 
 
@@ -117,6 +117,7 @@ def load_library():
     L.gsplit_sage_activations.argtypes = [vp, i32, C.POINTER(vp)]
     L.gsplit_gat_score_terms.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     L.gsplit_gather_features.argtypes = [vp, vp, i32, i64, i64, vp, vp]
+    L.gsplit_gather_features_multi.argtypes = [C.POINTER(vp), i32, vp, i32, i64, i64, C.POINTER(vp), vp]
     L.gsplit_sage_fwd.argtypes = [vp, C.POINTER(_SageParams), vp, vp, vp]
     L.gsplit_sage_bwd.argtypes = [vp, C.POINTER(_SageParams), vp, C.POINTER(vp), C.POINTER(vp),
                                   C.POINTER(vp), vp]
@@ -243,6 +244,21 @@ def gsplit_sample_split_multi(ctxs, targets, seed: int, iters):
     for c, t in zip(ctxs, targets):
         c._targets = t
     rc = ctxs[0].lib.gsplit_sample_split_multi(hs, n, tg, nt, C.c_uint64(seed), its, _stream())
+    ctxs[0]._check(rc)
+
+
+def gsplit_gather_features_multi(ctxs, table: torch.Tensor, outs):
+    """The loading step of ctxs[b] into outs[b] for all b in one launch."""
+    n = len(ctxs)
+    assert n >= 1 and len(outs) == n
+    assert table.is_cuda and table.dim() == 2 and table.stride(1) == 1
+    for o in outs:
+        assert o.is_cuda and o.is_contiguous() and o.dtype == table.dtype and o.shape[1] == table.shape[1]
+    dt = {torch.float32: GSPLIT_F32, torch.bfloat16: GSPLIT_BF16}[table.dtype]
+    hs = (C.c_void_p * n)(*[c.h.value for c in ctxs])
+    ps = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+    rc = ctxs[0].lib.gsplit_gather_features_multi(hs, n, table.data_ptr(), dt, table.shape[1],
+                                                  table.stride(0) * table.element_size(), ps, _stream())
     ctxs[0]._check(rc)
 
 

@@ -126,22 +126,29 @@ def test_multi_batch_sampling_bit_exact(name, n_batches):
     bit-equal to the oracle's (and hence to gsplit_sample_split's), batches of different sizes
     (the last one empty when there are more than two), both sides of the shuffle index included;
     then a training step on one of them."""
-    from paper_2303_13775_amd import Context, GsplitError, gsplit_sample_split_multi
+    from paper_2303_13775_amd import Context, GsplitError, gsplit_sample_split_multi, gsplit_gather_features_multi
     dev = _dev()
     w = CASES[name]()
     gi, gx, gp = w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev)
     ctxs = [Context(gi, gx, gp, w.n_splits, w.fanouts, w.batch, table_mode=1 + n_batches % 2) for _ in range(n_batches)]
+    table = w.feat.to(dev)
     for rnd in (0, 1):
         its = [10 * rnd + b for b in range(n_batches)]
         tgs = [w.targets(it)[:max(0, w.batch - 37 * b)] for b, it in enumerate(its)]
         if n_batches > 2:
             tgs[-1] = tgs[-1][:0]
         gsplit_sample_split_multi(ctxs, [t.to(dev) for t in tgs], 777, its)
+        # the loading step of all of them in one launch: byte for byte the table's rows
+        outs = [torch.full((c.gsplit_max_rows(0), w.dims[0]), 7.0, device=dev) for c in ctxs]
+        gsplit_gather_features_multi(ctxs, table, outs)
         for b in range(n_batches):
             ob = _oracle_batch(w, tgs[b], 777, its[b])
             assert_batch_equal(ctxs[b].fetch_batch(), ob, w.n_splits, w.n_layers)
             for l in range(w.n_layers):
                 SC.assert_shuffle_index_equal(ctxs[b], ob, l, has_rev=l >= 1)
+            ids = torch.from_numpy(ob.local_cat(0)).long().to(dev)
+            assert torch.equal(outs[b][:ids.numel()], table[ids]), ("rows loaded by the grouped call", b)
+            assert bool((outs[b][ids.numel():] == 7.0).all()), ("rows past the batch written", b)
     with pytest.raises(GsplitError):                       # the same context twice
         gsplit_sample_split_multi([ctxs[0], ctxs[0]], [tgs[0].to(dev)] * 2, 1, [0, 1])
     other = Context(gi, gx, gp, w.n_splits, w.fanouts, max(1, w.batch // 2), table_mode=1 + n_batches % 2)
