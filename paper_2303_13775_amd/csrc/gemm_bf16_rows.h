@@ -10,19 +10,19 @@
 //   * B stays in registers for the whole launch: a wave's 32 * NI columns x K are 128 VGPRs, loaded
 //     once in the fragment layout of v_mfma_f32_32x32x16_bf16 (8 consecutive k of one column per lane);
 //   * A streams through LDS in units of 64 rows x 128 k (16 KiB) that go straight from global
-//     memory into one of four stages (global_load_lds_dwordx4, 16 bytes a lane, two instructions a
-//     wave and unit), three units ahead of the one being multiplied.  The 16-byte granules of a row
+//     memory into one of four or six stages (global_load_lds_dwordx4, 16 bytes a lane, two instructions
+//     a wave and unit), three or five units ahead of the one being multiplied.  The 16-byte granules of a row
 //     are stored at granule ^ (row & 15): 16 consecutive rows of one granule column then fall into
 //     16 different bank groups and a fragment read (one 128-bit read per lane) is conflict-free;
 //   * a finished tile leaves the accumulators through a wave-private LDS patch (bias / ReLU /
 //     bfloat16 or the 1 / count scaling applied on the way in) and is written to global memory at
 //     the top of the next step with 16-byte stores of whole row segments, so the stores have a
 //     whole step to drain before the next wait.
-// Waiting: a wave waits until at most four of its vector-memory operations are outstanding, i.e.
-// (they complete in order) everything but the two units it issued last, then the workgroup meets
+// Waiting: a wave waits until at most four (eight with six stages) of its vector-memory operations
+// are outstanding, i.e. (they complete in order) everything but the units it issued last, then the workgroup meets
 // at a barrier; after it every wave may read the unit and the stage of the unit before is free.
 // The prefetch is issued unconditionally (past the end it re-reads the last unit into a free
-// stage), so the last four operations before a wait are always those loads.
+// stage), so the last operations before a wait are always those loads.
 #pragma once
 
 constexpr int RB_BM = 64;                  // rows of a tile
@@ -38,13 +38,22 @@ struct RbEpi {
     int relu;
 };
 
-template <int KS16, bool OUT_F32>
+template <class F, int... I>
+__device__ __forceinline__ void rb_for_each(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+constexpr int rb_lcm(int a, int b) { int x = a; while (x % b) x += a; return x; }
+
+// NS: LDS stages (4 or 6): NS - 1 units are in flight ahead of the one being multiplied
+template <int KS16, bool OUT_F32, int NS>
 __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict__ A, const uint16_t *__restrict__ Bt,
                                                       int NB, RbEpi epi, const GsLevelMeta *__restrict__ meta_up, int S) {
     constexpr int NI = 32 / KS16, BN = 128 * NI, UPT = KS16 / 8, K = KS16 * 16;
     static_assert(KS16 == 16 || KS16 == 32, "contraction of 256 or 512");
     static_assert(GNT == 512, "eight waves");
+    static_assert(NS == 4 || NS == 6, "four or six stages");
     __shared__ __attribute__((aligned(16))) uint4 st0[RB_UNIT4], st1[RB_UNIT4], st2[RB_UNIT4], st3[RB_UNIT4];
+    __shared__ __attribute__((aligned(16))) uint4 st4[NS > 4 ? RB_UNIT4 : 1], st5[NS > 4 ? RB_UNIT4 : 1];
     constexpr int PITCH = OUT_F32 ? (32 * NI + 4) * 4 : (32 * NI + 8) * 2;     // bytes of a patch row
     __shared__ __attribute__((aligned(16))) unsigned char patches[8 * 32 * PITCH];
 
@@ -90,7 +99,7 @@ __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict
         prow[x] = 4 * p + (lane >> 4);
         pgran[x] = ((lane & 15) ^ (prow[x] & 15)) * 8;       // element offset of the global granule that lands here
     }
-    auto issue = [&](uint4 *stage, int v) {
+    auto issue = [&](uint4 *stage, int v) __attribute__((always_inline)) {
         v = min(v, nu - 1);
         const int tile = walker + (v / UPT) * nwalk, kp = v % UPT;
 #pragma unroll
@@ -109,7 +118,7 @@ __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict
         for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
 
     const int arow = wm0 + l32, abase = arow * 16, asw = arow & 15;
-    auto multiply = [&](const uint4 *stage, auto kp_c) {
+    auto multiply = [&](const uint4 *stage, auto kp_c) __attribute__((always_inline)) {
         constexpr int KP = decltype(kp_c)::value;
 #pragma unroll
         for (int k8 = 0; k8 < 8; ++k8) {
@@ -123,14 +132,14 @@ __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict
 
     // ---- epilogue halves
     float4 inv[4];                       // 1 / count of the lane's 16 accumulator rows (input gradient)
-    auto load_inv = [&](int m0) {
+    auto load_inv = [&](int m0) __attribute__((always_inline)) {
         if (OUT_F32) {
 #pragma unroll
             for (int g = 0; g < 4; ++g)
                 inv[g] = *reinterpret_cast<const float4 *>(epi.inv_cnt + m0 + wm0 + 8 * g + 4 * half);
         }
     };
-    auto to_patch = [&]() {
+    auto to_patch = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int n = n0 + wn0 + 32 * j + l32;
@@ -155,7 +164,7 @@ __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict
     constexpr int GPR = (OUT_F32 ? 8 : 4) * NI;          // 16-byte granules of a patch row
     constexpr int RPI = 64 / GPR;                        // rows a wave stores with one instruction
     constexpr int EPG = OUT_F32 ? 4 : 8;                 // elements of a granule
-    auto from_patch = [&](int m0) {
+    auto from_patch = [&](int m0) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = RPI * i + lane / GPR, gr = lane % GPR;
@@ -170,41 +179,52 @@ __global__ __launch_bounds__(GNT) void k_rows_gemm_hb(const uint16_t *__restrict
 
     // One step = one unit.  cur: the stage that holds unit u; free: the stage unit u - 1 was in.
     int m_done = -1;                      // first row of the tile waiting in the patch, -1: none
-    auto step = [&](const uint4 *cur, uint4 *free_stage, int u, auto kp_c) {
+    auto step = [&](const uint4 *cur, uint4 *free_stage, int u, auto kp_c) __attribute__((always_inline)) {
         constexpr int KP = decltype(kp_c)::value;
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        // all but the youngest NS - 2 units (two loads each) have landed: that includes unit u
+        if (NS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         const int m0 = (walker + (u / UPT) * nwalk) * RB_BM;
         if (KP == 0) {
             if (m_done >= 0) from_patch(m_done);
             load_inv(m0);
         }
-        issue(free_stage, u + 3);
+        issue(free_stage, u + NS - 1);
         multiply(cur, kp_c);
         if (KP == UPT - 1) {
             to_patch();
             m_done = m0;
         }
     };
-    using K0 = std::integral_constant<int, 0>;
-    using K1 = std::integral_constant<int, 1 % UPT>;
-    using K2 = std::integral_constant<int, 2 % UPT>;
-    using K3 = std::integral_constant<int, 3 % UPT>;
-
-    issue(st0, 0);
-    issue(st1, 1);
-    issue(st2, 2);
+    auto stage = [&](auto ic) __attribute__((always_inline)) -> uint4 * {
+        constexpr int x = decltype(ic)::value;
+        if constexpr (x == 0) return st0;
+        else if constexpr (x == 1) return st1;
+        else if constexpr (x == 2) return st2;
+        else if constexpr (x == 3) return st3;
+        else if constexpr (x == 4) return st4;
+        else return st5;
+    };
+    // a round: as many steps as bring both the stages and the units of a tile back to where they started
+    constexpr int ROUND = rb_lcm(NS, UPT);
+    rb_for_each([&](auto ic) __attribute__((always_inline)) { issue(stage(ic), decltype(ic)::value); }, std::make_integer_sequence<int, NS - 1>{});
     int u = 0;
-    // UPT divides 4, so a round of four steps starts at the first unit of a tile
-    for (; u + 4 <= nu; u += 4) {
-        step(st0, st3, u, K0{});
-        step(st1, st0, u + 1, K1{});
-        step(st2, st1, u + 2, K2{});
-        step(st3, st2, u + 3, K3{});
-    }
-    if (u < nu) {                          // UPT == 2 and an odd number of tiles: one more tile
-        step(st0, st3, u, K0{});
-        step(st1, st0, u + 1, K1{});
+    for (; u + ROUND <= nu; u += ROUND)
+        rb_for_each([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            step(stage(std::integral_constant<int, i % NS>{}), stage(std::integral_constant<int, (i + NS - 1) % NS>{}), u + i,
+                 std::integral_constant<int, i % UPT>{});
+        }, std::make_integer_sequence<int, ROUND>{});
+    if (u < nu) {                          // the tiles of an incomplete round
+        const int left = nu - u;
+        rb_for_each([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            if (i < left)
+                step(stage(std::integral_constant<int, i % NS>{}), stage(std::integral_constant<int, (i + NS - 1) % NS>{}),
+                     u + i, std::integral_constant<int, i % UPT>{});
+        }, std::make_integer_sequence<int, ROUND>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (m_done >= 0) from_patch(m_done);

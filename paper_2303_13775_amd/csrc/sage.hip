@@ -805,6 +805,7 @@ __global__ __launch_bounds__(TOP_T) void k_sage_top_fused(TopArgs a) {
 // The streaming bf16 row-block kernel takes a product when the contraction is 256 or 512, the output
 // rows are whole 16-byte granules and the level is large enough (by its bound) to fill the chip.
 constexpr int64_t RB_MIN_ROWS = 32768;
+constexpr int RB_FWD_STAGES = 4;        // (six stages fit beside the forward product's bf16 patch and measured the same: 197 against 198 us)
 bool rows_gemm_fits(int64_t ub_rows, int K, int NB, int granule) {
     return (K == 256 || K == 512) && NB % granule == 0 && ub_rows >= RB_MIN_ROWS;
 }
@@ -1046,10 +1047,10 @@ int sage_forward(gsplit_ctx *ctx, const gsplit_sage_params *p, const void *d_fea
             if (l < L - 1 && rows_gemm_fits(ub, 2 * D, N, 8)) {
                 RbEpi re{sb.hidden[l + 1], N, (const float *)p->d_bias[l], nullptr, 0, 1};
                 if (2 * D == 256)
-                    hipLaunchKernelGGL((k_rows_gemm_hb<16, false>), dim3(rows_gemm_grid(ctx, N, 256)), dim3(GNT), 0, st,
+                    hipLaunchKernelGGL((k_rows_gemm_hb<16, false, RB_FWD_STAGES>), dim3(rows_gemm_grid(ctx, N, 256)), dim3(GNT), 0, st,
                                        x.p, wt.p, N, re, mu, S);
                 else
-                    hipLaunchKernelGGL((k_rows_gemm_hb<32, false>), dim3(rows_gemm_grid(ctx, N, 128)), dim3(GNT), 0, st,
+                    hipLaunchKernelGGL((k_rows_gemm_hb<32, false, RB_FWD_STAGES>), dim3(rows_gemm_grid(ctx, N, 128)), dim3(GNT), 0, st,
                                        x.p, wt.p, N, re, mu, S);
             } else {
                 dim3 grid(row_block_grid<TileMid>(ctx, ub, N));
@@ -1176,10 +1177,10 @@ int sage_backward(gsplit_ctx *ctx, const gsplit_sage_params *p, const float *d_g
                     if (dz_h && rows_gemm_fits(ub, N, 2 * D, 4)) {
                         RbEpi re{sb.gtmp, 2 * D, nullptr, sb.inv_cnt[l], D, 0};
                         if (N == 256)
-                            hipLaunchKernelGGL((k_rows_gemm_hb<16, true>), dim3(rows_gemm_grid(ctx, 2 * D, 256)), dim3(GNT), 0,
+                            hipLaunchKernelGGL((k_rows_gemm_hb<16, true, 4>), dim3(rows_gemm_grid(ctx, 2 * D, 256)), dim3(GNT), 0,
                                                st, dzh.p, wsk.p, 2 * D, re, mu, S);
                         else
-                            hipLaunchKernelGGL((k_rows_gemm_hb<32, true>), dim3(rows_gemm_grid(ctx, 2 * D, 128)), dim3(GNT), 0,
+                            hipLaunchKernelGGL((k_rows_gemm_hb<32, true, 4>), dim3(rows_gemm_grid(ctx, 2 * D, 128)), dim3(GNT), 0,
                                                st, dzh.p, wsk.p, 2 * D, re, mu, S);
                     } else if (dz_h) hipLaunchKernelGGL(k_sage_grad_in_hh, grid, dim3(GNT), 0, st, dzh, wsk, ei, mu, S);
                     else if (vdz) hipLaunchKernelGGL((k_sage_grad_in_h<4>), grid, dim3(GNT), 0, st, dz, wsk, ei, mu, S);
