@@ -1,5 +1,6 @@
 // Context life cycle, workspace sizing and the read-only views of the current batch.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "gsplit_internal.h"
@@ -167,6 +168,16 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     A((void **)&ctx->ent_local, sizeof(int32_t) * max_items, "ent_local");
     A((void **)&ctx->mixed_ent, sizeof(int32_t) * max_items, "mixed_ent");
     A((void **)&ctx->cls, sizeof(uint32_t) * max_items, "class masks");
+    if (const char *e = std::getenv("GSPLIT_WIDE_SLOTS")) {
+        const long long v = std::strtoll(e, nullptr, 10);
+        if (v >= 1) ctx->wide_slots = v;
+    }
+    bool any_wide = false;
+    for (int l = 0; l < L; ++l) any_wide = any_wide || ctx->ub_front[l + 1] * ctx->fan[l] >= ctx->wide_slots;
+    if (any_wide) {
+        A((void **)&ctx->pos_pair, sizeof(int32_t) * 2 * max_items, "row pairs by position");
+        A((void **)&ctx->mixed_pos, sizeof(int32_t) * max_items, "positions of mixed rows");
+    }
     A((void **)&ctx->part_hist, sizeof(int32_t) * 1024 * 25, "partition histogram");
     A((void **)&ctx->part_base, sizeof(int32_t) * 1024 * 25, "partition bases");
     if (rc == GSPLIT_OK && hipMemset(ctx->d_meta, 0, sizeof(GsLevelMeta) * (L + 1)) != hipSuccess)

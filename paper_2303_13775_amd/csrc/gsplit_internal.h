@@ -13,6 +13,9 @@
 // "long" row: the backward pass hands those to whole workgroups
 #define GS_REV_LONG 256
 #define GS_MAXS GSPLIT_MAX_SPLITS
+// a sampling layer with at least this many slots (by its bound) is "wide": its relabelling runs as two
+// launches, which cuts the dependent random accesses per slot from three to one
+#define GS_WIDE_SLOTS (1ll << 20)
 #define GS_MAXL GSPLIT_MAX_LAYERS
 
 // Device-resident bookkeeping of one level l (0..L) of the current batch.  Every kernel reads its
@@ -177,6 +180,11 @@ struct gsplit_ctx {
     int32_t     *ent_local = nullptr;       // tab_local entry of each destination / received id
     int32_t     *mixed_ent = nullptr;       // tab_local entry of each mixed-frontier row
     uint32_t    *cls = nullptr;             // class mask left by a count pass for its scatter pass
+    // wide layers only (contexts that have one): per position of a key's first occurrence the pair
+    // (row in the split's mixed frontier, row in local_cat), and per mixed-frontier row that position
+    int32_t     *pos_pair = nullptr;        // [2 * max_items]
+    int32_t     *mixed_pos = nullptr;       // [max_items]
+    int64_t      wide_slots = GS_WIDE_SLOTS; // the bar in force (GSPLIT_WIDE_SLOTS in the environment moves it: tests)
     int32_t     *part_hist = nullptr;       // partition scratch
     int32_t     *part_base = nullptr;
 

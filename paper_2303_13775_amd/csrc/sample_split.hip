@@ -247,7 +247,8 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             int64_t pos = -1;
             if (floyd) pos = beg + (int64_t)chosen;
             else if ((uint32_t)q < d) pos = beg + q;
-            if (pos >= 0) val = indices[pos];
+            // (the graph is read once, at random: a load that leaves the caches to what is used again)
+            if (pos >= 0) val = __builtin_nontemporal_load(&indices[pos]);
             const int64_t g = (int64_t)row * fan + q;
             nbr[g] = val;
             if (epos) epos[g] = pos;
@@ -649,6 +650,7 @@ struct PartLayer {
     GsLevelMeta *meta_lo; const GsLevelMeta *meta_up; int S; int fan; int rev;
     RevUp up;
     int layer;
+    int32_t *pos_pair; int32_t *mixed_pos;      // a wide layer's (null otherwise)
     __device__ int n1() const { return meta_up->front_off[S]; }
     __device__ int n() const { return n1() * fan; }
     // classes s and 8 + t and 17 + t exist for the splits the context has, class 16 always
@@ -763,7 +765,8 @@ struct PartLayer {
         const int32_t id = nbr[g];
         const int at = n1() + g;               // a winner: the first occurrence of its (vertex, split) key
         mixed[rk[s]] = id;
-        tab_mixed.row[at] = rk[s] - o.a[s];
+        if (pos_pair) { pos_pair[2 * (size_t)at] = rk[s] - o.a[s]; mixed_pos[rk[s]] = at; }
+        else tab_mixed.row[at] = rk[s] - o.a[s];
         mixed_ent[rk[s]] = ent_local[at];      // where the vertex first occurs in the whole stream (-1: no entry)
         recv[rk[8 + t]] = id;
         if ((m >> 17) & 0xFFu) {               // that place is this one
@@ -794,7 +797,8 @@ struct PartLayer {
         const int j = o.a[s] + loc, rowp = o.c[s] + loc;
         // a destination vertex holds the smallest position of both of its keys: position i
         mixed[j] = id;
-        tab_mixed.row[i] = loc;
+        if (pos_pair) { pos_pair[2 * (size_t)i] = loc; mixed_pos[j] = i; }
+        else tab_mixed.row[i] = loc;
         mixed_ent[j] = hl >= 0 ? i : -1;
         front_lo[rowp] = id;
         tab_local.row[i] = rowp;
@@ -813,6 +817,7 @@ struct ShuffleArgs {
     const int32_t *ent_mixed, *ent_local, *mixed_ent, *blk_indptr;
     int32_t *blk_src, *src_row, *self_row, *edge_row, *rev_cnt;
     const GsLevelMeta *meta_lo, *meta_up;
+    int32_t *pos_pair; const int32_t *mixed_pos;        // a wide layer's (null otherwise)
 };
 struct ShuffleArgsSet { ShuffleArgs b[GS_MAXB]; };
 
@@ -832,13 +837,17 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
     const GsLevelMeta *__restrict__ meta_up = a.meta_up;
     const int n1 = meta_up->front_off[S];
     const int64_t n_mixed = meta_lo->mixed_off[S];
-    const int64_t n_slots = (int64_t)n1 * fan;
+    // A wide layer leaves the slots to k_shuffle_edges: here every mixed-frontier row also notes its row
+    // of local_cat at the position where its key first occurs, beside the row the scatter pass left there.
+    const int64_t n_slots = a.pos_pair ? 0 : (int64_t)n1 * fan;
     const int64_t total = n_mixed + n1 + n_slots;
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < total;
          x += (int64_t)gridDim.x * blockDim.x) {
         if (x < n_mixed) {
             const int p = mixed_ent[x];
-            src_row[x] = p >= 0 ? tab_local.row[p] : -1;
+            const int r = p >= 0 ? tab_local.row[p] : -1;
+            src_row[x] = r;
+            if (a.pos_pair) a.pos_pair[2 * (size_t)a.mixed_pos[x] + 1] = r;
         } else if (x < n_mixed + n1) {
             const int i = (int)(x - n_mixed);
             const int h = ent_local[i];
@@ -873,6 +882,34 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
             if (x < nr) tab_mixed.slot[x] = EMPTY_ENTRY;
             else tab_local.slot[x - nr] = EMPTY_ENTRY;
         }
+    }
+}
+
+// The slots of a wide layer, after k_shuffle_index.  In one launch a slot is three dependent random
+// accesses (the mixed-frontier row kept where its key first occurs -> that row's vertex entry -> its
+// row of local_cat), and a wide layer runs at the rate at which the memory completes such accesses;
+// once every mixed-frontier row has left its row of local_cat at that same position, a slot is one
+// access of 8 bytes.
+__global__ __launch_bounds__(256) void k_shuffle_edges(ShuffleArgsSet set, int S, int fan) {
+    const ShuffleArgs &a = set.b[blockIdx.y];
+    const int32_t *__restrict__ ent_mixed = a.ent_mixed;
+    const int32_t *__restrict__ blk_indptr = a.blk_indptr;
+    const int2 *__restrict__ pair = reinterpret_cast<const int2 *>(a.pos_pair);
+    int32_t *__restrict__ blk_src = a.blk_src;
+    int32_t *__restrict__ edge_row = a.edge_row;
+    int32_t *__restrict__ rev_cnt = a.rev_cnt;
+    const int n1 = a.meta_up->front_off[S];
+    const int64_t n_slots = (int64_t)n1 * fan;
+    for (int64_t g = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; g < n_slots;
+         g += (int64_t)gridDim.x * blockDim.x) {
+        const int first = ent_mixed[n1 + g];
+        if (first < 0) continue;
+        const int i = (int)(g / fan), q = (int)(g - (int64_t)i * fan);
+        const int2 v = pair[first];
+        const int e = blk_indptr[i] + q;
+        blk_src[e] = v.x;
+        edge_row[e] = v.y;
+        if (rev_cnt && v.y >= 0) atomicAdd(&rev_cnt[v.y], 1);
     }
 }
 
@@ -1085,6 +1122,8 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
 
         PartSet<PartLayer> pset{};
         ShuffleArgsSet sset{};
+        bool wide = ub1 * fan >= ctx->wide_slots;
+        for (int b = 0; b < nbat; ++b) wide = wide && ctxs[b]->pos_pair && ctxs[b]->mixed_pos;
         for (int b = 0; b < nbat; ++b) {
             gsplit_ctx *c = ctxs[b];
             GsLayerBuf &B = c->layer[l];
@@ -1093,7 +1132,8 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
             PartLayer pa{c->tab_mixed, c->tab_local, c->front[l + 1], B.nbr, c->graph.d_pmap,
                          c->ent_mixed, c->ent_local, c->cls, c->mixed_ent,
                          B.mixed, B.blk_indptr, B.recv, c->front[l], B.rev_cnt,
-                         ml, mu, S, fan, l >= c->rev_from ? 1 : 0, RevUp{}, l};
+                         ml, mu, S, fan, l >= c->rev_from ? 1 : 0, RevUp{}, l,
+                         wide ? c->pos_pair : nullptr, wide ? c->mixed_pos : nullptr};
             if (l + 1 < L && l + 1 >= c->rev_from) {
                 const GsLayerBuf &U = c->layer[l + 1];
                 pa.up = RevUp{1, U.rev_cnt, U.rev_ptr, U.rev_fill, U.rev_list, U.rev_eid, U.cnt, U.blk_indptr,
@@ -1104,13 +1144,17 @@ int sample_split(gsplit_ctx *const *ctxs, int nbat, const int32_t *const *d_targ
             pset.hist[b] = c->part_hist;
             sset.b[b] = ShuffleArgs{c->tab_local, c->tab_mixed, c->ent_mixed, c->ent_local, c->mixed_ent, B.blk_indptr,
                                     B.blk_src, B.src_row, B.self_row, B.edge_row, l >= c->rev_from ? B.rev_cnt : nullptr,
-                                    ml, mu};
+                                    ml, mu, wide ? c->pos_pair : nullptr, wide ? c->mixed_pos : nullptr};
         }
         run_partition(ctxs, nbat, pset, ub1 * fan, st, "mixed_buckets", l);
         {
             GsTimeScope ts(ctx, "shuffle_index", l, st);
             hipLaunchKernelGGL(k_shuffle_index, dim3(grid_for(ctx, ub1 * (2 + 2 * fan), nbat), nbat), dim3(256), 0, st,
                                sset, S, fan, l > 0 ? ctx->fan[l - 1] : 0, l == 0 ? top_cap : 0);
+        }
+        if (wide) {
+            GsTimeScope ts(ctx, "shuffle_edges", l, st);
+            hipLaunchKernelGGL(k_shuffle_edges, dim3(grid_for(ctx, ub1 * fan, nbat), nbat), dim3(256), 0, st, sset, S, fan);
         }
     }
     // the bottom layer's reverse index (contexts that keep one) has no partition below it to ride on

@@ -102,6 +102,27 @@ def test_sample_split_bit_exact(name, table_mode):
     ctx.close()
 
 
+@pytest.mark.parametrize("name", list(CASES))
+def test_wide_layer_relabelling_bit_exact(name, monkeypatch):
+    """The relabelling of wide layers (the slots in a launch of their own, one access per slot) on every
+    layer of every case: the bar that selects it is lowered to one slot.  A context that keeps the
+    scatter side for the bottom layer too, so every layer counts its reverse index on this path."""
+    from paper_2303_13775_amd import Context
+    monkeypatch.setenv("GSPLIT_WIDE_SLOTS", "1")
+    dev = _dev()
+    w = CASES[name]()
+    ctx = Context(w.indptr.to(dev), w.indices.to(dev), w.pmap.to(dev), w.n_splits, w.fanouts, w.batch,
+                  gat_index=True, table_mode=1 + len(name) % 2)
+    for it in (0, 1):
+        tg = w.targets(it)[:w.batch - 11 * it]
+        ctx.gsplit_sample_split(tg.to(dev), seed=4321 + it, it=it)
+        ob = _oracle_batch(w, tg, 4321 + it, it)
+        assert_batch_equal(ctx.fetch_batch(), ob, w.n_splits, w.n_layers)
+        for l in range(w.n_layers):
+            SC.assert_shuffle_index_equal(ctx, ob, l, has_rev=True, has_eid=True)
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", ["tiny", "ragged-S3", "fan32-S8-int64", "S1"])
 def test_shuffle_index_scatter_side_with_edge_ids(name):
     """A context that keeps the scatter side for the bottom layer too (gat_index): every layer's
