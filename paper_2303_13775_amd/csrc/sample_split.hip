@@ -680,10 +680,15 @@ struct PartLayer {
                 const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
                 const unsigned long long *e = tab_mixed.pos + (size_t)idc * (uint32_t)S;
                 uint32_t first = pos, lfirst = pos;
-                for (int ss = 0; ss < S; ++ss) {
-                    const unsigned long long v = e[ss];
-                    if (ss == s) first = (uint32_t)v;
-                    if ((uint32_t)(v >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v);
+                // (all of the vertex's entries are asked for at once; an entry the context does not
+                // have reads as empty, whose upper half is no stamp)
+                unsigned long long v[GS_MAXS];
+#pragma unroll
+                for (int ss = 0; ss < GS_MAXS; ++ss) v[ss] = ss < S ? e[ss] : EMPTY_ENTRY;
+#pragma unroll
+                for (int ss = 0; ss < GS_MAXS; ++ss) {
+                    if (ss == s) first = (uint32_t)v[ss];
+                    if ((uint32_t)(v[ss] >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v[ss]);
                 }
                 m = 1u << 16;
                 ent_mixed[at] = (int32_t)first;
