@@ -158,7 +158,8 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
             // (vertex, split) keys only: the entries of a vertex lie side by side, which answers the
             // questions a table keyed by the vertex alone would
             if (t == &ctx->tab_mixed) A((void **)&t->pos, sizeof(unsigned long long) * keys_m, "direct table entries");
-        } else {
+        } else if (t == &ctx->tab_mixed) {
+            // hashed by the vertex: the keys of a vertex share lines, which answers the same questions
             A((void **)&t->slot, sizeof(unsigned long long) * tab_cap, "table entries");
         }
         // rows are handed out by position in the slot stream, not by table entry
@@ -185,7 +186,7 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     // every table entry empty (all bits set): a batch starts on clean tables, and leaves them so
     for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
         if (rc != GSPLIT_OK) break;
-        if (ctx->direct_tables && !t->pos) continue;
+        if (ctx->direct_tables ? !t->pos : !t->slot) continue;
         if (t == &ctx->tab_local && t->slot == ctx->tab_mixed.slot && t->pos == ctx->tab_mixed.pos) continue;   // one split: one table
         const hipError_t e = ctx->direct_tables ? hipMemset(t->pos, 0xFF, sizeof(unsigned long long) * keys_m)
                                                 : hipMemset(t->slot, 0xFF, sizeof(unsigned long long) * tab_cap);

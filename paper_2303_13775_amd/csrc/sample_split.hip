@@ -120,6 +120,87 @@ __device__ __forceinline__ uint32_t table_pos(const GsTable &t, int h) {
     return t.pos ? (uint32_t)t.pos[h] : (uint32_t)t.slot[h];
 }
 
+// The hashed table of a context with several splits holds (vertex, split) keys only, hashed by the
+// vertex: the keys of a vertex start at the same line of 16 entries (128 bytes, what one access to
+// the memory moves whatever it asks for) and lie there side by side, filled from the front, running
+// over into the next line when one is full.  So the first occurrence of the vertex in the whole
+// stream (the smallest position among its keys) is read off the line the slot's own entry is in, and
+// there is no second table keyed by the vertex, with its own insert and its own line per access.
+constexpr int LINE_ENTRIES = 16;
+__device__ __forceinline__ uint32_t table_line(uint32_t vertex, int bits) {
+    return ((vertex * 0x9E3779B1u) >> (32 - (bits - 4))) << 4;
+}
+
+// Insert into that table.  The line is read once, with plain loads: what such a read shows of a taken
+// entry is true for good (an entry keeps its key, its position only falls), and an entry it shows
+// empty is taken with a compare-and-swap, which answers with the truth.  The probe starts at the first
+// entry that is the key's or empty, and from there is the linear probe of table_insert.
+// claim_first (small layers): no read at all, a compare-and-swap on one entry after the other from
+// the front of the line.
+__device__ __forceinline__ int table_insert_line(const GsTable &t, int bits, uint32_t vertex, uint32_t S, uint32_t split,
+                                                 uint32_t p, int32_t *err, bool *behind, bool claim_first) {
+    const uint32_t key = vertex * S + split;
+    const uint32_t mask = (1u << bits) - 1u;
+    const unsigned long long mine = ((unsigned long long)key << 32) | p;
+    uint32_t h = table_line(vertex, bits);
+    for (uint32_t probe = 0; probe <= mask; probe += LINE_ENTRIES) {
+        int j0 = 0;
+        unsigned long long at0 = EMPTY_ENTRY;
+        if (!claim_first) {
+            const ulonglong2 *line = reinterpret_cast<const ulonglong2 *>(t.slot + h);
+            ulonglong2 q[LINE_ENTRIES / 2];
+#pragma unroll
+            for (int i = 0; i < LINE_ENTRIES / 2; ++i) q[i] = line[i];
+            j0 = LINE_ENTRIES;
+#pragma unroll
+            for (int j = LINE_ENTRIES - 1; j >= 0; --j) {
+                const unsigned long long e = (j & 1) ? q[j >> 1].y : q[j >> 1].x;
+                if (e == EMPTY_ENTRY || (uint32_t)(e >> 32) == key) { j0 = j; at0 = e; }
+            }
+        }
+        for (int j = j0; j < LINE_ENTRIES; ++j) {
+            unsigned long long cur = (claim_first || j == j0) ? at0
+                                         : __hip_atomic_load(&t.slot[h + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (cur == EMPTY_ENTRY) {
+                cur = atomicCAS(&t.slot[h + j], EMPTY_ENTRY, mine);
+                if (cur == EMPTY_ENTRY) return (int)(h + j);
+            }
+            if ((uint32_t)(cur >> 32) == key) {
+                if (mine < cur) atomicMin(&t.slot[h + j], mine);
+                else if (behind) *behind = true;
+                return (int)(h + j);
+            }
+        }
+        h = (h + LINE_ENTRIES) & mask;
+    }
+    *err = 1;
+    return -1;
+}
+
+// smallest position among the keys of a vertex in that table (at most `start`): its lines are read
+// until one shows an empty entry
+__device__ __forceinline__ uint32_t table_line_first(const GsTable &t, int bits, uint32_t vertex, uint32_t S, uint32_t start) {
+    const uint32_t mask = (1u << bits) - 1u;
+    const uint32_t base = vertex * S;
+    uint32_t h = table_line(vertex, bits), best = start;
+    for (uint32_t probe = 0; probe <= mask; probe += LINE_ENTRIES) {
+        const ulonglong2 *line = reinterpret_cast<const ulonglong2 *>(t.slot + h);
+        ulonglong2 q[LINE_ENTRIES / 2];
+#pragma unroll
+        for (int i = 0; i < LINE_ENTRIES / 2; ++i) q[i] = line[i];
+        bool open = false;
+#pragma unroll
+        for (int j = 0; j < LINE_ENTRIES; ++j) {
+            const unsigned long long e = (j & 1) ? q[j >> 1].y : q[j >> 1].x;
+            if (e == EMPTY_ENTRY) open = true;
+            else if ((uint32_t)(e >> 32) - base < S) best = min(best, (uint32_t)e);
+        }
+        if (open) break;
+        h = (h + LINE_ENTRIES) & mask;
+    }
+    return best;
+}
+
 // Stamp of the direct tables for sampling layer `layer` of the batch a context is working on: falls
 // with every batch and, inside a batch, from the top layer down (8 = GSPLIT_MAX_LAYERS per batch).
 __device__ __forceinline__ uint32_t table_stamp(const GsLevelMeta *meta_level0, uint32_t layer) {
@@ -181,6 +262,7 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
     // direct tables with several splits: the (vertex, split) entries of a vertex are neighbours in
     // memory, the partition reads them together, and there is no table keyed by the vertex alone
     const bool no_local = !tab_local.pos && !tab_local.slot;
+    const bool lines = no_local && !tab.pos;     // hashed, several splits: the keys of a vertex share lines
     int32_t *__restrict__ ent_mixed = a.ent_mixed;
     int32_t *__restrict__ ent_local = a.ent_local;
     int32_t *__restrict__ nbr = a.nbr;
@@ -255,8 +337,10 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
             if (q == 0) {
                 cnt[row] = d < (uint32_t)fan ? (int32_t)d : fan;
                 if (!spare) {
-                    const int hm = table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
-                                                &meta_lo->error);
+                    const int hm = lines ? table_insert_line(tab, bits, (uint32_t)v, (uint32_t)S, sp, (uint32_t)row,
+                                                             &meta_lo->error, nullptr, false)
+                                         : table_insert(tab, bits, (uint32_t)v * (uint32_t)S + sp, (uint32_t)row,
+                                                        &meta_lo->error);
                     ent_mixed[row] = hm;
                     ent_local[row] = (S == 1 || no_local) ? hm : table_insert(tab_local, bits, (uint32_t)v, (uint32_t)row,
                                                                               &meta_lo->error);
@@ -279,8 +363,9 @@ __global__ __launch_bounds__(256) void k_sample_layer(const IndPtrT *__restrict_
                 // entry in the vertex table, so it does not make one
                 // (with a single split the two keys are the same key, the two tables the same table,
                 // and a vertex has the same row in the mixed and in the next local frontier)
-                hm = table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind,
-                                  claim_first);
+                hm = lines ? table_insert_line(tab, bits, (uint32_t)key_v, (uint32_t)S, sp, pos_v, &meta_lo->error, &behind, claim_first)
+                           : table_insert(tab, bits, (uint32_t)key_v * (uint32_t)S + sp, pos_v, &meta_lo->error, &behind,
+                                          claim_first);
                 if (S == 1 || no_local) hl = hm;
                 else if (!behind)
                     hl = table_insert(tab_local, bits, (uint32_t)key_v, pos_v, &meta_lo->error, nullptr, claim_first);
@@ -672,23 +757,30 @@ struct PartLayer {
         const uint32_t pos = (uint32_t)at;
         unsigned m = 0u;
         if (!tab_local.pos && !tab_local.slot) {
-            // one direct table of (vertex, split) keys: the vertex's entries for the single splits lie side
-            // by side; the slot's own one tells where its key first occurs, the smallest of those that
-            // carry this layer's stamp where the vertex first occurs in the whole stream
+            // one table of (vertex, split) keys.  Direct: the vertex's entries for the single splits lie
+            // side by side; the slot's own one tells where its key first occurs, the smallest of those
+            // that carry this layer's stamp where the vertex first occurs in the whole stream.  Hashed:
+            // the slot's own entry, and for a winner the smallest position in the vertex's lines.
             if (h != -1) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
-                const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
-                const unsigned long long *e = tab_mixed.pos + (size_t)idc * (uint32_t)S;
                 uint32_t first = pos, lfirst = pos;
-                // (all of the vertex's entries are asked for at once; an entry the context does not
-                // have reads as empty, whose upper half is no stamp)
-                unsigned long long v[GS_MAXS];
+                if (tab_mixed.pos) {
+                    const uint32_t stamp = table_stamp(meta_lo - layer, (uint32_t)layer);
+                    const unsigned long long *e = tab_mixed.pos + (size_t)idc * (uint32_t)S;
+                    // (all of the vertex's entries are asked for at once; an entry the context does not
+                    // have reads as empty, whose upper half is no stamp)
+                    unsigned long long v[GS_MAXS];
 #pragma unroll
-                for (int ss = 0; ss < GS_MAXS; ++ss) v[ss] = ss < S ? e[ss] : EMPTY_ENTRY;
+                    for (int ss = 0; ss < GS_MAXS; ++ss) v[ss] = ss < S ? e[ss] : EMPTY_ENTRY;
 #pragma unroll
-                for (int ss = 0; ss < GS_MAXS; ++ss) {
-                    if (ss == s) first = (uint32_t)v[ss];
-                    if ((uint32_t)(v[ss] >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v[ss]);
+                    for (int ss = 0; ss < GS_MAXS; ++ss) {
+                        if (ss == s) first = (uint32_t)v[ss];
+                        if ((uint32_t)(v[ss] >> 32) == stamp) lfirst = min(lfirst, (uint32_t)v[ss]);
+                    }
+                } else {
+                    first = (uint32_t)tab_mixed.slot[h >= 0 ? h : -2 - h];
+                    if (h >= 0 && first == pos && hl >= 0)
+                        lfirst = table_line_first(tab_mixed, table_bits(n1() * (1 + fan)), idc, (uint32_t)S, pos);
                 }
                 m = 1u << 16;
                 ent_mixed[at] = (int32_t)first;
@@ -882,7 +974,8 @@ __global__ __launch_bounds__(256) void k_shuffle_index(ShuffleArgsSet set, int S
     // does not have to
     if (!tab_mixed.pos && (fan_next > 0 || top_cap > 0)) {
         const int64_t nr = fan_next > 0 ? 1ll << table_bits(meta_lo->front_off[S] * (1 + fan_next)) : top_cap;
-        for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < 2 * nr;
+        const int64_t both = tab_local.slot ? 2 * nr : nr;       // (several splits: there is one table)
+        for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < both;
              x += (int64_t)gridDim.x * blockDim.x) {
             if (x < nr) tab_mixed.slot[x] = EMPTY_ENTRY;
             else tab_local.slot[x - nr] = EMPTY_ENTRY;
@@ -1229,7 +1322,7 @@ __global__ __launch_bounds__(256) void k_noalloc_reset(GsTable a, GsTable b, int
                                                        int n_meta_words) {
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n_entries; x += (int64_t)gridDim.x * blockDim.x) {
         a.slot[x] = EMPTY_ENTRY;
-        if (b.slot != a.slot) b.slot[x] = EMPTY_ENTRY;
+        if (b.slot && b.slot != a.slot) b.slot[x] = EMPTY_ENTRY;
     }
     if (blockIdx.x == 0)
         for (int x = threadIdx.x; x < n_meta_words; x += blockDim.x) meta_words[x] = 0;
@@ -1299,7 +1392,6 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     auto carve = [&](size_t bytes) { const size_t at = need; need += (bytes + 255) & ~(size_t)255; return at; };
     const size_t o_meta = carve(sizeof(GsLevelMeta) * (L + 1));
     const size_t o_mslot = carve(sizeof(unsigned long long) * tab_cap), o_mrow = carve(sizeof(int32_t) * max_items);
-    const size_t o_lslot = S == 1 ? o_mslot : carve(sizeof(unsigned long long) * tab_cap);
     const size_t o_lrow = S == 1 ? o_mrow : carve(sizeof(int32_t) * max_items);
     const size_t o_em = carve(sizeof(int32_t) * max_items), o_el = carve(sizeof(int32_t) * max_items);
     const size_t o_me = carve(sizeof(int32_t) * max_items), o_cls = carve(sizeof(uint32_t) * max_items);
@@ -1318,7 +1410,8 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     ctx.n_cu = dev->n_cu;
     ctx.d_meta = (GsLevelMeta *)(base + o_meta);
     ctx.tab_mixed = GsTable{(unsigned long long *)(base + o_mslot), (int32_t *)(base + o_mrow), nullptr};
-    ctx.tab_local = GsTable{(unsigned long long *)(base + o_lslot), (int32_t *)(base + o_lrow), nullptr};
+    // (one split: the vertex is the key, the two tables are one; several: the (vertex, split) table serves as both)
+    ctx.tab_local = GsTable{S == 1 ? (unsigned long long *)(base + o_mslot) : nullptr, (int32_t *)(base + o_lrow), nullptr};
     ctx.ent_mixed = (int32_t *)(base + o_em); ctx.ent_local = (int32_t *)(base + o_el);
     ctx.mixed_ent = (int32_t *)(base + o_me); ctx.cls = (uint32_t *)(base + o_cls);
     ctx.part_hist = (int32_t *)(base + o_hist);
