@@ -82,7 +82,7 @@ typedef struct {
                                        kernels' workgroups */
     int32_t        table_mode;      /* dedup tables of the split step: 0 = the library chooses, 1 = hashed (open
                                        addressing, sized for the largest layer), 2 = direct (indexed by the key
-                                       itself: 8 bytes per vertex and split plus 8 per vertex, one atomic per
+                                       itself: 8 bytes per vertex and split, one atomic per
                                        insert; needs n_vertices * n_splits < 2^30).  Same results either way */
 } gsplit_config;
 
@@ -158,10 +158,9 @@ GSPLIT_API int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets
  *
  * Capacity: with B = max_l max_targets * prod_{k >= l} (1 + fanouts[k]) (the no-dedup bound on the
  * destinations plus slots of a layer) the call needs 32 bytes per element of B (28 with one split)
- * plus 16 bytes per entry of its two tables (8 with one split), which have the next power of two
- * above 2 * B entries.  ECAPACITY, with the figures in gsplit_last_error(NULL), when that exceeds
- * the array (1024 targets with fanouts [10, 5] take 6.3 MiB and fit; with [15, 10, 5] they would take
- * about 100 MiB and do not).
+ * plus 8 bytes per entry of its table, which has the next power of two above 2 * B entries.  ECAPACITY, with the figures in gsplit_last_error(NULL), when that exceeds
+ * the array (1024 targets with fanouts [10, 5] take 4.1 MiB and fit; with [15, 10, 5] they would take
+ * about 65 MiB and do not).
  *
  * Output sizes (entries, with ub[L] = max_targets, ub[l] = min(n_vertices, ub[l+1] * (1 + fanouts[l]))):
  *   d_local_cat[l] ub[l] (l = 0 .. L);  d_nbr[l], d_blk_src[l], d_recv_cat[l] ub[l+1] * fanouts[l];

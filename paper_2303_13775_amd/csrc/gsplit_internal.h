@@ -41,13 +41,14 @@ struct GsLevelMeta {
 };
 
 // Dedup table in HBM, in one of two forms.
-//   hashed: open addressing, entry = key << 32 | smallest position seen.
+//   hashed: open addressing, entry = key << 32 | smallest position seen.  A context with several
+//   splits has one such table of (vertex, split) keys, hashed by the vertex (tab_mixed; tab_local then
+//   has a row array only); a context with one split keys by the vertex (the two tables are one).
 //   direct (pos != nullptr): one 64-bit entry per possible key, indexed by the key itself: an insert
 //   is a single atomic min, no probing, no key compare, and nothing is ever reset: the entry is
 //   stamp << 32 | smallest position seen, where the stamp of a (batch, layer) is smaller than every
 //   stamp before it, so whatever an older layer left behind loses against the first insert of the
-//   current one.  Takes 8 bytes per key of the key space (|V| * S for (vertex, split) keys, |V| for
-//   vertex keys).
+//   current one.  Takes 8 bytes per key of the key space (|V| * S keys).
 // row: the final row of a key, kept at the position of the key's first occurrence in the slot
 // stream (one entry per element of the largest layer, whatever the form of the table).
 struct GsTable {
