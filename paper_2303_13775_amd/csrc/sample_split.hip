@@ -121,14 +121,17 @@ __device__ __forceinline__ uint32_t table_pos(const GsTable &t, int h) {
 }
 
 // The hashed table of a context with several splits holds (vertex, split) keys only, hashed by the
-// vertex: the keys of a vertex start at the same line of 16 entries (128 bytes, what one access to
-// the memory moves whatever it asks for) and lie there side by side, filled from the front, running
-// over into the next line when one is full.  So the first occurrence of the vertex in the whole
-// stream (the smallest position among its keys) is read off the line the slot's own entry is in, and
-// there is no second table keyed by the vertex, with its own insert and its own line per access.
-constexpr int LINE_ENTRIES = 16;
+// vertex: the keys of a vertex start at the same line of 8 entries (64 bytes; a vertex has at most
+// 8 keys) and lie there side by side, filled from the front, running over into the next line when
+// one is full.  So the first occurrence of the vertex in the whole stream (the smallest position
+// among its keys) is read off the line the slot's own entry is in, and there is no second table
+// keyed by the vertex, with its own insert and its own access to the memory per slot.
+// (Lines of 16 entries, the 128 bytes one access to the memory moves anyway, measured slower: what
+// a lane asks of a line costs by the request, and half the line is half the requests.)
+constexpr int LINE_ENTRIES = 8;
+constexpr int LINE_LOG = 3;
 __device__ __forceinline__ uint32_t table_line(uint32_t vertex, int bits) {
-    return ((vertex * 0x9E3779B1u) >> (32 - (bits - 4))) << 4;
+    return ((vertex * 0x9E3779B1u) >> (32 - (bits - LINE_LOG))) << LINE_LOG;
 }
 
 // Insert into that table.  The line is read once, with plain loads: what such a read shows of a taken
