@@ -756,7 +756,10 @@ struct PartLayer {
         const int32_t id = nbr[g];                          // -1 in an empty slot
         const int hl = ent_local[at];
         const uint32_t idc = id >= 0 ? (uint32_t)id : 0u;
-        const unsigned t = pmap[idc] & (GS_MAXS - 1);
+        // (with hashed tables, the form of the large layers, the owner is fetched for the winners alone:
+        // such a layer runs at the rate of its random accesses, not of the chain)
+        const bool owner_late = !tab_mixed.pos;
+        unsigned t = owner_late ? 0u : pmap[idc] & (GS_MAXS - 1);
         const uint32_t pos = (uint32_t)at;
         unsigned m = 0u;
         if (!tab_local.pos && !tab_local.slot) {
@@ -788,6 +791,7 @@ struct PartLayer {
                 m = 1u << 16;
                 ent_mixed[at] = (int32_t)first;
                 if (h >= 0 && first == pos) {
+                    if (owner_late) t = pmap[idc] & (GS_MAXS - 1);
                     m |= (1u << s) | (1u << (8 + t));
                     if (hl >= 0) {
                         ent_local[at] = (int32_t)lfirst;
@@ -808,6 +812,7 @@ struct PartLayer {
             ent_mixed[at] = (int32_t)first;
             if (first == pos) {
                 const int s = split_of(meta_up->front_off, S, g / fan);
+                if (owner_late) t = pmap[idc] & (GS_MAXS - 1);
                 m |= (1u << s) | (1u << (8 + t));
                 if (hl >= 0) {
                     const uint32_t lfirst = table_pos(tab_local, hl);
