@@ -157,7 +157,7 @@ GSPLIT_API int gsplit_sample_split_dev(gsplit_ctx *ctx, const int32_t *d_targets
  * call allocates nothing, frees nothing and enqueues only kernels on `stream`.
  *
  * Capacity: with B = max_l max_targets * prod_{k >= l} (1 + fanouts[k]) (the no-dedup bound on the
- * destinations plus slots of a layer) the call needs 32 bytes per element of B (28 with one split)
+ * destinations plus slots of a layer) the call needs 32 bytes per element of B
  * plus 8 bytes per entry of its table, which has the next power of two above 2 * B entries.  ECAPACITY, with the figures in gsplit_last_error(NULL), when that exceeds
  * the array (1024 targets with fanouts [10, 5] take 4.1 MiB and fit; with [15, 10, 5] they would take
  * about 65 MiB and do not).

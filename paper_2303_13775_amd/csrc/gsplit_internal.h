@@ -41,9 +41,8 @@ struct GsLevelMeta {
 };
 
 // Dedup table in HBM, in one of two forms.
-//   hashed: open addressing, entry = key << 32 | smallest position seen.  A context with several
-//   splits has one such table of (vertex, split) keys, hashed by the vertex (tab_mixed; tab_local then
-//   has a row array only); a context with one split keys by the vertex (the two tables are one).
+//   hashed: open addressing, entry = key << 32 | smallest position seen.  One table of
+//   (vertex, split) keys, hashed by the vertex (tab_mixed; tab_local has a row array only).
 //   direct (pos != nullptr): one 64-bit entry per possible key, indexed by the key itself: an insert
 //   is a single atomic min, no probing, no key compare, and nothing is ever reset: the entry is
 //   stamp << 32 | smallest position seen, where the stamp of a (batch, layer) is smaller than every

@@ -785,8 +785,8 @@ struct PartLayer {
                     }
                 } else {
                     first = (uint32_t)tab_mixed.slot[h >= 0 ? h : -2 - h];
-                    if (h >= 0 && first == pos && hl >= 0)
-                        lfirst = table_line_first(tab_mixed, table_bits(n1() * (1 + fan)), idc, (uint32_t)S, pos);
+                    if (h >= 0 && first == pos && hl >= 0)       // (one split: the vertex has this one key)
+                        lfirst = S == 1 ? first : table_line_first(tab_mixed, table_bits(n1() * (1 + fan)), idc, (uint32_t)S, pos);
                 }
                 m = 1u << 16;
                 ent_mixed[at] = (int32_t)first;
@@ -1400,7 +1400,7 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     auto carve = [&](size_t bytes) { const size_t at = need; need += (bytes + 255) & ~(size_t)255; return at; };
     const size_t o_meta = carve(sizeof(GsLevelMeta) * (L + 1));
     const size_t o_mslot = carve(sizeof(unsigned long long) * tab_cap), o_mrow = carve(sizeof(int32_t) * max_items);
-    const size_t o_lrow = S == 1 ? o_mrow : carve(sizeof(int32_t) * max_items);
+    const size_t o_lrow = carve(sizeof(int32_t) * max_items);
     const size_t o_em = carve(sizeof(int32_t) * max_items), o_el = carve(sizeof(int32_t) * max_items);
     const size_t o_me = carve(sizeof(int32_t) * max_items), o_cls = carve(sizeof(uint32_t) * max_items);
     const size_t o_self = carve(sizeof(int32_t) * max_items), o_edge = carve(sizeof(int32_t) * max_items);
@@ -1418,8 +1418,8 @@ extern "C" int gsplit_sample_split_noalloc(const gsplit_graph *g, const gsplit_c
     ctx.n_cu = dev->n_cu;
     ctx.d_meta = (GsLevelMeta *)(base + o_meta);
     ctx.tab_mixed = GsTable{(unsigned long long *)(base + o_mslot), (int32_t *)(base + o_mrow), nullptr};
-    // (one split: the vertex is the key, the two tables are one; several: the (vertex, split) table serves as both)
-    ctx.tab_local = GsTable{S == 1 ? (unsigned long long *)(base + o_mslot) : nullptr, (int32_t *)(base + o_lrow), nullptr};
+    // (the table of (vertex, split) keys serves as both)
+    ctx.tab_local = GsTable{nullptr, (int32_t *)(base + o_lrow), nullptr};
     ctx.ent_mixed = (int32_t *)(base + o_em); ctx.ent_local = (int32_t *)(base + o_el);
     ctx.mixed_ent = (int32_t *)(base + o_me); ctx.cls = (uint32_t *)(base + o_cls);
     ctx.part_hist = (int32_t *)(base + o_hist);
