@@ -146,7 +146,14 @@ extern "C" int gsplit_create(gsplit_ctx **out, const gsplit_graph *g, const gspl
     A((void **)&ctx->d_meta, sizeof(GsLevelMeta) * (L + 1), "meta");
     // one split: the (vertex, split) key is the vertex key (direct form: one table under both names)
     const int64_t keys_m = g->n_vertices * (int64_t)g->n_splits;
-    ctx->direct_tables = c->table_mode == 2 || (c->table_mode == 0 && direct_tables_pay(keys_m, tab_cap));
+    int table_mode = c->table_mode;
+    if (table_mode == 0) {      // (GSPLIT_TABLE_MODE in the environment decides where the configuration leaves the choice open)
+        if (const char *e = std::getenv("GSPLIT_TABLE_MODE")) {
+            const long v = std::strtol(e, nullptr, 10);
+            if (v == 1 || v == 2) table_mode = (int)v;
+        }
+    }
+    ctx->direct_tables = table_mode == 2 || (table_mode == 0 && direct_tables_pay(keys_m, tab_cap));
     if (ctx->direct_tables && keys_m >= (1ll << 30)) ctx->direct_tables = false;     // entry indices are 31-bit
     for (GsTable *t : {&ctx->tab_mixed, &ctx->tab_local}) {
         if (t == &ctx->tab_local && ctx->S == 1 && ctx->direct_tables) {
