@@ -78,6 +78,10 @@ CASES = {
                                                batch=500, n_splits=4, pmap_kind="range", name="deep"),
     "fan64": lambda: workloads.custom(1500, 120000, dims=[8, 8], fanouts=[64], batch=64, n_splits=2,
                                       name="fan64"),
+    # many distinct vertices per sampled slot and eight keys per vertex: the hashed table at its highest
+    # load, full lines and probes that run over into the next line
+    "table-load": lambda: workloads.custom(200000, 1200000, dims=[8, 8, 4], fanouts=[4, 3], batch=20000,
+                                           n_splits=8, name="load"),
     # more than 2**20 slots at the upper bound of the bottom layer: the 1024-chunk partition
     "many-chunks": lambda: workloads.custom(60000, 1500000, dims=[8, 8, 8, 4], fanouts=[15, 10, 5], batch=2048,
                                             n_splits=4, pmap_kind="range", name="chunks"),
