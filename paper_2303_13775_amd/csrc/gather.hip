@@ -34,13 +34,22 @@ __global__ __launch_bounds__(256) void k_gather_rows(const uint8_t *__restrict__
     const int64_t stride = want < launched ? want : launched;
     const int64_t x0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
     if (x0 >= stride) return;
+    const bool narrow = total < (1ll << 31);        // (a 64-bit division costs several times a 32-bit one)
     for (int64_t x = x0; x < total; x += UNROLL * stride) {
         int64_t off[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t y = x + u * stride < total ? x + u * stride : x;
-            const int64_t r = y / vec_per_row;
-            const int c = (int)(y - r * vec_per_row);
+            int64_t r;
+            int c;
+            if (narrow) {
+                const uint32_t r32 = (uint32_t)y / (uint32_t)vec_per_row;
+                r = r32;
+                c = (int)((uint32_t)y - r32 * (uint32_t)vec_per_row);
+            } else {
+                r = y / vec_per_row;
+                c = (int)(y - r * vec_per_row);
+            }
             off[u] = (int64_t)ids[r] * row_stride_bytes + (int64_t)c * sizeof(VecT);
         }
         VecT v[UNROLL];
