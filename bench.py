@@ -998,6 +998,10 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         out["sampling_target"] = {"target_frac_of_hbm_peak": 0.6, "achieved_frac": out["roofline_sampling"]["frac"],
                                   "note": "algorithmic bytes of a word-granular random-access kernel; every such access "
                                           "moves a whole 128-byte line (traffic, where a profile exists, is the hardware view)"}
+        if out["roofline_sampling"].get("traffic_GBps") is not None:
+            # the same launch by the lines it moves: measured traffic over the HBM peak (random 4-byte reads by
+            # themselves reach 50 G lines/s on this chip, i.e. 0.8 of the peak)
+            out["sampling_target"]["achieved_frac_by_measured_traffic"] = out["roofline_sampling"]["traffic_GBps"] / HBM_PEAK_GBS
     if model == "sage":
         out["roofline_linear"] = [roofline_of(k) for k in sorted(per_step_us)
                                   if k.startswith(("linear_fwd", "grad_w", "grad_in"))]
