@@ -340,17 +340,31 @@ class PipelinedGroups:
                 torch.zeros(1, device=dev)
         torch.cuda.synchronize()
 
-    def slot_of_step(self, i, first):
-        j = (i - first) // self.k
-        return self.groups[j % 2][(i - first) % self.k]
+    def plan(self, first, count):
+        """(first step, size) of every group of a run: sizes 2, 4, ... up to K, then K.  The first
+        group is sampled before any training can start, so it is the shortest; each later group is sampled
+        while the one before it, half its size or as large, trains."""
+        out, lo, n = [], first, 2
+        while lo < first + count:
+            m = min(n, self.k, first + count - lo)
+            out.append((lo, m))
+            lo += m
+            n *= 2
+        return out
+
+    def slot_of_step(self, i, first, count):
+        for j, (lo, n) in enumerate(self.plan(first, count)):
+            if lo <= i < lo + n:
+                return self.groups[j % 2][i - lo]
+        raise IndexError(i)
 
     def run(self, targets, first, count):
         import queue
         import threading
         from paper_2303_13775_amd import gsplit_sample_split_multi
         torch = self.torch
-        k = self.k
-        n_groups = (count + k - 1) // k
+        plan = self.plan(first, count)
+        n_groups = len(plan)
         sampled, freed = queue.Queue(), queue.Queue()
         for _ in range(2):
             freed.put(None)
@@ -362,8 +376,7 @@ class PipelinedGroups:
                 for j in range(n_groups):
                     freed.get()
                     g = j % 2
-                    lo = first + j * k
-                    n = min(k, first + count - lo)
+                    lo, n = plan[j]
                     rs = self.groups[g][:n]
                     with torch.cuda.stream(self.s_sample):
                         self.s_sample.wait_event(self.free[g])
@@ -384,8 +397,7 @@ class PipelinedGroups:
                 if got != j:
                     raise RuntimeError(f"sampling thread failed: {failure}")
                 g = j % 2
-                lo = first + j * k
-                n = min(k, first + count - lo)
+                lo, n = plan[j]
                 with torch.cuda.stream(self.s_train):
                     self.s_train.wait_event(self.ready[g])
                     for r in self.groups[g][:n]:
@@ -966,9 +978,10 @@ def measure(a, w, dev, *, workload, dtype, model="sage", heads=4, steps, warmup,
         "value": steps / dt, "ms_per_step": dt / steps * 1e3,
         "schedule": ("serial, one stream" if not pipeline else
                      (f"1 sampling stream + 1 training stream: sample+split (one gsplit_sample_split_multi call for "
-                      f"{K} mini-batches) and gather (one gsplit_gather_features_multi call) of the next {K} steps overlap "
-                      f"fwd/loss/bwd of the current {K}; "
-                      f"every step does all of its work") if K > 1 and not use_graph else
+                      f"a group of mini-batches) and gather (one gsplit_gather_features_multi call) of the next group "
+                      f"overlap fwd/loss/bwd of the current one; groups of 2, 4, ... up to {K} steps, then {K} (the first "
+                      f"group of a run has nothing to overlap with, so it is the shortest); "
+                      f"every step does all of its work inside the timed region") if K > 1 and not use_graph else
                      f"{a.ahead} sampling stream(s) + 1 training stream: sample+split+gather of the next {a.ahead} "
                      f"step(s) overlap fwd/loss/bwd of step i; every step does all of its work"),
         "serial": {"value": steps / dt_serial, "ms_per_step": dt_serial / steps * 1e3,

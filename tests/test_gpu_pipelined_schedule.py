@@ -25,12 +25,12 @@ def test_pipelined_schedule_leaves_the_oracles_results_in_every_slot(model, sche
     assert torch.cuda.is_available(), "needs the MI355X"
     dev = torch.device("cuda:0")
     w = workloads.medium(device=dev)
-    n_steps = 19 if schedule == "groups" else 11     # not a multiple of the slots, the last group is partial
+    n_steps = 27 if schedule == "groups" else 11     # groups of 2, 4, 8, 8 and a partial last one of 5
     targets = [w.targets(i) for i in range(n_steps)]
     torch.cuda.synchronize()
     if schedule == "groups":
         pipe = bench.PipelinedGroups(w, dev, 8, model, 4, 2)
-        slot_of = lambda i: pipe.slot_of_step(i, 0)
+        slot_of = lambda i: pipe.slot_of_step(i, 0, n_steps)
     else:
         pipe = bench.Pipelined(w, dev, 2, model, 4, 2)
         slot_of = lambda i: pipe.slots[i % pipe.n]
